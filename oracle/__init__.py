@@ -1,0 +1,188 @@
+"""CPU oracle for MXFP4 + OAS + MBS (test infrastructure, NOT part of the product path).
+
+Thin ctypes/numpy marshalling around ``mx_oracle.c``; every number is computed in that C file.
+Only tests, ``__graft_entry__.smoke()`` and ``bench.py``'s cpu_baseline leg may import this
+package; the HIP library and its Python binding never do.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mx_oracle.c")
+_LIB = os.path.join(_HERE, "libmx_oracle.so")
+
+RULE_OCP, RULE_FLOOR, RULE_OAS = 0, 1, 2
+RULES = {"ocp": RULE_OCP, "floor": RULE_FLOOR, "oas": RULE_OAS}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over rows only). Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        i64, vp, ci, dbl = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_double
+        L.mxo_bf16_value.restype = dbl
+        L.mxo_bf16_value.argtypes = [ctypes.c_uint16]
+        L.mxo_e2m1_decode.restype = dbl
+        L.mxo_e2m1_decode.argtypes = [ci]
+        L.mxo_e2m1_nearest.restype = ci
+        L.mxo_e2m1_nearest.argtypes = [dbl]
+        L.mxo_mbs_static_m8.restype = ci
+        L.mxo_mbs_static_m8.argtypes = [dbl]
+        L.mxo_scale_exponent.restype = ci
+        L.mxo_scale_exponent.argtypes = [dbl, ci]
+        L.mxo_e8m0_from_exponent.restype = ci
+        L.mxo_e8m0_from_exponent.argtypes = [ci]
+        L.mxo_quantize.restype = ci
+        L.mxo_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
+        L.mxo_dequantize.restype = ci
+        L.mxo_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp]
+        L.mxo_gemm_rows.restype = ci
+        L.mxo_gemm_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, i64, vp]
+        L.mxo_matmul_bf16_rows.restype = ci
+        L.mxo_matmul_bf16_rows.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]
+        L.mxo_qsnr_db.restype = dbl
+        L.mxo_qsnr_db.argtypes = [vp, vp, i64]
+        L.mxo_num_threads.restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _rule(rule) -> int:
+    return RULES[rule] if isinstance(rule, str) else int(rule)
+
+
+# ---- scalar helpers (used by the pin tests) ---------------------------------------------------
+def bf16_value(h: int) -> float:
+    return lib().mxo_bf16_value(h)
+
+
+def e2m1_decode(code: int) -> float:
+    return lib().mxo_e2m1_decode(code)
+
+
+def e2m1_nearest(y: float) -> int:
+    return lib().mxo_e2m1_nearest(float(y))
+
+
+def mbs_static_m8(alpha: float) -> int:
+    return lib().mxo_mbs_static_m8(float(alpha))
+
+
+def scale_exponent(alpha: float, rule) -> int:
+    return lib().mxo_scale_exponent(float(alpha), _rule(rule))
+
+
+def e8m0_from_exponent(s: int) -> int:
+    return lib().mxo_e8m0_from_exponent(int(s))
+
+
+def num_threads() -> int:
+    return lib().mxo_num_threads()
+
+
+# ---- tensor functions --------------------------------------------------------------------------
+def quantize(x_bf16: np.ndarray, rule="oas", mbs: bool = False, block: int = 32, macro: int = 128):
+    """x_bf16: uint16 [rows, K] bf16 bit patterns. Returns (codes, scales, mbs_words or None)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    assert x.ndim == 2
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    words = np.zeros((rows, (K + macro - 1) // macro), np.uint8) if mbs else None
+    rc = lib().mxo_quantize(_ptr(x), rows, K, K, _rule(rule), int(bool(mbs)), block, macro,
+                            _ptr(codes), _ptr(scales), _ptr(words))
+    if rc != 0:
+        raise ValueError("mxo_quantize: bad arguments")
+    return codes, scales, words
+
+
+def dequantize(codes, scales, mbs=None, block: int = 32, macro: int = 128) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.uint8)
+    mbs = None if mbs is None else np.ascontiguousarray(mbs, np.uint8)
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    out = np.empty((rows, K), np.float64)
+    rc = lib().mxo_dequantize(_ptr(codes), _ptr(scales), _ptr(mbs), rows, K, block, macro, _ptr(out))
+    if rc != 0:
+        raise ValueError("mxo_dequantize: bad arguments")
+    return out
+
+
+def gemm(a, b, rows=None, block: int = 32, macro: int = 128) -> np.ndarray:
+    """a, b: (codes, scales, mbs-or-None) triples of A [M,K] and B [N,K]; returns A.B^T [len(rows), N] fp64."""
+    ac, asc, am = [None if t is None else np.ascontiguousarray(t, np.uint8) for t in a]
+    bc, bsc, bm = [None if t is None else np.ascontiguousarray(t, np.uint8) for t in b]
+    M, K = ac.shape[0], ac.shape[1] * 2
+    N = bc.shape[0]
+    assert bc.shape[1] * 2 == K
+    idx = None if rows is None else np.ascontiguousarray(rows, np.int64)
+    n = M if idx is None else len(idx)
+    C = np.empty((n, N), np.float64)
+    rc = lib().mxo_gemm_rows(_ptr(ac), _ptr(asc), _ptr(am), _ptr(bc), _ptr(bsc), _ptr(bm),
+                             M, N, K, block, macro, _ptr(idx), n, _ptr(C))
+    if rc != 0:
+        raise ValueError("mxo_gemm_rows: bad arguments")
+    return C
+
+
+def matmul_bf16(A_bf16, B_bf16, rows=None) -> np.ndarray:
+    A = np.ascontiguousarray(A_bf16, np.uint16)
+    B = np.ascontiguousarray(B_bf16, np.uint16)
+    M, K = A.shape
+    N = B.shape[0]
+    idx = None if rows is None else np.ascontiguousarray(rows, np.int64)
+    n = M if idx is None else len(idx)
+    C = np.empty((n, N), np.float64)
+    rc = lib().mxo_matmul_bf16_rows(_ptr(A), K, _ptr(B), K, M, N, K, _ptr(idx), n, _ptr(C))
+    if rc != 0:
+        raise ValueError("mxo_matmul_bf16_rows: bad arguments")
+    return C
+
+
+def qsnr_db(ref, test) -> float:
+    r = np.ascontiguousarray(ref, np.float64).ravel()
+    t = np.ascontiguousarray(test, np.float64).ravel()
+    assert r.size == t.size
+    return lib().mxo_qsnr_db(_ptr(r), _ptr(t), r.size)
+
+
+def bf16_to_f64(x_bf16: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns (the reference signal of Eq. 1)."""
+    u = np.ascontiguousarray(x_bf16, np.uint16).astype(np.uint32) << 16
+    return u.view(np.float32).astype(np.float64)
+
+
+def mbs_overhead_model(tm: int = 128, tn: int = 128, tk: int = 128):
+    """Analytic per-tile cost of the MBS correction (App. B, Eq. 7-8).
+
+    Returns (extra fp32 ops / FP4 multiply ops, extra bytes / output-tile bytes): the correction is
+    two fp32 operations per output element per tile (Eq. 7 counts them against the tm*tn*tk FP4
+    multiplies), and it loads one 2-byte sigma per row of A and per row of B against a tm x tn fp32
+    output tile (Eq. 8).
+    """
+    ops = (2 * tm * tn) / (tm * tn * tk)
+    traffic = (2 * (tm + tn)) / (4 * tm * tn)
+    return ops, traffic
