@@ -1,0 +1,123 @@
+/*
+ * mx4.h -- C ABI of the MI355X (gfx950) library for MXFP4 quantization with Overflow-Aware
+ * Scaling (OAS) and static Macro Block Scaling (MBS-S), and the block-scaled GEMM that consumes
+ * those operands and applies the MBS correction in its fp32 accumulation.
+ *
+ * Conventions common to every entry point
+ *   - Every pointer argument is a DEVICE pointer owned by the caller (the library never allocates,
+ *     frees or keeps them), except `stream`, which is a hipStream_t passed as void* (NULL = the
+ *     default stream).
+ *   - Calls are asynchronous on `stream`, never synchronise with the host, and return an int:
+ *     MX_OK, or a negative error code, in which case nothing was launched.
+ *   - Arguments are checked before the GPU is touched, so argument errors are reported even
+ *     without a GPU.  A call with zero rows / M / N is a valid no-op.
+ *   - Quantization always runs along K, the contraction dimension, for both GEMM operands
+ *     (A is [M,K], B is [N,K], the product is C = A * B^T; Sec. 4.3.2).
+ *
+ * Canonical layouts (row-major, the surface on which bit-exactness is judged)
+ *   codes   uint8 [rows, K/2]        two E2M1 codes per byte, element 2j in the low nibble;
+ *                                    code = sign<<3 | index into {0,.5,1,1.5,2,3,4,6} (Sec. 2.2)
+ *   scales  uint8 [rows, K/32]       E8M0, bias 127: the de-quantization scale 2^(E-127) shared
+ *                                    by 32 elements (Sec. 2.2); 255 = NaN (non-finite input block)
+ *   mbs     uint8 [rows, ceil(K/128)] the 8 stored mantissa bits m8 of the macro-block factor
+ *                                    F = 1 + m8/256 in [1,2), one per 1x128 window (Sec. 4.3.1)
+ *   x       bf16  [rows, ldx]        input, K <= ldx (elements)
+ * A value is reconstructed as  x_hat = value(code) * 2^(E-127) / F   (Sec. 4.3.1).
+ *
+ * Alignment: x must be 16-byte aligned and ldx a multiple of 8; codes must be 16-byte aligned;
+ * scales, mbs: no requirement.  C must be aligned to its element size.
+ */
+#ifndef MX4_H
+#define MX4_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define MX_OK 0
+#define MX_EINVAL (-1)        /* negative size, K % 32 != 0, ld < K (or < N), bad enum value      */
+#define MX_ENULL (-2)         /* a required pointer is NULL                                       */
+#define MX_EALIGN (-3)        /* pointer or leading dimension violates the alignment above        */
+#define MX_EUNSUPPORTED (-4)  /* no HIP device, or the current device is not gfx950                */
+#define MX_ELAUNCH (-5)       /* the HIP runtime rejected the launch                              */
+
+/* Rule that picks the power-of-two scale of a 32-element block from its absmax (Sec. 4.2). */
+typedef enum {
+    MX_RULE_OCP = 0,   /* MXFP4-OCP: shared exponent floor(log2 absmax) - 2, absmax -> [4, 8)      */
+    MX_RULE_FLOOR = 1, /* "standard": 6/absmax with the mantissa masked off, absmax -> (3, 6]      */
+    MX_RULE_OAS = 2    /* Overflow-Aware Scaling: FLOOR, doubled when absmax lands in (3, 3.5],
+                          absmax -> (3.5, 7]                                                       */
+} mx_rule_t;
+
+typedef enum { MX_OUT_F32 = 0, MX_OUT_BF16 = 1 } mx_dtype_t;
+
+/* Plain MXFP4 quantization of `rows` rows of K bf16 values with the given scale rule, no MBS
+ * (Sec. 2.2 for the format, Sec. 4.2 for the rules).  Elements round to the nearest E2M1 value,
+ * ties to the even code, saturating at +-6; the sign bit is copied from the input, also for
+ * values that round to zero.  An all-zero block stores E = 127.  A block holding Inf/NaN stores
+ * E = 255 and zero codes.  Writes codes [rows,K/2] and scales [rows,K/32]. */
+int mx_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                uint8_t* codes, uint8_t* scales, void* stream);
+
+/* mx_quantize with MX_RULE_OAS (Sec. 4.2). */
+int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx,
+                    uint8_t* codes, uint8_t* scales, void* stream);
+
+/* MBS-Static quantization (Sec. 4.3.1, Eq. 3; Sec. 5.3): per 1x128 window, m8 = the 8 leading
+ * mantissa bits of 6/absmax128; every element of the window is multiplied by F = 1 + m8/256 and
+ * each 32-element block is then quantized as in mx_quantize with `rule` (MX_RULE_OAS is the
+ * paper's MBS-S) on its scaled absmax.  A last window shorter than 128 uses the elements that
+ * exist.  Additionally writes mbs [rows, ceil(K/128)].  Non-finite elements are ignored when the
+ * window absmax is taken. */
+int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
+/* Reconstruct x_hat = value(code) * 2^(E-127) / F (Sec. 4.3.1) into out [rows, ldo] of
+ * `out_dtype` (fp32: correctly rounded; bf16: that fp32 value rounded to nearest even).
+ * mbs_or_null == NULL means F = 1.  E = 255 gives NaN. */
+int mx_dequantize(const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs_or_null,
+                  int64_t rows, int64_t K, mx_dtype_t out_dtype, void* out, int64_t ldo,
+                  void* stream);
+
+/* Plain MXFP4 GEMM, C[M,N] = A[M,K] * B[N,K]^T with A, B given as codes + E8M0 scales
+ * (the baseline the MBS kernel is measured against, Sec. 5.3 / Tab. 4).  fp32 accumulation on the
+ * block-scaled MFMA; C is written as c_dtype with leading dimension ldc >= N (elements). */
+int mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+            const uint8_t* b_codes, const uint8_t* b_scales,
+            int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,
+            void* stream);
+
+/* GEMM with the MBS correction (Sec. 4.3.2, App. E): for every 128-deep macro block g the
+ * block-scaled partial product P_g is multiplied by sigma_A[i,g] * sigma_B[j,g], sigma = 1/F, and
+ * accumulated in fp32:  C[i,j] = sum_g P_g[i,j] * sigma_A[i,g] * sigma_B[j,g].
+ * a_mbs_or_null / b_mbs_or_null == NULL means that operand carries no MBS words (sigma = 1). */
+int mx_gemm_mbs(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
+                const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
+                int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,
+                void* stream);
+
+/* Grouped (mixture-of-experts) form of mx_gemm_mbs (Sec. 5.1: every expert's linear layers are
+ * quantized): the rows of A and C are grouped, group e owning rows
+ * row_offsets[e] .. row_offsets[e+1]-1 (row_offsets: DEVICE int64 [num_groups+1], non-decreasing,
+ * row_offsets[0] = 0, row_offsets[num_groups] <= M_total), and is multiplied with its own weight
+ * B_e [N,K]; the b_* arrays hold the num_groups weights stacked along rows ([num_groups*N, ...]).
+ * Empty groups are allowed.  Rows of C at or beyond row_offsets[num_groups] are not written. */
+int mx_gemm_mbs_grouped(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
+                        const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
+                        int32_t num_groups, const int64_t* row_offsets,
+                        int64_t M_total, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C,
+                        int64_t ldc, void* stream);
+
+/* Human-readable text for a status code (static storage, host pointer). */
+const char* mx_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int mx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MX4_H */

@@ -1,0 +1,13 @@
+"""MI355X-native MXFP4 quantization with Overflow-Aware Scaling and Macro Block Scaling, and the
+block-scaled GEMM with the MBS correction.
+
+This package is argument marshalling only: every step runs in the HIP kernels of ``libmx4.so``
+(C ABI declared in ``include/mx4.h``).  PyTorch provides device memory and streams.  There is no
+CPU fallback: if the library is missing, importing :mod:`paper_2603_08713_amd.binding` members that
+need it raises.
+"""
+from .binding import (  # noqa: F401
+    MX_OUT_BF16, MX_OUT_F32, MX_RULE_FLOOR, MX_RULE_OAS, MX_RULE_OCP, MxError, load_library,
+    mx_dequantize, mx_gemm, mx_gemm_mbs, mx_gemm_mbs_grouped, mx_quantize, mx_quantize_mbs,
+    mx_quantize_oas, mx_status_string, mx_version,
+)

@@ -1,0 +1,223 @@
+"""ctypes binding of ``libmx4.so`` (C ABI in ``include/mx4.h``), same names as the C entry points.
+
+Marshalling only: tensors in, ``data_ptr()`` + sizes + the current HIP stream out.  Output tensors
+are allocated with torch when the caller does not pass them.  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmx4.so")
+
+MX_RULE_OCP, MX_RULE_FLOOR, MX_RULE_OAS = 0, 1, 2
+MX_OUT_F32, MX_OUT_BF16 = 0, 1
+_RULES = {"ocp": MX_RULE_OCP, "floor": MX_RULE_FLOOR, "oas": MX_RULE_OAS}
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class MxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, mx_status_string(status), status))
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree HIP library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "libmx4.so is missing: build it with `python -m paper_2603_08713_amd.build` "
+            "(or __graft_entry__.build()); this package has no CPU fallback")
+    L = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp, ci = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int
+    L.mx_quantize.restype = ci
+    L.mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
+    L.mx_quantize_oas.restype = ci
+    L.mx_quantize_oas.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.mx_quantize_mbs.restype = ci
+    L.mx_quantize_mbs.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp]
+    L.mx_dequantize.restype = ci
+    L.mx_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, vp, i64, vp]
+    L.mx_gemm.restype = ci
+    L.mx_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
+    L.mx_gemm_mbs.restype = ci
+    L.mx_gemm_mbs.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
+    L.mx_gemm_mbs_grouped.restype = ci
+    L.mx_gemm_mbs_grouped.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i64, i64, i64, ci, vp, i64, vp]
+    L.mx_status_string.restype = ctypes.c_char_p
+    L.mx_status_string.argtypes = [ci]
+    L.mx_version.restype = ci
+    L.mx_version.argtypes = []
+    _lib = L
+    return L
+
+
+def mx_status_string(status: int) -> str:
+    return load_library().mx_status_string(int(status)).decode()
+
+
+def mx_version() -> int:
+    return load_library().mx_version()
+
+
+# ---- helpers ---------------------------------------------------------------------------------------
+def _torch():
+    import torch
+
+    return torch
+
+
+def _rule(rule) -> int:
+    return _RULES[rule] if isinstance(rule, str) else int(rule)
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MxError(status, where)
+
+
+def _rows_ld(x):
+    torch = _torch()
+    if x.dim() != 2 or x.dtype != torch.bfloat16 or not x.is_cuda:
+        raise TypeError("expected a 2-D bf16 CUDA tensor")
+    if x.shape[1] > 1 and x.stride(1) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    return x.shape[0], x.shape[1], (x.stride(0) if x.shape[0] > 1 else max(x.stride(0), x.shape[1]))
+
+
+def _u8(t, shape, name):
+    torch = _torch()
+    if t.dtype != torch.uint8 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise TypeError("%s must be a contiguous uint8 CUDA tensor of shape %s" % (name, tuple(shape)))
+    return t
+
+
+def _alloc_outputs(x, rows, K, codes, scales, mbs, want_mbs):
+    torch = _torch()
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    if want_mbs and mbs is None:
+        mbs = torch.empty((rows, (K + 127) // 128), dtype=torch.uint8, device=x.device)
+    _u8(codes, (rows, K // 2), "codes")
+    _u8(scales, (rows, K // 32), "scales")
+    if want_mbs:
+        _u8(mbs, (rows, (K + 127) // 128), "mbs")
+    return codes, scales, mbs
+
+
+# ---- entry points ----------------------------------------------------------------------------------
+def mx_quantize(x, rule="ocp", codes=None, scales=None):
+    """bf16 [rows, K] -> (codes uint8 [rows, K/2], scales uint8 [rows, K/32]) with `rule`, no MBS."""
+    rows, K, ldx = _rows_ld(x)
+    codes, scales, _ = _alloc_outputs(x, rows, K, codes, scales, None, False)
+    _check(load_library().mx_quantize(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
+                                      _stream()), "mx_quantize")
+    return codes, scales
+
+
+def mx_quantize_oas(x, codes=None, scales=None):
+    rows, K, ldx = _rows_ld(x)
+    codes, scales, _ = _alloc_outputs(x, rows, K, codes, scales, None, False)
+    _check(load_library().mx_quantize_oas(_ptr(x), rows, K, ldx, _ptr(codes), _ptr(scales), _stream()),
+           "mx_quantize_oas")
+    return codes, scales
+
+
+def mx_quantize_mbs(x, rule="oas", codes=None, scales=None, mbs=None):
+    """MBS-Static quantization -> (codes, scales, mbs uint8 [rows, ceil(K/128)])."""
+    rows, K, ldx = _rows_ld(x)
+    codes, scales, mbs = _alloc_outputs(x, rows, K, codes, scales, mbs, True)
+    _check(load_library().mx_quantize_mbs(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
+                                          _ptr(mbs), _stream()), "mx_quantize_mbs")
+    return codes, scales, mbs
+
+
+def _out_dtype(dtype) -> Tuple[int, object]:
+    torch = _torch()
+    if dtype in (MX_OUT_F32, "f32", "fp32", torch.float32):
+        return MX_OUT_F32, torch.float32
+    if dtype in (MX_OUT_BF16, "bf16", torch.bfloat16):
+        return MX_OUT_BF16, torch.bfloat16
+    raise ValueError("output dtype must be fp32 or bf16")
+
+
+def mx_dequantize(codes, scales, mbs=None, out_dtype="f32", out=None):
+    torch = _torch()
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    code, tdt = _out_dtype(out_dtype)
+    if out is None:
+        out = torch.empty((rows, K), dtype=tdt, device=codes.device)
+    if out.dtype != tdt or out.dim() != 2 or tuple(out.shape) != (rows, K) or (K > 1 and out.stride(1) != 1):
+        raise TypeError("out must be [rows, K] of the requested dtype with a contiguous last dimension")
+    ldo = out.stride(0) if rows > 1 else max(out.stride(0), K)
+    _check(load_library().mx_dequantize(_ptr(codes), _ptr(scales), _ptr(mbs), rows, K, code, _ptr(out), ldo,
+                                        _stream()), "mx_dequantize")
+    return out
+
+
+def _c_tensor(M, N, out_dtype, out, device):
+    torch = _torch()
+    code, tdt = _out_dtype(out_dtype)
+    if out is None:
+        out = torch.empty((M, N), dtype=tdt, device=device)
+    if out.dtype != tdt or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise TypeError("C must be [M, N] of the requested dtype with a contiguous last dimension")
+    ldc = out.stride(0) if M > 1 else max(out.stride(0), N)
+    return code, out, ldc
+
+
+def mx_gemm(a_codes, a_scales, b_codes, b_scales, out_dtype="f32", out=None):
+    """Plain MXFP4 GEMM: C[M,N] = A[M,K] . B[N,K]^T."""
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    if b_codes.shape[1] * 2 != K:
+        raise ValueError("A and B disagree on K")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
+    _check(load_library().mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), M, N, K, code,
+                                  _ptr(out), ldc, _stream()), "mx_gemm")
+    return out
+
+
+def mx_gemm_mbs(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, out_dtype="f32", out=None):
+    """GEMM with the per-macro-block MBS correction; a_mbs / b_mbs may be None."""
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    if b_codes.shape[1] * 2 != K:
+        raise ValueError("A and B disagree on K")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
+    _check(load_library().mx_gemm_mbs(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes), _ptr(b_scales),
+                                      _ptr(b_mbs), M, N, K, code, _ptr(out), ldc, _stream()), "mx_gemm_mbs")
+    return out
+
+
+def mx_gemm_mbs_grouped(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, row_offsets, N, out_dtype="f32",
+                        out=None):
+    """Grouped GEMM: rows row_offsets[e]..row_offsets[e+1]-1 of A times B_e^T, B stacked [G*N, K]."""
+    torch = _torch()
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    if row_offsets.dtype != torch.int64 or not row_offsets.is_cuda or not row_offsets.is_contiguous():
+        raise TypeError("row_offsets must be a contiguous int64 CUDA tensor")
+    G = row_offsets.numel() - 1
+    if b_codes.shape[0] != G * N or b_codes.shape[1] * 2 != K:
+        raise ValueError("B must hold num_groups stacked [N, K] weights")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
+    _check(load_library().mx_gemm_mbs_grouped(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes),
+                                              _ptr(b_scales), _ptr(b_mbs), G, _ptr(row_offsets), M, N, K, code,
+                                              _ptr(out), ldc, _stream()), "mx_gemm_mbs_grouped")
+    return out

@@ -1,0 +1,296 @@
+// MXFP4 quantizer with Overflow-Aware Scaling and static Macro Block Scaling for gfx950.
+//
+// Work decomposition (one pass over the tensor, Sec. 4.3: no second traversal is needed because
+// the macro block is local):  a lane owns 8 consecutive bf16 (one 16-byte load), 4 lanes own a
+// 32-element block, a row of 16 lanes owns a 1x128 macro block, a wavefront owns 512 consecutive
+// elements of one tensor row.  Block and macro-block maxima are DPP reductions over the bf16
+// magnitude bits (integer order == magnitude order); no LDS traffic is needed for them.
+//
+// Arithmetic is arranged so that every decision is exact:
+//   - MBS word (Sec. 4.3.1, Eq. 3): the 8 leading mantissa bits of 6/absmax128 depend only on
+//     the 7 mantissa bits of the bf16 absmax, so they come from a 128-entry table built with
+//     integer division.
+//   - x * F (F = 1 + m8/256) has at most 17 significant bits and is exact in fp32, and so is its
+//     product with the power-of-two block scale.
+//   - the block exponent is read off the fp32 pattern of absmax * F with a carry trick: adding
+//     (2^23 - 1 - threshold) to the pattern bumps the exponent field exactly when the mantissa
+//     exceeds the rule's threshold (Sec. 4.2: FLOOR 1.5, OAS 1.75, OCP never).
+// Blocks whose magnitudes are so small or so large that fp32 products could leave the normal
+// range, and blocks holding Inf/NaN, take a wave-uniform detour through an all-integer path.
+#include "mx_common.h"
+
+namespace mx {
+namespace {
+
+constexpr int kChunk = 512;        // elements per wavefront step
+constexpr int kUnroll = 4;         // chunks in flight per wavefront
+constexpr int kThreads = 256;
+
+struct QuantArgs {
+    const uint16_t* x;
+    uint8_t* codes;
+    uint8_t* scales;
+    uint8_t* mbs;
+    int64_t K, ldx, chunks_per_row, total_chunks, nmac;
+    uint32_t carry;  // 2^23 - 1 - mantissa threshold of the rule, 0 for OCP
+    int rule;
+    int use_mbs;
+    int scales_dword;  // scales of a macro block can be stored as one aligned dword
+};
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    us2 r = __builtin_elementwise_max(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// 8 leading mantissa bits of 6/alpha for alpha = (128 + k) * 2^e:  6*128/(128+k) lies in (3, 6];
+// normalised to [1,2) it is 192/(128+k) for k <= 64 and 384/(128+k) above.
+__device__ __forceinline__ uint32_t mbs_word_of_mantissa(uint32_t k) {
+    const uint32_t n = 128u + k;
+    return (k <= 64u ? 49152u / n : 98304u / n) - 256u;
+}
+
+// Round |t| (t already multiplied by the block scale) to the E2M1 grid, nearest-even, saturating.
+// Adding 1.5 * 2^(22 + e), e = max(exponent(t), 0), leaves t in units of the grid step of its
+// binade in the low mantissa bits of the sum.
+__device__ __forceinline__ uint32_t e2m1_code_alu(float t) {
+    const uint32_t tb = __float_as_uint(t);
+    const float y = fminf(__uint_as_float(tb & 0x7FFFFFFFu), 6.0f);
+    const uint32_t ey = max(__float_as_uint(y) >> 23, 127u);
+    const float w = y + __uint_as_float(((ey + 22u) << 23) | 0x400000u);
+    const uint32_t mag = (__float_as_uint(w) & 0xFu) + 2u * (ey - 127u);
+    return mag | ((tb >> 28) & 8u);
+}
+
+struct ChunkResult {
+    uint32_t codes;  // 8 E2M1 codes of this lane
+    uint32_t E;      // E8M0 byte of this lane's block
+    uint32_t m8;     // MBS word of this lane's macro block
+};
+
+// All-integer path, exact for every bf16 input including subnormals, huge values and Inf/NaN.
+__device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int use_mbs,
+                                                         const uint8_t* table) {
+    uint32_t h[8] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16,
+                     v.z & 0xFFFFu, v.z >> 16, v.w & 0xFFFFu, v.w >> 16};
+    uint32_t amax = 0, nf = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t a = h[i] & 0x7FFFu;
+        if (a >= 0x7F80u) nf = 1; else amax = max(amax, a);
+    }
+    nf |= dpp_quad_xor1(nf);
+    nf |= dpp_quad_xor2(nf);
+    amax = max(amax, dpp_quad_xor1(amax));
+    amax = max(amax, dpp_quad_xor2(amax));
+    uint32_t mmax = amax;
+    mmax = max(mmax, dpp_row_ror4(mmax));
+    mmax = max(mmax, dpp_row_ror8(mmax));
+
+    uint32_t m8 = 0;
+    if (use_mbs && mmax) {
+        uint32_t k = mmax & 0x7Fu;
+        if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;  // normalise a subnormal absmax
+        m8 = table[k];
+    }
+    const uint32_t u = 256u + m8;  // F = u / 256
+
+    int E;
+    if (nf) {
+        E = 255;
+    } else if (amax == 0) {
+        E = 127;
+    } else {
+        const uint32_t ea = amax >> 7;
+        const uint32_t na = ea ? (128u | (amax & 0x7Fu)) : (amax & 0x7Fu);
+        const int ex = (int)(ea ? ea : 1u) - 134;            // absmax = na * 2^ex
+        const uint32_t P = na * u;                           // absmax * F = P * 2^(ex-8)
+        const int msb = 31 - __clz(P);
+        const int p = ex - 8 + msb;                          // floor(log2(absmax * F))
+        bool low = true;                                     // mantissa at or below the threshold
+        if (rule == MX_RULE_FLOOR) low = 2u * P <= (3u << msb);
+        else if (rule == MX_RULE_OAS) low = 4u * P <= (7u << msb);
+        const int s = low ? 2 - p : 1 - p;
+        E = min(max(127 - s, 0), 254);
+    }
+    const int s = 127 - E;
+
+    uint32_t codes = 0;
+    if (!nf) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t a = h[i] & 0x7FFFu, e = a >> 7;
+            const uint32_t n = e ? (128u | (a & 0x7Fu)) : (a & 0x7Fu);
+            const int sh = (int)(e ? e : 1u) - 134 - 8 + s + 2;  // |x| F 2^s = n u 2^sh quarter units
+            uint32_t T = n * u;
+            int r = 0;
+            if (sh >= 0) T <<= min(sh, 8); else r = min(-sh, 18);
+            // thresholds 1/4, 3/4, 5/4, 7/4, 5/2, 7/2, 5 in quarter units; ties go to the even code
+            const uint32_t c = (T > (1u << r)) + (T >= (3u << r)) + (T > (5u << r)) + (T >= (7u << r)) +
+                               (T > (10u << r)) + (T >= (14u << r)) + (T > (20u << r));
+            codes |= (c | ((h[i] >> 12) & 8u)) << (4 * i);
+        }
+    }
+    return {codes, (uint32_t)E, m8};
+}
+
+template <bool kHwCvt>
+__device__ __forceinline__ ChunkResult quantize_chunk(u32x4 v, const QuantArgs& q, const uint8_t* table) {
+    // lane, block and macro-block absmax on the magnitude bits
+    uint32_t m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
+                            pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
+    uint32_t amax = max(m & 0xFFFFu, m >> 16);
+    amax = max(amax, dpp_quad_xor1(amax));
+    amax = max(amax, dpp_quad_xor2(amax));
+
+    // exponent field outside [24, 249] (or Inf/NaN): leave fp32 arithmetic, wave-uniformly
+    const bool odd = (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) return quantize_chunk_exact(v, q.rule, q.use_mbs, table);
+
+    uint32_t m8 = 0;
+    if (q.use_mbs) {
+        uint32_t mmax = max(amax, dpp_row_ror4(amax));
+        mmax = max(mmax, dpp_row_ror8(mmax));
+        m8 = mmax ? table[mmax & 0x7Fu] : 0u;
+    }
+    // absmax * F is exact in fp32; exponent field + carry gives the stored byte
+    const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));
+    uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - 2u;
+    E = amax ? E : 127u;
+    // multiplier F * 2^(127-E): exponent field 254-E under F's mantissa
+    const float mult = __uint_as_float(((254u - E) << 23) | (m8 << 15));
+
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t codes = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float t0 = __uint_as_float(w[i] << 16) * mult;
+        const float t1 = __uint_as_float(w[i] & 0xFFFF0000u) * mult;
+        if constexpr (kHwCvt) {
+            // hardware fp32 -> E2M1 pair convert (scale 1: the block scale is already applied)
+            if (i == 0) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 0);
+            if (i == 1) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 1);
+            if (i == 2) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 2);
+            if (i == 3) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 3);
+        } else {
+            codes |= (e2m1_code_alu(t0) | (e2m1_code_alu(t1) << 4)) << (8 * i);
+        }
+    }
+    return {codes, E, m8};
+}
+
+template <bool kHwCvt>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
+    __shared__ uint8_t table[128];
+    if (threadIdx.x < 128) table[threadIdx.x] = (uint8_t)mbs_word_of_mantissa(threadIdx.x);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * (kThreads / kWave);
+
+    for (int64_t c0 = wave * kUnroll; c0 < q.total_chunks; c0 += nwaves * kUnroll) {
+        u32x4 v[kUnroll];
+        int64_t row[kUnroll], col[kUnroll];
+        bool valid[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t c = c0 + u;
+            row[u] = c / q.chunks_per_row;
+            col[u] = (c - row[u] * q.chunks_per_row) * kChunk + lane * 8;
+            valid[u] = c < q.total_chunks && col[u] < q.K;
+            v[u] = u32x4{0, 0, 0, 0};
+            if (valid[u]) {
+                const u32x4* p = reinterpret_cast<const u32x4*>(q.x + row[u] * q.ldx + col[u]);
+                v[u] = __builtin_nontemporal_load(p);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (c0 + u >= q.total_chunks) break;  // wave-uniform
+            const ChunkResult r = quantize_chunk<kHwCvt>(v[u], q, table);
+            // scales of the macro block gathered into one dword across the row of 16 lanes
+            uint32_t ew = r.E << (8 * ((lane >> 2) & 3));
+            if ((lane & 3) != 0) ew = 0;
+            ew |= dpp_row_ror4(ew);
+            ew |= dpp_row_ror8(ew);
+            if (!valid[u]) continue;
+            const int64_t kblk = col[u] >> 5;
+            uint8_t* srow = q.scales + row[u] * (q.K >> 5);
+            *reinterpret_cast<uint32_t*>(q.codes + row[u] * (q.K >> 1) + (col[u] >> 1)) = r.codes;
+            if (q.scales_dword) {
+                if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
+            } else if ((lane & 3) == 0) {
+                srow[kblk] = (uint8_t)r.E;
+            }
+            if (q.use_mbs && (lane & 15) == 0) q.mbs[row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)r.m8;
+        }
+    }
+}
+
+int g_quant_hwcvt = 1;
+
+int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
+    if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
+    if (rows == 0 || K == 0) return MX_OK;
+    if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
+    if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 16)) return MX_EALIGN;
+    if (int st = check_device()) return st;
+
+    QuantArgs q;
+    q.x = static_cast<const uint16_t*>(x);
+    q.codes = codes;
+    q.scales = scales;
+    q.mbs = mbs;
+    q.K = K;
+    q.ldx = ldx;
+    q.chunks_per_row = (K + kChunk - 1) / kChunk;
+    q.total_chunks = q.chunks_per_row * rows;
+    q.nmac = (K + kMacro - 1) / kMacro;
+    q.rule = rule;
+    q.use_mbs = use_mbs;
+    q.carry = rule == MX_RULE_FLOOR ? 0x3FFFFFu : rule == MX_RULE_OAS ? 0x1FFFFFu : 0u;
+    q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
+
+    const int64_t waves_needed = (q.total_chunks + kUnroll - 1) / kUnroll;
+    int64_t blocks = (waves_needed + (kThreads / kWave) - 1) / (kThreads / kWave);
+    const int64_t max_blocks = 256 * 8;  // 8 resident workgroups per compute unit
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (g_quant_hwcvt)
+        hipLaunchKernelGGL(quantize_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, s, q);
+    else
+        hipLaunchKernelGGL(quantize_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, q);
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace mx
+
+extern "C" {
+
+int mx_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                uint8_t* codes, uint8_t* scales, void* stream) {
+    return mx::launch_quantize(x_bf16, rows, K, ldx, (int)rule, 0, codes, scales, nullptr, stream);
+}
+
+int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, uint8_t* codes,
+                    uint8_t* scales, void* stream) {
+    return mx::launch_quantize(x_bf16, rows, K, ldx, MX_RULE_OAS, 0, codes, scales, nullptr, stream);
+}
+
+int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize(x_bf16, rows, K, ldx, (int)rule, 1, codes, scales, mbs, stream);
+}
+
+// Development switch (not part of the public ABI): 1 = hardware fp32->E2M1 convert instruction,
+// 0 = integer/float ALU rounding.  Both must give identical codes.
+void mx_internal_set_quantize_convert(int hw) { mx::g_quant_hwcvt = hw; }
+
+}  // extern "C"

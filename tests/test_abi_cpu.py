@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mx4.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2603_08713_amd import build as mxbuild
+    from paper_2603_08713_amd import binding
+
+    if not os.path.exists(mxbuild.LIB):
+        mxbuild.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
+            "mx_gemm_mbs_grouped", "mx_status_string", "mx_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert lib.mx_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = lib.mx_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in lib.mx_status_string(-99).decode()
+
+
+A16 = 0x10000  # fake, suitably aligned device addresses: rejected calls never dereference them
+
+
+def test_quantize_argument_errors(lib):
+    q = lib.mx_quantize
+    assert q(A16, 4, 48, 48, 0, A16, A16, None) == -1          # K % 32
+    assert q(A16, -1, 64, 64, 0, A16, A16, None) == -1         # negative rows
+    assert q(A16, 4, 64, 32, 0, A16, A16, None) == -1          # ldx < K
+    assert q(A16, 4, 64, 64, 7, A16, A16, None) == -1          # bad rule
+    assert q(None, 4, 64, 64, 0, A16, A16, None) == -2
+    assert q(A16, 4, 64, 64, 0, None, A16, None) == -2
+    assert q(A16, 4, 64, 64, 0, A16, None, None) == -2
+    assert q(A16 + 2, 4, 64, 64, 0, A16, A16, None) == -3      # x misaligned
+    assert q(A16, 4, 64, 68, 0, A16, A16, None) == -3          # ldx % 8
+    assert q(A16, 4, 64, 64, 0, A16 + 4, A16, None) == -3      # codes misaligned
+    assert q(A16, 0, 64, 64, 0, A16, A16, None) == 0           # empty is a no-op
+    assert lib.mx_quantize_oas(A16, 4, 40, 40, A16, A16, None) == -1
+    assert lib.mx_quantize_mbs(A16, 4, 64, 64, 2, A16, A16, None, None) == -2   # mbs required
+    assert lib.mx_quantize_mbs(A16, 0, 64, 64, 2, A16, A16, None, None) == 0
+
+
+def test_dequantize_argument_errors(lib):
+    d = lib.mx_dequantize
+    assert d(A16, A16, None, 4, 48, 0, A16, 48, None) == -1
+    assert d(A16, A16, None, 4, 64, 5, A16, 64, None) == -1
+    assert d(A16, A16, None, 4, 64, 0, A16, 32, None) == -1
+    assert d(None, A16, None, 4, 64, 0, A16, 64, None) == -2
+    assert d(A16, A16, None, 4, 64, 0, None, 64, None) == -2
+    assert d(A16, A16, None, 4, 64, 0, A16 + 2, 64, None) == -3
+    assert d(A16, A16, None, 0, 64, 0, A16, 64, None) == 0
+
+
+def test_gemm_argument_errors(lib):
+    g = lib.mx_gemm
+    assert g(A16, A16, A16, A16, 8, 8, 48, 0, A16, 8, None) == -1
+    assert g(A16, A16, A16, A16, -8, 8, 64, 0, A16, 8, None) == -1
+    assert g(A16, A16, A16, A16, 8, 8, 64, 0, A16, 4, None) == -1     # ldc < N
+    assert g(A16, A16, A16, A16, 8, 8, 64, 9, A16, 8, None) == -1
+    assert g(None, A16, A16, A16, 8, 8, 64, 0, A16, 8, None) == -2
+    assert g(A16, A16, A16, A16, 8, 8, 64, 0, None, 8, None) == -2
+    assert g(A16 + 8, A16, A16, A16, 8, 8, 64, 0, A16, 8, None) == -3
+    assert g(A16, A16, A16, A16, 0, 8, 64, 0, A16, 8, None) == 0
+    m = lib.mx_gemm_mbs
+    assert m(A16, A16, None, A16, A16, None, 8, 8, 40, 0, A16, 8, None) == -1
+    assert m(A16, A16, None, A16, A16, None, 8, 0, 64, 0, A16, 8, None) == 0
+    gg = lib.mx_gemm_mbs_grouped
+    assert gg(A16, A16, None, A16, A16, None, 2, None, 8, 8, 64, 0, A16, 8, None) == -2
+    assert gg(A16, A16, None, A16, A16, None, -1, A16, 8, 8, 64, 0, A16, 8, None) == -1
+    assert gg(A16, A16, None, A16, A16, None, 0, A16, 8, 8, 64, 0, A16, 8, None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2603_08713_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_08713_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("test oracle", ""), f
