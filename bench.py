@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the MXFP4 OAS+MBS hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input resident in HBM:
+    quantize A (OAS + MBS-S)  ->  quantize W (OAS + MBS-S)  ->  C = A.W^T with the MBS correction (bf16 out)
+on the Llama-3-8B FFN up-projection shape (A 4096x4096, W 14336x4096).  Prints ONE JSON line.
+
+`value` is 2*M*N*K divided by the wall time of a whole step (quantizers included).  The roofline
+object is for the dominant kernel, the MBS GEMM, timed with HIP events on the launch stream inside
+the timed region.  The CPU oracle is timed on a bounded sample as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+M, N, K = 4096, 14336, 4096
+WORKLOAD = "llama3-8b-ffn-up: A 4096x4096 bf16 Student-t(4) + 1% outlier channels x20, W 14336x4096 bf16 N(0,0.02^2)"
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=30)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    p.add_argument("--no-extras", action="store_true", help="skip plain-GEMM / dequantize / QSNR side measurements")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
+              "`value` is one MI355X's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2603_08713_amd as mx
+    from paper_2603_08713_amd import metrics, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    mx.load_library()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def to_dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    a_bits, w_bits = synth.llama8b_ffn_up(M, N, K)
+    # Distinct buffers rotated per step so that bf16 inputs are read from HBM, not from the 256 MB
+    # Infinity Cache: 8 x 32 MiB of A, 5 x 112 MiB of W, 3 x 112 MiB of C.
+    xa = [to_dev(a_bits) for _ in range(8)]
+    xw = [to_dev(w_bits) for _ in range(5)]
+    qa = [tuple(torch.empty(s, dtype=torch.uint8, device=dev) for s in ((M, K // 2), (M, K // 32), (M, K // 128)))
+          for _ in xa]
+    qw = [tuple(torch.empty(s, dtype=torch.uint8, device=dev) for s in ((N, K // 2), (N, K // 32), (N, K // 128)))
+          for _ in xw]
+    cs = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+
+    def step(i, ev=None):
+        a, w, c = i % len(xa), i % len(xw), i % len(cs)
+        if ev:
+            ev[0].record()
+        mx.mx_quantize_mbs(xa[a], "oas", *qa[a])
+        if ev:
+            ev[1].record()
+        mx.mx_quantize_mbs(xw[w], "oas", *qw[w])
+        if ev:
+            ev[2].record()
+        mx.mx_gemm_mbs(qa[a][0], qa[a][1], qa[a][2], qw[w][0], qw[w][1], qw[w][2], "bf16", out=cs[c])
+        if ev:
+            ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    def avg(j):
+        return sum(e[j].elapsed_time(e[j + 1]) for e in events) / len(events)
+
+    ms_qa, ms_qw, ms_gemm = avg(0), avg(1), avg(2)
+    flops = metrics.gemm_flops(M, N, K)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    gemm_tflops = flops / (ms_gemm * 1e-3) / 1e12
+    bpe = metrics.QUANT_BYTES_PER_ELT_MBS
+    qa_gbps = M * K * bpe / (ms_qa * 1e-3) / 1e9
+    qw_gbps = N * K * bpe / (ms_qw * 1e-3) / 1e9
+
+    out = {
+        "metric": "OAS+MBS MXFP4 GEMM TFLOP/s (whole step: quantize A, quantize W, MBS GEMM)",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "mxfp4 (E2M1 x E8M0/32, fp32 accumulate, bf16 out)",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD, "M": M, "N": N, "K": K, "rule": "oas", "mbs": "static/128",
+                   "buffers": "inputs rotated over %d A / %d W / %d C buffers" % (len(xa), len(xw), len(cs))},
+        "roofline": {
+            "kernel": "gemm_kernel<mbs> (mx_gemm_mbs)",
+            "bound": "mfma",
+            "achieved": round(gemm_tflops, 2),
+            "peak": metrics.MFMA_FP4_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(gemm_tflops / metrics.MFMA_FP4_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "avg_launch_ms": round(ms_gemm, 4),
+        },
+        "quantize": {
+            "bound": "hbm", "bytes_per_element": bpe, "peak": metrics.HBM_PEAK_GBPS, "unit": "GB/s",
+            "A": {"ms": round(ms_qa, 4), "achieved": round(qa_gbps, 1), "frac": round(qa_gbps / metrics.HBM_PEAK_GBPS, 4)},
+            "W": {"ms": round(ms_qw, 4), "achieved": round(qw_gbps, 1), "frac": round(qw_gbps / metrics.HBM_PEAK_GBPS, 4)},
+        },
+    }
+
+    if not args.no_extras:
+        out["extras"] = extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(np, a_bits, w_bits, flops, metrics)
+    print(json.dumps(out))
+
+
+def time_loop(torch, fn, iters, warm=3):
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        fn(warm + i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):
+    """Side measurements outside the timed region: plain MXFP4 GEMM on the same shape (for the
+    Tab. 4 style overhead), a device copy as the achievable-HBM yardstick, the dequantizer."""
+    n = max(5, min(args.steps, 20))
+    res = {}
+    # operands quantized without MBS for the plain kernel (same codes layout, OCP rule)
+    pa = mx.mx_quantize(xa[0], "ocp")
+    pw = mx.mx_quantize(xw[0], "ocp")
+    ms_plain = time_loop(torch, lambda i: mx.mx_gemm(pa[0], pa[1], pw[0], pw[1], "bf16", out=cs[i % len(cs)]), n)
+    ms_mbs = time_loop(torch, lambda i: mx.mx_gemm_mbs(qa[0][0], qa[0][1], qa[0][2], qw[0][0], qw[0][1], qw[0][2],
+                                                        "bf16", out=cs[i % len(cs)]), n)
+    plain_tflops = flops / (ms_plain * 1e-3) / 1e12
+    mbs_tflops = flops / (ms_mbs * 1e-3) / 1e12
+    res["gemm_plain_tflops"] = round(plain_tflops, 2)
+    res["gemm_mbs_tflops"] = round(mbs_tflops, 2)
+    res["gemm_mbs_overhead"] = round(metrics.overhead_fraction(plain_tflops, mbs_tflops), 4)
+    res["paper_context"] = "paper reports 6.2% average MBS GEMM overhead on NVIDIA B200 / CUTLASS 4.3.0 (other hardware)"
+    # copy yardstick: read + write of the same byte count as one W tensor
+    src, dst = xw[1], xw[2]
+    ms_copy = time_loop(torch, lambda i: dst.copy_(src), n)
+    res["copy_gbps"] = round(2 * src.numel() * 2 / (ms_copy * 1e-3) / 1e9, 1)
+    # plain-rule quantizer and dequantizer throughput (algorithmic bytes)
+    ms_q = time_loop(torch, lambda i: mx.mx_quantize(xw[i % len(xw)], "ocp", pw[0], pw[1]), n)
+    res["quantize_plain_W_gbps"] = round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_PLAIN / (ms_q * 1e-3) / 1e9, 1)
+    deq = torch.empty((xw[0].shape[0], xw[0].shape[1]), dtype=torch.bfloat16, device=xw[0].device)
+    ms_d = time_loop(torch, lambda i: mx.mx_dequantize(qw[i % len(qw)][0], qw[i % len(qw)][1], qw[i % len(qw)][2],
+                                                       "bf16", out=deq), n)
+    res["dequantize_W_gbps"] = round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_MBS / (ms_d * 1e-3) / 1e9, 1)
+    return res
+
+
+def cpu_baseline(np, a_bits, w_bits, flops, metrics):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload."""
+    import oracle
+
+    oracle.build()
+    threads = oracle.num_threads()
+    rows_q = N                                      # the whole W tensor gives the quantizer rate
+    t0 = time.perf_counter()
+    w = oracle.quantize(w_bits, "oas", mbs=True)
+    tq = time.perf_counter() - t0
+    q_rate = rows_q * K / tq                        # elements / s
+    a = oracle.quantize(a_bits[:64], "oas", mbs=True)
+    rows = np.arange(0, 64, 2)                      # 32 sampled output rows, all N columns
+    t0 = time.perf_counter()
+    oracle.gemm(a, w, rows=rows)
+    tg = time.perf_counter() - t0
+    g_rate = 2.0 * len(rows) * N * K / tg           # flop / s
+    est_step_s = (M + N) * K / q_rate + flops / g_rate
+    return {
+        "value": round(flops / est_step_s / 1e12, 6),
+        "unit": "TFLOP/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": "quantize %d of %d W rows (%.2f s), fp64 GEMM of %d of %d output rows (%.2f s); whole-step time "
+                  "extrapolated linearly from the two rates" % (rows_q, N, tq, len(rows), M, tg),
+        "quantize_melem_per_s": round(q_rate / 1e6, 2),
+        "gemm_gflops": round(g_rate / 1e9, 3),
+    }
+
+
+if __name__ == "__main__":
+    main()
