@@ -51,78 +51,108 @@ struct GemmArgs {
     int vec_store;               // C rows allow 4-element vector stores
 };
 
-struct __attribute__((aligned(16))) Stage {
-    uint8_t codes_m[kTile / 16][kStageMacros][kFragBytes];  // A rows (activations)
-    uint8_t codes_n[kTile / 16][kStageMacros][kFragBytes];  // B rows (weights)
-    uint32_t scale_m[kStageMacros][2][kWave];               // [macro][wave half][lane]: 4 fragments' bytes
+// LDS map (dynamic, 72 KiB): the two code stages first, so that the direct-to-LDS loads target the
+// low 64 KiB, then the small per-stage arrays.
+struct __attribute__((aligned(16))) StageCodes {
+    uint8_t m[kTile / 16][kStageMacros][kFragBytes];  // A rows (activations): fragment-major, lane order
+    uint8_t n[kTile / 16][kStageMacros][kFragBytes];  // B rows (weights)
+};
+struct __attribute__((aligned(16))) StageSmall {
+    uint32_t scale_m[kStageMacros][2][kWave];  // [macro][wave half][lane]: bytes = the 4 fragments of that half
     uint32_t scale_n[kStageMacros][2][kWave];
     float sigma_m[kStageMacros][kTile];
     float sigma_n[kStageMacros][kTile];
 };
+constexpr int kLdsBytes = 2 * (int)sizeof(StageCodes) + 2 * (int)sizeof(StageSmall);
 
-// One operand (A or B) of the tile as seen by the loader.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// One operand (A or B) of the tile as the loader sees it: buffer resources rebased to the tile's first
+// row and sized to its valid rows, so that rows past the end read as zero without any branch.
 struct Operand {
-    const uint8_t* codes;
-    const uint8_t* scales;
-    const uint8_t* mbs;
-    int64_t row0;      // first row of the tile
-    int64_t row_end;   // one past the last valid row
+    __amdgpu_buffer_rsrc_t codes, scales, mbs;
+    int row_bytes;    // K / 2
+    int scale_bytes;  // K / 32
+    int nmac;         // ceil(K / 128)
+    bool has_mbs;
 };
 
-struct Prefetch {
-    v4i codes[4];
-    uint32_t scale;
-    uint32_t m8;
-};
-
-__device__ __forceinline__ void load_operand(const Operand& op, int64_t K, int64_t k0, int tid, Prefetch& pf,
-                                             bool with_mbs) {
-    const int w = tid >> 6, l = tid & 63;
-    const int64_t row_bytes = K >> 1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int pair = i * 4 + w;  // (16-row block, macro block) handled by this wavefront
-        const int rb = pair >> 1, mb = pair & 1;
-        const int64_t row = op.row0 + rb * 16 + (l & 15);
-        const int64_t k = k0 + mb * kMacro + (l >> 4) * kBlock;
-        v4i v = {0, 0, 0, 0};
-        if (row < op.row_end && k < K) v = *reinterpret_cast<const v4i*>(op.codes + row * row_bytes + (k >> 1));
-        pf.codes[i] = v;
-    }
-    // one (row, macro block) per thread: its four E8M0 bytes and its MBS word
-    const int64_t row = op.row0 + (tid & 127);
-    const int64_t g = k0 / kMacro + (tid >> 7);
-    uint32_t sc = 0x7F7F7F7Fu, m8 = 0;
-    if (row < op.row_end && g * kMacro < K) {
-        const uint8_t* sp = op.scales + row * (K >> 5) + g * 4;
-        if (g * kMacro + kMacro <= K) {
-            sc = (uint32_t)sp[0] | ((uint32_t)sp[1] << 8) | ((uint32_t)sp[2] << 16) | ((uint32_t)sp[3] << 24);
-        } else {
-            const int nvalid = (int)((K - g * kMacro) >> 5);
-            sc = 0;
-            for (int j = 0; j < 4; ++j) sc |= (uint32_t)(j < nvalid ? sp[j] : 0x7F) << (8 * j);
-        }
-        if (with_mbs && op.mbs) m8 = op.mbs[row * ((K + kMacro - 1) / kMacro) + g];
-    }
-    pf.scale = sc;
-    pf.m8 = m8;
+__device__ __forceinline__ Operand make_operand(const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs,
+                                                int64_t row0, int64_t row_end, int64_t K) {
+    Operand op;
+    const int64_t rows = row_end > row0 ? (row_end - row0 < kTile ? row_end - row0 : kTile) : 0;
+    op.row_bytes = (int)(K >> 1);
+    op.scale_bytes = (int)(K >> 5);
+    op.nmac = (int)((K + kMacro - 1) / kMacro);
+    op.has_mbs = mbs != nullptr;
+    const int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
+    op.codes = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(codes) + row0 * op.row_bytes, 0,
+                                                 (int)(rows * op.row_bytes), kRsrcFlags);
+    op.scales = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(scales) + row0 * op.scale_bytes, 0,
+                                                  (int)(rows * op.scale_bytes), kRsrcFlags);
+    op.mbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(mbs ? mbs + row0 * op.nmac : codes), 0,
+                                               mbs ? (int)(rows * op.nmac) : 0, kRsrcFlags);
+    return op;
 }
 
-__device__ __forceinline__ void store_operand(const Prefetch& pf, uint8_t (*codes)[kStageMacros][kFragBytes],
-                                              uint32_t (*scale)[2][kWave], float (*sigma)[kTile], int tid,
-                                              bool with_mbs) {
+constexpr int kOob = 0x7FFFFFF0;  // byte offset beyond any buffer: the load returns zero
+
+// Codes of one stage straight into LDS.  Each wavefront issues four 1-KiB loads per operand; load i
+// of wavefront w fills fragment (16-row block, macro block) = (pair >> 1, pair & 1), pair = 4 i + w,
+// lane l fetching row l % 16, 32-element block l / 16 -- which is exactly the lane order the
+// instruction wants, so the LDS image needs no further shuffling.
+template <bool kRaggedK>
+__device__ __forceinline__ void load_codes(const Operand& op, uint8_t (*dst)[kStageMacros][kFragBytes], int64_t K,
+                                           int k0, int tid) {
     const int w = tid >> 6, l = tid & 63;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int pair = i * 4 + w;
-        *reinterpret_cast<v4i*>(&codes[pair >> 1][pair & 1][l * 16]) = pf.codes[i];
+        const int rb = pair >> 1, mb = pair & 1;
+        const int k = mb * kMacro + (l >> 4) * kBlock;  // within the stage
+        int voff = (rb * 16 + (l & 15)) * op.row_bytes + (k >> 1);
+        if (kRaggedK && k0 + k >= K) voff = kOob;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(op.codes, (lds_ptr_t)(&dst[rb][mb][0]), 16, voff, k0 >> 1, 0, 0);
     }
+}
+
+struct Small {
+    uint32_t scale;  // the four E8M0 bytes of one (row, macro block)
+    uint32_t m8;
+};
+
+// One (row, macro block) per thread: its four E8M0 bytes and its MBS word.
+template <bool kMbs, bool kScaleDword>
+__device__ __forceinline__ Small load_small(const Operand& op, int64_t K, int k0, int tid) {
+    const int row = tid & 127;
+    const int g = k0 / kMacro + (tid >> 7);
+    Small r;
+    const int off = row * op.scale_bytes + g * 4;
+    if (kScaleDword) {
+        r.scale = __builtin_amdgcn_raw_buffer_load_b32(op.scales, g * kMacro < K ? off : kOob, 0, 0);
+    } else {
+        // rows are not dword aligned or the last macro block is short: byte loads, absent blocks read 0
+        r.scale = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int o = g * kMacro + j * kBlock < K ? off + j : kOob;
+            r.scale |= (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(op.scales, o, 0, 0) << (8 * j);
+        }
+    }
+    r.m8 = 0;
+    if (kMbs) r.m8 = __builtin_amdgcn_raw_buffer_load_b8(op.mbs, g * kMacro < K ? row * op.nmac + g : kOob, 0, 0);
+    return r;
+}
+
+template <bool kMbs>
+__device__ __forceinline__ void store_small(const Small& v, uint32_t (*scale)[2][kWave], float (*sigma)[kTile],
+                                            int tid) {
     const int row = tid & 127, mb = tid >> 7;
     const int half = row >> 6, frag = (row >> 4) & 3, r = row & 15;
     uint8_t* sb = reinterpret_cast<uint8_t*>(&scale[mb][half][0]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) sb[(q * 16 + r) * 4 + frag] = (uint8_t)(pf.scale >> (8 * q));
-    if (with_mbs) sigma[mb][row] = 1.0f / (1.0f + (float)pf.m8 * (1.0f / 256.0f));
+    for (int q = 0; q < 4; ++q) sb[(q * 16 + r) * 4 + frag] = (uint8_t)(v.scale >> (8 * q));
+    if (kMbs) sigma[mb][row] = 1.0f / (1.0f + (float)v.m8 * (1.0f / 256.0f));
 }
 
 template <int kSelN, int kSelM>
@@ -160,10 +190,13 @@ __device__ __forceinline__ void tile_row(v4f (&acc)[4][4], const v4i (&m_frag)[4
     tile_step<kMbs, kMi, 3>(acc, m_frag, n_frag, sn, sm, sig_m, sig_n);
 }
 
-template <bool kMbs>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
+// kMbs: apply the per-macro-block correction; kScaleDword: the four E8M0 bytes of a macro block are an
+// aligned dword (K % 128 == 0, 4-byte aligned scale arrays); kRaggedK: K is not a multiple of the stage.
+template <bool kMbs, bool kScaleDword, bool kRaggedK>
+__global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    Stage* stage = reinterpret_cast<Stage*>(smem);
+    StageCodes* codes = reinterpret_cast<StageCodes*>(smem);
+    StageSmall* small = reinterpret_cast<StageSmall*>(smem + 2 * sizeof(StageCodes));
 
     // ---- which tile --------------------------------------------------------------------------
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles and
@@ -179,8 +212,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     int tm = first_m + (linear % band) % band_rows;
     const int tn = (linear % band) / band_rows;
 
-    Operand opa{g.a_codes, g.a_scales, g.a_mbs, 0, g.M};
-    Operand opb{g.b_codes, g.b_scales, g.b_mbs, (int64_t)tn * kTile, g.N};
+    int64_t a_row0 = (int64_t)tm * kTile, a_end = g.M;
+    int64_t b_row0 = (int64_t)tn * kTile, b_end = g.N;
     if (g.num_groups > 0) {
         // tm counts tiles over all groups; find the group that owns it
         int e = 0;
@@ -194,13 +227,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
             tm -= nt;
         }
         if (!found) return;
-        opa.row0 = lo + (int64_t)tm * kTile;
-        opa.row_end = hi;
-        opb.row0 += (int64_t)e * g.N;
-        opb.row_end = (int64_t)e * g.N + g.N;
-    } else {
-        opa.row0 = (int64_t)tm * kTile;
+        a_row0 = lo + (int64_t)tm * kTile;
+        a_end = hi;
+        b_row0 += (int64_t)e * g.N;
+        b_end = (int64_t)e * g.N + g.N;
     }
+    const Operand opa = make_operand(g.a_codes, g.a_scales, g.a_mbs, a_row0, a_end, g.K);
+    const Operand opb = make_operand(g.b_codes, g.b_scales, g.b_mbs, b_row0, b_end, g.K);
 
     const int tid = threadIdx.x, l = tid & 63, w = tid >> 6;
     const int wm = w & 1, wn = w >> 1;  // quadrant of the tile owned by this wavefront
@@ -212,19 +245,29 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
         for (int j = 0; j < 4; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
     const int nstages = (int)((g.K + kStageK - 1) / kStageK);
-    Prefetch pa, pb;
-    load_operand(opa, g.K, 0, tid, pa, kMbs);
-    load_operand(opb, g.K, 0, tid, pb, kMbs);
-    store_operand(pa, stage[0].codes_m, stage[0].scale_m, stage[0].sigma_m, tid, kMbs);
-    store_operand(pb, stage[0].codes_n, stage[0].scale_n, stage[0].sigma_n, tid, kMbs);
-    __syncthreads();
+    if (nstages > 0) {
+        load_codes<kRaggedK>(opa, codes[0].m, g.K, 0, tid);
+        load_codes<kRaggedK>(opb, codes[0].n, g.K, 0, tid);
+        const Small sa = load_small<kMbs, kScaleDword>(opa, g.K, 0, tid);
+        const Small sb = load_small<kMbs, kScaleDword>(opb, g.K, 0, tid);
+        store_small<kMbs>(sa, small[0].scale_m, small[0].sigma_m, tid);
+        store_small<kMbs>(sb, small[0].scale_n, small[0].sigma_n, tid);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
+        __syncthreads();
+    }
 
     for (int s = 0; s < nstages; ++s) {
-        const Stage& cur = stage[s & 1];
-        if (s + 1 < nstages) {
-            load_operand(opa, g.K, (int64_t)(s + 1) * kStageK, tid, pa, kMbs);
-            load_operand(opb, g.K, (int64_t)(s + 1) * kStageK, tid, pb, kMbs);
-        }
+        const StageCodes& cc = codes[s & 1];
+        const StageSmall& cs = small[s & 1];
+        // Next stage into the other buffer (last read before the barrier that ended the previous
+        // iteration).  Unconditional, so that the loop body stays one basic block: past the end of K
+        // the loads are out of range and return zeros that nobody reads.
+        const int k1 = (s + 1) * kStageK;
+        load_codes<kRaggedK>(opa, codes[(s + 1) & 1].m, g.K, k1, tid);
+        load_codes<kRaggedK>(opb, codes[(s + 1) & 1].n, g.K, k1, tid);
+        const Small sa = load_small<kMbs, kScaleDword>(opa, g.K, k1, tid);
+        const Small sb = load_small<kMbs, kScaleDword>(opb, g.K, k1, tid);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mb = 0; mb < kStageMacros; ++mb) {
             v4i m_frag[4], n_frag[4];
@@ -232,27 +275,28 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
             v4f sig_n[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                m_frag[i] = *reinterpret_cast<const v4i*>(&cur.codes_m[wm * 4 + i][mb][l * 16]);
-                n_frag[i] = *reinterpret_cast<const v4i*>(&cur.codes_n[wn * 4 + i][mb][l * 16]);
+                m_frag[i] = *reinterpret_cast<const v4i*>(&cc.m[wm * 4 + i][mb][l * 16]);
+                n_frag[i] = *reinterpret_cast<const v4i*>(&cc.n[wn * 4 + i][mb][l * 16]);
                 if constexpr (kMbs) {
-                    sig_m[i] = cur.sigma_m[mb][wm * 64 + i * 16 + (l & 15)];
-                    sig_n[i] = *reinterpret_cast<const v4f*>(&cur.sigma_n[mb][wn * 64 + i * 16 + (l >> 4) * 4]);
+                    sig_m[i] = cs.sigma_m[mb][wm * 64 + i * 16 + (l & 15)];
+                    sig_n[i] = *reinterpret_cast<const v4f*>(&cs.sigma_n[mb][wn * 64 + i * 16 + (l >> 4) * 4]);
                 } else {
                     sig_n[i] = v4f{1.f, 1.f, 1.f, 1.f};
                 }
             }
-            const uint32_t sm = cur.scale_m[mb][wm][l];
-            const uint32_t sn = cur.scale_n[mb][wn][l];
+            const uint32_t sm = cs.scale_m[mb][wm][l];
+            const uint32_t sn = cs.scale_n[mb][wn][l];
             tile_row<kMbs, 0>(acc, m_frag, n_frag, sn, sm, sig_m, sig_n);
             tile_row<kMbs, 1>(acc, m_frag, n_frag, sn, sm, sig_m, sig_n);
             tile_row<kMbs, 2>(acc, m_frag, n_frag, sn, sm, sig_m, sig_n);
             tile_row<kMbs, 3>(acc, m_frag, n_frag, sn, sm, sig_m, sig_n);
         }
-        if (s + 1 < nstages) {
-            Stage& nxt = stage[(s + 1) & 1];
-            store_operand(pa, nxt.codes_m, nxt.scale_m, nxt.sigma_m, tid, kMbs);
-            store_operand(pb, nxt.codes_n, nxt.scale_n, nxt.sigma_n, tid, kMbs);
-        }
+        // keep the multiply phase ahead of the wait for the next stage's loads
+        __builtin_amdgcn_sched_barrier(0);
+        StageSmall& ns = small[(s + 1) & 1];
+        store_small<kMbs>(sa, ns.scale_m, ns.sigma_m, tid);
+        store_small<kMbs>(sb, ns.scale_n, ns.sigma_n, tid);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
         __syncthreads();
     }
 
@@ -260,8 +304,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     const int64_t n_base = (int64_t)tn * kTile + wn * 64 + (l >> 4) * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int64_t m = opa.row0 + wm * 64 + i * 16 + (l & 15);
-        if (m >= opa.row_end) continue;
+        const int64_t m = a_row0 + wm * 64 + i * 16 + (l & 15);
+        if (m >= a_end) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t n = n_base + j * 16;
@@ -294,6 +338,22 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     }
 }
 
+template <bool kMbs, bool kScaleDword, bool kRaggedK>
+int launch_variant(const GemmArgs& g, unsigned blocks, hipStream_t s) {
+    static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
+    auto* fn = gemm_kernel<kMbs, kScaleDword, kRaggedK>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return MX_ELAUNCH;
+        }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kThreads), kLdsBytes, s, g);
+    return launch_status();
+}
+
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
                 bool grouped, int64_t M, int64_t N, int64_t K, int c_dtype, void* C, int64_t ldc, bool mbs_entry,
@@ -301,7 +361,7 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     if (M < 0 || N < 0 || K < 0 || (K % kBlock) != 0 || ldc < N) return MX_EINVAL;
     if (c_dtype != MX_OUT_F32 && c_dtype != MX_OUT_BF16) return MX_EINVAL;
     if (grouped && num_groups < 0) return MX_EINVAL;
-    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || (grouped && (int64_t)num_groups * N > (int64_t)1 << 40))
+    if (K > (int64_t)1 << 24 || M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || (grouped && (int64_t)num_groups * N > (int64_t)1 << 40))
         return MX_EINVAL;
     if (M == 0 || N == 0 || (grouped && num_groups == 0)) return MX_OK;
     if (!C || (grouped && !row_offsets)) return MX_ENULL;
@@ -326,25 +386,16 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
 
     const int total = g.tiles_m * g.tiles_n;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    const size_t lds = 2 * sizeof(Stage);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = mbs_entry && (a_mbs || b_mbs);
-    static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            (void)hipGetLastError();
-            return MX_ELAUNCH;
-        }
-        attr_set = true;
+    const bool dword = (K % kMacro) == 0 && aligned(a_scales, 4) && aligned(b_scales, 4);
+    const bool ragged = (K % kStageK) != 0;
+    if (use_mbs) {
+        if (dword) return ragged ? launch_variant<true, true, true>(g, blocks, s) : launch_variant<true, true, false>(g, blocks, s);
+        return launch_variant<true, false, true>(g, blocks, s);
     }
-    if (use_mbs)
-        hipLaunchKernelGGL(gemm_kernel<true>, dim3(blocks), dim3(kThreads), lds, s, g);
-    else
-        hipLaunchKernelGGL(gemm_kernel<false>, dim3(blocks), dim3(kThreads), lds, s, g);
-    return launch_status();
+    if (dword) return ragged ? launch_variant<false, true, true>(g, blocks, s) : launch_variant<false, true, false>(g, blocks, s);
+    return launch_variant<false, false, true>(g, blocks, s);
 }
 
 }  // namespace
