@@ -42,4 +42,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> packed bf16 (first value in the low half) with the hardware convert, round to nearest even.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    const v2f v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));
+}
+
 }  // namespace mx

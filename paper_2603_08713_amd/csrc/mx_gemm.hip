@@ -10,8 +10,7 @@
 // Operand mapping of the instruction (64 lanes, lane = 16 q + r):
 //   srcA: 16 rows x 128 k;  lane holds row r, k-block q: 32 FP4 = 16 bytes (4 of the 8 operand VGPRs)
 //   srcB: 16 cols x 128 k;  lane holds col r, k-block q
-//   scale operands: one E8M0 byte per lane (for its row/col and k-block), picked out of a VGPR
-//                   by a per-instruction byte selector
+//   scale operands: one E8M0 byte per lane (for its row/col and k-block), byte 0 of a VGPR here
 //   D:    lane holds D[4 q + i][r], i = 0..3
 // The weight matrix B feeds srcA and the activation matrix A feeds srcB, so that a lane ends up
 // with four consecutive n of one output row m and stores them as one vector.
@@ -19,14 +18,22 @@
 // Tiling: a workgroup of NWM x NWN wavefronts computes a TM x TN tile of C, each wavefront
 // FM x FN 16x16 fragments.  FP4 operands are so small next to the MFMA rate (4096 FLOP/clk/SIMD)
 // that the tile has to be large for the L2 to keep up: a T x T tile moves 1/(2T) bytes per FLOP.
-// K advances in stages of 256 elements (two macro blocks, one 128-byte line per row and operand),
-// double-buffered in LDS.  The codes go from global memory straight into LDS (buffer loads with
-// the LDS bit) as a row-major image with XOR-swizzled 16-byte chunks: eight lanes fetch one full
-// 128-byte line, and the 16-byte fragment reads of the multiply phase are bank-conflict free.
-// Buffer resources are sized to the tile's valid rows, so ragged tiles read zeros without a branch.  The E8M0 bytes and the sigma values
-// are staged through registers: the scales are regrouped so that one dword holds the bytes of
-// four fragments for a given lane (the instruction's byte selector then picks the fragment), and
-// the MBS words are turned into fp32 sigma once per (row, macro block).
+//
+// Data movement: K advances in stages of 256 elements (two macro blocks, one 128-byte line per row
+// and operand).  Everything a stage needs travels from global memory straight into LDS with buffer
+// loads that carry the LDS bit, so no vector register ever waits on global memory:
+//   codes   three stages in LDS (two in flight while one is multiplied), row-major with XOR-swizzled
+//           16-byte chunks: eight lanes fetch one full 128-byte line, and the 16-byte fragment reads
+//           of the multiply phase are bank-conflict free;
+//   scales  the 8 E8M0 bytes per row and stage, two slots; each lane later picks its own byte;
+//   MBS     the 2 words per row and stage, three slots; one stage ahead of their use they are turned
+//           into fp32 sigma values (two slots) by the workgroup.
+// The loads of a stage are issued a few at a time between the matrix instructions, because the
+// memory pipeline of a compute unit accepts them far more slowly than a wavefront can issue them.
+// Buffer resources are sized to the tile's valid rows, so ragged tiles read zeros without a branch.
+// The loop is software-pipelined by one macro block: while the matrix cores work on one macro block
+// the LDS reads of the next one are in flight; the barrier that publishes stage s + 1 sits between the
+// two macro blocks of stage s.
 #include <utility>
 
 #include "mx_common.h"
@@ -36,8 +43,9 @@ namespace {
 
 constexpr int kStageK = 256;  // K elements per pipeline stage
 constexpr int kStageMacros = kStageK / kMacro;
-constexpr int kFragBytes = 1024;  // 16 rows x 128 FP4
-constexpr int kGroupM = 8;        // tile-rows walked together for L2 reuse
+constexpr int kRowStage = kStageK / 2;  // code bytes per row and stage
+constexpr int kGroupM = 8;              // tile-rows walked together for L2 reuse
+constexpr int kCodeBufs = 3, kScaleBufs = 2, kSigmaBufs = 2;
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -53,27 +61,42 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
 // Tile shape: NWM x NWN wavefronts, each FM x FN fragments of 16 x 16 outputs.
-template <int NWM_, int NWN_, int FM_, int FN_, int NBUF_>
+template <int NWM_, int NWN_, int FM_, int FN_>
 struct Shape {
     static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_;
-    static constexpr int NBUF = NBUF_;  // code stages in LDS; NBUF - 1 stages are in flight while one is multiplied
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 16, TN = NWN * FN * 16;
-    // LDS map: NBUF x [codes m | n], then 2 x [scale_m | scale_n | sigma_m | sigma_n]
-    static constexpr int kCodesStage = (TM + TN) * (kStageK / 2);
-    static constexpr int kSmallBase = NBUF * kCodesStage;
-    static constexpr int kScaleM = 0;                                // u32 [macro][TM/64][64]
-    static constexpr int kScaleN = kScaleM + kStageMacros * TM * 4;  // u32 [macro][TN/64][64]
-    static constexpr int kSigmaM = kScaleN + kStageMacros * TN * 4;  // f32 [macro][TM]
-    static constexpr int kSigmaN = kSigmaM + kStageMacros * TM * 4;  // f32 [macro][TN]
-    static constexpr int kSmallStage = kSigmaN + kStageMacros * TN * 4;
-    static constexpr int kLdsBytes = kSmallBase + 2 * kSmallStage;
-    static_assert(FM == 2 || FM % 4 == 0, "fragment count per wave: 2 or a multiple of 4");
-    static_assert(FN == 2 || FN % 4 == 0, "fragment count per wave: 2 or a multiple of 4");
-    static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "8-row loads per wave");
-    static_assert(TM % 64 == 0 && TN % 64 == 0, "scale dwords group four fragments");
-    static_assert(NBUF == 2 || NBUF == 3, "double or triple buffering");
+    static constexpr int kRows = TM + TN;  // rows of A followed by rows of B
+    static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "8-row code loads: operand fixed per load index");
+    static_assert((kRows / 8 / NW) % 2 == 0, "code loads are split over the two macro-block phases");
+};
+
+// LDS map and direct-to-LDS load counts of one kernel variant.  A direct-to-LDS load always writes one
+// dword per lane, also when it fetches a single byte (zero-extended), so the byte-wise fallbacks
+// (kScaleDword / kM8Quad false) cost four LDS bytes per byte and only fit the smaller tile.
+//   kScaleDword: the four E8M0 bytes of a macro block are an aligned dword (K % 128 == 0, aligned array)
+//   kM8Quad:     the MBS words of two stages are an aligned dword (K % 512 == 0, aligned arrays)
+template <typename S, bool kScaleDword, bool kM8Quad>
+struct Layout {
+    static constexpr int NW = S::NW, kRows = S::kRows;
+    // loads per wavefront and stage (every wavefront issues the same number)
+    static constexpr int kCodeDma = kRows / 8 / NW;                                              // 8 rows x 128 B
+    static constexpr int kScaleDma = ceil_div(kScaleDword ? kRows * 2 : kRows * 8, kWave * NW);  // 64 lanes each
+    static constexpr int kM8Dma = ceil_div(kM8Quad ? kRows : kRows * 2, kWave * NW);
+    static constexpr int kScaleStride = kScaleDword ? 1 : 4;  // LDS bytes per E8M0 byte
+    static constexpr int kCodesStage = kRows * kRowStage;
+    static constexpr int kScaleStage = kRows * 8 * kScaleStride;          // [row][8 E8M0 bytes of the stage]
+    static constexpr int kM8Stage = kM8Quad ? kRows * 4 : kRows * 2 * 4;  // quad: [row] dword = words of 2 stages
+    static constexpr int kM8Bufs = kM8Quad ? 2 : 3;
+    static constexpr int kSigmaStage = kRows * 8;                         // f32 [macro][row]
+    static constexpr int kScaleBase = kCodeBufs * kCodesStage;
+    static constexpr int kM8Base = kScaleBase + kScaleBufs * kScaleStage;
+    static constexpr int kSigmaBase = kM8Base + kM8Bufs * kM8Stage;
+    static constexpr int kDummy = kSigmaBase + kSigmaBufs * kSigmaStage;  // target of padding loads
+    static constexpr int kLdsBytes = kDummy + 256;
     static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
 };
 
@@ -93,107 +116,46 @@ struct GemmArgs {
 // row and sized to its valid rows, so that rows past the end read as zero without any branch.
 struct Operand {
     __amdgpu_buffer_rsrc_t codes, scales, mbs;
-    int row_bytes;    // K / 2
-    int scale_bytes;  // K / 32
-    int nmac;         // ceil(K / 128)
 };
 
 __device__ __forceinline__ Operand make_operand(const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs,
                                                 int64_t row0, int64_t row_end, int tile_rows, int64_t K) {
     Operand op;
     const int64_t rows = row_end > row0 ? (row_end - row0 < tile_rows ? row_end - row0 : tile_rows) : 0;
-    op.row_bytes = (int)(K >> 1);
-    op.scale_bytes = (int)(K >> 5);
-    op.nmac = (int)((K + kMacro - 1) / kMacro);
+    const int64_t row_bytes = K >> 1, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro;
     const int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
-    op.codes = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(codes) + row0 * op.row_bytes, 0,
-                                                 (int)(rows * op.row_bytes), kRsrcFlags);
-    op.scales = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(scales) + row0 * op.scale_bytes, 0,
-                                                  (int)(rows * op.scale_bytes), kRsrcFlags);
-    op.mbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(mbs ? mbs + row0 * op.nmac : codes), 0,
-                                               mbs ? (int)(rows * op.nmac) : 0, kRsrcFlags);
+    op.codes = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(codes) + row0 * row_bytes, 0,
+                                                 (int)(rows * row_bytes), kRsrcFlags);
+    op.scales = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(scales) + row0 * scale_bytes, 0,
+                                                  (int)(rows * scale_bytes), kRsrcFlags);
+    op.mbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(mbs ? mbs + row0 * nmac : codes), 0,
+                                               mbs ? (int)(rows * nmac) : 0, kRsrcFlags);
     return op;
 }
 
 constexpr int kOob = 0x7FFFFFF0;  // byte offset beyond any buffer: the load returns zero
 
-// Codes of one stage straight into LDS.  The LDS image of an operand is row-major, 128 bytes (the
-// stage's 256 k) per row, with the eight 16-byte chunks of a row XOR-swizzled by (row >> 1) & 7:
-// chunk c of row r sits at r * 128 + ((c ^ ((r >> 1) & 7)) * 16).  A wavefront-wide load covers 8 rows;
-// lane l writes LDS slot l (hardware order) and therefore fetches row l / 8, chunk (l % 8) ^ swizzle:
-// eight lanes read one full 128-byte line of global memory, and the later fragment reads (16 lanes =
-// 16 consecutive rows, one chunk each) hit 16 distinct 16-byte bank groups.
-template <int kRows, int NW, bool kRaggedK>
-__device__ __forceinline__ void load_codes(const Operand& op, uint8_t* lds_codes, int64_t K, int k0, int tid) {
-    const int w = tid >> 6, l = tid & 63;
-    constexpr int kLoads = kRows / 8 / NW;
-#pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-        const int row0 = (i * NW + w) * 8;
-        const int row = row0 + (l >> 3);
-        const int c = (l & 7) ^ ((row >> 1) & 7);
-        int voff = row * op.row_bytes + c * 16;
-        if (kRaggedK && k0 + c * kBlock >= K) voff = kOob;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(op.codes, (lds_ptr_t)(lds_codes + row0 * (kStageK / 2)), 16, voff,
-                                                 k0 >> 1, 0, 0);
-    }
-}
-
-struct Small {
-    uint32_t scale;  // the four E8M0 bytes of one (row, macro block)
-    uint32_t m8;
-};
-
-// (row, macro block) pair p of the stage: its four E8M0 bytes and its MBS word.
-template <int kRows, bool kMbs, bool kScaleDword>
-__device__ __forceinline__ Small load_small(const Operand& op, int64_t K, int k0, int p) {
-    const int row = p >> 1;  // two lanes share a row, i.e. a cache line of scales
-    const int g = k0 / kMacro + (p & 1);
-    Small r;
-    const int off = row * op.scale_bytes + g * 4;
-    const bool have = g * kMacro < K && p < kRows * kStageMacros;
-    if (kScaleDword) {
-        r.scale = __builtin_amdgcn_raw_buffer_load_b32(op.scales, have ? off : kOob, 0, 0);
-    } else {
-        // rows are not dword aligned or the last macro block is short: byte loads, absent blocks read 0
-        r.scale = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int o = have && g * kMacro + j * kBlock < K ? off + j : kOob;
-            r.scale |= (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(op.scales, o, 0, 0) << (8 * j);
-        }
-    }
-    r.m8 = 0;
-    if (kMbs) r.m8 = __builtin_amdgcn_raw_buffer_load_b8(op.mbs, have ? row * op.nmac + g : kOob, 0, 0);
-    return r;
-}
-
-// Scale bytes regrouped: dword [macro][row / 64][16 q + row % 16] byte (row / 16) % 4 = E8M0 of k-block q.
-template <int kRows, bool kMbs>
-__device__ __forceinline__ void store_small(const Small& v, uint8_t* scale, uint8_t* sigma, int p) {
-    if (p >= kRows * kStageMacros) return;
-    const int row = p >> 1, mb = p & 1;
-    const int group = row >> 6, frag = (row >> 4) & 3, r = row & 15;
-    uint8_t* sb = scale + ((mb * (kRows / 64) + group) * kWave) * 4;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) sb[(q * 16 + r) * 4 + frag] = (uint8_t)(v.scale >> (8 * q));
-    // sigma = 1/F to within an ulp (the hardware reciprocal); F = 1 + m8/256 is exact
-    if (kMbs) reinterpret_cast<float*>(sigma)[mb * kRows + row] = __builtin_amdgcn_rcpf(1.0f + (float)v.m8 * (1.0f / 256.0f));
-}
-
-template <int kSelN, int kSelM>
 __device__ __forceinline__ v4f mfma_fp4(v4i n_frag, v4i m_frag, v4f c, uint32_t scale_n, uint32_t scale_m) {
     const v8i a = __builtin_shufflevector(n_frag, n_frag, 0, 1, 2, 3, -1, -1, -1, -1);
     const v8i b = __builtin_shufflevector(m_frag, m_frag, 0, 1, 2, 3, -1, -1, -1, -1);
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4 /*A: FP4*/, 4 /*B: FP4*/, kSelN,
-                                                            (int)scale_n, kSelM, (int)scale_m);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4 /*A: FP4*/, 4 /*B: FP4*/, 0, (int)scale_n,
+                                                            0, (int)scale_m);
 }
 
-// kMbs: apply the per-macro-block correction; kScaleDword: the four E8M0 bytes of a macro block are an
-// aligned dword (K % 128 == 0, 4-byte aligned scale arrays); kRaggedK: K is not a multiple of the stage.
-template <typename S, bool kMbs, bool kScaleDword, bool kRaggedK>
+// s_waitcnt vmcnt(n) lgkmcnt(0): at most n direct-to-LDS loads outstanding, own LDS traffic done.
+constexpr int wait_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
+
+// Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for ALL
+// outstanding vector-memory operations, which would drain the younger stages still in flight.
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// kMbs: apply the per-macro-block correction; kFast: aligned dword loads of scales and MBS words (see
+// Layout), otherwise byte loads; kRaggedK: K is not a multiple of the stage.
+template <typename S, bool kMbs, bool kFast, bool kRaggedK>
 __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
-    constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NT = S::NT, NW = S::NW;
+    constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NT = S::NT, NW = S::NW, kRows = S::kRows;
+    constexpr bool kScaleDword = kFast, kM8Quad = kFast;
+    using L = Layout<S, kScaleDword, kM8Quad>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile --------------------------------------------------------------------------
@@ -232,9 +194,149 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     }
     const Operand opa = make_operand(g.a_codes, g.a_scales, g.a_mbs, a_row0, a_end, TM, g.K);
     const Operand opb = make_operand(g.b_codes, g.b_scales, g.b_mbs, b_row0, b_end, TN, g.K);
+    const int K = (int)g.K;
+    const int row_bytes = K >> 1, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro;
 
-    const int tid = threadIdx.x, l = tid & 63, w = tid >> 6;
-    const int wm = w % S::NWM, wn = w / S::NWM;  // position of this wavefront in the tile
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept in a scalar register
+    const int wm = w % S::NWM, wn = w / S::NWM;              // position of this wavefront in the tile
+
+    // ---- per-lane byte offsets of the direct-to-LDS loads (constant over the K loop) ----------------
+    // Codes: load i of wavefront w covers the 8 rows (i * NW + w) * 8 .. + 7 of the A-then-B row space;
+    // lane l writes LDS slot l of that 1-KiB block (hardware order) and fetches row l / 8, chunk
+    // (l % 8) ^ ((row >> 1) & 7): chunk c of row r lives at r * 128 + ((c ^ ((r >> 1) & 7)) * 16).
+    constexpr int kCodeDma = L::kCodeDma;
+    int code_off[kCodeDma], code_chunk[kCodeDma];
+#pragma unroll
+    for (int i = 0; i < kCodeDma; ++i) {
+        const int row = ((i * NW + w) * 8 + (l >> 3)) - (i * NW * 8 < TM ? 0 : TM);  // row within its operand
+        code_chunk[i] = (l & 7) ^ ((row >> 1) & 7);
+        code_off[i] = row * row_bytes + code_chunk[i] * 16;
+    }
+    // Scales: dword loads fetch (row, macro block) pair p = (i * NW + w) * 64 + l, byte loads fetch byte
+    // p of the [row][8] image.  MBS words: byte loads of pair p.  Loads past the image are padding.
+    constexpr int kScaleDma = L::kScaleDma;
+    int scale_off[kScaleDma], scale_sub[kScaleDma];  // sub = k-block (byte loads) or macro block (dword loads)
+    bool scale_is_a[kScaleDma], scale_pad[kScaleDma];
+#pragma unroll
+    for (int i = 0; i < kScaleDma; ++i) {
+        const int p = (i * NW + w) * kWave + l;
+        const int grow = kScaleDword ? p >> 1 : p >> 3;  // row in the A-then-B row space
+        scale_sub[i] = kScaleDword ? p & 1 : p & 7;
+        scale_is_a[i] = (i * NW + w) * kWave < (kScaleDword ? TM * 2 : TM * 8);
+        scale_pad[i] = (i * NW + w) * kWave >= (kScaleDword ? kRows * 2 : kRows * 8);
+        const int row = grow - (scale_is_a[i] ? 0 : TM);
+        scale_off[i] = scale_pad[i] ? kOob : row * scale_bytes + scale_sub[i] * (kScaleDword ? 4 : 1);
+    }
+    // MBS words: quad mode fetches one dword per row (the words of two stages), byte mode one byte per
+    // (row, macro block) pair.
+    constexpr int kM8Dma = L::kM8Dma;
+    int m8_off[kM8Dma];
+    bool m8_is_a[kM8Dma], m8_pad[kM8Dma];
+#pragma unroll
+    for (int i = 0; i < kM8Dma; ++i) {
+        const int p = (i * NW + w) * kWave + l;
+        m8_is_a[i] = (i * NW + w) * kWave < (kM8Quad ? TM : TM * 2);
+        m8_pad[i] = (i * NW + w) * kWave >= (kM8Quad ? kRows : kRows * 2);
+        const int row = (kM8Quad ? p : p >> 1) - (m8_is_a[i] ? 0 : TM);
+        m8_off[i] = m8_pad[i] ? kOob : row * nmac + (kM8Quad ? 0 : p & 1);
+    }
+
+    auto dma_codes = [&](int s, auto part) {  // half of the code loads of stage s
+        constexpr int h = kCodeDma / 2, first = decltype(part)::value * h;
+        uint8_t* base = smem + (s % kCodeBufs) * L::kCodesStage;
+#pragma unroll
+        for (int i = first; i < first + h; ++i) {
+            int voff = code_off[i];
+            if (kRaggedK && s * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
+                                                     (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
+                                                     s * kRowStage, 0, 0);
+        }
+    };
+    auto dma_scales = [&](int s) {
+        uint8_t* base = smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage;
+#pragma unroll
+        for (int i = 0; i < kScaleDma; ++i) {
+            int voff = scale_off[i];
+            // past the end of K the block does not exist: read zero (2^-127), never a stray NaN scale
+            if (kRaggedK && (kScaleDword ? (s * kStageMacros + scale_sub[i]) * kMacro : (s * 8 + scale_sub[i]) * kBlock) >= K)
+                voff = kOob;
+            uint8_t* dst = scale_pad[i] ? smem + L::kDummy : base + (i * NW + w) * 256;  // one dword per lane
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(scale_is_a[i] ? opa.scales : opb.scales, (lds_ptr_t)dst,
+                                                     kScaleDword ? 4 : 1, voff, s * 8, 0, 0);
+        }
+    };
+    // Quad mode: the words of stages 2t and 2t + 1 as one dword per row into slot t % 2; issued every
+    // iteration so that each wavefront's load count stays fixed, odd calls go to the padding area.
+    // Byte mode: the words of stage s, one zero-extended byte per dword, into slot s % 3.
+    auto dma_m8 = [&](int s) {
+#pragma unroll
+        for (int i = 0; i < kM8Dma; ++i) {
+            if constexpr (kM8Quad) {
+                const bool real = (s & 1) == 0 && !m8_pad[i];
+                uint8_t* dst = real ? smem + L::kM8Base + ((s >> 1) & 1) * L::kM8Stage + (i * NW + w) * 256 : smem + L::kDummy;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(m8_is_a[i] ? opa.mbs : opb.mbs, (lds_ptr_t)dst, 4,
+                                                         (s & 1) == 0 ? m8_off[i] : kOob, s * kStageMacros, 0, 0);
+            } else {
+                uint8_t* dst = m8_pad[i] ? smem + L::kDummy : smem + L::kM8Base + (s % 3) * L::kM8Stage + (i * NW + w) * 256;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(m8_is_a[i] ? opa.mbs : opb.mbs, (lds_ptr_t)dst, 1, m8_off[i],
+                                                         s * kStageMacros, 0, 0);
+            }
+        }
+    };
+    // MBS words of stage s (landed) -> fp32 sigma = 1/F, F = 1 + m8/256 exact, reciprocal within an ulp.
+    auto convert_sigma = [&](int s) {
+        const uint32_t* raw = reinterpret_cast<const uint32_t*>(
+            smem + L::kM8Base + (kM8Quad ? (s >> 1) & 1 : s % 3) * L::kM8Stage);
+        float* sig = reinterpret_cast<float*>(smem + L::kSigmaBase + (s % kSigmaBufs) * L::kSigmaStage);
+        const int g0 = s * kStageMacros;
+#pragma unroll
+        for (int i = 0; i < ceil_div(kRows * 2, NT); ++i) {
+            const int p = i * NT + tid;  // pair (row p / 2 of the A-then-B row space, macro block p % 2)
+            if (kRows * 2 % NT == 0 || p < kRows * 2) {
+                uint32_t m8 = kM8Quad ? (raw[p >> 1] >> (8 * ((s & 1) * 2 + (p & 1)))) & 0xFFu : raw[p] & 0xFFu;
+                // a macro block past the end of K has no word (the row's next bytes belong to other blocks)
+                if (g0 + (p & 1) >= nmac) m8 = 0;
+                sig[(p & 1) * kRows + (p >> 1)] = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
+            }
+        }
+    };
+
+    // ---- operands of one macro block in registers ---------------------------------------------------
+    struct Frags {
+        v4i m[FM], n[FN];
+        uint32_t scl_m[FM], scl_n[FN];
+        float sig_m[FM];
+        v4f sig_n[FN];
+    };
+    // byte offset of this lane's 16 bytes inside a 16-row block of the swizzled code image, per macro block
+    int frag_off[kStageMacros];
+#pragma unroll
+    for (int mb = 0; mb < kStageMacros; ++mb)
+        frag_off[mb] = (l & 15) * kRowStage + (((mb * 4 + (l >> 4)) ^ ((l & 15) >> 1)) * 16);
+    // this lane's E8M0 byte inside a 16-row block of the [row][8] scale image (+ 4 * macro block)
+    const int lane_scale = ((l & 15) * 8 + (l >> 4)) * L::kScaleStride;
+
+    auto read_frags = [&](Frags& f, int s, auto mb_) {
+        constexpr int mb = decltype(mb_)::value;
+        const uint8_t* cm = smem + (s % kCodeBufs) * L::kCodesStage;
+        const uint8_t* cn = cm + TM * kRowStage;
+        const uint8_t* sc = smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage + lane_scale + mb * 4 * L::kScaleStride;
+        const float* sig = reinterpret_cast<const float*>(smem + L::kSigmaBase + (s % kSigmaBufs) * L::kSigmaStage) + mb * kRows;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            f.m[i] = *reinterpret_cast<const v4i*>(cm + (wm * FM + i) * (16 * kRowStage) + frag_off[mb]);
+            f.scl_m[i] = sc[(wm * FM + i) * 128 * L::kScaleStride];
+            if constexpr (kMbs) f.sig_m[i] = sig[(wm * FM + i) * 16 + (l & 15)];
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            f.n[j] = *reinterpret_cast<const v4i*>(cn + (wn * FN + j) * (16 * kRowStage) + frag_off[mb]);
+            f.scl_n[j] = sc[(TM / 16 + wn * FN + j) * 128 * L::kScaleStride];
+            if constexpr (kMbs) f.sig_n[j] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 16 + (l >> 4) * 4);
+        }
+    };
 
     v4f acc[FM][FN];
 #pragma unroll
@@ -242,126 +344,113 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int kPairsM = (TM * kStageMacros + NT - 1) / NT, kPairsN = (TN * kStageMacros + NT - 1) / NT;
-    constexpr int kDepth = S::NBUF - 1;  // code stages in flight
-    // Direct-to-LDS loads one wavefront issues per stage.  They complete in order, so "at most
-    // (kDepth - 1) stages' worth outstanding" means the oldest stage in flight has landed.
-    constexpr int kDmaPerStage = (TM + TN) / 8 / NW;
-    constexpr int kWaitOps = (kDepth - 1) * kDmaPerStage;
-    static_assert(kWaitOps < 64, "vmcnt is a 6-bit counter");
-    // s_waitcnt vmcnt(kWaitOps) lgkmcnt(0): the landed stage plus this wavefront's own LDS stores
-    constexpr int kWaitImm = (kWaitOps & 0xF) | ((kWaitOps >> 4) << 14) | 0x0070;
-
-    auto issue_codes = [&](int s) {
-        uint8_t* cbase = smem + (s % S::NBUF) * S::kCodesStage;
-        const int k0 = s * kStageK;
-        load_codes<TM, NW, kRaggedK>(opa, cbase, g.K, k0, tid);
-        load_codes<TN, NW, kRaggedK>(opb, cbase + TM * (kStageK / 2), g.K, k0, tid);
+    // FM x FN matrix instructions on one macro block; `between(t)` runs after instruction t and is
+    // where the loads of later stages are slipped in.
+    auto multiply = [&](const Frags& f, auto&& between) {
+        static_for<FM>([&](auto mi) {
+            static_for<FN>([&](auto ni) {
+                constexpr int i = decltype(mi)::value, j = decltype(ni)::value;
+                if constexpr (kMbs) {
+                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                    const v4f p = mfma_fp4(f.n[j], f.m[i], zero, f.scl_n[j], f.scl_m[i]);
+                    const float sa_ = f.sig_m[i];
+                    acc[i][j].x = fmaf(p.x, sa_ * f.sig_n[j].x, acc[i][j].x);
+                    acc[i][j].y = fmaf(p.y, sa_ * f.sig_n[j].y, acc[i][j].y);
+                    acc[i][j].z = fmaf(p.z, sa_ * f.sig_n[j].z, acc[i][j].z);
+                    acc[i][j].w = fmaf(p.w, sa_ * f.sig_n[j].w, acc[i][j].w);
+                } else {
+                    acc[i][j] = mfma_fp4(f.n[j], f.m[i], acc[i][j], f.scl_n[j], f.scl_m[i]);
+                }
+                between(std::integral_constant<int, i * FN + j>{});
+            });
+        });
     };
-    auto issue_small = [&](int s, Small (&sa)[kPairsM], Small (&sb)[kPairsN]) {
-        const int k0 = s * kStageK;
-#pragma unroll
-        for (int i = 0; i < kPairsM; ++i) sa[i] = load_small<TM, kMbs, kScaleDword>(opa, g.K, k0, i * NT + tid);
-#pragma unroll
-        for (int i = 0; i < kPairsN; ++i) sb[i] = load_small<TN, kMbs, kScaleDword>(opb, g.K, k0, i * NT + tid);
-    };
-    // Publish stage s: its scales and sigmas go to small slot s % 2 (last read two stages ago); its
-    // codes have landed once at most kWaitOps younger direct-to-LDS loads are outstanding.
-    auto commit_stage = [&](int s, const Small (&sa)[kPairsM], const Small (&sb)[kPairsN]) {
-        uint8_t* sbase = smem + S::kSmallBase + (s & 1) * S::kSmallStage;
-#pragma unroll
-        for (int i = 0; i < kPairsM; ++i)
-            store_small<TM, kMbs>(sa[i], sbase + S::kScaleM, sbase + S::kSigmaM, i * NT + tid);
-#pragma unroll
-        for (int i = 0; i < kPairsN; ++i)
-            store_small<TN, kMbs>(sb[i], sbase + S::kScaleN, sbase + S::kSigmaN, i * NT + tid);
-        __builtin_amdgcn_s_waitcnt(kWaitImm);
-        // Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for
-        // ALL outstanding vector-memory operations, which would drain the younger stages still in flight.
-        asm volatile("s_barrier" ::: "memory");
-    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    constexpr int kMfmas = FM * FN;
 
-    // byte offset of this lane's 16 bytes inside a 16-row block of the swizzled LDS image, per macro block
-    int frag_off[kStageMacros];
-#pragma unroll
-    for (int mb = 0; mb < kStageMacros; ++mb)
-        frag_off[mb] = (l & 15) * (kStageK / 2) + (((mb * 4 + (l >> 4)) ^ ((l & 15) >> 1)) * 16);
-
-    const int nstages = (int)((g.K + kStageK - 1) / kStageK);
+    // ---- prologue: stages 0 and 1 (and the MBS words of stage 2) -------------------------------------
+    const int nstages = (K + kStageK - 1) / kStageK;
+    Frags f0, f1;
     if (nstages > 0) {
-        Small sa[kPairsM], sb[kPairsN];
-        issue_codes(0);
-        issue_small(0, sa, sb);
-#pragma unroll
-        for (int d = 1; d < kDepth; ++d) issue_codes(d);
-        commit_stage(0, sa, sb);
+        dma_codes(0, C0{});
+        dma_codes(0, C1{});
+        dma_scales(0);
+        dma_codes(1, C0{});
+        dma_codes(1, C1{});
+        dma_scales(1);
+        if constexpr (kMbs) {
+            dma_m8(0);
+            dma_m8(1);  // quad mode: padding
+            dma_m8(2);
+        }
+        __builtin_amdgcn_s_waitcnt(wait_imm(0));
+        bare_barrier();
+        if constexpr (kMbs) {
+            convert_sigma(0);
+            convert_sigma(1);
+            __builtin_amdgcn_s_waitcnt(wait_imm(0));
+            bare_barrier();
+        }
+        read_frags(f0, 0, C0{});
     }
 
+    // Loads younger than stage s + 1 at the barrier inside iteration s: the first half of the codes of
+    // stage s + 2 and the MBS words of stage s + 3.
+    constexpr int kYounger = kCodeDma / 2 + (kMbs ? kM8Dma : 0);
+    static_assert(kYounger < 64, "vmcnt is a 6-bit counter");
+    constexpr int kStepA = kMfmas / (kCodeDma / 2 + (kMbs ? 1 : 0) + 1);  // spacing of the slipped-in loads
+    constexpr int kStepB = kMfmas / (kCodeDma / 2 + 1 + 1);
+
     for (int s = 0; s < nstages; ++s) {
-        const uint8_t* cm = smem + (s % S::NBUF) * S::kCodesStage;
-        const uint8_t* cn = cm + TM * (kStageK / 2);
-        const uint8_t* sm_base = smem + S::kSmallBase + (s & 1) * S::kSmallStage;
-        // The register-staged scales of the next stage first, then the codes of stage s + kDepth into
-        // the buffer that was read last in the previous iteration (every wavefront is past the barrier
-        // that ended it).  In this order, "the scales have arrived" implies that every older
-        // direct-to-LDS load has landed too.  Unconditional, so that the loop body stays one basic
-        // block: past the end of K the loads are out of range or land in rows nobody reads.
-        Small sa[kPairsM], sb[kPairsN];
-        issue_small(s + 1, sa, sb);
-        issue_codes(s + kDepth);
+        // Past the end of K the loads below are out of range or land in rows nobody reads; issuing them
+        // unconditionally keeps the loop body one basic block.
+        read_frags(f1, s, C1{});
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mb = 0; mb < kStageMacros; ++mb) {
-            v4i m_frag[FM], n_frag[FN];
-            float sig_m[FM];
-            v4f sig_n[FN];
-            uint32_t scl_m[(FM + 3) / 4], scl_n[(FN + 3) / 4];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                m_frag[i] = *reinterpret_cast<const v4i*>(cm + (wm * FM + i) * (16 * kStageK / 2) + frag_off[mb]);
-                if constexpr (kMbs)
-                    sig_m[i] = reinterpret_cast<const float*>(sm_base + S::kSigmaM)[mb * TM + (wm * FM + i) * 16 + (l & 15)];
+        multiply(f0, [&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            // first half of the codes of stage s + 2, into the buffer stage s - 1 was read from (those reads
+            // completed before the barrier of the previous iteration)
+            constexpr int h = kCodeDma / 2;
+            if constexpr ((t + 1) % kStepA == 0 && (t + 1) / kStepA <= h) {
+                constexpr int i = (t + 1) / kStepA - 1;
+                uint8_t* base = smem + ((s + 2) % kCodeBufs) * L::kCodesStage;
+                int voff = code_off[i];
+                if (kRaggedK && (s + 2) * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
+                                                         (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
+                                                         (s + 2) * kRowStage, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            } else if constexpr (kMbs && (t + 1) == kStepA * (h + 1)) {
+                dma_m8(s + 3);  // slot of stage s, whose words were converted two iterations ago
+                __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                n_frag[j] = *reinterpret_cast<const v4i*>(cn + (wn * FN + j) * (16 * kStageK / 2) + frag_off[mb]);
-                if constexpr (kMbs)
-                    sig_n[j] = *reinterpret_cast<const v4f*>(sm_base + S::kSigmaN +
-                                                             (mb * TN + (wn * FN + j) * 16 + (l >> 4) * 4) * 4);
-            }
-            // scale dwords: group = (first fragment) / 4; a 2-fragment wave uses half a dword
-#pragma unroll
-            for (int d = 0; d < (FM + 3) / 4; ++d) {
-                const int group = (wm * FM) / 4 + d;
-                scl_m[d] = reinterpret_cast<const uint32_t*>(sm_base + S::kScaleM)[(mb * (TM / 64) + group) * kWave + l];
-                if (FM == 2) scl_m[d] >>= 16 * (wm & 1);
-            }
-#pragma unroll
-            for (int d = 0; d < (FN + 3) / 4; ++d) {
-                const int group = (wn * FN) / 4 + d;
-                scl_n[d] = reinterpret_cast<const uint32_t*>(sm_base + S::kScaleN)[(mb * (TN / 64) + group) * kWave + l];
-                if (FN == 2) scl_n[d] >>= 16 * (wn & 1);
-            }
-            static_for<FM>([&](auto mi) {
-                static_for<FN>([&](auto ni) {
-                    constexpr int i = decltype(mi)::value, j = decltype(ni)::value;
-                    if constexpr (kMbs) {
-                        const v4f zero = {0.f, 0.f, 0.f, 0.f};
-                        const v4f p = mfma_fp4<j % 4, i % 4>(n_frag[j], m_frag[i], zero, scl_n[j / 4], scl_m[i / 4]);
-                        const float sa_ = sig_m[i];
-                        acc[i][j].x = fmaf(p.x, sa_ * sig_n[j].x, acc[i][j].x);
-                        acc[i][j].y = fmaf(p.y, sa_ * sig_n[j].y, acc[i][j].y);
-                        acc[i][j].z = fmaf(p.z, sa_ * sig_n[j].z, acc[i][j].z);
-                        acc[i][j].w = fmaf(p.w, sa_ * sig_n[j].w, acc[i][j].w);
-                    } else {
-                        acc[i][j] = mfma_fp4<j % 4, i % 4>(n_frag[j], m_frag[i], acc[i][j], scl_n[j / 4], scl_m[i / 4]);
-                    }
-                });
-            });
-        }
-        // keep the multiply phase ahead of the wait for the next stage's loads
+        });
         __builtin_amdgcn_sched_barrier(0);
-        commit_stage(s + 1, sa, sb);
+        // publish stage s + 1: everything issued before this iteration has landed
+        __builtin_amdgcn_s_waitcnt(wait_imm(kYounger));
+        bare_barrier();
+        if constexpr (kMbs) convert_sigma(s + 2);  // into the slot of stage s, all of whose reads are done
+        read_frags(f0, s + 1, C0{});
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(f1, [&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            constexpr int h = kCodeDma / 2;
+            if constexpr ((t + 1) % kStepB == 0 && (t + 1) / kStepB <= h) {
+                constexpr int i = h + (t + 1) / kStepB - 1;
+                uint8_t* base = smem + ((s + 2) % kCodeBufs) * L::kCodesStage;
+                int voff = code_off[i];
+                if (kRaggedK && (s + 2) * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
+                                                         (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
+                                                         (s + 2) * kRowStage, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            } else if constexpr ((t + 1) == kStepB * (h + 1)) {
+                dma_scales(s + 2);  // slot of stage s: its bytes were all read before the barrier above
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- epilogue: lane holds C[m][n .. n+3] for each of its fragments ------------------------------
@@ -377,15 +466,14 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
             const v4f v = acc[i][j];
             if (g.c_bf16) {
                 uint16_t* o = static_cast<uint16_t*>(g.C) + m * g.ldc + n;
-                const uint32_t b0 = f32_to_bf16_bits(v.x), b1 = f32_to_bf16_bits(v.y);
-                const uint32_t b2 = f32_to_bf16_bits(v.z), b3 = f32_to_bf16_bits(v.w);
+                const uint32_t lo = pack_bf16(v.x, v.y), hi = pack_bf16(v.z, v.w);  // round to nearest even
                 if (g.vec_store && n + 3 < g.N) {
-                    *reinterpret_cast<uint2*>(o) = make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
+                    *reinterpret_cast<uint2*>(o) = make_uint2(lo, hi);
                 } else {
-                    o[0] = (uint16_t)b0;
-                    if (n + 1 < g.N) o[1] = (uint16_t)b1;
-                    if (n + 2 < g.N) o[2] = (uint16_t)b2;
-                    if (n + 3 < g.N) o[3] = (uint16_t)b3;
+                    o[0] = (uint16_t)lo;
+                    if (n + 1 < g.N) o[1] = (uint16_t)(lo >> 16);
+                    if (n + 2 < g.N) o[2] = (uint16_t)hi;
+                    if (n + 3 < g.N) o[3] = (uint16_t)(hi >> 16);
                 }
             } else {
                 float* o = static_cast<float*>(g.C) + m * g.ldc + n;
@@ -402,8 +490,9 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     }
 }
 
-template <typename S, bool kMbs, bool kScaleDword, bool kRaggedK>
+template <typename S, bool kMbs, bool kFast, bool kRaggedK>
 int launch_variant(GemmArgs g, bool grouped, hipStream_t s) {
+    using L = Layout<S, kFast, kFast>;
     const int64_t tiles_m = (g.M + S::TM - 1) / S::TM + (grouped ? g.num_groups : 0);
     const int64_t tiles_n = (g.N + S::TN - 1) / S::TN;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
@@ -411,36 +500,32 @@ int launch_variant(GemmArgs g, bool grouped, hipStream_t s) {
     g.tiles_n = (int)tiles_n;
     const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
     static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
-    auto* fn = gemm_kernel<S, kMbs, kScaleDword, kRaggedK>;
+    auto* fn = gemm_kernel<S, kMbs, kFast, kRaggedK>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                S::kLdsBytes) != hipSuccess) {
+                                L::kLdsBytes) != hipSuccess) {
             (void)hipGetLastError();
             return MX_ELAUNCH;
         }
         attr_set = true;
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(S::NT), S::kLdsBytes, s, g);
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(S::NT), L::kLdsBytes, s, g);
     return launch_status();
 }
 
-template <typename S>
-int launch_shape(const GemmArgs& g, bool grouped, bool use_mbs, bool dword, bool ragged, hipStream_t s) {
-    if (use_mbs) {
-        if (!dword) return launch_variant<S, true, false, true>(g, grouped, s);
-        return ragged ? launch_variant<S, true, true, true>(g, grouped, s)
-                      : launch_variant<S, true, true, false>(g, grouped, s);
-    }
-    if (!dword) return launch_variant<S, false, false, true>(g, grouped, s);
-    return ragged ? launch_variant<S, false, true, true>(g, grouped, s)
-                  : launch_variant<S, false, true, false>(g, grouped, s);
+template <typename S, bool kFast>
+int launch_shape(const GemmArgs& g, bool grouped, bool use_mbs, bool ragged, hipStream_t s) {
+    if (use_mbs)
+        return ragged ? launch_variant<S, true, kFast, true>(g, grouped, s)
+                      : launch_variant<S, true, kFast, false>(g, grouped, s);
+    return ragged ? launch_variant<S, false, kFast, true>(g, grouped, s)
+                  : launch_variant<S, false, kFast, false>(g, grouped, s);
 }
 
-using Shape128 = Shape<2, 4, 4, 2, 3>;      // 8 waves, 128 x 128 tile, 64 x 32 per wave, 3 code stages
-using Shape256x128 = Shape<4, 2, 4, 4, 3>;  // 8 waves, 256 x 128 tile, 64 x 64 per wave, 3 code stages
-using Shape256 = Shape<2, 4, 8, 4, 2>;      // 8 waves, 256 x 256 tile, 128 x 64 per wave, 2 code stages
+using Shape128 = Shape<2, 4, 4, 2>;      // 8 waves, 128 x 128 tile, 64 x 32 per wave
+using Shape256x128 = Shape<4, 2, 4, 4>;  // 8 waves, 256 x 128 tile, 64 x 64 per wave
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = 256x256
+int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -471,19 +556,21 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = mbs_entry && (a_mbs || b_mbs);
-    const bool dword = (K % kMacro) == 0 && aligned(a_scales, 4) && aligned(b_scales, 4);
     const bool ragged = (K % kStageK) != 0;
+    // Fast variant: scales of a macro block and MBS words of two stages are aligned dwords.
+    bool fast = (K % kMacro) == 0 && aligned(a_scales, 4) && aligned(b_scales, 4);
+    if (use_mbs) fast = fast && (K % (2 * kStageK)) == 0 && (!a_mbs || aligned(a_mbs, 4)) && (!b_mbs || aligned(b_mbs, 4));
 
-    // Tile shape: large tiles need enough of them to fill 256 compute units.
+    // Tile shape: the large tile needs enough tiles to fill 256 compute units, and the fast variant
+    // (the byte-wise fallback does not fit its LDS).
     int shape = 0;
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t256x128 = ((M + 255) / 256) * ((N + 127) / 128);
-    if (t256 >= 512 && !use_mbs) shape = 2;  // with MBS the 128 x 64 wave tile runs out of registers
-    else if (t256x128 >= 512) shape = 1;
+    const int64_t t256x128 = ((M + 255) / 256) * ((N + 127) / 128);
+    if (t256x128 >= 512) shape = 1;
     if (grouped) shape = 0;
     if (g_force_shape >= 0) shape = g_force_shape;
-    if (shape == 2) return launch_shape<Shape256>(g, grouped, use_mbs, dword, ragged, s);
-    if (shape == 1) return launch_shape<Shape256x128>(g, grouped, use_mbs, dword, ragged, s);
-    return launch_shape<Shape128>(g, grouped, use_mbs, dword, ragged, s);
+    if (!fast) return launch_shape<Shape128, false>(g, grouped, use_mbs, ragged, s);
+    if (shape >= 1) return launch_shape<Shape256x128, true>(g, grouped, use_mbs, ragged, s);
+    return launch_shape<Shape128, true>(g, grouped, use_mbs, ragged, s);
 }
 
 }  // namespace
