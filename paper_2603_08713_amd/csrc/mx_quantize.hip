@@ -8,8 +8,9 @@
 //
 // Arithmetic is arranged so that every decision is exact:
 //   - MBS word (Sec. 4.3.1, Eq. 3): the 8 leading mantissa bits of 6/absmax128 depend only on
-//     the 7 mantissa bits of the bf16 absmax, so they come from a 128-entry table built with
-//     integer division.
+//     the 7 mantissa bits k of the bf16 absmax: floor(N / (128 + k)) - 256 with N = 49152 or 98304.
+//     The quotient is taken with the hardware reciprocal plus 2^-10: N / (128 + k) is either an
+//     integer (k = 0, 64) or at least 1/255 away from one, far more than the reciprocal's error.
 //   - x * F (F = 1 + m8/256) has at most 17 significant bits and is exact in fp32, and so is its
 //     product with the power-of-two block scale.
 //   - the block exponent is read off the fp32 pattern of absmax * F with a carry trick: adding
@@ -31,7 +32,8 @@ struct QuantArgs {
     uint8_t* codes;
     uint8_t* scales;
     uint8_t* mbs;
-    int64_t K, ldx, chunks_per_row, total_chunks, nmac;
+    int64_t K, ldx, nmac;
+    uint32_t chunks_per_row, total_chunks;
     uint32_t carry;  // 2^23 - 1 - mantissa threshold of the rule, 0 for OCP
     int rule;
     int use_mbs;
@@ -51,6 +53,12 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
 __device__ __forceinline__ uint32_t mbs_word_of_mantissa(uint32_t k) {
     const uint32_t n = 128u + k;
     return (k <= 64u ? 49152u / n : 98304u / n) - 256u;
+}
+// The same quotient through the hardware reciprocal (see the note at the top of the file).
+__device__ __forceinline__ uint32_t mbs_word_of_mantissa_fast(uint32_t k) {
+    const float num = k <= 64u ? 49152.0f : 98304.0f;
+    const float quo = fmaf(num, __builtin_amdgcn_rcpf((float)(128u + k)), 0x1.0p-10f);
+    return (uint32_t)quo - 256u;
 }
 
 // Round |t| (t already multiplied by the block scale) to the E2M1 grid, nearest-even, saturating.
@@ -72,8 +80,7 @@ struct ChunkResult {
 };
 
 // All-integer path, exact for every bf16 input including subnormals, huge values and Inf/NaN.
-__device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int use_mbs,
-                                                         const uint8_t* table) {
+__device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int use_mbs) {
     uint32_t h[8] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16,
                      v.z & 0xFFFFu, v.z >> 16, v.w & 0xFFFFu, v.w >> 16};
     uint32_t amax = 0, nf = 0;
@@ -94,7 +101,7 @@ __device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int 
     if (use_mbs && mmax) {
         uint32_t k = mmax & 0x7Fu;
         if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;  // normalise a subnormal absmax
-        m8 = table[k];
+        m8 = mbs_word_of_mantissa(k);
     }
     const uint32_t u = 256u + m8;  // F = u / 256
 
@@ -137,8 +144,8 @@ __device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int 
     return {codes, (uint32_t)E, m8};
 }
 
-template <bool kHwCvt>
-__device__ __forceinline__ ChunkResult quantize_chunk(u32x4 v, const QuantArgs& q, const uint8_t* table) {
+template <bool kHwCvt, bool kMbs>
+__device__ __forceinline__ ChunkResult quantize_chunk(u32x4 v, const QuantArgs& q) {
     // lane, block and macro-block absmax on the magnitude bits
     uint32_t m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
                             pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
@@ -148,85 +155,98 @@ __device__ __forceinline__ ChunkResult quantize_chunk(u32x4 v, const QuantArgs& 
 
     // exponent field outside [24, 249] (or Inf/NaN): leave fp32 arithmetic, wave-uniformly
     const bool odd = (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
-    if (__builtin_amdgcn_ballot_w64(odd) != 0) return quantize_chunk_exact(v, q.rule, q.use_mbs, table);
-
-    uint32_t m8 = 0;
-    if (q.use_mbs) {
-        uint32_t mmax = max(amax, dpp_row_ror4(amax));
-        mmax = max(mmax, dpp_row_ror8(mmax));
-        m8 = mmax ? table[mmax & 0x7Fu] : 0u;
-    }
-    // absmax * F is exact in fp32; exponent field + carry gives the stored byte
-    const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));
-    uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - 2u;
-    E = amax ? E : 127u;
-    // multiplier F * 2^(127-E): exponent field 254-E under F's mantissa
-    const float mult = __uint_as_float(((254u - E) << 23) | (m8 << 15));
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) return quantize_chunk_exact(v, q.rule, kMbs);
 
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     uint32_t codes = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float t0 = __uint_as_float(w[i] << 16) * mult;
-        const float t1 = __uint_as_float(w[i] & 0xFFFF0000u) * mult;
-        if constexpr (kHwCvt) {
-            // hardware fp32 -> E2M1 pair convert (scale 1: the block scale is already applied)
-            if (i == 0) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 0);
-            if (i == 1) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 1);
-            if (i == 2) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 2);
-            if (i == 3) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 3);
-        } else {
-            codes |= (e2m1_code_alu(t0) | (e2m1_code_alu(t1) << 4)) << (8 * i);
+    if constexpr (!kMbs && kHwCvt) {
+        // no MBS: the block exponent comes straight off the bf16 absmax, and the hardware converts
+        // bf16 pairs with the block scale applied (x / 2^(E-127), nearest-even, saturating)
+        uint32_t E = (((amax << 16) + q.carry) >> 23) - 2u;
+        E = amax ? E : 127u;
+        const float scale = __uint_as_float(E << 23);
+        typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+        codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(codes, __builtin_bit_cast(v2bf, w[0]), scale, 0);
+        codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(codes, __builtin_bit_cast(v2bf, w[1]), scale, 1);
+        codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(codes, __builtin_bit_cast(v2bf, w[2]), scale, 2);
+        codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(codes, __builtin_bit_cast(v2bf, w[3]), scale, 3);
+        return {codes, E, 0u};
+    } else {
+        uint32_t m8 = 0;
+        if constexpr (kMbs) {
+            uint32_t mmax = max(amax, dpp_row_ror4(amax));
+            mmax = max(mmax, dpp_row_ror8(mmax));
+            m8 = mmax ? mbs_word_of_mantissa_fast(mmax & 0x7Fu) : 0u;
         }
+        // absmax * F is exact in fp32; exponent field + carry gives the stored byte
+        const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));
+        uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - 2u;
+        E = amax ? E : 127u;
+        // multiplier F * 2^(127-E): exponent field 254-E under F's mantissa
+        const float mult = __uint_as_float(((254u - E) << 23) | (m8 << 15));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float t0 = __uint_as_float(w[i] << 16) * mult;
+            const float t1 = __uint_as_float(w[i] & 0xFFFF0000u) * mult;
+            if constexpr (kHwCvt) {
+                // hardware fp32 -> E2M1 pair convert (scale 1: the block scale is already applied)
+                if (i == 0) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 0);
+                if (i == 1) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 1);
+                if (i == 2) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 2);
+                if (i == 3) codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 3);
+            } else {
+                codes |= (e2m1_code_alu(t0) | (e2m1_code_alu(t1) << 4)) << (8 * i);
+            }
+        }
+        return {codes, E, m8};
     }
-    return {codes, E, m8};
 }
 
-template <bool kHwCvt>
+template <bool kHwCvt, bool kMbs>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
-    __shared__ uint8_t table[128];
-    if (threadIdx.x < 128) table[threadIdx.x] = (uint8_t)mbs_word_of_mantissa(threadIdx.x);
-    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kThreads / kWave);
 
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    const int64_t nwaves = (int64_t)gridDim.x * (kThreads / kWave);
-
-    for (int64_t c0 = wave * kUnroll; c0 < q.total_chunks; c0 += nwaves * kUnroll) {
+    // chunk ids are wave-uniform: (row, chunk-in-row) is found once per batch of kUnroll chunks and then
+    // stepped, so the division stays off the per-element path
+    for (uint32_t c0 = wave * kUnroll; c0 < q.total_chunks; c0 += nwaves * kUnroll) {
         u32x4 v[kUnroll];
-        int64_t row[kUnroll], col[kUnroll];
+        uint32_t row[kUnroll], col[kUnroll];
         bool valid[kUnroll];
+        uint32_t r = c0 / q.chunks_per_row, cc = c0 - r * q.chunks_per_row;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int64_t c = c0 + u;
-            row[u] = c / q.chunks_per_row;
-            col[u] = (c - row[u] * q.chunks_per_row) * kChunk + lane * 8;
-            valid[u] = c < q.total_chunks && col[u] < q.K;
+            row[u] = r;
+            col[u] = cc * kChunk + lane * 8;
+            valid[u] = c0 + u < q.total_chunks && col[u] < q.K;
             v[u] = u32x4{0, 0, 0, 0};
             if (valid[u]) {
-                const u32x4* p = reinterpret_cast<const u32x4*>(q.x + row[u] * q.ldx + col[u]);
-                v[u] = __builtin_nontemporal_load(p);
+                const uint16_t* rowp = q.x + (int64_t)r * q.ldx;  // uniform base + 32-bit lane offset
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rowp + col[u]));
             }
+            if (++cc == q.chunks_per_row) { cc = 0; ++r; }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             if (c0 + u >= q.total_chunks) break;  // wave-uniform
-            const ChunkResult r = quantize_chunk<kHwCvt>(v[u], q, table);
+            const ChunkResult res = quantize_chunk<kHwCvt, kMbs>(v[u], q);
             // scales of the macro block gathered into one dword across the row of 16 lanes
-            uint32_t ew = r.E << (8 * ((lane >> 2) & 3));
+            uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
             if ((lane & 3) != 0) ew = 0;
             ew |= dpp_row_ror4(ew);
             ew |= dpp_row_ror8(ew);
             if (!valid[u]) continue;
-            const int64_t kblk = col[u] >> 5;
-            uint8_t* srow = q.scales + row[u] * (q.K >> 5);
-            *reinterpret_cast<uint32_t*>(q.codes + row[u] * (q.K >> 1) + (col[u] >> 1)) = r.codes;
+            const uint32_t kblk = col[u] >> 5;
+            uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
+            uint8_t* crow = q.codes + (int64_t)row[u] * (q.K >> 1);
+            *reinterpret_cast<uint32_t*>(crow + (col[u] >> 1)) = res.codes;
             if (q.scales_dword) {
                 if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
             } else if ((lane & 3) == 0) {
-                srow[kblk] = (uint8_t)r.E;
+                srow[kblk] = (uint8_t)res.E;
             }
-            if (q.use_mbs && (lane & 15) == 0) q.mbs[row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)r.m8;
+            if (kMbs && (lane & 15) == 0) q.mbs[(int64_t)row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)res.m8;
         }
     }
 }
@@ -249,23 +269,31 @@ int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rul
     q.mbs = mbs;
     q.K = K;
     q.ldx = ldx;
-    q.chunks_per_row = (K + kChunk - 1) / kChunk;
-    q.total_chunks = q.chunks_per_row * rows;
+    const int64_t cpr = (K + kChunk - 1) / kChunk;
+    if (cpr * rows >= ((int64_t)1 << 32)) return MX_EINVAL;  // chunk ids are 32-bit
+    q.chunks_per_row = (uint32_t)cpr;
+    q.total_chunks = (uint32_t)(cpr * rows);
     q.nmac = (K + kMacro - 1) / kMacro;
     q.rule = rule;
     q.use_mbs = use_mbs;
     q.carry = rule == MX_RULE_FLOOR ? 0x3FFFFFu : rule == MX_RULE_OAS ? 0x1FFFFFu : 0u;
     q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
 
-    const int64_t waves_needed = (q.total_chunks + kUnroll - 1) / kUnroll;
+    const int64_t waves_needed = ((int64_t)q.total_chunks + kUnroll - 1) / kUnroll;
     int64_t blocks = (waves_needed + (kThreads / kWave) - 1) / (kThreads / kWave);
-    const int64_t max_blocks = 256 * 8;  // 8 resident workgroups per compute unit
+    // one batch of kUnroll chunks per wavefront (the hardware balances the workgroups); the loop in
+    // the kernel only matters beyond this cap
+    const int64_t max_blocks = 1 << 22;
     if (blocks > max_blocks) blocks = max_blocks;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (g_quant_hwcvt)
-        hipLaunchKernelGGL(quantize_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, s, q);
-    else
-        hipLaunchKernelGGL(quantize_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, s, q);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (g_quant_hwcvt) {
+        if (use_mbs) hipLaunchKernelGGL((quantize_kernel<true, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((quantize_kernel<true, false>), grid, block, 0, s, q);
+    } else {
+        if (use_mbs) hipLaunchKernelGGL((quantize_kernel<false, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((quantize_kernel<false, false>), grid, block, 0, s, q);
+    }
     return launch_status();
 }
 
