@@ -45,12 +45,13 @@ constexpr int kStageK = 256;  // K elements per pipeline stage
 constexpr int kStageMacros = kStageK / kMacro;
 constexpr int kRowStage = kStageK / 2;  // code bytes per row and stage
 constexpr int kGroupM = 8;              // tile-rows walked together for L2 reuse
-constexpr int kCodeBufs = 3, kScaleBufs = 2, kSigmaBufs = 2;
+constexpr int kCodeBufs = 3, kSigmaBufs = 2;
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(3))) const uint8_t* lds_byte_ptr_t;
 
 template <typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -71,7 +72,6 @@ struct Shape {
     static constexpr int TM = NWM * FM * 16, TN = NWN * FN * 16;
     static constexpr int kRows = TM + TN;  // rows of A followed by rows of B
     static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "8-row code loads: operand fixed per load index");
-    static_assert((kRows / 8 / NW) % 2 == 0, "code loads are split over the two macro-block phases");
 };
 
 // LDS map and direct-to-LDS load counts of one kernel variant.  A direct-to-LDS load always writes one
@@ -79,9 +79,12 @@ struct Shape {
 // (kScaleDword / kM8Quad false) cost four LDS bytes per byte and only fit the smaller tile.
 //   kScaleDword: the four E8M0 bytes of a macro block are an aligned dword (K % 128 == 0, aligned array)
 //   kM8Quad:     the MBS words of two stages are an aligned dword (K % 512 == 0, aligned arrays)
-template <typename S, bool kScaleDword, bool kM8Quad>
+template <typename S, bool kMbs, bool kScaleDword, bool kM8Quad>
 struct Layout {
     static constexpr int NW = S::NW, kRows = S::kRows;
+    // E8M0 slots: with three, the scales of stage s + 2 can be requested as early as its codes; the MBS
+    // variants need the LDS for the sigma tables and request them one phase later into two slots
+    static constexpr int kScaleBufs = kMbs ? 2 : 3;
     // loads per wavefront and stage (every wavefront issues the same number)
     static constexpr int kCodeDma = kRows / 8 / NW;                                              // 8 rows x 128 B
     static constexpr int kScaleDma = ceil_div(kScaleDword ? kRows * 2 : kRows * 8, kWave * NW);  // 64 lanes each
@@ -89,9 +92,9 @@ struct Layout {
     static constexpr int kScaleStride = kScaleDword ? 1 : 4;  // LDS bytes per E8M0 byte
     static constexpr int kCodesStage = kRows * kRowStage;
     static constexpr int kScaleStage = kRows * 8 * kScaleStride;          // [row][8 E8M0 bytes of the stage]
-    static constexpr int kM8Stage = kM8Quad ? kRows * 4 : kRows * 2 * 4;  // quad: [row] dword = words of 2 stages
+    static constexpr int kM8Stage = !kMbs ? 0 : kM8Quad ? kRows * 4 : kRows * 2 * 4;  // quad: [row] dword = words of 2 stages
     static constexpr int kM8Bufs = kM8Quad ? 2 : 3;
-    static constexpr int kSigmaStage = kRows * 8;                         // f32 [macro][row]
+    static constexpr int kSigmaStage = kMbs ? kRows * 8 : 0;              // f32 [macro][row]
     static constexpr int kScaleBase = kCodeBufs * kCodesStage;
     static constexpr int kM8Base = kScaleBase + kScaleBufs * kScaleStage;
     static constexpr int kSigmaBase = kM8Base + kM8Bufs * kM8Stage;
@@ -144,6 +147,8 @@ __device__ __forceinline__ v4f mfma_fp4(v4i n_frag, v4i m_frag, v4f c, uint32_t 
 
 // s_waitcnt vmcnt(n) lgkmcnt(0): at most n direct-to-LDS loads outstanding, own LDS traffic done.
 constexpr int wait_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
+// s_waitcnt lgkmcnt(0) alone: own LDS traffic done, vector-memory operations left in flight.
+constexpr int kWaitLds = 0xC07F;
 
 // Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for ALL
 // outstanding vector-memory operations, which would drain the younger stages still in flight.
@@ -155,7 +160,8 @@ template <typename S, bool kMbs, bool kFast, bool kRaggedK>
 __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NT = S::NT, NW = S::NW, kRows = S::kRows;
     constexpr bool kScaleDword = kFast, kM8Quad = kFast;
-    using L = Layout<S, kScaleDword, kM8Quad>;
+    using L = Layout<S, kMbs, kScaleDword, kM8Quad>;
+    constexpr int kScaleBufs = L::kScaleBufs;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile --------------------------------------------------------------------------
@@ -242,30 +248,25 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         m8_off[i] = m8_pad[i] ? kOob : row * nmac + (kM8Quad ? 0 : p & 1);
     }
 
-    auto dma_codes = [&](int s, auto part) {  // half of the code loads of stage s
-        constexpr int h = kCodeDma / 2, first = decltype(part)::value * h;
-        uint8_t* base = smem + (s % kCodeBufs) * L::kCodesStage;
-#pragma unroll
-        for (int i = first; i < first + h; ++i) {
-            int voff = code_off[i];
-            if (kRaggedK && s * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
-                                                     (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
-                                                     s * kRowStage, 0, 0);
-        }
-    };
-    auto dma_scales = [&](int s) {
+    auto dma_scale = [&](int s, auto i_) {  // load i of the E8M0 bytes of stage s
+        constexpr int i = decltype(i_)::value;
         uint8_t* base = smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage;
-#pragma unroll
-        for (int i = 0; i < kScaleDma; ++i) {
-            int voff = scale_off[i];
-            // past the end of K the block does not exist: read zero (2^-127), never a stray NaN scale
-            if (kRaggedK && (kScaleDword ? (s * kStageMacros + scale_sub[i]) * kMacro : (s * 8 + scale_sub[i]) * kBlock) >= K)
-                voff = kOob;
-            uint8_t* dst = scale_pad[i] ? smem + L::kDummy : base + (i * NW + w) * 256;  // one dword per lane
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(scale_is_a[i] ? opa.scales : opb.scales, (lds_ptr_t)dst,
-                                                     kScaleDword ? 4 : 1, voff, s * 8, 0, 0);
-        }
+        int voff = scale_off[i];
+        // past the end of K the block does not exist: read zero (2^-127), never a stray NaN scale
+        if (kRaggedK && (kScaleDword ? (s * kStageMacros + scale_sub[i]) * kMacro : (s * 8 + scale_sub[i]) * kBlock) >= K)
+            voff = kOob;
+        uint8_t* dst = scale_pad[i] ? smem + L::kDummy : base + (i * NW + w) * 256;  // one dword per lane
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(scale_is_a[i] ? opa.scales : opb.scales, (lds_ptr_t)dst,
+                                                 kScaleDword ? 4 : 1, voff, s * 8, 0, 0);
+    };
+    auto dma_scales = [&](int s) { static_for<kScaleDma>([&](auto i_) { dma_scale(s, i_); }); };
+    auto dma_code = [&](int s, auto i_) {  // load i of the codes of stage s
+        constexpr int i = decltype(i_)::value;
+        uint8_t* base = smem + (s % kCodeBufs) * L::kCodesStage;
+        int voff = code_off[i];
+        if (kRaggedK && s * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
+                                                 (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff, s * kRowStage, 0, 0);
     };
     // Quad mode: the words of stages 2t and 2t + 1 as one dword per row into slot t % 2; issued every
     // iteration so that each wavefront's load count stays fixed, odd calls go to the padding area.
@@ -293,13 +294,16 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         const int g0 = s * kStageMacros;
 #pragma unroll
         for (int i = 0; i < ceil_div(kRows * 2, NT); ++i) {
-            const int p = i * NT + tid;  // pair (row p / 2 of the A-then-B row space, macro block p % 2)
-            if (kRows * 2 % NT == 0 || p < kRows * 2) {
-                uint32_t m8 = kM8Quad ? (raw[p >> 1] >> (8 * ((s & 1) * 2 + (p & 1)))) & 0xFFu : raw[p] & 0xFFu;
-                // a macro block past the end of K has no word (the row's next bytes belong to other blocks)
-                if (g0 + (p & 1) >= nmac) m8 = 0;
-                sig[(p & 1) * kRows + (p >> 1)] = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
-            }
+            // pair (row p / 2 of the A-then-B row space, macro block p % 2); threads past the last pair redo
+            // pair 0 and store to the padding area, which keeps the loop body free of branches
+            const int q = i * NT + tid;
+            const bool live = kRows * 2 % NT == 0 || q < kRows * 2;
+            const int p = live ? q : 0;
+            uint32_t m8 = kM8Quad ? (raw[p >> 1] >> (8 * ((s & 1) * 2 + (p & 1)))) & 0xFFu : raw[p] & 0xFFu;
+            // a macro block past the end of K has no word (the row's next bytes belong to other blocks)
+            if (g0 + (p & 1) >= nmac) m8 = 0;
+            float* dst = live ? sig + (p & 1) * kRows + (p >> 1) : reinterpret_cast<float*>(smem + L::kDummy);
+            *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
         }
     };
 
@@ -322,7 +326,9 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         constexpr int mb = decltype(mb_)::value;
         const uint8_t* cm = smem + (s % kCodeBufs) * L::kCodesStage;
         const uint8_t* cn = cm + TM * kRowStage;
-        const uint8_t* sc = smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage + lane_scale + mb * 4 * L::kScaleStride;
+        // (typed as an LDS pointer: the byte load then zero-extends by itself)
+        const lds_byte_ptr_t sc = (lds_byte_ptr_t)(smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage + lane_scale +
+                                                   mb * 4 * L::kScaleStride);
         const float* sig = reinterpret_cast<const float*>(smem + L::kSigmaBase + (s % kSigmaBufs) * L::kSigmaStage) + mb * kRows;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
@@ -344,40 +350,63 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // FM x FN matrix instructions on one macro block; `between(t)` runs after instruction t and is
-    // where the loads of later stages are slipped in.
+    constexpr int kMfmas = FM * FN;
+    Frags f0, f1;
+
+    // Plain path: FM x FN matrix instructions on one macro block, accumulating in place; `between(t)` runs
+    // after instruction t and is where the loads of later stages are slipped in.
     auto multiply = [&](const Frags& f, auto&& between) {
-        static_for<FM>([&](auto mi) {
-            static_for<FN>([&](auto ni) {
-                constexpr int i = decltype(mi)::value, j = decltype(ni)::value;
-                if constexpr (kMbs) {
-                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
-                    const v4f p = mfma_fp4(f.n[j], f.m[i], zero, f.scl_n[j], f.scl_m[i]);
-                    const float sa_ = f.sig_m[i];
-                    acc[i][j].x = fmaf(p.x, sa_ * f.sig_n[j].x, acc[i][j].x);
-                    acc[i][j].y = fmaf(p.y, sa_ * f.sig_n[j].y, acc[i][j].y);
-                    acc[i][j].z = fmaf(p.z, sa_ * f.sig_n[j].z, acc[i][j].z);
-                    acc[i][j].w = fmaf(p.w, sa_ * f.sig_n[j].w, acc[i][j].w);
-                } else {
-                    acc[i][j] = mfma_fp4(f.n[j], f.m[i], acc[i][j], f.scl_n[j], f.scl_m[i]);
-                }
-                between(std::integral_constant<int, i * FN + j>{});
-            });
+        static_for<kMfmas>([&](auto t_) {
+            constexpr int i = decltype(t_)::value / FN, j = decltype(t_)::value % FN;
+            acc[i][j] = mfma_fp4(f.n[j], f.m[i], acc[i][j], f.scl_n[j], f.scl_m[i]);
+            between(t_);
+        });
+    };
+
+    // MBS path (Sec. 4.3, Fig. 6): each matrix instruction yields the partial sums of one macro block, which
+    // the vector ALU folds into the accumulators as acc += p * (sigma_m * sigma_n).  A product is consumed
+    // kDepth instructions after it was issued, so the vector work never waits on the matrix pipeline.  Unit u
+    // of an iteration is instruction u % kMfmas of macro block u / kMfmas (f0, then f1); units past
+    // 2 * kMfmas belong to the next iteration's f0.
+    constexpr int kDepth = 2;
+    static_assert((2 * kMfmas) % kDepth == 0, "ring slots must line up across iterations");
+    v4f prod[kDepth];
+    auto issue = [&](auto u_) {
+        constexpr int u = decltype(u_)::value, t = u % kMfmas, i = t / FN, j = t % FN;
+        const Frags& f = ((u / kMfmas) & 1) ? f1 : f0;
+        const v4f zero = {0.f, 0.f, 0.f, 0.f};
+        prod[u % kDepth] = mfma_fp4(f.n[j], f.m[i], zero, f.scl_n[j], f.scl_m[i]);
+    };
+    auto retire = [&](auto u_) {
+        constexpr int u = decltype(u_)::value, t = u % kMfmas, i = t / FN, j = t % FN;
+        const Frags& f = ((u / kMfmas) & 1) ? f1 : f0;
+        const v4f p = prod[u % kDepth];
+        const float sm = f.sig_m[i];
+        acc[i][j].x = fmaf(p.x, sm * f.sig_n[j].x, acc[i][j].x);
+        acc[i][j].y = fmaf(p.y, sm * f.sig_n[j].y, acc[i][j].y);
+        acc[i][j].z = fmaf(p.z, sm * f.sig_n[j].z, acc[i][j].z);
+        acc[i][j].w = fmaf(p.w, sm * f.sig_n[j].w, acc[i][j].w);
+    };
+    // one macro block of the MBS path: units base .. base + kMfmas - 1 retire, the units kDepth ahead issue
+    auto multiply_mbs = [&](auto base_, auto&& between) {
+        constexpr int base = decltype(base_)::value;
+        static_for<kMfmas>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            retire(std::integral_constant<int, base + t>{});
+            issue(std::integral_constant<int, base + t + kDepth>{});
+            __builtin_amdgcn_sched_barrier(0);
+            between(t_);
         });
     };
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
-    constexpr int kMfmas = FM * FN;
 
     // ---- prologue: stages 0 and 1 (and the MBS words of stage 2) -------------------------------------
     const int nstages = (K + kStageK - 1) / kStageK;
-    Frags f0, f1;
     if (nstages > 0) {
-        dma_codes(0, C0{});
-        dma_codes(0, C1{});
+        static_for<kCodeDma>([&](auto i_) { dma_code(0, i_); });
         dma_scales(0);
-        dma_codes(1, C0{});
-        dma_codes(1, C1{});
+        static_for<kCodeDma>([&](auto i_) { dma_code(1, i_); });
         dma_scales(1);
         if constexpr (kMbs) {
             dma_m8(0);
@@ -393,63 +422,70 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
             bare_barrier();
         }
         read_frags(f0, 0, C0{});
+        if constexpr (kMbs) static_for<kDepth>([&](auto u_) { issue(u_); });
     }
 
-    // Loads younger than stage s + 1 at the barrier inside iteration s: the first half of the codes of
-    // stage s + 2 and the MBS words of stage s + 3.
-    constexpr int kYounger = kCodeDma / 2 + (kMbs ? kM8Dma : 0);
-    static_assert(kYounger < 64, "vmcnt is a 6-bit counter");
-    constexpr int kStepA = kMfmas / (kCodeDma / 2 + (kMbs ? 1 : 0) + 1);  // spacing of the slipped-in loads
-    constexpr int kStepB = kMfmas / (kCodeDma / 2 + 1 + 1);
+    // Loads of later stages slipped in between the matrix instructions, split evenly over the two phases so
+    // that the texture-address path sees a steady stream.  The codes of stage s + 2 go into the buffer stage
+    // s - 1 was read from (those reads completed before the barrier of the previous iteration), part in
+    // phase A and the rest in phase B.  Phase A also takes the MBS words of stage s + 3 (slot of stage s,
+    // converted two iterations ago).  Phase B, after the barrier, takes the scales of stage s + 2: with two
+    // scale slots (MBS) that is the slot of stage s, whose bytes were all read before the barrier.
+    constexpr int kM8Loads = kMbs ? kM8Dma : 0;
+    constexpr int kCodesA = (kCodeDma + kScaleDma - kM8Loads + 1) / 2 < 0 ? 0
+                            : (kCodeDma + kScaleDma - kM8Loads + 1) / 2 > kCodeDma ? kCodeDma
+                            : (kCodeDma + kScaleDma - kM8Loads + 1) / 2;
+    constexpr int kSlotsA = kCodesA + (kMbs ? 1 : 0);               // calls slipped into phase A
+    constexpr int kSlotsB = kCodeDma - kCodesA + kScaleDma;          // calls slipped into phase B
+    constexpr int kLoadsA = kCodesA + kM8Loads;                      // load instructions of phase A
+    static_assert(kLoadsA < 64, "vmcnt is a 6-bit counter");
+    auto load_a = [&](int s, auto n_) {
+        constexpr int n = decltype(n_)::value;
+        if constexpr (n < kCodesA) dma_code(s + 2, n_);
+        else dma_m8(s + 3);
+    };
+    auto load_b = [&](int s, auto n_) {
+        constexpr int n = decltype(n_)::value;
+        if constexpr (n < kCodeDma - kCodesA) dma_code(s + 2, std::integral_constant<int, kCodesA + n>{});
+        else dma_scale(s + 2, std::integral_constant<int, n - (kCodeDma - kCodesA)>{});
+    };
+    // after matrix instruction t of a phase, issue the loads whose evenly spread position is t
+    auto slip = [&](auto t_, auto count_, auto&& issue) {
+        constexpr int t = decltype(t_)::value, count = decltype(count_)::value;
+        static_for<count>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+            if constexpr ((n * kMfmas) / count == t) {
+                issue(n_);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    };
 
     for (int s = 0; s < nstages; ++s) {
         // Past the end of K the loads below are out of range or land in rows nobody reads; issuing them
         // unconditionally keeps the loop body one basic block.
+        // f0 was requested a whole phase ago: waiting for it first keeps the matrix instructions below from
+        // queueing behind the reads of f1, which all wavefronts issue at once
+        __builtin_amdgcn_s_waitcnt(kWaitLds);
         read_frags(f1, s, C1{});
         __builtin_amdgcn_sched_barrier(0);
-        multiply(f0, [&](auto t_) {
-            constexpr int t = decltype(t_)::value;
-            // first half of the codes of stage s + 2, into the buffer stage s - 1 was read from (those reads
-            // completed before the barrier of the previous iteration)
-            constexpr int h = kCodeDma / 2;
-            if constexpr ((t + 1) % kStepA == 0 && (t + 1) / kStepA <= h) {
-                constexpr int i = (t + 1) / kStepA - 1;
-                uint8_t* base = smem + ((s + 2) % kCodeBufs) * L::kCodesStage;
-                int voff = code_off[i];
-                if (kRaggedK && (s + 2) * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
-                                                         (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
-                                                         (s + 2) * kRowStage, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            } else if constexpr (kMbs && (t + 1) == kStepA * (h + 1)) {
-                dma_m8(s + 3);  // slot of stage s, whose words were converted two iterations ago
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
+        auto loads_a = [&](auto t_) {
+            slip(t_, std::integral_constant<int, kSlotsA>{}, [&](auto n_) { load_a(s, n_); });
+        };
+        if constexpr (kMbs) multiply_mbs(std::integral_constant<int, 0>{}, loads_a);
+        else multiply(f0, loads_a);
         __builtin_amdgcn_sched_barrier(0);
         // publish stage s + 1: everything issued before this iteration has landed
-        __builtin_amdgcn_s_waitcnt(wait_imm(kYounger));
+        __builtin_amdgcn_s_waitcnt(wait_imm(kLoadsA));
         bare_barrier();
         if constexpr (kMbs) convert_sigma(s + 2);  // into the slot of stage s, all of whose reads are done
         read_frags(f0, s + 1, C0{});
         __builtin_amdgcn_sched_barrier(0);
-        multiply(f1, [&](auto t_) {
-            constexpr int t = decltype(t_)::value;
-            constexpr int h = kCodeDma / 2;
-            if constexpr ((t + 1) % kStepB == 0 && (t + 1) / kStepB <= h) {
-                constexpr int i = h + (t + 1) / kStepB - 1;
-                uint8_t* base = smem + ((s + 2) % kCodeBufs) * L::kCodesStage;
-                int voff = code_off[i];
-                if (kRaggedK && (s + 2) * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
-                                                         (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff,
-                                                         (s + 2) * kRowStage, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            } else if constexpr ((t + 1) == kStepB * (h + 1)) {
-                dma_scales(s + 2);  // slot of stage s: its bytes were all read before the barrier above
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
+        auto loads_b = [&](auto t_) {
+            slip(t_, std::integral_constant<int, kSlotsB>{}, [&](auto n_) { load_b(s, n_); });
+        };
+        if constexpr (kMbs) multiply_mbs(std::integral_constant<int, kMfmas>{}, loads_b);
+        else multiply(f1, loads_b);
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -492,7 +528,7 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
 
 template <typename S, bool kMbs, bool kFast, bool kRaggedK>
 int launch_variant(GemmArgs g, bool grouped, hipStream_t s) {
-    using L = Layout<S, kFast, kFast>;
+    using L = Layout<S, kMbs, kFast, kFast>;
     const int64_t tiles_m = (g.M + S::TM - 1) / S::TM + (grouped ? g.num_groups : 0);
     const int64_t tiles_n = (g.N + S::TN - 1) / S::TN;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
