@@ -3,8 +3,11 @@ from __future__ import annotations
 
 import glob
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -13,35 +16,57 @@ LIB = os.path.join(HERE, "libmx4.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # MFMA results go to ordinary VGPRs, where the vector ALUs can consume them without copies
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+# MFMA results in ordinary VGPRs, where the vector ALUs consume them without copies (MBS correction)
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+# Per-source extra flags.  The large-tile plain GEMM keeps its accumulators in the accumulation registers
+# and is therefore compiled without the VGPR form.
+EXTRA = {"mx_gemm_wide.hip": []}
 
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + sources() + ["-o", tmp]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature; that is harmless
     out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + out)
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB)
+
+
+def build(verbose: bool = False) -> str:
+    work = tempfile.mkdtemp(prefix="mx4_build_")
+    try:
+        objs = []
+        jobs = []
+        for src in sources():
+            name = os.path.basename(src)
+            obj = os.path.join(work, name + ".o")
+            objs.append(obj)
+            jobs.append([HIPCC] + FLAGS + EXTRA.get(name, VGPR_FORM) + ["-c", src, "-o", obj])
+        with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        tmp = os.path.join(work, "libmx4.so")
+        _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp], verbose)
+        # a kernel the host pass failed to emit shows up only as an unresolved symbol of our own namespace
+        undefined = subprocess.run(["nm", "-u", tmp], stdout=subprocess.PIPE, text=True).stdout
+        missing = [l.split()[-1] for l in undefined.splitlines() if "_ZN2mx" in l]
+        if missing:
+            raise RuntimeError("libmx4.so has unresolved symbols: " + ", ".join(missing))
+        os.replace(tmp, LIB) if os.path.dirname(tmp) == HERE else shutil.move(tmp, LIB)
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
     return LIB
 
 

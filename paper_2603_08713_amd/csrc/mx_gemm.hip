@@ -34,9 +34,7 @@
 // The loop is software-pipelined by one macro block: while the matrix cores work on one macro block
 // the LDS reads of the next one are in flight; the barrier that publishes stage s + 1 sits between the
 // two macro blocks of stage s.
-#include <utility>
-
-#include "mx_common.h"
+#include "mx_gemm_shared.h"
 
 namespace mx {
 namespace {
@@ -47,29 +45,13 @@ constexpr int kRowStage = kStageK / 2;  // code bytes per row and stage
 constexpr int kGroupM = 8;              // tile-rows walked together for L2 reuse
 constexpr int kCodeBufs = 3, kSigmaBufs = 2;
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef __attribute__((address_space(3))) const uint8_t* lds_byte_ptr_t;
-
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
-
-// Tile shape: NWM x NWN wavefronts, each FM x FN fragments of 16 x 16 outputs.
-template <int NWM_, int NWN_, int FM_, int FN_>
+// Tile shape: NWM x NWN wavefronts, each FM x FN fragments of kFrag x kFrag outputs (16: one 16x16x128
+// instruction per fragment pair and macro block; 32: two chained 32x32x64 instructions).
+template <int NWM_, int NWN_, int FM_, int FN_, int kFrag_>
 struct Shape {
-    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_;
+    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kFrag = kFrag_;
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
-    static constexpr int TM = NWM * FM * 16, TN = NWN * FN * 16;
+    static constexpr int TM = NWM * FM * kFrag, TN = NWN * FN * kFrag;
     static constexpr int kRows = TM + TN;  // rows of A followed by rows of B
     static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "8-row code loads: operand fixed per load index");
 };
@@ -103,62 +85,14 @@ struct Layout {
     static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
 };
 
-struct GemmArgs {
-    const uint8_t *a_codes, *a_scales, *a_mbs;
-    const uint8_t *b_codes, *b_scales, *b_mbs;
-    void* C;
-    const int64_t* row_offsets;  // grouped mode only
-    int64_t M, N, K, ldc;
-    int num_groups;              // 0 = plain GEMM
-    int tiles_m, tiles_n;        // tile grid (tiles_m is an upper bound in grouped mode)
-    int c_bf16;
-    int vec_store;               // C rows allow 4-element vector stores
-};
-
-// One operand (A or B) of the tile as the loader sees it: buffer resources rebased to the tile's first
-// row and sized to its valid rows, so that rows past the end read as zero without any branch.
-struct Operand {
-    __amdgpu_buffer_rsrc_t codes, scales, mbs;
-};
-
-__device__ __forceinline__ Operand make_operand(const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs,
-                                                int64_t row0, int64_t row_end, int tile_rows, int64_t K) {
-    Operand op;
-    const int64_t rows = row_end > row0 ? (row_end - row0 < tile_rows ? row_end - row0 : tile_rows) : 0;
-    const int64_t row_bytes = K >> 1, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro;
-    const int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
-    op.codes = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(codes) + row0 * row_bytes, 0,
-                                                 (int)(rows * row_bytes), kRsrcFlags);
-    op.scales = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(scales) + row0 * scale_bytes, 0,
-                                                  (int)(rows * scale_bytes), kRsrcFlags);
-    op.mbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(mbs ? mbs + row0 * nmac : codes), 0,
-                                               mbs ? (int)(rows * nmac) : 0, kRsrcFlags);
-    return op;
-}
-
-constexpr int kOob = 0x7FFFFFF0;  // byte offset beyond any buffer: the load returns zero
-
-__device__ __forceinline__ v4f mfma_fp4(v4i n_frag, v4i m_frag, v4f c, uint32_t scale_n, uint32_t scale_m) {
-    const v8i a = __builtin_shufflevector(n_frag, n_frag, 0, 1, 2, 3, -1, -1, -1, -1);
-    const v8i b = __builtin_shufflevector(m_frag, m_frag, 0, 1, 2, 3, -1, -1, -1, -1);
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4 /*A: FP4*/, 4 /*B: FP4*/, 0, (int)scale_n,
-                                                            0, (int)scale_m);
-}
-
-// s_waitcnt vmcnt(n) lgkmcnt(0): at most n direct-to-LDS loads outstanding, own LDS traffic done.
-constexpr int wait_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
-// s_waitcnt lgkmcnt(0) alone: own LDS traffic done, vector-memory operations left in flight.
-constexpr int kWaitLds = 0xC07F;
-
-// Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for ALL
-// outstanding vector-memory operations, which would drain the younger stages still in flight.
-__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
 // kMbs: apply the per-macro-block correction; kFast: aligned dword loads of scales and MBS words (see
 // Layout), otherwise byte loads; kRaggedK: K is not a multiple of the stage.
 template <typename S, bool kMbs, bool kFast, bool kRaggedK>
 __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NT = S::NT, NW = S::NW, kRows = S::kRows;
+    constexpr int kFrag = S::kFrag;
+    constexpr int kSub = kFrag == 32 ? 2 : 1;  // matrix instructions per fragment pair and macro block
+    static_assert(kFrag == 16 || (kFrag == 32 && !kMbs), "the MBS path is written for 16 x 16 fragments");
     constexpr bool kScaleDword = kFast, kM8Quad = kFast;
     using L = Layout<S, kMbs, kScaleDword, kM8Quad>;
     constexpr int kScaleBufs = L::kScaleBufs;
@@ -308,19 +242,27 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     };
 
     // ---- operands of one macro block in registers ---------------------------------------------------
+    // Lane coordinates inside a fragment: row lr; k-block lq of the instruction's blocks (4 of 32 elements
+    // for the 16-row form, 2 for the 32-row form).  The two instructions of a 32-row fragment pair split the
+    // macro block so that lane half lq takes blocks 2 lq (first instruction) and 2 lq + 1 (second): its two
+    // E8M0 bytes are then neighbours and come with one 16-bit LDS read, selected per instruction by op_sel.
+    const int lr = l & (kFrag - 1), lq = l / kFrag;
+    constexpr int kSclRegs = (kFrag == 32 && !kScaleDword) ? 2 : 1;
     struct Frags {
-        v4i m[FM], n[FN];
-        uint32_t scl_m[FM], scl_n[FN];
+        v4i m[FM][kSub], n[FN][kSub];
+        uint32_t scl_m[FM][kSclRegs], scl_n[FN][kSclRegs];
         float sig_m[FM];
         v4f sig_n[FN];
     };
-    // byte offset of this lane's 16 bytes inside a 16-row block of the swizzled code image, per macro block
-    int frag_off[kStageMacros];
+    // byte offset of this lane's 16 bytes inside a fragment's rows of the swizzled code image
+    int frag_off[kStageMacros][kSub];
 #pragma unroll
     for (int mb = 0; mb < kStageMacros; ++mb)
-        frag_off[mb] = (l & 15) * kRowStage + (((mb * 4 + (l >> 4)) ^ ((l & 15) >> 1)) * 16);
-    // this lane's E8M0 byte inside a 16-row block of the [row][8] scale image (+ 4 * macro block)
-    const int lane_scale = ((l & 15) * 8 + (l >> 4)) * L::kScaleStride;
+#pragma unroll
+        for (int kk = 0; kk < kSub; ++kk)
+            frag_off[mb][kk] = lr * kRowStage + (((mb * 4 + lq * kSub + kk) ^ ((lr >> 1) & 7)) * 16);
+    // this lane's first E8M0 byte inside a fragment's rows of the [row][8] scale image (+ 4 * macro block)
+    const int lane_scale = (lr * 8 + lq * kSub) * L::kScaleStride;
 
     auto read_frags = [&](Frags& f, int s, auto mb_) {
         constexpr int mb = decltype(mb_)::value;
@@ -330,35 +272,57 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         const lds_byte_ptr_t sc = (lds_byte_ptr_t)(smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage + lane_scale +
                                                    mb * 4 * L::kScaleStride);
         const float* sig = reinterpret_cast<const float*>(smem + L::kSigmaBase + (s % kSigmaBufs) * L::kSigmaStage) + mb * kRows;
+        auto read_scales = [&](uint32_t (&dst)[kSclRegs], int row0) {
+            const lds_byte_ptr_t q = sc + row0 * 8 * L::kScaleStride;
+            if constexpr (kFrag == 32 && kScaleDword) dst[0] = *(lds_half_ptr_t)q;
+            else
+#pragma unroll
+                for (int kk = 0; kk < kSclRegs; ++kk) dst[kk] = q[kk * L::kScaleStride];
+        };
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
-            f.m[i] = *reinterpret_cast<const v4i*>(cm + (wm * FM + i) * (16 * kRowStage) + frag_off[mb]);
-            f.scl_m[i] = sc[(wm * FM + i) * 128 * L::kScaleStride];
-            if constexpr (kMbs) f.sig_m[i] = sig[(wm * FM + i) * 16 + (l & 15)];
+#pragma unroll
+            for (int kk = 0; kk < kSub; ++kk)
+                f.m[i][kk] = *reinterpret_cast<const v4i*>(cm + (wm * FM + i) * (kFrag * kRowStage) + frag_off[mb][kk]);
+            read_scales(f.scl_m[i], (wm * FM + i) * kFrag);
+            if constexpr (kMbs) f.sig_m[i] = sig[(wm * FM + i) * 16 + lr];
         }
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-            f.n[j] = *reinterpret_cast<const v4i*>(cn + (wn * FN + j) * (16 * kRowStage) + frag_off[mb]);
-            f.scl_n[j] = sc[(TM / 16 + wn * FN + j) * 128 * L::kScaleStride];
-            if constexpr (kMbs) f.sig_n[j] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 16 + (l >> 4) * 4);
+#pragma unroll
+            for (int kk = 0; kk < kSub; ++kk)
+                f.n[j][kk] = *reinterpret_cast<const v4i*>(cn + (wn * FN + j) * (kFrag * kRowStage) + frag_off[mb][kk]);
+            read_scales(f.scl_n[j], TM + (wn * FN + j) * kFrag);
+            if constexpr (kMbs) f.sig_n[j] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 16 + lq * 4);
         }
     };
 
-    v4f acc[FM][FN];
+    using acc_t = std::conditional_t<kFrag == 32, v16f, v4f>;
+    acc_t acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < kFrag * kFrag / kWave; ++e) acc[i][j][e] = 0.f;
 
-    constexpr int kMfmas = FM * FN;
+    constexpr int kMfmas = FM * FN * kSub;  // matrix instructions per macro block
     Frags f0, f1;
 
     // Plain path: FM x FN matrix instructions on one macro block, accumulating in place; `between(t)` runs
     // after instruction t and is where the loads of later stages are slipped in.
+    // The two instructions of a 32-row fragment pair are FM * FN instructions apart, so none waits for its
+    // predecessor's result.
     auto multiply = [&](const Frags& f, auto&& between) {
         static_for<kMfmas>([&](auto t_) {
-            constexpr int i = decltype(t_)::value / FN, j = decltype(t_)::value % FN;
-            acc[i][j] = mfma_fp4(f.n[j], f.m[i], acc[i][j], f.scl_n[j], f.scl_m[i]);
+            constexpr int kk = decltype(t_)::value / (FM * FN), i = decltype(t_)::value % (FM * FN) / FN,
+                          j = decltype(t_)::value % FN;
+            if constexpr (kFrag == 32) {
+                constexpr int sel = kSclRegs == 1 ? kk : 0, reg = kSclRegs == 1 ? 0 : kk;
+                acc[i][j] = mfma_fp4_wide<sel, sel>(f.n[j][kk], f.m[i][kk], acc[i][j], f.scl_n[j][reg], f.scl_m[i][reg]);
+            } else {
+                acc[i][j] = mfma_fp4(f.n[j][0], f.m[i][0], acc[i][j], f.scl_n[j][0], f.scl_m[i][0]);
+            }
             between(t_);
         });
     };
@@ -375,7 +339,7 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         constexpr int u = decltype(u_)::value, t = u % kMfmas, i = t / FN, j = t % FN;
         const Frags& f = ((u / kMfmas) & 1) ? f1 : f0;
         const v4f zero = {0.f, 0.f, 0.f, 0.f};
-        prod[u % kDepth] = mfma_fp4(f.n[j], f.m[i], zero, f.scl_n[j], f.scl_m[i]);
+        prod[u % kDepth] = mfma_fp4(f.n[j][0], f.m[i][0], zero, f.scl_n[j][0], f.scl_m[i][0]);
     };
     auto retire = [&](auto u_) {
         constexpr int u = decltype(u_)::value, t = u % kMfmas, i = t / FN, j = t % FN;
@@ -489,38 +453,22 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- epilogue: lane holds C[m][n .. n+3] for each of its fragments ------------------------------
-    const int64_t n_base = (int64_t)tn * TN + wn * FN * 16 + (l >> 4) * 4;
+    // ---- epilogue: a lane holds, per fragment, row m = lr and groups of four consecutive n --------------
+    // (16-row form: the group starting at 4 lq; 32-row form: the groups starting at 8 g + 4 lq, g = 0..3)
+    constexpr int kGroups = kFrag == 32 ? 4 : 1;
+    const int64_t n_base = (int64_t)tn * TN + wn * FN * kFrag + lq * 4;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-        const int64_t m = a_row0 + (wm * FM + i) * 16 + (l & 15);
+        const int64_t m = a_row0 + (wm * FM + i) * kFrag + lr;
         if (m >= a_end) continue;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-            const int64_t n = n_base + j * 16;
-            if (n >= g.N) continue;
-            const v4f v = acc[i][j];
-            if (g.c_bf16) {
-                uint16_t* o = static_cast<uint16_t*>(g.C) + m * g.ldc + n;
-                const uint32_t lo = pack_bf16(v.x, v.y), hi = pack_bf16(v.z, v.w);  // round to nearest even
-                if (g.vec_store && n + 3 < g.N) {
-                    *reinterpret_cast<uint2*>(o) = make_uint2(lo, hi);
-                } else {
-                    o[0] = (uint16_t)lo;
-                    if (n + 1 < g.N) o[1] = (uint16_t)(lo >> 16);
-                    if (n + 2 < g.N) o[2] = (uint16_t)hi;
-                    if (n + 3 < g.N) o[3] = (uint16_t)(hi >> 16);
-                }
-            } else {
-                float* o = static_cast<float*>(g.C) + m * g.ldc + n;
-                if (g.vec_store && n + 3 < g.N) {
-                    *reinterpret_cast<v4f*>(o) = v;
-                } else {
-                    o[0] = v.x;
-                    if (n + 1 < g.N) o[1] = v.y;
-                    if (n + 2 < g.N) o[2] = v.z;
-                    if (n + 3 < g.N) o[3] = v.w;
-                }
+#pragma unroll
+            for (int gq = 0; gq < kGroups; ++gq) {
+                const int64_t n = n_base + j * kFrag + gq * 8;
+                if (n >= g.N) continue;
+                const v4f v = {acc[i][j][gq * 4], acc[i][j][gq * 4 + 1], acc[i][j][gq * 4 + 2], acc[i][j][gq * 4 + 3]};
+                store_c4(g, m, n, v);
             }
         }
     }
@@ -549,19 +497,24 @@ int launch_variant(GemmArgs g, bool grouped, hipStream_t s) {
     return launch_status();
 }
 
-template <typename S, bool kFast>
+// SMbs / SPlain: the same tile with 16-row fragments (MBS path) and 32-row fragments (plain path)
+template <typename SMbs, typename SPlain, bool kFast>
 int launch_shape(const GemmArgs& g, bool grouped, bool use_mbs, bool ragged, hipStream_t s) {
+    static_assert(SMbs::TM == SPlain::TM && SMbs::TN == SPlain::TN && SMbs::NT == SPlain::NT, "one tile, two fragment sizes");
     if (use_mbs)
-        return ragged ? launch_variant<S, true, kFast, true>(g, grouped, s)
-                      : launch_variant<S, true, kFast, false>(g, grouped, s);
-    return ragged ? launch_variant<S, false, kFast, true>(g, grouped, s)
-                  : launch_variant<S, false, kFast, false>(g, grouped, s);
+        return ragged ? launch_variant<SMbs, true, kFast, true>(g, grouped, s)
+                      : launch_variant<SMbs, true, kFast, false>(g, grouped, s);
+    return ragged ? launch_variant<SPlain, false, kFast, true>(g, grouped, s)
+                  : launch_variant<SPlain, false, kFast, false>(g, grouped, s);
 }
 
-using Shape128 = Shape<2, 4, 4, 2>;      // 8 waves, 128 x 128 tile, 64 x 32 per wave
-using Shape256x128 = Shape<4, 2, 4, 4>;  // 8 waves, 256 x 128 tile, 64 x 64 per wave
+// 8 wavefronts each; 128 x 128 tile with 64 x 32 per wavefront, 256 x 128 tile with 64 x 64 per wavefront
+using Shape128 = Shape<2, 4, 4, 2, 16>;
+using Shape128Wide = Shape<2, 4, 2, 1, 32>;
+using Shape256x128 = Shape<4, 2, 4, 4, 16>;
+using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128
+int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = 256x256 (plain only)
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -589,6 +542,7 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     g.tiles_m = g.tiles_n = 0;
     g.c_bf16 = c_dtype == MX_OUT_BF16;
     g.vec_store = aligned(C, 4 * esz) && (ldc % 4) == 0;
+    g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = mbs_entry && (a_mbs || b_mbs);
@@ -603,10 +557,18 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     const int64_t t256x128 = ((M + 255) / 256) * ((N + 127) / 128);
     if (t256x128 >= 512) shape = 1;
     if (grouped) shape = 0;
+    // plain GEMMs with enough 256 x 256 tiles for every compute unit take the large-tile kernel
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const bool wide_ok = !use_mbs && !grouped && K > 0 && (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16);
+    if (wide_ok && t256 >= 256) shape = 2;
     if (g_force_shape >= 0) shape = g_force_shape;
-    if (!fast) return launch_shape<Shape128, false>(g, grouped, use_mbs, ragged, s);
-    if (shape >= 1) return launch_shape<Shape256x128, true>(g, grouped, use_mbs, ragged, s);
-    return launch_shape<Shape128, true>(g, grouped, use_mbs, ragged, s);
+    if (shape == 2) {
+        if (!wide_ok) return MX_EINVAL;  // only reachable through the development switch
+        return launch_gemm_wide(g, s);
+    }
+    if (!fast) return launch_shape<Shape128, Shape128Wide, false>(g, grouped, use_mbs, ragged, s);
+    if (shape >= 1) return launch_shape<Shape256x128, Shape256x128Wide, true>(g, grouped, use_mbs, ragged, s);
+    return launch_shape<Shape128, Shape128Wide, true>(g, grouped, use_mbs, ragged, s);
 }
 
 }  // namespace

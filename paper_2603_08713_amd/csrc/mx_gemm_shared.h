@@ -1,0 +1,124 @@
+// Pieces shared by the MXFP4 GEMM kernels (private; the public ABI is include/mx4.h).
+#pragma once
+
+#include <type_traits>
+#include <utility>
+
+#include "mx_common.h"
+
+namespace mx {
+
+struct GemmArgs {
+    const uint8_t *a_codes, *a_scales, *a_mbs;
+    const uint8_t *b_codes, *b_scales, *b_mbs;
+    void* C;
+    const int64_t* row_offsets;  // grouped mode only
+    int64_t M, N, K, ldc;
+    int num_groups;              // 0 = plain GEMM
+    int tiles_m, tiles_n;        // tile grid (tiles_m is an upper bound in grouped mode)
+    int c_bf16;
+    int vec_store;               // C rows allow 4-element vector stores
+    int vec_store16;             // C rows allow 16-byte vector stores
+};
+
+// Large-tile kernel for the plain (no MBS, not grouped) GEMM, defined in mx_gemm_wide.hip.
+int launch_gemm_wide(const GemmArgs& g, hipStream_t s);
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(3))) const uint16_t* lds_half_ptr_t;
+typedef __attribute__((address_space(3))) const uint8_t* lds_byte_ptr_t;
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// One operand (A or B) of the tile as the loader sees it: buffer resources rebased to the tile's first
+// row and sized to its valid rows, so that rows past the end read as zero without any branch.
+struct Operand {
+    __amdgpu_buffer_rsrc_t codes, scales, mbs;
+};
+
+__device__ __forceinline__ Operand make_operand(const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs,
+                                                int64_t row0, int64_t row_end, int tile_rows, int64_t K) {
+    Operand op;
+    const int64_t rows = row_end > row0 ? (row_end - row0 < tile_rows ? row_end - row0 : tile_rows) : 0;
+    const int64_t row_bytes = K >> 1, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro;
+    const int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
+    op.codes = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(codes) + row0 * row_bytes, 0,
+                                                 (int)(rows * row_bytes), kRsrcFlags);
+    op.scales = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(scales) + row0 * scale_bytes, 0,
+                                                  (int)(rows * scale_bytes), kRsrcFlags);
+    op.mbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(mbs ? mbs + row0 * nmac : codes), 0,
+                                               mbs ? (int)(rows * nmac) : 0, kRsrcFlags);
+    return op;
+}
+
+constexpr int kOob = 0x7FFFFFF0;  // byte offset beyond any buffer: the load returns zero
+
+__device__ __forceinline__ v4f mfma_fp4(v4i n_frag, v4i m_frag, v4f c, uint32_t scale_n, uint32_t scale_m) {
+    const v8i a = __builtin_shufflevector(n_frag, n_frag, 0, 1, 2, 3, -1, -1, -1, -1);
+    const v8i b = __builtin_shufflevector(m_frag, m_frag, 0, 1, 2, 3, -1, -1, -1, -1);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4 /*A: FP4*/, 4 /*B: FP4*/, 0, (int)scale_n,
+                                                            0, (int)scale_m);
+}
+
+// 32x32x64 form: lane = 32 h + r holds row r, k-block h of the instruction's two blocks; the scale operand is
+// byte `sel` of the lane's scale register; D[8 (j / 4) + 4 h + j % 4][r] in result register j.
+template <int kSelN, int kSelM>
+__device__ __forceinline__ v16f mfma_fp4_wide(v4i n_frag, v4i m_frag, v16f c, uint32_t scale_n, uint32_t scale_m) {
+    const v8i a = __builtin_shufflevector(n_frag, n_frag, 0, 1, 2, 3, -1, -1, -1, -1);
+    const v8i b = __builtin_shufflevector(m_frag, m_frag, 0, 1, 2, 3, -1, -1, -1, -1);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 4 /*A: FP4*/, 4 /*B: FP4*/, kSelN, (int)scale_n,
+                                                            kSelM, (int)scale_m);
+}
+
+// s_waitcnt vmcnt(n) lgkmcnt(0): at most n direct-to-LDS loads outstanding, own LDS traffic done.
+constexpr int wait_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
+// s_waitcnt lgkmcnt(0) alone: own LDS traffic done, vector-memory operations left in flight.
+constexpr int kWaitLds = 0xC07F;
+
+// Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for ALL
+// outstanding vector-memory operations, which would drain the younger stages still in flight.
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Stores C[m][n .. n + 3] (bf16, round to nearest even, or fp32); elements at or past N are dropped.
+__device__ __forceinline__ void store_c4(const GemmArgs& g, int64_t m, int64_t n, v4f v) {
+    if (g.c_bf16) {
+        uint16_t* o = static_cast<uint16_t*>(g.C) + m * g.ldc + n;
+        const uint32_t lo = pack_bf16(v.x, v.y), hi = pack_bf16(v.z, v.w);
+        if (g.vec_store && n + 3 < g.N) {
+            *reinterpret_cast<uint2*>(o) = make_uint2(lo, hi);
+        } else {
+            o[0] = (uint16_t)lo;
+            if (n + 1 < g.N) o[1] = (uint16_t)(lo >> 16);
+            if (n + 2 < g.N) o[2] = (uint16_t)hi;
+            if (n + 3 < g.N) o[3] = (uint16_t)(hi >> 16);
+        }
+    } else {
+        float* o = static_cast<float*>(g.C) + m * g.ldc + n;
+        if (g.vec_store && n + 3 < g.N) {
+            *reinterpret_cast<v4f*>(o) = v;
+        } else {
+            o[0] = v.x;
+            if (n + 1 < g.N) o[1] = v.y;
+            if (n + 2 < g.N) o[2] = v.z;
+            if (n + 3 < g.N) o[3] = v.w;
+        }
+    }
+}
+
+}  // namespace
+}  // namespace mx

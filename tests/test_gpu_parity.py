@@ -305,6 +305,56 @@ def test_gemm_full_size_sampled_rows(mx, oracle):
     assert all(np.array_equal(x, y) for x, y in zip(ah, oa))
 
 
+def random_operand(rng, rows, K, lo=110, hi=140):
+    return (rng.integers(0, 256, (rows, K // 2), dtype=np.uint8), rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8),
+            rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
+
+
+@pytest.mark.parametrize("shape", [0, 1, 2])
+def test_gemm_every_tile_shape(mx, oracle, shape):
+    """Each tile shape forced in turn (0: 128 x 128, 1: 256 x 128, 2: the 256 x 256 kernel of the plain
+    path) on sizes with ragged tiles in M and N, several K stages and both output types."""
+    lib = mx.load_library()
+    rng = np.random.default_rng(50 + shape)
+    try:
+        lib.mx_internal_set_gemm_shape(shape)
+        for (M, N, K) in ((700, 530, 1536), (257, 300, 512)):
+            a, b = random_operand(rng, M, K), random_operand(rng, N, K)
+            want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None))
+            c32 = gpu_gemm(mx, a, b, "f32", plain=True)
+            assert_gemm_close(host(c32), want, "plain shape %d %dx%dx%d" % (shape, M, N, K))
+            assert torch.equal(gpu_gemm(mx, a, b, "bf16", plain=True), c32.to(torch.bfloat16))
+            # rows of C that start at odd element offsets: no vector stores, the frame around C stays untouched
+            da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+            for dt in (torch.float32, torch.bfloat16):
+                big = torch.full((M + 2, N + 3), -3.0, dtype=dt, device="cuda")
+                mx.mx_gemm(da[0], da[1], db[0], db[1], "f32" if dt == torch.float32 else "bf16", out=big[1:M + 1, 1:N + 1])
+                assert torch.equal(big[1:M + 1, 1:N + 1], c32.to(dt))
+                frame = big.clone()
+                frame[1:M + 1, 1:N + 1] = -3.0
+                assert bool((frame == -3.0).all())
+            if shape != 2:
+                assert_gemm_close(host(gpu_gemm(mx, a, b, "f32")), oracle.gemm(a, b), "mbs shape %d" % shape)
+    finally:
+        lib.mx_internal_set_gemm_shape(-1)
+
+
+def test_gemm_plain_full_size_sampled_rows(mx, oracle):
+    """The plain GEMM at the bench shape (it takes the 256 x 256 kernel there): sampled rows against the
+    oracle, bf16 output equal to the rounded fp32 output."""
+    rng = np.random.default_rng(51)
+    M, N, K = 4096, 14336, 4096
+    a, b = random_operand(rng, M, K, 120, 134), random_operand(rng, N, K, 120, 134)
+    da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+    c = mx.mx_gemm(da[0], da[1], db[0], db[1], "f32")
+    c16 = mx.mx_gemm(da[0], da[1], db[0], db[1], "bf16")
+    assert torch.equal(c16, c.to(torch.bfloat16))
+    rows = np.sort(rng.choice(M, 16, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None), rows=rows)
+    assert_gemm_close(host(c[torch.from_numpy(rows).cuda()]), want, "plain llama8b sampled rows")
+
+
 def test_grouped_gemm(mx, oracle):
     rng = np.random.default_rng(77)
     G, N, K = 5, 160, 2880
