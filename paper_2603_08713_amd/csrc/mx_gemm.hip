@@ -514,7 +514,7 @@ using Shape128Wide = Shape<2, 4, 2, 1, 32>;
 using Shape256x128 = Shape<4, 2, 4, 4, 16>;
 using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = 256x256 (plain only)
+int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 = main MBS kernel
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -557,14 +557,17 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     const int64_t t256x128 = ((M + 255) / 256) * ((N + 127) / 128);
     if (t256x128 >= 512) shape = 1;
     if (grouped) shape = 0;
-    // plain GEMMs with enough 256 x 256 tiles for every compute unit take the large-tile kernel
+    // The main kernels need K in whole groups of four macro blocks, aligned per-row arrays and enough tiles
+    // for every compute unit; everything else (grouped, ragged K, small problems) stays here.
+    const bool ring_ok = !grouped && K > 0 && (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16) &&
+                         (!use_mbs || ((!a_mbs || aligned(a_mbs, 4)) && (!b_mbs || aligned(b_mbs, 4))));
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    const bool wide_ok = !use_mbs && !grouped && K > 0 && (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16);
-    if (wide_ok && t256 >= 256) shape = 2;
+    if (ring_ok && !use_mbs && t256 >= 256) shape = 2;
+    if (ring_ok && use_mbs && t256x128 >= 256) shape = 3;
     if (g_force_shape >= 0) shape = g_force_shape;
-    if (shape == 2) {
-        if (!wide_ok) return MX_EINVAL;  // only reachable through the development switch
-        return launch_gemm_wide(g, s);
+    if (shape >= 2) {
+        if (!ring_ok || (shape == 2) == use_mbs) return MX_EINVAL;  // only reachable through the development switch
+        return shape == 2 ? launch_gemm_wide(g, s) : launch_gemm_mbs_ring(g, s);
     }
     if (!fast) return launch_shape<Shape128, Shape128Wide, false>(g, grouped, use_mbs, ragged, s);
     if (shape >= 1) return launch_shape<Shape256x128, Shape256x128Wide, true>(g, grouped, use_mbs, ragged, s);

@@ -1,0 +1,13 @@
+// MXFP4 GEMM with the MBS correction on 256 x 128 tiles: eight wavefronts, two per SIMD, 64 x 64 outputs
+// each.  The vector ALUs consume every matrix-instruction result (acc += P * sigma_A * sigma_B), so this
+// translation unit is compiled with the VGPR form of the matrix instructions, and two wavefronts per SIMD
+// let one fold products in while the other's matrix instructions run.
+#include "mx_gemm_ring.h"
+
+namespace mx {
+
+// Requires K % 512 == 0, K > 0, 16-byte aligned scale arrays and 4-byte aligned MBS arrays (a row's words of
+// four stages are fetched as one dword); the caller has checked all of them.  A null MBS array means sigma = 1.
+int launch_gemm_mbs_ring(const GemmArgs& g, hipStream_t s) { return launch_ring<RingShape<4, 2, 2, 2, true>>(g, s); }
+
+}  // namespace mx

@@ -1,0 +1,473 @@
+// Block-scaled MXFP4 GEMM  C = A * B^T  on v_mfma_scale_f32_32x32x64_f8f6f4: the main kernel template
+// (private; instantiated by mx_gemm_wide.hip without MBS and by mx_gemm_mbs.hip with MBS).
+//
+// What limits the instruction in practice is instruction issue and data movement, not the matrix pipeline:
+//   * every scaled matrix instruction keeps the vector-ALU issue port busy for about 12 clocks whatever its
+//     size, so the 32x32x64 form (32 clocks in the pipeline) leaves issue slots where the 16x16x128 form
+//     (16 clocks) leaves none;
+//   * a direct-to-LDS load holds up its wavefront while the texture-address unit, shared by the four
+//     SIMDs, works through its 64 lanes - 16 clocks for 16 bytes per lane, but 64 clocks for 4 bytes per
+//     lane - so everything is fetched in 16-byte pieces and the wavefronts issue at different slots.
+//
+// Tiling: NWM x NWN wavefronts, each FM x FN fragments of 32 x 32 outputs.  The weight matrix feeds srcA
+// and the activation matrix srcB, so a lane ends up with groups of four consecutive n of one output row m.
+// Operand mapping (lane = 32 h + r): srcA/srcB hold row r, k-block h of the instruction's two 32-element
+// blocks (16 bytes of FP4); the scale operand is one E8M0 byte per lane; D[8 (j / 4) + 4 h + j % 4][r] is
+// result register j.  The two instructions of a fragment pair split the macro block so that lane half h
+// takes blocks 2 h and 2 h + 1: its two E8M0 bytes are neighbours, one 16-bit LDS read fetches both and
+// op_sel picks the byte.
+//
+// Pipeline: K advances one macro block (128 elements: 64 code bytes, 4 E8M0 bytes, one MBS word per row)
+// per stage through a ring of four LDS code slots.  While stage s is multiplied out of registers, stage
+// s + 1 is read from LDS into the other register set and the loads of stage s + 4 are issued into the
+// slot stage s has just left: three stages are in flight, enough to cover a miss in the L2.  One
+// workgroup barrier per stage publishes stage s + 1 and, because every wavefront has finished reading
+// stage s by then, frees its slot.  E8M0 bytes and MBS words travel per group of four stages: a row's 16
+// scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each).
+//
+// MBS (Sec. 4.3.2, App. E): the two instructions of a fragment pair start from a zero accumulator and
+// yield the partial sums of one macro block, which the vector ALUs fold into the running result as
+//     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
+// The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
+// one of three LDS tables.  A product is folded in while the next pair's instructions run.
+//
+// LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
+// c ^ ((r >> 2) & 3), which keeps the 16-lane groups of a fragment read on distinct banks and lets four
+// lanes of a load fetch one contiguous 64-byte piece of a row.
+#pragma once
+
+#include "mx_gemm_shared.h"
+
+namespace mx {
+namespace {
+
+constexpr int kRingStageK = kMacro;             // K elements per stage
+constexpr int kRingRowStage = kRingStageK / 2;  // code bytes per row and stage
+constexpr int kRingSlots = 4;
+constexpr int kRingGroup = 4;                   // stages per 16-byte piece of a row's E8M0 bytes
+constexpr int kRingGroupM = 4;                  // tile-rows walked together for L2 reuse
+constexpr int kSigmaSlots = 3;
+
+template <int NWM_, int NWN_, int FM_, int FN_, bool kMbs_>
+struct RingShape {
+    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_;
+    static constexpr bool kMbs = kMbs_;
+    static constexpr int NW = NWM * NWN, NT = NW * kWave;
+    static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
+    static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
+    static constexpr int kCodeDma = kRows / 16 / NW;  // per wavefront and stage: 16 rows x 64 B per load
+    static constexpr int kRowDma = ceil_div(kRows, kWave * NW);  // per wavefront and group: one row per lane
+    static constexpr int kRowsPadded = kRowDma * NW * kWave;
+    static constexpr int kCodesStage = kRows * kRingRowStage;
+    static constexpr int kScaleGroup = kRowsPadded * 16;
+    static constexpr int kM8Group = kMbs ? kRowsPadded * 4 : 0;
+    static constexpr int kSigmaStage = kMbs ? kRows * 4 : 0;
+    static constexpr int kScaleBase = kRingSlots * kCodesStage;
+    static constexpr int kM8Base = kScaleBase + 2 * kScaleGroup;
+    static constexpr int kSigmaBase = kM8Base + 2 * kM8Group;
+    static constexpr int kDummy = kSigmaBase + kSigmaSlots * kSigmaStage;  // target of padding stores
+    static constexpr int kLdsBytes = kDummy + 256;
+    static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
+    static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
+    static_assert((TM / 16) % NW == 0 && (TN / 16) % NW == 0, "16-row code loads: operand fixed per load index");
+    static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
+    static_assert(NW * kStageRegion <= kLdsBytes, "epilogue staging fits the LDS of the main loop");
+    static_assert(FM * FN * 16 <= 256, "accumulators fill at most the accumulation registers");
+    static_assert(!kMbs || ((FM * FN) % 2 == 0 && FM >= 2 && FN >= 2), "MBS path: product slots, fragment refill points");
+};
+
+template <typename S>
+__global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
+    constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, NT = S::NT, kRows = S::kRows;
+    constexpr int kCodeDma = S::kCodeDma, kRowDma = S::kRowDma;
+    constexpr bool kMbs = S::kMbs;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
+    // tiles, walked in bands of kRingGroupM tile-rows so that concurrent workgroups share panels in its L2
+    const int total = g.tiles_m * g.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int linear = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || linear >= total) return;
+    const int band = kRingGroupM * g.tiles_n;
+    const int first_m = (linear / band) * kRingGroupM;
+    const int band_rows = min(g.tiles_m - first_m, kRingGroupM);
+    const int tm = first_m + (linear % band) % band_rows;
+    const int tn = (linear % band) / band_rows;
+    const int64_t a_row0 = (int64_t)tm * TM, b_row0 = (int64_t)tn * TN;
+
+    const int K = (int)g.K;
+    const int row_bytes = K >> 1, scale_bytes = K >> 5, nmac = K / kMacro;
+    const int nstages = K / kRingStageK, ngroups = nstages / kRingGroup;
+    const Operand opa = make_operand(g.a_codes, g.a_scales, g.a_mbs, a_row0, g.M, TM, g.K);
+    const Operand opb = make_operand(g.b_codes, g.b_scales, g.b_mbs, b_row0, g.N, TN, g.K);
+
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w % S::NWM, wn = w / S::NWM;
+    const int lr = l & 31, lh = l >> 5;
+
+    // ---- per-lane byte offsets of the direct-to-LDS loads (constant over the K loop) ----------------
+    // Codes: load i of wavefront w covers rows (i * NW + w) * 16 .. + 15 of the A-then-B row space; lane l
+    // writes LDS slot l of that 1-KiB block and fetches row l / 4, chunk (l % 4) ^ ((row >> 2) & 3).
+    int code_off[kCodeDma];
+#pragma unroll
+    for (int i = 0; i < kCodeDma; ++i) {
+        const int row = ((i * NW + w) * 16 + (l >> 2)) - (i * NW * 16 < TM ? 0 : TM);  // row within its operand
+        code_off[i] = row * row_bytes + (((l & 3) ^ ((row >> 2) & 3)) * 16);
+    }
+    // Per-row loads: load i of wavefront w serves row (i * NW + w) * 64 + l with the 16 E8M0 bytes, or the 4
+    // MBS words, of a group of four stages; rows past the tile are padding and read zero.
+    int scale_off[kRowDma], m8_off[kRowDma];
+    bool row_is_a[kRowDma];
+#pragma unroll
+    for (int i = 0; i < kRowDma; ++i) {
+        const int grow = (i * NW + w) * kWave + l;
+        row_is_a[i] = (i * NW + w) * kWave < TM;
+        const int row = grow - (row_is_a[i] ? 0 : TM);
+        scale_off[i] = grow >= kRows ? kOob : row * scale_bytes;
+        m8_off[i] = grow >= kRows ? kOob : row * nmac;
+    }
+
+    // A stage or group past the end of K is never used; its loads (the pipeline issues them regardless, into
+    // slots that are no longer read) fetch the last one again, so that no address leaves the operands.
+    // (The offsets and resources are passed as named copies: handed over as array elements or conditional
+    // expressions, the host pass of the compiler drops the kernel.)
+    auto dma_code = [&](int s, auto i_) {  // load i of the codes of stage s
+        constexpr int i = decltype(i_)::value;
+        uint8_t* dst = smem + (s % kRingSlots) * S::kCodesStage + (i * NW + w) * 1024;
+        const int voff = code_off[i];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 16 < TM ? opa.codes : opb.codes, (lds_ptr_t)dst, 16, voff,
+                                                 min(s, nstages - 1) * kRingRowStage, 0, 0);
+    };
+    auto dma_scale = [&](int grp, auto i_) {  // load i of the E8M0 bytes of stages 4 grp .. 4 grp + 3
+        constexpr int i = decltype(i_)::value;
+        uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 1024;
+        const int voff = scale_off[i];
+        const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.scales : opb.scales;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 16, voff, min(grp, ngroups - 1) * 16, 0, 0);
+    };
+    auto dma_m8 = [&](int grp, auto i_) {  // load i of the MBS words of stages 4 grp .. 4 grp + 3
+        constexpr int i = decltype(i_)::value;
+        uint8_t* dst = smem + S::kM8Base + (grp & 1) * S::kM8Group + (i * NW + w) * 256;
+        const int voff = m8_off[i];
+        const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.mbs : opb.mbs;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 4, voff, min(grp, ngroups - 1) * 4, 0, 0);
+    };
+    // MBS words of stage s (landed and published) -> fp32 sigma = 1/F, F = 1 + m8/256 exact, reciprocal
+    // within an ulp.  Thread p serves row p; threads past the last row redo row 0 and store to the padding
+    // area, which keeps the stage body free of branches.
+    auto convert_sigma = [&](int s) {
+        const uint32_t* raw = reinterpret_cast<const uint32_t*>(smem + S::kM8Base + ((s / kRingGroup) & 1) * S::kM8Group);
+        float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
+#pragma unroll
+        for (int i = 0; i < ceil_div(kRows, NT); ++i) {
+            const int q = i * NT + tid;
+            const bool live = kRows % NT == 0 || q < kRows;
+            const int p = live ? q : 0;
+            const uint32_t m8 = (raw[p] >> (8 * (s % kRingGroup))) & 0xFFu;
+            float* dst = live ? sig + p : reinterpret_cast<float*>(smem + S::kDummy);
+            *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
+        }
+    };
+
+    // ---- operands of one macro block in registers ----------------------------------------------------
+    struct Frags {
+        v4i m[FM][2], n[FN][2];
+        uint32_t scl_m[FM], scl_n[FN];
+    };
+    // sigma values in registers: this lane's output row of each A fragment, per stage parity, and the eight
+    // output columns of the B fragment that the next product half needs, fetched one half ahead.
+    float sig_m[2][FM];
+    v4f sig_n[2][2];
+    int frag_off[2];  // this lane's 16 bytes inside a fragment's 32 rows, per instruction of the pair
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) frag_off[kk] = lr * kRingRowStage + (((lh * 2 + kk) ^ ((lr >> 2) & 3)) * 16);
+    const int lane_scale = lr * 16 + lh * 2;
+
+    // LDS read `idx` of the kReads that fetch the fragments of stage s: per fragment (A's FM, then B's FN) the
+    // two 16-byte code pieces and the 16-bit scale pair.
+    constexpr int kReads = (FM + FN) * 3;
+    auto read_item = [&](Frags& f, int s, auto idx_) {
+        constexpr int idx = decltype(idx_)::value, fr = idx / 3, part = idx % 3;
+        constexpr bool is_m = fr < FM;
+        constexpr int q = is_m ? fr : fr - FM;
+        const int row0 = is_m ? (wm * FM + q) * 32 : TM + (wn * FN + q) * 32;  // in the A-then-B row space
+        if constexpr (part < 2) {
+            const v4i v = *reinterpret_cast<const v4i*>(smem + (s % kRingSlots) * S::kCodesStage + row0 * kRingRowStage +
+                                                        frag_off[part]);
+            if constexpr (is_m) f.m[q][part] = v;
+            else f.n[q][part] = v;
+        } else {
+            const uint32_t v = *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
+                                                 (s % kRingGroup) * 4 + lane_scale + row0 * 16);
+            if constexpr (is_m) f.scl_m[q] = v;
+            else f.scl_n[q] = v;
+        }
+    };
+    // sigma values of stage s: one float per A fragment, four float4 per B fragment (columns 8 g + 4 h .. + 3)
+    auto read_sigma_m = [&](int s, auto par_) {
+        const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
+    };
+    // product half u = 2 q + h of stage s covers columns 8 g + 4 h' .. + 3 of B fragment j = q / FM for g = 2 h, 2 h + 1
+    auto read_sigma_n = [&](int s, auto u_) {
+        constexpr int u = decltype(u_)::value, j = (u / 2) / FM, h = u % 2;
+        const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
+#pragma unroll
+        for (int gq = 0; gq < 2; ++gq)
+            sig_n[u % 2][gq] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 32 + (h * 2 + gq) * 8 + lh * 4);
+    };
+
+    v16f acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- loads per stage ---------------------------------------------------------------------------
+    // Every stage requests the codes of stage s + 4; the first stage of a group (phase 0) also the scales of
+    // the next group, into the slot the previous group left two stages ago; the third (phase 2) the MBS
+    // words of the group after next, which have to be on hand two stages before their first use.
+    constexpr int kLoads[4] = {kCodeDma + kRowDma, kCodeDma, kCodeDma + (kMbs ? kRowDma : 0), kCodeDma};
+    static_assert(kRingSlots * kCodeDma + 3 * kRowDma < 64, "vmcnt is a 6-bit counter");
+
+    // ---- prologue: fill the ring, fetch the operands of stage 0 --------------------------------------
+    static_for<kRowDma>([&](auto i_) { dma_scale(0, i_); });
+    if constexpr (kMbs) {
+        static_for<kRowDma>([&](auto i_) { dma_m8(0, i_); });
+        static_for<kRowDma>([&](auto i_) { dma_m8(1, i_); });
+    }
+    static_for<kRingSlots * kCodeDma>([&](auto t_) {
+        constexpr int t = decltype(t_)::value;
+        dma_code(t / kCodeDma, std::integral_constant<int, t % kCodeDma>{});
+    });
+    __builtin_amdgcn_s_waitcnt(wait_imm((kRingSlots - 1) * kCodeDma));
+    bare_barrier();
+    Frags f0, f1;
+    if constexpr (kMbs) {
+        convert_sigma(0);
+        convert_sigma(1);
+        __builtin_amdgcn_s_waitcnt(kWaitLds);
+        bare_barrier();
+        read_sigma_m(0, std::integral_constant<int, 0>{});
+        read_sigma_n(0, std::integral_constant<int, 0>{});
+    }
+    static_for<kReads>([&](auto idx_) { read_item(f0, 0, idx_); });
+
+    // ---- the matrix instructions of one stage ---------------------------------------------------------
+    // Plain: instruction t is half kk = t / (FM FN) of fragment pair (i, j); the two halves of a pair are
+    // FM FN instructions apart, so none waits for its predecessor.  MBS: pair q = (j, i) takes instructions
+    // 2 q (from a zero accumulator) and 2 q + 1 (on top of it) into product slot q % 2.
+    constexpr int kPairs = FM * FN, kMfmas = kPairs * 2;
+    v16f prod[2];
+    auto product = [&](const Frags& f, auto q_, auto kk_) {
+        constexpr int q = decltype(q_)::value, kk = decltype(kk_)::value, j = q / FM, i = q % FM;
+        if constexpr (kk == 0) {
+            v16f zero;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+            prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
+        } else {
+            prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
+        }
+    };
+    // folds half h of the product of pair q into the accumulators
+    auto retire = [&](auto par_, auto q_, auto h_) {
+        constexpr int q = decltype(q_)::value, h = decltype(h_)::value, j = q / FM, i = q % FM;
+        const float sm = sig_m[decltype(par_)::value][i];
+#pragma unroll
+        for (int e = h * 8; e < h * 8 + 8; ++e)
+            acc[i][j][e] = fmaf(prod[q % 2][e], sm * sig_n[h][(e / 4) % 2][e % 4], acc[i][j][e]);
+    };
+
+    // One stage: publish stage s + 1; multiply stage s out of `cur`; slipped in between the matrix
+    // instructions, the LDS reads of stage s + 1 into `next` and, with kIssue, this stage's loads.  The
+    // wavefronts issue their loads at different instruction slots (kLate 0 or 1).
+    auto stage = [&](int s, const Frags& cur, Frags& next, auto phase_, auto late_, auto issue_) {
+        constexpr int kPhase = decltype(phase_)::value, kLate = decltype(late_)::value;
+        using Par = std::integral_constant<int, kPhase % 2>;       // stage parity: kRingGroup is even
+        using NextPar = std::integral_constant<int, 1 - kPhase % 2>;
+        constexpr bool kIssue = decltype(issue_)::value;
+        constexpr int kN = kLoads[kPhase];
+        // Own loads of stage s + 1 (and of what the group loads two or more stages old carry) have landed;
+        // the loads issued in the last two stages may still fly.  Own reads of `cur` are done.
+        constexpr int kYounger = kLoads[(kPhase + 2) % 4] + kLoads[(kPhase + 3) % 4];
+        __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? kYounger : 0));
+        bare_barrier();
+        if constexpr (kMbs) convert_sigma(s + 2);  // into the table stage s - 1 was read from
+        auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
+            constexpr int t = decltype(t_)::value;
+            if constexpr (!kMbs) {
+                static_for<kReads>([&](auto r_) {
+                    if constexpr ((decltype(r_)::value * kMfmas) / kReads == t) read_item(next, s + 1, r_);
+                });
+            }
+            if constexpr (kMbs && t == kMfmas / 2) read_sigma_m(s + 1, NextPar{});
+            if constexpr (kIssue) {
+                static_for<kN>([&](auto n_) {
+                    constexpr int n = decltype(n_)::value, slot = (n * kMfmas) / kN + kLate;
+                    if constexpr ((slot < kMfmas ? slot : kMfmas - 1) == t) {
+                        if constexpr (n < kCodeDma) dma_code(s + kRingSlots, n_);
+                        else if constexpr (kPhase == 0) dma_scale(s / kRingGroup + 1, std::integral_constant<int, n - kCodeDma>{});
+                        else dma_m8(s / kRingGroup + 2, std::integral_constant<int, n - kCodeDma>{});
+                    }
+                });
+            }
+        };
+        if constexpr (kMbs) {
+            // step q: the instructions of pair q + 1 (of the next stage for the last step) around the two
+            // halves of folding in pair q, whose instructions were issued one step earlier
+            static_for<kPairs>([&](auto q_) {
+                constexpr int q = decltype(q_)::value;
+                using Next = std::integral_constant<int, (q + 1) % kPairs>;
+                using K0 = std::integral_constant<int, 0>;
+                using K1 = std::integral_constant<int, 1>;
+                if constexpr (q + 1 < kPairs) product(cur, Next{}, K0{});
+                else product(next, Next{}, K0{});
+                slip(std::integral_constant<int, 2 * q>{});
+                read_sigma_n(s, std::integral_constant<int, 2 * q + 1>{});
+                retire(Par{}, q_, K0{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (q + 1 < kPairs) product(cur, Next{}, K1{});
+                else product(next, Next{}, K1{});
+                // The MBS path keeps one set of fragment registers (`cur` and `next` are the same object): a
+                // fragment is refilled with the next stage's data right after the last pair that uses it.
+                if constexpr (q + 1 < kPairs) {
+                    constexpr int pj = (q + 1) / FM, pi = (q + 1) % FM;
+                    if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
+                        read_item(next, s + 1, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
+                    });
+                    if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
+                        read_item(next, s + 1, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
+                    });
+                }
+                slip(std::integral_constant<int, 2 * q + 1>{});
+                if constexpr (q + 1 < kPairs) read_sigma_n(s, std::integral_constant<int, 2 * q + 2>{});
+                else read_sigma_n(s + 1, std::integral_constant<int, 0>{});
+                retire(Par{}, q_, K1{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else {
+            static_for<kMfmas>([&](auto t_) {
+                constexpr int t = decltype(t_)::value, kk = t / kPairs, i = t % kPairs / FN, j = t % FN;
+                acc[i][j] = mfma_fp4_wide<kk, kk>(cur.n[j][kk], cur.m[i][kk], acc[i][j], cur.scl_n[j], cur.scl_m[i]);
+                slip(t_);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+    };
+    using Zero = std::integral_constant<int, 0>;
+    if constexpr (kMbs) {  // the first pair of stage 0
+        product(f0, Zero{}, Zero{});
+        product(f0, Zero{}, std::integral_constant<int, 1>{});
+    }
+    // Stages whose iteration still has a stage s + 4 to request, rounded up to whole groups (the extra ones
+    // fetch the last stage again into slots that are no longer read); the rest runs without loads.
+    const int n_issue = (max(nstages - kRingSlots, 0) + kRingGroup - 1) / kRingGroup * kRingGroup;
+    auto run = [&](auto late_) {
+        using Yes = std::integral_constant<bool, true>;
+        using No = std::integral_constant<bool, false>;
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        using P2 = std::integral_constant<int, 2>;
+        using P3 = std::integral_constant<int, 3>;
+        Frags& fa = f0;
+        Frags& fb = kMbs ? f0 : f1;  // the MBS path refills one set in place
+        int s = 0;
+        for (; s < n_issue; s += 4) {
+            stage(s, fa, fb, P0{}, late_, Yes{});
+            stage(s + 1, fb, fa, P1{}, late_, Yes{});
+            stage(s + 2, fa, fb, P2{}, late_, Yes{});
+            stage(s + 3, fb, fa, P3{}, late_, Yes{});
+        }
+        for (; s < nstages; s += 4) {  // nstages is a multiple of the group
+            stage(s, fa, fb, P0{}, late_, No{});
+            stage(s + 1, fb, fa, P1{}, late_, No{});
+            stage(s + 2, fa, fb, P2{}, late_, No{});
+            stage(s + 3, fb, fa, P3{}, late_, No{});
+        }
+    };
+    if (w % 4 < 2) run(std::integral_constant<int, 0>{});
+    else run(std::integral_constant<int, 1>{});
+
+    // ---- epilogue ------------------------------------------------------------------------------------
+    // A lane holds, per fragment, output row lr and the column groups 8 g + 4 h .. + 3.  Each wavefront
+    // passes its block through its own piece of LDS, 32 output rows at a time, so that the global stores
+    // cover whole row segments (16 bytes per lane, consecutive lanes along n).
+    __builtin_amdgcn_s_waitcnt(wait_imm(0));
+    bare_barrier();  // every wavefront's loads have landed and all LDS reads are done: the LDS is free
+    constexpr int kCols = FN * 32;
+    uint8_t* stg = smem + w * S::kStageRegion;
+    const int64_t m0 = a_row0 + wm * FM * 32, n0 = (int64_t)tn * TN + wn * kCols;
+    auto flush = [&](auto bf16_) {
+        constexpr bool kBf16 = decltype(bf16_)::value;
+        constexpr int esz = kBf16 ? 2 : 4, per = 16 / esz;  // bytes per element, elements per lane and store
+        constexpr int pitch = kCols * esz + 16;             // bytes per staged row; the pad spreads the rows over the banks
+        constexpr int lanes_per_row = kCols * esz / 16, rows_per_pass = kWave / lanes_per_row;
+        const int rd_row = l / lanes_per_row, rd_chunk = l % lanes_per_row;
+        const int64_t n = n0 + rd_chunk * per;
+        const bool whole = g.vec_store16 && n + per <= g.N;
+        static_for<FM>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+            static_for<FN * 4>([&](auto q_) {
+                constexpr int j = decltype(q_)::value / 4, gq = decltype(q_)::value % 4;
+                const int col = j * 32 + gq * 8 + lh * 4;
+                const v4f v = {acc[i][j][gq * 4], acc[i][j][gq * 4 + 1], acc[i][j][gq * 4 + 2], acc[i][j][gq * 4 + 3]};
+                if constexpr (kBf16)
+                    *reinterpret_cast<uint2*>(stg + lr * pitch + col * 2) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+                else
+                    *reinterpret_cast<v4f*>(stg + lr * pitch + col * 4) = v;
+            });
+            __builtin_amdgcn_s_waitcnt(kWaitLds);
+            static_for<32 / rows_per_pass>([&](auto p_) {
+                const int row = decltype(p_)::value * rows_per_pass + rd_row;
+                const v4i v = *reinterpret_cast<const v4i*>(stg + row * pitch + rd_chunk * 16);
+                const int64_t m = m0 + i * 32 + row;
+                if (m < g.M && n < g.N) {
+                    uint8_t* o = static_cast<uint8_t*>(g.C) + (m * g.ldc + n) * esz;
+                    if (whole) {
+                        *reinterpret_cast<v4i*>(o) = v;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < per; ++e) {
+                            if (n + e >= g.N) break;
+                            if constexpr (kBf16) reinterpret_cast<uint16_t*>(o)[e] = (uint16_t)((uint32_t)v[e >> 1] >> ((e & 1) * 16));
+                            else reinterpret_cast<int*>(o)[e] = v[e];
+                        }
+                    }
+                }
+            });
+            __builtin_amdgcn_s_waitcnt(kWaitLds);  // the rows are in registers before the next block overwrites them
+        });
+    };
+    if (g.c_bf16) flush(std::integral_constant<bool, true>{});
+    else flush(std::integral_constant<bool, false>{});
+}
+
+template <typename S>
+int launch_ring(GemmArgs g, hipStream_t s) {
+    const int64_t tiles_m = (g.M + S::TM - 1) / S::TM, tiles_n = (g.N + S::TN - 1) / S::TN;
+    if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
+    g.tiles_m = (int)tiles_m;
+    g.tiles_n = (int)tiles_n;
+    const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
+    static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
+    auto* fn = gemm_ring_kernel<S>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                S::kLdsBytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return MX_ELAUNCH;
+        }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(S::NT), S::kLdsBytes, s, g);
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace mx

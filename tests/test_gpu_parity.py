@@ -310,31 +310,40 @@ def random_operand(rng, rows, K, lo=110, hi=140):
             rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3])
 def test_gemm_every_tile_shape(mx, oracle, shape):
-    """Each tile shape forced in turn (0: 128 x 128, 1: 256 x 128, 2: the 256 x 256 kernel of the plain
-    path) on sizes with ragged tiles in M and N, several K stages and both output types."""
+    """Each kernel forced in turn (0, 1: the generic kernel on 128 x 128 and 256 x 128 tiles; 2, 3: the main
+    kernels without and with MBS) on sizes with ragged tiles in M and N, several K stages, both output
+    types and rows of C that vector stores cannot serve."""
     lib = mx.load_library()
     rng = np.random.default_rng(50 + shape)
     try:
         lib.mx_internal_set_gemm_shape(shape)
         for (M, N, K) in ((700, 530, 1536), (257, 300, 512)):
             a, b = random_operand(rng, M, K), random_operand(rng, N, K)
-            want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None))
-            c32 = gpu_gemm(mx, a, b, "f32", plain=True)
-            assert_gemm_close(host(c32), want, "plain shape %d %dx%dx%d" % (shape, M, N, K))
-            assert torch.equal(gpu_gemm(mx, a, b, "bf16", plain=True), c32.to(torch.bfloat16))
-            # rows of C that start at odd element offsets: no vector stores, the frame around C stays untouched
             da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
-            for dt in (torch.float32, torch.bfloat16):
-                big = torch.full((M + 2, N + 3), -3.0, dtype=dt, device="cuda")
-                mx.mx_gemm(da[0], da[1], db[0], db[1], "f32" if dt == torch.float32 else "bf16", out=big[1:M + 1, 1:N + 1])
-                assert torch.equal(big[1:M + 1, 1:N + 1], c32.to(dt))
-                frame = big.clone()
-                frame[1:M + 1, 1:N + 1] = -3.0
-                assert bool((frame == -3.0).all())
-            if shape != 2:
-                assert_gemm_close(host(gpu_gemm(mx, a, b, "f32")), oracle.gemm(a, b), "mbs shape %d" % shape)
+            for plain in ((True, False) if shape < 2 else (shape == 2,)):
+                want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None)) if plain else oracle.gemm(a, b)
+                what = "%s shape %d %dx%dx%d" % ("plain" if plain else "mbs", shape, M, N, K)
+                c32 = gpu_gemm(mx, a, b, "f32", plain=plain)
+                assert_gemm_close(host(c32), want, what)
+                assert torch.equal(gpu_gemm(mx, a, b, "bf16", plain=plain), c32.to(torch.bfloat16)), what
+                # rows of C that start at odd element offsets: no vector stores, the frame around C stays untouched
+                for dt in (torch.float32, torch.bfloat16):
+                    big = torch.full((M + 2, N + 3), -3.0, dtype=dt, device="cuda")
+                    out, name = big[1:M + 1, 1:N + 1], "f32" if dt == torch.float32 else "bf16"
+                    if plain:
+                        mx.mx_gemm(da[0], da[1], db[0], db[1], name, out=out)
+                    else:
+                        mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], db[2], name, out=out)
+                    assert torch.equal(out, c32.to(dt)), what
+                    frame = big.clone()
+                    frame[1:M + 1, 1:N + 1] = -3.0
+                    assert bool((frame == -3.0).all()), what
+            if shape == 3:  # one-sided MBS: a null array means sigma = 1
+                want = oracle.gemm(a, (b[0], b[1], None))
+                got = mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], None, "f32")
+                assert_gemm_close(host(got), want, "A-only mbs shape 3")
     finally:
         lib.mx_internal_set_gemm_shape(-1)
 
