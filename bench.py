@@ -122,13 +122,14 @@ def main():
         "config": {"workload": WORKLOAD, "M": M, "N": N, "K": K, "rule": "oas", "mbs": "static/128",
                    "buffers": "inputs rotated over %d A / %d W / %d C buffers" % (len(xa), len(xw), len(cs))},
         "roofline": {
-            "kernel": "gemm_kernel<mbs> (mx_gemm_mbs)",
+            "kernel": "gemm_ring_kernel<256x128 tile, MBS> (mx_gemm_mbs)",
             "bound": "mfma",
             "achieved": round(gemm_tflops, 2),
             "peak": metrics.MFMA_FP4_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(gemm_tflops / metrics.MFMA_FP4_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": metrics.GEMM_MBS_TRAFFIC_BYTES,
+            "algorithmic_operand_bytes": metrics.gemm_operand_bytes(M, N, K, mbs=True) + M * N * 2,
             "avg_launch_ms": round(ms_gemm, 4),
         },
         "quantize": {
@@ -174,6 +175,10 @@ def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):
     res["gemm_plain_tflops"] = round(plain_tflops, 2)
     res["gemm_mbs_tflops"] = round(mbs_tflops, 2)
     res["gemm_mbs_overhead"] = round(metrics.overhead_fraction(plain_tflops, mbs_tflops), 4)
+    # what the matrix cores sustain with nothing else going on: the practical ceiling for these clocks and
+    # this power limit (the published peak assumes 2.4 GHz, which random operand bits do not reach)
+    res["mfma_issue_only_tflops"] = {"constant_operands": round(mx.mfma_rate(False), 1),
+                                     "random_operands": round(mx.mfma_rate(True), 1)}
     res["paper_context"] = "paper reports 6.2% average MBS GEMM overhead on NVIDIA B200 / CUTLASS 4.3.0 (other hardware)"
     # copy yardstick: read + write of the same byte count as one W tensor
     src, dst = xw[1], xw[2]

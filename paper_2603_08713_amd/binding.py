@@ -54,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_status_string.argtypes = [ci]
     L.mx_version.restype = ci
     L.mx_version.argtypes = []
+    L.mx_internal_mfma_rate.restype = ci
+    L.mx_internal_mfma_rate.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_double)]
     _lib = L
     return L
 
@@ -67,6 +69,14 @@ def mx_version() -> int:
 
 
 # ---- helpers ---------------------------------------------------------------------------------------
+def mfma_rate(random_operands: bool, iters: int = 20000) -> float:
+    """Measurement aid, not part of the path: the FP4 matrix-instruction rate (TFLOP/s) the device
+    sustains out of registers, with constant or with random operand bits."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().mx_internal_mfma_rate(1 if random_operands else 0, iters, ctypes.byref(out)), "mx_internal_mfma_rate")
+    return out.value
+
+
 def _torch():
     import torch
 

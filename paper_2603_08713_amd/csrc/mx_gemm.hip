@@ -567,7 +567,8 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     if (g_force_shape >= 0) shape = g_force_shape;
     if (shape >= 2) {
         if (!ring_ok || (shape == 2) == use_mbs) return MX_EINVAL;  // only reachable through the development switch
-        return shape == 2 ? launch_gemm_wide(g, s) : launch_gemm_mbs_ring(g, s);
+        // (forced through the development switch the plain kernel keeps to its large tile)
+        return shape == 2 ? launch_gemm_wide(g, g_force_shape < 0, s) : launch_gemm_mbs_ring(g, s);
     }
     if (!fast) return launch_shape<Shape128, Shape128Wide, false>(g, grouped, use_mbs, ragged, s);
     if (shape >= 1) return launch_shape<Shape256x128, Shape256x128Wide, true>(g, grouped, use_mbs, ragged, s);

@@ -19,3 +19,14 @@ def overhead_fraction(tflops_plain: float, tflops_mbs: float) -> float:
     """GEMM overhead of the MBS kernel over the plain MXFP4 kernel, in the convention of the
     paper's Tab. 4: 1 - TFLOPS_MBS / TFLOPS_plain (e.g. 35.90 -> 30.57 is 14.84 %)."""
     return 1.0 - tflops_mbs / tflops_plain
+
+
+def gemm_operand_bytes(M: int, N: int, K: int, mbs: bool) -> float:
+    """Algorithmic operand bytes of one GEMM launch: each code, E8M0 byte and MBS word read once."""
+    per_elt = 0.5 + 1.0 / 32.0 + (1.0 / 128.0 if mbs else 0.0)
+    return (M + N) * K * per_elt
+
+
+# HBM traffic of one MBS GEMM launch on the bench shape (bytes), from the FETCH_SIZE and WRITE_SIZE counter
+# runs whose summaries are kept under profiles/ (scaled by the copy-kernel calibration stated there).
+GEMM_MBS_TRAFFIC_BYTES = int((235.7 + 113.8) * 2 ** 20)  # read 235.7 MiB + written 113.8 MiB
