@@ -7,7 +7,13 @@
 namespace mx {
 
 // Requires K % 512 == 0, K > 0, 16-byte aligned scale arrays and 4-byte aligned MBS arrays (a row's words of
-// four stages are fetched as one dword); the caller has checked all of them.  A null MBS array means sigma = 1.
-int launch_gemm_mbs_ring(const GemmArgs& g, hipStream_t s) { return launch_ring<RingShape<4, 2, 2, 2, true>>(g, s); }
+// four stages are fetched as one dword); the caller has checked all of them.  A null MBS array means sigma = 1
+// for that operand: the one-sided variants fold a product in with one multiply-add per output instead of two
+// operations.
+int launch_gemm_mbs_ring(const GemmArgs& g, hipStream_t s) {
+    if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<4, 2, 2, 2, 3>>(g, s);
+    if (g.a_mbs) return launch_ring<RingShape<4, 2, 2, 2, 1>>(g, s);
+    return launch_ring<RingShape<4, 2, 2, 2, 2>>(g, s);
+}
 
 }  // namespace mx

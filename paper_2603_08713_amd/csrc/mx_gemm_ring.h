@@ -48,10 +48,11 @@ constexpr int kRingGroup = 4;                   // stages per 16-byte piece of a
 constexpr int kRingGroupM = 4;                  // tile-rows walked together for L2 reuse
 constexpr int kSigmaSlots = 3;
 
-template <int NWM_, int NWN_, int FM_, int FN_, bool kMbs_>
+// kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both)
+template <int NWM_, int NWN_, int FM_, int FN_, int kSides_>
 struct RingShape {
-    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_;
-    static constexpr bool kMbs = kMbs_;
+    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
+    static constexpr bool kMbs = kSides != 0;
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
     static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
@@ -80,7 +81,7 @@ template <typename S>
 __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, NT = S::NT, kRows = S::kRows;
     constexpr int kCodeDma = S::kCodeDma, kRowDma = S::kRowDma;
-    constexpr bool kMbs = S::kMbs;
+    constexpr bool kMbs = S::kMbs, kSigmaA = (S::kSides & 1) != 0, kSigmaB = (S::kSides & 2) != 0;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
         for (int i = 0; i < ceil_div(kRows, NT); ++i) {
-            const int q = i * NT + tid;
+            const int q = i * NT + tid;  // (a side without words reads zero and stores sigma = 1, which nobody reads)
             const bool live = kRows % NT == 0 || q < kRows;
             const int p = live ? q : 0;
             const uint32_t m8 = (raw[p] >> (8 * (s % kRingGroup))) & 0xFFu;
@@ -207,6 +208,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     };
     // sigma values of stage s: one float per A fragment, four float4 per B fragment (columns 8 g + 4 h .. + 3)
     auto read_sigma_m = [&](int s, auto par_) {
+        if constexpr (!kSigmaA) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
         for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
@@ -214,6 +216,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // product half u = 2 q + h of stage s covers columns 8 g + 4 h' .. + 3 of B fragment j = q / FM for g = 2 h, 2 h + 1
     auto read_sigma_n = [&](int s, auto u_) {
         constexpr int u = decltype(u_)::value, j = (u / 2) / FM, h = u % 2;
+        if constexpr (!kSigmaB) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
         for (int gq = 0; gq < 2; ++gq)
@@ -280,8 +283,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         constexpr int q = decltype(q_)::value, h = decltype(h_)::value, j = q / FM, i = q % FM;
         const float sm = sig_m[decltype(par_)::value][i];
 #pragma unroll
-        for (int e = h * 8; e < h * 8 + 8; ++e)
-            acc[i][j][e] = fmaf(prod[q % 2][e], sm * sig_n[h][(e / 4) % 2][e % 4], acc[i][j][e]);
+        for (int e = h * 8; e < h * 8 + 8; ++e) {
+            const float sn = sig_n[h][(e / 4) % 2][e % 4];
+            acc[i][j][e] = fmaf(prod[q % 2][e], kSigmaA && kSigmaB ? sm * sn : kSigmaA ? sm : sn, acc[i][j][e]);
+        }
     };
 
     // One stage: publish stage s + 1; multiply stage s out of `cur`; slipped in between the matrix

@@ -14,8 +14,8 @@ namespace mx {
 // launches where that saves time: 256 x 256 tiles for as many columns as make whole rounds, 256 x 128 tiles
 // (half the cost each) for the rest.
 int launch_gemm_wide(const GemmArgs& g, bool allow_split, hipStream_t s) {
-    using Main = RingShape<2, 2, 4, 4, false>;
-    using Tail = RingShape<2, 2, 4, 2, false>;
+    using Main = RingShape<2, 2, 4, 4, 0>;
+    using Tail = RingShape<2, 2, 4, 2, 0>;
     constexpr int64_t kUnits = 256;  // compute units of the device
     const int64_t tiles_m = (g.M + Main::TM - 1) / Main::TM, cols = (g.N + Main::TN - 1) / Main::TN;
     auto rounds = [&](int64_t tiles) { return (tiles + kUnits - 1) / kUnits; };
