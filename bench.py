@@ -141,9 +141,27 @@ def main():
 
     if not args.no_extras:
         out["extras"] = extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args)
+        out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, a_bits, w_bits, flops, metrics)
     print(json.dumps(out))
+
+
+QSNR_ROWS = 256  # rows of the activation tensor the QSNR ladder is computed on, by both paths
+QSNR_LADDER = (("mxfp4", "ocp", False), ("+oas", "oas", False), ("+mbs", "ocp", True), ("+oas+mbs", "oas", True))
+
+
+def qsnr_ladder_gpu(mx, torch, x):
+    """QSNR (dB) of quantize -> dequantize through the HIP kernels for plain MXFP4, +OAS, +MBS, +OAS+MBS
+    (Sec. 3.1's metric: 10 log10(sum x^2 / sum (x - xq)^2)); the sums are taken in fp64 with torch."""
+    res = {}
+    ref = x.to(torch.float64)
+    for name, rule, mbs in QSNR_LADDER:
+        q = mx.mx_quantize_mbs(x, rule) if mbs else mx.mx_quantize(x, rule)
+        back = mx.mx_dequantize(q[0], q[1], q[2] if mbs else None, "f32").to(torch.float64)
+        res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
+    res["sample"] = "first %d rows of A" % QSNR_ROWS
+    return res
 
 
 def time_loop(torch, fn, iters, warm=3):
@@ -205,14 +223,21 @@ def cpu_baseline(np, a_bits, w_bits, flops, metrics):
     w = oracle.quantize(w_bits, "oas", mbs=True)
     tq = time.perf_counter() - t0
     q_rate = rows_q * K / tq                        # elements / s
-    a = oracle.quantize(a_bits[:64], "oas", mbs=True)
-    rows = np.arange(0, 64, 2)                      # 32 sampled output rows, all N columns
+    a = oracle.quantize(a_bits[:256], "oas", mbs=True)
+    rows = np.arange(0, 256)                        # 256 output rows, all N columns (about 10-15 s)
     t0 = time.perf_counter()
     oracle.gemm(a, w, rows=rows)
     tg = time.perf_counter() - t0
     g_rate = 2.0 * len(rows) * N * K / tg           # flop / s
     est_step_s = (M + N) * K / q_rate + flops / g_rate
+    x = a_bits[:QSNR_ROWS]
+    ref = oracle.bf16_to_f64(x)
+    ladder = {}
+    for name, rule, mbs in QSNR_LADDER:
+        q = oracle.quantize(x, rule, mbs=mbs)
+        ladder[name] = round(oracle.qsnr_db(ref, oracle.dequantize(q[0], q[1], q[2])), 3)
     return {
+        "qsnr_db_oracle": ladder,
         "value": round(flops / est_step_s / 1e12, 6),
         "unit": "TFLOP/s",
         "cores": threads,
