@@ -514,7 +514,7 @@ using Shape128Wide = Shape<2, 4, 2, 1, 32>;
 using Shape256x128 = Shape<4, 2, 4, 4, 16>;
 using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 = main MBS kernel
+int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 / 4 = main MBS kernel (128x32 / 64x64 per wavefront)
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -568,7 +568,7 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     if (shape >= 2) {
         if (!ring_ok || (shape == 2) == use_mbs) return MX_EINVAL;  // only reachable through the development switch
         // (forced through the development switch the plain kernel keeps to its large tile)
-        return shape == 2 ? launch_gemm_wide(g, g_force_shape < 0, s) : launch_gemm_mbs_ring(g, s);
+        return shape == 2 ? launch_gemm_wide(g, g_force_shape < 0, s) : launch_gemm_mbs_ring(g, shape == 4, s);
     }
     if (!fast) return launch_shape<Shape128, Shape128Wide, false>(g, grouped, use_mbs, ragged, s);
     if (shape >= 1) return launch_shape<Shape256x128, Shape256x128Wide, true>(g, grouped, use_mbs, ragged, s);

@@ -1,7 +1,10 @@
-// MXFP4 GEMM with the MBS correction on 256 x 128 tiles: eight wavefronts, two per SIMD, 64 x 64 outputs
-// each.  The vector ALUs consume every matrix-instruction result (acc += P * sigma_A * sigma_B), so this
-// translation unit is compiled with the VGPR form of the matrix instructions, and two wavefronts per SIMD
-// let one fold products in while the other's matrix instructions run.
+// MXFP4 GEMM with the MBS correction on 256 x 128 tiles: eight wavefronts, two per SIMD.  The vector ALUs
+// consume every matrix-instruction result (acc += P * sigma_A * sigma_B), so this translation unit is
+// compiled with the VGPR form of the matrix instructions, and two wavefronts per SIMD let one fold its
+// product in while the other's matrix instructions run.  A wavefront owns 128 x 32 outputs (four A
+// fragments against one B fragment): the 16 per-lane sigma_B values of the B fragment are read from LDS once
+// per stage and serve four products (the 64 x 64 arrangement, kept behind the development switch, reads
+// twice as many).
 #include "mx_gemm_ring.h"
 
 namespace mx {
@@ -10,10 +13,15 @@ namespace mx {
 // four stages are fetched as one dword); the caller has checked all of them.  A null MBS array means sigma = 1
 // for that operand: the one-sided variants fold a product in with one multiply-add per output instead of two
 // operations.
-int launch_gemm_mbs_ring(const GemmArgs& g, hipStream_t s) {
-    if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<4, 2, 2, 2, 3>>(g, s);
-    if (g.a_mbs) return launch_ring<RingShape<4, 2, 2, 2, 1>>(g, s);
-    return launch_ring<RingShape<4, 2, 2, 2, 2>>(g, s);
+int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s) {
+    if (variant == 1) {  // development: 64 x 64 per wavefront
+        if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<4, 2, 2, 2, 3>>(g, s);
+        if (g.a_mbs) return launch_ring<RingShape<4, 2, 2, 2, 1>>(g, s);
+        return launch_ring<RingShape<4, 2, 2, 2, 2>>(g, s);
+    }
+    if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<2, 4, 4, 1, 3>>(g, s);
+    if (g.a_mbs) return launch_ring<RingShape<2, 4, 4, 1, 1>>(g, s);
+    return launch_ring<RingShape<2, 4, 4, 1, 2>>(g, s);
 }
 
 }  // namespace mx

@@ -29,7 +29,8 @@
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
 // The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
-// one of three LDS tables.  A product is folded in while the next pair's instructions run.
+// one of three LDS tables.  A wavefront folds a product in as soon as it is there; meanwhile the SIMD's other
+// wavefront issues its matrix instructions or folds in its own product.
 //
 // LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
 // c ^ ((r >> 2) & 3), which keeps the 16-lane groups of a fragment read on distinct banks and lets four
@@ -74,7 +75,7 @@ struct RingShape {
     static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
     static_assert(NW * kStageRegion <= kLdsBytes, "epilogue staging fits the LDS of the main loop");
     static_assert(FM * FN * 16 <= 256, "accumulators fill at most the accumulation registers");
-    static_assert(!kMbs || ((FM * FN) % 2 == 0 && FM >= 2 && FN >= 2), "MBS path: product slots, fragment refill points");
+    static_assert(!kMbs || FN == 1 || FN % 2 == 0, "MBS path: sigma sets line up across stages");
 };
 
 template <typename S>
@@ -177,10 +178,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         v4i m[FM][2], n[FN][2];
         uint32_t scl_m[FM], scl_n[FN];
     };
-    // sigma values in registers: this lane's output row of each A fragment, per stage parity, and the eight
-    // output columns of the B fragment that the next product half needs, fetched one half ahead.
+    // sigma values in registers: this lane's output row of each A fragment, per stage parity, and its 16
+    // output columns of a B fragment.  Pairs run B fragment by B fragment; while one fragment's FM pairs
+    // are folded in, the next fragment's values (of this or of the next stage) arrive in the other set.
     float sig_m[2][FM];
-    v4f sig_n[2][2];
+    v4f sig_n[2][4];
     int frag_off[2];  // this lane's 16 bytes inside a fragment's 32 rows, per instruction of the pair
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) frag_off[kk] = lr * kRingRowStage + (((lh * 2 + kk) ^ ((lr >> 2) & 3)) * 16);
@@ -213,14 +215,13 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
     };
-    // product half u = 2 q + h of stage s covers columns 8 g + 4 h' .. + 3 of B fragment j = q / FM for g = 2 h, 2 h + 1
-    auto read_sigma_n = [&](int s, auto u_) {
-        constexpr int u = decltype(u_)::value, j = (u / 2) / FM, h = u % 2;
+    auto read_sigma_n = [&](int s, auto j_, auto set_) {
+        constexpr int j = decltype(j_)::value, set = decltype(set_)::value;
         if constexpr (!kSigmaB) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
-        for (int gq = 0; gq < 2; ++gq)
-            sig_n[u % 2][gq] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 32 + (h * 2 + gq) * 8 + lh * 4);
+        for (int gq = 0; gq < 4; ++gq)
+            sig_n[set][gq] = *reinterpret_cast<const v4f*>(sig + TM + (wn * FN + j) * 32 + gq * 8 + lh * 4);
     };
 
     v16f acc[FM][FN];
@@ -257,35 +258,35 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         __builtin_amdgcn_s_waitcnt(kWaitLds);
         bare_barrier();
         read_sigma_m(0, std::integral_constant<int, 0>{});
-        read_sigma_n(0, std::integral_constant<int, 0>{});
+        read_sigma_n(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     }
     static_for<kReads>([&](auto idx_) { read_item(f0, 0, idx_); });
 
     // ---- the matrix instructions of one stage ---------------------------------------------------------
     // Plain: instruction t is half kk = t / (FM FN) of fragment pair (i, j); the two halves of a pair are
-    // FM FN instructions apart, so none waits for its predecessor.  MBS: pair q = (j, i) takes instructions
-    // 2 q (from a zero accumulator) and 2 q + 1 (on top of it) into product slot q % 2.
+    // FM FN instructions apart, so none waits for its predecessor.  MBS: pair q = (j, i) takes two
+    // instructions, the first from a zero accumulator and the second on top of it, and is folded into the
+    // accumulators right away; while this wavefront waits for its product, the SIMD's other wavefront
+    // folds its own in, so the vector port stays busy with one product register set per wavefront.
     constexpr int kPairs = FM * FN, kMfmas = kPairs * 2;
-    v16f prod[2];
-    auto product = [&](const Frags& f, auto q_, auto kk_) {
-        constexpr int q = decltype(q_)::value, kk = decltype(kk_)::value, j = q / FM, i = q % FM;
-        if constexpr (kk == 0) {
-            v16f zero;
+    v16f prod;
+    auto product = [&](const Frags& f, auto q_) {
+        constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
+        v16f zero;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-            prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
-        } else {
-            prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
-        }
+        for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+        prod = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
+        prod = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod, f.scl_n[j], f.scl_m[i]);
     };
-    // folds half h of the product of pair q into the accumulators
-    auto retire = [&](auto par_, auto q_, auto h_) {
-        constexpr int q = decltype(q_)::value, h = decltype(h_)::value, j = q / FM, i = q % FM;
+    auto retire = [&](auto par_, auto q_) {
+        constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
         const float sm = sig_m[decltype(par_)::value][i];
+        // sigma set of B fragment j of this stage: fragments alternate sets, counted over all stages
+        constexpr int set = FN == 1 ? decltype(par_)::value : j % 2;
 #pragma unroll
-        for (int e = h * 8; e < h * 8 + 8; ++e) {
-            const float sn = sig_n[h][(e / 4) % 2][e % 4];
-            acc[i][j][e] = fmaf(prod[q % 2][e], kSigmaA && kSigmaB ? sm * sn : kSigmaA ? sm : sn, acc[i][j][e]);
+        for (int e = 0; e < 16; ++e) {
+            const float sn = sig_n[set][e / 4][e % 4];
+            acc[i][j][e] = fmaf(prod[e], kSigmaA && kSigmaB ? sm * sn : kSigmaA ? sm : sn, acc[i][j][e]);
         }
     };
 
@@ -324,36 +325,28 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             }
         };
         if constexpr (kMbs) {
-            // step q: the instructions of pair q + 1 (of the next stage for the last step) around the two
-            // halves of folding in pair q, whose instructions were issued one step earlier
+            // The MBS path keeps one set of fragment registers (`cur` and `next` are the same object): a
+            // fragment is refilled with the next stage's data right after the instructions of the last pair
+            // that uses it have been issued.
             static_for<kPairs>([&](auto q_) {
-                constexpr int q = decltype(q_)::value;
-                using Next = std::integral_constant<int, (q + 1) % kPairs>;
-                using K0 = std::integral_constant<int, 0>;
-                using K1 = std::integral_constant<int, 1>;
-                if constexpr (q + 1 < kPairs) product(cur, Next{}, K0{});
-                else product(next, Next{}, K0{});
-                slip(std::integral_constant<int, 2 * q>{});
-                read_sigma_n(s, std::integral_constant<int, 2 * q + 1>{});
-                retire(Par{}, q_, K0{});
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (q + 1 < kPairs) product(cur, Next{}, K1{});
-                else product(next, Next{}, K1{});
-                // The MBS path keeps one set of fragment registers (`cur` and `next` are the same object): a
-                // fragment is refilled with the next stage's data right after the last pair that uses it.
-                if constexpr (q + 1 < kPairs) {
-                    constexpr int pj = (q + 1) / FM, pi = (q + 1) % FM;
-                    if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
-                        read_item(next, s + 1, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
-                    });
-                    if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
-                        read_item(next, s + 1, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
-                    });
+                constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
+                product(cur, q_);
+                if constexpr (i == FM - 1) static_for<3>([&](auto part_) {
+                    read_item(next, s + 1, std::integral_constant<int, (FM + j) * 3 + decltype(part_)::value>{});
+                });
+                if constexpr (j == FN - 1) static_for<3>([&](auto part_) {
+                    read_item(next, s + 1, std::integral_constant<int, i * 3 + decltype(part_)::value>{});
+                });
+                // first pair of a B fragment: request the sigma values of the next one into the other set
+                if constexpr (i == 0) {
+                    using OtherSet = std::integral_constant<int, FN == 1 ? 1 - kPhase % 2 : (j + 1) % 2>;
+                    if constexpr (j + 1 < FN) read_sigma_n(s, std::integral_constant<int, j + 1>{}, OtherSet{});
+                    else read_sigma_n(s + 1, std::integral_constant<int, 0>{}, OtherSet{});
                 }
+                slip(std::integral_constant<int, 2 * q>{});
                 slip(std::integral_constant<int, 2 * q + 1>{});
-                if constexpr (q + 1 < kPairs) read_sigma_n(s, std::integral_constant<int, 2 * q + 2>{});
-                else read_sigma_n(s + 1, std::integral_constant<int, 0>{});
-                retire(Par{}, q_, K1{});
+                __builtin_amdgcn_sched_barrier(0);
+                retire(Par{}, q_);
                 __builtin_amdgcn_sched_barrier(0);
             });
         } else {
@@ -365,11 +358,6 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             });
         }
     };
-    using Zero = std::integral_constant<int, 0>;
-    if constexpr (kMbs) {  // the first pair of stage 0
-        product(f0, Zero{}, Zero{});
-        product(f0, Zero{}, std::integral_constant<int, 1>{});
-    }
     // Stages whose iteration still has a stage s + 4 to request, rounded up to whole groups (the extra ones
     // fetch the last stage again into slots that are no longer read); the rest runs without loads.
     const int n_issue = (max(nstages - kRingSlots, 0) + kRingGroup - 1) / kRingGroup * kRingGroup;
@@ -396,7 +384,9 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             stage(s + 3, fb, fa, P3{}, late_, No{});
         }
     };
-    if (w % 4 < 2) run(std::integral_constant<int, 0>{});
+    // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
+    // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
+    if (NW == 8 || w % 4 < 2) run(std::integral_constant<int, 0>{});
     else run(std::integral_constant<int, 1>{});
 
     // ---- epilogue ------------------------------------------------------------------------------------

@@ -24,7 +24,7 @@ struct GemmArgs {
 // Main kernels (mx_gemm_ring.h) for K % 512 == 0 and aligned scale and MBS arrays, not grouped: without MBS on
 // 256 x 256 tiles (mx_gemm_wide.hip), with MBS on 256 x 128 tiles (mx_gemm_mbs.hip).
 int launch_gemm_wide(const GemmArgs& g, bool allow_split, hipStream_t s);
-int launch_gemm_mbs_ring(const GemmArgs& g, hipStream_t s);
+int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
 
 namespace {
 

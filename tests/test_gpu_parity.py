@@ -310,10 +310,10 @@ def random_operand(rng, rows, K, lo=110, hi=140):
             rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4])
 def test_gemm_every_tile_shape(mx, oracle, shape):
-    """Each kernel forced in turn (0, 1: the generic kernel on 128 x 128 and 256 x 128 tiles; 2, 3: the main
-    kernels without and with MBS) on sizes with ragged tiles in M and N, several K stages, both output
+    """Each kernel forced in turn (0, 1: the generic kernel on 128 x 128 and 256 x 128 tiles; 2: the main
+    kernel without MBS; 3, 4: the main kernel with MBS, 128 x 32 and 64 x 64 outputs per wavefront) on sizes with ragged tiles in M and N, several K stages, both output
     types and rows of C that vector stores cannot serve."""
     lib = mx.load_library()
     rng = np.random.default_rng(50 + shape)
@@ -340,10 +340,13 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
                     frame = big.clone()
                     frame[1:M + 1, 1:N + 1] = -3.0
                     assert bool((frame == -3.0).all()), what
-            if shape == 3:  # one-sided MBS: a null array means sigma = 1
+            if shape >= 3:  # one-sided MBS: a null array means sigma = 1
                 want = oracle.gemm(a, (b[0], b[1], None))
                 got = mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], None, "f32")
-                assert_gemm_close(host(got), want, "A-only mbs shape 3")
+                assert_gemm_close(host(got), want, "A-only mbs shape %d" % shape)
+                want = oracle.gemm((a[0], a[1], None), b)
+                got = mx.mx_gemm_mbs(da[0], da[1], None, db[0], db[1], db[2], "f32")
+                assert_gemm_close(host(got), want, "B-only mbs shape %d" % shape)
     finally:
         lib.mx_internal_set_gemm_shape(-1)
 
