@@ -389,3 +389,77 @@ def test_grouped_gemm(mx, oracle):
             continue
         want = oracle.gemm(tuple(t[lo:hi] for t in a), tuple(t[e * N:(e + 1) * N] for t in b))
         assert_gemm_close(got[lo:hi], want, "group %d" % e)
+
+
+# ------------------------------------------------------------------------------------------------
+# The other workload configurations at their real shapes
+# ------------------------------------------------------------------------------------------------
+def test_config_decode_skinny(mx, oracle):
+    """M = 16 activations quantized online against offline-quantized weights, N = 4096 and 14336: the whole
+    output against the oracle."""
+    from paper_2603_08713_amd import synth
+
+    for n in (4096, 14336):
+        a_bits, w_bits = synth.decode_skinny(n, 4096)
+        a = mx.mx_quantize_mbs(dev_bf16(a_bits), "oas")
+        b = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
+        ah, bh = [host(t) for t in a], [host(t) for t in b]
+        assert all(np.array_equal(x, y) for x, y in zip(ah, oracle.quantize(a_bits, "oas", mbs=True)))
+        c = mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "f32")
+        assert_gemm_close(host(c), oracle.gemm(ah, bh), "decode skinny N=%d" % n)
+        assert torch.equal(mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "bf16"), c.to(torch.bfloat16))
+
+
+def test_config_llama70b_ffn_sampled(mx, oracle):
+    """M = 8192, N = 28672, K = 8192: quantized operands bit-exact on sampled rows, sampled output rows of
+    the MBS GEMM and of the plain GEMM against the oracle."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 8192, 28672, 8192
+    a_bits, w_bits = synth.llama70b_ffn(M, N, K)
+    a = mx.mx_quantize_mbs(dev_bf16(a_bits), "oas")
+    b = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
+    rng = np.random.default_rng(70)
+    rows = np.sort(rng.choice(M, 8, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    wrows = np.sort(rng.choice(N, 64, replace=False))
+    ah = [host(t[torch.from_numpy(rows).cuda()]) for t in a]
+    assert all(np.array_equal(x, y) for x, y in zip(ah, oracle.quantize(a_bits[rows], "oas", mbs=True)))
+    bw = [host(t[torch.from_numpy(wrows).cuda()]) for t in b]
+    assert all(np.array_equal(x, y) for x, y in zip(bw, oracle.quantize(w_bits[wrows], "oas", mbs=True)))
+    bh = [host(t) for t in b]
+    c = mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "bf16")
+    c32 = mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "f32")
+    assert torch.equal(c, c32.to(torch.bfloat16))
+    assert_gemm_close(host(c32[torch.from_numpy(rows).cuda()]), oracle.gemm(ah, bh), "llama70b mbs sampled rows")
+    p32 = mx.mx_gemm(a[0], a[1], b[0], b[1], "f32")
+    want = oracle.gemm((ah[0], ah[1], None), (bh[0], bh[1], None))
+    assert_gemm_close(host(p32[torch.from_numpy(rows).cuda()]), want, "llama70b plain sampled rows")
+
+
+def test_config_moe_grouped_sampled(mx, oracle):
+    """32 experts of 2880 x 2880, 8192 tokens routed top-4 with Zipf load (32768 rows in expert order): rows
+    sampled from every non-empty expert against the oracle; K = 2880 ends in a half macro block."""
+    from paper_2603_08713_amd import synth
+
+    x_bits, w_bits, offsets, token_of_row = synth.moe()
+    G, dim = 32, 2880
+    xa = dev_bf16(x_bits[token_of_row])               # activations gathered into expert order
+    a = mx.mx_quantize_mbs(xa, "oas")
+    b = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
+    off = torch.from_numpy(np.asarray(offsets, dtype=np.int64)).cuda()
+    c = mx.mx_gemm_mbs_grouped(a[0], a[1], a[2], b[0], b[1], b[2], off, dim, "f32")
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(c).all())
+    rng = np.random.default_rng(5)
+    ah, bh = [host(t) for t in a], [host(t) for t in b]
+    for e in range(G):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if lo == hi:
+            continue
+        rows = np.unique(np.concatenate([[lo, hi - 1], rng.integers(lo, hi, 2)]))
+        want = oracle.gemm(tuple(t[rows] for t in ah), tuple(t[e * dim:(e + 1) * dim] for t in bh))
+        assert_gemm_close(host(c[torch.from_numpy(rows).cuda()]), want, "moe expert %d" % e)
+    sample = np.sort(rng.choice(len(token_of_row), 64, replace=False))
+    want_q = oracle.quantize(x_bits[token_of_row[sample]], "oas", mbs=True)
+    assert all(np.array_equal(t[sample], y) for t, y in zip(ah, want_q))
