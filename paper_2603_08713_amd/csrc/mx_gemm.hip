@@ -514,7 +514,7 @@ using Shape128Wide = Shape<2, 4, 2, 1, 32>;
 using Shape256x128 = Shape<4, 2, 4, 4, 16>;
 using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 / 4 = main MBS kernel (128x32 / 64x64 per wavefront)
+int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 / 4 = main MBS kernel (128x32 / 64x64 per wavefront), 5 = few-row kernel
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -564,7 +564,13 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     if (ring_ok && !use_mbs && t256 >= 256) shape = 2;
     if (ring_ok && use_mbs && t256x128 >= 256) shape = 3;
+    const bool skinny_ok = ring_ok && M <= 64 && K <= 8192;
+    if (skinny_ok) shape = 5;
     if (g_force_shape >= 0) shape = g_force_shape;
+    if (shape == 5) {
+        if (!skinny_ok) return MX_EINVAL;  // only reachable through the development switch
+        return launch_gemm_skinny(g, use_mbs, s);
+    }
     if (shape >= 2) {
         if (!ring_ok || (shape == 2) == use_mbs) return MX_EINVAL;  // only reachable through the development switch
         // (forced through the development switch the plain kernel keeps to its large tile)

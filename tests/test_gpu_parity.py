@@ -391,6 +391,30 @@ def test_grouped_gemm(mx, oracle):
         assert_gemm_close(got[lo:hi], want, "group %d" % e)
 
 
+@pytest.mark.parametrize("M", [1, 7, 16, 17, 33, 64])
+def test_gemm_few_rows(mx, oracle, M):
+    """The few-row (decode) kernel: every fragment count, ragged N, K of one to several load groups per
+    wavefront, plain / one-sided / two-sided MBS, both output types."""
+    rng = np.random.default_rng(90 + M)
+    for (N, K) in ((1000, 512), (48, 1536), (530, 8192)):
+        a, b = random_operand(rng, M, K), random_operand(rng, N, K)
+        da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+        c32 = mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], db[2], "f32")
+        assert_gemm_close(host(c32), oracle.gemm(a, b), "few rows mbs %dx%dx%d" % (M, N, K))
+        assert torch.equal(mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], db[2], "bf16"), c32.to(torch.bfloat16))
+        assert_gemm_close(host(mx.mx_gemm(da[0], da[1], db[0], db[1], "f32")),
+                          oracle.gemm((a[0], a[1], None), (b[0], b[1], None)), "few rows plain %dx%dx%d" % (M, N, K))
+        assert_gemm_close(host(mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], None, "f32")),
+                          oracle.gemm(a, (b[0], b[1], None)), "few rows A-only %dx%dx%d" % (M, N, K))
+        assert_gemm_close(host(mx.mx_gemm_mbs(da[0], da[1], None, db[0], db[1], db[2], "f32")),
+                          oracle.gemm((a[0], a[1], None), b), "few rows B-only %dx%dx%d" % (M, N, K))
+        big = torch.full((M + 2, N + 3), -3.0, dtype=torch.float32, device="cuda")
+        mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], db[2], "f32", out=big[1:M + 1, 1:N + 1])
+        assert torch.equal(big[1:M + 1, 1:N + 1], c32)
+        big[1:M + 1, 1:N + 1] = -3.0
+        assert bool((big == -3.0).all())
+
+
 # ------------------------------------------------------------------------------------------------
 # The other workload configurations at their real shapes
 # ------------------------------------------------------------------------------------------------
