@@ -29,8 +29,8 @@
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
 // The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
-// one of three LDS tables.  A wavefront folds a product in as soon as it is there; meanwhile the SIMD's other
-// wavefront issues its matrix instructions or folds in its own product.
+// one of three LDS tables.  A wavefront folds a product in while the next pair's instructions run, and
+// the SIMD's other wavefront fills what gaps remain.
 //
 // LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
 // c ^ ((r >> 2) & 3), which keeps the 16-lane groups of a fragment read on distinct banks and lets four
@@ -265,18 +265,18 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // ---- the matrix instructions of one stage ---------------------------------------------------------
     // Plain: instruction t is half kk = t / (FM FN) of fragment pair (i, j); the two halves of a pair are
     // FM FN instructions apart, so none waits for its predecessor.  MBS: pair q = (j, i) takes two
-    // instructions, the first from a zero accumulator and the second on top of it, and is folded into the
-    // accumulators right away; while this wavefront waits for its product, the SIMD's other wavefront
-    // folds its own in, so the vector port stays busy with one product register set per wavefront.
+    // instructions, the first from a zero accumulator and the second on top of it; the instructions of pair
+    // q + 1 are issued before the product of pair q is folded into the accumulators (two product register
+    // sets), and the SIMD's other wavefront fills what gaps remain.
     constexpr int kPairs = FM * FN, kMfmas = kPairs * 2;
-    v16f prod;
+    v16f prod[2];
     auto product = [&](const Frags& f, auto q_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
         v16f zero;
 #pragma unroll
         for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-        prod = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
-        prod = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod, f.scl_n[j], f.scl_m[i]);
+        prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
+        prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
     };
     auto retire = [&](auto par_, auto q_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const float sn = sig_n[set][e / 4][e % 4];
-            acc[i][j][e] = fmaf(prod[e], kSigmaA && kSigmaB ? sm * sn : kSigmaA ? sm : sn, acc[i][j][e]);
+            acc[i][j][e] = fmaf(prod[q % 2][e], kSigmaA && kSigmaB ? sm * sn : kSigmaA ? sm : sn, acc[i][j][e]);
         }
     };
 
@@ -328,15 +328,20 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             // The MBS path keeps one set of fragment registers (`cur` and `next` are the same object): a
             // fragment is refilled with the next stage's data right after the instructions of the last pair
             // that uses it have been issued.
+            auto issue = [&](auto p_) {  // the instructions of pair p, then the refills it makes possible
+                constexpr int pj = decltype(p_)::value / FM, pi = decltype(p_)::value % FM;
+                product(cur, p_);
+                if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
+                    read_item(next, s + 1, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
+                });
+                if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
+                    read_item(next, s + 1, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
+                });
+            };
+            issue(std::integral_constant<int, 0>{});
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
-                product(cur, q_);
-                if constexpr (i == FM - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, std::integral_constant<int, (FM + j) * 3 + decltype(part_)::value>{});
-                });
-                if constexpr (j == FN - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, std::integral_constant<int, i * 3 + decltype(part_)::value>{});
-                });
+                if constexpr (q + 1 < kPairs) issue(std::integral_constant<int, q + 1>{});
                 // first pair of a B fragment: request the sigma values of the next one into the other set
                 if constexpr (i == 0) {
                     using OtherSet = std::integral_constant<int, FN == 1 ? 1 - kPhase % 2 : (j + 1) % 2>;
