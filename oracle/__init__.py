@@ -25,7 +25,7 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+            ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
              "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -53,6 +53,12 @@ def lib() -> ctypes.CDLL:
         L.mxo_e8m0_from_exponent.argtypes = [ci]
         L.mxo_quantize.restype = ci
         L.mxo_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
+        L.mxo_quantize_given_mbs.restype = ci
+        L.mxo_quantize_given_mbs.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        L.mxo_mbs_dynamic_cost.restype = ctypes.c_float
+        L.mxo_mbs_dynamic_cost.argtypes = [vp, ci, ci, ci, ci, ci, ci]
+        L.mxo_quantize_mbs_dynamic.restype = ci
+        L.mxo_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.mxo_dequantize.restype = ci
         L.mxo_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp]
         L.mxo_gemm_rows.restype = ci
@@ -117,6 +123,48 @@ def quantize(x_bf16: np.ndarray, rule="oas", mbs: bool = False, block: int = 32,
     if rc != 0:
         raise ValueError("mxo_quantize: bad arguments")
     return codes, scales, words
+
+
+def quantize_given_mbs(x_bf16: np.ndarray, words: np.ndarray, rule="oas", block: int = 32, macro: int = 128):
+    """Quantize with caller-chosen MBS words [rows, ceil(K/macro)]. Returns (codes, scales, words)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    words = np.ascontiguousarray(words, np.uint8)
+    assert words.shape == (rows, (K + macro - 1) // macro)
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    rc = lib().mxo_quantize_given_mbs(_ptr(x), rows, K, K, _rule(rule), block, macro, _ptr(words),
+                                      _ptr(codes), _ptr(scales))
+    if rc != 0:
+        raise ValueError("mxo_quantize_given_mbs: bad arguments")
+    return codes, scales, words
+
+
+# Default candidate list of MBS-Dynamic: 16 words equally spaced round the circle of factors,
+# starting at the static word (the paper fixes the count, 16, but not the list).
+DYNAMIC_DEFAULT = dict(cand_first=0, cand_count=16, cand_stride=16)
+
+
+def quantize_mbs_dynamic(x_bf16: np.ndarray, rule="oas", cand_first: int = 0, cand_count: int = 16,
+                         cand_stride: int = 16, block: int = 32, macro: int = 128):
+    """MBS-Dynamic: per macro block the candidate word of least cost. Returns (codes, scales, words)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    words = np.zeros((rows, (K + macro - 1) // macro), np.uint8)
+    rc = lib().mxo_quantize_mbs_dynamic(_ptr(x), rows, K, K, _rule(rule), block, macro, cand_first,
+                                        cand_count, cand_stride, _ptr(codes), _ptr(scales), _ptr(words))
+    if rc != 0:
+        raise ValueError("mxo_quantize_mbs_dynamic: bad arguments")
+    return codes, scales, words
+
+
+def mbs_dynamic_cost(xm_bf16: np.ndarray, m8: int, e128: int, rule="oas", block: int = 32,
+                     macro: int = 128) -> float:
+    """The binary32 cost MBS-Dynamic assigns to word m8 on one macro block (1-D bf16 bit patterns)."""
+    xm = np.ascontiguousarray(xm_bf16, dtype=np.uint16)
+    return float(lib().mxo_mbs_dynamic_cost(_ptr(xm), xm.size, int(m8), _rule(rule), block, macro, int(e128)))
 
 
 def dequantize(codes, scales, mbs=None, block: int = 32, macro: int = 128) -> np.ndarray:

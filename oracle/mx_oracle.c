@@ -1,6 +1,7 @@
 /*
  * mx_oracle.c -- CPU oracle for MXFP4 quantization with Overflow-Aware Scaling (OAS) and
- * static Macro Block Scaling (MBS-S), and for the block-scaled GEMM with the MBS correction.
+ * Macro Block Scaling (static, MBS-S, and searched, MBS-D), and for the block-scaled GEMM with the
+ * MBS correction.
  *
  * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, step-by-step restatement of what the
  * paper defines; only tests, the smoke check and the benchmark's cpu_baseline leg may call it.
@@ -12,7 +13,9 @@
  * Arithmetic: every real number is a C double.  bf16 inputs, the MBS factor (9 significant
  * bits), their product (17 bits) and any power-of-two multiple of it are exact in a double, so
  * codes, scales and MBS words are decided on exact values; there is no rounding anywhere before
- * the final "nearest E2M1 value" decision.  GEMM and QSNR sums are fp64.
+ * the final "nearest E2M1 value" decision.  GEMM and QSNR sums are fp64.  The one exception is the
+ * cost that MBS-Dynamic minimises: a minimum over rounded sums is reproducible only if the sums
+ * are, so that cost is defined in IEEE binary32 with a stated order of operations (see there).
  *
  * Conventions (paper silent; fixed here and used by the tests):
  *   - E2M1 code = sign<<3 | magnitude index into {0, .5, 1, 1.5, 2, 3, 4, 6}   (Sec. 2.2, 3.2)
@@ -126,16 +129,53 @@ int mxo_e8m0_from_exponent(int s) {
 
 static int is_finite_bf16(uint16_t h) { return (h & 0x7F80u) != 0x7F80u; }
 
+/* One macro block of one row, elements [k0, k1): multiply by F = 1 + m8/256, then quantize each
+ * sub-block with the chosen rule on its scaled absmax (Sec. 4.3.1; Sec. 5.3: "scale each alpha_i by
+ * (1+m8) to obtain ... SF_i").  A sub-block holding a non-finite value gets E = 255 and zero codes.
+ * cr / sr are the row's code and scale arrays. */
+static void quantize_macro_block(const uint16_t* xr, int64_t k0, int64_t k1, int m8, int rule,
+                                 int block, uint8_t* cr, uint8_t* sr) {
+    const double F = 1.0 + m8 / 256.0;
+    for (int64_t b0 = k0; b0 < k1; b0 += block) {
+        int finite = 1;
+        double amax = 0.0;
+        for (int64_t k = b0; k < b0 + block; ++k) {
+            if (!is_finite_bf16(xr[k])) finite = 0;
+            else amax = fmax(amax, fabs(mxo_bf16_value(xr[k]) * F));
+        }
+        int E, s;
+        if (!finite) { E = 255; s = 0; }
+        else if (amax == 0.0) { E = 127; s = 0; }
+        else { E = mxo_e8m0_from_exponent(mxo_scale_exponent(amax, rule)); s = 127 - E; }
+        sr[b0 / block] = (uint8_t)E;
+        for (int64_t k = b0; k < b0 + block; ++k) {
+            int code = 0;
+            if (finite) {
+                double t = ldexp(mxo_bf16_value(xr[k]) * F, s); /* x * F * SF, exact */
+                code = mxo_e2m1_nearest(fabs(t)) | ((xr[k] & 0x8000u) ? 8 : 0);
+            }
+            if (k & 1) cr[k / 2] = (uint8_t)((cr[k / 2] & 0x0F) | (code << 4));
+            else       cr[k / 2] = (uint8_t)code;
+        }
+    }
+}
+
+/* Absmax of the finite elements [k0, k1) of a row (Sec. 4.3.1: alpha_max^128). */
+static double macro_absmax(const uint16_t* xr, int64_t k0, int64_t k1) {
+    double a128 = 0.0;
+    for (int64_t k = k0; k < k1; ++k)
+        if (is_finite_bf16(xr[k])) a128 = fmax(a128, fabs(mxo_bf16_value(xr[k])));
+    return a128;
+}
+
 /* Quantize rows of bf16 along K.
  *   x      [rows, ldx] bf16 bit patterns, row-major, K <= ldx
  *   rule   MXO_RULE_*;  use_mbs 0/1;  block = elements per E8M0 scale (32; 16 = the paper's
  *   "MXFP4-16"); macro = elements per MBS word (128), a multiple of block
  *   codes  [rows, K/2]          scales [rows, K/block]       mbs [rows, ceil(K/macro)] (use_mbs)
- * Per macro block (Sec. 4.3.1): alpha128 = max of the sub-block absmaxes -> m8 -> F = 1+m8/256;
- * every element is multiplied by F; then each sub-block is quantized with the chosen rule on its
- * scaled absmax (Sec. 5.3: "scale each alpha_i by (1+m8) to obtain ... SF_i").  A last macro block
- * shorter than `macro` uses the elements that exist.  Non-finite input: the sub-block holding it
- * gets E = 255 and zero codes; the MBS word is taken from the finite elements of the macro block.
+ * Per macro block (Sec. 4.3.1): alpha128 = max of the sub-block absmaxes -> m8 (MBS-Static, Eq. 3),
+ * then quantize_macro_block.  A last macro block shorter than `macro` uses the elements that
+ * exist.  The MBS word is taken from the finite elements of the macro block.
  * Returns 0, or -1 on bad arguments. */
 int mxo_quantize(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
                  int block, int macro, uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
@@ -146,42 +186,140 @@ int mxo_quantize(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int ru
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
         const uint16_t* xr = x + r * ldx;
-        uint8_t* cr = codes + r * (K / 2);
-        uint8_t* sr = scales + r * nblk;
         for (int64_t g = 0; g < nmac; ++g) {
             const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
-            /* macro-block absmax over finite elements, MBS word and factor */
-            double F = 1.0;
+            int m8 = 0;
             if (use_mbs) {
-                double a128 = 0.0;
-                for (int64_t k = k0; k < k1; ++k)
-                    if (is_finite_bf16(xr[k])) a128 = fmax(a128, fabs(mxo_bf16_value(xr[k])));
-                int m8 = mxo_mbs_static_m8(a128);
+                m8 = mxo_mbs_static_m8(macro_absmax(xr, k0, k1));
                 mbs[r * nmac + g] = (uint8_t)m8;
-                F = 1.0 + m8 / 256.0;
             }
-            for (int64_t b0 = k0; b0 < k1; b0 += block) {
-                int finite = 1;
-                double amax = 0.0;
-                for (int64_t k = b0; k < b0 + block; ++k) {
-                    if (!is_finite_bf16(xr[k])) finite = 0;
-                    else amax = fmax(amax, fabs(mxo_bf16_value(xr[k]) * F));
-                }
-                int E, s;
-                if (!finite) { E = 255; s = 0; }
-                else if (amax == 0.0) { E = 127; s = 0; }
-                else { E = mxo_e8m0_from_exponent(mxo_scale_exponent(amax, rule)); s = 127 - E; }
-                sr[b0 / block] = (uint8_t)E;
-                for (int64_t k = b0; k < b0 + block; ++k) {
-                    int code = 0;
-                    if (finite) {
-                        double t = ldexp(mxo_bf16_value(xr[k]) * F, s); /* x * F * SF, exact */
-                        code = mxo_e2m1_nearest(fabs(t)) | ((xr[k] & 0x8000u) ? 8 : 0);
-                    }
-                    if (k & 1) cr[k / 2] = (uint8_t)((cr[k / 2] & 0x0F) | (code << 4));
-                    else       cr[k / 2] = (uint8_t)code;
+            quantize_macro_block(xr, k0, k1, m8, rule, block, codes + r * (K / 2), scales + r * nblk);
+        }
+    }
+    return 0;
+}
+
+/* The same with the MBS words given by the caller (mbs_in [rows, ceil(K/macro)]) instead of derived:
+ * what any choice of word means for codes and scales.  Used to examine candidate words. */
+int mxo_quantize_given_mbs(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
+                           int block, int macro, const uint8_t* mbs_in, uint8_t* codes,
+                           uint8_t* scales) {
+    if (rows < 0 || K < 0 || ldx < K || block <= 0 || (block & 1) || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            quantize_macro_block(x + r * ldx, k0, k1, mbs_in[r * nmac + g], rule, block,
+                                 codes + r * (K / 2), scales + r * nblk);
+        }
+    return 0;
+}
+
+/* ---- MBS-Dynamic (Sec. 4.3.1 "Dynamic", Sec. 5.3) ------------------------------------------- */
+
+/* The paper picks, out of 16 candidate words, the one with the smallest sum of squared errors of
+ * the 1x128 block, and evaluates that sum through a table of approximate squared relative errors.
+ * Neither the candidate list nor the table is given, so this build searches the candidates
+ *     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count-1
+ * (the factor 1 + m/256 is defined up to a power of two, which the local scales absorb, so the
+ * words form a circle), and evaluates the sum of squared errors itself rather than a table.
+ *
+ * A minimum over floating-point sums is only reproducible if the sums are: the cost below is
+ * therefore DEFINED in IEEE binary32 with a fixed order of operations, the same one the GPU kernel
+ * uses, and is not "the exact SSE" (the pin tests bound its distance from the exact SSE).
+ *
+ * cost(m), for a macro block whose absmax alpha128 has the biased exponent field e128:
+ *   F = 1 + m/256.  For each sub-block b: E_b, s_b as in quantize_macro_block; for each element
+ *   t = x F 2^s_b (exact), q = the E2M1 value it rounds to, r = t - q (exact);
+ *   the 8 elements of each aligned group of 8 accumulate r*r by fused multiply-add, in element
+ *   order, starting from 0; the groups of a sub-block are added pairwise ((g0+g1)+(g2+g3));
+ *   that sum is multiplied by 4^(E_b - e128) (exact), which expresses it in units of the macro
+ *   block's binade instead of the sub-block's; the sub-blocks are added pairwise in the same way
+ *   (a missing sub-block of a short last macro block is 0); the total is divided by F*F (exact
+ *   product, one correctly rounded division).  Errors were measured on x F, hence the division.
+ *   A sub-block whose own absmax lies more than 30 binades below alpha128 (exponent field below
+ *   e128 - 30), or is zero, contributes 0.
+ * The search runs only where binary32 holds every intermediate exactly: e128 in [64, 249] and no
+ * non-finite element in the macro block.  Elsewhere the static word is kept.
+ * The static word is the incumbent; candidates are scanned in the order j = 0, 1, ... and one
+ * replaces the current choice only with a strictly smaller cost. */
+
+static float pairwise_sum(const float* v, int n) { /* n a power of two */
+    if (n == 1) return v[0];
+    return pairwise_sum(v, n / 2) + pairwise_sum(v + n / 2, n / 2);
+}
+
+static int exponent_field_bf16(double a) { /* floor(log2 a) + 127: the biased exponent field of a normal a */
+    int ex;
+    frexp(a, &ex);
+    return ex - 1 + 127;
+}
+
+/* cost of word m8 for the macro block xm[0..n), n a multiple of block, block a multiple of 8 with
+ * block/8 and macro/block powers of two; all elements finite, e128 as described above. */
+float mxo_mbs_dynamic_cost(const uint16_t* xm, int n, int m8, int rule, int block, int macro,
+                           int e128) {
+    const float F = 1.0f + (float)m8 / 256.0f;
+    float sub[64] = {0};
+    for (int b = 0; b * block < n; ++b) {
+        const uint16_t* xb = xm + b * block;
+        double amax0 = 0.0; /* unscaled absmax of the sub-block */
+        for (int k = 0; k < block; ++k) amax0 = fmax(amax0, fabs(mxo_bf16_value(xb[k])));
+        if (amax0 == 0.0 || exponent_field_bf16(amax0) < e128 - 30) continue;
+        const int E = mxo_e8m0_from_exponent(mxo_scale_exponent(amax0 * (double)F, rule));
+        const int s = 127 - E;
+        float grp[16];
+        for (int g = 0; g < block / 8; ++g) {
+            float acc = 0.0f;
+            for (int k = 8 * g; k < 8 * g + 8; ++k) {
+                const float t = ldexpf((float)mxo_bf16_value(xb[k]) * F, s);
+                float q = (float)E2M1_VALUE[mxo_e2m1_nearest(fabs((double)t))];
+                if (xb[k] & 0x8000u) q = -q;
+                const float r = t - q;
+                acc = fmaf(r, r, acc);
+            }
+            grp[g] = acc;
+        }
+        sub[b] = ldexpf(pairwise_sum(grp, block / 8), 2 * (E - e128));
+    }
+    return pairwise_sum(sub, macro / block) / (F * F);
+}
+
+/* Quantize with MBS-Dynamic words.  Arguments as mxo_quantize plus the candidate list; block must
+ * be 8, 16, 32 or 64 and macro/block a power of two (at most 64).  Returns 0 or -1. */
+int mxo_quantize_mbs_dynamic(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
+                             int block, int macro, int cand_first, int cand_count, int cand_stride,
+                             uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
+    if (rows < 0 || K < 0 || ldx < K || K % block || macro % block) return -1;
+    if (block != 8 && block != 16 && block != 32 && block != 64) return -1;
+    const int nsub = macro / block;
+    if (nsub < 1 || nsub > 64 || (nsub & (nsub - 1))) return -1;
+    if (rule < 0 || rule > 2 || cand_count < 0 || cand_count > 256) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * ldx;
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            const double a128 = macro_absmax(xr, k0, k1);
+            const int m_static = mxo_mbs_static_m8(a128);
+            int finite = 1;
+            for (int64_t k = k0; k < k1; ++k) finite &= is_finite_bf16(xr[k]);
+            int best = m_static;
+            if (finite && a128 >= ldexp(1.0, 64 - 127) && a128 < ldexp(1.0, 250 - 127)) {
+                const int e128 = exponent_field_bf16(a128);
+                float best_cost = mxo_mbs_dynamic_cost(xr + k0, (int)(k1 - k0), m_static, rule, block, macro, e128);
+                for (int j = 0; j < cand_count; ++j) {
+                    const int m = (int)(((int64_t)m_static + (int64_t)(cand_first + j) * cand_stride) & 255);
+                    const float c = mxo_mbs_dynamic_cost(xr + k0, (int)(k1 - k0), m, rule, block, macro, e128);
+                    if (c < best_cost) { best_cost = c; best = m; }
                 }
             }
+            mbs[r * nmac + g] = (uint8_t)best;
+            quantize_macro_block(xr, k0, k1, best, rule, block, codes + r * (K / 2), scales + r * nblk);
         }
     }
     return 0;

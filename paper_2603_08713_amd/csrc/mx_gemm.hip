@@ -182,10 +182,13 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
         m8_off[i] = m8_pad[i] ? kOob : row * nmac + (kM8Quad ? 0 : p & 1);
     }
 
+    // The loop requests up to three stages past the last one so that every wavefront's load count stays
+    // fixed; those requests are sent out of range (they read zero and touch no memory).
+    const int nstages = (K + kStageK - 1) / kStageK;
     auto dma_scale = [&](int s, auto i_) {  // load i of the E8M0 bytes of stage s
         constexpr int i = decltype(i_)::value;
         uint8_t* base = smem + L::kScaleBase + (s % kScaleBufs) * L::kScaleStage;
-        int voff = scale_off[i];
+        int voff = s < nstages ? scale_off[i] : kOob;
         // past the end of K the block does not exist: read zero (2^-127), never a stray NaN scale
         if (kRaggedK && (kScaleDword ? (s * kStageMacros + scale_sub[i]) * kMacro : (s * 8 + scale_sub[i]) * kBlock) >= K)
             voff = kOob;
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     auto dma_code = [&](int s, auto i_) {  // load i of the codes of stage s
         constexpr int i = decltype(i_)::value;
         uint8_t* base = smem + (s % kCodeBufs) * L::kCodesStage;
-        int voff = code_off[i];
+        int voff = s < nstages ? code_off[i] : kOob;
         if (kRaggedK && s * kStageK + code_chunk[i] * kBlock >= K) voff = kOob;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 8 < TM ? opa.codes : opb.codes,
                                                  (lds_ptr_t)(base + (i * NW + w) * 1024), 16, voff, s * kRowStage, 0, 0);
@@ -212,11 +215,11 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
                 const bool real = (s & 1) == 0 && !m8_pad[i];
                 uint8_t* dst = real ? smem + L::kM8Base + ((s >> 1) & 1) * L::kM8Stage + (i * NW + w) * 256 : smem + L::kDummy;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(m8_is_a[i] ? opa.mbs : opb.mbs, (lds_ptr_t)dst, 4,
-                                                         (s & 1) == 0 ? m8_off[i] : kOob, s * kStageMacros, 0, 0);
+                                                         (s & 1) == 0 && s < nstages ? m8_off[i] : kOob, s * kStageMacros, 0, 0);
             } else {
                 uint8_t* dst = m8_pad[i] ? smem + L::kDummy : smem + L::kM8Base + (s % 3) * L::kM8Stage + (i * NW + w) * 256;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(m8_is_a[i] ? opa.mbs : opb.mbs, (lds_ptr_t)dst, 1, m8_off[i],
-                                                         s * kStageMacros, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(m8_is_a[i] ? opa.mbs : opb.mbs, (lds_ptr_t)dst, 1,
+                                                         s < nstages ? m8_off[i] : kOob, s * kStageMacros, 0, 0);
             }
         }
     };
@@ -366,7 +369,6 @@ __global__ __launch_bounds__(S::NT, 2) void gemm_kernel(GemmArgs g) {
     using C1 = std::integral_constant<int, 1>;
 
     // ---- prologue: stages 0 and 1 (and the MBS words of stage 2) -------------------------------------
-    const int nstages = (K + kStageK - 1) / kStageK;
     if (nstages > 0) {
         static_for<kCodeDma>([&](auto i_) { dma_code(0, i_); });
         dma_scales(0);
