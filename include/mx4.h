@@ -75,6 +75,20 @@ int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx,
 int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                     uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
+/* MBS-Dynamic quantization (Sec. 4.3.1 "Dynamic", Sec. 5.3; meant for weights, which are quantized
+ * offline: MBS-Hybrid = this for B, mx_quantize_mbs for A): as mx_quantize_mbs, but the word of each
+ * window is searched for the least sum of squared errors of the window among the static word and
+ *     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,   j = 0 .. cand_count-1
+ * (the paper searches 16 candidates and does not list them; cand_first 0, cand_count 16,
+ * cand_stride 16 spaces them equally over all factors).  0 <= cand_count <= 256, |cand_first| and
+ * |cand_stride| <= 65536, else MX_EINVAL.  The sum of squared errors is evaluated in fp32 in a fixed
+ * order of operations, so the result is deterministic; ties keep the static word, then the lowest j.
+ * Windows holding Inf/NaN, and windows whose absmax is below 2^-63 or at least 2^123, keep the static
+ * word.  Outputs as mx_quantize_mbs; mx_gemm_mbs consumes them unchanged. */
+int mx_quantize_mbs_dynamic(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                            int32_t cand_first, int32_t cand_count, int32_t cand_stride,
+                            uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
 /* Reconstruct x_hat = value(code) * 2^(E-127) / F (Sec. 4.3.1) into out [rows, ldo] of
  * `out_dtype` (fp32: correctly rounded; bf16: that fp32 value rounded to nearest even).
  * mbs_or_null == NULL means F = 1.  E = 255 gives NaN. */

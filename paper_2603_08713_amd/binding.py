@@ -42,6 +42,9 @@ def load_library() -> ctypes.CDLL:
     L.mx_quantize_oas.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.mx_quantize_mbs.restype = ci
     L.mx_quantize_mbs.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp]
+    L.mx_quantize_mbs_dynamic.restype = ci
+    L.mx_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          vp, vp, vp, vp]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, vp, i64, vp]
     L.mx_gemm.restype = ci
@@ -155,6 +158,17 @@ def mx_quantize_mbs(x, rule="oas", codes=None, scales=None, mbs=None):
     codes, scales, mbs = _alloc_outputs(x, rows, K, codes, scales, mbs, True)
     _check(load_library().mx_quantize_mbs(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
                                           _ptr(mbs), _stream()), "mx_quantize_mbs")
+    return codes, scales, mbs
+
+
+def mx_quantize_mbs_dynamic(x, rule="oas", cand_first=0, cand_count=16, cand_stride=16, codes=None, scales=None,
+                            mbs=None):
+    """MBS-Dynamic quantization (searched word per 1x128 window) -> (codes, scales, mbs)."""
+    rows, K, ldx = _rows_ld(x)
+    codes, scales, mbs = _alloc_outputs(x, rows, K, codes, scales, mbs, True)
+    _check(load_library().mx_quantize_mbs_dynamic(_ptr(x), rows, K, ldx, _rule(rule), int(cand_first),
+                                                  int(cand_count), int(cand_stride), _ptr(codes), _ptr(scales),
+                                                  _ptr(mbs), _stream()), "mx_quantize_mbs_dynamic")
     return codes, scales, mbs
 
 

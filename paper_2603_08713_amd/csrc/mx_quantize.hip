@@ -80,7 +80,8 @@ struct ChunkResult {
 };
 
 // All-integer path, exact for every bf16 input including subnormals, huge values and Inf/NaN.
-__device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int use_mbs) {
+// m8_given >= 0 replaces the static word (the searched word of MBS-Dynamic).
+__device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int use_mbs, int m8_given = -1) {
     uint32_t h[8] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16,
                      v.z & 0xFFFFu, v.z >> 16, v.w & 0xFFFFu, v.w >> 16};
     uint32_t amax = 0, nf = 0;
@@ -103,6 +104,7 @@ __device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int 
         if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;  // normalise a subnormal absmax
         m8 = mbs_word_of_mantissa(k);
     }
+    if (m8_given >= 0) m8 = (uint32_t)m8_given;
     const uint32_t u = 256u + m8;  // F = u / 256
 
     int E;
@@ -251,18 +253,169 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
     }
 }
 
+// ---- MBS-Dynamic (Sec. 4.3.1 "Dynamic", Sec. 5.3) ----------------------------------------------------
+// Per macro block the word is searched among the candidates
+//     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count - 1,
+// for the least sum of squared errors of the 1x128 block.  The paper reads squared relative errors from a
+// table; here the error is measured directly: the hardware converts the scaled pair to E2M1 and back, the
+// difference is exact in fp32, and its squares are accumulated.  So that the minimum is reproducible the
+// cost has a fixed order of operations: fused multiply-adds over the lane's 8 elements in order, pairwise
+// sums over the 4 lanes of a block, an exact rescale from the block's binade to the macro block's,
+// pairwise sums over the 4 blocks, one correctly rounded division by F^2.  The static word is the
+// incumbent; a candidate replaces the current choice only with a strictly smaller cost.  The search runs
+// where fp32 holds every intermediate exactly (exponent field of the macro-block absmax in [64, 249], no
+// Inf/NaN in it); a block whose own absmax is zero or more than 30 binades below contributes nothing.
+struct DynArgs {
+    QuantArgs q;
+    int cand_first, cand_count, cand_stride;
+};
+
+__device__ __forceinline__ float dpp_quad_xor1_f(float v) { return __uint_as_float(dpp_quad_xor1(__float_as_uint(v))); }
+__device__ __forceinline__ float dpp_quad_xor2_f(float v) { return __uint_as_float(dpp_quad_xor2(__float_as_uint(v))); }
+// lane i <-> 7 - i inside each half row, lane i <-> 15 - i inside each row: on values that are uniform
+// over aligned groups of 4 (resp. 8) lanes these exchange neighbouring groups
+__device__ __forceinline__ float dpp_half_mirror_f(float v) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x141, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_mirror_f(float v) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x140, 0xF, 0xF, true));
+}
+
+struct Candidate {
+    uint32_t codes, E;
+    float cost;
+};
+
+// Codes, scale byte and macro-block cost of word m.  xf: the lane's 8 elements; amax: bf16 magnitude bits
+// of the block's absmax; counts: the block contributes to the cost; e128: exponent field of the macro
+// block's absmax.  The cost is uniform over the 16 lanes of the macro block.
+__device__ __forceinline__ Candidate eval_candidate(const float (&xf)[8], uint32_t amax, bool counts, uint32_t e128,
+                                                    uint32_t m, uint32_t carry) {
+#pragma clang fp contract(off)
+    const float F = __uint_as_float(0x3F800000u | (m << 15));
+    const float scaled_max = __uint_as_float(amax << 16) * F;  // exact
+    uint32_t E = ((__float_as_uint(scaled_max) + carry) >> 23) - 2u;
+    E = amax ? E : 127u;
+    const float mult = __uint_as_float(((254u - E) << 23) | (m << 15));  // F * 2^(127 - E)
+    uint32_t codes = 0;
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float t0 = xf[2 * i] * mult, t1 = xf[2 * i + 1] * mult;  // exact
+        typedef float v2f __attribute__((ext_vector_type(2)));
+        v2f q;
+        if (i == 0) { codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 0); q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0); }
+        if (i == 1) { codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 1); q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1); }
+        if (i == 2) { codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 2); q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2); }
+        if (i == 3) { codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, t0, t1, 1.0f, 3); q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3); }
+        const float r0 = t0 - q.x, r1 = t1 - q.y;  // exact: the grid value is within a factor 2 of t, or t is tiny
+        acc = __builtin_fmaf(r0, r0, acc);
+        acc = __builtin_fmaf(r1, r1, acc);
+    }
+    // block sum, then from units of the block's binade to units of the macro block's: 4^(E - e128)
+    acc = counts ? acc : 0.0f;
+    acc = acc + dpp_quad_xor1_f(acc);
+    acc = acc + dpp_quad_xor2_f(acc);
+    const float rescale = __uint_as_float(counts ? (127u + 2u * (E - e128)) << 23 : 0x3F800000u);
+    acc = acc * rescale;
+    acc = acc + dpp_half_mirror_f(acc);
+    acc = acc + dpp_mirror_f(acc);
+    return {codes, E, acc / (F * F)};
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
+    const QuantArgs& q = d.q;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kThreads / kWave);
+    for (uint32_t c = wave; c < q.total_chunks; c += nwaves) {
+        const uint32_t row = c / q.chunks_per_row, col = (c - row * q.chunks_per_row) * kChunk + lane * 8;
+        const bool valid = col < q.K;
+        u32x4 v = {0, 0, 0, 0};
+        if (valid) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q.x + (int64_t)row * q.ldx + col));
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+
+        // absmax over the finite elements of the lane, block and macro block; Inf/NaN flag of the macro block
+        uint32_t amax = 0, nf = 0;
+        float xf[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+            if (lo >= 0x7F80u) nf = 1; else amax = max(amax, lo);
+            if (hi >= 0x7F80u) nf = 1; else amax = max(amax, hi);
+            xf[2 * i] = __uint_as_float(w[i] << 16);
+            xf[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+        nf |= dpp_quad_xor1(nf);
+        nf |= dpp_quad_xor2(nf);
+        const uint32_t nf_block = nf;
+        nf |= dpp_row_ror4(nf);
+        nf |= dpp_row_ror8(nf);
+        amax = max(amax, dpp_quad_xor1(amax));
+        amax = max(amax, dpp_quad_xor2(amax));
+        uint32_t mmax = max(amax, dpp_row_ror4(amax));
+        mmax = max(mmax, dpp_row_ror8(mmax));
+
+        // static word (Eq. 3) from the mantissa of the absmax, a subnormal absmax normalised first
+        uint32_t m_static = 0;
+        if (mmax) {
+            uint32_t k = mmax & 0x7Fu;
+            if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;
+            m_static = mbs_word_of_mantissa(k);
+        }
+        const uint32_t e128 = mmax >> 7;
+        const bool searchable = !nf && e128 >= 64u && e128 <= 249u;
+        const bool counts = amax != 0 && (amax >> 7) + 30u >= e128;
+
+        Candidate best = eval_candidate(xf, amax, counts, e128, m_static, q.carry);
+        uint32_t m_best = m_static;
+        for (int j = 0; j < d.cand_count; ++j) {
+            uint32_t m = (m_static + (uint32_t)((d.cand_first + j) * d.cand_stride)) & 255u;
+            m = searchable ? m : m_static;
+            const Candidate cand = eval_candidate(xf, amax, counts, e128, m, q.carry);
+            if (cand.cost < best.cost) {
+                best = cand;
+                m_best = m;
+            }
+        }
+
+        // the fp32 route gave valid codes unless some block of this wavefront lies outside its range
+        // (Inf/NaN, or an absmax exponent field outside [24, 249]); then the all-integer path redoes the
+        // chunk with the chosen word
+        const bool odd = nf_block || (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
+        ChunkResult res = {best.codes, best.E, m_best};
+        if (__builtin_amdgcn_ballot_w64(odd) != 0) res = quantize_chunk_exact(v, q.rule, 1, (int)m_best);
+
+        uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
+        if ((lane & 3) != 0) ew = 0;
+        ew |= dpp_row_ror4(ew);
+        ew |= dpp_row_ror8(ew);
+        if (!valid) continue;
+        const uint32_t kblk = col >> 5;
+        uint8_t* srow = q.scales + (int64_t)row * (q.K >> 5);
+        uint8_t* crow = q.codes + (int64_t)row * (q.K >> 1);
+        *reinterpret_cast<uint32_t*>(crow + (col >> 1)) = res.codes;
+        if (q.scales_dword) {
+            if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
+        } else if ((lane & 3) == 0) {
+            srow[kblk] = (uint8_t)res.E;
+        }
+        if ((lane & 15) == 0) q.mbs[(int64_t)row * q.nmac + (col >> 7)] = (uint8_t)res.m8;
+    }
+}
+
 int g_quant_hwcvt = 1;
 
-int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
-                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+// argument checks and the fields common to both quantizer kernels; MX_OK with *empty set means nothing to do
+int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
+    *empty = true;
     if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
     if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
     if (rows == 0 || K == 0) return MX_OK;
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
     if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 16)) return MX_EALIGN;
     if (int st = check_device()) return st;
-
-    QuantArgs q;
     q.x = static_cast<const uint16_t*>(x);
     q.codes = codes;
     q.scales = scales;
@@ -278,6 +431,16 @@ int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rul
     q.use_mbs = use_mbs;
     q.carry = rule == MX_RULE_FLOOR ? 0x3FFFFFu : rule == MX_RULE_OAS ? 0x1FFFFFu : 0u;
     q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
+    *empty = false;
+    return MX_OK;
+}
+
+int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    QuantArgs q;
+    bool empty;
+    if (int st = fill_quant_args(q, &empty, x, rows, K, ldx, rule, use_mbs, codes, scales, mbs)) return st;
+    if (empty) return MX_OK;
 
     const int64_t waves_needed = ((int64_t)q.total_chunks + kUnroll - 1) / kUnroll;
     int64_t blocks = (waves_needed + (kThreads / kWave) - 1) / (kThreads / kWave);
@@ -294,6 +457,28 @@ int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rul
         if (use_mbs) hipLaunchKernelGGL((quantize_kernel<false, true>), grid, block, 0, s, q);
         else hipLaunchKernelGGL((quantize_kernel<false, false>), grid, block, 0, s, q);
     }
+    return launch_status();
+}
+
+int launch_quantize_dynamic(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int cand_first,
+                            int cand_count, int cand_stride, uint8_t* codes, uint8_t* scales, uint8_t* mbs,
+                            void* stream) {
+    constexpr int kCandLimit = 1 << 16;  // keeps (cand_first + j) * cand_stride inside 32 bits
+    if (cand_count < 0 || cand_count > 256 || cand_first < -kCandLimit || cand_first > kCandLimit ||
+        cand_stride < -kCandLimit || cand_stride > kCandLimit)
+        return MX_EINVAL;
+    DynArgs d;
+    bool empty;
+    if (int st = fill_quant_args(d.q, &empty, x, rows, K, ldx, rule, 1, codes, scales, mbs)) return st;
+    if (empty) return MX_OK;
+    d.cand_first = cand_first;
+    d.cand_count = cand_count;
+    d.cand_stride = cand_stride;
+    // one chunk per wavefront and step: the kernel is bound by arithmetic, not by loads in flight
+    int64_t blocks = ((int64_t)d.q.total_chunks + (kThreads / kWave) - 1) / (kThreads / kWave);
+    const int64_t max_blocks = 1 << 20;
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL(quantize_dynamic_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), d);
     return launch_status();
 }
 
@@ -315,6 +500,13 @@ int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, ui
 int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                     uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
     return mx::launch_quantize(x_bf16, rows, K, ldx, (int)rule, 1, codes, scales, mbs, stream);
+}
+
+int mx_quantize_mbs_dynamic(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                            int32_t cand_first, int32_t cand_count, int32_t cand_stride, uint8_t* codes,
+                            uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize_dynamic(x_bf16, rows, K, ldx, (int)rule, cand_first, cand_count, cand_stride, codes,
+                                       scales, mbs, stream);
 }
 
 // Development switch (not part of the public ABI): 1 = hardware fp32->E2M1 convert instruction,

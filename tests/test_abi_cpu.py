@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
-    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
+    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
             "mx_gemm_mbs_grouped", "mx_status_string", "mx_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -63,6 +63,14 @@ def test_quantize_argument_errors(lib):
     assert lib.mx_quantize_oas(A16, 4, 40, 40, A16, A16, None) == -1
     assert lib.mx_quantize_mbs(A16, 4, 64, 64, 2, A16, A16, None, None) == -2   # mbs required
     assert lib.mx_quantize_mbs(A16, 0, 64, 64, 2, A16, A16, None, None) == 0
+    d = lib.mx_quantize_mbs_dynamic
+    assert d(A16, 4, 64, 64, 2, 0, 257, 16, A16, A16, A16, None) == -1          # too many candidates
+    assert d(A16, 4, 64, 64, 2, 0, -1, 16, A16, A16, A16, None) == -1
+    assert d(A16, 4, 64, 64, 2, 1 << 20, 16, 16, A16, A16, A16, None) == -1     # offsets out of range
+    assert d(A16, 4, 64, 64, 2, 0, 16, -(1 << 20), A16, A16, A16, None) == -1
+    assert d(A16, 4, 48, 48, 2, 0, 16, 16, A16, A16, A16, None) == -1           # K % 32
+    assert d(A16, 4, 64, 64, 2, 0, 16, 16, A16, A16, None, None) == -2          # mbs required
+    assert d(A16, 0, 64, 64, 2, 0, 16, 16, A16, A16, A16, None) == 0
 
 
 def test_dequantize_argument_errors(lib):

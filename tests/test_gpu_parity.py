@@ -147,6 +147,99 @@ def test_quantize_full_size_activation(mx, oracle):
 
 
 # ------------------------------------------------------------------------------------------------
+# MBS-Dynamic quantizer (searched word)
+# ------------------------------------------------------------------------------------------------
+def assert_dynamic_equal(mx, oracle, bits, rule="oas", what="", oracle_rows=None, **cands):
+    """GPU on all rows; oracle on all rows or on the listed ones (rows are independent)."""
+    c, s, w = mx.mx_quantize_mbs_dynamic(dev_bf16(bits), rule, **cands)
+    torch.cuda.synchronize()
+    sel = slice(None) if oracle_rows is None else oracle_rows
+    oc, os_, ow = oracle.quantize_mbs_dynamic(bits[sel], rule, **cands)
+    tag = "%s rule=%s %s" % (what, rule, cands)
+    for name, got, want in (("MBS words", host(w)[sel], ow), ("scales", host(s)[sel], os_), ("code bytes", host(c)[sel], oc)):
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, "%s: %d %s differ, first at %s gpu=%s oracle=%s" % (
+            tag, len(bad), name, bad[:3], got[tuple(bad[0])], want[tuple(bad[0])])
+    return ow
+
+
+@pytest.mark.parametrize("cands", [dict(), dict(cand_first=-8, cand_count=16, cand_stride=1),
+                                   dict(cand_first=-100, cand_count=256, cand_stride=3), dict(cand_count=0),
+                                   dict(cand_first=5, cand_count=7, cand_stride=-21)])
+def test_quantize_dynamic_small(mx, oracle, cands):
+    from paper_2603_08713_amd import synth
+
+    a, w = synth.tiny(0)
+    moved = 0
+    for rule in RULES:
+        for name, bits in (("tiny A", a), ("tiny W", w), ("t(3) outliers", synth.activations_student_t(37, 1024 + 64, 3.0, 0.01, 50.0, 9))):
+            words = assert_dynamic_equal(mx, oracle, bits, rule, name, **cands)
+            moved += int((words != oracle.quantize(bits, rule, mbs=True)[2]).sum())
+    assert (moved > 0) == (cands.get("cand_count", 16) > 0)   # the search is really exercised
+
+
+def test_quantize_dynamic_edge_cases(mx, oracle):
+    """Every bf16 pattern (natural order and shuffled: Inf/NaN, subnormals, huge values: windows outside
+    the search's domain keep the static word), ties, zero rows, blocks far below their window's absmax,
+    and values on the grid beside tiny ones (squared errors in the subnormal range)."""
+    rng = np.random.default_rng(21)
+    allbits = np.arange(65536, dtype=np.uint16).reshape(128, 512)
+    finite = allbits.reshape(-1)[(allbits.reshape(-1) & 0x7F80) != 0x7F80]
+    cases = {
+        "natural": allbits,
+        "shuffled-all": rng.permutation(allbits.reshape(-1)).reshape(128, 512),
+        "shuffled-finite": rng.choice(finite, size=(64, 640)),
+        "zeros": np.zeros((3, 256), np.uint16),
+    }
+    spread = np.random.default_rng(22).standard_normal((48, 512)).astype(np.float32)
+    for r in range(48):
+        spread[r, 32:64] *= np.float32(2.0) ** -(r + 2)        # one block 2..49 binades down
+        spread[r, 200:210] *= np.float32(2.0) ** -(2 * r)      # single tiny elements
+    cases["spread"] = (spread.view(np.uint32) >> 16).astype(np.uint16)
+    grid = np.array([0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, 0.0], np.float32)
+    g = rng.choice(grid, size=(40, 256)) * np.float32(2.0) ** rng.integers(-3, 4, size=(40, 1)).astype(np.float32)
+    g[:, 0] = 6.0 * g[:, 1].clip(min=1.0)
+    for r in range(40):
+        g[r, 17::29] = np.float32(2.0) ** -(60 + r)             # tiny, beside exactly representable values
+    cases["grid+tiny"] = (g.view(np.uint32) >> 16).astype(np.uint16)
+    for name, bits in cases.items():
+        for rule in RULES:
+            assert_dynamic_equal(mx, oracle, bits, rule, name)
+        assert_dynamic_equal(mx, oracle, bits, "oas", name, cand_first=-128, cand_count=256, cand_stride=1)
+
+
+@pytest.mark.parametrize("rows,K,ld", [(1, 32, 32), (3, 96, 104), (5, 2880, 2880), (2, 4096 + 64, 4232), (130, 160, 160)])
+def test_quantize_dynamic_ragged_shapes(mx, oracle, rows, K, ld):
+    from paper_2603_08713_amd import synth
+
+    full = synth.gaussian(rows, ld, 0.02, rows * 7 + K)
+    x = dev_bf16(full)[:, :K]
+    c, s, w = mx.mx_quantize_mbs_dynamic(x, "oas")
+    torch.cuda.synchronize()
+    oc, os_, ow = oracle.quantize_mbs_dynamic(np.ascontiguousarray(full[:, :K]), "oas")
+    assert np.array_equal(host(w), ow) and np.array_equal(host(s), os_) and np.array_equal(host(c), oc)
+
+
+def test_quantize_dynamic_full_size_weights_sampled_rows(mx, oracle):
+    """The Llama-3-8B FFN up-projection weight (14336 x 4096), every row on the GPU, 512 seeded rows
+    on the oracle; and the hybrid GEMM (searched words for W, static for A) on sampled rows."""
+    from paper_2603_08713_amd import synth
+
+    a_bits, w_bits = synth.llama8b_ffn_up()
+    rows = np.sort(np.random.default_rng(31).choice(w_bits.shape[0], 512, replace=False))
+    rows[0], rows[-1] = 0, w_bits.shape[0] - 1
+    assert_dynamic_equal(mx, oracle, w_bits, "oas", "L3-8B W", oracle_rows=rows)
+    wq = mx.mx_quantize_mbs_dynamic(dev_bf16(w_bits), "oas")
+    aq = mx.mx_quantize_mbs(dev_bf16(a_bits), "oas")
+    C = mx.mx_gemm_mbs(*aq, *wq, out_dtype="f32")
+    torch.cuda.synchronize()
+    pick = np.sort(np.random.default_rng(32).choice(a_bits.shape[0], 8, replace=False))
+    want = oracle.gemm(oracle.quantize(a_bits[pick], "oas", mbs=True), tuple(host(t) for t in wq))
+    got = host(C)[pick]
+    assert np.abs(got - want).max() <= GEMM_TOL * np.sqrt(np.mean(want ** 2))
+
+
+# ------------------------------------------------------------------------------------------------
 # dequantizer and QSNR from both paths
 # ------------------------------------------------------------------------------------------------
 def test_dequantize_matches_oracle(mx, oracle):
