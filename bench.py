@@ -142,6 +142,7 @@ def main():
     if not args.no_extras:
         out["extras"] = extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args)
         out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
+        out["extras"]["qsnr_db_gpu_weights"] = qsnr_weights_gpu(mx, torch, xw[0][:QSNR_ROWS])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, a_bits, w_bits, flops, metrics)
     print(json.dumps(out))
@@ -161,6 +162,19 @@ def qsnr_ladder_gpu(mx, torch, x):
         back = mx.mx_dequantize(q[0], q[1], q[2] if mbs else None, "f32").to(torch.float64)
         res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
     res["sample"] = "first %d rows of A" % QSNR_ROWS
+    return res
+
+
+def qsnr_weights_gpu(mx, torch, x):
+    """QSNR (dB) of the weight tensor with OAS alone, with the static MBS word and with the searched one
+    (MBS-Dynamic, the weight half of the paper's MBS-Hybrid, Sec. 4.3.1 and 4.4), through the HIP kernels."""
+    res = {}
+    ref = x.to(torch.float64)
+    for name, q in (("+oas", mx.mx_quantize(x, "oas") + (None,)), ("+oas+mbs-s", mx.mx_quantize_mbs(x, "oas")),
+                    ("+oas+mbs-d", mx.mx_quantize_mbs_dynamic(x, "oas"))):
+        back = mx.mx_dequantize(q[0], q[1], q[2], "f32").to(torch.float64)
+        res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
+    res["sample"] = "first %d rows of W" % QSNR_ROWS
     return res
 
 
@@ -205,6 +219,16 @@ def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):
     # plain-rule quantizer and dequantizer throughput (algorithmic bytes)
     ms_q = time_loop(torch, lambda i: mx.mx_quantize(xw[i % len(xw)], "ocp", pw[0], pw[1]), n)
     res["quantize_plain_W_gbps"] = round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_PLAIN / (ms_q * 1e-3) / 1e9, 1)
+    # MBS-Dynamic (offline weight quantization: 17 evaluations of the window instead of one)
+    ms_s = time_loop(torch, lambda i: mx.mx_quantize_mbs(xw[i % len(xw)], "oas", *qw[i % len(qw)]), n)
+    ms_dyn = time_loop(torch, lambda i: mx.mx_quantize_mbs_dynamic(xw[i % len(xw)], "oas", 0, 16, 16, *qw[i % len(qw)]), n)
+    res["quantize_dynamic_W"] = {"ms": round(ms_dyn, 4), "static_ms": round(ms_s, 4), "slowdown_vs_static": round(ms_dyn / ms_s, 2),
+                                 "gbps": round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_MBS / (ms_dyn * 1e-3) / 1e9, 1),
+                                 "candidates": "static word + 16 equally spaced",
+                                 "paper_context": "paper reports its MBS-D kernel 2.5-3x slower than MBS-S (NVIDIA B200)"}
+    # the timing loop above rewrote qw with searched words: put the static ones back for what follows
+    for i in range(len(qw)):
+        mx.mx_quantize_mbs(xw[i % len(xw)], "oas", *qw[i])
     deq = torch.empty((xw[0].shape[0], xw[0].shape[1]), dtype=torch.bfloat16, device=xw[0].device)
     ms_d = time_loop(torch, lambda i: mx.mx_dequantize(qw[i % len(qw)][0], qw[i % len(qw)][1], qw[i % len(qw)][2],
                                                        "bf16", out=deq), n)
@@ -236,8 +260,15 @@ def cpu_baseline(np, a_bits, w_bits, flops, metrics):
     for name, rule, mbs in QSNR_LADDER:
         q = oracle.quantize(x, rule, mbs=mbs)
         ladder[name] = round(oracle.qsnr_db(ref, oracle.dequantize(q[0], q[1], q[2])), 3)
+    xw = w_bits[:QSNR_ROWS]
+    refw = oracle.bf16_to_f64(xw)
+    ladder_w = {}
+    for name, q in (("+oas", oracle.quantize(xw, "oas")), ("+oas+mbs-s", oracle.quantize(xw, "oas", mbs=True)),
+                    ("+oas+mbs-d", oracle.quantize_mbs_dynamic(xw, "oas"))):
+        ladder_w[name] = round(oracle.qsnr_db(refw, oracle.dequantize(q[0], q[1], q[2])), 3)
     return {
         "qsnr_db_oracle": ladder,
+        "qsnr_db_oracle_weights": ladder_w,
         "value": round(flops / est_step_s / 1e12, 6),
         "unit": "TFLOP/s",
         "cores": threads,
