@@ -41,7 +41,7 @@ extern "C" {
 #define MX_EINVAL (-1)        /* negative size, K % 32 != 0, ld < K (or < N), bad enum value      */
 #define MX_ENULL (-2)         /* a required pointer is NULL                                       */
 #define MX_EALIGN (-3)        /* pointer or leading dimension violates the alignment above        */
-#define MX_EUNSUPPORTED (-4)  /* no HIP device, or the current device is not gfx950                */
+#define MX_EUNSUPPORTED (-4)  /* no HIP device, device is not gfx950, or a shape the entry point does not cover */
 #define MX_ELAUNCH (-5)       /* the HIP runtime rejected the launch                              */
 
 /* Rule that picks the power-of-two scale of a 32-element block from its absmax (Sec. 4.2). */
@@ -112,6 +112,18 @@ int mx_gemm_mbs(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
                 const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
                 int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,
                 void* stream);
+
+/* Few-row (decode) form with the activations quantized on the fly (Sec. 4.3: activations are
+ * "quantized on-the-fly"; Sec. 5.3): C = Q(A) * B^T where Q is mx_quantize_mbs(rule) if a_use_mbs != 0,
+ * else mx_quantize(rule), applied inside the GEMM kernel to a_bf16 [M, lda] (bf16, row-major, 16-byte
+ * aligned, lda % 8 == 0, lda >= K); the quantized activations are never written to memory.  The result
+ * is bit-identical to mx_quantize_mbs / mx_quantize followed by mx_gemm_mbs on the same weights.
+ * Covers M <= 64, K % 512 == 0, 0 < K <= 8192, b_scales 16-byte aligned, b_mbs 4-byte aligned; anything
+ * else returns MX_EUNSUPPORTED and nothing is launched (use the two calls). */
+int mx_gemm_mbs_quantize_a(const void* a_bf16, int64_t lda, mx_rule_t rule, int a_use_mbs,
+                           const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
+                           int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,
+                           void* stream);
 
 /* Grouped (mixture-of-experts) form of mx_gemm_mbs (Sec. 5.1: every expert's linear layers are
  * quantized): the rows of A and C are grouped, group e owning rows

@@ -42,6 +42,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_quantize_oas.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.mx_quantize_mbs.restype = ci
     L.mx_quantize_mbs.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp]
+    L.mx_gemm_mbs_quantize_a.restype = ci
+    L.mx_gemm_mbs_quantize_a.argtypes = [vp, i64, ci, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_quantize_mbs_dynamic.restype = ci
     L.mx_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                           vp, vp, vp, vp]
@@ -227,6 +229,19 @@ def mx_gemm_mbs(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, out_dtype="f
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
     _check(load_library().mx_gemm_mbs(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes), _ptr(b_scales),
                                       _ptr(b_mbs), M, N, K, code, _ptr(out), ldc, _stream()), "mx_gemm_mbs")
+    return out
+
+
+def mx_gemm_mbs_quantize_a(a, rule, b_codes, b_scales, b_mbs, out_dtype="f32", out=None, a_use_mbs=True):
+    """Few-row GEMM with the bf16 activations `a` [M, K] quantized inside the kernel (M <= 64)."""
+    M, K, lda = _rows_ld(a)
+    N = b_codes.shape[0]
+    if b_codes.shape[1] * 2 != K:
+        raise ValueError("A and B disagree on K")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a.device)
+    _check(load_library().mx_gemm_mbs_quantize_a(_ptr(a), lda, _rule(rule), int(bool(a_use_mbs)), _ptr(b_codes),
+                                                 _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,
+                                                 _stream()), "mx_gemm_mbs_quantize_a")
     return out
 
 

@@ -583,10 +583,42 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     return launch_shape<Shape128, Shape128Wide, true>(g, grouped, use_mbs, ragged, s);
 }
 
+// Few-row GEMM with A given as bf16 and quantized inside the kernel (mx_gemm_skinny.hip).
+int launch_gemm_quantize_a(const void* a_bf16, int64_t lda, int rule, int a_use_mbs, const uint8_t* b_codes,
+                           const uint8_t* b_scales, const uint8_t* b_mbs, int64_t M, int64_t N, int64_t K, int c_dtype,
+                           void* C, int64_t ldc, void* stream) {
+    if (M < 0 || N < 0 || K < 0 || (K % kBlock) != 0 || ldc < N || lda < K) return MX_EINVAL;
+    if (c_dtype != MX_OUT_F32 && c_dtype != MX_OUT_BF16) return MX_EINVAL;
+    if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
+    if (N > (int64_t)1 << 30) return MX_EINVAL;
+    if (M == 0 || N == 0) return MX_OK;
+    if (!C || !a_bf16 || !b_codes || !b_scales) return MX_ENULL;
+    const size_t esz = c_dtype == MX_OUT_F32 ? 4 : 2;
+    if (!aligned(C, esz) || !aligned(a_bf16, 16) || (lda % 8) != 0 || !aligned(b_codes, 16)) return MX_EALIGN;
+    // what the few-row kernel covers; larger problems take mx_quantize_mbs + mx_gemm_mbs
+    if (M > 64 || K == 0 || (K % 512) != 0 || K > 8192 || !aligned(b_scales, 16) || (b_mbs && !aligned(b_mbs, 4)) ||
+        ((M - 1) * lda + K) * 2 >= (int64_t)1 << 31)
+        return MX_EUNSUPPORTED;
+    if (int st = check_device()) return st;
+    GemmArgs g = {};
+    g.b_codes = b_codes; g.b_scales = b_scales; g.b_mbs = b_mbs;
+    g.C = C;
+    g.M = M; g.N = N; g.K = K; g.ldc = ldc;
+    g.c_bf16 = c_dtype == MX_OUT_BF16;
+    return launch_gemm_skinny_fused(g, a_bf16, lda, rule, a_use_mbs != 0, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 }  // namespace mx
 
 extern "C" {
+
+int mx_gemm_mbs_quantize_a(const void* a_bf16, int64_t lda, mx_rule_t rule, int a_use_mbs, const uint8_t* b_codes,
+                           const uint8_t* b_scales, const uint8_t* b_mbs_or_null, int64_t M, int64_t N, int64_t K,
+                           mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream) {
+    return mx::launch_gemm_quantize_a(a_bf16, lda, (int)rule, a_use_mbs, b_codes, b_scales, b_mbs_or_null, M, N, K,
+                                      (int)c_dtype, C, ldc, stream);
+}
 
 int mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes, const uint8_t* b_scales,
             int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream) {

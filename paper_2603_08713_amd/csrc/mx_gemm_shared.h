@@ -27,6 +27,7 @@ int launch_gemm_wide(const GemmArgs& g, bool allow_split, hipStream_t s);
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
 // Few activation rows (M <= 64, K <= 8192, otherwise the same conditions), defined in mx_gemm_skinny.hip.
 int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s);
+int launch_gemm_skinny_fused(const GemmArgs& g, const void* x_bf16, int64_t ldx, int rule, bool a_mbs, hipStream_t s);
 
 namespace {
 

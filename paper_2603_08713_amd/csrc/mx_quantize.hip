@@ -18,7 +18,7 @@
 //     exceeds the rule's threshold (Sec. 4.2: FLOOR 1.5, OAS 1.75, OCP never).
 // Blocks whose magnitudes are so small or so large that fp32 products could leave the normal
 // range, and blocks holding Inf/NaN, take a wave-uniform detour through an all-integer path.
-#include "mx_common.h"
+#include "mx_quantize_math.h"
 
 namespace mx {
 namespace {
@@ -40,26 +40,7 @@ struct QuantArgs {
     int scales_dword;  // scales of a macro block can be stored as one aligned dword
 };
 
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
-    us2 r = __builtin_elementwise_max(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b));
-    return __builtin_bit_cast(uint32_t, r);
-}
-
-// 8 leading mantissa bits of 6/alpha for alpha = (128 + k) * 2^e:  6*128/(128+k) lies in (3, 6];
-// normalised to [1,2) it is 192/(128+k) for k <= 64 and 384/(128+k) above.
-__device__ __forceinline__ uint32_t mbs_word_of_mantissa(uint32_t k) {
-    const uint32_t n = 128u + k;
-    return (k <= 64u ? 49152u / n : 98304u / n) - 256u;
-}
-// The same quotient through the hardware reciprocal (see the note at the top of the file).
-__device__ __forceinline__ uint32_t mbs_word_of_mantissa_fast(uint32_t k) {
-    const float num = k <= 64u ? 49152.0f : 98304.0f;
-    const float quo = fmaf(num, __builtin_amdgcn_rcpf((float)(128u + k)), 0x1.0p-10f);
-    return (uint32_t)quo - 256u;
-}
 
 // Round |t| (t already multiplied by the block scale) to the E2M1 grid, nearest-even, saturating.
 // Adding 1.5 * 2^(22 + e), e = max(exponent(t), 0), leaves t in units of the grid step of its
@@ -98,50 +79,16 @@ __device__ __noinline__ ChunkResult quantize_chunk_exact(u32x4 v, int rule, int 
     mmax = max(mmax, dpp_row_ror4(mmax));
     mmax = max(mmax, dpp_row_ror8(mmax));
 
-    uint32_t m8 = 0;
-    if (use_mbs && mmax) {
-        uint32_t k = mmax & 0x7Fu;
-        if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;  // normalise a subnormal absmax
-        m8 = mbs_word_of_mantissa(k);
-    }
+    uint32_t m8 = use_mbs ? mbs_word_of_absmax(mmax) : 0u;
     if (m8_given >= 0) m8 = (uint32_t)m8_given;
     const uint32_t u = 256u + m8;  // F = u / 256
 
-    int E;
-    if (nf) {
-        E = 255;
-    } else if (amax == 0) {
-        E = 127;
-    } else {
-        const uint32_t ea = amax >> 7;
-        const uint32_t na = ea ? (128u | (amax & 0x7Fu)) : (amax & 0x7Fu);
-        const int ex = (int)(ea ? ea : 1u) - 134;            // absmax = na * 2^ex
-        const uint32_t P = na * u;                           // absmax * F = P * 2^(ex-8)
-        const int msb = 31 - __clz(P);
-        const int p = ex - 8 + msb;                          // floor(log2(absmax * F))
-        bool low = true;                                     // mantissa at or below the threshold
-        if (rule == MX_RULE_FLOOR) low = 2u * P <= (3u << msb);
-        else if (rule == MX_RULE_OAS) low = 4u * P <= (7u << msb);
-        const int s = low ? 2 - p : 1 - p;
-        E = min(max(127 - s, 0), 254);
-    }
+    const int E = nf ? 255 : amax == 0 ? 127 : exact_scale_byte(amax, u, rule);
     const int s = 127 - E;
-
     uint32_t codes = 0;
     if (!nf) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t a = h[i] & 0x7FFFu, e = a >> 7;
-            const uint32_t n = e ? (128u | (a & 0x7Fu)) : (a & 0x7Fu);
-            const int sh = (int)(e ? e : 1u) - 134 - 8 + s + 2;  // |x| F 2^s = n u 2^sh quarter units
-            uint32_t T = n * u;
-            int r = 0;
-            if (sh >= 0) T <<= min(sh, 8); else r = min(-sh, 18);
-            // thresholds 1/4, 3/4, 5/4, 7/4, 5/2, 7/2, 5 in quarter units; ties go to the even code
-            const uint32_t c = (T > (1u << r)) + (T >= (3u << r)) + (T > (5u << r)) + (T >= (7u << r)) +
-                               (T > (10u << r)) + (T >= (14u << r)) + (T > (20u << r));
-            codes |= (c | ((h[i] >> 12) & 8u)) << (4 * i);
-        }
+        for (int i = 0; i < 8; ++i) codes |= exact_code(h[i], u, s) << (4 * i);
     }
     return {codes, (uint32_t)E, m8};
 }
@@ -357,12 +304,7 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
         mmax = max(mmax, dpp_row_ror8(mmax));
 
         // static word (Eq. 3) from the mantissa of the absmax, a subnormal absmax normalised first
-        uint32_t m_static = 0;
-        if (mmax) {
-            uint32_t k = mmax & 0x7Fu;
-            if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;
-            m_static = mbs_word_of_mantissa(k);
-        }
+        const uint32_t m_static = mbs_word_of_absmax(mmax);
         const uint32_t e128 = mmax >> 7;
         const bool searchable = !nf && e128 >= 64u && e128 <= 249u;
         const bool counts = amax != 0 && (amax >> 7) + 30u >= e128;
@@ -429,7 +371,7 @@ int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int6
     q.nmac = (K + kMacro - 1) / kMacro;
     q.rule = rule;
     q.use_mbs = use_mbs;
-    q.carry = rule == MX_RULE_FLOOR ? 0x3FFFFFu : rule == MX_RULE_OAS ? 0x1FFFFFu : 0u;
+    q.carry = rule_carry(rule);
     q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
     *empty = false;
     return MX_OK;

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
-    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
+    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_gemm_mbs_quantize_a", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
             "mx_gemm_mbs_grouped", "mx_status_string", "mx_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -71,6 +71,31 @@ def test_quantize_argument_errors(lib):
     assert d(A16, 4, 48, 48, 2, 0, 16, 16, A16, A16, A16, None) == -1           # K % 32
     assert d(A16, 4, 64, 64, 2, 0, 16, 16, A16, A16, None, None) == -2          # mbs required
     assert d(A16, 0, 64, 64, 2, 0, 16, 16, A16, A16, A16, None) == 0
+
+
+def test_gemm_quantize_a_argument_errors(lib):
+    f = lib.mx_gemm_mbs_quantize_a
+    ok = (A16, 512, 2, 1, A16, A16, A16, 16, 64, 512, 0, A16, 64, None)
+
+    def call(**kw):
+        names = ("a", "lda", "rule", "a_mbs", "bc", "bs", "bm", "M", "N", "K", "dt", "C", "ldc", "stream")
+        args = dict(zip(names, ok))
+        args.update(kw)
+        return f(*[args[n] for n in names])
+
+    assert call(K=48, lda=48) == -1
+    assert call(lda=256) == -1              # lda < K
+    assert call(ldc=32) == -1               # ldc < N
+    assert call(rule=9) == -1
+    assert call(dt=3) == -1
+    assert call(M=0) == 0 and call(N=0) == 0
+    assert call(a=None) == -2 and call(bc=None) == -2 and call(bs=None) == -2 and call(C=None) == -2
+    assert call(a=A16 + 2) == -3 and call(lda=516) == -3 and call(bc=A16 + 8) == -3
+    assert call(M=65) == -4                 # shapes the few-row kernel does not cover
+    assert call(K=544, lda=544) == -4
+    assert call(K=16384, lda=16384) == -4
+    assert call(bs=A16 + 4) == -4
+    assert call(bm=A16 + 2) == -4
 
 
 def test_dequantize_argument_errors(lib):

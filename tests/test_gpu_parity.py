@@ -147,6 +147,68 @@ def test_quantize_full_size_activation(mx, oracle):
 
 
 # ------------------------------------------------------------------------------------------------
+# few-row GEMM with the activations quantized inside the kernel
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K", [(1, 64, 512), (7, 200, 1024), (16, 4096, 4096), (17, 16 * 300, 2048), (33, 16 * 600, 512),
+                                   (64, 1000, 8192), (16, 14336, 4096)])
+def test_gemm_quantize_a_fused(mx, oracle, M, N, K):
+    """C = Q(A) B^T in one launch: bit-identical to quantize + GEMM through the two entry points, and within
+    tolerance of the oracle; every rule, with and without MBS words on either side, padded rows of A."""
+    from paper_2603_08713_amd import synth
+
+    lda = K + 64
+    full = synth.activations_student_t(M, lda, 4.0, 0.01, 20.0, M * 31 + N)
+    a_bits = np.ascontiguousarray(full[:, :K])
+    w_bits = synth.gaussian(N, K, 0.02, N + K)
+    xa = dev_bf16(full)[:, :K]
+    wq = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
+    ow = tuple(host(t) for t in wq)
+    for rule, a_mbs, b_mbs in (("oas", True, True), ("ocp", False, True), ("floor", True, False), ("oas", False, False)):
+        bm = wq[2] if b_mbs else None
+        for dt in ("f32", "bf16"):
+            got = mx.mx_gemm_mbs_quantize_a(xa, rule, wq[0], wq[1], bm, dt, a_use_mbs=a_mbs)
+            aq = mx.mx_quantize_mbs(xa, rule) if a_mbs else mx.mx_quantize(xa, rule) + (None,)
+            two = mx.mx_gemm_mbs(aq[0], aq[1], aq[2], wq[0], wq[1], bm, dt)
+            torch.cuda.synchronize()
+            assert torch.equal(got, two), "rule=%s a_mbs=%s b_mbs=%s %s" % (rule, a_mbs, b_mbs, dt)
+        rows = None if M * N <= 1 << 16 else np.array([0, M - 1])
+        want = oracle.gemm(oracle.quantize(a_bits, rule, mbs=a_mbs), (ow[0], ow[1], ow[2] if b_mbs else None), rows=rows)
+        g32 = host(mx.mx_gemm_mbs_quantize_a(xa, rule, wq[0], wq[1], bm, "f32", a_use_mbs=a_mbs))
+        g32 = g32 if rows is None else g32[rows]
+        assert np.abs(g32 - want).max() <= GEMM_TOL * np.sqrt(np.mean(want ** 2))
+
+
+def test_gemm_quantize_a_fused_edge_values(mx, oracle):
+    """Activation blocks outside the fp32 route's range (subnormal, tiny, huge, zero rows, Inf/NaN): the
+    in-kernel quantizer must agree with the quantizer kernel to the bit, which the product shows."""
+    rng = np.random.default_rng(41)
+    M, N, K = 16, 256, 1024
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[1] *= np.float32(2.0 ** -110)
+    x[2] *= np.float32(2.0 ** -130)
+    x[3] *= np.float32(2.0 ** 120)
+    x[4] = 0
+    x[5, 100:140] *= np.float32(2.0 ** -120)
+    x[6, ::3] = 0
+    bits = (x.view(np.uint32) >> 16).astype(np.uint16)
+    bits[7, 5] = 0x7F80       # +Inf
+    bits[8, 900] = 0xFFC0     # NaN
+    w_bits = (rng.standard_normal((N, K)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    wq = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
+    xa = dev_bf16(bits)
+    for rule in RULES:
+        for a_mbs in (True, False):
+            got = mx.mx_gemm_mbs_quantize_a(xa, rule, *wq, "f32", a_use_mbs=a_mbs)
+            aq = mx.mx_quantize_mbs(xa, rule) if a_mbs else mx.mx_quantize(xa, rule) + (None,)
+            two = mx.mx_gemm_mbs(*aq, *wq, "f32")
+            torch.cuda.synchronize()
+            g, t2 = host(got), host(two)
+            assert np.array_equal(np.isnan(g), np.isnan(t2))
+            assert not np.isnan(g[:7]).any()
+            assert np.array_equal(g[~np.isnan(g)], t2[~np.isnan(t2)]), "rule=%s a_mbs=%s" % (rule, a_mbs)
+
+
+# ------------------------------------------------------------------------------------------------
 # MBS-Dynamic quantizer (searched word)
 # ------------------------------------------------------------------------------------------------
 def assert_dynamic_equal(mx, oracle, bits, rule="oas", what="", oracle_rows=None, **cands):
