@@ -75,6 +75,15 @@ int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx,
 int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                     uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
+/* mx_quantize_mbs for two tensors that share K -- the two operands of one GEMM (Sec. 4.3.2: both A and
+ * B carry MBS words) -- in a single launch; outputs identical to two mx_quantize_mbs calls.  Either
+ * tensor may have zero rows. */
+int mx_quantize_mbs_pair(const void* x0_bf16, int64_t rows0, int64_t ldx0,
+                         uint8_t* codes0, uint8_t* scales0, uint8_t* mbs0,
+                         const void* x1_bf16, int64_t rows1, int64_t ldx1,
+                         uint8_t* codes1, uint8_t* scales1, uint8_t* mbs1,
+                         int64_t K, mx_rule_t rule, void* stream);
+
 /* MBS-Dynamic quantization (Sec. 4.3.1 "Dynamic", Sec. 5.3; meant for weights, which are quantized
  * offline: MBS-Hybrid = this for B, mx_quantize_mbs for A): as mx_quantize_mbs, but the word of each
  * window is searched for the least sum of squared errors of the window among the static word and

@@ -42,6 +42,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_quantize_oas.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.mx_quantize_mbs.restype = ci
     L.mx_quantize_mbs.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp]
+    L.mx_quantize_mbs_pair.restype = ci
+    L.mx_quantize_mbs_pair.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, vp, vp, vp, i64, ci, vp]
     L.mx_gemm_mbs_quantize_a.restype = ci
     L.mx_gemm_mbs_quantize_a.argtypes = [vp, i64, ci, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_quantize_mbs_dynamic.restype = ci
@@ -161,6 +163,20 @@ def mx_quantize_mbs(x, rule="oas", codes=None, scales=None, mbs=None):
     _check(load_library().mx_quantize_mbs(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
                                           _ptr(mbs), _stream()), "mx_quantize_mbs")
     return codes, scales, mbs
+
+
+def mx_quantize_mbs_pair(x0, x1, rule="oas", out0=None, out1=None):
+    """MBS-Static quantization of two tensors with the same K in one launch -> ((codes, scales, mbs), (...))."""
+    rows0, K, ld0 = _rows_ld(x0)
+    rows1, K1, ld1 = _rows_ld(x1)
+    if K != K1:
+        raise ValueError("the two tensors must share K")
+    o0 = _alloc_outputs(x0, rows0, K, *(out0 or (None, None, None)), True)
+    o1 = _alloc_outputs(x1, rows1, K, *(out1 or (None, None, None)), True)
+    _check(load_library().mx_quantize_mbs_pair(_ptr(x0), rows0, ld0, _ptr(o0[0]), _ptr(o0[1]), _ptr(o0[2]),
+                                               _ptr(x1), rows1, ld1, _ptr(o1[0]), _ptr(o1[1]), _ptr(o1[2]),
+                                               K, _rule(rule), _stream()), "mx_quantize_mbs_pair")
+    return o0, o1
 
 
 def mx_quantize_mbs_dynamic(x, rule="oas", cand_first=0, cand_count=16, cand_stride=16, codes=None, scales=None,

@@ -38,6 +38,12 @@ struct QuantArgs {
     int rule;
     int use_mbs;
     int scales_dword;  // scales of a macro block can be stored as one aligned dword
+    // optional second tensor with the same K, quantized by the same launch: its chunks follow the first
+    // tensor's, whose count is rounded up to a whole batch (split) so that no batch straddles the two
+    const uint16_t* x2;
+    uint8_t *codes2, *scales2, *mbs2;
+    int64_t ldx2;
+    uint32_t split, total_chunks2;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -159,7 +165,17 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
 
     // chunk ids are wave-uniform: (row, chunk-in-row) is found once per batch of kUnroll chunks and then
     // stepped, so the division stays off the per-element path
-    for (uint32_t c0 = wave * kUnroll; c0 < q.total_chunks; c0 += nwaves * kUnroll) {
+    for (uint32_t g0 = wave * kUnroll; g0 < q.split + q.total_chunks2; g0 += nwaves * kUnroll) {
+        // which tensor (wave-uniform)
+        const bool second = g0 >= q.split;
+        const uint16_t* x = second ? q.x2 : q.x;
+        uint8_t* codes = second ? q.codes2 : q.codes;
+        uint8_t* scales = second ? q.scales2 : q.scales;
+        uint8_t* mbs = second ? q.mbs2 : q.mbs;
+        const int64_t ldx = second ? q.ldx2 : q.ldx;
+        const uint32_t total = second ? q.total_chunks2 : q.total_chunks;
+        const uint32_t c0 = second ? g0 - q.split : g0;
+        if (c0 >= total) continue;
         u32x4 v[kUnroll];
         uint32_t row[kUnroll], col[kUnroll];
         bool valid[kUnroll];
@@ -168,17 +184,17 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
         for (int u = 0; u < kUnroll; ++u) {
             row[u] = r;
             col[u] = cc * kChunk + lane * 8;
-            valid[u] = c0 + u < q.total_chunks && col[u] < q.K;
+            valid[u] = c0 + u < total && col[u] < q.K;
             v[u] = u32x4{0, 0, 0, 0};
             if (valid[u]) {
-                const uint16_t* rowp = q.x + (int64_t)r * q.ldx;  // uniform base + 32-bit lane offset
+                const uint16_t* rowp = x + (int64_t)r * ldx;  // uniform base + 32-bit lane offset
                 v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rowp + col[u]));
             }
             if (++cc == q.chunks_per_row) { cc = 0; ++r; }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            if (c0 + u >= q.total_chunks) break;  // wave-uniform
+            if (c0 + u >= total) break;  // wave-uniform
             const ChunkResult res = quantize_chunk<kHwCvt, kMbs>(v[u], q);
             // scales of the macro block gathered into one dword across the row of 16 lanes
             uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
@@ -187,15 +203,15 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
             ew |= dpp_row_ror8(ew);
             if (!valid[u]) continue;
             const uint32_t kblk = col[u] >> 5;
-            uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
-            uint8_t* crow = q.codes + (int64_t)row[u] * (q.K >> 1);
+            uint8_t* srow = scales + (int64_t)row[u] * (q.K >> 5);
+            uint8_t* crow = codes + (int64_t)row[u] * (q.K >> 1);
             *reinterpret_cast<uint32_t*>(crow + (col[u] >> 1)) = res.codes;
             if (q.scales_dword) {
                 if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
             } else if ((lane & 3) == 0) {
                 srow[kblk] = (uint8_t)res.E;
             }
-            if (kMbs && (lane & 15) == 0) q.mbs[(int64_t)row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)res.m8;
+            if (kMbs && (lane & 15) == 0) mbs[(int64_t)row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)res.m8;
         }
     }
 }
@@ -348,16 +364,19 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
 
 int g_quant_hwcvt = 1;
 
+int launch_filled(const QuantArgs& q, int use_mbs, void* stream);
+
 // argument checks and the fields common to both quantizer kernels; MX_OK with *empty set means nothing to do
 int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
-                    uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, bool device_check = true) {
     *empty = true;
     if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
     if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
     if (rows == 0 || K == 0) return MX_OK;
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
     if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 16)) return MX_EALIGN;
-    if (int st = check_device()) return st;
+    if (device_check)
+        if (int st = check_device()) return st;
     q.x = static_cast<const uint16_t*>(x);
     q.codes = codes;
     q.scales = scales;
@@ -373,6 +392,11 @@ int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int6
     q.use_mbs = use_mbs;
     q.carry = rule_carry(rule);
     q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
+    q.x2 = nullptr;
+    q.codes2 = q.scales2 = q.mbs2 = nullptr;
+    q.ldx2 = 0;
+    q.split = q.total_chunks;
+    q.total_chunks2 = 0;
     *empty = false;
     return MX_OK;
 }
@@ -383,8 +407,37 @@ int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rul
     bool empty;
     if (int st = fill_quant_args(q, &empty, x, rows, K, ldx, rule, use_mbs, codes, scales, mbs)) return st;
     if (empty) return MX_OK;
+    return launch_filled(q, use_mbs, stream);
+}
 
-    const int64_t waves_needed = ((int64_t)q.total_chunks + kUnroll - 1) / kUnroll;
+// Two tensors with the same K (the two operands of a GEMM) in one launch: the smaller one no longer pays
+// for a launch and a ramp of its own.
+int launch_quantize_pair(const void* x0, int64_t rows0, int64_t ldx0, uint8_t* codes0, uint8_t* scales0, uint8_t* mbs0,
+                         const void* x1, int64_t rows1, int64_t ldx1, uint8_t* codes1, uint8_t* scales1, uint8_t* mbs1,
+                         int64_t K, int rule, void* stream) {
+    QuantArgs q0, q1;
+    bool empty0, empty1;
+    if (int st = fill_quant_args(q0, &empty0, x0, rows0, K, ldx0, rule, 1, codes0, scales0, mbs0, false)) return st;
+    if (int st = fill_quant_args(q1, &empty1, x1, rows1, K, ldx1, rule, 1, codes1, scales1, mbs1, false)) return st;
+    if (empty0 && empty1) return MX_OK;
+    if (int st = check_device()) return st;
+    if (empty0) return launch_filled(q1, 1, stream);
+    if (empty1) return launch_filled(q0, 1, stream);
+    const int64_t split = ((int64_t)q0.total_chunks + kUnroll - 1) / kUnroll * kUnroll;
+    if (split + q1.total_chunks >= ((int64_t)1 << 32)) return MX_EINVAL;  // chunk ids are 32-bit
+    q0.x2 = q1.x;
+    q0.codes2 = q1.codes;
+    q0.scales2 = q1.scales;
+    q0.mbs2 = q1.mbs;
+    q0.ldx2 = q1.ldx;
+    q0.split = (uint32_t)split;
+    q0.total_chunks2 = q1.total_chunks;
+    q0.scales_dword = q0.scales_dword && q1.scales_dword;
+    return launch_filled(q0, 1, stream);
+}
+
+int launch_filled(const QuantArgs& q, int use_mbs, void* stream) {
+    const int64_t waves_needed = ((int64_t)q.split + q.total_chunks2 + kUnroll - 1) / kUnroll;
     int64_t blocks = (waves_needed + (kThreads / kWave) - 1) / (kThreads / kWave);
     // one batch of kUnroll chunks per wavefront (the hardware balances the workgroups); the loop in
     // the kernel only matters beyond this cap
@@ -442,6 +495,13 @@ int mx_quantize_oas(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, ui
 int mx_quantize_mbs(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                     uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
     return mx::launch_quantize(x_bf16, rows, K, ldx, (int)rule, 1, codes, scales, mbs, stream);
+}
+
+int mx_quantize_mbs_pair(const void* x0_bf16, int64_t rows0, int64_t ldx0, uint8_t* codes0, uint8_t* scales0,
+                         uint8_t* mbs0, const void* x1_bf16, int64_t rows1, int64_t ldx1, uint8_t* codes1,
+                         uint8_t* scales1, uint8_t* mbs1, int64_t K, mx_rule_t rule, void* stream) {
+    return mx::launch_quantize_pair(x0_bf16, rows0, ldx0, codes0, scales0, mbs0, x1_bf16, rows1, ldx1, codes1, scales1,
+                                    mbs1, K, (int)rule, stream);
 }
 
 int mx_quantize_mbs_dynamic(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
-    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_gemm_mbs_quantize_a", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
+    assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_quantize_mbs_pair", "mx_gemm_mbs_quantize_a", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
             "mx_gemm_mbs_grouped", "mx_status_string", "mx_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -63,6 +63,12 @@ def test_quantize_argument_errors(lib):
     assert lib.mx_quantize_oas(A16, 4, 40, 40, A16, A16, None) == -1
     assert lib.mx_quantize_mbs(A16, 4, 64, 64, 2, A16, A16, None, None) == -2   # mbs required
     assert lib.mx_quantize_mbs(A16, 0, 64, 64, 2, A16, A16, None, None) == 0
+    p = lib.mx_quantize_mbs_pair
+    assert p(A16, 4, 64, A16, A16, A16, A16, 4, 64, A16, A16, A16, 48, 2, None) == -1      # K % 32
+    assert p(A16, 4, 64, A16, A16, A16, A16, 4, 32, A16, A16, A16, 64, 2, None) == -1      # second ld < K
+    assert p(A16, 4, 64, A16, A16, None, A16, 4, 64, A16, A16, A16, 64, 2, None) == -2
+    assert p(A16, 4, 64, A16, A16, A16, A16 + 2, 4, 64, A16, A16, A16, 64, 2, None) == -3
+    assert p(A16, 0, 64, A16, A16, A16, A16, 0, 64, A16, A16, A16, 64, 2, None) == 0
     d = lib.mx_quantize_mbs_dynamic
     assert d(A16, 4, 64, 64, 2, 0, 257, 16, A16, A16, A16, None) == -1          # too many candidates
     assert d(A16, 4, 64, 64, 2, 0, -1, 16, A16, A16, A16, None) == -1

@@ -146,6 +146,27 @@ def test_quantize_full_size_activation(mx, oracle):
     assert_quant_equal(mx, oracle, a, "ocp", False, "llama8b A")
 
 
+@pytest.mark.parametrize("rows0,rows1,K", [(64, 256, 512), (5, 3, 2880), (1, 130, 160), (0, 7, 1024), (9, 0, 96), (4096, 1000, 4096)])
+def test_quantize_pair_equals_two_calls(mx, oracle, rows0, rows1, K):
+    """Two tensors in one launch: identical to the oracle (and so to two separate calls), for every rule;
+    row counts that leave partial batches at the seam between the tensors."""
+    from paper_2603_08713_amd import synth
+
+    b0 = synth.activations_student_t(max(rows0, 1), K, 4.0, 0.01, 20.0, rows0 + 1)[:rows0]
+    b1 = synth.gaussian(max(rows1, 1), K, 0.02, rows1 + 2)[:rows1]
+    for rule in RULES:
+        q0, q1 = mx.mx_quantize_mbs_pair(dev_bf16(b0), dev_bf16(b1), rule)
+        torch.cuda.synchronize()
+        for bits, got in ((b0, q0), (b1, q1)):
+            if bits.shape[0] == 0:
+                continue
+            rows = None if bits.shape[0] <= 512 else np.arange(0, bits.shape[0], 37)
+            want = oracle.quantize(bits if rows is None else bits[rows], rule, mbs=True)
+            for g, w_ in zip(got, want):
+                g = host(g)
+                assert np.array_equal(g if rows is None else g[rows], w_)
+
+
 # ------------------------------------------------------------------------------------------------
 # few-row GEMM with the activations quantized inside the kernel
 # ------------------------------------------------------------------------------------------------
