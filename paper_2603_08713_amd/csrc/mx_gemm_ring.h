@@ -47,7 +47,7 @@ constexpr int kRingRowStage = kRingStageK / 2;  // code bytes per row and stage
 constexpr int kRingSlots = 4;
 constexpr int kRingGroup = 4;                   // stages per 16-byte piece of a row's E8M0 bytes
 constexpr int kRingGroupM = 4;                  // tile-rows walked together for L2 reuse
-constexpr int kSigmaSlots = 3;
+constexpr int kSigmaSlots = 4;                  // as many as ring slots: a stage's table index is a compile-time constant
 
 // kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both)
 template <int NWM_, int NWN_, int FM_, int FN_, int kSides_>
@@ -64,11 +64,14 @@ struct RingShape {
     static constexpr int kScaleGroup = kRowsPadded * 16;
     static constexpr int kM8Group = kMbs ? kRowsPadded * 4 : 0;
     static constexpr int kSigmaStage = kMbs ? kRows * 4 : 0;
-    static constexpr int kScaleBase = kRingSlots * kCodesStage;
-    static constexpr int kM8Base = kScaleBase + 2 * kScaleGroup;
+    // The small arrays come first: their addresses then fit the 16-bit constant of an LDS instruction.
+    static constexpr int kM8Base = 0;
     static constexpr int kSigmaBase = kM8Base + 2 * kM8Group;
-    static constexpr int kDummy = kSigmaBase + kSigmaSlots * kSigmaStage;  // target of padding stores
-    static constexpr int kLdsBytes = kDummy + 256;
+    static constexpr int kScaleBase = (kSigmaBase + kSigmaSlots * kSigmaStage + 16383) / 16384 * 16384;
+    static constexpr int kDummy = kScaleBase + 2 * kScaleGroup;  // target of padding stores
+    static constexpr int kCodesBase = kDummy + 256;
+    static constexpr int kLdsBytes = kCodesBase + kRingSlots * kCodesStage;
+    static_assert(kCodesBase % 64 == 0 && kCodesBase < 65536, "code rows stay 64-byte aligned; small arrays below 64 KiB");
     static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
     static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
     static_assert((TM / 16) % NW == 0 && (TN / 16) % NW == 0, "16-row code loads: operand fixed per load index");
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // expressions, the host pass of the compiler drops the kernel.)
     auto dma_code = [&](int s, auto i_) {  // load i of the codes of stage s
         constexpr int i = decltype(i_)::value;
-        uint8_t* dst = smem + (s % kRingSlots) * S::kCodesStage + (i * NW + w) * 1024;
+        uint8_t* dst = smem + S::kCodesBase + (s % kRingSlots) * S::kCodesStage + (i * NW + w) * 1024;
         const int voff = code_off[i];
         __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 16 < TM ? opa.codes : opb.codes, (lds_ptr_t)dst, 16, voff,
                                                  min(s, nstages - 1) * kRingRowStage, 0, 0);
@@ -183,25 +186,41 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // are folded in, the next fragment's values (of this or of the next stage) arrive in the other set.
     float sig_m[2][FM];
     v4f sig_n[2][4];
-    int frag_off[2];  // this lane's 16 bytes inside a fragment's 32 rows, per instruction of the pair
+    // This lane's 16 bytes inside a fragment's 32 rows, per instruction of the pair, with the wavefront's
+    // first row of A (index 0) or of B (index 1) folded in.  The LDS read instruction adds a 16-bit constant
+    // to its address register; ring slot, fragment and operand are compile-time constants, so with a second
+    // copy of each base 64 KiB up every code read is a bare instruction (no address arithmetic on the
+    // vector ALU, which the MBS path has no cycles to spare for).  The empty asm keeps the compiler from
+    // folding the copies back into one base plus additions.
+    int code_base[2][2][2];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) frag_off[kk] = lr * kRingRowStage + (((lh * 2 + kk) ^ ((lr >> 2) & 3)) * 16);
+    for (int kk = 0; kk < 2; ++kk) {
+        const int in_frag = lr * kRingRowStage + (((lh * 2 + kk) ^ ((lr >> 2) & 3)) * 16);
+        code_base[0][kk][0] = wm * FM * 32 * kRingRowStage + in_frag;
+        code_base[1][kk][0] = (TM + wn * FN * 32) * kRingRowStage + in_frag;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            code_base[o][kk][1] = code_base[o][kk][0] + 65536;
+            asm volatile("" : "+v"(code_base[o][kk][0]));
+            asm volatile("" : "+v"(code_base[o][kk][1]));
+        }
+    }
     const int lane_scale = lr * 16 + lh * 2;
 
-    // LDS read `idx` of the kReads that fetch the fragments of stage s: per fragment (A's FM, then B's FN) the
-    // two 16-byte code pieces and the 16-bit scale pair.
+    // LDS read `idx` of the kReads that fetch the fragments of a stage in ring slot `slot`: per fragment (A's
+    // FM, then B's FN) the two 16-byte code pieces and the 16-bit scale pair.
     constexpr int kReads = (FM + FN) * 3;
-    auto read_item = [&](Frags& f, int s, auto idx_) {
-        constexpr int idx = decltype(idx_)::value, fr = idx / 3, part = idx % 3;
+    auto read_item = [&](Frags& f, int s, auto slot_, auto idx_) {
+        constexpr int idx = decltype(idx_)::value, fr = idx / 3, part = idx % 3, slot = decltype(slot_)::value;
         constexpr bool is_m = fr < FM;
         constexpr int q = is_m ? fr : fr - FM;
-        const int row0 = is_m ? (wm * FM + q) * 32 : TM + (wn * FN + q) * 32;  // in the A-then-B row space
         if constexpr (part < 2) {
-            const v4i v = *reinterpret_cast<const v4i*>(smem + (s % kRingSlots) * S::kCodesStage + row0 * kRingRowStage +
-                                                        frag_off[part]);
+            constexpr int off = S::kCodesBase + slot * S::kCodesStage + q * 32 * kRingRowStage, hi = off > 65535 - 16 ? 1 : 0;
+            const v4i v = *reinterpret_cast<const v4i*>(smem + code_base[is_m ? 0 : 1][part][hi] + (off - hi * 65536));
             if constexpr (is_m) f.m[q][part] = v;
             else f.n[q][part] = v;
         } else {
+            const int row0 = is_m ? (wm * FM + q) * 32 : TM + (wn * FN + q) * 32;  // in the A-then-B row space
             const uint32_t v = *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
                                                  (s % kRingGroup) * 4 + lane_scale + row0 * 16);
             if constexpr (is_m) f.scl_m[q] = v;
@@ -260,7 +279,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         read_sigma_m(0, std::integral_constant<int, 0>{});
         read_sigma_n(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     }
-    static_for<kReads>([&](auto idx_) { read_item(f0, 0, idx_); });
+    static_for<kReads>([&](auto idx_) { read_item(f0, 0, std::integral_constant<int, 0>{}, idx_); });
 
     // ---- the matrix instructions of one stage ---------------------------------------------------------
     // Plain: instruction t is half kk = t / (FM FN) of fragment pair (i, j); the two halves of a pair are
@@ -297,6 +316,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         constexpr int kPhase = decltype(phase_)::value, kLate = decltype(late_)::value;
         using Par = std::integral_constant<int, kPhase % 2>;       // stage parity: kRingGroup is even
         using NextPar = std::integral_constant<int, 1 - kPhase % 2>;
+        using NextSlot = std::integral_constant<int, (kPhase + 1) % kRingSlots>;  // stage s sits in slot s % 4 = kPhase
+        static_assert(kRingSlots == kRingGroup, "the phase of a stage is also its ring slot");
         constexpr bool kIssue = decltype(issue_)::value;
         constexpr int kN = kLoads[kPhase];
         // Own loads of stage s + 1 (and of what the group loads two or more stages old carry) have landed;
@@ -304,12 +325,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         constexpr int kYounger = kLoads[(kPhase + 2) % 4] + kLoads[(kPhase + 3) % 4];
         __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? kYounger : 0));
         bare_barrier();
-        if constexpr (kMbs) convert_sigma(s + 2);  // into the table stage s - 1 was read from
+        if constexpr (kMbs) convert_sigma(s + 2);  // into the table stage s - 2 was read from
         auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
             constexpr int t = decltype(t_)::value;
             if constexpr (!kMbs) {
                 static_for<kReads>([&](auto r_) {
-                    if constexpr ((decltype(r_)::value * kMfmas) / kReads == t) read_item(next, s + 1, r_);
+                    if constexpr ((decltype(r_)::value * kMfmas) / kReads == t) read_item(next, s + 1, NextSlot{}, r_);
                 });
             }
             if constexpr (kMbs && t == kMfmas / 2) read_sigma_m(s + 1, NextPar{});
@@ -332,10 +353,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 constexpr int pj = decltype(p_)::value / FM, pi = decltype(p_)::value % FM;
                 product(cur, p_);
                 if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
+                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
                 });
                 if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
+                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
                 });
             };
             issue(std::integral_constant<int, 0>{});
