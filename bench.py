@@ -202,7 +202,7 @@ def time_loop(torch, fn, iters, warm=20):
     return e0.elapsed_time(e1) / iters
 
 
-def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):
+def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):  # noqa: C901
     """Side measurements outside the timed region: plain MXFP4 GEMM on the same shape (for the
     Tab. 4 style overhead), a device copy as the achievable-HBM yardstick, the dequantizer."""
     n = max(5, min(args.steps, 100))
@@ -230,6 +230,9 @@ def extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args):
     # plain-rule quantizer and dequantizer throughput (algorithmic bytes)
     ms_q = time_loop(torch, lambda i: mx.mx_quantize(xw[i % len(xw)], "ocp", pw[0], pw[1]), n)
     res["quantize_plain_W_gbps"] = round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_PLAIN / (ms_q * 1e-3) / 1e9, 1)
+    # the step's quantizer launch on its own (back to back, inputs rotating): its rate without the GEMM between launches
+    ms_pair = time_loop(torch, lambda i: mx.mx_quantize_mbs_pair(xa[i % len(xa)], xw[i % len(xw)], "oas", qa[i % len(qa)], qw[i % len(qw)]), n)
+    res["quantize_pair_alone_gbps"] = round((xa[0].numel() + xw[0].numel()) * metrics.QUANT_BYTES_PER_ELT_MBS / (ms_pair * 1e-3) / 1e9, 1)
     # MBS-Dynamic (offline weight quantization: 17 evaluations of the window instead of one)
     ms_s = time_loop(torch, lambda i: mx.mx_quantize_mbs(xw[i % len(xw)], "oas", *qw[i % len(qw)]), n)
     ms_dyn = time_loop(torch, lambda i: mx.mx_quantize_mbs_dynamic(xw[i % len(xw)], "oas", 0, 16, 16, *qw[i % len(qw)]), n)

@@ -328,7 +328,9 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
         Candidate best = eval_candidate(xf, amax, counts, e128, m_static, q.carry);
         uint32_t m_best = m_static;
         for (int j = 0; j < d.cand_count; ++j) {
-            uint32_t m = (m_static + (uint32_t)((d.cand_first + j) * d.cand_stride)) & 255u;
+            const uint32_t step = (uint32_t)((d.cand_first + j) * d.cand_stride) & 255u;
+            if (step == 0) continue;  // the static word again: it cannot beat itself (uniform over the launch)
+            uint32_t m = (m_static + step) & 255u;
             m = searchable ? m : m_static;
             const Candidate cand = eval_candidate(xf, amax, counts, e128, m, q.carry);
             if (cand.cost < best.cost) {
