@@ -356,6 +356,32 @@ def test_dequantize_matches_oracle(mx, oracle):
     assert torch.equal(torch.nan_to_num(big[:, :K]), torch.nan_to_num(mx.mx_dequantize(dev_u8(codes), dev_u8(scales), dev_u8(words), "f32")))
 
 
+def test_dequantize_every_scale_byte_and_word(mx, oracle):
+    """Every E8M0 byte (0..254 and the NaN code) against every code, and every MBS word: both routes of the
+    kernel (two quotients per lane for normal results, element by element at the ends of the range)."""
+    rng = np.random.default_rng(6)
+    rows, K = 256, 1024 + 32
+    codes = rng.integers(0, 256, (rows, K // 2), dtype=np.uint8)
+    codes[:, :8] = np.arange(8, dtype=np.uint8) * 0x11 + np.array([0, 0x80, 0x08, 0x88, 0, 0x80, 0x08, 0x88], np.uint8)
+    scales = np.repeat(np.arange(rows, dtype=np.uint8)[:, None], K // 32, 1)      # row r: byte r everywhere
+    scales[:, 1::3] = rng.integers(0, 255, scales[:, 1::3].shape, dtype=np.uint8)   # mixed bytes inside a wavefront
+    words = rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8)
+    words[:, 0] = np.arange(rows, dtype=np.uint8)
+    for w in (None, words):
+        want = oracle.dequantize(codes, scales, w)
+        with np.errstate(over="ignore"):
+            want32 = want.astype(np.float32)
+        nan = np.isnan(want32)
+        got32 = host(mx.mx_dequantize(dev_u8(codes), dev_u8(scales), dev_u8(w), "f32"))
+        assert np.array_equal(np.isnan(got32), nan)
+        bad = np.argwhere(got32[~nan].view(np.uint32) != want32[~nan].view(np.uint32))
+        assert bad.size == 0, "%d fp32 values differ" % len(bad)
+        got16 = mx.mx_dequantize(dev_u8(codes), dev_u8(scales), dev_u8(w), "bf16").cpu()
+        want16 = torch.from_numpy(want32).to(torch.bfloat16)
+        assert np.array_equal(got16.view(torch.int16).numpy()[~nan], want16.view(torch.int16).numpy()[~nan])
+        assert np.all(np.isnan(got16.float().numpy()[nan]))
+
+
 def test_qsnr_identical_from_both_paths(mx, oracle):
     from paper_2603_08713_amd import synth
 
