@@ -152,6 +152,7 @@ def main():
 
     if not args.no_extras:
         out["extras"] = extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args)
+        out["extras"]["decode_m16_k4096"] = decode_extras(mx, torch, synth, np)
         out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
         out["extras"]["qsnr_db_gpu_weights"] = qsnr_weights_gpu(mx, torch, xw[0][:QSNR_ROWS])
     if not args.no_cpu_baseline:
@@ -186,6 +187,46 @@ def qsnr_weights_gpu(mx, torch, x):
         back = mx.mx_dequantize(q[0], q[1], q[2], "f32").to(torch.float64)
         res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
     res["sample"] = "first %d rows of W" % QSNR_ROWS
+    return res
+
+
+def decode_extras(mx, torch, synth, np):
+    """The decode configuration (16 activation rows, K = 4096, weights quantized offline): one step = quantize
+    the activations + few-row MBS GEMM, as two launches and as the one fused launch.  The steps are replayed
+    from a HIP graph (a launch from Python costs as much as these kernels run) that walks over enough copies
+    of the weights to exceed the 256 MB Infinity Cache, so the weights stream from HBM."""
+    res = {}
+    for n, copies in ((4096, 32), (14336, 10)):
+        a_bits, w_bits = synth.decode_skinny(n, 4096)
+        xa = torch.from_numpy(a_bits.view(np.int16)).view(torch.bfloat16).cuda()
+        w0 = mx.mx_quantize_mbs(torch.from_numpy(w_bits.view(np.int16)).view(torch.bfloat16).cuda(), "oas")
+        ws = [tuple(t.clone() for t in w0) for _ in range(copies)]
+        aq = mx.mx_quantize_mbs(xa, "oas")
+        c = torch.empty((16, n), dtype=torch.bfloat16, device="cuda")
+        mx.mx_gemm_mbs(*aq, *ws[0], "bf16", out=c)
+        mx.mx_gemm_mbs_quantize_a(xa, "oas", *ws[0], "bf16", out=c)
+        torch.cuda.synchronize()
+
+        def two(i):
+            mx.mx_quantize_mbs(xa, "oas", *aq)
+            mx.mx_gemm_mbs(*aq, *ws[i], "bf16", out=c)
+
+        def fused(i):
+            mx.mx_gemm_mbs_quantize_a(xa, "oas", *ws[i], "bf16", out=c)
+
+        entry = {}
+        for name, fn in (("quantize_then_gemm", two), ("fused", fused)):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(copies):
+                    fn(i)
+            us = time_loop(torch, lambda i: graph.replay(), 20, warm=5) * 1e3 / copies
+            entry[name + "_us"] = round(us, 2)
+        wbytes = n * 4096 * 0.5390625
+        entry["fused_weight_gbps"] = round(wbytes / entry["fused_us"] / 1e3, 1)
+        res["N=%d" % n] = entry
+        del ws
+    res["bound"] = "hbm (weights streamed once: 0.539 B per weight element)"
     return res
 
 

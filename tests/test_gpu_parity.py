@@ -229,6 +229,45 @@ def test_gemm_quantize_a_fused_edge_values(mx, oracle):
             assert np.array_equal(g[~np.isnan(g)], t2[~np.isnan(t2)]), "rule=%s a_mbs=%s" % (rule, a_mbs)
 
 
+def test_hip_graph_replay_matches_eager(mx, oracle):
+    """The entry points launch on the caller's stream, allocate nothing and never synchronise, so a step can be
+    captured in a HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce
+    the eager result bit for bit: the decode step in both forms and the prefill step."""
+    from paper_2603_08713_amd import synth
+
+    a_bits, w_bits = synth.decode_skinny(512, 1024)
+    xa, xw = dev_bf16(a_bits), dev_bf16(w_bits)
+    wq = mx.mx_quantize_mbs(xw, "oas")
+    big_a, big_w = dev_bf16(synth.activations_student_t(300, 1024, 4.0, 0.01, 20.0, 3)), dev_bf16(synth.gaussian(384, 1024, 0.02, 4))
+    # eager results (also warms up everything that must not happen during capture)
+    aq = mx.mx_quantize_mbs(xa, "oas")
+    want_two = mx.mx_gemm_mbs(*aq, *wq, "bf16")
+    want_fused = mx.mx_gemm_mbs_quantize_a(xa, "oas", *wq, "bf16")
+    pa, pw = mx.mx_quantize_mbs_pair(big_a, big_w, "oas")
+    want_big = mx.mx_gemm_mbs(*pa, *pw, "f32")
+    torch.cuda.synchronize()
+    # static buffers of the captured steps
+    aq_g = tuple(torch.zeros_like(t) for t in aq)
+    pa_g, pw_g = tuple(torch.zeros_like(t) for t in pa), tuple(torch.zeros_like(t) for t in pw)
+    out_two, out_fused, out_big = torch.zeros_like(want_two), torch.zeros_like(want_fused), torch.zeros_like(want_big)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mx.mx_quantize_mbs(xa, "oas", *aq_g)
+        mx.mx_gemm_mbs(*aq_g, *wq, "bf16", out=out_two)
+        mx.mx_gemm_mbs_quantize_a(xa, "oas", *wq, "bf16", out=out_fused)
+        mx.mx_quantize_mbs_pair(big_a, big_w, "oas", pa_g, pw_g)
+        mx.mx_gemm_mbs(*pa_g, *pw_g, "f32", out=out_big)
+    for replay in range(4):
+        for t in (out_two, out_fused, out_big) + aq_g + pa_g + pw_g:
+            t.fill_(1)                                   # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_two, want_two) and torch.equal(out_fused, want_fused), replay
+        assert torch.equal(out_big, want_big), replay
+        assert all(torch.equal(a, b) for a, b in zip(aq_g, aq))
+
+
 # ------------------------------------------------------------------------------------------------
 # MBS-Dynamic quantizer (searched word)
 # ------------------------------------------------------------------------------------------------
