@@ -153,6 +153,7 @@ def main():
     if not args.no_extras:
         out["extras"] = extras(mx, torch, metrics, xa, xw, qa, qw, cs, flops, gemm_tflops, args)
         out["extras"]["decode_m16_k4096"] = decode_extras(mx, torch, synth, np)
+        out["extras"]["square_shapes"] = square_shapes(mx, torch, synth, np, metrics)
         out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
         out["extras"]["qsnr_db_gpu_weights"] = qsnr_weights_gpu(mx, torch, xw[0][:QSNR_ROWS])
     if not args.no_cpu_baseline:
@@ -227,6 +228,25 @@ def decode_extras(mx, torch, synth, np):
         res["N=%d" % n] = entry
         del ws
     res["bound"] = "hbm (weights streamed once: 0.539 B per weight element)"
+    return res
+
+
+def square_shapes(mx, torch, synth, np, metrics):
+    """Plain and MBS GEMM on the square shapes M = N = K of the paper's Tab. 4 (its numbers are for another
+    machine and are context only): TFLOP/s and the overhead 1 - MBS/plain per shape, and their average."""
+    res, overheads = {}, []
+    for n in (512, 1024, 2048, 4096, 8192):
+        a = mx.mx_quantize_mbs(torch.from_numpy(synth.activations_student_t(n, n, 4.0, 0.01, 20.0, 11).view(np.int16)).view(torch.bfloat16).cuda(), "oas")
+        b = mx.mx_quantize_mbs(torch.from_numpy(synth.gaussian(n, n, 0.02, 12).view(np.int16)).view(torch.bfloat16).cuda(), "oas")
+        c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+        iters = 200 if n <= 2048 else 50
+        ms_p = time_loop(torch, lambda i: mx.mx_gemm(a[0], a[1], b[0], b[1], "bf16", out=c), iters)
+        ms_m = time_loop(torch, lambda i: mx.mx_gemm_mbs(*a, *b, "bf16", out=c), iters)
+        tp, tm = 2.0 * n ** 3 / ms_p / 1e9, 2.0 * n ** 3 / ms_m / 1e9
+        overheads.append(metrics.overhead_fraction(tp, tm))
+        res[str(n)] = {"plain_tflops": round(tp, 1), "mbs_tflops": round(tm, 1), "overhead": round(overheads[-1], 4)}
+    res["average_overhead"] = round(sum(overheads) / len(overheads), 4)
+    res["paper_context"] = "Tab. 4 (NVIDIA B200): overheads 14.84, 9.01, 0.17, 2.42, 4.73 %, average 6.2 %"
     return res
 
 

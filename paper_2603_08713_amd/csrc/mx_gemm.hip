@@ -516,7 +516,8 @@ using Shape128Wide = Shape<2, 4, 2, 1, 32>;
 using Shape256x128 = Shape<4, 2, 4, 4, 16>;
 using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
-int g_force_shape = -1;  // development switch: 0 = 128x128, 1 = 256x128, 2 = main plain kernel, 3 / 4 = main MBS kernel (128x32 / 64x64 per wavefront), 5 = few-row kernel
+constexpr int64_t kRingMinTiles = 8;  // 128 x 128 tiles a problem needs before the main kernels take it
+int g_force_shape = -1;  // development switch: 0 / 1 = generic kernel on 128x128 / 256x128 tiles, 2 / 6 / 7 = main plain kernel on 256x256 / 256x128 / 128x128 tiles, 3 / 4 = main MBS kernel on 256x128 / 128x128 tiles, 5 = few-row kernel
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -563,9 +564,16 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     // for every compute unit; everything else (grouped, ragged K, small problems) stays here.
     const bool ring_ok = !grouped && K > 0 && (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16) &&
                          (!use_mbs || ((!a_mbs || aligned(a_mbs, 4)) && (!b_mbs || aligned(b_mbs, 4))));
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    if (ring_ok && !use_mbs && t256 >= 256) shape = 2;
-    if (ring_ok && use_mbs && t256x128 >= 256) shape = 3;
+    // (plain: the launcher picks 256 x 256, 256 x 128 or 128 x 128 tiles by how many fill the device; MBS:
+    // 256 x 128 tiles when they fill it, else 128 x 128)
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    if (ring_ok && !use_mbs && t128 >= kRingMinTiles) shape = 2;
+    if (ring_ok && use_mbs && t128 >= kRingMinTiles) {
+        // rounds of one tile per compute unit x tile area / efficiency (the small tile reaches about 0.8 of the
+        // large tile's rate per output, measured)
+        const double big = 2.0 * ((t256x128 + 255) / 256), small = 1.25 * ((t128 + 255) / 256);
+        shape = big <= small ? 3 : 4;
+    }
     const bool skinny_ok = ring_ok && M <= 64 && K <= 8192;
     if (skinny_ok) shape = 5;
     if (g_force_shape >= 0) shape = g_force_shape;
@@ -574,9 +582,11 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
         return launch_gemm_skinny(g, use_mbs, s);
     }
     if (shape >= 2) {
-        if (!ring_ok || (shape == 2) == use_mbs) return MX_EINVAL;  // only reachable through the development switch
-        // (forced through the development switch the plain kernel keeps to its large tile)
-        return shape == 2 ? launch_gemm_wide(g, g_force_shape < 0, s) : launch_gemm_mbs_ring(g, shape == 4, s);
+        const bool plain_shape = shape == 2 || shape == 6 || shape == 7;
+        if (shape > 7 || !ring_ok || plain_shape == use_mbs) return MX_EINVAL;  // only reachable through the development switch
+        // (forced through the development switch: 2 = 256 x 256 only, 6 = 256 x 128 only, 7 = 128 x 128 only)
+        if (plain_shape) return launch_gemm_wide(g, g_force_shape < 0 ? 0 : shape == 2 ? 1 : shape == 6 ? 2 : 3, s);
+        return launch_gemm_mbs_ring(g, shape == 4, s);
     }
     if (!fast) return launch_shape<Shape128, Shape128Wide, false>(g, grouped, use_mbs, ragged, s);
     if (shape >= 1) return launch_shape<Shape256x128, Shape256x128Wide, true>(g, grouped, use_mbs, ragged, s);

@@ -3,8 +3,8 @@
 // compiled with the VGPR form of the matrix instructions, and two wavefronts per SIMD let one fold its
 // product in while the other's matrix instructions run.  A wavefront owns 128 x 32 outputs (four A
 // fragments against one B fragment): the 16 per-lane sigma_B values of the B fragment are read from LDS once
-// per stage and serve four products (the 64 x 64 arrangement, kept behind the development switch, reads
-// twice as many).
+// per stage and serve four products.  Problems with too few 256 x 128 tiles for the device take 128 x 128
+// tiles (64 x 32 per wavefront).
 #include "mx_gemm_ring.h"
 
 namespace mx {
@@ -14,10 +14,10 @@ namespace mx {
 // for that operand: the one-sided variants fold a product in with one multiply-add per output instead of two
 // operations.
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s) {
-    if (variant == 1) {  // development: 64 x 64 per wavefront
-        if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<4, 2, 2, 2, 3>>(g, s);
-        if (g.a_mbs) return launch_ring<RingShape<4, 2, 2, 2, 1>>(g, s);
-        return launch_ring<RingShape<4, 2, 2, 2, 2>>(g, s);
+    if (variant == 1) {  // 128 x 128 tiles
+        if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<2, 4, 2, 1, 3>>(g, s);
+        if (g.a_mbs) return launch_ring<RingShape<2, 4, 2, 1, 1>>(g, s);
+        return launch_ring<RingShape<2, 4, 2, 1, 2>>(g, s);
     }
     if (g.a_mbs && g.b_mbs) return launch_ring<RingShape<2, 4, 4, 1, 3>>(g, s);
     if (g.a_mbs) return launch_ring<RingShape<2, 4, 4, 1, 1>>(g, s);

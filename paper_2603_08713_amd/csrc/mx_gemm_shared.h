@@ -23,7 +23,7 @@ struct GemmArgs {
 
 // Main kernels (mx_gemm_ring.h) for K % 512 == 0 and aligned scale and MBS arrays, not grouped: without MBS on
 // 256 x 256 tiles (mx_gemm_wide.hip), with MBS on 256 x 128 tiles (mx_gemm_mbs.hip).
-int launch_gemm_wide(const GemmArgs& g, bool allow_split, hipStream_t s);
+int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s);
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
 // Few activation rows (M <= 64, K <= 8192, otherwise the same conditions), defined in mx_gemm_skinny.hip.
 int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s);

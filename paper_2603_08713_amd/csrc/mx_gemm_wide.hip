@@ -1,4 +1,4 @@
-// Plain (no MBS) MXFP4 GEMM on 256 x 256 tiles: four wavefronts, one per SIMD, each owning a 128 x 128
+// Plain (no MBS) MXFP4 GEMM, on 256 x 256 tiles where the problem has enough of them: four wavefronts, one per SIMD, each owning a 128 x 128
 // block whose 16 accumulator fragments (256 registers) live in the accumulation half of the register
 // file.  Nothing but the matrix cores touches them, so this translation unit is compiled without the
 // VGPR form of the matrix instructions.  The large register tile reads each LDS byte for four instructions.
@@ -13,10 +13,31 @@ namespace mx {
 // fills only part of the chip costs as much as a full one.  The columns of C are therefore split in two
 // launches where that saves time: 256 x 256 tiles for as many columns as make whole rounds, 256 x 128 tiles
 // (half the cost each) for the rest.
-int launch_gemm_wide(const GemmArgs& g, bool allow_split, hipStream_t s) {
+//
+// Problems with too few large tiles for the device take 256 x 128 or 128 x 128 tiles throughout (four
+// wavefronts of 128 x 64 or 64 x 64).
+//
+// tile: 0 = choose, 1 = 256 x 256 only, 2 = 256 x 128 only, 3 = 128 x 128 only (development switch).
+int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s) {
     using Main = RingShape<2, 2, 4, 4, 0>;
     using Tail = RingShape<2, 2, 4, 2, 0>;
+    using Small = RingShape<2, 2, 2, 2, 0>;
     constexpr int64_t kUnits = 256;  // compute units of the device
+    if (tile == 0) {
+        // Tiles run in rounds of one per compute unit.  Cost of a launch in units of a 128 x 128 tile's time:
+        // rounds x tile area / efficiency, the smaller tiles reaching about 0.85 and 0.78 of the large tile's
+        // rate per output (measured; 0.72 is used for the smallest so that an underfilled round of large tiles keeps its edge); the large tile wins ties, and only it is split over two launches.
+        auto rounds = [&](int64_t tm, int64_t tn) {
+            return (((g.M + tm - 1) / tm) * ((g.N + tn - 1) / tn) + kUnits - 1) / kUnits;
+        };
+        const double c256 = 4.0 * rounds(256, 256), c256x128 = 2.0 * rounds(256, 128) / 0.85,
+                     c128 = 1.0 * rounds(128, 128) / 0.72;
+        if (c256x128 < c256 && c256x128 <= c128) tile = 2;
+        else if (c128 < c256) tile = 3;
+    }
+    if (tile == 2) return launch_ring<Tail>(g, s);
+    if (tile == 3) return launch_ring<Small>(g, s);
+    const bool allow_split = tile == 0;
     const int64_t tiles_m = (g.M + Main::TM - 1) / Main::TM, cols = (g.N + Main::TN - 1) / Main::TN;
     auto rounds = [&](int64_t tiles) { return (tiles + kUnits - 1) / kUnits; };
     // cost in half-rounds of giving the first c tile columns to the large tile
