@@ -517,7 +517,7 @@ using Shape256x128 = Shape<4, 2, 4, 4, 16>;
 using Shape256x128Wide = Shape<4, 2, 2, 2, 32>;
 
 constexpr int64_t kRingMinTiles = 8;  // 128 x 128 tiles a problem needs before the main kernels take it
-int g_force_shape = -1;  // development switch: 0 / 1 = generic kernel on 128x128 / 256x128 tiles, 2 / 6 / 7 = main plain kernel on 256x256 / 256x128 / 128x128 tiles, 3 / 4 = main MBS kernel on 256x128 / 128x128 tiles, 5 = few-row kernel
+int g_force_shape = -1;  // development switch: 0 / 1 = generic kernel on 128x128 / 256x128 tiles, 2 / 6 / 7 = main plain kernel on 256x256 / 256x128 / 128x128 tiles, 3 / 4 = main MBS kernel on 256x128 / 128x128 tiles, 5 = few-row kernel, 8 / 9 = general form of the main kernels on 256x128 / 128x128 tiles
 
 int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, const uint8_t* b_codes,
                 const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups, const int64_t* row_offsets,
@@ -574,6 +574,13 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
         const double big = 2.0 * ((t256x128 + 255) / 256), small = 1.25 * ((t128 + 255) / 256);
         shape = big <= small ? 3 : 4;
     }
+    // The general form of the main kernels: any K % 64 == 0, scale rows on even addresses, grouped or not.
+    const bool gen_ok = K > 0 && (K % 64) == 0 && aligned(a_scales, 2) && aligned(b_scales, 2);
+    if (!ring_ok && gen_ok && t128 >= kRingMinTiles) {
+        const double big = 2.0 * ((t256x128 + 255) / 256) / (use_mbs ? 1.0 : 0.85),
+                     small = ((t128 + 255) / 256) / (use_mbs ? 0.8 : 0.72);
+        shape = big <= small ? 8 : 9;
+    }
     const bool skinny_ok = ring_ok && M <= 64 && K <= 8192;
     if (skinny_ok) shape = 5;
     if (g_force_shape >= 0) shape = g_force_shape;
@@ -581,6 +588,11 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
         if (!skinny_ok) return MX_EINVAL;  // only reachable through the development switch
         return launch_gemm_skinny(g, use_mbs, s);
     }
+    if (shape == 8 || shape == 9) {
+        if (!gen_ok) return MX_EINVAL;  // only reachable through the development switch
+        return use_mbs ? launch_gemm_mbs_general(g, shape - 8, s) : launch_gemm_wide_general(g, shape - 8, s);
+    }
+    if (grouped && shape >= 2) return MX_EINVAL;  // only reachable through the development switch
     if (shape >= 2) {
         const bool plain_shape = shape == 2 || shape == 6 || shape == 7;
         if (shape > 7 || !ring_ok || plain_shape == use_mbs) return MX_EINVAL;  // only reachable through the development switch

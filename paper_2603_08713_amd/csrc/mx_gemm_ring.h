@@ -49,20 +49,29 @@ constexpr int kRingGroup = 4;                   // stages per 16-byte piece of a
 constexpr int kRingGroupM = 4;                  // tile-rows walked together for L2 reuse
 constexpr int kSigmaSlots = 4;                  // as many as ring slots: a stage's table index is a compile-time constant
 
-// kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both)
-template <int NWM_, int NWN_, int FM_, int FN_, int kSides_>
+// kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both).
+// kGen: general form.  The fast form wants K % 512 == 0 and 16-byte (E8M0) / 4-byte (MBS) aligned rows, so that a
+// row's bytes of four stages travel as one piece per lane.  The general form takes any K % 64 == 0 (rows of
+// E8M0 bytes start on even addresses, rows of MBS words anywhere) and grouped problems: E8M0 bytes travel as
+// 2-byte pieces (one per lane and pair of blocks), MBS words as single bytes, either one per LDS dword; the
+// last stage may be half empty and the stage count is padded to whole groups with stages that read zeros.
+template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, bool kGen_ = false>
 struct RingShape {
     static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
-    static constexpr bool kMbs = kSides != 0;
+    static constexpr bool kMbs = kSides != 0, kGen = kGen_;
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
     static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
     static constexpr int kCodeDma = kRows / 16 / NW;  // per wavefront and stage: 16 rows x 64 B per load
-    static constexpr int kRowDma = ceil_div(kRows, kWave * NW);  // per wavefront and group: one row per lane
+    // per wavefront and group of four stages: E8M0 bytes (fast: one row per lane; general: 8 rows x 8 pairs
+    // per load) and MBS words (fast: one row per lane; general: 16 rows x 4 words per load)
+    static constexpr int kRowDma = ceil_div(kRows, kWave * NW);
+    static constexpr int kScaleDma = kGen ? kRows / 8 / NW : kRowDma;
+    static constexpr int kM8Dma = kGen ? kRows / 16 / NW : kRowDma;
     static constexpr int kRowsPadded = kRowDma * NW * kWave;
     static constexpr int kCodesStage = kRows * kRingRowStage;
-    static constexpr int kScaleGroup = kRowsPadded * 16;
-    static constexpr int kM8Group = kMbs ? kRowsPadded * 4 : 0;
+    static constexpr int kScaleGroup = kGen ? kRows * 32 : kRowsPadded * 16;
+    static constexpr int kM8Group = !kMbs ? 0 : kGen ? kRows * 16 : kRowsPadded * 4;
     static constexpr int kSigmaStage = kMbs ? kRows * 4 : 0;
     // The small arrays come first: their addresses then fit the 16-bit constant of an LDS instruction.
     static constexpr int kM8Base = 0;
@@ -75,6 +84,7 @@ struct RingShape {
     static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
     static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
     static_assert((TM / 16) % NW == 0 && (TN / 16) % NW == 0, "16-row code loads: operand fixed per load index");
+    static_assert(!kGen || (TM % 128 == 0 && TN % 128 == 0 && kRows % (16 * NW) == 0), "general form: operand fixed per load index");
     static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
     static_assert(NW * kStageRegion <= kLdsBytes, "epilogue staging fits the LDS of the main loop");
     static_assert(FM * FN * 16 <= 256, "accumulators fill at most the accumulation registers");
@@ -84,7 +94,7 @@ struct RingShape {
 template <typename S>
 __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, NT = S::NT, kRows = S::kRows;
-    constexpr int kCodeDma = S::kCodeDma, kRowDma = S::kRowDma;
+    constexpr int kCodeDma = S::kCodeDma, kRowDma = S::kRowDma, kScaleDma = S::kScaleDma, kM8Dma = S::kM8Dma;
     constexpr bool kMbs = S::kMbs, kSigmaA = (S::kSides & 1) != 0, kSigmaB = (S::kSides & 2) != 0;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -99,13 +109,36 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     const int band_rows = min(g.tiles_m - first_m, kRingGroupM);
     const int tm = first_m + (linear % band) % band_rows;
     const int tn = (linear % band) / band_rows;
-    const int64_t a_row0 = (int64_t)tm * TM, b_row0 = (int64_t)tn * TN;
+    // Rows of A and C this tile covers and the rows of B it multiplies with.  Grouped (general form only):
+    // tile-rows are counted group by group; group e owns rows row_offsets[e] .. row_offsets[e + 1] - 1 and
+    // the e-th of the stacked [N, K] weights.
+    int64_t a_row0 = (int64_t)tm * TM, a_end = g.M, b_row0 = (int64_t)tn * TN, b_end = g.N;
+    if constexpr (S::kGen) {
+        if (g.num_groups > 0) {
+            int e = 0, first = 0;  // first tile-row of group e
+            int64_t lo = g.row_offsets[0], hi = lo;
+            for (;; ++e) {
+                if (e == g.num_groups) return;  // tile-rows beyond the last group (the grid is an upper bound)
+                hi = g.row_offsets[e + 1];
+                const int rows_e = (int)((hi - lo + TM - 1) / TM);
+                if (tm < first + rows_e) break;
+                first += rows_e;
+                lo = hi;
+            }
+            a_row0 = lo + (int64_t)(tm - first) * TM;
+            a_end = hi;
+            b_row0 = (int64_t)e * g.N + (int64_t)tn * TN;
+            b_end = (int64_t)(e + 1) * g.N;
+        }
+    }
 
     const int K = (int)g.K;
-    const int row_bytes = K >> 1, scale_bytes = K >> 5, nmac = K / kMacro;
-    const int nstages = K / kRingStageK, ngroups = nstages / kRingGroup;
-    const Operand opa = make_operand(g.a_codes, g.a_scales, g.a_mbs, a_row0, g.M, TM, g.K);
-    const Operand opb = make_operand(g.b_codes, g.b_scales, g.b_mbs, b_row0, g.N, TN, g.K);
+    // general form: K in stages of 128 (the last one possibly half), padded to whole groups of four stages
+    const int row_bytes = K >> 1, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro;
+    const int nstages = S::kGen ? (nmac + kRingGroup - 1) / kRingGroup * kRingGroup : K / kRingStageK;
+    const int ngroups = nstages / kRingGroup;
+    const Operand opa = make_operand(g.a_codes, g.a_scales, g.a_mbs, a_row0, a_end, TM, g.K);
+    const Operand opb = make_operand(g.b_codes, g.b_scales, g.b_mbs, b_row0, b_end, TN, g.K);
 
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -121,8 +154,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         const int row = ((i * NW + w) * 16 + (l >> 2)) - (i * NW * 16 < TM ? 0 : TM);  // row within its operand
         code_off[i] = row * row_bytes + (((l & 3) ^ ((row >> 2) & 3)) * 16);
     }
-    // Per-row loads: load i of wavefront w serves row (i * NW + w) * 64 + l with the 16 E8M0 bytes, or the 4
-    // MBS words, of a group of four stages; rows past the tile are padding and read zero.
+    // Per-row loads, fast form: load i of wavefront w serves row (i * NW + w) * 64 + l with the 16 E8M0 bytes, or
+    // the 4 MBS words, of a group of four stages; rows past the tile are padding and read zero.
     int scale_off[kRowDma], m8_off[kRowDma];
     bool row_is_a[kRowDma];
 #pragma unroll
@@ -133,6 +166,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         scale_off[i] = grow >= kRows ? kOob : row * scale_bytes;
         m8_off[i] = grow >= kRows ? kOob : row * nmac;
     }
+    // General form: E8M0 load i of wavefront w serves rows (i * NW + w) * 8 .. + 7, lane l pair l % 8 of the
+    // group's 8 pairs of bytes of row l / 8; MBS load i serves rows (i * NW + w) * 16 .. + 15, lane l word
+    // l % 4 of row l / 4.
+    const int gen_code_col = ((l & 3) ^ ((l >> 4) & 3)) * 16;  // this lane's chunk of the 64-byte stage piece
+    const int gen_scale_off = (w * 8 + (l >> 3)) * scale_bytes + (l & 7) * 2, gen_scale_col = (l & 7) * 2;
+    const int gen_m8_off = (w * 16 + (l >> 2)) * nmac + (l & 3), gen_m8_col = l & 3;
 
     // A stage or group past the end of K is never used; its loads (the pipeline issues them regardless, into
     // slots that are no longer read) fetch the last one again, so that no address leaves the operands.
@@ -141,23 +180,49 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     auto dma_code = [&](int s, auto i_) {  // load i of the codes of stage s
         constexpr int i = decltype(i_)::value;
         uint8_t* dst = smem + S::kCodesBase + (s % kRingSlots) * S::kCodesStage + (i * NW + w) * 1024;
-        const int voff = code_off[i];
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 16 < TM ? opa.codes : opb.codes, (lds_ptr_t)dst, 16, voff,
-                                                 min(s, nstages - 1) * kRingRowStage, 0, 0);
+        int voff = code_off[i];
+        if constexpr (S::kGen) {
+            // chunks at or past the end of K (half of the last stage, all of a padding stage) read zero
+            if (s * kRingRowStage + gen_code_col >= row_bytes) voff = kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 16 < TM ? opa.codes : opb.codes, (lds_ptr_t)dst, 16, voff,
+                                                     s * kRingRowStage, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i * NW * 16 < TM ? opa.codes : opb.codes, (lds_ptr_t)dst, 16, voff,
+                                                     min(s, nstages - 1) * kRingRowStage, 0, 0);
+        }
     };
     auto dma_scale = [&](int grp, auto i_) {  // load i of the E8M0 bytes of stages 4 grp .. 4 grp + 3
         constexpr int i = decltype(i_)::value;
-        uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 1024;
-        const int voff = scale_off[i];
-        const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.scales : opb.scales;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 16, voff, min(grp, ngroups - 1) * 16, 0, 0);
+        if constexpr (S::kGen) {
+            constexpr bool is_a = i * NW * 8 < TM;
+            uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 256;
+            // (the row goes into the per-lane offset, which is what the hardware checks against the valid rows)
+            const int in_range = gen_scale_off + (i * NW * 8 - (is_a ? 0 : TM)) * scale_bytes;
+            const int voff = grp * 16 + gen_scale_col < scale_bytes ? in_range : kOob;  // past K: zero
+            const __amdgpu_buffer_rsrc_t rsrc = is_a ? opa.scales : opb.scales;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 2, voff, grp * 16, 0, 0);
+        } else {
+            uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 1024;
+            const int voff = scale_off[i];
+            const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.scales : opb.scales;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 16, voff, min(grp, ngroups - 1) * 16, 0, 0);
+        }
     };
     auto dma_m8 = [&](int grp, auto i_) {  // load i of the MBS words of stages 4 grp .. 4 grp + 3
         constexpr int i = decltype(i_)::value;
-        uint8_t* dst = smem + S::kM8Base + (grp & 1) * S::kM8Group + (i * NW + w) * 256;
-        const int voff = m8_off[i];
-        const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.mbs : opb.mbs;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 4, voff, min(grp, ngroups - 1) * 4, 0, 0);
+        if constexpr (S::kGen) {
+            constexpr bool is_a = i * NW * 16 < TM;
+            uint8_t* dst = smem + S::kM8Base + (grp & 1) * S::kM8Group + (i * NW + w) * 256;
+            const int in_range = gen_m8_off + (i * NW * 16 - (is_a ? 0 : TM)) * nmac;
+            const int voff = grp * 4 + gen_m8_col < nmac ? in_range : kOob;  // past K: zero
+            const __amdgpu_buffer_rsrc_t rsrc = is_a ? opa.mbs : opb.mbs;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 1, voff, grp * 4, 0, 0);
+        } else {
+            uint8_t* dst = smem + S::kM8Base + (grp & 1) * S::kM8Group + (i * NW + w) * 256;
+            const int voff = m8_off[i];
+            const __amdgpu_buffer_rsrc_t rsrc = row_is_a[i] ? opa.mbs : opb.mbs;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 4, voff, min(grp, ngroups - 1) * 4, 0, 0);
+        }
     };
     // MBS words of stage s (landed and published) -> fp32 sigma = 1/F, F = 1 + m8/256 exact, reciprocal
     // within an ulp.  Thread p serves row p; threads past the last row redo row 0 and store to the padding
@@ -170,7 +235,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             const int q = i * NT + tid;  // (a side without words reads zero and stores sigma = 1, which nobody reads)
             const bool live = kRows % NT == 0 || q < kRows;
             const int p = live ? q : 0;
-            const uint32_t m8 = (raw[p] >> (8 * (s % kRingGroup))) & 0xFFu;
+            // fast form: a row's four words in one dword; general form: one word per dword, [row][4]
+            const uint32_t m8 = S::kGen ? raw[p * kRingGroup + s % kRingGroup] & 0xFFu : (raw[p] >> (8 * (s % kRingGroup))) & 0xFFu;
             float* dst = live ? sig + p : reinterpret_cast<float*>(smem + S::kDummy);
             *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
         }
@@ -205,7 +271,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             asm volatile("" : "+v"(code_base[o][kk][1]));
         }
     }
-    const int lane_scale = lr * 16 + lh * 2;
+    const int lane_scale = S::kGen ? lr * 32 + lh * 4 : lr * 16 + lh * 2;
 
     // LDS read `idx` of the kReads that fetch the fragments of a stage in ring slot `slot`: per fragment (A's
     // FM, then B's FN) the two 16-byte code pieces and the 16-bit scale pair.
@@ -221,8 +287,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             else f.n[q][part] = v;
         } else {
             const int row0 = is_m ? (wm * FM + q) * 32 : TM + (wn * FN + q) * 32;  // in the A-then-B row space
-            const uint32_t v = *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
-                                                 (s % kRingGroup) * 4 + lane_scale + row0 * 16);
+            // fast form: [row][16 bytes of the group]; general form: [row][8 pairs], one pair per dword
+            const uint32_t v = S::kGen ? *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
+                                                          (s % kRingGroup) * 8 + lane_scale + row0 * 32)
+                                       : *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
+                                                          (s % kRingGroup) * 4 + lane_scale + row0 * 16);
             if constexpr (is_m) f.scl_m[q] = v;
             else f.scl_n[q] = v;
         }
@@ -255,14 +324,14 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // Every stage requests the codes of stage s + 4; the first stage of a group (phase 0) also the scales of
     // the next group, into the slot the previous group left two stages ago; the third (phase 2) the MBS
     // words of the group after next, which have to be on hand two stages before their first use.
-    constexpr int kLoads[4] = {kCodeDma + kRowDma, kCodeDma, kCodeDma + (kMbs ? kRowDma : 0), kCodeDma};
-    static_assert(kRingSlots * kCodeDma + 3 * kRowDma < 64, "vmcnt is a 6-bit counter");
+    constexpr int kLoads[4] = {kCodeDma + kScaleDma, kCodeDma, kCodeDma + (kMbs ? kM8Dma : 0), kCodeDma};
+    static_assert(kRingSlots * kCodeDma + kScaleDma + 2 * kM8Dma < 64, "vmcnt is a 6-bit counter");
 
     // ---- prologue: fill the ring, fetch the operands of stage 0 --------------------------------------
-    static_for<kRowDma>([&](auto i_) { dma_scale(0, i_); });
+    static_for<kScaleDma>([&](auto i_) { dma_scale(0, i_); });
     if constexpr (kMbs) {
-        static_for<kRowDma>([&](auto i_) { dma_m8(0, i_); });
-        static_for<kRowDma>([&](auto i_) { dma_m8(1, i_); });
+        static_for<kM8Dma>([&](auto i_) { dma_m8(0, i_); });
+        static_for<kM8Dma>([&](auto i_) { dma_m8(1, i_); });
     }
     static_for<kRingSlots * kCodeDma>([&](auto t_) {
         constexpr int t = decltype(t_)::value;
@@ -448,7 +517,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 const int row = decltype(p_)::value * rows_per_pass + rd_row;
                 const v4i v = *reinterpret_cast<const v4i*>(stg + row * pitch + rd_chunk * 16);
                 const int64_t m = m0 + i * 32 + row;
-                if (m < g.M && n < g.N) {
+                if (m < a_end && n < g.N) {
                     uint8_t* o = static_cast<uint8_t*>(g.C) + (m * g.ldc + n) * esz;
                     if (whole) {
                         *reinterpret_cast<v4i*>(o) = v;
@@ -471,7 +540,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 
 template <typename S>
 int launch_ring(GemmArgs g, hipStream_t s) {
-    const int64_t tiles_m = (g.M + S::TM - 1) / S::TM, tiles_n = (g.N + S::TN - 1) / S::TN;
+    // grouped: every group may end with a partial tile-row, so this is an upper bound (the surplus exits)
+    const int64_t tiles_m = g.num_groups > 0 ? g.M / S::TM + g.num_groups : (g.M + S::TM - 1) / S::TM;
+    const int64_t tiles_n = (g.N + S::TN - 1) / S::TN;
+    if (g.num_groups > 0 && !S::kGen) return MX_EINVAL;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;

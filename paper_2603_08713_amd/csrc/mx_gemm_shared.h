@@ -25,6 +25,10 @@ struct GemmArgs {
 // 256 x 256 tiles (mx_gemm_wide.hip), with MBS on 256 x 128 tiles (mx_gemm_mbs.hip).
 int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s);
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
+// The same kernels in their general form (K % 64 == 0, 2-byte aligned scale arrays, grouped or not), defined in
+// mx_gemm_general.hip (with MBS) and mx_gemm_wide.hip (without).  tile: 0 = 256 x 128, 1 = 128 x 128.
+int launch_gemm_mbs_general(const GemmArgs& g, int tile, hipStream_t s);
+int launch_gemm_wide_general(const GemmArgs& g, int tile, hipStream_t s);
 // Few activation rows (M <= 64, K <= 8192, otherwise the same conditions), defined in mx_gemm_skinny.hip.
 int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s);
 int launch_gemm_skinny_fused(const GemmArgs& g, const void* x_bf16, int64_t ldx, int rule, bool a_mbs, hipStream_t s);

@@ -60,4 +60,11 @@ int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s) {
     return launch_ring<Tail>(tail, s);
 }
 
+// The general form (mx_gemm_ring.h: any K % 64 == 0, 2-byte aligned scale arrays, grouped or not) without MBS.
+// tile: 0 = 256 x 128, 1 = 128 x 128.
+int launch_gemm_wide_general(const GemmArgs& g, int tile, hipStream_t s) {
+    if (tile == 0) return launch_ring<RingShape<2, 2, 4, 2, 0, true>>(g, s);
+    return launch_ring<RingShape<2, 2, 2, 2, 0, true>>(g, s);
+}
+
 }  // namespace mx
