@@ -156,6 +156,7 @@ def main():
         out["extras"]["square_shapes"] = square_shapes(mx, torch, synth, np, metrics)
         out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
         out["extras"]["qsnr_db_gpu_weights"] = qsnr_weights_gpu(mx, torch, xw[0][:QSNR_ROWS])
+        out["extras"]["qsnr_ab_db_gpu"] = qsnr_ab_gpu(mx, torch, xa[0], xw[0])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, a_bits, w_bits, flops, metrics)
     print(json.dumps(out))
@@ -175,6 +176,31 @@ def qsnr_ladder_gpu(mx, torch, x):
         back = mx.mx_dequantize(q[0], q[1], q[2] if mbs else None, "f32").to(torch.float64)
         res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
     res["sample"] = "first %d rows of A" % QSNR_ROWS
+    return res
+
+
+QSNR_AB_ROWS, QSNR_AB_COLS = 64, 2048   # output sample of QSNR(AB): rows of A x rows of W
+QSNR_AB_LADDER = (("mxfp4", "ocp", "none"), ("+oas", "oas", "none"), ("+oas+mbs-s", "oas", "static"),
+                  ("+oas+mbs-h", "oas", "hybrid"))
+
+
+def qsnr_ab_gpu(mx, torch, xa, xw):
+    """QSNR (dB) of the product (Eq. 2: reference = the bf16 tensors multiplied in fp64, here with torch) for
+    plain MXFP4, +OAS, +OAS+MBS-S and MBS-Hybrid (searched words for W, static for A), every operand quantized
+    and multiplied by the HIP kernels (fp32 output)."""
+    a, w = xa[:QSNR_AB_ROWS], xw[:QSNR_AB_COLS]
+    ref = a.to(torch.float64) @ w.to(torch.float64).T
+    res = {}
+    for name, rule, mbs in QSNR_AB_LADDER:
+        if mbs == "none":
+            qa, qw = mx.mx_quantize(a, rule), mx.mx_quantize(w, rule)
+            c = mx.mx_gemm(qa[0], qa[1], qw[0], qw[1], "f32")
+        else:
+            qa = mx.mx_quantize_mbs(a, rule)
+            qw = mx.mx_quantize_mbs(w, rule) if mbs == "static" else mx.mx_quantize_mbs_dynamic(w, rule)
+            c = mx.mx_gemm_mbs(*qa, *qw, "f32")
+        res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - c.to(torch.float64)) ** 2).sum())), 3)
+    res["sample"] = "first %d rows of A x first %d rows of W" % (QSNR_AB_ROWS, QSNR_AB_COLS)
     return res
 
 
@@ -342,9 +368,17 @@ def cpu_baseline(np, a_bits, w_bits, flops, metrics):
     for name, q in (("+oas", oracle.quantize(xw, "oas")), ("+oas+mbs-s", oracle.quantize(xw, "oas", mbs=True)),
                     ("+oas+mbs-d", oracle.quantize_mbs_dynamic(xw, "oas"))):
         ladder_w[name] = round(oracle.qsnr_db(refw, oracle.dequantize(q[0], q[1], q[2])), 3)
+    a_s, w_s = a_bits[:QSNR_AB_ROWS], w_bits[:QSNR_AB_COLS]
+    ref_ab = oracle.matmul_bf16(a_s, w_s)
+    ladder_ab = {}
+    for name, rule, mbs in QSNR_AB_LADDER:
+        qa_ = oracle.quantize(a_s, rule, mbs=mbs != "none")
+        qw_ = oracle.quantize_mbs_dynamic(w_s, rule) if mbs == "hybrid" else oracle.quantize(w_s, rule, mbs=mbs != "none")
+        ladder_ab[name] = round(oracle.qsnr_db(ref_ab, oracle.gemm(qa_, qw_)), 3)
     return {
         "qsnr_db_oracle": ladder,
         "qsnr_db_oracle_weights": ladder_w,
+        "qsnr_ab_db_oracle": ladder_ab,
         "value": round(flops / est_step_s / 1e12, 6),
         "unit": "TFLOP/s",
         "cores": threads,
