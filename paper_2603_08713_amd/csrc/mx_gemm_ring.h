@@ -479,6 +479,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             stage(s + 3, fb, fa, P3{}, late_, No{});
         }
     };
+    // The loads in flight when a stage starts are, in the steady state, those the last two stages issued, and
+    // the stage waits for all but that many.  Stage 0 starts with the prologue's loads of stages 2 and 3 in
+    // flight instead: with MBS that is fewer than two steady-state stages issue, so its wait would let a load
+    // of stage 1 slip past the barrier that publishes stage 1.  Wait for stage 1 here.
+    __builtin_amdgcn_s_waitcnt(wait_imm((kRingSlots - 2) * kCodeDma));
     // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
     // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
     if (NW == 8 || w % 4 < 2) run(std::integral_constant<int, 0>{});

@@ -229,6 +229,36 @@ def test_gemm_quantize_a_fused_edge_values(mx, oracle):
             assert np.array_equal(g[~np.isnan(g)], t2[~np.isnan(t2)]), "rule=%s a_mbs=%s" % (rule, a_mbs)
 
 
+def test_gemm_first_launch_of_a_process_matches_later_ones(mx):
+    """Regression: a kernel's very first launch in a process runs with cold instruction caches and address
+    translation, so its wavefronts drift apart far more than later; the prologue of the main kernel once let a
+    load of stage 1 slip past the barrier that publishes it, which showed as a wrong patch of C in that first
+    launch only.  A fresh process multiplies a large problem twice (with MBS and without) and compares."""
+    import os
+    import subprocess
+    import sys
+
+    code = """
+import torch, paper_2603_08713_amd as mx
+torch.manual_seed(0)
+a = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+w = (torch.randn(28672, 8192, device="cuda") * 0.02).to(torch.bfloat16)
+qa, qw = mx.mx_quantize_mbs(a, "oas"), mx.mx_quantize_mbs(w, "oas")
+first = mx.mx_gemm_mbs(*qa, *qw, "bf16")
+again = mx.mx_gemm_mbs(*qa, *qw, "bf16")
+p1 = mx.mx_gemm(qa[0], qa[1], qw[0], qw[1], "bf16")
+p2 = mx.mx_gemm(qa[0], qa[1], qw[0], qw[1], "bf16")
+torch.cuda.synchronize()
+assert torch.equal(first, again), int((first != again).sum())
+assert torch.equal(p1, p2), int((p1 != p2).sum())
+print("first launch ok")
+"""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, PYTHONPATH=root + os.pathsep + os.environ.get("PYTHONPATH", ""))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=280)
+    assert out.returncode == 0 and "first launch ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+
+
 def test_hip_graph_replay_matches_eager(mx, oracle):
     """The entry points launch on the caller's stream, allocate nothing and never synchronise, so a step can be
     captured in a HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce
