@@ -251,6 +251,18 @@ p2 = mx.mx_gemm(qa[0], qa[1], qw[0], qw[1], "bf16")
 torch.cuda.synchronize()
 assert torch.equal(first, again), int((first != again).sum())
 assert torch.equal(p1, p2), int((p1 != p2).sum())
+# the other forms of the kernel, each launched for the first time here: 128 x 128 tiles, and the general form
+# (K = 2880) plain, with MBS and grouped
+for m, n, k in ((2048, 2048, 8192), (8192, 5760, 2880)):
+    qa, qw = mx.mx_quantize_mbs(a[:m, :k].contiguous(), "oas"), mx.mx_quantize_mbs(w[:n, :k].contiguous(), "oas")
+    for fn in (lambda: mx.mx_gemm_mbs(*qa, *qw, "bf16"), lambda: mx.mx_gemm(qa[0], qa[1], qw[0], qw[1], "bf16")):
+        c1 = fn(); c2 = fn()
+        torch.cuda.synchronize()
+        assert torch.equal(c1, c2), (m, n, k, int((c1 != c2).sum()))
+off = torch.tensor([0, 3000, 3000, 8192], dtype=torch.int64, device="cuda")
+g1 = mx.mx_gemm_mbs_grouped(*qa, *qw, off, 1920, "bf16"); g2 = mx.mx_gemm_mbs_grouped(*qa, *qw, off, 1920, "bf16")
+torch.cuda.synchronize()
+assert torch.equal(g1, g2), int((g1 != g2).sum())
 print("first launch ok")
 """
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
