@@ -1,5 +1,6 @@
 // Block-scaled MXFP4 GEMM  C = A * B^T  on v_mfma_scale_f32_32x32x64_f8f6f4: the main kernel template
-// (private; instantiated by mx_gemm_wide.hip without MBS and by mx_gemm_mbs.hip with MBS).
+// (private; instantiated by mx_gemm_wide.hip without MBS, by mx_gemm_mbs.hip with MBS and by
+// mx_gemm_general.hip in its general form with MBS).
 //
 // What limits the instruction in practice is instruction issue and data movement, not the matrix pipeline:
 //   * every scaled matrix instruction keeps the vector-ALU issue port busy for about 12 clocks whatever its
@@ -23,13 +24,14 @@
 // slot stage s has just left: three stages are in flight, enough to cover a miss in the L2.  One
 // workgroup barrier per stage publishes stage s + 1 and, because every wavefront has finished reading
 // stage s by then, frees its slot.  E8M0 bytes and MBS words travel per group of four stages: a row's 16
-// scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each).
+// scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each); the general form, for K
+// and row addresses that do not allow such pieces, is described at RingShape.
 //
 // MBS (Sec. 4.3.2, App. E): the two instructions of a fragment pair start from a zero accumulator and
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
 // The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
-// one of three LDS tables.  A wavefront folds a product in while the next pair's instructions run, and
+// one of four LDS tables.  A wavefront folds a product in while the next pair's instructions run, and
 // the SIMD's other wavefront fills what gaps remain.
 //
 // LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
