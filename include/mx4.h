@@ -107,7 +107,8 @@ int mx_dequantize(const uint8_t* codes, const uint8_t* scales, const uint8_t* mb
 
 /* Plain MXFP4 GEMM, C[M,N] = A[M,K] * B[N,K]^T with A, B given as codes + E8M0 scales
  * (the baseline the MBS kernel is measured against, Sec. 5.3 / Tab. 4).  fp32 accumulation on the
- * block-scaled MFMA; C is written as c_dtype with leading dimension ldc >= N (elements). */
+ * block-scaled MFMA; C is written as c_dtype with leading dimension ldc >= N (elements).
+ * Limits (all GEMM entry points): K <= 2^22, M and N <= 2^30, else MX_EINVAL. */
 int mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
             const uint8_t* b_codes, const uint8_t* b_scales,
             int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,

@@ -526,7 +526,8 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     if (M < 0 || N < 0 || K < 0 || (K % kBlock) != 0 || ldc < N) return MX_EINVAL;
     if (c_dtype != MX_OUT_F32 && c_dtype != MX_OUT_BF16) return MX_EINVAL;
     if (grouped && num_groups < 0) return MX_EINVAL;
-    if (K > (int64_t)1 << 24 || M > (int64_t)1 << 30 || N > (int64_t)1 << 30 ||
+    // (a tile's rows times the bytes of a row must fit the 32-bit offsets of the buffer loads)
+    if (K > (int64_t)1 << 22 || M > (int64_t)1 << 30 || N > (int64_t)1 << 30 ||
         (grouped && (int64_t)num_groups * N > (int64_t)1 << 40))
         return MX_EINVAL;
     if (M == 0 || N == 0 || (grouped && num_groups == 0)) return MX_OK;
