@@ -52,27 +52,29 @@ constexpr int kRingGroupM = 4;                  // tile-rows walked together for
 constexpr int kSigmaSlots = 4;                  // as many as ring slots: a stage's table index is a compile-time constant
 
 // kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both).
-// kGen: general form.  The fast form wants K % 512 == 0 and 16-byte (E8M0) / 4-byte (MBS) aligned rows, so that a
-// row's bytes of four stages travel as one piece per lane.  The general form takes any K % 64 == 0 (rows of
-// E8M0 bytes start on even addresses, rows of MBS words anywhere) and grouped problems: E8M0 bytes travel as
-// 2-byte pieces (one per lane and pair of blocks), MBS words as single bytes, either one per LDS dword; the
-// last stage may be half empty and the stage count is padded to whole groups with stages that read zeros.
-template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, bool kGen_ = false>
+// kForm: 0 = fast form, which wants K % 512 == 0 and 16-byte (E8M0) / 4-byte (MBS) aligned rows, so that a row's
+// bytes of four stages travel as one piece per lane.  1, 2 = general forms for everything else, grouped problems
+// included: E8M0 bytes travel as 2-byte pieces (1: any K % 64 == 0, rows of E8M0 bytes on even addresses; one
+// piece per lane and pair of blocks) or as single bytes (2: any K % 32 == 0, any address), MBS words as single
+// bytes, each piece in an LDS dword of its own; the last stage may be partly empty and the stage count is
+// padded to whole groups with stages that read zeros.
+template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, int kForm_ = 0>
 struct RingShape {
     static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
-    static constexpr bool kMbs = kSides != 0, kGen = kGen_;
+    static constexpr bool kMbs = kSides != 0, kGen = kForm_ != 0, kBytes = kForm_ == 2;
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
     static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
     static constexpr int kCodeDma = kRows / 16 / NW;  // per wavefront and stage: 16 rows x 64 B per load
-    // per wavefront and group of four stages: E8M0 bytes (fast: one row per lane; general: 8 rows x 8 pairs
-    // per load) and MBS words (fast: one row per lane; general: 16 rows x 4 words per load)
+    // per wavefront and group of four stages: E8M0 bytes (fast: one row per lane; general: 8 rows x 8 pairs or
+    // 4 rows x 16 bytes per load) and MBS words (fast: one row per lane; general: 16 rows x 4 words per load)
     static constexpr int kRowDma = ceil_div(kRows, kWave * NW);
-    static constexpr int kScaleDma = kGen ? kRows / 8 / NW : kRowDma;
+    static constexpr int kScaleRowsPerLoad = kBytes ? 4 : 8;  // general forms
+    static constexpr int kScaleDma = kGen ? kRows / kScaleRowsPerLoad / NW : kRowDma;
     static constexpr int kM8Dma = kGen ? kRows / 16 / NW : kRowDma;
     static constexpr int kRowsPadded = kRowDma * NW * kWave;
     static constexpr int kCodesStage = kRows * kRingRowStage;
-    static constexpr int kScaleGroup = kGen ? kRows * 32 : kRowsPadded * 16;
+    static constexpr int kScaleGroup = kBytes ? kRows * 64 : kGen ? kRows * 32 : kRowsPadded * 16;
     static constexpr int kM8Group = !kMbs ? 0 : kGen ? kRows * 16 : kRowsPadded * 4;
     static constexpr int kSigmaStage = kMbs ? kRows * 4 : 0;
     // The small arrays come first: their addresses then fit the 16-bit constant of an LDS instruction.
@@ -86,7 +88,7 @@ struct RingShape {
     static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
     static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
     static_assert((TM / 16) % NW == 0 && (TN / 16) % NW == 0, "16-row code loads: operand fixed per load index");
-    static_assert(!kGen || (TM % 128 == 0 && TN % 128 == 0 && kRows % (16 * NW) == 0), "general form: operand fixed per load index");
+    static_assert(!kGen || (TM % 128 == 0 && TN % 128 == 0 && kRows % (16 * NW) == 0), "general forms: operand fixed per load index");
     static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
     static_assert(NW * kStageRegion <= kLdsBytes, "epilogue staging fits the LDS of the main loop");
     static_assert(FM * FN * 16 <= 256, "accumulators fill at most the accumulation registers");
@@ -168,11 +170,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         scale_off[i] = grow >= kRows ? kOob : row * scale_bytes;
         m8_off[i] = grow >= kRows ? kOob : row * nmac;
     }
-    // General form: E8M0 load i of wavefront w serves rows (i * NW + w) * 8 .. + 7, lane l pair l % 8 of the
-    // group's 8 pairs of bytes of row l / 8; MBS load i serves rows (i * NW + w) * 16 .. + 15, lane l word
-    // l % 4 of row l / 4.
+    // General forms: E8M0 load i of wavefront w serves rows (i * NW + w) * 8 .. + 7, lane l pair l % 8 of the
+    // group's 8 pairs of bytes of row l / 8 (or rows (i * NW + w) * 4 .. + 3, lane l byte l % 16 of row l / 16);
+    // MBS load i serves rows (i * NW + w) * 16 .. + 15, lane l word l % 4 of row l / 4.
     const int gen_code_col = ((l & 3) ^ ((l >> 4) & 3)) * 16;  // this lane's chunk of the 64-byte stage piece
-    const int gen_scale_off = (w * 8 + (l >> 3)) * scale_bytes + (l & 7) * 2, gen_scale_col = (l & 7) * 2;
+    const int gen_scale_col = S::kBytes ? l & 15 : (l & 7) * 2;
+    const int gen_scale_off = (S::kBytes ? w * 4 + (l >> 4) : w * 8 + (l >> 3)) * scale_bytes + gen_scale_col;
     const int gen_m8_off = (w * 16 + (l >> 2)) * nmac + (l & 3), gen_m8_col = l & 3;
 
     // A stage or group past the end of K is never used; its loads (the pipeline issues them regardless, into
@@ -196,13 +199,14 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     auto dma_scale = [&](int grp, auto i_) {  // load i of the E8M0 bytes of stages 4 grp .. 4 grp + 3
         constexpr int i = decltype(i_)::value;
         if constexpr (S::kGen) {
-            constexpr bool is_a = i * NW * 8 < TM;
+            constexpr int kPer = S::kScaleRowsPerLoad;
+            constexpr bool is_a = i * NW * kPer < TM;
             uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 256;
             // (the row goes into the per-lane offset, which is what the hardware checks against the valid rows)
-            const int in_range = gen_scale_off + (i * NW * 8 - (is_a ? 0 : TM)) * scale_bytes;
+            const int in_range = gen_scale_off + (i * NW * kPer - (is_a ? 0 : TM)) * scale_bytes;
             const int voff = grp * 16 + gen_scale_col < scale_bytes ? in_range : kOob;  // past K: zero
             const __amdgpu_buffer_rsrc_t rsrc = is_a ? opa.scales : opb.scales;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 2, voff, grp * 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, S::kBytes ? 1 : 2, voff, grp * 16, 0, 0);
         } else {
             uint8_t* dst = smem + S::kScaleBase + (grp & 1) * S::kScaleGroup + (i * NW + w) * 1024;
             const int voff = scale_off[i];
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             asm volatile("" : "+v"(code_base[o][kk][1]));
         }
     }
-    const int lane_scale = S::kGen ? lr * 32 + lh * 4 : lr * 16 + lh * 2;
+    const int lane_scale = S::kBytes ? lr * 64 + lh * 8 : S::kGen ? lr * 32 + lh * 4 : lr * 16 + lh * 2;
 
     // LDS read `idx` of the kReads that fetch the fragments of a stage in ring slot `slot`: per fragment (A's
     // FM, then B's FN) the two 16-byte code pieces and the 16-bit scale pair.
@@ -289,11 +293,18 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             else f.n[q][part] = v;
         } else {
             const int row0 = is_m ? (wm * FM + q) * 32 : TM + (wn * FN + q) * 32;  // in the A-then-B row space
-            // fast form: [row][16 bytes of the group]; general form: [row][8 pairs], one pair per dword
-            const uint32_t v = S::kGen ? *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
-                                                          (s % kRingGroup) * 8 + lane_scale + row0 * 32)
-                                       : *(lds_half_ptr_t)(smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup +
-                                                          (s % kRingGroup) * 4 + lane_scale + row0 * 16);
+            // fast form: [row][16 bytes of the group]; general forms: [row][8 pairs], one pair per dword, or
+            // [row][16 bytes], one byte per dword (the lane's two bytes come as two dwords and are packed)
+            uint32_t v;
+            const uint8_t* grp_base = smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup;
+            if constexpr (S::kBytes) {
+                const uint2 two = *reinterpret_cast<const uint2*>(grp_base + (s % kRingGroup) * 16 + lane_scale + row0 * 64);
+                v = (two.x & 0xFFu) | ((two.y & 0xFFu) << 8);
+            } else if constexpr (S::kGen) {
+                v = *(lds_half_ptr_t)(grp_base + (s % kRingGroup) * 8 + lane_scale + row0 * 32);
+            } else {
+                v = *(lds_half_ptr_t)(grp_base + (s % kRingGroup) * 4 + lane_scale + row0 * 16);
+            }
             if constexpr (is_m) f.scl_m[q] = v;
             else f.scl_n[q] = v;
         }

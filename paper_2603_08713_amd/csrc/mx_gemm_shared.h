@@ -21,14 +21,16 @@ struct GemmArgs {
     int vec_store16;             // C rows allow 16-byte vector stores
 };
 
-// Main kernels (mx_gemm_ring.h) for K % 512 == 0 and aligned scale and MBS arrays, not grouped: without MBS on
-// 256 x 256 tiles (mx_gemm_wide.hip), with MBS on 256 x 128 tiles (mx_gemm_mbs.hip).
+// Main kernels (mx_gemm_ring.h), fast form: K % 512 == 0 and aligned scale and MBS arrays, not grouped; without MBS
+// (mx_gemm_wide.hip: 256 x 256, 256 x 128 or 128 x 128 tiles) and with MBS (mx_gemm_mbs.hip: 256 x 128 or 128 x 128).
 int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s);
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
-// The same kernels in their general form (K % 64 == 0, 2-byte aligned scale arrays, grouped or not), defined in
-// mx_gemm_general.hip (with MBS) and mx_gemm_wide.hip (without).  tile: 0 = 256 x 128, 1 = 128 x 128.
-int launch_gemm_mbs_general(const GemmArgs& g, int tile, hipStream_t s);
-int launch_gemm_wide_general(const GemmArgs& g, int tile, hipStream_t s);
+// The same kernels in their general forms (any K % 32 == 0, any alignment of the scale arrays, grouped or not),
+// defined in mx_gemm_general.hip (with MBS) and mx_gemm_wide.hip (without).  tile: 0 = 256 x 128, 1 = 128 x 128;
+// bytes: E8M0 bytes fetched one at a time (needed when K % 64 != 0 or a scale array sits on an odd address;
+// 128 x 128 tiles only).
+int launch_gemm_mbs_general(const GemmArgs& g, int tile, bool bytes, hipStream_t s);
+int launch_gemm_wide_general(const GemmArgs& g, int tile, bool bytes, hipStream_t s);
 // Few activation rows (M <= 64, K <= 8192, otherwise the same conditions), defined in mx_gemm_skinny.hip.
 int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s);
 int launch_gemm_skinny_fused(const GemmArgs& g, const void* x_bf16, int64_t ldx, int rule, bool a_mbs, hipStream_t s);

@@ -60,11 +60,12 @@ int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s) {
     return launch_ring<Tail>(tail, s);
 }
 
-// The general form (mx_gemm_ring.h: any K % 64 == 0, 2-byte aligned scale arrays, grouped or not) without MBS.
-// tile: 0 = 256 x 128, 1 = 128 x 128.
-int launch_gemm_wide_general(const GemmArgs& g, int tile, hipStream_t s) {
-    if (tile == 0) return launch_ring<RingShape<2, 2, 4, 2, 0, true>>(g, s);
-    return launch_ring<RingShape<2, 2, 2, 2, 0, true>>(g, s);
+// The general forms (mx_gemm_ring.h: any K, any alignment of the scale arrays, grouped or not) without MBS.
+// tile: 0 = 256 x 128, 1 = 128 x 128.  bytes: E8M0 bytes one at a time (128 x 128 tiles only).
+int launch_gemm_wide_general(const GemmArgs& g, int tile, bool bytes, hipStream_t s) {
+    if (bytes) return launch_ring<RingShape<2, 2, 2, 2, 0, 2>>(g, s);
+    if (tile == 0) return launch_ring<RingShape<2, 2, 4, 2, 0, 1>>(g, s);
+    return launch_ring<RingShape<2, 2, 2, 2, 0, 1>>(g, s);
 }
 
 }  // namespace mx

@@ -560,6 +560,16 @@ def test_gemm_empty_and_zero_k(mx):
     b = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
     bs = torch.full((8, 4), 127, dtype=torch.uint8, device="cuda")
     assert mx.mx_gemm(z, s, b, bs).shape == (0, 8)
+    # K = 0: an empty sum, C = 0 (every load of the kernel is out of range and reads zero)
+    a0, s0 = torch.empty((5, 0), dtype=torch.uint8, device="cuda"), torch.empty((5, 0), dtype=torch.uint8, device="cuda")
+    b0, t0 = torch.empty((130, 0), dtype=torch.uint8, device="cuda"), torch.empty((130, 0), dtype=torch.uint8, device="cuda")
+    for dt in ("f32", "bf16"):
+        out = torch.full((5, 130), 7.0, dtype=torch.float32 if dt == "f32" else torch.bfloat16, device="cuda")
+        mx.mx_gemm(a0, s0, b0, t0, dt, out=out)
+        assert float(out.abs().max()) == 0.0
+        out.fill_(7.0)
+        mx.mx_gemm_mbs(a0, s0, s0, b0, t0, t0, dt, out=out)
+        assert float(out.abs().max()) == 0.0
 
 
 def test_gemm_full_size_sampled_rows(mx, oracle):
@@ -593,22 +603,24 @@ def random_operand(rng, rows, K, lo=110, hi=140):
             rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 6, 7, 8, 9])
+@pytest.mark.parametrize("shape", [2, 3, 4, 6, 7, 8, 9, 10])
 def test_gemm_every_tile_shape(mx, oracle, shape):
-    """Each kernel forced in turn (0, 1: the generic kernel on 128 x 128 and 256 x 128 tiles; 2, 6, 7: the main
-    kernel without MBS on 256 x 256, 256 x 128 and 128 x 128 tiles; 3, 4: the main kernel with MBS on 256 x 128
-    and 128 x 128 tiles; 8, 9: the general form of the main kernels on 256 x 128 and 128 x 128 tiles, with and
-    without MBS, also on a K that ends in half a stage and on one of a single pair of blocks) on sizes with
-    ragged tiles in M and N, several K stages, both output types and rows of C that vector stores cannot serve."""
+    """Each kernel forced in turn (2, 6, 7: the fast form without MBS on 256 x 256, 256 x 128 and 128 x 128 tiles;
+    3, 4: the fast form with MBS on 256 x 128 and 128 x 128 tiles; 8, 9: the general form with 2-byte pieces on
+    256 x 128 and 128 x 128 tiles, 10: the general form with single bytes; these three with and without MBS,
+    also on a K that ends in half a stage and on one of a single pair of blocks, and 10 on K % 64 = 32) on sizes
+    with ragged tiles in M and N, several K stages, both output types and rows of C that vector stores cannot
+    serve."""
     lib = mx.load_library()
     rng = np.random.default_rng(50 + shape)
     try:
         lib.mx_internal_set_gemm_shape(shape)
         sizes = ((700, 530, 1536), (257, 300, 512)) + (((300, 260, 2880), (130, 129, 64)) if shape >= 8 else ())
+        sizes += ((200, 140, 2016), (33, 50, 32)) if shape == 10 else ()
         for (M, N, K) in sizes:
             a, b = random_operand(rng, M, K), random_operand(rng, N, K)
             da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
-            for plain in ((True, False) if shape < 2 or shape >= 8 else (shape in (2, 6, 7),)):
+            for plain in ((True, False) if shape >= 8 else (shape in (2, 6, 7),)):
                 want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None)) if plain else oracle.gemm(a, b)
                 what = "%s shape %d %dx%dx%d" % ("plain" if plain else "mbs", shape, M, N, K)
                 c32 = gpu_gemm(mx, a, b, "f32", plain=plain)
@@ -626,7 +638,7 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
                     frame = big.clone()
                     frame[1:M + 1, 1:N + 1] = -3.0
                     assert bool((frame == -3.0).all()), what
-            if shape in (3, 4, 8, 9):  # one-sided MBS: a null array means sigma = 1
+            if shape in (3, 4, 8, 9, 10):  # one-sided MBS: a null array means sigma = 1
                 want = oracle.gemm(a, (b[0], b[1], None))
                 got = mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], None, "f32")
                 assert_gemm_close(host(got), want, "A-only mbs shape %d" % shape)
