@@ -38,7 +38,6 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     g.num_groups = grouped ? num_groups : 0;
     g.tiles_m = g.tiles_n = 0;
     g.c_bf16 = c_dtype == MX_OUT_BF16;
-    g.vec_store = aligned(C, 4 * esz) && (ldc % 4) == 0;
     g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);

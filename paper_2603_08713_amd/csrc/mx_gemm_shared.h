@@ -17,7 +17,6 @@ struct GemmArgs {
     int num_groups;              // 0 = plain GEMM
     int tiles_m, tiles_n;        // tile grid (tiles_m is an upper bound in grouped mode)
     int c_bf16;
-    int vec_store;               // C rows allow 4-element vector stores
     int vec_store16;             // C rows allow 16-byte vector stores
 };
 
@@ -43,7 +42,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(3))) const uint16_t* lds_half_ptr_t;
-typedef __attribute__((address_space(3))) const uint8_t* lds_byte_ptr_t;
 
 template <typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -104,32 +102,6 @@ constexpr int kWaitLds = 0xC07F;
 // Workgroup barrier as a bare instruction: the compiler's own barrier intrinsic forces a wait for ALL
 // outstanding vector-memory operations, which would drain the younger stages still in flight.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
-// Stores C[m][n .. n + 3] (bf16, round to nearest even, or fp32); elements at or past N are dropped.
-__device__ __forceinline__ void store_c4(const GemmArgs& g, int64_t m, int64_t n, v4f v) {
-    if (g.c_bf16) {
-        uint16_t* o = static_cast<uint16_t*>(g.C) + m * g.ldc + n;
-        const uint32_t lo = pack_bf16(v.x, v.y), hi = pack_bf16(v.z, v.w);
-        if (g.vec_store && n + 3 < g.N) {
-            *reinterpret_cast<uint2*>(o) = make_uint2(lo, hi);
-        } else {
-            o[0] = (uint16_t)lo;
-            if (n + 1 < g.N) o[1] = (uint16_t)(lo >> 16);
-            if (n + 2 < g.N) o[2] = (uint16_t)hi;
-            if (n + 3 < g.N) o[3] = (uint16_t)(hi >> 16);
-        }
-    } else {
-        float* o = static_cast<float*>(g.C) + m * g.ldc + n;
-        if (g.vec_store && n + 3 < g.N) {
-            *reinterpret_cast<v4f*>(o) = v;
-        } else {
-            o[0] = v.x;
-            if (n + 1 < g.N) o[1] = v.y;
-            if (n + 2 < g.N) o[2] = v.z;
-            if (n + 3 < g.N) o[3] = v.w;
-        }
-    }
-}
 
 }  // namespace
 }  // namespace mx
