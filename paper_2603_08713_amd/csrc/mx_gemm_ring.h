@@ -407,7 +407,6 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         constexpr int kYounger = kLoads[(kPhase + 2) % 4] + kLoads[(kPhase + 3) % 4];
         __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? kYounger : 0));
         bare_barrier();
-        if constexpr (kMbs) convert_sigma(s + 2);  // into the table stage s - 2 was read from
         auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
             constexpr int t = decltype(t_)::value;
             if constexpr (!kMbs) {
@@ -442,6 +441,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 });
             };
             issue(std::integral_constant<int, 0>{});
+            // (behind the first pair's instructions: the LDS round trip of the MBS words then overlaps their run)
+            convert_sigma(s + 2);  // into the table stage s - 2 was read from
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 if constexpr (q + 1 < kPairs) issue(std::integral_constant<int, q + 1>{});
