@@ -271,6 +271,19 @@ print("first launch ok")
     assert out.returncode == 0 and "first launch ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 14336, 4096), (2048, 2048, 2048), (3000, 2880, 2880), (700, 530, 2016)])
+def test_gemm_repeated_launches_are_bit_identical(mx, M, N, K):
+    """The kernels have no atomics and a fixed summation order, so every launch on the same operands must give
+    the same bits; a difference means a synchronisation hole (fast form, small tiles, both general forms)."""
+    rng = np.random.default_rng(M + N + K)
+    a, b = [dev_u8(t) for t in random_operand(rng, M, K, 120, 134)], [dev_u8(t) for t in random_operand(rng, N, K, 120, 134)]
+    first_m = mx.mx_gemm_mbs(*a, *b, "bf16")
+    first_p = mx.mx_gemm(a[0], a[1], b[0], b[1], "bf16")
+    for rep in range(12):
+        assert torch.equal(mx.mx_gemm_mbs(*a, *b, "bf16"), first_m), rep
+        assert torch.equal(mx.mx_gemm(a[0], a[1], b[0], b[1], "bf16"), first_p), rep
+
+
 def test_hip_graph_replay_matches_eager(mx, oracle):
     """The entry points launch on the caller's stream, allocate nothing and never synchronise, so a step can be
     captured in a HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce
