@@ -539,7 +539,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 if (m < a_end && n < g.N) {
                     uint8_t* o = static_cast<uint8_t*>(g.C) + (m * g.ldc + n) * esz;
                     if (whole) {
-                        *reinterpret_cast<v4i*>(o) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(o));
                     } else {
 #pragma unroll
                         for (int e = 0; e < per; ++e) {
