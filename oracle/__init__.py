@@ -68,6 +68,24 @@ def lib() -> ctypes.CDLL:
         L.mxo_qsnr_db.restype = dbl
         L.mxo_qsnr_db.argtypes = [vp, vp, i64]
         L.mxo_num_threads.restype = ci
+        L.mxo_elem_bits.restype = ci
+        L.mxo_elem_bits.argtypes = [ci]
+        L.mxo_elem_decode.restype = dbl
+        L.mxo_elem_decode.argtypes = [ci, ci]
+        L.mxo_elem_max.restype = dbl
+        L.mxo_elem_max.argtypes = [ci]
+        L.mxo_elem_nearest.restype = ci
+        L.mxo_elem_nearest.argtypes = [ci, dbl]
+        L.mxo_elem_scale_exponent.restype = ci
+        L.mxo_elem_scale_exponent.argtypes = [ci, dbl, ci]
+        L.mxo_elem_mbs_static_m8.restype = ci
+        L.mxo_elem_mbs_static_m8.argtypes = [ci, dbl]
+        L.mxo_elem_quantize.restype = ci
+        L.mxo_elem_quantize.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
+        L.mxo_elem_dequantize.restype = ci
+        L.mxo_elem_dequantize.argtypes = [ci, vp, vp, vp, i64, i64, ci, ci, vp]
+        L.mxo_elem_gemm_rows.restype = ci
+        L.mxo_elem_gemm_rows.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, i64, i64, i64, ci, ci, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -221,6 +239,81 @@ def bf16_to_f64(x_bf16: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns (the reference signal of Eq. 1)."""
     u = np.ascontiguousarray(x_bf16, np.uint16).astype(np.uint32) << 16
     return u.view(np.float32).astype(np.float64)
+
+
+# ---- other MX element formats (codes one per byte) ----------------------------------------------
+ELEMS = {"e2m1": 0, "e4m3": 1, "e5m2": 2, "e2m3": 3, "e3m2": 4}
+
+
+def _elem(fmt) -> int:
+    return ELEMS[fmt] if isinstance(fmt, str) else int(fmt)
+
+
+def elem_bits(fmt) -> int:
+    return lib().mxo_elem_bits(_elem(fmt))
+
+
+def elem_decode(fmt, code: int) -> float:
+    return lib().mxo_elem_decode(_elem(fmt), int(code))
+
+
+def elem_max(fmt) -> float:
+    return lib().mxo_elem_max(_elem(fmt))
+
+
+def elem_nearest(fmt, y: float) -> int:
+    return lib().mxo_elem_nearest(_elem(fmt), float(y))
+
+
+def elem_scale_exponent(fmt, alpha: float, rule) -> int:
+    return lib().mxo_elem_scale_exponent(_elem(fmt), float(alpha), _rule(rule))
+
+
+def elem_mbs_static_m8(fmt, alpha: float) -> int:
+    return lib().mxo_elem_mbs_static_m8(_elem(fmt), float(alpha))
+
+
+def elem_quantize(fmt, x_bf16: np.ndarray, rule="oas", mbs: bool = False, block: int = 32, macro: int = 128):
+    """Quantize into element format fmt. Returns (codes [rows, K] one per byte, scales, mbs words or None)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    codes = np.zeros((rows, K), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    words = np.zeros((rows, (K + macro - 1) // macro), np.uint8) if mbs else None
+    rc = lib().mxo_elem_quantize(_elem(fmt), _ptr(x), rows, K, K, _rule(rule), int(bool(mbs)), block, macro,
+                                 _ptr(codes), _ptr(scales), _ptr(words))
+    if rc != 0:
+        raise ValueError("mxo_elem_quantize: bad arguments")
+    return codes, scales, words
+
+
+def elem_dequantize(fmt, codes, scales, mbs=None, block: int = 32, macro: int = 128) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.uint8)
+    mbs = None if mbs is None else np.ascontiguousarray(mbs, np.uint8)
+    rows, K = codes.shape
+    out = np.empty((rows, K), np.float64)
+    rc = lib().mxo_elem_dequantize(_elem(fmt), _ptr(codes), _ptr(scales), _ptr(mbs), rows, K, block, macro, _ptr(out))
+    if rc != 0:
+        raise ValueError("mxo_elem_dequantize: bad arguments")
+    return out
+
+
+def elem_gemm(fmt_a, a, fmt_b, b, rows=None, block: int = 32, macro: int = 128) -> np.ndarray:
+    """a, b: (codes one per byte, scales, mbs-or-None) of A [M,K] and B [N,K]; A.B^T [len(rows), N] fp64."""
+    ac, asc, am = [None if t is None else np.ascontiguousarray(t, np.uint8) for t in a]
+    bc, bsc, bm = [None if t is None else np.ascontiguousarray(t, np.uint8) for t in b]
+    M, K = ac.shape
+    N = bc.shape[0]
+    assert bc.shape[1] == K
+    idx = None if rows is None else np.ascontiguousarray(rows, np.int64)
+    n = M if idx is None else len(idx)
+    C = np.empty((n, N), np.float64)
+    rc = lib().mxo_elem_gemm_rows(_elem(fmt_a), _ptr(ac), _ptr(asc), _ptr(am), _elem(fmt_b), _ptr(bc), _ptr(bsc),
+                                  _ptr(bm), M, N, K, block, macro, _ptr(idx), n, _ptr(C))
+    if rc != 0:
+        raise ValueError("mxo_elem_gemm_rows: bad arguments")
+    return C
 
 
 def mbs_overhead_model(tm: int = 128, tn: int = 128, tk: int = 128):

@@ -23,7 +23,8 @@
  *   - the scale byte E is E8M0 with bias 127 and holds the DE-quantization scale 2^(E-127);
  *     the paper's multiplicative SF (Sec. 4.2) is its reciprocal, SF = 2^s with s = 127 - E
  *   - the MBS word m8 is the 8 stored mantissa bits; factor F = 1 + m8/256 in [1,2) (Sec. 4.3.1)
- *   - parity status: every exported function is pinned by tests/test_oracle_pins.py
+ *   - parity status: every exported function is pinned by tests/test_oracle_pins.py; the functions
+ *     for the other MX element formats (mxo_elem_*, last section) by tests/test_oracle_elem_pins.py
  */
 #include <math.h>
 #include <stdint.h>
@@ -396,6 +397,216 @@ int mxo_matmul_bf16_rows(const uint16_t* A, int64_t lda, const uint16_t* B, int6
             double c = 0.0;
             for (int64_t k = 0; k < K; ++k)
                 c += mxo_bf16_value(A[i * lda + k]) * mxo_bf16_value(B[j * ldb + k]);
+            C[t * N + j] = c;
+        }
+    return 0;
+}
+
+/* ---- the other MX element formats (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8) ---- */
+
+/* The paper works MXFP4 through and says only that OAS and MBS generalise.  The reading taken here
+ * restates each rule with the element format's own constants in place of E2M1's:
+ *   V      largest finite magnitude (E2M1: 6)            = vm * 2^emax, vm in [1, 2)
+ *   h      half of the spacing of the format's top binade (E2M1: 1) = 2^(emax - mbits - 1)
+ *   FLOOR: SF = 2^floor(log2(V/alpha)), scaled absmax in (V/2, V]
+ *   OAS:   from FLOOR; a scaled absmax of at most (V + h)/2 doubles SF: scaled absmax in
+ *          ((V + h)/2, V + h].  V + h is where E2M1's 7 comes from: saturating a value of (V, V + h]
+ *          to V costs no more than rounding inside the top binade does.
+ *   OCP:   shared exponent floor(log2 alpha) - emax, scaled absmax in [2^emax, 2^(emax+1))
+ *   MBS-S: m8 = 8 leading mantissa bits of V/alpha128, so that the macro-block absmax lands on V
+ * Element formats as in the OCP MX specification: E4M3 (bias 7; S.1111.111 is NaN, so V = 448),
+ * E5M2 (bias 15; exponent field 31 is Inf/NaN, V = 57344), E2M3 (bias 1, V = 7.5) and E3M2 (bias 3,
+ * V = 28) with every code finite, and E2M1 itself, which must reproduce mxo_quantize.
+ * Codes are stored one per byte (sign in the format's top bit), whatever the format's width.
+ * Parity status: pinned by tests/test_oracle_elem_pins.py; no value of the paper covers these
+ * formats, so what is pinned is this reading against exact arithmetic and a library's FP8 types. */
+#define MXO_ELEM_E2M1 0
+#define MXO_ELEM_E4M3 1
+#define MXO_ELEM_E5M2 2
+#define MXO_ELEM_E2M3 3
+#define MXO_ELEM_E3M2 4
+
+typedef struct {
+    int ebits, mbits, bias;
+    int max_code; /* magnitude code of V */
+} elem_format;
+
+static const elem_format ELEM[5] = {
+    {2, 1, 1, 0x07}, /* E2M1: 1.5 * 2^2            */
+    {4, 3, 7, 0x7E}, /* E4M3: 1.75 * 2^8, 0x7F NaN */
+    {5, 2, 15, 0x7B}, /* E5M2: 1.75 * 2^15, exponent 31 Inf/NaN */
+    {2, 3, 1, 0x1F}, /* E2M3: 1.875 * 2^2          */
+    {3, 2, 3, 0x1F}, /* E3M2: 1.75 * 2^4           */
+};
+
+int mxo_elem_bits(int fmt) { return (fmt < 0 || fmt > 4) ? -1 : 1 + ELEM[fmt].ebits + ELEM[fmt].mbits; }
+
+/* Value of magnitude code c (sign stripped): subnormal m * 2^(1-bias-mbits) when the exponent field
+ * is 0, else (1 + m/2^mbits) * 2^(e-bias). */
+static double elem_magnitude(const elem_format* f, int c) {
+    const int e = c >> f->mbits, m = c & ((1 << f->mbits) - 1);
+    if (e == 0) return ldexp((double)m, 1 - f->bias - f->mbits);
+    return ldexp((double)((1 << f->mbits) + m), e - f->bias - f->mbits);
+}
+
+/* Value of a stored code (sign bit = bit ebits+mbits).  Codes above the largest finite magnitude
+ * (E4M3's NaN, E5M2's Inf/NaN) decode to NaN; the quantizer never produces them. */
+double mxo_elem_decode(int fmt, int code) {
+    if (fmt < 0 || fmt > 4) return NAN;
+    const elem_format* f = &ELEM[fmt];
+    const int sign_bit = 1 << (f->ebits + f->mbits), c = code & (sign_bit - 1);
+    if (c > f->max_code) return NAN;
+    const double v = elem_magnitude(f, c);
+    return (code & sign_bit) ? -v : v;
+}
+
+double mxo_elem_max(int fmt) { return (fmt < 0 || fmt > 4) ? NAN : elem_magnitude(&ELEM[fmt], ELEM[fmt].max_code); }
+
+/* Magnitude code of the format's value nearest to y >= 0: saturating at V, a tie to the code with
+ * an even mantissa.  Plain search over every finite code. */
+int mxo_elem_nearest(int fmt, double y) {
+    if (fmt < 0 || fmt > 4) return -1;
+    const elem_format* f = &ELEM[fmt];
+    if (y >= elem_magnitude(f, f->max_code)) return f->max_code;
+    int best = 0;
+    double best_d = fabs(y - elem_magnitude(f, 0));
+    for (int c = 1; c <= f->max_code; ++c) {
+        const double d = fabs(y - elem_magnitude(f, c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;
+}
+
+/* emax and the mantissa vm of V = vm * 2^emax. */
+static double elem_vmax_parts(const elem_format* f, int* emax) {
+    int ex;
+    const double fr = frexp(elem_magnitude(f, f->max_code), &ex); /* V = fr * 2^ex, fr in [0.5, 1) */
+    *emax = ex - 1;
+    return 2.0 * fr;
+}
+
+/* Exponent s of SF = 2^s for a block of (MBS-scaled) absmax alpha > 0 under the rules above. */
+int mxo_elem_scale_exponent(int fmt, double alpha, int rule) {
+    const elem_format* f = &ELEM[fmt];
+    int emax, ex;
+    const double vm = elem_vmax_parts(f, &emax);
+    const double fr = frexp(alpha, &ex); /* alpha = fr * 2^ex */
+    if (rule == MXO_RULE_OCP) return emax - (ex - 1);
+    /* V/alpha = (vm / (2 fr)) * 2^(emax - ex + 1) with vm/(2 fr) in (vm/2, vm]: its floor(log2) is
+     * emax - ex + 1 when vm/(2 fr) >= 1, i.e. fr <= vm/2 (compared so that no division rounds). */
+    int s = (fr <= vm / 2.0) ? emax - ex + 1 : emax - ex;
+    if (rule == MXO_RULE_OAS) {
+        const double V = elem_magnitude(f, f->max_code), h = ldexp(1.0, emax - f->mbits - 1);
+        if (ldexp(alpha, s) <= (V + h) / 2.0) s += 1; /* all exact */
+    }
+    return s;
+}
+
+/* MBS-Static word: the 8 leading mantissa bits of V/alpha, by exact integer division. */
+int mxo_elem_mbs_static_m8(int fmt, double alpha) {
+    if (!(alpha > 0.0) || isinf(alpha)) return 0;
+    const elem_format* f = &ELEM[fmt];
+    int emax, ex;
+    const double vm = elem_vmax_parts(f, &emax);
+    const double fr = frexp(alpha, &ex);
+    const uint64_t n = (uint64_t)ldexp(fr, 53);               /* fr = n / 2^53                 */
+    /* normalised quotient 1+m = vm/(2 fr) when that is >= 1, else vm/fr; 256 vm is an integer     */
+    const unsigned __int128 vm256 = (unsigned __int128)(uint64_t)(256.0 * vm);
+    const unsigned __int128 num = (fr <= vm / 2.0) ? (vm256 << 52) : (vm256 << 53);
+    return (int)(uint64_t)(num / n) - 256;
+}
+
+/* Quantize rows of bf16 into element format fmt: as mxo_quantize, with codes [rows, K] one per byte. */
+int mxo_elem_quantize(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
+                      int use_mbs, int block, int macro, uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
+    if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || ldx < K || block <= 0 || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const elem_format* f = &ELEM[fmt];
+    const int sign_bit = 1 << (f->ebits + f->mbits);
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * ldx;
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            int m8 = 0;
+            if (use_mbs) {
+                m8 = mxo_elem_mbs_static_m8(fmt, macro_absmax(xr, k0, k1));
+                mbs[r * nmac + g] = (uint8_t)m8;
+            }
+            const double F = 1.0 + m8 / 256.0;
+            for (int64_t b0 = k0; b0 < k1; b0 += block) {
+                int finite = 1;
+                double amax = 0.0;
+                for (int64_t k = b0; k < b0 + block; ++k) {
+                    if (!is_finite_bf16(xr[k])) finite = 0;
+                    else amax = fmax(amax, fabs(mxo_bf16_value(xr[k]) * F));
+                }
+                int E, s;
+                if (!finite) { E = 255; s = 0; }
+                else if (amax == 0.0) { E = 127; s = 0; }
+                else { E = mxo_e8m0_from_exponent(mxo_elem_scale_exponent(fmt, amax, rule)); s = 127 - E; }
+                scales[r * nblk + b0 / block] = (uint8_t)E;
+                for (int64_t k = b0; k < b0 + block; ++k) {
+                    int code = 0;
+                    if (finite) {
+                        const double t = ldexp(mxo_bf16_value(xr[k]) * F, s); /* exact */
+                        code = mxo_elem_nearest(fmt, fabs(t)) | ((xr[k] & 0x8000u) ? sign_bit : 0);
+                    }
+                    codes[r * K + k] = (uint8_t)code;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* out [rows, K] fp64 = code value * 2^(E-127) / F. */
+int mxo_elem_dequantize(int fmt, const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs,
+                        int64_t rows, int64_t K, int block, int macro, double* out) {
+    if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || block <= 0 || macro % block || K % block) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            const double F = mbs ? 1.0 + mbs[r * nmac + k / macro] / 256.0 : 1.0;
+            out[r * K + k] = mxo_elem_decode(fmt, codes[r * K + k]) * scale_value(scales[r * nblk + k / block]) / F;
+        }
+    return 0;
+}
+
+/* mxo_gemm_rows for operands in element formats fmt_a and fmt_b (Sec. 4.3.2 unchanged: the MBS
+ * correction does not depend on the element format). */
+int mxo_elem_gemm_rows(int fmt_a, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs,
+                       int fmt_b, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs,
+                       int64_t M, int64_t N, int64_t K, int block, int macro,
+                       const int64_t* row_idx, int64_t nrows, double* C) {
+    if (fmt_a < 0 || fmt_a > 4 || fmt_b < 0 || fmt_b > 4) return -1;
+    if (M < 0 || N < 0 || K < 0 || block <= 0 || macro % block || K % block) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+    for (int64_t t = 0; t < nrows; ++t)
+        if (row_idx && (row_idx[t] < 0 || row_idx[t] >= M)) return -1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t t = 0; t < nrows; ++t)
+        for (int64_t j = 0; j < N; ++j) {
+            const int64_t i = row_idx ? row_idx[t] : t;
+            double c = 0.0;
+            for (int64_t g = 0; g < nmac; ++g) {
+                const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+                double p = 0.0;
+                for (int64_t k = k0; k < k1; ++k) {
+                    const double av = mxo_elem_decode(fmt_a, a_codes[i * K + k]) * scale_value(a_scales[i * nblk + k / block]);
+                    const double bv = mxo_elem_decode(fmt_b, b_codes[j * K + k]) * scale_value(b_scales[j * nblk + k / block]);
+                    p += av * bv;
+                }
+                const double Fa = a_mbs ? 1.0 + a_mbs[i * nmac + g] / 256.0 : 1.0;
+                const double Fb = b_mbs ? 1.0 + b_mbs[j * nmac + g] / 256.0 : 1.0;
+                c += p * (1.0 / Fa) * (1.0 / Fb);
+            }
             C[t * N + j] = c;
         }
     return 0;
