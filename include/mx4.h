@@ -147,6 +147,39 @@ int mx_gemm_mbs_grouped(const uint8_t* a_codes, const uint8_t* a_scales, const u
                         int64_t M_total, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C,
                         int64_t ldc, void* stream);
 
+/* ---- the 8-bit MX element formats (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8) ----------
+ * The paper works MXFP4 through and only states that OAS and MBS generalise; these entry points restate
+ * each rule with the element format's own constants in place of E2M1's 6 and 1: V, its largest finite
+ * magnitude, and h, half the spacing of its top binade.
+ *   MX_RULE_FLOOR  block absmax -> (V/2, V]            MX_RULE_OCP  shared exponent floor(log2 absmax) - emax
+ *   MX_RULE_OAS    FLOOR, doubled when the absmax lands at or below (V + h)/2: absmax -> ((V + h)/2, V + h]
+ *   MBS-Static     m8 = the 8 leading mantissa bits of V / (absmax of the 1x128 window)
+ * Elements round to the nearest value of the format, ties to the even code, saturating at +-V; the sign
+ * bit is copied.  Layout: codes uint8 [rows, K], one element per byte (E4M3: S.EEEE.MMM, bias 7, V = 448,
+ * h = 16; E5M2: S.EEEEE.MM, bias 15, V = 57344, h = 4096; both as in the OCP MX specification); scales and
+ * mbs as for MXFP4.  MX_ELEM_E2M1 names the 4-bit format of the other entry points and is not accepted
+ * here; the 6-bit formats are declared for completeness and return MX_EUNSUPPORTED. */
+typedef enum {
+    MX_ELEM_E2M1 = 0,
+    MX_ELEM_E4M3 = 1,
+    MX_ELEM_E5M2 = 2,
+    MX_ELEM_E2M3 = 3,
+    MX_ELEM_E3M2 = 4
+} mx_elem_t;
+
+/* mx_quantize (use_mbs = 0, mbs ignored) or mx_quantize_mbs (use_mbs != 0) into an 8-bit element format.
+ * Alignment: x 16 bytes and ldx a multiple of 8, codes 8 bytes.  K % 32 == 0. */
+int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                     int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
+/* mx_gemm_mbs for operands in 8-bit element formats (they may differ between A and B): the same sum, the
+ * same MBS correction per 128 K-elements (Sec. 4.3.2, which does not depend on the element format), on the
+ * same scaled matrix instruction.  Covers K > 0, K % 128 == 0, codes 16-byte and scale arrays 4-byte
+ * aligned; anything else returns MX_EUNSUPPORTED and nothing is launched. */
+int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
+                     mx_elem_t b_elem, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
+                     int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream);
+
 /* Human-readable text for a status code (static storage, host pointer). */
 const char* mx_status_string(int status);
 

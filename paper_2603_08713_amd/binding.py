@@ -14,6 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libmx4.so")
 
 MX_RULE_OCP, MX_RULE_FLOOR, MX_RULE_OAS = 0, 1, 2
 MX_OUT_F32, MX_OUT_BF16 = 0, 1
+MX_ELEM_E2M1, MX_ELEM_E4M3, MX_ELEM_E5M2, MX_ELEM_E2M3, MX_ELEM_E3M2 = 0, 1, 2, 3, 4
+_ELEMS = {"e2m1": MX_ELEM_E2M1, "e4m3": MX_ELEM_E4M3, "e5m2": MX_ELEM_E5M2, "e2m3": MX_ELEM_E2M3, "e3m2": MX_ELEM_E3M2}
 _RULES = {"ocp": MX_RULE_OCP, "floor": MX_RULE_FLOOR, "oas": MX_RULE_OAS}
 
 _lib: Optional[ctypes.CDLL] = None
@@ -57,6 +59,10 @@ def load_library() -> ctypes.CDLL:
     L.mx_gemm_mbs.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_gemm_mbs_grouped.restype = ci
     L.mx_gemm_mbs_grouped.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i64, i64, i64, ci, vp, i64, vp]
+    L.mx_quantize_elem.restype = ci
+    L.mx_quantize_elem.argtypes = [ci, vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    L.mx_gemm_mbs_elem.restype = ci
+    L.mx_gemm_mbs_elem.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_status_string.restype = ctypes.c_char_p
     L.mx_status_string.argtypes = [ci]
     L.mx_version.restype = ci
@@ -92,6 +98,10 @@ def _torch():
 
 def _rule(rule) -> int:
     return _RULES[rule] if isinstance(rule, str) else int(rule)
+
+
+def _elem(elem) -> int:
+    return _ELEMS[elem] if isinstance(elem, str) else int(elem)
 
 
 def _stream() -> int:
@@ -245,6 +255,39 @@ def mx_gemm_mbs(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, out_dtype="f
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
     _check(load_library().mx_gemm_mbs(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes), _ptr(b_scales),
                                       _ptr(b_mbs), M, N, K, code, _ptr(out), ldc, _stream()), "mx_gemm_mbs")
+    return out
+
+
+def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scales=None, mbs=None):
+    """Quantize into an 8-bit MX element format (codes one per byte), with or without MBS words."""
+    torch = _torch()
+    rows, K, ldx = _rows_ld(x)
+    if codes is None:
+        codes = torch.empty((rows, K), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    if use_mbs and mbs is None:
+        mbs = torch.empty((rows, (K + 127) // 128), dtype=torch.uint8, device=x.device)
+    _u8(codes, (rows, K), "codes")
+    _u8(scales, (rows, K // 32), "scales")
+    if use_mbs:
+        _u8(mbs, (rows, (K + 127) // 128), "mbs")
+    _check(load_library().mx_quantize_elem(_elem(elem), _ptr(x), rows, K, ldx, _rule(rule), int(bool(use_mbs)),
+                                           _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None, _stream()),
+           "mx_quantize_elem")
+    return codes, scales, (mbs if use_mbs else None)
+
+
+def mx_gemm_mbs_elem(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales, b_mbs, out_dtype="f32", out=None):
+    """GEMM with the MBS correction for operands in 8-bit MX element formats; a_mbs / b_mbs may be None."""
+    M, K = a_codes.shape
+    N = b_codes.shape[0]
+    if b_codes.shape[1] != K:
+        raise ValueError("A and B disagree on K")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
+    _check(load_library().mx_gemm_mbs_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
+                                           _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,
+                                           _stream()), "mx_gemm_mbs_elem")
     return out
 
 

@@ -1,0 +1,305 @@
+// Quantizer for the 8-bit MX element formats (E4M3, E5M2) with Overflow-Aware Scaling and static Macro Block
+// Scaling for gfx950 (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8).
+//
+// The rules of Sec. 4.2 and 4.3.1 are restated with the element format's constants in place of E2M1's 6 and 1:
+// V = vm * 2^emax, the largest finite magnitude (both formats: vm = 1.75), and h = 2^(emax - mbits - 1), half the
+// spacing of the top binade.  In terms of the mantissa t of the (MBS-scaled) block absmax, written t * 2^p:
+//   OCP    stored exponent p - emax                        FLOOR  one more when t > vm
+//   OAS    one more when t > vm + h / 2^emax               MBS-S  m8 = 8 leading mantissa bits of V / absmax128
+// Work decomposition and exactness arguments are those of the MXFP4 quantizer (mx_quantize.hip): a lane owns 8
+// consecutive bf16, 4 lanes a block, 16 lanes a macro block, a wavefront 512 elements of a row; x * F is exact
+// in fp32 and so is its product with the power-of-two block scale; the block exponent is read off the fp32
+// pattern of absmax * F with a carry; blocks that could leave fp32's normal range, or hold Inf/NaN, take a
+// wave-uniform detour through all-integer arithmetic.
+#include "mx_quantize_math.h"
+
+namespace mx {
+namespace {
+
+constexpr int kChunk8 = 512;   // elements per wavefront step
+constexpr int kUnroll8 = 4;    // chunks in flight per wavefront
+constexpr int kThreads8 = 256;
+
+template <int kElem>
+struct Fp8;
+template <>
+struct Fp8<MX_ELEM_E4M3> {
+    static constexpr int kEmax = 8, kMbits = 3, kBias = 7, kMaxCode = 0x7E;
+    static constexpr uint32_t kMaxBits = 0x43E00000u;                       // 448.0f
+    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x17FFFFu;  // 2^23 - 1 - mantissa bits of 1.75, 1.8125
+    static constexpr uint32_t kOasNum = 29, kOasShift = 4;                  // 1.8125 = 29 / 16
+};
+template <>
+struct Fp8<MX_ELEM_E5M2> {
+    static constexpr int kEmax = 15, kMbits = 2, kBias = 15, kMaxCode = 0x7B;
+    static constexpr uint32_t kMaxBits = 0x47600000u;                       // 57344.0f
+    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x0FFFFFu;  // 1.75, 1.875
+    static constexpr uint32_t kOasNum = 15, kOasShift = 3;                  // 1.875 = 15 / 8
+};
+
+struct Quant8Args {
+    const uint16_t* x;
+    uint8_t *codes, *scales, *mbs;
+    int64_t K, ldx, nmac;
+    uint32_t chunks_per_row, total_chunks;
+    uint32_t carry;
+    int rule;
+    int scales_dword;
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 8 leading mantissa bits of V / alpha for alpha = (128 + k) * 2^e, V = 1.75 * 2^emax: 224 / (128 + k) lies in
+// (0.875, 1.75]; normalised to [1, 2) it is 224 / (128 + k) for k <= 96 and 448 / (128 + k) above.  The quotient
+// is taken with the hardware reciprocal plus 2^-10 (an integer, or at least 1/255 away from one).
+__device__ __forceinline__ uint32_t mbs8_word_of_mantissa(uint32_t k) {
+    const float num = k <= 96u ? 57344.0f : 114688.0f;
+    const float quo = fmaf(num, __builtin_amdgcn_rcpf((float)(128u + k)), 0x1.0p-10f);
+    return (uint32_t)quo - 256u;
+}
+__device__ __forceinline__ uint32_t mbs8_word_of_absmax(uint32_t mmax) {
+    if (mmax == 0) return 0;
+    uint32_t k = mmax & 0x7Fu;
+    if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;
+    const uint32_t n = 128u + k;
+    return (k <= 96u ? 57344u / n : 114688u / n) - 256u;
+}
+
+// ---- all-integer arithmetic, exact for every finite bf16 input ----
+template <typename T>
+__device__ __forceinline__ int exact_scale_byte8(uint32_t amax, uint32_t u, int rule) {
+    const uint32_t ea = amax >> 7;
+    const uint32_t na = ea ? (128u | (amax & 0x7Fu)) : (amax & 0x7Fu);
+    const int ex = (int)(ea ? ea : 1u) - 134;  // absmax = na * 2^ex
+    const uint32_t P = na * u;                 // absmax * F = P * 2^(ex - 8)
+    const int msb = 31 - __clz(P);
+    const int p = ex - 8 + msb;                // floor(log2(absmax * F))
+    bool low = true;                           // mantissa at or below the rule's threshold
+    if (rule == MX_RULE_FLOOR) low = 4u * P <= (7u << msb);
+    else if (rule == MX_RULE_OAS) low = (P << T::kOasShift) <= (T::kOasNum << msb);
+    const int s = low ? T::kEmax - p : T::kEmax - 1 - p;
+    return min(max(127 - s, 0), 254);
+}
+// Code of the bf16 pattern h scaled by F = u / 256 and by 2^s: nearest, ties to even, saturating, sign copied.
+template <typename T>
+__device__ __forceinline__ uint32_t exact_code8(uint32_t h, uint32_t u, int s) {
+    const uint32_t sign = (h >> 8) & 0x80u;
+    const uint32_t a = h & 0x7FFFu, e = a >> 7;
+    const uint32_t n = e ? (128u | (a & 0x7Fu)) : (a & 0x7Fu);
+    const uint32_t Tv = n * u;  // |x| F 2^s = Tv * 2^e2
+    if (Tv == 0) return sign;
+    const int e2 = (int)(e ? e : 1u) - 134 - 8 + s;
+    const int p = 31 - __clz(Tv) + e2;
+    if (p > T::kEmax) return (uint32_t)T::kMaxCode | sign;
+    const int ey = max(p, 1 - T::kBias);       // binade whose spacing applies (subnormals share the lowest)
+    const int shift = e2 - (ey - T::kMbits);   // in units of that spacing the value is Tv * 2^shift
+    uint32_t q;
+    if (shift >= 0) {
+        q = Tv << shift;                       // at most 2^(mbits + 1)
+    } else {
+        const int r = min(-shift, 20);
+        const uint32_t q0 = Tv >> r, rem = Tv & ((1u << r) - 1u), half = 1u << (r - 1);
+        q = q0 + ((rem > half || (rem == half && (q0 & 1u))) ? 1u : 0u);
+    }
+    const uint32_t code = ((uint32_t)(ey + T::kBias) << T::kMbits) + q - (1u << T::kMbits);
+    return min(code, (uint32_t)T::kMaxCode) | sign;
+}
+
+struct Chunk8 {
+    uint32_t lo, hi;  // 8 codes of this lane
+    uint32_t E, m8;
+};
+
+template <typename T>
+__device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_mbs) {
+    uint32_t h[8] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16,
+                     v.z & 0xFFFFu, v.z >> 16, v.w & 0xFFFFu, v.w >> 16};
+    uint32_t amax = 0, nf = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t a = h[i] & 0x7FFFu;
+        if (a >= 0x7F80u) nf = 1; else amax = max(amax, a);
+    }
+    nf |= dpp_quad_xor1(nf);
+    nf |= dpp_quad_xor2(nf);
+    amax = max(amax, dpp_quad_xor1(amax));
+    amax = max(amax, dpp_quad_xor2(amax));
+    uint32_t mmax = amax;
+    mmax = max(mmax, dpp_row_ror4(mmax));
+    mmax = max(mmax, dpp_row_ror8(mmax));
+    const uint32_t m8 = use_mbs ? mbs8_word_of_absmax(mmax) : 0u;
+    const uint32_t u = 256u + m8;
+    const int E = nf ? 255 : amax == 0 ? 127 : exact_scale_byte8<T>(amax, u, rule);
+    uint32_t lo = 0, hi = 0;
+    if (!nf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lo |= exact_code8<T>(h[i], u, 127 - E) << (8 * i);
+            hi |= exact_code8<T>(h[4 + i], u, 127 - E) << (8 * i);
+        }
+    }
+    return {lo, hi, (uint32_t)E, m8};
+}
+
+// |t| (already scaled) to the format's grid with ordinary arithmetic: adding 1.5 * 2^(23 - mbits + ey), ey the
+// binade of min(|t|, V) (not below the lowest normal one), leaves t in units of that binade's spacing in the low
+// mantissa bits of the sum, rounded to nearest even.
+template <typename T>
+__device__ __forceinline__ uint32_t code8_alu(float t) {
+    const uint32_t tb = __float_as_uint(t);
+    const float y = fminf(__uint_as_float(tb & 0x7FFFFFFFu), __uint_as_float(T::kMaxBits));
+    const uint32_t ey = max(__float_as_uint(y) >> 23, (uint32_t)(127 + 1 - T::kBias));
+    const float w = y + __uint_as_float(((ey + 23u - T::kMbits) << 23) | 0x400000u);
+    const uint32_t q = __float_as_uint(w) & ((1u << (T::kMbits + 2)) - 1u);
+    return (((ey - 127u + T::kBias) << T::kMbits) + q - (1u << T::kMbits)) | ((tb >> 24) & 0x80u);
+}
+
+template <int kElem, bool kHwCvt, bool kMbs>
+__device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) {
+    using T = Fp8<kElem>;
+    uint32_t m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
+                            pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
+    uint32_t amax = max(m & 0xFFFFu, m >> 16);
+    amax = max(amax, dpp_quad_xor1(amax));
+    amax = max(amax, dpp_quad_xor2(amax));
+    // exponent field outside [24, 249] (or Inf/NaN): leave fp32 arithmetic, wave-uniformly
+    const bool odd = (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) return quantize_chunk8_exact<T>(v, q.rule, kMbs);
+
+    uint32_t m8 = 0;
+    if constexpr (kMbs) {
+        uint32_t mmax = max(amax, dpp_row_ror4(amax));
+        mmax = max(mmax, dpp_row_ror8(mmax));
+        m8 = mmax ? mbs8_word_of_mantissa(mmax & 0x7Fu) : 0u;
+    }
+    const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));  // exact
+    uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - (uint32_t)T::kEmax;
+    E = amax ? E : 127u;
+    const float mult = __uint_as_float(((254u - E) << 23) | (m8 << 15));  // F * 2^(127 - E)
+    const float vmax = __uint_as_float(T::kMaxBits);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t out[2] = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float t0 = __uint_as_float(w[i] << 16) * mult;          // exact
+        const float t1 = __uint_as_float(w[i] & 0xFFFF0000u) * mult;
+        if constexpr (kHwCvt) {
+            // hardware fp32 -> FP8 pair convert (nearest even); the clamp makes saturation explicit
+            const float c0 = __builtin_amdgcn_fmed3f(t0, -vmax, vmax), c1 = __builtin_amdgcn_fmed3f(t1, -vmax, vmax);
+            if constexpr (kElem == MX_ELEM_E4M3) {
+                if (i % 2 == 0) out[i / 2] = __builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, out[i / 2], false);
+                else out[i / 2] = __builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, out[i / 2], true);
+            } else {
+                if (i % 2 == 0) out[i / 2] = __builtin_amdgcn_cvt_pk_bf8_f32(c0, c1, out[i / 2], false);
+                else out[i / 2] = __builtin_amdgcn_cvt_pk_bf8_f32(c0, c1, out[i / 2], true);
+            }
+        } else {
+            out[i / 2] |= (code8_alu<T>(t0) | (code8_alu<T>(t1) << 8)) << (16 * (i % 2));
+        }
+    }
+    return {out[0], out[1], E, m8};
+}
+
+template <int kElem, bool kHwCvt, bool kMbs>
+__global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads8 / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kThreads8 / kWave);
+    for (uint32_t c0 = wave * kUnroll8; c0 < q.total_chunks; c0 += nwaves * kUnroll8) {
+        u32x4 v[kUnroll8];
+        uint32_t row[kUnroll8], col[kUnroll8];
+        bool valid[kUnroll8];
+        uint32_t r = c0 / q.chunks_per_row, cc = c0 - r * q.chunks_per_row;
+#pragma unroll
+        for (int u = 0; u < kUnroll8; ++u) {
+            row[u] = r;
+            col[u] = cc * kChunk8 + lane * 8;
+            valid[u] = c0 + u < q.total_chunks && col[u] < q.K;
+            v[u] = u32x4{0, 0, 0, 0};
+            if (valid[u])
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q.x + (int64_t)r * q.ldx + col[u]));
+            if (++cc == q.chunks_per_row) { cc = 0; ++r; }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll8; ++u) {
+            if (c0 + u >= q.total_chunks) break;  // wave-uniform
+            const Chunk8 res = quantize_chunk8<kElem, kHwCvt, kMbs>(v[u], q);
+            uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
+            if ((lane & 3) != 0) ew = 0;
+            ew |= dpp_row_ror4(ew);
+            ew |= dpp_row_ror8(ew);
+            if (!valid[u]) continue;
+            const uint32_t kblk = col[u] >> 5;
+            uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
+            *reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * q.K + col[u]) = make_uint2(res.lo, res.hi);
+            if (q.scales_dword) {
+                if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
+            } else if ((lane & 3) == 0) {
+                srow[kblk] = (uint8_t)res.E;
+            }
+            if (kMbs && (lane & 15) == 0) q.mbs[(int64_t)row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)res.m8;
+        }
+    }
+}
+
+int g_quant8_hwcvt = 1;
+
+template <int kElem>
+void launch8(const Quant8Args& q, int use_mbs, dim3 grid, hipStream_t s) {
+    const dim3 block(kThreads8);
+    if (g_quant8_hwcvt) {
+        if (use_mbs) hipLaunchKernelGGL((quantize8_kernel<kElem, true, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((quantize8_kernel<kElem, true, false>), grid, block, 0, s, q);
+    } else {
+        if (use_mbs) hipLaunchKernelGGL((quantize8_kernel<kElem, false, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((quantize8_kernel<kElem, false, false>), grid, block, 0, s, q);
+    }
+}
+
+int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                         uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    if (elem < MX_ELEM_E2M1 || elem > MX_ELEM_E3M2 || elem == MX_ELEM_E2M1) return MX_EINVAL;
+    if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
+    if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
+    if (rows == 0 || K == 0) return MX_OK;
+    if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
+    if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 8)) return MX_EALIGN;
+    if (elem != MX_ELEM_E4M3 && elem != MX_ELEM_E5M2) return MX_EUNSUPPORTED;  // the 6-bit formats
+    const int64_t chunks_per_row = (K + kChunk8 - 1) / kChunk8, total = rows * chunks_per_row;
+    if (total >= ((int64_t)1 << 32) - kUnroll8 || rows >= ((int64_t)1 << 31)) return MX_EINVAL;  // 32-bit chunk ids
+    if (int st = check_device()) return st;
+    Quant8Args q;
+    q.x = static_cast<const uint16_t*>(x);
+    q.codes = codes; q.scales = scales; q.mbs = mbs;
+    q.K = K; q.ldx = ldx; q.nmac = (K + kMacro - 1) / kMacro;
+    q.chunks_per_row = (uint32_t)chunks_per_row;
+    q.total_chunks = (uint32_t)total;
+    q.rule = rule;
+    q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
+    const bool e4 = elem == MX_ELEM_E4M3;
+    q.carry = rule == MX_RULE_FLOOR ? (e4 ? Fp8<MX_ELEM_E4M3>::kCarryFloor : Fp8<MX_ELEM_E5M2>::kCarryFloor)
+              : rule == MX_RULE_OAS ? (e4 ? Fp8<MX_ELEM_E4M3>::kCarryOas : Fp8<MX_ELEM_E5M2>::kCarryOas) : 0u;
+    const int64_t waves = (total + kUnroll8 - 1) / kUnroll8;
+    int64_t blocks = (waves + (kThreads8 / kWave) - 1) / (kThreads8 / kWave);
+    if (blocks > (1 << 22)) blocks = 1 << 22;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (e4) launch8<MX_ELEM_E4M3>(q, use_mbs, dim3((unsigned)blocks), s);
+    else launch8<MX_ELEM_E5M2>(q, use_mbs, dim3((unsigned)blocks), s);
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace mx
+
+extern "C" {
+
+int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                     int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize_elem((int)elem, x_bf16, rows, K, ldx, (int)rule, use_mbs, codes, scales, mbs, stream);
+}
+
+// Development switch (not part of the public ABI): 1 = hardware fp32->FP8 convert instruction, 0 = ordinary
+// arithmetic.  Both must give identical codes.
+void mx_internal_set_quantize_elem_convert(int hw) { mx::g_quant8_hwcvt = hw; }
+
+}  // extern "C"

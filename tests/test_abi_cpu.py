@@ -29,7 +29,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_quantize_mbs_pair", "mx_gemm_mbs_quantize_a", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
-            "mx_gemm_mbs_grouped", "mx_status_string", "mx_version"} <= set(names)
+            "mx_gemm_mbs_grouped", "mx_quantize_elem", "mx_gemm_mbs_elem", "mx_status_string", "mx_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -132,6 +132,30 @@ def test_gemm_argument_errors(lib):
     assert gg(A16, A16, None, A16, A16, None, 2, None, 8, 8, 64, 0, A16, 8, None) == -2
     assert gg(A16, A16, None, A16, A16, None, -1, A16, 8, 8, 64, 0, A16, 8, None) == -1
     assert gg(A16, A16, None, A16, A16, None, 0, A16, 8, 8, 64, 0, A16, 8, None) == 0
+
+
+def test_elem_argument_errors(lib):
+    q = lib.mx_quantize_elem
+    E4, E5, E23, E2M1 = 1, 2, 3, 0
+    assert q(E4, A16, 4, 48, 48, 2, 1, A16, A16, A16, None) == -1      # K % 32
+    assert q(E2M1, A16, 4, 64, 64, 2, 1, A16, A16, A16, None) == -1    # the 4-bit format has its own entry points
+    assert q(9, A16, 4, 64, 64, 2, 1, A16, A16, A16, None) == -1       # bad element format
+    assert q(E4, A16, 4, 64, 64, 5, 1, A16, A16, A16, None) == -1      # bad rule
+    assert q(E4, A16, 4, 64, 64, 2, 1, A16, A16, None, None) == -2     # MBS words wanted, no array
+    assert q(E4, None, 4, 64, 64, 2, 0, A16, A16, None, None) == -2
+    assert q(E5, A16, 4, 64, 64, 2, 0, A16 + 4, A16, None, None) == -3  # codes 8-byte aligned
+    assert q(E23, A16, 4, 64, 64, 2, 0, A16, A16, None, None) == -4    # 6-bit formats: declared, not built
+    assert q(E4, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0
+    g = lib.mx_gemm_mbs_elem
+    assert g(E4, A16, A16, None, E4, A16, A16, None, 8, 8, 48, 0, A16, 8, None) == -1
+    assert g(E2M1, A16, A16, None, E4, A16, A16, None, 8, 8, 128, 0, A16, 8, None) == -1
+    assert g(E4, A16, A16, None, E5, A16, A16, None, 8, 8, 128, 0, A16, 4, None) == -1   # ldc < N
+    assert g(E4, None, A16, None, E5, A16, A16, None, 8, 8, 128, 0, A16, 8, None) == -2
+    assert g(E4, A16, A16, None, E5, A16, A16, None, 8, 8, 128, 0, None, 8, None) == -2
+    assert g(E4, A16, A16, None, E5, A16, A16, None, 8, 8, 64, 0, A16, 8, None) == -4    # K % 128
+    assert g(E4, A16, A16, None, E5, A16, A16 + 2, None, 8, 8, 128, 0, A16, 8, None) == -4  # scale rows not dword-aligned
+    assert g(E4, A16, A16, None, E23, A16, A16, None, 8, 8, 128, 0, A16, 8, None) == -4  # 6-bit formats
+    assert g(E4, A16, A16, None, E5, A16, A16, None, 0, 8, 128, 0, A16, 8, None) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

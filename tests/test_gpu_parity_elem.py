@@ -1,0 +1,302 @@
+"""GPU parity for the 8-bit MX element formats (E4M3, E5M2): the HIP path through the C ABI against the CPU
+oracle on the same seeded inputs.  Bar as for MXFP4: bit-exact codes, E8M0 scales and MBS words; GEMM on
+quantized tensors within max|C - C_oracle| <= 1e-3 * RMS(C_oracle) on the fp32 output, and the bf16 output equal
+to the rounding of the kernel's own fp32 output.  Uniformly random codes are held to a per-output bound derived
+from how the matrix instruction adds FP8 products (see ABS_TOL), and sums that need no alignment must be exact.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+RULES = ("ocp", "floor", "oas")
+ELEMS = ("e4m3", "e5m2")
+MAX_CODE = {"e4m3": 0x7E, "e5m2": 0x7B}
+GEMM_TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def mx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_08713_amd as mx_
+
+    mx_.load_library()
+    return mx_
+
+
+def dev_bf16(bits: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def dev_u8(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return None if t is None else t.cpu().numpy()
+
+
+def set_convert(mx, hw: int):
+    mx.load_library().mx_internal_set_quantize_elem_convert(int(hw))
+
+
+def assert_quant_equal(mx, oracle, elem, bits, rule, mbs, what="", x=None):
+    x = dev_bf16(bits) if x is None else x
+    c, s, w = mx.mx_quantize_elem(x, elem, rule, use_mbs=mbs)
+    torch.cuda.synchronize()
+    oc, os_, ow = oracle.elem_quantize(elem, bits, rule, mbs=mbs)
+    tag = "%s %s rule=%s mbs=%s" % (what, elem, rule, mbs)
+    if mbs:
+        bad = np.argwhere(host(w) != ow)
+        assert bad.size == 0, "%s: %d MBS words differ, first at %s" % (tag, len(bad), bad[:3])
+    bad = np.argwhere(host(s) != os_)
+    assert bad.size == 0, "%s: %d scales differ, first at %s gpu=%s oracle=%s" % (
+        tag, len(bad), bad[:3], host(s)[tuple(bad[0])], os_[tuple(bad[0])])
+    bad = np.argwhere(host(c) != oc)
+    assert bad.size == 0, "%s: %d codes differ, first at %s gpu=%#x oracle=%#x" % (
+        tag, len(bad), bad[:3], host(c)[tuple(bad[0])], oc[tuple(bad[0])])
+
+
+# ------------------------------------------------------------------------------------------------
+# quantizer
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("hw", [1, 0])
+@pytest.mark.parametrize("elem", ELEMS)
+def test_quantize_elem_tiny_config(mx, oracle, elem, hw):
+    from paper_2603_08713_amd import synth
+
+    set_convert(mx, hw)
+    try:
+        a, w = synth.tiny(0)
+        for rule in RULES:
+            for mbs in (False, True):
+                assert_quant_equal(mx, oracle, elem, a, rule, mbs, "tiny A")
+                assert_quant_equal(mx, oracle, elem, w, rule, mbs, "tiny W")
+    finally:
+        set_convert(mx, 1)
+
+
+@pytest.mark.parametrize("hw", [1, 0])
+@pytest.mark.parametrize("elem", ELEMS)
+def test_quantize_elem_every_bf16_pattern(mx, oracle, elem, hw):
+    """All 65536 bf16 patterns (subnormals, Inf, NaN, both zeros): in natural order (blocks of similar
+    magnitude) and shuffled so that blocks mix magnitudes and elements land in every binade of the element
+    format, its subnormals included; plus exact ties of every spacing."""
+    set_convert(mx, hw)
+    try:
+        allbits = np.arange(65536, dtype=np.uint16).reshape(128, 512)
+        rng = np.random.default_rng(0)
+        flat = allbits.reshape(-1)
+        finite = flat[(flat & 0x7F80) != 0x7F80]
+        mid = finite[((finite >> 7) & 0xFF > 100) & ((finite >> 7) & 0xFF < 150)]
+        cases = {
+            "natural": allbits,
+            "shuffled-all": rng.permutation(flat).reshape(128, 512),
+            "shuffled-mid": rng.choice(mid, size=(96, 1024)),
+            "shuffled-finite": rng.choice(finite, size=(64, 640)),
+        }
+        # ties: odd multiples of half a spacing in every binade below a block maximum that is a power of two
+        # (scale 2^-e under OCP), for binades from the top of the format down into its subnormals
+        k = np.arange(1, 64, 2, dtype=np.float32)  # 32 odd numerators
+        rows = []
+        for e in range(0, 20):
+            row = k * np.float32(2.0) ** (-e - 5)
+            row[0] = 1.0  # the block maximum
+            rows.append(row)
+        t = np.stack(rows).astype(np.float32)
+        tb = (t.view(np.uint32) >> 16).astype(np.uint16)
+        assert np.array_equal((tb.astype(np.uint32) << 16).view(np.float32), t)
+        tb[:, 1::2] |= 0x8000
+        cases["ties"] = np.tile(tb, (1, 4))
+        for name, bits in cases.items():
+            for rule in RULES:
+                for mbs in (False, True):
+                    assert_quant_equal(mx, oracle, elem, bits, rule, mbs, name)
+    finally:
+        set_convert(mx, 1)
+
+
+@pytest.mark.parametrize("rows,K,ld", [(1, 32, 32), (3, 96, 104), (5, 2880, 2880), (2, 4096 + 64, 4232), (7, 512, 512),
+                                        (130, 160, 160)])
+def test_quantize_elem_ragged_shapes(mx, oracle, rows, K, ld):
+    from paper_2603_08713_amd import synth
+
+    rng = np.random.default_rng(rows * 1000 + K)
+    full = synth.to_bf16_bits(rng.standard_t(3, (rows, ld)))
+    x = dev_bf16(full)[:, :K]
+    for elem in ELEMS:
+        for rule, mbs in (("oas", True), ("ocp", False), ("floor", True)):
+            assert_quant_equal(mx, oracle, elem, full[:, :K], rule, mbs, "ragged", x=x)
+
+
+def test_quantize_elem_empty(mx):
+    x = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
+    c, s, w = mx.mx_quantize_elem(x, "e4m3")
+    assert c.shape == (0, 128) and s.shape == (0, 4) and w.shape == (0, 1)
+
+
+def test_quantize_elem_full_size_activation(mx, oracle):
+    """Llama-3-8B FFN activation shape (4096 x 4096); every 8th row is checked against the oracle."""
+    from paper_2603_08713_amd import synth
+
+    a = synth.activations_student_t(4096, 4096, 4.0, 0.01, 20.0, 1)
+    x = dev_bf16(a)
+    for elem, rule in (("e4m3", "oas"), ("e5m2", "oas"), ("e4m3", "ocp")):
+        c, s, w = mx.mx_quantize_elem(x, elem, rule, use_mbs=True)
+        torch.cuda.synchronize()
+        oc, os_, ow = oracle.elem_quantize(elem, a[::8], rule, mbs=True)
+        assert np.array_equal(host(w)[::8], ow) and np.array_equal(host(s)[::8], os_) and np.array_equal(host(c)[::8], oc)
+
+
+# ------------------------------------------------------------------------------------------------
+# GEMM
+# ------------------------------------------------------------------------------------------------
+def random_operand(rng, elem, rows, K, lo=110, hi=140):
+    """Uniformly random finite codes, a spread of E8M0 bytes, random MBS words."""
+    c = rng.integers(0, 256, (rows, K), dtype=np.uint8)
+    mag = c & 0x7F
+    c = np.where(mag > MAX_CODE[elem], (c & 0x80) | (mag & 0x3F), c).astype(np.uint8)
+    return (c, rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8), rng.integers(0, 256, (rows, K // 128), dtype=np.uint8))
+
+
+def gpu_gemm(mx, ea, a, eb, b, out_dtype="f32", out=None):
+    da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+    return mx.mx_gemm_mbs_elem(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], out_dtype, out=out)
+
+
+def assert_gemm_close(got, want, what=""):
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    err = float(np.max(np.abs(got.astype(np.float64) - want)))
+    assert err <= GEMM_TOL * rms, "%s: max err %.3e vs %.3e (rms %.3e)" % (what, err, GEMM_TOL * rms, rms)
+
+
+# The matrix instruction adds FP8 products with less than fp32 precision: inside a group of products it aligns
+# them to the group's largest exponent and cuts each off about 13 bits below it (measured: 448 * 448 + p, both
+# in one group, returns p truncated to a multiple of 8; the same p in another group comes back exact).  An
+# error of at most 2^-13 of the group's largest product per product is at most 15 * 2^-13 * sum_k |a_ik b_jk| per
+# output, and far less unless every group has one dominant product.  On quantized tensors this stays inside
+# the 1e-3 * RMS bar (tests below); uniformly random codes under scales spread over 30 binades are checked
+# against the per-output bound 2^-11 * sum_k |a_ik| |b_jk| (the largest measured ratio is below 2^-13).
+ABS_TOL = 2.0 ** -11
+
+
+def assert_gemm_within_abs_bound(oracle, got, ea, a, eb, b, what=""):
+    want = oracle.elem_gemm(ea, a, eb, b)
+    absc = oracle.elem_gemm(ea, (a[0] & 0x7F, a[1], a[2]), eb, (b[0] & 0x7F, b[1], b[2]))
+    ratio = np.abs(got.astype(np.float64) - want) / absc
+    assert float(np.nanmax(ratio)) <= ABS_TOL, "%s: max |err| / sum|a||b| = %.3e" % (what, float(np.nanmax(ratio)))
+
+
+@pytest.mark.parametrize("ea,eb", [("e4m3", "e4m3"), ("e4m3", "e5m2"), ("e5m2", "e4m3"), ("e5m2", "e5m2")])
+def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
+    """Exercises every code, scale byte and lane position of the operand layout; shapes span several tiles of
+    256 x 128 with ragged tails, K several turns of the three-slot ring plus each remainder."""
+    rng = np.random.default_rng(42)
+    hi = 132 if "e5m2" in (ea, eb) else 140  # keep |C| inside fp32 with E5M2's 2^15
+    for (M, N, K) in ((16, 16, 128), (64, 48, 256), (130, 200, 384), (257, 129, 1024), (300, 260, 640), (520, 390, 896)):
+        a, b = random_operand(rng, ea, M, K, 110, hi), random_operand(rng, eb, N, K, 110, hi)
+        assert_gemm_within_abs_bound(oracle, host(gpu_gemm(mx, ea, a, eb, b)), ea, a, eb, b, "mbs %dx%dx%d" % (M, N, K))
+        for a1, b1, name in (((a[0], a[1], None), b, "B words only"), (a, (b[0], b[1], None), "A words only"),
+                             ((a[0], a[1], None), (b[0], b[1], None), "no words")):
+            assert_gemm_within_abs_bound(oracle, host(gpu_gemm(mx, ea, a1, eb, b1)), ea, a1, eb, b1,
+                                         "%s %dx%dx%d" % (name, M, N, K))
+
+
+def test_gemm_elem_exact_on_small_integers(mx, oracle):
+    """Products that need no alignment (codes for 0, +-0.5, +-1, +-2, 4) add up exactly: any misplaced element,
+    scale byte or sigma shows as an integer-sized error."""
+    rng = np.random.default_rng(44)
+    pool = np.array([0x00, 0x30, 0xB0, 0x38, 0xB8, 0x40, 0xC0, 0x48], np.uint8)  # E4M3
+    M, N, K = 300, 200, 640
+    a = (rng.choice(pool, (M, K)), rng.integers(124, 131, (M, K // 32), dtype=np.uint8), np.zeros((M, K // 128), np.uint8))
+    b = (rng.choice(pool, (N, K)), rng.integers(124, 131, (N, K // 32), dtype=np.uint8), np.zeros((N, K // 128), np.uint8))
+    got = host(gpu_gemm(mx, "e4m3", a, "e4m3", b))
+    assert np.array_equal(got.astype(np.float64), oracle.elem_gemm("e4m3", a, "e4m3", b))
+    # MBS words whose sigma is a power of two or 2/3 (m8 = 0, 128): exact up to the rounding of 2/3
+    a = (a[0], a[1], rng.choice(np.array([0, 128], np.uint8), (M, K // 128)))
+    want = oracle.elem_gemm("e4m3", a, "e4m3", b)
+    got = host(gpu_gemm(mx, "e4m3", a, "e4m3", b))
+    assert np.max(np.abs(got - want)) <= 1e-5 * np.sqrt(np.mean(want ** 2))
+
+
+def test_gemm_elem_bf16_output_and_strided_c(mx, oracle):
+    rng = np.random.default_rng(43)
+    M, N, K = 96, 136, 512
+    a, b = random_operand(rng, "e4m3", M, K, 120, 134), random_operand(rng, "e4m3", N, K, 120, 134)
+    c32 = gpu_gemm(mx, "e4m3", a, "e4m3", b, "f32")
+    c16 = gpu_gemm(mx, "e4m3", a, "e4m3", b, "bf16")
+    assert torch.equal(c16, c32.to(torch.bfloat16))
+    big = torch.zeros((M, N + 24), dtype=torch.float32, device="cuda")
+    gpu_gemm(mx, "e4m3", a, "e4m3", b, "f32", out=big[:, :N])
+    assert torch.equal(big[:, :N], c32) and float(big[:, N:].abs().max()) == 0.0
+    # an odd number of columns and a C that only allows element stores
+    odd = torch.zeros((M, N + 3), dtype=torch.bfloat16, device="cuda")
+    gpu_gemm(mx, "e4m3", a, "e4m3", (b[0][:N - 1], b[1][:N - 1], b[2][:N - 1]), "bf16", out=odd[:, 1:N])
+    assert torch.equal(odd[:, 1:N], c16[:, :N - 1]) and float(odd[:, N:].abs().max()) == 0.0 and float(odd[:, 0].abs().max()) == 0.0
+
+
+def test_gemm_elem_empty_and_unsupported(mx):
+    z = torch.empty((0, 128), dtype=torch.uint8, device="cuda")
+    s = torch.empty((0, 4), dtype=torch.uint8, device="cuda")
+    b = torch.zeros((8, 128), dtype=torch.uint8, device="cuda")
+    bs = torch.full((8, 4), 127, dtype=torch.uint8, device="cuda")
+    assert mx.mx_gemm_mbs_elem("e4m3", z, s, None, "e4m3", b, bs, None).shape == (0, 8)
+    b64 = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
+    s64 = torch.full((8, 2), 127, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mx.MxError) as e:
+        mx.mx_gemm_mbs_elem("e4m3", b64, s64, None, "e4m3", b64, s64, None)  # K % 128 != 0
+    assert e.value.status == -4
+
+
+def test_gemm_elem_quantized_tensors_and_repeat(mx, oracle):
+    """Operands quantized on the GPU from heavy-tailed activations and Gaussian weights, every rule; the whole
+    result against the oracle, and a second launch bit-identical to the first."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 200, 300, 1152
+    a_bits = synth.activations_student_t(M, K, 3.0, 0.01, 20.0, 3)
+    w_bits = synth.gaussian(N, K, 0.02, 4)
+    xa, xw = dev_bf16(a_bits), dev_bf16(w_bits)
+    for ea, eb, rule in (("e4m3", "e4m3", "oas"), ("e5m2", "e4m3", "floor"), ("e4m3", "e5m2", "ocp")):
+        a = mx.mx_quantize_elem(xa, ea, rule)
+        b = mx.mx_quantize_elem(xw, eb, rule)
+        c = mx.mx_gemm_mbs_elem(ea, a[0], a[1], a[2], eb, b[0], b[1], b[2], "f32")
+        c2 = mx.mx_gemm_mbs_elem(ea, a[0], a[1], a[2], eb, b[0], b[1], b[2], "f32")
+        torch.cuda.synchronize()
+        assert torch.equal(c, c2)
+        ah, bh = [host(t) for t in a], [host(t) for t in b]
+        oa, ob = oracle.elem_quantize(ea, a_bits, rule, mbs=True), oracle.elem_quantize(eb, w_bits, rule, mbs=True)
+        assert all(np.array_equal(x, y) for x, y in zip(ah, oa)) and all(np.array_equal(x, y) for x, y in zip(bh, ob))
+        assert_gemm_close(host(c), oracle.elem_gemm(ea, oa, eb, ob), "%s x %s %s" % (ea, eb, rule))
+
+
+def test_gemm_elem_full_size_sampled_rows(mx, oracle):
+    """Llama-3-8B FFN up-projection shape in MXFP8 (E4M3), as bench.py launches it: sampled output rows against
+    the fp64 oracle, and QSNR(AB) against the bf16 product above MXFP4's (more element bits, same method)."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 4096, 14336, 4096
+    a_bits, w_bits = synth.llama8b_ffn_up(M, N, K)
+    xa, xw = dev_bf16(a_bits), dev_bf16(w_bits)
+    a = mx.mx_quantize_elem(xa, "e4m3", "oas")
+    b = mx.mx_quantize_elem(xw, "e4m3", "oas")
+    c = mx.mx_gemm_mbs_elem("e4m3", a[0], a[1], a[2], "e4m3", b[0], b[1], b[2], "f32")
+    c16 = mx.mx_gemm_mbs_elem("e4m3", a[0], a[1], a[2], "e4m3", b[0], b[1], b[2], "bf16")
+    torch.cuda.synchronize()
+    assert torch.equal(c16, c.to(torch.bfloat16))
+    assert bool(torch.isfinite(c).all())
+    rows = np.sort(np.random.default_rng(9).choice(M, 12, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    ah, bh = [host(t) for t in a], [host(t) for t in b]
+    want = oracle.elem_gemm("e4m3", ah, "e4m3", bh, rows=rows)
+    got = host(c[torch.from_numpy(rows).cuda()])
+    assert_gemm_close(got, want, "llama8b e4m3 sampled rows")
+    ref = oracle.matmul_bf16(a_bits, w_bits, rows=rows)
+    q8 = oracle.qsnr_db(ref, got)
+    a4, b4 = mx.mx_quantize_mbs(xa, "oas"), mx.mx_quantize_mbs(xw, "oas")
+    c4 = mx.mx_gemm_mbs(a4[0], a4[1], a4[2], b4[0], b4[1], b4[2], "f32")
+    q4 = oracle.qsnr_db(ref, host(c4[torch.from_numpy(rows).cuda()]))
+    assert q8 > q4 + 10.0, (q8, q4)
