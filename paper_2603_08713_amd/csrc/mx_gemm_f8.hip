@@ -16,12 +16,23 @@
 // Instruction kk of a macro block takes blocks 2 kk and 2 kk + 1: lane half h shifts the row's dword of four
 // E8M0 bytes right by 8 h and op_sel picks byte 2 kk.  D[8 (j / 4) + 4 h + j % 4][r] is result register j.
 //
-// Pipeline: one macro block per stage through a ring of three LDS slots (256 + 128 rows x 128 B each).  The
-// loads of stage s + 2 - code rows straight into LDS, 8 rows x 128 B per instruction; E8M0 dwords and MBS words
-// into registers - are issued when stage s starts, after the barrier that publishes stage s and frees the slot
-// of stage s - 1.  LDS image of a stage: [row][128 B], the 16-byte piece c of row r at position
-// c ^ ((r >> 1) & 7), which spreads the 16 lanes of a fragment read over all banks.  Each wavefront turns its own
-// 64 + 64 MBS words into fp32 sigma values in a private LDS table, so no second barrier is needed.
+// Pipeline: one macro block per stage through a ring of three LDS slots per operand (256 resp. 128 rows x 128 B).
+// The registers hold the fragments of stage s while the loads of stages s + 1 and s + 2 are in flight; the
+// barrier at the start of stage s publishes stage s + 1 and, because every wavefront read stage s out of its slot
+// during stage s - 1, frees that slot for the loads of stage s + 3.  A fragment is refilled from stage s + 1 right
+// after the last matrix instruction that reads it has been issued.  Code rows go straight into LDS, 8 rows x
+// 128 B per instruction; LDS image of a stage: [row][128 B], the 16-byte piece c of row r at position
+// c ^ ((r >> 1) & 7), which spreads the 16 lanes of a fragment read over all banks.
+//
+// E8M0 bytes and MBS words are a fraction of the bytes but not of the load instructions: a load of 4 bytes per
+// lane from 64 different rows costs the texture-address unit as much as four loads of 16 bytes per lane, and
+// fetched per stage they alone would take three times as long as the matrix instructions.  The fast form
+// (K % 512 == 0, 16-byte aligned E8M0 rows, 4-byte aligned MBS rows) therefore fetches them per group of four
+// stages: a row's 16 E8M0 bytes as one 16-byte piece into one of two LDS buffers, its four MBS words as one dword
+// into a register of the thread that owns the row.  That thread turns the word of stage s + 1 into
+// sigma = 1 / (1 + m8 / 256) during stage s, into one of two LDS tables that the barrier publishes.  The general
+// form (any K % 128 == 0) fetches one dword of E8M0 bytes and one MBS word per lane and stage into registers and
+// keeps a sigma table per wavefront.
 #include "mx_gemm_shared.h"
 
 namespace mx {
@@ -31,26 +42,35 @@ constexpr int kF8Slots = 3;
 constexpr int kF8RowStage = kMacro;  // code bytes per row and stage
 constexpr int kF8GroupM = 4;         // tile-rows walked together for L2 reuse
 
+template <bool kFast_>
 struct F8Shape {
+    static constexpr bool kFast = kFast_;
     static constexpr int NWM = 4, NWN = 2, FM = 2, FN = 2, NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32, kRows = TM + TN;
-    static constexpr int kCodeDma = kRows / 8 / NW;        // per wavefront and stage: 8 rows x 128 B per load
-    static constexpr int kRegLoads = FM + FN + 2;          // E8M0 dwords and MBS words per lane and stage
+    static constexpr int kCodeDma = kRows / 8 / NW;                     // per wavefront and stage: 8 rows x 128 B per load
+    static constexpr int kRegLoads = kFast ? 0 : FM + FN + 2;           // general form: E8M0 dwords and MBS words per lane and stage
     static constexpr int kLoads = kCodeDma + kRegLoads;
-    static constexpr int kStage = kRows * kF8RowStage;
-    static constexpr int kSigmaBase = kF8Slots * kStage;
-    static constexpr int kSigmaWave = (FM + FN) * 32 * 4;  // per wavefront: sigma of its A rows, then of its B rows
-    static constexpr int kLdsBytes = kSigmaBase + NW * kSigmaWave;
-    static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
+    static constexpr int kGroup = 4;                                    // fast form: stages per 16-byte piece of E8M0 bytes
+    static constexpr int kStageA = TM * kF8RowStage, kStageB = TN * kF8RowStage, kStage = kStageA + kStageB;
+    static constexpr int kBaseB = 0, kBaseA = kF8Slots * kStageB;       // the ring slots of B, then those of A
+    static constexpr int kSmallBase = kF8Slots * kStage;
+    // fast form: two buffers of [row][16 E8M0 bytes], two tables of [row] sigma; general form: a table per wavefront
+    static constexpr int kScaleGroup = kRows * 16, kSigmaTable = kRows * 4;
+    static constexpr int kSigmaBase = kSmallBase + (kFast ? 2 * kScaleGroup : 0);
+    static constexpr int kSigmaWave = (FM + FN) * 32 * 4;
+    static constexpr int kSpare = kSigmaBase + 2 * kSigmaTable;         // fast form: 1 KiB nobody reads
+    static constexpr int kLdsBytes = kFast ? kSpare + 1024 : kSigmaBase + NW * kSigmaWave;
+    static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);        // per wavefront, epilogue staging
     static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "operand fixed per load index");
+    static_assert(kRows % kWave == 0 && TM % kWave == 0, "fast form: a wavefront's rows belong to one operand");
     static_assert(kLdsBytes <= 160 * 1024 && NW * kStageRegion <= kLdsBytes, "LDS capacity of a gfx950 compute unit");
-    static_assert(2 * kLoads < 64, "vmcnt is a 6-bit counter");
+    static_assert(3 * kLoads + 4 < 64, "vmcnt is a 6-bit counter");
 };
 
 // kFmtA / kFmtB: the matrix instruction's format selector of tensor A / B (0 = E4M3, 1 = E5M2).
-template <int kFmtA, int kFmtB, bool kMbs>
-__global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
-    using S = F8Shape;
+template <int kFmtA, int kFmtB, bool kMbs, bool kFast>
+__global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g) {
+    using S = F8Shape<kFast>;
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, kCodeDma = S::kCodeDma;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -93,50 +113,73 @@ __global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
     // ---- per-lane byte offsets of the loads (constant over the K loop; the stage goes into the scalar offset) ----
     // Codes: load i of wavefront w covers rows (i * NW + w) * 8 .. + 7 of the A-then-B row space; lane l writes LDS
     // position l of that 1-KiB block and fetches row l / 8, piece (l % 8) ^ ((row >> 1) & 7).
-    int code_off[kCodeDma];
-#pragma unroll
-    for (int i = 0; i < kCodeDma; ++i) {
-        const int row = ((i * NW + w) * 8 + (l >> 3)) - (i * NW * 8 < TM ? 0 : TM);  // row within its operand
-        code_off[i] = row * K + (((l & 7) ^ ((row >> 1) & 7)) * 16);
-    }
-    int scale_off_a[FM], scale_off_b[FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i) scale_off_a[i] = ((wm * FM + i) * 32 + lr) * scale_bytes;
-#pragma unroll
-    for (int j = 0; j < FN; ++j) scale_off_b[j] = ((wn * FN + j) * 32 + lr) * scale_bytes;
+    // (load i adds i * NW * 8 whole rows, which leaves (row >> 1) & 7 as it is; the row has to stay in the per-lane
+    // offset, the only part of the address the hardware checks against the buffer's valid rows)
+    const int code_row0 = w * 8 + (l >> 3);
+    const int code_off0 = code_row0 * K + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
+    // general form: a lane's E8M0 dword per fragment and stage, and the MBS word of the row it converts
+    const int scale_off_a0 = (wm * FM * 32 + lr) * scale_bytes, scale_off_b0 = (wn * FN * 32 + lr) * scale_bytes;
     const int m8_off_a = (wm * FM * 32 + l) * nmac, m8_off_b = (wn * FN * 32 + l) * nmac;
+    // fast form: thread t < kRows owns row t of the A-then-B row space (wavefronts 0 .. 3: A, 4 and 5: B)
+    const bool owner_is_a = w * kWave < TM;
+    const int own_row = tid - (owner_is_a ? 0 : TM);
+    const int own_scale_off = tid < S::kRows ? own_row * scale_bytes : kOob, own_m8_off = tid < S::kRows ? own_row * nmac : kOob;
 
-    struct Pref {  // what a stage needs besides its codes
+    struct Pref {  // general form: what a stage needs besides its codes
         uint32_t sa[FM], sb[FN];
         uint32_t ma, mb;
     };
-    Pref pref[kF8Slots];
+    Pref pref[kFast ? 1 : kF8Slots];
+    uint32_t own_m8[kF8Slots] = {0u, 0u, 0u};  // fast form: the owned row's four MBS words of group g, in g % 3
 
-    // Loads of stage s into ring slot `slot`.  A stage past the end of K is never used; its loads fetch the last
-    // one again (into a slot that is no longer read), so that every stage issues the same number of loads.
-    auto issue = [&](int s, auto slot_) {
+    auto issue_codes = [&](int st, auto slot_) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_)::value;
+        static_for<kCodeDma>([&](auto i_) {
+            constexpr int i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
+            if constexpr (i < kLoadsA) {
+                uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
+                const int voff = code_off0 + i * NW * 8 * K;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+            } else {
+                uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
+                const int voff = code_off0 + (i - kLoadsA) * NW * 8 * K;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+            }
+        });
+    };
+    // Fast form: E8M0 bytes and MBS words of the four stages of group grp, the E8M0 bytes into LDS buffer grp % 2
+    // ([row][16]), the words into own_m8[grp % 3].  Wavefronts 6 and 7 own no rows: their loads are out of range
+    // and their 16-byte pieces (zeros) go to a spare KiB, which keeps the sequence free of branches.
+    const int ngroups = nstages / S::kGroup;
+    const bool owns = w * kWave < S::kRows;
+    const __amdgpu_buffer_rsrc_t own_scales = owner_is_a ? a_scales : b_scales, own_mbs = owner_is_a ? a_mbs : b_mbs;
+    auto issue_group = [&](int grp, auto mod3_) __attribute__((always_inline)) {  // mod3_: grp % 3
+        const int gg = min(grp, ngroups - 1);
+        uint8_t* dst = smem + (owns ? S::kSmallBase + (grp & 1) * S::kScaleGroup + w * 1024 : S::kSpare);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(own_scales, (lds_ptr_t)dst, 16, own_scale_off, gg * 16, 0, 0);
+        own_m8[decltype(mod3_)::value] = __builtin_amdgcn_raw_buffer_load_b32(own_mbs, own_m8_off, gg * 4, 0);
+    };
+    // Loads of stage s into ring slot `slot`; in the fast form the first stage of a group also requests the next
+    // group's E8M0 bytes and MBS words, ahead of the codes, so that the wait for the codes covers them.  A stage or
+    // group past the end of K is never used; its loads fetch the last one again (into places that are no longer
+    // read), so that every stage issues the same number of loads.
+    auto issue = [&](int s, auto slot_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
         const int st = min(s, nstages - 1);
         asm volatile("" ::: "memory");
-        static_for<kCodeDma>([&](auto i_) {
-            constexpr int i = decltype(i_)::value;
-            uint8_t* dst = smem + slot * S::kStage + (i * NW + w) * 1024;
-            const int voff = code_off[i];
-            if constexpr (i * NW * 8 < TM)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
-            else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
-        });
-        static_for<FM>([&](auto i_) {
-            const int voff = scale_off_a[decltype(i_)::value];
-            pref[slot].sa[decltype(i_)::value] = __builtin_amdgcn_raw_buffer_load_b32(a_scales, voff, st * 4, 0);
-        });
-        static_for<FN>([&](auto j_) {
-            const int voff = scale_off_b[decltype(j_)::value];
-            pref[slot].sb[decltype(j_)::value] = __builtin_amdgcn_raw_buffer_load_b32(b_scales, voff, st * 4, 0);
-        });
-        pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
-        pref[slot].mb = __builtin_amdgcn_raw_buffer_load_b8(b_mbs, m8_off_b, st, 0);
+        issue_codes(st, slot_);
+        if constexpr (!kFast) {
+            static_for<FM>([&](auto i_) {
+                const int voff = scale_off_a0 + decltype(i_)::value * 32 * scale_bytes;
+                pref[slot].sa[decltype(i_)::value] = __builtin_amdgcn_raw_buffer_load_b32(a_scales, voff, st * 4, 0);
+            });
+            static_for<FN>([&](auto j_) {
+                const int voff = scale_off_b0 + decltype(j_)::value * 32 * scale_bytes;
+                pref[slot].sb[decltype(j_)::value] = __builtin_amdgcn_raw_buffer_load_b32(b_scales, voff, st * 4, 0);
+            });
+            pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
+            pref[slot].mb = __builtin_amdgcn_raw_buffer_load_b8(b_mbs, m8_off_b, st, 0);
+        }
         // (the waits below count loads: keep the compiler from mixing the loads of two stages)
         asm volatile("" ::: "memory");
     };
@@ -149,75 +192,117 @@ __global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + w * S::kSigmaWave);
-    // this lane's 16-byte pieces inside a fragment's 32 rows: instruction kk, register half `part` takes the
-    // piece lh of block 2 kk + part, i.e. piece 2 (2 kk + part) + lh of row lr
-    int piece_off[2][2];
+    // general form: this wavefront's sigma table; fast form: the workgroup's two tables, [row] of the A-then-B space
+    float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + (kFast ? 0 : w * S::kSigmaWave));
+    // The LDS read instruction adds a 16-bit constant to its address register: with the wavefront's first row
+    // folded into the register, ring slot and fragment are that constant, and A's third slot, which lies more
+    // than 64 KiB up, gets a second copy of the registers (the empty asm keeps the compiler from folding the
+    // copies back into one base plus additions).
+    int frag_b[2][2], frag_a[2][2], frag_a_hi[2][2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int part = 0; part < 2; ++part)
-            piece_off[kk][part] = lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
+        for (int part = 0; part < 2; ++part) {
+            const int piece = lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
+            frag_b[kk][part] = S::kBaseB + wn * FN * 32 * kF8RowStage + piece;
+            frag_a[kk][part] = S::kBaseA + wm * FM * 32 * kF8RowStage + piece;
+            frag_a_hi[kk][part] = frag_a[kk][part] + 65536;
+            asm volatile("" : "+v"(frag_b[kk][part]));
+            asm volatile("" : "+v"(frag_a[kk][part]));
+            asm volatile("" : "+v"(frag_a_hi[kk][part]));
+        }
 
-    auto stage = [&](int s, auto slot_) {
+    // Operands of one macro block in registers.  They are refilled in place: a fragment takes the next stage's
+    // data right after the last matrix instruction that reads it has been issued.
+    v8i fa[FM][2], fb[FN][2];
+    auto read_frag = [&](auto slot_, auto is_a_, auto idx_, auto kk_) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_)::value, idx = decltype(idx_)::value, kk = decltype(kk_)::value;
+        constexpr bool is_a = decltype(is_a_)::value;
+        constexpr int off = (is_a ? slot * S::kStageA : slot * S::kStageB) + idx * 32 * kF8RowStage;
+        constexpr bool far = is_a && off >= 65536;  // past the range of the instruction's constant
+        const int b0 = is_a ? (far ? frag_a_hi[kk][0] : frag_a[kk][0]) : frag_b[kk][0];
+        const int b1 = is_a ? (far ? frag_a_hi[kk][1] : frag_a[kk][1]) : frag_b[kk][1];
+        const v4i lo = *reinterpret_cast<const v4i*>(smem + b0 + (far ? off - 65536 : off));
+        const v4i hi = *reinterpret_cast<const v4i*>(smem + b1 + (far ? off - 65536 : off));
+        const v8i v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        if constexpr (is_a) fa[idx][kk] = v;
+        else fb[idx][kk] = v;
+    };
+    using IsA = std::integral_constant<bool, true>;
+    using IsB = std::integral_constant<bool, false>;
+
+    // E8M0 operands of a stage: lane half h supplies the byte of block 2 kk + h, i.e. bytes h and 2 + h of the row's
+    // four, so the dword goes in shifted right by 8 h and op_sel picks byte 0 or 2.
+    uint32_t scl_a[FM], scl_b[FN];
+    const int lane_scale_a = S::kSmallBase + (wm * FM * 32 + lr) * 16, lane_scale_b = S::kSmallBase + (TM + wn * FN * 32 + lr) * 16;
+    auto read_scales_fast = [&](int s) __attribute__((always_inline)) {  // stage s out of its group's LDS buffer
+        const int at = ((s / S::kGroup) & 1) * S::kScaleGroup + (s % S::kGroup) * 4;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            scl_a[i] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_a + at + i * 32 * 16) >> (8 * lh);
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            scl_b[j] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_b + at + j * 32 * 16) >> (8 * lh);
+    };
+    // fast form: the owner of a row turns its MBS word of stage s into sigma, into table s % 2
+    auto convert_sigma_fast = [&](int s, auto mod3_) __attribute__((always_inline)) {  // mod3_: (s / 4) % 3
+        const uint32_t words = own_m8[decltype(mod3_)::value];
+        const uint32_t m8 = (words >> (8 * (s % S::kGroup))) & 0xFFu;
+        // (threads that own no row store to the spare KiB: no branch)
+        float* dst = tid < S::kRows ? sig + (s & 1) * S::kRows + tid : reinterpret_cast<float*>(smem + S::kSpare) + l;
+        *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
+    };
+
+    // One stage.  On entry the registers hold the fragments (fast form: and the E8M0 operands) of stage s; the
+    // loads of stages s + 1 and s + 2 are in flight.
+    auto stage = [&](int s, auto slot_, auto phase_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
-        // own loads of stage s have landed (those of stage s + 1 may still fly); own LDS traffic is done.  (The
-        // count is only right if every load of the previous stage's issue() has been issued by now: the empty
-        // asm keeps the compiler from moving one across.)
+        using Next = std::integral_constant<int, (slot + 1) % kF8Slots>;
+        // own loads of stage s + 1 have landed (those of stage s + 2 may still fly; the fast form's group loads
+        // are requested ahead of a stage's codes, so they have landed a stage after their request); own LDS
+        // traffic is done.  (The count is only right if every load of the earlier issue() calls has been issued
+        // by now: the empty asm keeps the compiler from moving one across.)
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_imm(S::kLoads));
-        bare_barrier();  // stage s is published; every wavefront has left stage s - 1, whose slot is free
-        issue(s + 2, std::integral_constant<int, (slot + 2) % kF8Slots>{});
-
-        float sig_m[FM];
-        v4f sig_n[FN][4];
-        if constexpr (kMbs) {
-            sig[l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].ma * (1.0f / 256.0f));
-            sig[64 + l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].mb * (1.0f / 256.0f));
+        bare_barrier();
+        if constexpr (kFast) {
+            // (t: the stage's place in the turn of the loop, 3 groups of 4 stages)
+            constexpr int t = decltype(phase_)::value;
+            if constexpr (kMbs) convert_sigma_fast(s + 1, std::integral_constant<int, (t + 1) / S::kGroup % 3>{});  // (past the end: a table nobody reads)
+            if constexpr (t % S::kGroup == 0) issue_group(s / S::kGroup + 1, std::integral_constant<int, (t / S::kGroup + 1) % 3>{});
+        } else {
+            // what this stage needs of its prefetched registers, before the loads of stage s + 3 take them over
+#pragma unroll
+            for (int i = 0; i < FM; ++i) scl_a[i] = pref[slot].sa[i] >> (8 * lh);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) scl_b[j] = pref[slot].sb[j] >> (8 * lh);
+            if constexpr (kMbs) {
+                sig[l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].ma * (1.0f / 256.0f));
+                sig[64 + l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].mb * (1.0f / 256.0f));
+            }
         }
-        // fragments of the stage
-        v8i fa[FM][2], fb[FN][2];
-        const uint8_t* base = smem + slot * S::kStage;
-        static_for<FN>([&](auto j_) {
-            constexpr int j = decltype(j_)::value;
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const uint8_t* p = base + (TM + (wn * FN + j) * 32) * kF8RowStage;
-                const v4i lo = *reinterpret_cast<const v4i*>(p + piece_off[kk][0]);
-                const v4i hi = *reinterpret_cast<const v4i*>(p + piece_off[kk][1]);
-                fb[j][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        });
-        static_for<FM>([&](auto i_) {
-            constexpr int i = decltype(i_)::value;
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const uint8_t* p = base + ((wm * FM + i) * 32) * kF8RowStage;
-                const v4i lo = *reinterpret_cast<const v4i*>(p + piece_off[kk][0]);
-                const v4i hi = *reinterpret_cast<const v4i*>(p + piece_off[kk][1]);
-                fa[i][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        });
+        issue(s + 3, slot_);
+
+        // sigma of this lane's output row per A fragment; of its 16 output columns per B fragment, kept as four
+        // registers: lane l holds the value of column 8 gq + 4 h + l % 4, and the multiply fetches column i from
+        // lane i of its group of four (DPP quad_perm), a quarter of the LDS traffic of reading all sixteen into
+        // every lane
+        float sig_m[FM];
+        uint32_t sig_n[FN][4];
         if constexpr (kMbs) {
+            const float* sa = kFast ? sig + (s & 1) * S::kRows + wm * FM * 32 : sig;
+            const float* sb = kFast ? sig + (s & 1) * S::kRows + TM + wn * FN * 32 : sig + 64;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) sig_m[i] = sig[i * 32 + lr];
+            for (int i = 0; i < FM; ++i) sig_m[i] = sa[i * 32 + lr];
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int gq = 0; gq < 4; ++gq)
-                    sig_n[j][gq] = *reinterpret_cast<const v4f*>(sig + 64 + j * 32 + gq * 8 + lh * 4);
+                for (int gq = 0; gq < 4; ++gq) sig_n[j][gq] = __float_as_uint(sb[j * 32 + gq * 8 + lh * 4 + (l & 3)]);
         }
-        // lane half h supplies the E8M0 byte of block 2 kk + h: bytes h and 2 + h of the row's four
-        uint32_t scl_a[FM], scl_b[FN];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) scl_a[i] = pref[slot].sa[i] >> (8 * lh);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) scl_b[j] = pref[slot].sb[j] >> (8 * lh);
-
         if constexpr (kMbs) {
             constexpr int kPairs = FM * FN;
             v16f prod[2];
-            auto product = [&](auto q_) {
+            auto product = [&](auto q_) __attribute__((always_inline)) {  // the instructions of pair q, then the refills they make possible
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 v16f zero;
 #pragma unroll
@@ -226,46 +311,85 @@ __global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
                                                                                 (int)scl_b[j], 0, (int)scl_a[i]);
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][1], fa[i][1], prod[q % 2], kFmtB, kFmtA,
                                                                                 2, (int)scl_b[j], 2, (int)scl_a[i]);
+                if constexpr (i == FM - 1) {
+                    read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 0>{});
+                    read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 1>{});
+                }
+                if constexpr (j == FN - 1) {
+                    read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, 0>{});
+                    read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, 1>{});
+                }
             };
             product(std::integral_constant<int, 0>{});
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 if constexpr (q + 1 < kPairs) product(std::integral_constant<int, q + 1>{});
+                // (every instruction of the stage has its E8M0 operands: the next stage's may replace them)
+                if constexpr (kFast && q + 1 == kPairs - 1) read_scales_fast(s + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 const float sm = sig_m[i];
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    acc[i][j][e] = fmaf(prod[q % 2][e], sm * sig_n[j][e / 4][e % 4], acc[i][j][e]);
+                static_for<16>([&](auto e_) {
+                    constexpr int e = decltype(e_)::value;
+                    // sigma_A * sigma_B with the DPP fetch folded into the multiply (written out: the compiler
+                    // keeps the fetch as a move of its own)
+                    float ww;
+                    if constexpr (e % 4 == 0) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
+                    if constexpr (e % 4 == 1) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
+                    if constexpr (e % 4 == 2) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
+                    if constexpr (e % 4 == 3) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
+                    acc[i][j][e] = fmaf(prod[q % 2][e], ww, acc[i][j][e]);
+                });
                 __builtin_amdgcn_sched_barrier(0);
             });
         } else {
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = kk == 0 ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                                  fb[j][0], fa[i][0], acc[i][j], kFmtB, kFmtA, 0, (int)scl_b[j], 0, (int)scl_a[i])
-                                            : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                                  fb[j][1], fa[i][1], acc[i][j], kFmtB, kFmtA, 2, (int)scl_b[j], 2, (int)scl_a[i]);
+            // instruction t: half kk = t / (FM FN) of pair (i, j); a fragment half is refilled after its last use
+            static_for<2 * FM * FN>([&](auto t_) {
+                constexpr int t = decltype(t_)::value, kk = t / (FM * FN), i = t % (FM * FN) / FN, j = t % FN;
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][kk], fa[i][kk], acc[i][j], kFmtB, kFmtA, 2 * kk,
+                                                                             (int)scl_b[j], 2 * kk, (int)scl_a[i]);
+                if constexpr (i == FM - 1) read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, kk>{});
+                if constexpr (j == FN - 1) read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, kk>{});
+                if constexpr (kFast && t == 2 * FM * FN - 1) read_scales_fast(s + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
     };
 
-    // ---- prologue, main loop ----
+    // ---- prologue: three stages of loads in flight, the fragments of stage 0 into registers ----
+    if constexpr (kFast) issue_group(0, std::integral_constant<int, 0>{});
     issue(0, std::integral_constant<int, 0>{});
     issue(1, std::integral_constant<int, 1>{});
-    // (whole turns of the ring in the loop, the rest after it: a loop body with early exits would make the
-    // compiler assume the shortest path between a register load and its use, and wait for far too much)
-    int s = 0;
-    for (; s + kF8Slots <= nstages; s += kF8Slots) {
-        stage(s, std::integral_constant<int, 0>{});
-        stage(s + 1, std::integral_constant<int, 1>{});
-        stage(s + 2, std::integral_constant<int, 2>{});
+    issue(2, std::integral_constant<int, 2>{});
+    __builtin_amdgcn_s_waitcnt(wait_imm(2 * S::kLoads));
+    if constexpr (kFast && kMbs) {
+        convert_sigma_fast(0, std::integral_constant<int, 0>{});
+        __builtin_amdgcn_s_waitcnt(kWaitLds);
     }
+    bare_barrier();
+    static_for<2>([&](auto kk_) {
+        static_for<FN>([&](auto j_) { read_frag(std::integral_constant<int, 0>{}, IsB{}, j_, kk_); });
+        static_for<FM>([&](auto i_) { read_frag(std::integral_constant<int, 0>{}, IsA{}, i_, kk_); });
+    });
+    if constexpr (kFast) read_scales_fast(0);
+    // The loop body is a whole number of turns of the ring and, in the fast form, of groups, so that ring slot and
+    // place in the group are compile-time constants; what is left of K follows after the loop, as the first
+    // stages of one more turn.  (A loop body with early exits would also make the compiler assume the shortest
+    // path between a register load and its use, and wait for far too much.)
+    constexpr int kTurn = kFast ? kF8Slots * S::kGroup : kF8Slots;
+    constexpr int kStep = kFast ? S::kGroup : 1;  // the stage count is a multiple of this
+    auto run = [&](int s0, auto first_, auto count_) __attribute__((always_inline)) {
+        static_for<decltype(count_)::value>([&](auto t_) {
+            constexpr int t = decltype(first_)::value + decltype(t_)::value;
+            stage(s0 + t, std::integral_constant<int, t % kF8Slots>{}, std::integral_constant<int, t>{});
+        });
+    };
+    using Zero = std::integral_constant<int, 0>;
+    using Step = std::integral_constant<int, kStep>;
+    int s = 0;
+    for (; s + kTurn <= nstages; s += kTurn) run(s, Zero{}, std::integral_constant<int, kTurn>{});
     if (s < nstages) {
-        stage(s, std::integral_constant<int, 0>{});
-        if (s + 1 < nstages) stage(s + 1, std::integral_constant<int, 1>{});
+        run(s, Zero{}, Step{});
+        if (s + kStep < nstages) run(s, Step{}, Step{});
     }
 
     // ---- epilogue ----
@@ -277,7 +401,7 @@ __global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
     constexpr int kCols = FN * 32;
     uint8_t* stg = smem + w * S::kStageRegion;
     const int64_t m0 = a_row0 + wm * FM * 32, n0 = b_row0 + wn * kCols;
-    auto flush = [&](auto bf16_) {
+    auto flush = [&](auto bf16_) __attribute__((always_inline)) {
         constexpr bool kBf16 = decltype(bf16_)::value;
         constexpr int esz = kBf16 ? 2 : 4, per = 16 / esz;
         constexpr int pitch = kCols * esz + 16;  // the pad spreads the staged rows over the banks
@@ -322,11 +446,11 @@ __global__ __launch_bounds__(F8Shape::NT) void gemm_f8_kernel(GemmArgs g) {
     else flush(std::integral_constant<bool, false>{});
 }
 
-template <int kFmtA, int kFmtB, bool kMbs>
+template <int kFmtA, int kFmtB, bool kMbs, bool kFast>
 int launch_f8_kernel(const GemmArgs& g, unsigned blocks, hipStream_t s) {
-    using S = F8Shape;
+    using S = F8Shape<kFast>;
     static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
-    auto* fn = gemm_f8_kernel<kFmtA, kFmtB, kMbs>;
+    auto* fn = gemm_f8_kernel<kFmtA, kFmtB, kMbs, kFast>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kLdsBytes) != hipSuccess) {
@@ -339,15 +463,23 @@ int launch_f8_kernel(const GemmArgs& g, unsigned blocks, hipStream_t s) {
     return launch_status();
 }
 
+// development switch: 1 = always the general form
+int g_f8_general = 0;
+
 template <int kFmtA, int kFmtB>
 int launch_f8(GemmArgs g, bool use_mbs, hipStream_t s) {
-    using S = F8Shape;
+    using S = F8Shape<true>;
     const int64_t tiles_m = (g.M + S::TM - 1) / S::TM, tiles_n = (g.N + S::TN - 1) / S::TN;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
     const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
-    return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false>(g, blocks, s);
+    // fast form: E8M0 bytes and MBS words travel per group of four stages, as 16-byte pieces and dwords
+    const bool fast = !g_f8_general && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
+                      (!g.a_mbs || aligned(g.a_mbs, 4)) && (!g.b_mbs || aligned(g.b_mbs, 4));
+    if (fast)
+        return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, true>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, true>(g, blocks, s);
+    return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, false>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, false>(g, blocks, s);
 }
 
 int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, int b_elem,
@@ -393,3 +525,6 @@ extern "C" int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const 
     return mx::launch_gemm_elem((int)a_elem, a_codes, a_scales, a_mbs_or_null, (int)b_elem, b_codes, b_scales,
                                 b_mbs_or_null, M, N, K, (int)c_dtype, C, ldc, stream);
 }
+
+// Development switch (not part of the public ABI): 1 = the general form also where the fast form applies.
+extern "C" void mx_internal_set_gemm_elem_general(int general) { mx::g_f8_general = general; }

@@ -196,7 +196,10 @@ def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
     256 x 128 with ragged tails, K several turns of the three-slot ring plus each remainder."""
     rng = np.random.default_rng(42)
     hi = 132 if "e5m2" in (ea, eb) else 140  # keep |C| inside fp32 with E5M2's 2^15
-    for (M, N, K) in ((16, 16, 128), (64, 48, 256), (130, 200, 384), (257, 129, 1024), (300, 260, 640), (520, 390, 896)):
+    # (K % 512 == 0 takes the kernel's fast form: 1, 2, 3 and 4 groups of four stages, then one turn of the loop,
+    # and one turn plus one and plus two groups)
+    for (M, N, K) in ((16, 16, 128), (64, 48, 256), (130, 200, 384), (257, 129, 1024), (300, 260, 640), (520, 390, 896),
+                      (40, 200, 512), (257, 130, 1536), (100, 129, 2048), (70, 140, 6144), (33, 260, 6656), (260, 33, 7168)):
         a, b = random_operand(rng, ea, M, K, 110, hi), random_operand(rng, eb, N, K, 110, hi)
         assert_gemm_within_abs_bound(oracle, host(gpu_gemm(mx, ea, a, eb, b)), ea, a, eb, b, "mbs %dx%dx%d" % (M, N, K))
         for a1, b1, name in (((a[0], a[1], None), b, "B words only"), (a, (b[0], b[1], None), "A words only"),
@@ -205,16 +208,35 @@ def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
                                          "%s %dx%dx%d" % (name, M, N, K))
 
 
+def test_gemm_elem_general_form_equals_fast_form(mx, oracle):
+    """Where both forms of the kernel apply they run the same matrix instructions on the same data in the same
+    order: bit-identical results."""
+    rng = np.random.default_rng(45)
+    lib = mx.load_library()
+    for (M, N, K) in ((300, 200, 512), (257, 390, 2048), (64, 128, 6656)):
+        a, b = random_operand(rng, "e4m3", M, K, 118, 136), random_operand(rng, "e5m2", N, K, 118, 132)
+        for words in (True, False):
+            a1 = a if words else (a[0], a[1], None)
+            b1 = b if words else (b[0], b[1], None)
+            fast = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
+            lib.mx_internal_set_gemm_elem_general(1)
+            try:
+                general = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
+            finally:
+                lib.mx_internal_set_gemm_elem_general(0)
+            assert torch.equal(fast, general), (M, N, K, words)
+
+
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
     """Products that need no alignment (codes for 0, +-0.5, +-1, +-2, 4) add up exactly: any misplaced element,
     scale byte or sigma shows as an integer-sized error."""
     rng = np.random.default_rng(44)
     pool = np.array([0x00, 0x30, 0xB0, 0x38, 0xB8, 0x40, 0xC0, 0x48], np.uint8)  # E4M3
-    M, N, K = 300, 200, 640
-    a = (rng.choice(pool, (M, K)), rng.integers(124, 131, (M, K // 32), dtype=np.uint8), np.zeros((M, K // 128), np.uint8))
-    b = (rng.choice(pool, (N, K)), rng.integers(124, 131, (N, K // 32), dtype=np.uint8), np.zeros((N, K // 128), np.uint8))
-    got = host(gpu_gemm(mx, "e4m3", a, "e4m3", b))
-    assert np.array_equal(got.astype(np.float64), oracle.elem_gemm("e4m3", a, "e4m3", b))
+    for M, N, K in ((300, 200, 640), (200, 300, 1536)):
+        a = (rng.choice(pool, (M, K)), rng.integers(124, 131, (M, K // 32), dtype=np.uint8), np.zeros((M, K // 128), np.uint8))
+        b = (rng.choice(pool, (N, K)), rng.integers(124, 131, (N, K // 32), dtype=np.uint8), np.zeros((N, K // 128), np.uint8))
+        got = host(gpu_gemm(mx, "e4m3", a, "e4m3", b))
+        assert np.array_equal(got.astype(np.float64), oracle.elem_gemm("e4m3", a, "e4m3", b))
     # MBS words whose sigma is a power of two or 2/3 (m8 = 0, 128): exact up to the rounding of 2/3
     a = (a[0], a[1], rng.choice(np.array([0, 128], np.uint8), (M, K // 128)))
     want = oracle.elem_gemm("e4m3", a, "e4m3", b)
