@@ -64,7 +64,7 @@ struct F8Shape {
     static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "operand fixed per load index");
     static_assert(kRows % kWave == 0 && TM % kWave == 0, "fast form: a wavefront's rows belong to one operand");
     static_assert(kLdsBytes <= 160 * 1024 && NW * kStageRegion <= kLdsBytes, "LDS capacity of a gfx950 compute unit");
-    static_assert(3 * kLoads + 4 < 64, "vmcnt is a 6-bit counter");
+    static_assert(kCodeDma <= 2 * FM * FN - 2 && 3 * kLoads + 4 < 64, "vmcnt is a 6-bit counter");
 };
 
 // kFmtA / kFmtB: the matrix instruction's format selector of tensor A / B (0 = E4M3, 1 = E5M2).
@@ -132,20 +132,18 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     Pref pref[kFast ? 1 : kF8Slots];
     uint32_t own_m8[kF8Slots] = {0u, 0u, 0u};  // fast form: the owned row's four MBS words of group g, in g % 3
 
-    auto issue_codes = [&](int st, auto slot_) __attribute__((always_inline)) {
-        constexpr int slot = decltype(slot_)::value;
-        static_for<kCodeDma>([&](auto i_) {
-            constexpr int i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
-            if constexpr (i < kLoadsA) {
-                uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
-                const int voff = code_off0 + i * NW * 8 * K;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
-            } else {
-                uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
-                const int voff = code_off0 + (i - kLoadsA) * NW * 8 * K;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
-            }
-        });
+    // load i of the codes of stage st (a stage past the end of K fetches the last one again) into ring slot `slot`
+    auto issue_code = [&](int st, auto slot_, auto i_) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_)::value, i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
+        if constexpr (i < kLoadsA) {
+            uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
+            const int voff = code_off0 + i * NW * 8 * K;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+        } else if constexpr (i < kCodeDma) {
+            uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
+            const int voff = code_off0 + (i - kLoadsA) * NW * 8 * K;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+        }
     };
     // Fast form: E8M0 bytes and MBS words of the four stages of group grp, the E8M0 bytes into LDS buffer grp % 2
     // ([row][16]), the words into own_m8[grp % 3].  Wavefronts 6 and 7 own no rows: their loads are out of range
@@ -159,15 +157,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(own_scales, (lds_ptr_t)dst, 16, own_scale_off, gg * 16, 0, 0);
         own_m8[decltype(mod3_)::value] = __builtin_amdgcn_raw_buffer_load_b32(own_mbs, own_m8_off, gg * 4, 0);
     };
-    // Loads of stage s into ring slot `slot`; in the fast form the first stage of a group also requests the next
-    // group's E8M0 bytes and MBS words, ahead of the codes, so that the wait for the codes covers them.  A stage or
-    // group past the end of K is never used; its loads fetch the last one again (into places that are no longer
-    // read), so that every stage issues the same number of loads.
-    auto issue = [&](int s, auto slot_) __attribute__((always_inline)) {
+    // General form: E8M0 dwords and MBS words of stage st into the registers of ring slot `slot`.
+    auto issue_regs = [&](int st, auto slot_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
-        const int st = min(s, nstages - 1);
-        asm volatile("" ::: "memory");
-        issue_codes(st, slot_);
         if constexpr (!kFast) {
             static_for<FM>([&](auto i_) {
                 const int voff = scale_off_a0 + decltype(i_)::value * 32 * scale_bytes;
@@ -180,7 +172,14 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
             pref[slot].mb = __builtin_amdgcn_raw_buffer_load_b8(b_mbs, m8_off_b, st, 0);
         }
-        // (the waits below count loads: keep the compiler from mixing the loads of two stages)
+    };
+    // All loads of stage s at once (prologue).  The stage's waits count loads: the empty asm keeps the compiler from
+    // mixing the loads of two stages.
+    auto issue = [&](int s, auto slot_) __attribute__((always_inline)) {
+        const int st = min(s, nstages - 1);
+        asm volatile("" ::: "memory");
+        issue_regs(st, slot_);
+        static_for<kCodeDma>([&](auto i_) { issue_code(st, slot_, i_); });
         asm volatile("" ::: "memory");
     };
 
@@ -281,7 +280,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 sig[64 + l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].mb * (1.0f / 256.0f));
             }
         }
-        issue(s + 3, slot_);
+        // the loads of stage s + 3: registers now (general form), the codes one by one behind the matrix
+        // instructions - a direct-to-LDS load holds its wavefront up for as long as the texture-address unit needs
+        // for its 64 lanes, and six in a row from all eight wavefronts would stall the matrix pipeline
+        const int st3 = min(s + 3, nstages - 1);
+        issue_regs(st3, slot_);
 
         // sigma of this lane's output row per A fragment; of its 16 output columns per B fragment, kept as four
         // registers: lane l holds the value of column 8 gq + 4 h + l % 4, and the multiply fetches column i from
@@ -309,8 +312,10 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 for (int e = 0; e < 16; ++e) zero[e] = 0.f;
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][0], fa[i][0], zero, kFmtB, kFmtA, 0,
                                                                                 (int)scl_b[j], 0, (int)scl_a[i]);
+                issue_code(st3, slot_, std::integral_constant<int, 2 * q>{});
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][1], fa[i][1], prod[q % 2], kFmtB, kFmtA,
                                                                                 2, (int)scl_b[j], 2, (int)scl_a[i]);
+                issue_code(st3, slot_, std::integral_constant<int, 2 * q + 1>{});
                 if constexpr (i == FM - 1) {
                     read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 0>{});
                     read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 1>{});
@@ -347,6 +352,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 constexpr int t = decltype(t_)::value, kk = t / (FM * FN), i = t % (FM * FN) / FN, j = t % FN;
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][kk], fa[i][kk], acc[i][j], kFmtB, kFmtA, 2 * kk,
                                                                              (int)scl_b[j], 2 * kk, (int)scl_a[i]);
+                issue_code(st3, slot_, t_);
                 if constexpr (i == FM - 1) read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, kk>{});
                 if constexpr (j == FN - 1) read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, kk>{});
                 if constexpr (kFast && t == 2 * FM * FN - 1) read_scales_fast(s + 1);
