@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_gemm_mbs_grouped.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_quantize_elem.restype = ci
     L.mx_quantize_elem.argtypes = [ci, vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    L.mx_dequantize_elem.restype = ci
+    L.mx_dequantize_elem.argtypes = [ci, vp, vp, vp, i64, i64, ci, vp, i64, vp]
     L.mx_gemm_mbs_elem.restype = ci
     L.mx_gemm_mbs_elem.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_status_string.restype = ctypes.c_char_p
@@ -276,6 +278,21 @@ def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scale
                                            _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None, _stream()),
            "mx_quantize_elem")
     return codes, scales, (mbs if use_mbs else None)
+
+
+def mx_dequantize_elem(elem, codes, scales, mbs=None, out_dtype="f32", out=None):
+    """Dequantize codes of an 8-bit MX element format (one per byte) to fp32 or bf16."""
+    torch = _torch()
+    rows, K = codes.shape
+    code, dt = _out_dtype(out_dtype)
+    if out is None:
+        out = torch.empty((rows, K), dtype=dt, device=codes.device)
+    if out.dtype != dt or out.dim() != 2 or tuple(out.shape) != (rows, K) or (K > 1 and out.stride(1) != 1):
+        raise TypeError("out must be [rows, K] of the requested dtype with a contiguous last dimension")
+    ldo = out.stride(0) if rows > 1 else max(out.stride(0), K)
+    _check(load_library().mx_dequantize_elem(_elem(elem), _ptr(codes), _ptr(scales), _ptr(mbs), rows, K, code, _ptr(out),
+                                             ldo, _stream()), "mx_dequantize_elem")
+    return out
 
 
 def mx_gemm_mbs_elem(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales, b_mbs, out_dtype="f32", out=None):

@@ -1,0 +1,130 @@
+// Dequantizer for the 8-bit MX element formats: x_hat = value(code) * 2^(E-127) / F  (Sec. 4.3.1, with the
+// element formats of the OCP MX specification).  Every element goes through fp64, which the device has plenty
+// of: value * 2^(E-127) is exact, the quotient is rounded at 53 bits and once more to fp32; the bf16 result is
+// that fp32 value rounded to nearest even.  A block whose scale byte is 255 (non-finite input) gives NaN.
+//
+// A lane expands two runs of 8 codes, 512 apart; a wavefront 1024 consecutive elements of a row, so that every
+// load and store instruction of the wavefront covers one contiguous piece of the row.
+#include "mx_common.h"
+
+namespace mx {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDq8Threads = 256;
+constexpr int kDq8Chunk = kWave * 16;
+
+// Value of an FP8 code as fp32 (exact).  E4M3: S.EEEE.MMM, bias 7; E5M2: S.EEEEE.MM, bias 15; subnormals m * 2^(1 -
+// bias - mbits).  The codes past the largest finite one are not produced by the quantizer.
+template <int kElem>
+__device__ __forceinline__ float fp8_value(uint32_t code) {
+    constexpr int kMbits = kElem == MX_ELEM_E4M3 ? 3 : 2, kBias = kElem == MX_ELEM_E4M3 ? 7 : 15;
+    const uint32_t e = (code & 0x7Fu) >> kMbits, m = code & ((1u << kMbits) - 1u);
+    const uint32_t normal = ((e + 127u - kBias) << 23) | (m << (23 - kMbits));
+    const float sub = (float)m * __uint_as_float((uint32_t)(127 + 1 - kBias - kMbits) << 23);
+    return __uint_as_float(__float_as_uint(e ? __uint_as_float(normal) : sub) | ((code & 0x80u) << 24));
+}
+
+struct Dequant8Args {
+    const uint8_t *codes, *scales, *mbs;
+    void* out;
+    int64_t K, ldo, nmac;
+    uint32_t chunks_per_row, total_chunks;
+    int vec_out;  // every output row starts 16-byte aligned
+};
+
+template <int kElem, bool kBf16>
+__global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kDq8Threads / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kDq8Threads / kWave);
+    for (uint32_t c = wave; c < q.total_chunks; c += nwaves) {
+        const uint32_t row = c / q.chunks_per_row, col0 = (c - row * q.chunks_per_row) * kDq8Chunk + lane * 8;
+        uint2 cw[2];
+        uint32_t E[2], m8[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t col = col0 + u * 512;
+            cw[u] = make_uint2(0, 0); E[u] = 127; m8[u] = 0;
+            if (col < q.K) {
+                cw[u] = *reinterpret_cast<const uint2*>(q.codes + (int64_t)row * q.K + col);
+                E[u] = q.scales[(int64_t)row * (q.K >> 5) + (col >> 5)];
+                if (q.mbs) m8[u] = q.mbs[(int64_t)row * q.nmac + (col >> 7)];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t col = col0 + u * 512;
+            if (col >= q.K) continue;
+            const double F = 1.0 + (double)m8[u] * (1.0 / 256.0);
+            const double scale = __longlong_as_double((long long)(E[u] + 896u) << 52);  // 2^(E-127)
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
+                double y = (double)fp8_value<kElem>(code) * scale;
+                if (q.mbs) y = y / F;
+                v[j] = E[u] == 255u ? __uint_as_float(0x7FC00000u) : (float)y;
+            }
+            if constexpr (kBf16) {
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+                uint16_t* o = static_cast<uint16_t*>(q.out) + (int64_t)row * q.ldo + col;
+                if (q.vec_out) {
+                    __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(o));
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { o[2 * j] = (uint16_t)w[j]; o[2 * j + 1] = (uint16_t)(w[j] >> 16); }
+                }
+            } else {
+                float* o = static_cast<float*>(q.out) + (int64_t)row * q.ldo + col;
+                if (q.vec_out) {
+                    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(o));
+                    __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<f32x4*>(o) + 1);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = v[j];
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+}  // namespace mx
+
+extern "C" int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs_or_null,
+                                  int64_t rows, int64_t K, mx_dtype_t out_dtype, void* out, int64_t ldo, void* stream) {
+    using namespace mx;
+    if ((int)elem <= MX_ELEM_E2M1 || (int)elem > MX_ELEM_E3M2) return MX_EINVAL;
+    if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldo < K) return MX_EINVAL;
+    if (out_dtype != MX_OUT_F32 && out_dtype != MX_OUT_BF16) return MX_EINVAL;
+    if (rows == 0 || K == 0) return MX_OK;
+    if (!codes || !scales || !out) return MX_ENULL;
+    if (!aligned(codes, 8) || !aligned(out, out_dtype == MX_OUT_F32 ? 4 : 2)) return MX_EALIGN;
+    if (elem != MX_ELEM_E4M3 && elem != MX_ELEM_E5M2) return MX_EUNSUPPORTED;  // the 6-bit formats
+    if (int st = check_device()) return st;
+    Dequant8Args q;
+    q.codes = codes; q.scales = scales; q.mbs = mbs_or_null;
+    q.out = out;
+    q.K = K; q.ldo = ldo; q.nmac = (K + kMacro - 1) / kMacro;
+    const int64_t cpr = (K + kDq8Chunk - 1) / kDq8Chunk;
+    if (cpr * rows >= ((int64_t)1 << 32)) return MX_EINVAL;  // chunk ids are 32-bit
+    q.chunks_per_row = (uint32_t)cpr;
+    q.total_chunks = (uint32_t)(cpr * rows);
+    const int64_t esz = out_dtype == MX_OUT_F32 ? 4 : 2;
+    q.vec_out = aligned(out, 16) && (ldo * esz) % 16 == 0;
+    int64_t blocks = ((int64_t)q.total_chunks + (kDq8Threads / kWave) - 1) / (kDq8Threads / kWave);
+    if (blocks > (int64_t)1 << 22) blocks = (int64_t)1 << 22;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)blocks), block(kDq8Threads);
+    const bool e4 = elem == MX_ELEM_E4M3, bf = out_dtype == MX_OUT_BF16;
+    if (e4 && bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, true>), grid, block, 0, s, q);
+    else if (e4) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, false>), grid, block, 0, s, q);
+    else if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, true>), grid, block, 0, s, q);
+    else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, false>), grid, block, 0, s, q);
+    return launch_status();
+}

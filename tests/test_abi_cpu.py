@@ -29,7 +29,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert {"mx_quantize", "mx_quantize_oas", "mx_quantize_mbs", "mx_quantize_mbs_dynamic", "mx_quantize_mbs_pair", "mx_gemm_mbs_quantize_a", "mx_dequantize", "mx_gemm", "mx_gemm_mbs",
-            "mx_gemm_mbs_grouped", "mx_quantize_elem", "mx_gemm_mbs_elem", "mx_status_string", "mx_version"} <= set(names)
+            "mx_gemm_mbs_grouped", "mx_quantize_elem", "mx_gemm_mbs_elem", "mx_dequantize_elem", "mx_status_string", "mx_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -146,6 +146,15 @@ def test_elem_argument_errors(lib):
     assert q(E5, A16, 4, 64, 64, 2, 0, A16 + 4, A16, None, None) == -3  # codes 8-byte aligned
     assert q(E23, A16, 4, 64, 64, 2, 0, A16, A16, None, None) == -4    # 6-bit formats: declared, not built
     assert q(E4, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0
+    d = lib.mx_dequantize_elem
+    assert d(E4, A16, A16, None, 4, 48, 0, A16, 48, None) == -1     # K % 32
+    assert d(E2M1, A16, A16, None, 4, 64, 0, A16, 64, None) == -1   # the 4-bit format has its own entry point
+    assert d(E4, A16, A16, None, 4, 64, 0, A16, 32, None) == -1     # ldo < K
+    assert d(E4, A16, A16, None, 4, 64, 5, A16, 64, None) == -1     # bad output type
+    assert d(E4, None, A16, None, 4, 64, 0, A16, 64, None) == -2
+    assert d(E5, A16 + 4, A16, None, 4, 64, 0, A16, 64, None) == -3
+    assert d(E23, A16, A16, None, 4, 64, 0, A16, 64, None) == -4
+    assert d(E4, A16, A16, None, 0, 64, 0, A16, 64, None) == 0
     g = lib.mx_gemm_mbs_elem
     assert g(E4, A16, A16, None, E4, A16, A16, None, 8, 8, 48, 0, A16, 8, None) == -1
     assert g(E2M1, A16, A16, None, E4, A16, A16, None, 8, 8, 128, 0, A16, 8, None) == -1

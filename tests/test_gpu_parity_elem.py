@@ -152,6 +152,55 @@ def test_quantize_elem_full_size_activation(mx, oracle):
 
 
 # ------------------------------------------------------------------------------------------------
+# dequantizer
+# ------------------------------------------------------------------------------------------------
+def to_bf16_bits_rne(f32: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(f32, np.float32).view(np.uint32)
+    nan = np.isnan(f32)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    r[nan] = ((u[nan] >> 16) | 0x40).astype(np.uint16)
+    return r
+
+
+@pytest.mark.parametrize("elem", ELEMS)
+def test_dequantize_elem_matches_oracle(mx, oracle, elem):
+    """Quantized heavy-tailed tensors, and every code under every scale byte and MBS word: the fp32 output equals
+    the oracle's fp64 value rounded to fp32, the bf16 output that fp32 value rounded to nearest even; NaN blocks."""
+    from paper_2603_08713_amd import synth
+
+    x = synth.activations_student_t(37, 2880, 3.0, 0.01, 30.0, 21)
+    x[3, 40] = 0x7F80  # a non-finite block
+    cases = [oracle.elem_quantize(elem, x, "oas", mbs=True), oracle.elem_quantize(elem, x, "ocp", mbs=False)]
+    rng = np.random.default_rng(5)
+    rows, K = 256, 1024
+    c = rng.integers(0, 256, (rows, K), dtype=np.uint8)
+    mag = c & 0x7F
+    c = np.where(mag > MAX_CODE[elem], (c & 0x80) | (mag & 0x3F), c).astype(np.uint8)
+    s = np.repeat(np.arange(256, dtype=np.uint8)[:, None], K // 32, 1)       # row r: scale byte r (255: NaN)
+    w = rng.integers(0, 256, (rows, K // 128), dtype=np.uint8)
+    w[:, 0] = 0
+    cases.append((c, s, w))
+    for codes, scales, words in cases:
+        with np.errstate(over="ignore"):  # the largest scale bytes overflow fp32 on both sides
+            want = oracle.elem_dequantize(elem, codes, scales, words).astype(np.float32)
+        dc, ds, dw = dev_u8(codes), dev_u8(scales), dev_u8(words)
+        got32 = host(mx.mx_dequantize_elem(elem, dc, ds, dw, "f32"))
+        got16 = host(mx.mx_dequantize_elem(elem, dc, ds, dw, "bf16").view(torch.int16)).view(np.uint16)
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got32), nan)
+        assert np.array_equal(got32.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+        assert np.array_equal(got16[~nan], to_bf16_bits_rne(want)[~nan])
+        assert np.all((got16[nan] & 0x7F80) == 0x7F80) and np.all((got16[nan] & 0x7F) != 0)
+    # strided output and an odd column offset (element stores)
+    codes, scales, words = cases[0]
+    big = torch.zeros((37, 2880 + 9), dtype=torch.float32, device="cuda")
+    mx.mx_dequantize_elem(elem, dev_u8(codes), dev_u8(scales), dev_u8(words), "f32", out=big[:, 1:2881])
+    ref = mx.mx_dequantize_elem(elem, dev_u8(codes), dev_u8(scales), dev_u8(words), "f32")
+    ok = ~torch.isnan(ref)
+    assert torch.equal(big[:, 1:2881][ok], ref[ok]) and float(big[:, 0].abs().max()) == 0.0 and float(big[:, 2881:].abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------------------------------------
 # GEMM
 # ------------------------------------------------------------------------------------------------
 def random_operand(rng, elem, rows, K, lo=110, hi=140):
