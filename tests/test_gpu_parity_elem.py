@@ -344,6 +344,45 @@ def test_gemm_elem_quantized_tensors_and_repeat(mx, oracle):
         assert_gemm_close(host(c), oracle.elem_gemm(ea, oa, eb, ob), "%s x %s %s" % (ea, eb, rule))
 
 
+def test_gemm_elem_first_launch_of_a_process_matches_later_ones(mx):
+    """A kernel's very first launch in a process runs with cold instruction caches and address translation, so its
+    wavefronts drift apart far more than later: a load that the pipeline's waits do not cover would show as a
+    wrong patch of C in that launch only.  A fresh process multiplies a large problem in each form of the kernel
+    (fast and general, with and without MBS words), each launched for the first time there, and compares with the
+    second launch."""
+    import os
+    import subprocess
+    import sys
+
+    code = """
+import torch, paper_2603_08713_amd as mx
+torch.manual_seed(0)
+a = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+w = (torch.randn(14336, 8192, device="cuda") * 0.02).to(torch.bfloat16)
+qa, qw = mx.mx_quantize_elem(a, "e4m3", "oas"), mx.mx_quantize_elem(w, "e4m3", "oas")
+first = mx.mx_gemm_mbs_elem("e4m3", *qa, "e4m3", *qw, "bf16")
+again = mx.mx_gemm_mbs_elem("e4m3", *qa, "e4m3", *qw, "bf16")
+p1 = mx.mx_gemm_mbs_elem("e4m3", qa[0], qa[1], None, "e4m3", qw[0], qw[1], None, "bf16")
+p2 = mx.mx_gemm_mbs_elem("e4m3", qa[0], qa[1], None, "e4m3", qw[0], qw[1], None, "bf16")
+torch.cuda.synchronize()
+assert torch.equal(first, again), int((first != again).sum())
+assert torch.equal(p1, p2), int((p1 != p2).sum())
+# general form: K = 7808 = 61 macro blocks
+k = 7808
+qa, qw = mx.mx_quantize_elem(a[:, :k].contiguous(), "e5m2", "oas"), mx.mx_quantize_elem(w[:, :k].contiguous(), "e4m3", "oas")
+for words in (True, False):
+    fn = lambda: mx.mx_gemm_mbs_elem("e5m2", qa[0], qa[1], qa[2] if words else None, "e4m3", qw[0], qw[1], qw[2] if words else None, "bf16")
+    c1 = fn(); c2 = fn()
+    torch.cuda.synchronize()
+    assert torch.equal(c1, c2), (words, int((c1 != c2).sum()))
+print("first launch ok")
+"""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, PYTHONPATH=root + os.pathsep + os.environ.get("PYTHONPATH", ""))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=280)
+    assert out.returncode == 0 and "first launch ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+
+
 def test_gemm_elem_full_size_sampled_rows(mx, oracle):
     """Llama-3-8B FFN up-projection shape in MXFP8 (E4M3), as bench.py launches it: sampled output rows against
     the fp64 oracle, and QSNR(AB) against the bf16 product above MXFP4's (more element bits, same method)."""
