@@ -1,7 +1,8 @@
 /*
  * mx4.h -- C ABI of the MI355X (gfx950) library for MXFP4 quantization with Overflow-Aware
  * Scaling (OAS) and static Macro Block Scaling (MBS-S), and the block-scaled GEMM that consumes
- * those operands and applies the MBS correction in its fp32 accumulation.
+ * those operands and applies the MBS correction in its fp32 accumulation.  The same for the 8-bit
+ * MX element formats (MXFP8) through the *_elem entry points at the end.
  *
  * Conventions common to every entry point
  *   - Every pointer argument is a DEVICE pointer owned by the caller (the library never allocates,

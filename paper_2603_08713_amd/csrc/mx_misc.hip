@@ -1,4 +1,4 @@
-// Device check, status strings and version of the gfx950 MXFP4 library.
+// Device check, status strings and version of the gfx950 MX quantization library.
 #include <string.h>
 
 #include <atomic>
@@ -31,10 +31,10 @@ extern "C" const char* mx_status_string(int status) {
         case MX_EINVAL: return "invalid argument (negative size, K not a multiple of 32, leading dimension too small, or bad enum)";
         case MX_ENULL: return "required pointer is NULL";
         case MX_EALIGN: return "pointer or leading dimension is misaligned";
-        case MX_EUNSUPPORTED: return "no HIP device, or the current device is not gfx950";
+        case MX_EUNSUPPORTED: return "no HIP device, the current device is not gfx950, or a shape or element format this entry point does not cover";
         case MX_ELAUNCH: return "the HIP runtime rejected the kernel launch";
         default: return "unknown status";
     }
 }
 
-extern "C" int mx_version(void) { return 100; }
+extern "C" int mx_version(void) { return 200; }
