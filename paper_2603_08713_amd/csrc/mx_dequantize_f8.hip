@@ -1,7 +1,10 @@
 // Dequantizer for the 8-bit MX element formats: x_hat = value(code) * 2^(E-127) / F  (Sec. 4.3.1, with the
-// element formats of the OCP MX specification).  Every element goes through fp64, which the device has plenty
-// of: value * 2^(E-127) is exact, the quotient is rounded at 53 bits and once more to fp32; the bf16 result is
-// that fp32 value rounded to nearest even.  A block whose scale byte is 255 (non-finite input) gives NaN.
+// element formats of the OCP MX specification).  The fp32 result is defined through fp64: value * 2^(E-127) is
+// exact, the quotient is rounded at 53 bits and once more to fp32; the bf16 result is that fp32 value rounded to
+// nearest even.  A block whose scale byte is 255 (non-finite input) gives NaN.  Where every intermediate is a
+// normal fp32 number (scale byte in [24, 230]) one IEEE fp32 division gives the same bits - checked for every
+// pair of code value and MBS word on the host (tests/test_abi_cpu.py), and a power-of-two scale commutes with
+// rounding; other scale bytes take the fp64 route element by element.
 //
 // A lane expands two runs of 8 codes, 512 apart; a wavefront 1024 consecutive elements of a row, so that every
 // load and store instruction of the wavefront covers one contiguous piece of the row.
@@ -58,15 +61,25 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
         for (int u = 0; u < 2; ++u) {
             const uint32_t col = col0 + u * 512;
             if (col >= q.K) continue;
-            const double F = 1.0 + (double)m8[u] * (1.0 / 256.0);
-            const double scale = __longlong_as_double((long long)(E[u] + 896u) << 52);  // 2^(E-127)
             float v[8];
+            if (E[u] >= 24u && E[u] <= 230u) {
+                const float F = __uint_as_float(0x3F800000u | (m8[u] << 15));  // 1 + m8/256
+                const float scale = __uint_as_float(E[u] << 23);               // 2^(E-127)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
-                double y = (double)fp8_value<kElem>(code) * scale;
-                if (q.mbs) y = y / F;
-                v[j] = E[u] == 255u ? __uint_as_float(0x7FC00000u) : (float)y;
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
+                    v[j] = (fp8_value<kElem>(code) * scale) / F;  // exact product, IEEE division (m8 = 0: exact)
+                }
+            } else {
+                const double F = 1.0 + (double)m8[u] * (1.0 / 256.0);
+                const double scale = __longlong_as_double((long long)(E[u] + 896u) << 52);  // 2^(E-127)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
+                    double y = (double)fp8_value<kElem>(code) * scale;
+                    if (q.mbs) y = y / F;
+                    v[j] = E[u] == 255u ? __uint_as_float(0x7FC00000u) : (float)y;
+                }
             }
             if constexpr (kBf16) {
                 uint32_t w[4];

@@ -167,6 +167,28 @@ def test_elem_argument_errors(lib):
     assert g(E4, A16, A16, None, E5, A16, A16, None, 0, 8, 128, 0, A16, 8, None) == 0
 
 
+def test_fp8_dequantizer_shortcut_is_exact():
+    """The MXFP8 dequantizer divides in fp32 where every intermediate is a normal number, although its result is
+    defined through fp64 (quotient rounded at 53 bits, then to fp32).  The two agree for every pair of FP8 code
+    value and MBS word; a power-of-two block scale commutes with the rounding, so this covers every scale byte of
+    the shortcut's range."""
+    import numpy as np
+
+    def values(ebits, mbits, bias, top):
+        out = set()
+        for c in range(1, top + 1):
+            e, m = c >> mbits, c & ((1 << mbits) - 1)
+            out.add(m * 2.0 ** (1 - bias - mbits) if e == 0 else (1 + m / (1 << mbits)) * 2.0 ** (e - bias))
+        return sorted(out)
+
+    for vals in (values(4, 3, 7, 0x7E), values(5, 2, 15, 0x7B)):
+        v = np.array(vals, np.float64)[:, None]
+        F = 1.0 + np.arange(256, dtype=np.float64)[None, :] / 256.0
+        via64 = (v / F).astype(np.float32)
+        direct = v.astype(np.float32) / F.astype(np.float32)  # IEEE fp32 division
+        assert direct.dtype == np.float32 and np.array_equal(via64, direct)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2603_08713_amd import binding
 
