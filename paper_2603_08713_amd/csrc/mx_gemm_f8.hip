@@ -333,16 +333,20 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 if constexpr (kFast && q + 1 == kPairs - 1) read_scales_fast(s + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 const float sm = sig_m[i];
-                static_for<16>([&](auto e_) {
-                    constexpr int e = decltype(e_)::value;
-                    // sigma_A * sigma_B with the DPP fetch folded into the multiply (written out: the compiler
-                    // keeps the fetch as a move of its own)
-                    float ww;
-                    if constexpr (e % 4 == 0) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
-                    if constexpr (e % 4 == 1) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
-                    if constexpr (e % 4 == 2) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
-                    if constexpr (e % 4 == 3) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(ww) : "v"(sig_n[j][e / 4]), "v"(sm));
-                    acc[i][j][e] = fmaf(prod[q % 2][e], ww, acc[i][j][e]);
+                // sigma_A * sigma_B with the DPP fetch folded into the multiply (written out: the compiler keeps the
+                // fetch as a move of its own); four products at a time, so that no multiply-add follows the
+                // multiply it depends on directly (the compiler would put a wait state between the two)
+                static_for<4>([&](auto gq_) {
+                    constexpr int gq = decltype(gq_)::value;
+                    float w0, w1, w2, w3;
+                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w0) : "v"(sig_n[j][gq]), "v"(sm));
+                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w1) : "v"(sig_n[j][gq]), "v"(sm));
+                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w2) : "v"(sig_n[j][gq]), "v"(sm));
+                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w3) : "v"(sig_n[j][gq]), "v"(sm));
+                    acc[i][j][4 * gq + 0] = fmaf(prod[q % 2][4 * gq + 0], w0, acc[i][j][4 * gq + 0]);
+                    acc[i][j][4 * gq + 1] = fmaf(prod[q % 2][4 * gq + 1], w1, acc[i][j][4 * gq + 1]);
+                    acc[i][j][4 * gq + 2] = fmaf(prod[q % 2][4 * gq + 2], w2, acc[i][j][4 * gq + 2]);
+                    acc[i][j][4 * gq + 3] = fmaf(prod[q % 2][4 * gq + 3], w3, acc[i][j][4 * gq + 3]);
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
