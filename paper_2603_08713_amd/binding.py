@@ -260,17 +260,22 @@ def mx_gemm_mbs(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, out_dtype="f
     return out
 
 
+def elem_code_bytes(elem, K: int) -> int:
+    """Bytes of a row of K codes: one per element for the 8-bit formats, 6-bit codes packed for E2M3 / E3M2."""
+    return K * 3 // 4 if _elem(elem) in (MX_ELEM_E2M3, MX_ELEM_E3M2) else K
+
+
 def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scales=None, mbs=None):
-    """Quantize into an 8-bit MX element format (codes one per byte), with or without MBS words."""
+    """Quantize into an 8-bit (codes one per byte) or 6-bit (packed) MX element format, with or without MBS words."""
     torch = _torch()
     rows, K, ldx = _rows_ld(x)
     if codes is None:
-        codes = torch.empty((rows, K), dtype=torch.uint8, device=x.device)
+        codes = torch.empty((rows, elem_code_bytes(elem, K)), dtype=torch.uint8, device=x.device)
     if scales is None:
         scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
     if use_mbs and mbs is None:
         mbs = torch.empty((rows, (K + 127) // 128), dtype=torch.uint8, device=x.device)
-    _u8(codes, (rows, K), "codes")
+    _u8(codes, (rows, elem_code_bytes(elem, K)), "codes")
     _u8(scales, (rows, K // 32), "scales")
     if use_mbs:
         _u8(mbs, (rows, (K + 127) // 128), "mbs")

@@ -1,8 +1,8 @@
-// Quantizer for the 8-bit MX element formats (E4M3, E5M2) with Overflow-Aware Scaling and static Macro Block
-// Scaling for gfx950 (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8).
+// Quantizer for the 8-bit and 6-bit MX element formats (E4M3, E5M2; E2M3, E3M2) with Overflow-Aware Scaling and
+// static Macro Block Scaling for gfx950 (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8).
 //
 // The rules of Sec. 4.2 and 4.3.1 are restated with the element format's constants in place of E2M1's 6 and 1:
-// V = vm * 2^emax, the largest finite magnitude (both formats: vm = 1.75), and h = 2^(emax - mbits - 1), half the
+// V = vm * 2^emax, the largest finite magnitude (vm = 1.75, for E2M3 1.875), and h = 2^(emax - mbits - 1), half the
 // spacing of the top binade.  In terms of the mantissa t of the (MBS-scaled) block absmax, written t * 2^p:
 //   OCP    stored exponent p - emax                        FLOOR  one more when t > vm
 //   OAS    one more when t > vm + h / 2^emax               MBS-S  m8 = 8 leading mantissa bits of V / absmax128
@@ -11,6 +11,8 @@
 // in fp32 and so is its product with the power-of-two block scale; the block exponent is read off the fp32
 // pattern of absmax * F with a carry; blocks that could leave fp32's normal range, or hold Inf/NaN, take a
 // wave-uniform detour through all-integer arithmetic.
+// Output: 8-bit codes one per byte; 6-bit codes packed, element k of a row in bits 6 k .. 6 k + 5 of the row's
+// bytes (a block is 24 bytes, which the first lane of its four gathers and stores).
 #include "mx_quantize_math.h"
 
 namespace mx {
@@ -22,19 +24,39 @@ constexpr int kThreads8 = 256;
 
 template <int kElem>
 struct Fp8;
+// kFloorNum / 2^kFloorShift = vm, kOasNum / 2^kOasShift = vm + h / 2^emax; kCarry* = 2^23 - 1 - their mantissa bits;
+// MBS word: floor(kMbsNum / (128 + k)) - 256 for k <= kMbsSplit, twice the numerator above (256 vm 128 = kMbsNum).
 template <>
 struct Fp8<MX_ELEM_E4M3> {
-    static constexpr int kEmax = 8, kMbits = 3, kBias = 7, kMaxCode = 0x7E;
-    static constexpr uint32_t kMaxBits = 0x43E00000u;                       // 448.0f
-    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x17FFFFu;  // 2^23 - 1 - mantissa bits of 1.75, 1.8125
-    static constexpr uint32_t kOasNum = 29, kOasShift = 4;                  // 1.8125 = 29 / 16
+    static constexpr int kBits = 8, kEmax = 8, kMbits = 3, kBias = 7, kMaxCode = 0x7E;
+    static constexpr uint32_t kMaxBits = 0x43E00000u;  // 448.0f
+    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x17FFFFu;
+    static constexpr uint32_t kFloorNum = 7, kFloorShift = 2, kOasNum = 29, kOasShift = 4;  // 1.75, 1.8125
+    static constexpr uint32_t kMbsNum = 57344, kMbsSplit = 96;
 };
 template <>
 struct Fp8<MX_ELEM_E5M2> {
-    static constexpr int kEmax = 15, kMbits = 2, kBias = 15, kMaxCode = 0x7B;
-    static constexpr uint32_t kMaxBits = 0x47600000u;                       // 57344.0f
-    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x0FFFFFu;  // 1.75, 1.875
-    static constexpr uint32_t kOasNum = 15, kOasShift = 3;                  // 1.875 = 15 / 8
+    static constexpr int kBits = 8, kEmax = 15, kMbits = 2, kBias = 15, kMaxCode = 0x7B;
+    static constexpr uint32_t kMaxBits = 0x47600000u;  // 57344.0f
+    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x0FFFFFu;
+    static constexpr uint32_t kFloorNum = 7, kFloorShift = 2, kOasNum = 15, kOasShift = 3;  // 1.75, 1.875
+    static constexpr uint32_t kMbsNum = 57344, kMbsSplit = 96;
+};
+template <>
+struct Fp8<MX_ELEM_E2M3> {
+    static constexpr int kBits = 6, kEmax = 2, kMbits = 3, kBias = 1, kMaxCode = 0x1F;
+    static constexpr uint32_t kMaxBits = 0x40F00000u;  // 7.5f
+    static constexpr uint32_t kCarryFloor = 0x0FFFFFu, kCarryOas = 0x07FFFFu;
+    static constexpr uint32_t kFloorNum = 15, kFloorShift = 3, kOasNum = 31, kOasShift = 4;  // 1.875, 1.9375
+    static constexpr uint32_t kMbsNum = 61440, kMbsSplit = 112;
+};
+template <>
+struct Fp8<MX_ELEM_E3M2> {
+    static constexpr int kBits = 6, kEmax = 4, kMbits = 2, kBias = 3, kMaxCode = 0x1F;
+    static constexpr uint32_t kMaxBits = 0x41E00000u;  // 28.0f
+    static constexpr uint32_t kCarryFloor = 0x1FFFFFu, kCarryOas = 0x0FFFFFu;
+    static constexpr uint32_t kFloorNum = 7, kFloorShift = 2, kOasNum = 15, kOasShift = 3;  // 1.75, 1.875
+    static constexpr uint32_t kMbsNum = 57344, kMbsSplit = 96;
 };
 
 struct Quant8Args {
@@ -49,20 +71,22 @@ struct Quant8Args {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// 8 leading mantissa bits of V / alpha for alpha = (128 + k) * 2^e, V = 1.75 * 2^emax: 224 / (128 + k) lies in
-// (0.875, 1.75]; normalised to [1, 2) it is 224 / (128 + k) for k <= 96 and 448 / (128 + k) above.  The quotient
-// is taken with the hardware reciprocal plus 2^-10 (an integer, or at least 1/255 away from one).
+// 8 leading mantissa bits of V / alpha for alpha = (128 + k) * 2^e, V = vm * 2^emax: 128 vm / (128 + k) lies in
+// (vm / 2, vm]; normalised to [1, 2) it is 128 vm / (128 + k) for 128 + k <= 128 vm and twice that above.  The
+// quotient is taken with the hardware reciprocal plus 2^-10 (an integer, or at least 1/255 away from one).
+template <typename T>
 __device__ __forceinline__ uint32_t mbs8_word_of_mantissa(uint32_t k) {
-    const float num = k <= 96u ? 57344.0f : 114688.0f;
+    const float num = k <= T::kMbsSplit ? (float)T::kMbsNum : (float)(2 * T::kMbsNum);
     const float quo = fmaf(num, __builtin_amdgcn_rcpf((float)(128u + k)), 0x1.0p-10f);
     return (uint32_t)quo - 256u;
 }
+template <typename T>
 __device__ __forceinline__ uint32_t mbs8_word_of_absmax(uint32_t mmax) {
     if (mmax == 0) return 0;
     uint32_t k = mmax & 0x7Fu;
     if ((mmax >> 7) == 0) k = (k << (__clz(k) - 24)) & 0x7Fu;
     const uint32_t n = 128u + k;
-    return (k <= 96u ? 57344u / n : 114688u / n) - 256u;
+    return (k <= T::kMbsSplit ? T::kMbsNum / n : 2 * T::kMbsNum / n) - 256u;
 }
 
 // ---- all-integer arithmetic, exact for every finite bf16 input ----
@@ -75,7 +99,7 @@ __device__ __forceinline__ int exact_scale_byte8(uint32_t amax, uint32_t u, int 
     const int msb = 31 - __clz(P);
     const int p = ex - 8 + msb;                // floor(log2(absmax * F))
     bool low = true;                           // mantissa at or below the rule's threshold
-    if (rule == MX_RULE_FLOOR) low = 4u * P <= (7u << msb);
+    if (rule == MX_RULE_FLOOR) low = (P << T::kFloorShift) <= (T::kFloorNum << msb);
     else if (rule == MX_RULE_OAS) low = (P << T::kOasShift) <= (T::kOasNum << msb);
     const int s = low ? T::kEmax - p : T::kEmax - 1 - p;
     return min(max(127 - s, 0), 254);
@@ -83,7 +107,7 @@ __device__ __forceinline__ int exact_scale_byte8(uint32_t amax, uint32_t u, int 
 // Code of the bf16 pattern h scaled by F = u / 256 and by 2^s: nearest, ties to even, saturating, sign copied.
 template <typename T>
 __device__ __forceinline__ uint32_t exact_code8(uint32_t h, uint32_t u, int s) {
-    const uint32_t sign = (h >> 8) & 0x80u;
+    const uint32_t sign = (h >> 15) << (T::kBits - 1);
     const uint32_t a = h & 0x7FFFu, e = a >> 7;
     const uint32_t n = e ? (128u | (a & 0x7Fu)) : (a & 0x7Fu);
     const uint32_t Tv = n * u;  // |x| F 2^s = Tv * 2^e2
@@ -106,9 +130,17 @@ __device__ __forceinline__ uint32_t exact_code8(uint32_t h, uint32_t u, int s) {
 }
 
 struct Chunk8 {
-    uint32_t lo, hi;  // 8 codes of this lane
+    uint32_t lo, hi;  // 8 codes of this lane: 8 bytes, or 48 bits (32 in lo, 16 in hi) for the 6-bit formats
     uint32_t E, m8;
 };
+
+// code i of the lane's 8 goes to bits kBits * i of the 64-bit pair (lo, hi)
+template <typename T>
+__device__ __forceinline__ void put_code(uint32_t& lo, uint32_t& hi, int i, uint32_t code) {
+    const int bit = T::kBits * i;
+    if (bit < 32) lo |= code << bit;
+    if (bit + T::kBits > 32) hi |= bit >= 32 ? code << (bit - 32) : code >> (32 - bit);
+}
 
 template <typename T>
 __device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_mbs) {
@@ -127,16 +159,13 @@ __device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_
     uint32_t mmax = amax;
     mmax = max(mmax, dpp_row_ror4(mmax));
     mmax = max(mmax, dpp_row_ror8(mmax));
-    const uint32_t m8 = use_mbs ? mbs8_word_of_absmax(mmax) : 0u;
+    const uint32_t m8 = use_mbs ? mbs8_word_of_absmax<T>(mmax) : 0u;
     const uint32_t u = 256u + m8;
     const int E = nf ? 255 : amax == 0 ? 127 : exact_scale_byte8<T>(amax, u, rule);
     uint32_t lo = 0, hi = 0;
     if (!nf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lo |= exact_code8<T>(h[i], u, 127 - E) << (8 * i);
-            hi |= exact_code8<T>(h[4 + i], u, 127 - E) << (8 * i);
-        }
+        for (int i = 0; i < 8; ++i) put_code<T>(lo, hi, i, exact_code8<T>(h[i], u, 127 - E));
     }
     return {lo, hi, (uint32_t)E, m8};
 }
@@ -151,7 +180,7 @@ __device__ __forceinline__ uint32_t code8_alu(float t) {
     const uint32_t ey = max(__float_as_uint(y) >> 23, (uint32_t)(127 + 1 - T::kBias));
     const float w = y + __uint_as_float(((ey + 23u - T::kMbits) << 23) | 0x400000u);
     const uint32_t q = __float_as_uint(w) & ((1u << (T::kMbits + 2)) - 1u);
-    return (((ey - 127u + T::kBias) << T::kMbits) + q - (1u << T::kMbits)) | ((tb >> 24) & 0x80u);
+    return (((ey - 127u + T::kBias) << T::kMbits) + q - (1u << T::kMbits)) | ((tb >> 31) << (T::kBits - 1));
 }
 
 template <int kElem, bool kHwCvt, bool kMbs>
@@ -170,7 +199,7 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
     if constexpr (kMbs) {
         uint32_t mmax = max(amax, dpp_row_ror4(amax));
         mmax = max(mmax, dpp_row_ror8(mmax));
-        m8 = mmax ? mbs8_word_of_mantissa(mmax & 0x7Fu) : 0u;
+        m8 = mmax ? mbs8_word_of_mantissa<T>(mmax & 0x7Fu) : 0u;
     }
     const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));  // exact
     uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - (uint32_t)T::kEmax;
@@ -183,7 +212,7 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
     for (int i = 0; i < 4; ++i) {
         const float t0 = __uint_as_float(w[i] << 16) * mult;          // exact
         const float t1 = __uint_as_float(w[i] & 0xFFFF0000u) * mult;
-        if constexpr (kHwCvt) {
+        if constexpr (kHwCvt && T::kBits == 8) {
             // hardware fp32 -> FP8 pair convert (nearest even); the clamp makes saturation explicit
             const float c0 = __builtin_amdgcn_fmed3f(t0, -vmax, vmax), c1 = __builtin_amdgcn_fmed3f(t1, -vmax, vmax);
             if constexpr (kElem == MX_ELEM_E4M3) {
@@ -194,7 +223,8 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
                 else out[i / 2] = __builtin_amdgcn_cvt_pk_bf8_f32(c0, c1, out[i / 2], true);
             }
         } else {
-            out[i / 2] |= (code8_alu<T>(t0) | (code8_alu<T>(t1) << 8)) << (16 * (i % 2));
+            put_code<T>(out[0], out[1], 2 * i, code8_alu<T>(t0));
+            put_code<T>(out[0], out[1], 2 * i + 1, code8_alu<T>(t1));
         }
     }
     return {out[0], out[1], E, m8};
@@ -228,10 +258,39 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
             if ((lane & 3) != 0) ew = 0;
             ew |= dpp_row_ror4(ew);
             ew |= dpp_row_ror8(ew);
+            // 6-bit formats: the block's 4 x 48 bits gathered into six dwords (every lane fetches its three
+            // neighbours' bits; the block's first lane stores)
+            uint32_t six[6] = {0, 0, 0, 0, 0, 0};
+            if constexpr (Fp8<kElem>::kBits == 6) {
+                uint32_t lo[4], hi[4];
+                lo[0] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x00, 0xF, 0xF, true);  // quad_perm: [0,0,0,0]
+                hi[0] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x00, 0xF, 0xF, true);
+                lo[1] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x55, 0xF, 0xF, true);  // [1,1,1,1]
+                hi[1] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x55, 0xF, 0xF, true);
+                lo[2] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xAA, 0xF, 0xF, true);  // [2,2,2,2]
+                hi[2] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xAA, 0xF, 0xF, true);
+                lo[3] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xFF, 0xF, 0xF, true);  // [3,3,3,3]
+                hi[3] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xFF, 0xF, 0xF, true);
+                six[0] = lo[0];
+                six[1] = hi[0] | (lo[1] << 16);
+                six[2] = (lo[1] >> 16) | (hi[1] << 16);
+                six[3] = lo[2];
+                six[4] = hi[2] | (lo[3] << 16);
+                six[5] = (lo[3] >> 16) | (hi[3] << 16);
+            }
             if (!valid[u]) continue;
             const uint32_t kblk = col[u] >> 5;
             uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
-            *reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * q.K + col[u]) = make_uint2(res.lo, res.hi);
+            if constexpr (Fp8<kElem>::kBits == 6) {
+                if ((lane & 3) == 0) {
+                    uint2* dst = reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * (q.K / 4 * 3) + (int64_t)kblk * 24);
+                    dst[0] = make_uint2(six[0], six[1]);
+                    dst[1] = make_uint2(six[2], six[3]);
+                    dst[2] = make_uint2(six[4], six[5]);
+                }
+            } else {
+                *reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * q.K + col[u]) = make_uint2(res.lo, res.hi);
+            }
             if (q.scales_dword) {
                 if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
             } else if ((lane & 3) == 0) {
@@ -264,7 +323,6 @@ int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64
     if (rows == 0 || K == 0) return MX_OK;
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
     if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 8)) return MX_EALIGN;
-    if (elem != MX_ELEM_E4M3 && elem != MX_ELEM_E5M2) return MX_EUNSUPPORTED;  // the 6-bit formats
     const int64_t chunks_per_row = (K + kChunk8 - 1) / kChunk8, total = rows * chunks_per_row;
     if (total >= ((int64_t)1 << 32) - kUnroll8 || rows >= ((int64_t)1 << 31)) return MX_EINVAL;  // 32-bit chunk ids
     if (int st = check_device()) return st;
@@ -276,15 +334,20 @@ int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64
     q.total_chunks = (uint32_t)total;
     q.rule = rule;
     q.scales_dword = (K % kMacro) == 0 && aligned(scales, 4);
-    const bool e4 = elem == MX_ELEM_E4M3;
-    q.carry = rule == MX_RULE_FLOOR ? (e4 ? Fp8<MX_ELEM_E4M3>::kCarryFloor : Fp8<MX_ELEM_E5M2>::kCarryFloor)
-              : rule == MX_RULE_OAS ? (e4 ? Fp8<MX_ELEM_E4M3>::kCarryOas : Fp8<MX_ELEM_E5M2>::kCarryOas) : 0u;
+    const uint32_t carry_floor[5] = {0, Fp8<MX_ELEM_E4M3>::kCarryFloor, Fp8<MX_ELEM_E5M2>::kCarryFloor,
+                                     Fp8<MX_ELEM_E2M3>::kCarryFloor, Fp8<MX_ELEM_E3M2>::kCarryFloor};
+    const uint32_t carry_oas[5] = {0, Fp8<MX_ELEM_E4M3>::kCarryOas, Fp8<MX_ELEM_E5M2>::kCarryOas,
+                                   Fp8<MX_ELEM_E2M3>::kCarryOas, Fp8<MX_ELEM_E3M2>::kCarryOas};
+    q.carry = rule == MX_RULE_FLOOR ? carry_floor[elem] : rule == MX_RULE_OAS ? carry_oas[elem] : 0u;
     const int64_t waves = (total + kUnroll8 - 1) / kUnroll8;
     int64_t blocks = (waves + (kThreads8 / kWave) - 1) / (kThreads8 / kWave);
     if (blocks > (1 << 22)) blocks = 1 << 22;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (e4) launch8<MX_ELEM_E4M3>(q, use_mbs, dim3((unsigned)blocks), s);
-    else launch8<MX_ELEM_E5M2>(q, use_mbs, dim3((unsigned)blocks), s);
+    const dim3 grid((unsigned)blocks);
+    if (elem == MX_ELEM_E4M3) launch8<MX_ELEM_E4M3>(q, use_mbs, grid, s);
+    else if (elem == MX_ELEM_E5M2) launch8<MX_ELEM_E5M2>(q, use_mbs, grid, s);
+    else if (elem == MX_ELEM_E2M3) launch8<MX_ELEM_E2M3>(q, use_mbs, grid, s);
+    else launch8<MX_ELEM_E3M2>(q, use_mbs, grid, s);
     return launch_status();
 }
 

@@ -144,7 +144,7 @@ def test_elem_argument_errors(lib):
     assert q(E4, A16, 4, 64, 64, 2, 1, A16, A16, None, None) == -2     # MBS words wanted, no array
     assert q(E4, None, 4, 64, 64, 2, 0, A16, A16, None, None) == -2
     assert q(E5, A16, 4, 64, 64, 2, 0, A16 + 4, A16, None, None) == -3  # codes 8-byte aligned
-    assert q(E23, A16, 4, 64, 64, 2, 0, A16, A16, None, None) == -4    # 6-bit formats: declared, not built
+    assert q(E23, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0     # the 6-bit formats quantize too
     assert q(E4, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0
     d = lib.mx_dequantize_elem
     assert d(E4, A16, A16, None, 4, 48, 0, A16, 48, None) == -1     # K % 32

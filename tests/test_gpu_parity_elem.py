@@ -12,8 +12,19 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 RULES = ("ocp", "floor", "oas")
-ELEMS = ("e4m3", "e5m2")
+ELEMS = ("e4m3", "e5m2")          # GEMM and dequantizer
+QUANT_ELEMS = ELEMS + ("e2m3", "e3m2")  # quantizer
 MAX_CODE = {"e4m3": 0x7E, "e5m2": 0x7B}
+
+
+def canonical_codes(elem, codes: np.ndarray) -> np.ndarray:
+    """The oracle keeps one code per byte; the library packs 6-bit codes, element k of a row in bits 6k .. 6k+5."""
+    if elem in ELEMS:
+        return codes
+    c = codes.reshape(codes.shape[0], -1, 4).astype(np.uint32)
+    w = c[..., 0] | (c[..., 1] << 6) | (c[..., 2] << 12) | (c[..., 3] << 18)
+    out = np.stack([w & 0xFF, (w >> 8) & 0xFF, (w >> 16) & 0xFF], axis=-1).astype(np.uint8)
+    return out.reshape(codes.shape[0], -1)
 GEMM_TOL = 1e-3
 
 
@@ -48,6 +59,7 @@ def assert_quant_equal(mx, oracle, elem, bits, rule, mbs, what="", x=None):
     c, s, w = mx.mx_quantize_elem(x, elem, rule, use_mbs=mbs)
     torch.cuda.synchronize()
     oc, os_, ow = oracle.elem_quantize(elem, bits, rule, mbs=mbs)
+    oc = canonical_codes(elem, oc)
     tag = "%s %s rule=%s mbs=%s" % (what, elem, rule, mbs)
     if mbs:
         bad = np.argwhere(host(w) != ow)
@@ -64,7 +76,7 @@ def assert_quant_equal(mx, oracle, elem, bits, rule, mbs, what="", x=None):
 # quantizer
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("hw", [1, 0])
-@pytest.mark.parametrize("elem", ELEMS)
+@pytest.mark.parametrize("elem", QUANT_ELEMS)
 def test_quantize_elem_tiny_config(mx, oracle, elem, hw):
     from paper_2603_08713_amd import synth
 
@@ -80,7 +92,7 @@ def test_quantize_elem_tiny_config(mx, oracle, elem, hw):
 
 
 @pytest.mark.parametrize("hw", [1, 0])
-@pytest.mark.parametrize("elem", ELEMS)
+@pytest.mark.parametrize("elem", QUANT_ELEMS)
 def test_quantize_elem_every_bf16_pattern(mx, oracle, elem, hw):
     """All 65536 bf16 patterns (subnormals, Inf, NaN, both zeros): in natural order (blocks of similar
     magnitude) and shuffled so that blocks mix magnitudes and elements land in every binade of the element
@@ -127,7 +139,7 @@ def test_quantize_elem_ragged_shapes(mx, oracle, rows, K, ld):
     rng = np.random.default_rng(rows * 1000 + K)
     full = synth.to_bf16_bits(rng.standard_t(3, (rows, ld)))
     x = dev_bf16(full)[:, :K]
-    for elem in ELEMS:
+    for elem in QUANT_ELEMS:
         for rule, mbs in (("oas", True), ("ocp", False), ("floor", True)):
             assert_quant_equal(mx, oracle, elem, full[:, :K], rule, mbs, "ragged", x=x)
 
@@ -136,6 +148,7 @@ def test_quantize_elem_empty(mx):
     x = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
     c, s, w = mx.mx_quantize_elem(x, "e4m3")
     assert c.shape == (0, 128) and s.shape == (0, 4) and w.shape == (0, 1)
+    assert mx.mx_quantize_elem(x, "e2m3")[0].shape == (0, 96)
 
 
 def test_quantize_elem_full_size_activation(mx, oracle):
@@ -144,11 +157,12 @@ def test_quantize_elem_full_size_activation(mx, oracle):
 
     a = synth.activations_student_t(4096, 4096, 4.0, 0.01, 20.0, 1)
     x = dev_bf16(a)
-    for elem, rule in (("e4m3", "oas"), ("e5m2", "oas"), ("e4m3", "ocp")):
+    for elem, rule in (("e4m3", "oas"), ("e5m2", "oas"), ("e4m3", "ocp"), ("e2m3", "oas"), ("e3m2", "oas")):
         c, s, w = mx.mx_quantize_elem(x, elem, rule, use_mbs=True)
         torch.cuda.synchronize()
         oc, os_, ow = oracle.elem_quantize(elem, a[::8], rule, mbs=True)
-        assert np.array_equal(host(w)[::8], ow) and np.array_equal(host(s)[::8], os_) and np.array_equal(host(c)[::8], oc)
+        assert np.array_equal(host(w)[::8], ow) and np.array_equal(host(s)[::8], os_)
+        assert np.array_equal(host(c)[::8], canonical_codes(elem, oc))
 
 
 # ------------------------------------------------------------------------------------------------
