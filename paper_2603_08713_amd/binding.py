@@ -301,11 +301,11 @@ def mx_dequantize_elem(elem, codes, scales, mbs=None, out_dtype="f32", out=None)
 
 
 def mx_gemm_mbs_elem(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales, b_mbs, out_dtype="f32", out=None):
-    """GEMM with the MBS correction for operands in 8-bit MX element formats; a_mbs / b_mbs may be None."""
-    M, K = a_codes.shape
-    N = b_codes.shape[0]
-    if b_codes.shape[1] != K:
-        raise ValueError("A and B disagree on K")
+    """GEMM with the MBS correction for operands in 8-bit or (packed) 6-bit MX element formats; a_mbs / b_mbs may
+    be None.  K is taken from the scale arrays."""
+    M, N, K = a_codes.shape[0], b_codes.shape[0], a_scales.shape[1] * 32
+    if b_scales.shape[1] * 32 != K or a_codes.shape[1] != elem_code_bytes(a_elem, K) or b_codes.shape[1] != elem_code_bytes(b_elem, K):
+        raise ValueError("A and B disagree on K, or a code array does not have the row length of its format")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
     _check(load_library().mx_gemm_mbs_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
                                            _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,

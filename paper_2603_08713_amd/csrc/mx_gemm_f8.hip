@@ -72,6 +72,10 @@ template <int kFmtA, int kFmtB, bool kMbs, bool kFast>
 __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g) {
     using S = F8Shape<kFast>;
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, kCodeDma = S::kCodeDma;
+    // 6-bit codes (format selectors 2, 3) come packed, 24 bytes per block; both operands have the same width
+    constexpr bool kSix = kFmtA >= 2;
+    static_assert(kSix == (kFmtB >= 2) && (!kSix || kFast), "6-bit operands: both, and the fast form only");
+    constexpr int kRowStage = kSix ? 96 : kF8RowStage;  // code bytes per row and stage
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles,
@@ -88,13 +92,14 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     const int64_t a_row0 = (int64_t)tm * TM, b_row0 = (int64_t)tn * TN;
 
     const int K = (int)g.K, scale_bytes = K >> 5, nmac = K / kMacro, nstages = nmac;
+    const int row_bytes = kSix ? K / 4 * 3 : K;
     // buffer resources rebased to the tile's first row and sized to its valid rows: rows past the end read zero
     const int kRsrcFlags = 0x00020000;
     const int64_t a_rows = min((int64_t)TM, g.M - a_row0), b_rows = min((int64_t)TN, g.N - b_row0);
     const __amdgpu_buffer_rsrc_t a_codes = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(g.a_codes) + a_row0 * K, 0, (int)(a_rows * K), kRsrcFlags);
+        const_cast<uint8_t*>(g.a_codes) + a_row0 * row_bytes, 0, (int)(a_rows * row_bytes), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t b_codes = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(g.b_codes) + b_row0 * K, 0, (int)(b_rows * K), kRsrcFlags);
+        const_cast<uint8_t*>(g.b_codes) + b_row0 * row_bytes, 0, (int)(b_rows * row_bytes), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t a_scales = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(g.a_scales) + a_row0 * scale_bytes, 0, (int)(a_rows * scale_bytes), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t b_scales = __builtin_amdgcn_make_buffer_rsrc(
@@ -115,8 +120,14 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // position l of that 1-KiB block and fetches row l / 8, piece (l % 8) ^ ((row >> 1) & 7).
     // (load i adds i * NW * 8 whole rows, which leaves (row >> 1) & 7 as it is; the row has to stay in the per-lane
     // offset, the only part of the address the hardware checks against the buffer's valid rows)
-    const int code_row0 = w * 8 + (l >> 3);
-    const int code_off0 = code_row0 * K + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
+    // 6-bit codes: a row's stage is six 16-byte pieces; the 8 rows of a load take 48 of its 64 LDS positions,
+    // starting at position 0 or 1 by the parity of the 8-row group (the load index adds whole pairs of groups, so the
+    // parity is the wavefront's); the other lanes fetch out of range and pad with zeros.  Shifting every other
+    // group by one position halves the bank conflicts of the 8-byte fragment reads (rows are 24 dwords apart).
+    const int six_lane = l - (w & 1);
+    const int code_row0 = w * 8 + (kSix ? six_lane / 6 : l >> 3);
+    const int code_off0 = kSix ? (six_lane >= 0 && six_lane < 48 ? code_row0 * row_bytes + six_lane % 6 * 16 : kOob)
+                               : code_row0 * K + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
     // general form: a lane's E8M0 dword per fragment and stage, and the MBS word of the row it converts
     const int scale_off_a0 = (wm * FM * 32 + lr) * scale_bytes, scale_off_b0 = (wn * FN * 32 + lr) * scale_bytes;
     const int m8_off_a = (wm * FM * 32 + l) * nmac, m8_off_b = (wn * FN * 32 + l) * nmac;
@@ -137,12 +148,12 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         constexpr int slot = decltype(slot_)::value, i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
         if constexpr (i < kLoadsA) {
             uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
-            const int voff = code_off0 + i * NW * 8 * K;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+            const int voff = code_off0 + i * NW * 8 * row_bytes;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kRowStage, 0, 0);
         } else if constexpr (i < kCodeDma) {
             uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
-            const int voff = code_off0 + (i - kLoadsA) * NW * 8 * K;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kF8RowStage, 0, 0);
+            const int voff = code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kRowStage, 0, 0);
         }
     };
     // Fast form: E8M0 bytes and MBS words of the four stages of group grp, the E8M0 bytes into LDS buffer grp % 2
@@ -202,7 +213,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
         for (int part = 0; part < 2; ++part) {
-            const int piece = lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
+            // 8-bit: piece 2 (2 kk + part) + lh of row lr, swizzled.  6-bit: the lane's whole block 2 kk + lh, 24
+            // bytes, read as three 8-byte parts from the address in entry [kk][0] (group of 8 rows lr / 8 at 1 KiB
+            // pitch, odd groups one position up, rows 96 bytes apart)
+            const int piece = kSix ? (lr >> 3) * 1024 + ((lr >> 3) & 1) * 16 + (lr & 7) * 96 + (2 * kk + lh) * 24
+                                   : lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
             frag_b[kk][part] = S::kBaseB + wn * FN * 32 * kF8RowStage + piece;
             frag_a[kk][part] = S::kBaseA + wm * FM * 32 * kF8RowStage + piece;
             frag_a_hi[kk][part] = frag_a[kk][part] + 65536;
@@ -221,9 +236,18 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         constexpr bool far = is_a && off >= 65536;  // past the range of the instruction's constant
         const int b0 = is_a ? (far ? frag_a_hi[kk][0] : frag_a[kk][0]) : frag_b[kk][0];
         const int b1 = is_a ? (far ? frag_a_hi[kk][1] : frag_a[kk][1]) : frag_b[kk][1];
-        const v4i lo = *reinterpret_cast<const v4i*>(smem + b0 + (far ? off - 65536 : off));
-        const v4i hi = *reinterpret_cast<const v4i*>(smem + b1 + (far ? off - 65536 : off));
-        const v8i v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        v8i v;
+        if constexpr (kSix) {
+            const uint8_t* p = smem + b0 + (far ? off - 65536 : off);
+            const uint2 p0 = *reinterpret_cast<const uint2*>(p), p1 = *reinterpret_cast<const uint2*>(p + 8),
+                        p2 = *reinterpret_cast<const uint2*>(p + 16);
+            v = v8i{(int)p0.x, (int)p0.y, (int)p1.x, (int)p1.y, (int)p2.x, (int)p2.y, 0, 0};
+            (void)b1;
+        } else {
+            const v4i lo = *reinterpret_cast<const v4i*>(smem + b0 + (far ? off - 65536 : off));
+            const v4i hi = *reinterpret_cast<const v4i*>(smem + b1 + (far ? off - 65536 : off));
+            v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
         if constexpr (is_a) fa[idx][kk] = v;
         else fb[idx][kk] = v;
     };
@@ -487,9 +511,11 @@ int launch_f8(GemmArgs g, bool use_mbs, hipStream_t s) {
     // fast form: E8M0 bytes and MBS words travel per group of four stages, as 16-byte pieces and dwords
     const bool fast = !g_f8_general && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
                       (!g.a_mbs || aligned(g.a_mbs, 4)) && (!g.b_mbs || aligned(g.b_mbs, 4));
-    if (fast)
+    if (fast || kFmtA >= 2)  // (6-bit operands have been checked to allow the fast form)
         return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, true>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, true>(g, blocks, s);
-    return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, false>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, false>(g, blocks, s);
+    if constexpr (kFmtA < 2)
+        return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, false>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, false>(g, blocks, s);
+    return MX_EUNSUPPORTED;
 }
 
 int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, int b_elem,
@@ -504,10 +530,14 @@ int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales
     if (!C || (K > 0 && (!a_codes || !a_scales || !b_codes || !b_scales))) return MX_ENULL;
     const size_t esz = c_dtype == MX_OUT_F32 ? 4 : 2;
     if (!aligned(C, esz)) return MX_EALIGN;
-    const bool fp8 = (a_elem == MX_ELEM_E4M3 || a_elem == MX_ELEM_E5M2) && (b_elem == MX_ELEM_E4M3 || b_elem == MX_ELEM_E5M2);
-    if (!fp8 || K == 0 || (K % kMacro) != 0 || !aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(a_scales, 4) ||
+    const bool a8 = a_elem == MX_ELEM_E4M3 || a_elem == MX_ELEM_E5M2, b8 = b_elem == MX_ELEM_E4M3 || b_elem == MX_ELEM_E5M2;
+    if (a8 != b8 || K == 0 || (K % kMacro) != 0 || !aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(a_scales, 4) ||
         !aligned(b_scales, 4))
         return MX_EUNSUPPORTED;
+    // 6-bit operands: the kernel's fast form only
+    const bool fast_ok = (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16) && (!a_mbs || aligned(a_mbs, 4)) &&
+                         (!b_mbs || aligned(b_mbs, 4));
+    if (!a8 && !fast_ok) return MX_EUNSUPPORTED;
     if (int st = check_device()) return st;
     GemmArgs g = {};
     g.a_codes = a_codes; g.a_scales = a_scales; g.a_mbs = a_mbs;
@@ -518,6 +548,13 @@ int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales
     g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = a_mbs || b_mbs;
+    if (!a8) {
+        const bool a32 = a_elem == MX_ELEM_E3M2, b32 = b_elem == MX_ELEM_E3M2;
+        if (!a32 && !b32) return launch_f8<2, 2>(g, use_mbs, s);
+        if (!a32 && b32) return launch_f8<2, 3>(g, use_mbs, s);
+        if (a32 && !b32) return launch_f8<3, 2>(g, use_mbs, s);
+        return launch_f8<3, 3>(g, use_mbs, s);
+    }
     const bool a5 = a_elem == MX_ELEM_E5M2, b5 = b_elem == MX_ELEM_E5M2;
     if (!a5 && !b5) return launch_f8<0, 0>(g, use_mbs, s);
     if (!a5 && b5) return launch_f8<0, 1>(g, use_mbs, s);

@@ -271,6 +271,68 @@ def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
                                          "%s %dx%dx%d" % (name, M, N, K))
 
 
+@pytest.mark.parametrize("ea,eb", [("e2m3", "e2m3"), ("e2m3", "e3m2"), ("e3m2", "e2m3"), ("e3m2", "e3m2")])
+def test_gemm_elem_six_bit_random_codes_and_scales(mx, oracle, ea, eb):
+    """MXFP6 operands (packed 6-bit codes; every code is a finite value): every code, scale byte and lane position;
+    tiles with ragged tails; K of 1 to 4 groups of four stages, one turn of the loop, and a turn plus one and two
+    groups.  E2M3 products span 12 binades and add up without loss, like FP4's; with E3M2 (18 binades) the bound
+    of the 8-bit formats applies."""
+    rng = np.random.default_rng(46)
+    for (M, N, K) in ((16, 16, 512), (257, 130, 1536), (100, 129, 2048), (300, 260, 1024), (70, 140, 6144), (33, 260, 6656),
+                      (260, 33, 7168)):
+        a = (rng.integers(0, 64, (M, K), dtype=np.uint8), rng.integers(110, 140, (M, K // 32), dtype=np.uint8),
+             rng.integers(0, 256, (M, K // 128), dtype=np.uint8))
+        b = (rng.integers(0, 64, (N, K), dtype=np.uint8), rng.integers(110, 140, (N, K // 32), dtype=np.uint8),
+             rng.integers(0, 256, (N, K // 128), dtype=np.uint8))
+        for a1, b1, name in ((a, b, "mbs"), ((a[0], a[1], None), b, "B words only"), ((a[0], a[1], None), (b[0], b[1], None), "no words")):
+            pa, pb = (canonical_codes(ea, a1[0]), a1[1], a1[2]), (canonical_codes(eb, b1[0]), b1[1], b1[2])
+            got = host(gpu_gemm(mx, ea, pa, eb, pb))
+            want = oracle.elem_gemm(ea, a1, eb, b1)
+            if ea == "e2m3" and eb == "e2m3":
+                assert_gemm_close(got, want, "%s %s x %s %dx%dx%d" % (name, ea, eb, M, N, K))
+            else:
+                absc = oracle.elem_gemm(ea, (a1[0] & 0x1F, a1[1], a1[2]), eb, (b1[0] & 0x1F, b1[1], b1[2]))
+                ratio = float(np.nanmax(np.abs(got.astype(np.float64) - want) / absc))
+                assert ratio <= ABS_TOL, "%s %s x %s %dx%dx%d: %.3e" % (name, ea, eb, M, N, K, ratio)
+    with pytest.raises(mx.MxError) as e:  # 6-bit with 8-bit operands, and K outside the fast form
+        gpu_gemm(mx, "e2m3", (canonical_codes("e2m3", a[0]), a[1], a[2]), "e4m3", b)
+    assert e.value.status == -4
+    with pytest.raises(mx.MxError) as e:
+        gpu_gemm(mx, "e2m3", (canonical_codes("e2m3", a[0][:, :640]), a[1][:, :20], a[2][:, :5]), "e2m3",
+                 (canonical_codes("e2m3", b[0][:, :640]), b[1][:, :20], b[2][:, :5]))
+    assert e.value.status == -4
+
+
+def test_gemm_elem_six_bit_quantized_tensors(mx, oracle):
+    """MXFP6 end to end on the GPU (quantize both operands, multiply) against the oracle: operands bit-exact, the
+    product within 1e-3 RMS, a second launch bit-identical, and QSNR(AB) between MXFP4's and MXFP8's."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 200, 300, 1536
+    a_bits = synth.activations_student_t(M, K, 3.0, 0.01, 20.0, 3)
+    w_bits = synth.gaussian(N, K, 0.02, 4)
+    xa, xw = dev_bf16(a_bits), dev_bf16(w_bits)
+    ref = oracle.matmul_bf16(a_bits, w_bits)
+    q = {}
+    for ea, eb, rule in (("e2m3", "e2m3", "oas"), ("e3m2", "e2m3", "floor"), ("e2m3", "e3m2", "ocp"), ("e3m2", "e3m2", "oas")):
+        a = mx.mx_quantize_elem(xa, ea, rule)
+        b = mx.mx_quantize_elem(xw, eb, rule)
+        c = mx.mx_gemm_mbs_elem(ea, a[0], a[1], a[2], eb, b[0], b[1], b[2], "f32")
+        c2 = mx.mx_gemm_mbs_elem(ea, a[0], a[1], a[2], eb, b[0], b[1], b[2], "f32")
+        c16 = mx.mx_gemm_mbs_elem(ea, a[0], a[1], a[2], eb, b[0], b[1], b[2], "bf16")
+        torch.cuda.synchronize()
+        assert torch.equal(c, c2) and torch.equal(c16, c.to(torch.bfloat16))
+        oa, ob = oracle.elem_quantize(ea, a_bits, rule, mbs=True), oracle.elem_quantize(eb, w_bits, rule, mbs=True)
+        assert np.array_equal(host(a[0]), canonical_codes(ea, oa[0])) and np.array_equal(host(b[0]), canonical_codes(eb, ob[0]))
+        assert_gemm_close(host(c), oracle.elem_gemm(ea, oa, eb, ob), "%s x %s %s" % (ea, eb, rule))
+        q[(ea, eb, rule)] = oracle.qsnr_db(ref, host(c))
+    a4, b4 = mx.mx_quantize_mbs(xa, "oas"), mx.mx_quantize_mbs(xw, "oas")
+    q4 = oracle.qsnr_db(ref, host(mx.mx_gemm_mbs(*a4, *b4, "f32")))
+    a8, b8 = mx.mx_quantize_elem(xa, "e4m3", "oas"), mx.mx_quantize_elem(xw, "e4m3", "oas")
+    q8 = oracle.qsnr_db(ref, host(mx.mx_gemm_mbs_elem("e4m3", *a8, "e4m3", *b8, "f32")))
+    assert q4 + 5.0 < q[("e2m3", "e2m3", "oas")] < q8 + 1.0, (q4, q, q8)
+
+
 def test_gemm_elem_general_form_equals_fast_form(mx, oracle):
     """Where both forms of the kernel apply they run the same matrix instructions on the same data in the same
     order: bit-identical results."""
