@@ -213,10 +213,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
         for (int part = 0; part < 2; ++part) {
-            // 8-bit: piece 2 (2 kk + part) + lh of row lr, swizzled.  6-bit: the lane's whole block 2 kk + lh, 24
-            // bytes, read as three 8-byte parts from the address in entry [kk][0] (group of 8 rows lr / 8 at 1 KiB
-            // pitch, odd groups one position up, rows 96 bytes apart)
-            const int piece = kSix ? (lr >> 3) * 1024 + ((lr >> 3) & 1) * 16 + (lr & 7) * 96 + (2 * kk + lh) * 24
+            // 8-bit: piece 2 (2 kk + part) + lh of row lr, swizzled.  6-bit: the lane's whole block kk + 2 lh, 24
+            // bytes from the address in entry [kk][0] (group of 8 rows lr / 8 at 1 KiB pitch, odd groups one
+            // position up, rows 96 bytes apart).  Blocks 0 and 2 start on 16-byte boundaries, blocks 1 and 3 eight
+            // bytes past one: instruction 0 reads 16 + 8 bytes, instruction 1 reads 8 + 16
+            const int piece = kSix ? (lr >> 3) * 1024 + ((lr >> 3) & 1) * 16 + (lr & 7) * 96 + (kk + 2 * lh) * 24
                                    : lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
             frag_b[kk][part] = S::kBaseB + wn * FN * 32 * kF8RowStage + piece;
             frag_a[kk][part] = S::kBaseA + wm * FM * 32 * kF8RowStage + piece;
@@ -239,9 +240,15 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         v8i v;
         if constexpr (kSix) {
             const uint8_t* p = smem + b0 + (far ? off - 65536 : off);
-            const uint2 p0 = *reinterpret_cast<const uint2*>(p), p1 = *reinterpret_cast<const uint2*>(p + 8),
-                        p2 = *reinterpret_cast<const uint2*>(p + 16);
-            v = v8i{(int)p0.x, (int)p0.y, (int)p1.x, (int)p1.y, (int)p2.x, (int)p2.y, 0, 0};
+            if constexpr (kk == 0) {
+                const v4i p0 = *reinterpret_cast<const v4i*>(p);
+                const uint2 p1 = *reinterpret_cast<const uint2*>(p + 16);
+                v = v8i{p0.x, p0.y, p0.z, p0.w, (int)p1.x, (int)p1.y, 0, 0};
+            } else {
+                const uint2 p0 = *reinterpret_cast<const uint2*>(p);
+                const v4i p1 = *reinterpret_cast<const v4i*>(p + 8);
+                v = v8i{(int)p0.x, (int)p0.y, p1.x, p1.y, p1.z, p1.w, 0, 0};
+            }
             (void)b1;
         } else {
             const v4i lo = *reinterpret_cast<const v4i*>(smem + b0 + (far ? off - 65536 : off));
@@ -254,18 +261,20 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     using IsA = std::integral_constant<bool, true>;
     using IsB = std::integral_constant<bool, false>;
 
-    // E8M0 operands of a stage: lane half h supplies the byte of block 2 kk + h, i.e. bytes h and 2 + h of the row's
-    // four, so the dword goes in shifted right by 8 h and op_sel picks byte 0 or 2.
+    // E8M0 operands of a stage.  8-bit: lane half h supplies the byte of block 2 kk + h, i.e. bytes h and 2 + h of the
+    // row's four, so the dword goes in shifted right by 8 h and op_sel picks byte 0 or 2.  6-bit: the lane's own
+    // block kk + 2 h: shifted right by 16 h, op_sel picks byte 0 or 1.
+    constexpr int kSclShift = kSix ? 16 : 8, kSel1 = kSix ? 1 : 2;  // op_sel of a macro block's second instruction
     uint32_t scl_a[FM], scl_b[FN];
     const int lane_scale_a = S::kSmallBase + (wm * FM * 32 + lr) * 16, lane_scale_b = S::kSmallBase + (TM + wn * FN * 32 + lr) * 16;
     auto read_scales_fast = [&](int s) __attribute__((always_inline)) {  // stage s out of its group's LDS buffer
         const int at = ((s / S::kGroup) & 1) * S::kScaleGroup + (s % S::kGroup) * 4;
 #pragma unroll
         for (int i = 0; i < FM; ++i)
-            scl_a[i] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_a + at + i * 32 * 16) >> (8 * lh);
+            scl_a[i] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_a + at + i * 32 * 16) >> (kSclShift * lh);
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-            scl_b[j] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_b + at + j * 32 * 16) >> (8 * lh);
+            scl_b[j] = *reinterpret_cast<const uint32_t*>(smem + lane_scale_b + at + j * 32 * 16) >> (kSclShift * lh);
     };
     // fast form: the owner of a row turns its MBS word of stage s into sigma, into table s % 2
     auto convert_sigma_fast = [&](int s, auto mod3_) __attribute__((always_inline)) {  // mod3_: (s / 4) % 3
@@ -296,9 +305,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         } else {
             // what this stage needs of its prefetched registers, before the loads of stage s + 3 take them over
 #pragma unroll
-            for (int i = 0; i < FM; ++i) scl_a[i] = pref[slot].sa[i] >> (8 * lh);
+            for (int i = 0; i < FM; ++i) scl_a[i] = pref[slot].sa[i] >> (kSclShift * lh);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) scl_b[j] = pref[slot].sb[j] >> (8 * lh);
+            for (int j = 0; j < FN; ++j) scl_b[j] = pref[slot].sb[j] >> (kSclShift * lh);
             if constexpr (kMbs) {
                 sig[l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].ma * (1.0f / 256.0f));
                 sig[64 + l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].mb * (1.0f / 256.0f));
@@ -338,7 +347,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                                                                                 (int)scl_b[j], 0, (int)scl_a[i]);
                 issue_code(st3, slot_, std::integral_constant<int, 2 * q>{});
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][1], fa[i][1], prod[q % 2], kFmtB, kFmtA,
-                                                                                2, (int)scl_b[j], 2, (int)scl_a[i]);
+                                                                                kSel1, (int)scl_b[j], kSel1, (int)scl_a[i]);
                 issue_code(st3, slot_, std::integral_constant<int, 2 * q + 1>{});
                 if constexpr (i == FM - 1) {
                     read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 0>{});
@@ -378,8 +387,8 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             // instruction t: half kk = t / (FM FN) of pair (i, j); a fragment half is refilled after its last use
             static_for<2 * FM * FN>([&](auto t_) {
                 constexpr int t = decltype(t_)::value, kk = t / (FM * FN), i = t % (FM * FN) / FN, j = t % FN;
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][kk], fa[i][kk], acc[i][j], kFmtB, kFmtA, 2 * kk,
-                                                                             (int)scl_b[j], 2 * kk, (int)scl_a[i]);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][kk], fa[i][kk], acc[i][j], kFmtB, kFmtA, kSel1 * kk,
+                                                                             (int)scl_b[j], kSel1 * kk, (int)scl_a[i]);
                 issue_code(st3, slot_, t_);
                 if constexpr (i == FM - 1) read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, kk>{});
                 if constexpr (j == FN - 1) read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, kk>{});
