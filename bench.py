@@ -155,6 +155,7 @@ def main():
         out["extras"]["decode_m16_k4096"] = decode_extras(mx, torch, synth, np)
         out["extras"]["square_shapes"] = square_shapes(mx, torch, synth, np, metrics)
         out["extras"]["mxfp8_e4m3"] = mxfp8_extras(mx, torch, xa, xw, cs, flops, args)
+        out["extras"]["mxfp6_e2m3"] = mxfp8_extras(mx, torch, xa, xw, cs, flops, args, elem="e2m3")
         out["extras"]["qsnr_db_gpu"] = qsnr_ladder_gpu(mx, torch, xa[0][:QSNR_ROWS])
         out["extras"]["qsnr_db_gpu_weights"] = qsnr_weights_gpu(mx, torch, xw[0][:QSNR_ROWS])
         out["extras"]["qsnr_ab_db_gpu"] = qsnr_ab_gpu(mx, torch, xa[0], xw[0])
@@ -205,38 +206,43 @@ def qsnr_ab_gpu(mx, torch, xa, xw):
     return res
 
 
-def mxfp8_extras(mx, torch, xa, xw, cs, flops, args):
-    """The same step in MXFP8 (E4M3 elements; OAS and MBS restated on the element format's own constants): both
-    quantizers, then the MBS GEMM; and QSNR(AB) of the plain OCP rule against OAS + MBS-S on the product sample."""
+def mxfp8_extras(mx, torch, xa, xw, cs, flops, args, elem="e4m3"):
+    """The same step in MXFP8 (E4M3 elements) or MXFP6 (E2M3, packed codes), OAS and MBS restated on the element
+    format's own constants: both quantizers, then the MBS GEMM; and QSNR(AB) of the plain OCP rule against
+    OAS + MBS-S on the product sample."""
     n = max(5, min(args.steps, 100))
-    qa = [mx.mx_quantize_elem(x, "e4m3", "oas") for x in xa]
-    qw = [mx.mx_quantize_elem(x, "e4m3", "oas") for x in xw]
+    six = elem in ("e2m3", "e3m2")
+    qa = [mx.mx_quantize_elem(x, elem, "oas") for x in xa]
+    qw = [mx.mx_quantize_elem(x, elem, "oas") for x in xw]
 
     def step(i):
         a, w = qa[i % len(qa)], qw[i % len(qw)]
-        mx.mx_quantize_elem(xa[i % len(xa)], "e4m3", "oas", True, *a)
-        mx.mx_quantize_elem(xw[i % len(xw)], "e4m3", "oas", True, *w)
-        mx.mx_gemm_mbs_elem("e4m3", a[0], a[1], a[2], "e4m3", w[0], w[1], w[2], "bf16", out=cs[i % len(cs)])
+        mx.mx_quantize_elem(xa[i % len(xa)], elem, "oas", True, *a)
+        mx.mx_quantize_elem(xw[i % len(xw)], elem, "oas", True, *w)
+        mx.mx_gemm_mbs_elem(elem, a[0], a[1], a[2], elem, w[0], w[1], w[2], "bf16", out=cs[i % len(cs)])
 
     ms_step = time_loop(torch, step, n)
-    ms_mbs = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem("e4m3", *qa[i % len(qa)], "e4m3", *qw[i % len(qw)], "bf16", out=cs[i % len(cs)]), n)
-    ms_plain = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem("e4m3", qa[0][0], qa[0][1], None, "e4m3", qw[0][0], qw[0][1], None, "bf16",
+    ms_mbs = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem(elem, *qa[i % len(qa)], elem, *qw[i % len(qw)], "bf16", out=cs[i % len(cs)]), n)
+    ms_plain = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem(elem, qa[0][0], qa[0][1], None, elem, qw[0][0], qw[0][1], None, "bf16",
                                                               out=cs[i % len(cs)]), n)
-    ms_qw = time_loop(torch, lambda i: mx.mx_quantize_elem(xw[i % len(xw)], "e4m3", "oas", True, *qw[i % len(qw)]), n)
-    bytes_per_elt = 2 + 1 + 1 / 32 + 1 / 128
-    deq = torch.empty(tuple(xw[0].shape), dtype=torch.bfloat16, device=xw[0].device)
-    ms_d = time_loop(torch, lambda i: mx.mx_dequantize_elem("e4m3", *qw[i % len(qw)], "bf16", out=deq), n)
+    ms_qw = time_loop(torch, lambda i: mx.mx_quantize_elem(xw[i % len(xw)], elem, "oas", True, *qw[i % len(qw)]), n)
+    bytes_per_elt = 2 + (0.75 if six else 1) + 1 / 32 + 1 / 128
+    ms_d = None
+    if not six:  # (no dequantizer for the 6-bit formats)
+        deq = torch.empty(tuple(xw[0].shape), dtype=torch.bfloat16, device=xw[0].device)
+        ms_d = time_loop(torch, lambda i: mx.mx_dequantize_elem(elem, *qw[i % len(qw)], "bf16", out=deq), n)
     res = {"step_tflops": round(flops / (ms_step * 1e-3) / 1e12, 1), "ms_per_step": round(ms_step, 4),
-           "dequantize_W_gbps": round(xw[0].numel() * bytes_per_elt / (ms_d * 1e-3) / 1e9, 1),
+           "dequantize_W_gbps": None if ms_d is None else round(xw[0].numel() * bytes_per_elt / (ms_d * 1e-3) / 1e9, 1),
            "gemm_mbs_tflops": round(flops / (ms_mbs * 1e-3) / 1e12, 1), "gemm_plain_tflops": round(flops / (ms_plain * 1e-3) / 1e12, 1),
            "quantize_W_gbps": round(xw[0].numel() * bytes_per_elt / (ms_qw * 1e-3) / 1e9, 1),
-           "peak_context": "published dense FP8 peak 5.0 PFLOP/s; the paper has no MXFP8 figure"}
+           "peak_context": ("published dense FP6 peak 10.1 PFLOP/s" if six else "published dense FP8 peak 5.0 PFLOP/s") + "; the paper has no figure for this format"}
     a, w = xa[0][:QSNR_AB_ROWS], xw[0][:QSNR_AB_COLS]
     ref = a.to(torch.float64) @ w.to(torch.float64).T
     q = {}
-    for name, rule, mbs in (("MXFP8-OCP", "ocp", False), ("MXFP8-OAS", "oas", False), ("MXFP8-OAS+MBS-S", "oas", True)):
-        ta, tw = mx.mx_quantize_elem(a, "e4m3", rule, mbs), mx.mx_quantize_elem(w, "e4m3", rule, mbs)
-        c = mx.mx_gemm_mbs_elem("e4m3", *ta, "e4m3", *tw, "f32")
+    fam = "MXFP6" if six else "MXFP8"
+    for name, rule, mbs in ((fam + "-OCP", "ocp", False), (fam + "-OAS", "oas", False), (fam + "-OAS+MBS-S", "oas", True)):
+        ta, tw = mx.mx_quantize_elem(a, elem, rule, mbs), mx.mx_quantize_elem(w, elem, rule, mbs)
+        c = mx.mx_gemm_mbs_elem(elem, *ta, elem, *tw, "f32")
         q[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - c.to(torch.float64)) ** 2).sum())), 3)
     res["qsnr_ab_db_gpu"] = q
     return res

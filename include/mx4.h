@@ -148,7 +148,7 @@ int mx_gemm_mbs_grouped(const uint8_t* a_codes, const uint8_t* a_scales, const u
                         int64_t M_total, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C,
                         int64_t ldc, void* stream);
 
-/* ---- the 8-bit MX element formats (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8) ----------
+/* ---- the 8-bit and 6-bit MX element formats (Sec. 1, footnote: the methods carry over to MXFP6 / MXFP8) ----
  * The paper works MXFP4 through and only states that OAS and MBS generalise; these entry points restate
  * each rule with the element format's own constants in place of E2M1's 6 and 1: V, its largest finite
  * magnitude, and h, half the spacing of its top binade.
@@ -156,10 +156,12 @@ int mx_gemm_mbs_grouped(const uint8_t* a_codes, const uint8_t* a_scales, const u
  *   MX_RULE_OAS    FLOOR, doubled when the absmax lands at or below (V + h)/2: absmax -> ((V + h)/2, V + h]
  *   MBS-Static     m8 = the 8 leading mantissa bits of V / (absmax of the 1x128 window)
  * Elements round to the nearest value of the format, ties to the even code, saturating at +-V; the sign
- * bit is copied.  Layout: codes uint8 [rows, K], one element per byte (E4M3: S.EEEE.MMM, bias 7, V = 448,
- * h = 16; E5M2: S.EEEEE.MM, bias 15, V = 57344, h = 4096; both as in the OCP MX specification); scales and
- * mbs as for MXFP4.  MX_ELEM_E2M1 names the 4-bit format of the other entry points and is not accepted
- * here; the 6-bit formats are declared for completeness and return MX_EUNSUPPORTED. */
+ * bit is copied.  Formats as in the OCP MX specification: E4M3 (S.EEEE.MMM, bias 7, V = 448, h = 16), E5M2
+ * (S.EEEEE.MM, bias 15, V = 57344, h = 4096), E2M3 (S.EE.MMM, bias 1, V = 7.5, h = 0.25), E3M2 (S.EEE.MM, bias 3,
+ * V = 28, h = 2).  Layout of the codes: 8-bit formats uint8 [rows, K], one element per byte; 6-bit formats
+ * uint8 [rows, 3K/4], packed: element k of a row occupies bits 6k .. 6k+5 of the row's bytes taken as one
+ * little-endian number (a 32-element block is 24 bytes).  Scales and mbs as for MXFP4.  MX_ELEM_E2M1 names the
+ * 4-bit format of the other entry points and is not accepted here. */
 typedef enum {
     MX_ELEM_E2M1 = 0,
     MX_ELEM_E4M3 = 1,
@@ -168,22 +170,23 @@ typedef enum {
     MX_ELEM_E3M2 = 4
 } mx_elem_t;
 
-/* mx_quantize (use_mbs = 0, mbs ignored) or mx_quantize_mbs (use_mbs != 0) into an 8-bit element format.
- * Alignment: x 16 bytes and ldx a multiple of 8, codes 8 bytes.  K % 32 == 0. */
+/* mx_quantize (use_mbs = 0, mbs ignored) or mx_quantize_mbs (use_mbs != 0) into an 8-bit or 6-bit element
+ * format.  Alignment: x 16 bytes and ldx a multiple of 8, codes 8 bytes.  K % 32 == 0. */
 int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                      int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
 /* mx_dequantize for an 8-bit element format: out[r, k] = value(code) * 2^(E-127) / F, F = 1 without MBS words
  * (Sec. 4.3.1).  The fp32 result is the quotient evaluated in fp64 and rounded once more; the bf16 result is that
  * fp32 value rounded to nearest even; a block with E = 255 gives NaN.  Alignment: codes 8 bytes, out its element
- * size; ldo >= K in elements. */
+ * size; ldo >= K in elements.  8-bit formats only (the 6-bit ones return MX_EUNSUPPORTED). */
 int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs_or_null,
                        int64_t rows, int64_t K, mx_dtype_t out_dtype, void* out, int64_t ldo, void* stream);
 
-/* mx_gemm_mbs for operands in 8-bit element formats (they may differ between A and B): the same sum, the
- * same MBS correction per 128 K-elements (Sec. 4.3.2, which does not depend on the element format), on the
- * same scaled matrix instruction.  Covers K > 0, K % 128 == 0, codes 16-byte and scale arrays 4-byte
- * aligned; anything else returns MX_EUNSUPPORTED and nothing is launched. */
+/* mx_gemm_mbs for operands in 8-bit or in 6-bit element formats (A's and B's may differ, but both are 8-bit or
+ * both 6-bit): the same sum, the same MBS correction per 128 K-elements (Sec. 4.3.2, which does not depend on
+ * the element format), on the same scaled matrix instruction.  Covers, for 8-bit operands, K > 0, K % 128 == 0,
+ * codes 16-byte and scale arrays 4-byte aligned; for 6-bit operands K > 0, K % 512 == 0, codes and scale arrays
+ * 16-byte and MBS arrays 4-byte aligned; anything else returns MX_EUNSUPPORTED and nothing is launched. */
 int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
                      mx_elem_t b_elem, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
                      int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream);
