@@ -12,7 +12,7 @@
 // pattern of absmax * F with a carry; blocks that could leave fp32's normal range, or hold Inf/NaN, take a
 // wave-uniform detour through all-integer arithmetic.
 // Output: 8-bit codes one per byte; 6-bit codes packed, element k of a row in bits 6 k .. 6 k + 5 of the row's
-// bytes (a block is 24 bytes, which the first lane of its four gathers and stores).
+// bytes (a block is 24 bytes, which three of its four lanes store, 8 bytes each, after a DPP exchange).
 #include "mx_quantize_math.h"
 
 namespace mx {
@@ -282,11 +282,12 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
             const uint32_t kblk = col[u] >> 5;
             uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
             if constexpr (Fp8<kElem>::kBits == 6) {
-                if ((lane & 3) == 0) {
+                // lanes 0, 1, 2 of the block store 8 bytes each: one instruction covers the block's 24 bytes
+                const uint32_t part = lane & 3;
+                if (part < 3) {
                     uint2* dst = reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * (q.K / 4 * 3) + (int64_t)kblk * 24);
-                    dst[0] = make_uint2(six[0], six[1]);
-                    dst[1] = make_uint2(six[2], six[3]);
-                    dst[2] = make_uint2(six[4], six[5]);
+                    dst[part] = make_uint2(part == 0 ? six[0] : part == 1 ? six[2] : six[4],
+                                           part == 0 ? six[1] : part == 1 ? six[3] : six[5]);
                 }
             } else {
                 *reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * q.K + col[u]) = make_uint2(res.lo, res.hi);
