@@ -120,14 +120,12 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // position l of that 1-KiB block and fetches row l / 8, piece (l % 8) ^ ((row >> 1) & 7).
     // (load i adds i * NW * 8 whole rows, which leaves (row >> 1) & 7 as it is; the row has to stay in the per-lane
     // offset, the only part of the address the hardware checks against the buffer's valid rows)
-    // 6-bit codes: a row's stage is six 16-byte pieces; the 8 rows of a load take 48 of its 64 LDS positions,
-    // starting at position 0 or 1 by the parity of the 8-row group (the load index adds whole pairs of groups, so the
-    // parity is the wavefront's); the other lanes fetch out of range and pad with zeros.  Shifting every other
-    // group by one position halves the bank conflicts of the 8-byte fragment reads (rows are 24 dwords apart).
-    const int six_lane = l - (w & 1);
-    const int code_row0 = w * 8 + (kSix ? six_lane / 6 : l >> 3);
-    const int code_off0 = kSix ? (six_lane >= 0 && six_lane < 48 ? code_row0 * row_bytes + six_lane % 6 * 16 : kOob)
-                               : code_row0 * K + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
+    // 6-bit codes: a stage is 96 bytes of a row, which would straddle the 128-byte lines of the memory system; the
+    // unit of loading is therefore a plane, 128 bytes of every row, a third of the group of four stages (384 bytes
+    // a row).  Ring slot L holds plane L of the current group, in the 8-bit layout, and is loaded again, with the
+    // next group's plane, during stage L + 1 of the group, after the last fragment that reads it has been fetched.
+    const int code_row0 = w * 8 + (l >> 3);
+    const int code_off0 = code_row0 * row_bytes + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
     // general form: a lane's E8M0 dword per fragment and stage, and the MBS word of the row it converts
     const int scale_off_a0 = (wm * FM * 32 + lr) * scale_bytes, scale_off_b0 = (wn * FN * 32 + lr) * scale_bytes;
     const int m8_off_a = (wm * FM * 32 + l) * nmac, m8_off_b = (wn * FN * 32 + l) * nmac;
@@ -143,17 +141,17 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     Pref pref[kFast ? 1 : kF8Slots];
     uint32_t own_m8[kF8Slots] = {0u, 0u, 0u};  // fast form: the owned row's four MBS words of group g, in g % 3
 
-    // load i of the codes of stage st (a stage past the end of K fetches the last one again) into ring slot `slot`
-    auto issue_code = [&](int st, auto slot_, auto i_) __attribute__((always_inline)) {
+    // load i of the codes that start soff bytes into their rows into ring slot `slot`
+    auto issue_code = [&](int soff, auto slot_, auto i_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value, i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
         if constexpr (i < kLoadsA) {
             uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
             const int voff = code_off0 + i * NW * 8 * row_bytes;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, st * kRowStage, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         } else if constexpr (i < kCodeDma) {
             uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
             const int voff = code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, st * kRowStage, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         }
     };
     // Fast form: E8M0 bytes and MBS words of the four stages of group grp, the E8M0 bytes into LDS buffer grp % 2
@@ -190,7 +188,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         const int st = min(s, nstages - 1);
         asm volatile("" ::: "memory");
         issue_regs(st, slot_);
-        static_for<kCodeDma>([&](auto i_) { issue_code(st, slot_, i_); });
+        static_for<kCodeDma>([&](auto i_) { issue_code(st * kRowStage, slot_, i_); });
         asm volatile("" ::: "memory");
     };
 
@@ -213,12 +211,8 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
         for (int part = 0; part < 2; ++part) {
-            // 8-bit: piece 2 (2 kk + part) + lh of row lr, swizzled.  6-bit: the lane's whole block kk + 2 lh, 24
-            // bytes from the address in entry [kk][0] (group of 8 rows lr / 8 at 1 KiB pitch, odd groups one
-            // position up, rows 96 bytes apart).  Blocks 0 and 2 start on 16-byte boundaries, blocks 1 and 3 eight
-            // bytes past one: instruction 0 reads 16 + 8 bytes, instruction 1 reads 8 + 16
-            const int piece = kSix ? (lr >> 3) * 1024 + ((lr >> 3) & 1) * 16 + (lr & 7) * 96 + (kk + 2 * lh) * 24
-                                   : lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
+            // 8-bit: piece 2 (2 kk + part) + lh of row lr, swizzled (6-bit operands have registers of their own)
+            const int piece = lr * kF8RowStage + (((2 * (2 * kk + part) + lh) ^ ((lr >> 1) & 7)) * 16);
             frag_b[kk][part] = S::kBaseB + wn * FN * 32 * kF8RowStage + piece;
             frag_a[kk][part] = S::kBaseA + wm * FM * 32 * kF8RowStage + piece;
             frag_a_hi[kk][part] = frag_a[kk][part] + 65536;
@@ -227,30 +221,50 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             asm volatile("" : "+v"(frag_a_hi[kk][part]));
         }
 
+    // 6-bit: the lane's blocks kk + 2 lh of stage q of the group are the 48 bytes from 96 q + 48 lh of the row's
+    // 384, that is the 16-byte pieces 6 q + 3 lh .. + 2 of the group's 24 (eight to a plane, swizzled like the
+    // 8-bit pieces): instruction 0 reads the first piece and half of the second, instruction 1 the other half and
+    // the third.
+    int six_a[kSix ? 4 : 1][3], six_b[kSix ? 4 : 1][3];
+    if constexpr (kSix) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const int piece = 6 * q + 3 * lh + c, plane = piece >> 3;
+                const int at = lr * kF8RowStage + (((piece & 7) ^ ((lr >> 1) & 7)) * 16);
+                six_b[q][c] = S::kBaseB + plane * S::kStageB + wn * FN * 32 * kF8RowStage + at;
+                six_a[q][c] = S::kBaseA + plane * S::kStageA + wm * FM * 32 * kF8RowStage + at;
+                asm volatile("" : "+v"(six_b[q][c]));
+                asm volatile("" : "+v"(six_a[q][c]));
+            }
+    }
+
     // Operands of one macro block in registers.  They are refilled in place: a fragment takes the next stage's
     // data right after the last matrix instruction that reads it has been issued.
     v8i fa[FM][2], fb[FN][2];
+    // (slot_: the ring slot; for 6-bit operands the stage's place in its group)
     auto read_frag = [&](auto slot_, auto is_a_, auto idx_, auto kk_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value, idx = decltype(idx_)::value, kk = decltype(kk_)::value;
         constexpr bool is_a = decltype(is_a_)::value;
-        constexpr int off = (is_a ? slot * S::kStageA : slot * S::kStageB) + idx * 32 * kF8RowStage;
-        constexpr bool far = is_a && off >= 65536;  // past the range of the instruction's constant
-        const int b0 = is_a ? (far ? frag_a_hi[kk][0] : frag_a[kk][0]) : frag_b[kk][0];
-        const int b1 = is_a ? (far ? frag_a_hi[kk][1] : frag_a[kk][1]) : frag_b[kk][1];
         v8i v;
         if constexpr (kSix) {
-            const uint8_t* p = smem + b0 + (far ? off - 65536 : off);
+            const int* at = is_a ? six_a[slot] : six_b[slot];
+            constexpr int row0 = idx * 32 * kF8RowStage;
             if constexpr (kk == 0) {
-                const v4i p0 = *reinterpret_cast<const v4i*>(p);
-                const uint2 p1 = *reinterpret_cast<const uint2*>(p + 16);
+                const v4i p0 = *reinterpret_cast<const v4i*>(smem + at[0] + row0);
+                const uint2 p1 = *reinterpret_cast<const uint2*>(smem + at[1] + row0);
                 v = v8i{p0.x, p0.y, p0.z, p0.w, (int)p1.x, (int)p1.y, 0, 0};
             } else {
-                const uint2 p0 = *reinterpret_cast<const uint2*>(p);
-                const v4i p1 = *reinterpret_cast<const v4i*>(p + 8);
+                const uint2 p0 = *reinterpret_cast<const uint2*>(smem + at[1] + row0 + 8);
+                const v4i p1 = *reinterpret_cast<const v4i*>(smem + at[2] + row0);
                 v = v8i{(int)p0.x, (int)p0.y, p1.x, p1.y, p1.z, p1.w, 0, 0};
             }
-            (void)b1;
         } else {
+            constexpr int off = (is_a ? slot * S::kStageA : slot * S::kStageB) + idx * 32 * kF8RowStage;
+            constexpr bool far = is_a && off >= 65536;  // past the range of the instruction's constant
+            const int b0 = is_a ? (far ? frag_a_hi[kk][0] : frag_a[kk][0]) : frag_b[kk][0];
+            const int b1 = is_a ? (far ? frag_a_hi[kk][1] : frag_a[kk][1]) : frag_b[kk][1];
             const v4i lo = *reinterpret_cast<const v4i*>(smem + b0 + (far ? off - 65536 : off));
             const v4i hi = *reinterpret_cast<const v4i*>(smem + b1 + (far ? off - 65536 : off));
             v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -289,13 +303,17 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // loads of stages s + 1 and s + 2 are in flight.
     auto stage = [&](int s, auto slot_, auto phase_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
-        using Next = std::integral_constant<int, (slot + 1) % kF8Slots>;
+        constexpr int p = decltype(phase_)::value % S::kGroup;  // fast form: the stage's place in its group
+        using Next = std::integral_constant<int, kSix ? (p + 1) % S::kGroup : (slot + 1) % kF8Slots>;
         // own loads of stage s + 1 have landed (those of stage s + 2 may still fly; the fast form's group loads
         // are requested ahead of a stage's codes, so they have landed a stage after their request); own LDS
         // traffic is done.  (The count is only right if every load of the earlier issue() calls has been issued
         // by now: the empty asm keeps the compiler from moving one across.)
+        // 6-bit: the pieces the next stage's fragments come from belong to planes requested two stages ago or
+        // earlier; since then came one stage's plane (six loads) or, before the group's second stage, the group
+        // loads (of which the second may still fly).
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(wait_imm(S::kLoads));
+        __builtin_amdgcn_s_waitcnt(wait_imm(kSix ? (p == 1 ? 1 : kCodeDma) : S::kLoads));
         bare_barrier();
         if constexpr (kFast) {
             // (t: the stage's place in the turn of the loop, 3 groups of 4 stages)
@@ -318,6 +336,13 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         // for its 64 lanes, and six in a row from all eight wavefronts would stall the matrix pipeline
         const int st3 = min(s + 3, nstages - 1);
         issue_regs(st3, slot_);
+        // (6-bit: plane p - 1 of the next group, which the last group fetches from itself again; nothing in the
+        // group's first stage)
+        using CodeSlot = std::integral_constant<int, kSix ? (p > 0 ? p - 1 : 0) : slot>;
+        const int code_soff = kSix ? min(s / S::kGroup + 1, ngroups - 1) * (S::kGroup * kRowStage) + (p - 1) * 128 : st3 * kRowStage;
+        auto issue_next = [&](auto i_) __attribute__((always_inline)) {
+            if constexpr (!kSix || p > 0) issue_code(code_soff, CodeSlot{}, i_);
+        };
 
         // sigma of this lane's output row per A fragment; of its 16 output columns per B fragment, kept as four
         // registers: lane l holds the value of column 8 gq + 4 h + l % 4, and the multiply fetches column i from
@@ -345,10 +370,10 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 for (int e = 0; e < 16; ++e) zero[e] = 0.f;
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][0], fa[i][0], zero, kFmtB, kFmtA, 0,
                                                                                 (int)scl_b[j], 0, (int)scl_a[i]);
-                issue_code(st3, slot_, std::integral_constant<int, 2 * q>{});
+                issue_next(std::integral_constant<int, 2 * q>{});
                 prod[q % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][1], fa[i][1], prod[q % 2], kFmtB, kFmtA,
                                                                                 kSel1, (int)scl_b[j], kSel1, (int)scl_a[i]);
-                issue_code(st3, slot_, std::integral_constant<int, 2 * q + 1>{});
+                issue_next(std::integral_constant<int, 2 * q + 1>{});
                 if constexpr (i == FM - 1) {
                     read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 0>{});
                     read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, 1>{});
@@ -389,7 +414,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 constexpr int t = decltype(t_)::value, kk = t / (FM * FN), i = t % (FM * FN) / FN, j = t % FN;
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j][kk], fa[i][kk], acc[i][j], kFmtB, kFmtA, kSel1 * kk,
                                                                              (int)scl_b[j], kSel1 * kk, (int)scl_a[i]);
-                issue_code(st3, slot_, t_);
+                issue_next(t_);
                 if constexpr (i == FM - 1) read_frag(Next{}, IsB{}, std::integral_constant<int, j>{}, std::integral_constant<int, kk>{});
                 if constexpr (j == FN - 1) read_frag(Next{}, IsA{}, std::integral_constant<int, i>{}, std::integral_constant<int, kk>{});
                 if constexpr (kFast && t == 2 * FM * FN - 1) read_scales_fast(s + 1);
@@ -400,10 +425,18 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
 
     // ---- prologue: three stages of loads in flight, the fragments of stage 0 into registers ----
     if constexpr (kFast) issue_group(0, std::integral_constant<int, 0>{});
-    issue(0, std::integral_constant<int, 0>{});
-    issue(1, std::integral_constant<int, 1>{});
-    issue(2, std::integral_constant<int, 2>{});
-    __builtin_amdgcn_s_waitcnt(wait_imm(2 * S::kLoads));
+    if constexpr (kSix) {  // the three planes of group 0
+        static_for<kF8Slots>([&](auto L_) {
+            static_for<kCodeDma>([&](auto i_) { issue_code(decltype(L_)::value * 128, L_, i_); });
+        });
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(wait_imm(0));
+    } else {
+        issue(0, std::integral_constant<int, 0>{});
+        issue(1, std::integral_constant<int, 1>{});
+        issue(2, std::integral_constant<int, 2>{});
+        __builtin_amdgcn_s_waitcnt(wait_imm(2 * S::kLoads));
+    }
     if constexpr (kFast && kMbs) {
         convert_sigma_fast(0, std::integral_constant<int, 0>{});
         __builtin_amdgcn_s_waitcnt(kWaitLds);
