@@ -49,7 +49,7 @@ struct F8Shape {
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32, kRows = TM + TN;
     static constexpr int kCodeDma = kRows / 8 / NW;                     // per wavefront and stage: 8 rows x 128 B per load
     static constexpr int kRegLoads = kFast ? 0 : FM + FN + 2;           // general form: E8M0 dwords and MBS words per lane and stage
-    static constexpr int kLoads = kCodeDma + kRegLoads;
+    static constexpr int kLoads = kCodeDma + kRegLoads;                 // (the general form without MBS loads no words: two fewer)
     static constexpr int kGroup = 4;                                    // fast form: stages per 16-byte piece of E8M0 bytes
     static constexpr int kStageA = TM * kF8RowStage, kStageB = TN * kF8RowStage, kStage = kStageA + kStageB;
     static constexpr int kBaseB = 0, kBaseA = kF8Slots * kStageB;       // the ring slots of B, then those of A
@@ -76,6 +76,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     constexpr bool kSix = kFmtA >= 2;
     static_assert(kSix == (kFmtB >= 2) && (!kSix || kFast), "6-bit operands: both, and the fast form only");
     constexpr int kRowStage = kSix ? 96 : kF8RowStage;  // code bytes per row and stage
+    // loads a wavefront makes per stage: what the stage's wait counts (a count that assumed more would let the
+    // youngest loads of the stage it is about to read stay in flight)
+    constexpr int kLoads = S::kLoads - (kFast || kMbs ? 0 : 2);
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles,
@@ -178,8 +181,10 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 const int voff = scale_off_b0 + decltype(j_)::value * 32 * scale_bytes;
                 pref[slot].sb[decltype(j_)::value] = __builtin_amdgcn_raw_buffer_load_b32(b_scales, voff, st * 4, 0);
             });
-            pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
-            pref[slot].mb = __builtin_amdgcn_raw_buffer_load_b8(b_mbs, m8_off_b, st, 0);
+            if constexpr (kMbs) {
+                pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
+                pref[slot].mb = __builtin_amdgcn_raw_buffer_load_b8(b_mbs, m8_off_b, st, 0);
+            }
         }
     };
     // All loads of stage s at once (prologue).  The stage's waits count loads: the empty asm keeps the compiler from
@@ -243,7 +248,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // Operands of one macro block in registers.  They are refilled in place: a fragment takes the next stage's
     // data right after the last matrix instruction that reads it has been issued.
     v8i fa[FM][2], fb[FN][2];
-    // (slot_: the ring slot; for 6-bit operands the stage's place in its group)
+    // (slot_: the ring slot; for 6-bit operands the stage's place in its group.  The 8-byte reads use a plain vector
+    // type: with HIP's uint2 the compiler puts a wait for every outstanding direct-to-LDS load before each.)
+    typedef int v2i __attribute__((ext_vector_type(2)));
     auto read_frag = [&](auto slot_, auto is_a_, auto idx_, auto kk_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value, idx = decltype(idx_)::value, kk = decltype(kk_)::value;
         constexpr bool is_a = decltype(is_a_)::value;
@@ -253,12 +260,12 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             constexpr int row0 = idx * 32 * kF8RowStage;
             if constexpr (kk == 0) {
                 const v4i p0 = *reinterpret_cast<const v4i*>(smem + at[0] + row0);
-                const uint2 p1 = *reinterpret_cast<const uint2*>(smem + at[1] + row0);
-                v = v8i{p0.x, p0.y, p0.z, p0.w, (int)p1.x, (int)p1.y, 0, 0};
+                const v2i p1 = *reinterpret_cast<const v2i*>(smem + at[1] + row0);
+                v = v8i{p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, 0, 0};
             } else {
-                const uint2 p0 = *reinterpret_cast<const uint2*>(smem + at[1] + row0 + 8);
+                const v2i p0 = *reinterpret_cast<const v2i*>(smem + at[1] + row0 + 8);
                 const v4i p1 = *reinterpret_cast<const v4i*>(smem + at[2] + row0);
-                v = v8i{(int)p0.x, (int)p0.y, p1.x, p1.y, p1.z, p1.w, 0, 0};
+                v = v8i{p0.x, p0.y, p1.x, p1.y, p1.z, p1.w, 0, 0};
             }
         } else {
             constexpr int off = (is_a ? slot * S::kStageA : slot * S::kStageB) + idx * 32 * kF8RowStage;
@@ -313,7 +320,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         // earlier; since then came one stage's plane (six loads) or, before the group's second stage, the group
         // loads (of which the second may still fly).
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(wait_imm(kSix ? (p == 1 ? 1 : kCodeDma) : S::kLoads));
+        __builtin_amdgcn_s_waitcnt(wait_imm(kSix ? (p == 1 ? 1 : kCodeDma) : kLoads));
         bare_barrier();
         if constexpr (kFast) {
             // (t: the stage's place in the turn of the loop, 3 groups of 4 stages)
@@ -435,7 +442,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         issue(0, std::integral_constant<int, 0>{});
         issue(1, std::integral_constant<int, 1>{});
         issue(2, std::integral_constant<int, 2>{});
-        __builtin_amdgcn_s_waitcnt(wait_imm(2 * S::kLoads));
+        __builtin_amdgcn_s_waitcnt(wait_imm(2 * kLoads));
     }
     if constexpr (kFast && kMbs) {
         convert_sigma_fast(0, std::integral_constant<int, 0>{});
