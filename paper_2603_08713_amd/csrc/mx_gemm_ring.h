@@ -298,7 +298,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             uint32_t v;
             const uint8_t* grp_base = smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup;
             if constexpr (S::kBytes) {
-                const uint2 two = *reinterpret_cast<const uint2*>(grp_base + (s % kRingGroup) * 16 + lane_scale + row0 * 64);
+                // (a plain vector type: before a read through HIP's uint2 the compiler waits for every
+                // outstanding direct-to-LDS load)
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 two = *reinterpret_cast<const u32x2*>(grp_base + (s % kRingGroup) * 16 + lane_scale + row0 * 64);
                 v = (two.x & 0xFFu) | ((two.y & 0xFFu) << 8);
             } else if constexpr (S::kGen) {
                 v = *(lds_half_ptr_t)(grp_base + (s % kRingGroup) * 8 + lane_scale + row0 * 32);
