@@ -227,12 +227,10 @@ def mxfp8_extras(mx, torch, xa, xw, cs, flops, args, elem="e4m3"):
                                                               out=cs[i % len(cs)]), n)
     ms_qw = time_loop(torch, lambda i: mx.mx_quantize_elem(xw[i % len(xw)], elem, "oas", True, *qw[i % len(qw)]), n)
     bytes_per_elt = 2 + (0.75 if six else 1) + 1 / 32 + 1 / 128
-    ms_d = None
-    if not six:  # (no dequantizer for the 6-bit formats)
-        deq = torch.empty(tuple(xw[0].shape), dtype=torch.bfloat16, device=xw[0].device)
-        ms_d = time_loop(torch, lambda i: mx.mx_dequantize_elem(elem, *qw[i % len(qw)], "bf16", out=deq), n)
+    deq = torch.empty(tuple(xw[0].shape), dtype=torch.bfloat16, device=xw[0].device)
+    ms_d = time_loop(torch, lambda i: mx.mx_dequantize_elem(elem, *qw[i % len(qw)], "bf16", out=deq), n)
     res = {"step_tflops": round(flops / (ms_step * 1e-3) / 1e12, 1), "ms_per_step": round(ms_step, 4),
-           "dequantize_W_gbps": None if ms_d is None else round(xw[0].numel() * bytes_per_elt / (ms_d * 1e-3) / 1e9, 1),
+           "dequantize_W_gbps": round(xw[0].numel() * bytes_per_elt / (ms_d * 1e-3) / 1e9, 1),
            "gemm_mbs_tflops": round(flops / (ms_mbs * 1e-3) / 1e12, 1), "gemm_plain_tflops": round(flops / (ms_plain * 1e-3) / 1e12, 1),
            "quantize_W_gbps": round(xw[0].numel() * bytes_per_elt / (ms_qw * 1e-3) / 1e9, 1),
            "peak_context": ("published dense FP6 peak 10.1 PFLOP/s" if six else "published dense FP8 peak 5.0 PFLOP/s") + "; the paper has no figure for this format"}

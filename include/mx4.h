@@ -175,10 +175,10 @@ typedef enum {
 int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                      int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
-/* mx_dequantize for an 8-bit element format: out[r, k] = value(code) * 2^(E-127) / F, F = 1 without MBS words
- * (Sec. 4.3.1).  The fp32 result is the quotient evaluated in fp64 and rounded once more; the bf16 result is that
- * fp32 value rounded to nearest even; a block with E = 255 gives NaN.  Alignment: codes 8 bytes, out its element
- * size; ldo >= K in elements.  8-bit formats only (the 6-bit ones return MX_EUNSUPPORTED). */
+/* mx_dequantize for an 8-bit or 6-bit element format: out[r, k] = value(code) * 2^(E-127) / F, F = 1 without MBS
+ * words (Sec. 4.3.1).  The fp32 result is the quotient evaluated in fp64 and rounded once more; the bf16 result is
+ * that fp32 value rounded to nearest even; a block with E = 255 gives NaN.  Codes in the layout mx_quantize_elem
+ * writes (6-bit: packed, [rows, 3K/4]).  Alignment: codes 8 bytes, out its element size; ldo >= K in elements. */
 int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scales, const uint8_t* mbs_or_null,
                        int64_t rows, int64_t K, mx_dtype_t out_dtype, void* out, int64_t ldo, void* stream);
 

@@ -286,9 +286,12 @@ def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scale
 
 
 def mx_dequantize_elem(elem, codes, scales, mbs=None, out_dtype="f32", out=None):
-    """Dequantize codes of an 8-bit MX element format (one per byte) to fp32 or bf16."""
+    """Dequantize codes of an 8-bit (one per byte) or 6-bit (packed) MX element format to fp32 or bf16.  K is taken
+    from the scale array."""
     torch = _torch()
-    rows, K = codes.shape
+    rows, K = codes.shape[0], scales.shape[1] * 32
+    if codes.shape[1] != elem_code_bytes(elem, K):
+        raise ValueError("the code array does not have the row length of its format")
     code, dt = _out_dtype(out_dtype)
     if out is None:
         out = torch.empty((rows, K), dtype=dt, device=codes.device)

@@ -1,5 +1,5 @@
-// Dequantizer for the 8-bit MX element formats: x_hat = value(code) * 2^(E-127) / F  (Sec. 4.3.1, with the
-// element formats of the OCP MX specification).  The fp32 result is defined through fp64: value * 2^(E-127) is
+// Dequantizer for the 8-bit and 6-bit MX element formats: x_hat = value(code) * 2^(E-127) / F  (Sec. 4.3.1, with
+// the element formats of the OCP MX specification; 6-bit codes packed, 8 codes in 6 bytes).  The fp32 result is defined through fp64: value * 2^(E-127) is
 // exact, the quotient is rounded at 53 bits and once more to fp32; the bf16 result is that fp32 value rounded to
 // nearest even.  A block whose scale byte is 255 (non-finite input) gives NaN.  Where every intermediate is a
 // normal fp32 number (scale byte in [24, 230]) one IEEE fp32 division gives the same bits - checked for every
@@ -7,7 +7,8 @@
 // rounding; other scale bytes take the fp64 route element by element.
 //
 // A lane expands two runs of 8 codes, 512 apart; a wavefront 1024 consecutive elements of a row, so that every
-// load and store instruction of the wavefront covers one contiguous piece of the row.
+// load and store instruction of the wavefront covers one contiguous piece of the row.  (8 codes of a 6-bit format
+// are 6 bytes, 2-byte aligned: three 16-bit loads.)
 #include "mx_common.h"
 
 namespace mx {
@@ -19,15 +20,30 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDq8Threads = 256;
 constexpr int kDq8Chunk = kWave * 16;
 
-// Value of an FP8 code as fp32 (exact).  E4M3: S.EEEE.MMM, bias 7; E5M2: S.EEEEE.MM, bias 15; subnormals m * 2^(1 -
-// bias - mbits).  The codes past the largest finite one are not produced by the quantizer.
+// Value of a code as fp32 (exact).  E4M3: S.EEEE.MMM, bias 7; E5M2: S.EEEEE.MM, bias 15; E2M3: S.EE.MMM, bias 1;
+// E3M2: S.EEE.MM, bias 3; subnormals m * 2^(1 - bias - mbits).  The 8-bit codes past the largest finite one are
+// not produced by the quantizer; every 6-bit code is a number.
 template <int kElem>
 __device__ __forceinline__ float fp8_value(uint32_t code) {
-    constexpr int kMbits = kElem == MX_ELEM_E4M3 ? 3 : 2, kBias = kElem == MX_ELEM_E4M3 ? 7 : 15;
-    const uint32_t e = (code & 0x7Fu) >> kMbits, m = code & ((1u << kMbits) - 1u);
+    constexpr int kBits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E5M2 ? 8 : 6;
+    constexpr int kMbits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E2M3 ? 3 : 2;
+    constexpr int kBias = kElem == MX_ELEM_E4M3 ? 7 : kElem == MX_ELEM_E5M2 ? 15 : kElem == MX_ELEM_E2M3 ? 1 : 3;
+    const uint32_t mag = code & ((1u << (kBits - 1)) - 1u);
+    const uint32_t e = mag >> kMbits, m = mag & ((1u << kMbits) - 1u);
     const uint32_t normal = ((e + 127u - kBias) << 23) | (m << (23 - kMbits));
     const float sub = (float)m * __uint_as_float((uint32_t)(127 + 1 - kBias - kMbits) << 23);
-    return __uint_as_float(__float_as_uint(e ? __uint_as_float(normal) : sub) | ((code & 0x80u) << 24));
+    return __uint_as_float(__float_as_uint(e ? __uint_as_float(normal) : sub) | (((code >> (kBits - 1)) & 1u) << 31));
+}
+
+// code j of a lane's run of 8: a byte of the 64 bits, or 6 bits of the 48
+template <int kElem>
+__device__ __forceinline__ uint32_t run_code(uint2 w, int j) {
+    if constexpr (kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E5M2) {
+        return ((j < 4 ? w.x : w.y) >> (8 * (j & 3))) & 0xFFu;
+    } else {
+        const uint64_t all = ((uint64_t)w.y << 32) | w.x;
+        return (uint32_t)(all >> (6 * j)) & 0x3Fu;
+    }
 }
 
 struct Dequant8Args {
@@ -40,6 +56,8 @@ struct Dequant8Args {
 
 template <int kElem, bool kBf16>
 __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q) {
+    constexpr bool kSix = kElem == MX_ELEM_E2M3 || kElem == MX_ELEM_E3M2;
+    const int64_t row_bytes = kSix ? q.K / 4 * 3 : q.K;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kDq8Threads / kWave) + (threadIdx.x >> 6));
     const uint32_t nwaves = gridDim.x * (kDq8Threads / kWave);
@@ -52,7 +70,12 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
             const uint32_t col = col0 + u * 512;
             cw[u] = make_uint2(0, 0); E[u] = 127; m8[u] = 0;
             if (col < q.K) {
-                cw[u] = *reinterpret_cast<const uint2*>(q.codes + (int64_t)row * q.K + col);
+                if constexpr (kSix) {
+                    const uint16_t* p = reinterpret_cast<const uint16_t*>(q.codes + (int64_t)row * row_bytes + (col >> 3) * 6);
+                    cw[u] = make_uint2((uint32_t)p[0] | ((uint32_t)p[1] << 16), p[2]);
+                } else {
+                    cw[u] = *reinterpret_cast<const uint2*>(q.codes + (int64_t)row * row_bytes + col);
+                }
                 E[u] = q.scales[(int64_t)row * (q.K >> 5) + (col >> 5)];
                 if (q.mbs) m8[u] = q.mbs[(int64_t)row * q.nmac + (col >> 7)];
             }
@@ -67,7 +90,7 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
                 const float scale = __uint_as_float(E[u] << 23);               // 2^(E-127)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
+                    const uint32_t code = run_code<kElem>(cw[u], j);
                     v[j] = (fp8_value<kElem>(code) * scale) / F;  // exact product, IEEE division (m8 = 0: exact)
                 }
             } else {
@@ -75,7 +98,7 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
                 const double scale = __longlong_as_double((long long)(E[u] + 896u) << 52);  // 2^(E-127)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t code = ((j < 4 ? cw[u].x : cw[u].y) >> (8 * (j & 3))) & 0xFFu;
+                    const uint32_t code = run_code<kElem>(cw[u], j);
                     double y = (double)fp8_value<kElem>(code) * scale;
                     if (q.mbs) y = y / F;
                     v[j] = E[u] == 255u ? __uint_as_float(0x7FC00000u) : (float)y;
@@ -118,7 +141,6 @@ extern "C" int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const ui
     if (rows == 0 || K == 0) return MX_OK;
     if (!codes || !scales || !out) return MX_ENULL;
     if (!aligned(codes, 8) || !aligned(out, out_dtype == MX_OUT_F32 ? 4 : 2)) return MX_EALIGN;
-    if (elem != MX_ELEM_E4M3 && elem != MX_ELEM_E5M2) return MX_EUNSUPPORTED;  // the 6-bit formats
     if (int st = check_device()) return st;
     Dequant8Args q;
     q.codes = codes; q.scales = scales; q.mbs = mbs_or_null;
@@ -134,10 +156,24 @@ extern "C" int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const ui
     if (blocks > (int64_t)1 << 22) blocks = (int64_t)1 << 22;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)blocks), block(kDq8Threads);
-    const bool e4 = elem == MX_ELEM_E4M3, bf = out_dtype == MX_OUT_BF16;
-    if (e4 && bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, true>), grid, block, 0, s, q);
-    else if (e4) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, false>), grid, block, 0, s, q);
-    else if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, true>), grid, block, 0, s, q);
-    else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, false>), grid, block, 0, s, q);
+    const bool bf = out_dtype == MX_OUT_BF16;
+    switch (elem) {
+    case MX_ELEM_E4M3:
+        if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E4M3, false>), grid, block, 0, s, q);
+        break;
+    case MX_ELEM_E5M2:
+        if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E5M2, false>), grid, block, 0, s, q);
+        break;
+    case MX_ELEM_E2M3:
+        if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E2M3, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E2M3, false>), grid, block, 0, s, q);
+        break;
+    default:
+        if (bf) hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E3M2, true>), grid, block, 0, s, q);
+        else hipLaunchKernelGGL((dequantize8_kernel<MX_ELEM_E3M2, false>), grid, block, 0, s, q);
+        break;
+    }
     return launch_status();
 }

@@ -153,7 +153,8 @@ def test_elem_argument_errors(lib):
     assert d(E4, A16, A16, None, 4, 64, 5, A16, 64, None) == -1     # bad output type
     assert d(E4, None, A16, None, 4, 64, 0, A16, 64, None) == -2
     assert d(E5, A16 + 4, A16, None, 4, 64, 0, A16, 64, None) == -3
-    assert d(E23, A16, A16, None, 4, 64, 0, A16, 64, None) == -4
+    assert d(E23, A16, A16, None, 4, 48, 0, A16, 48, None) == -1    # the 6-bit formats: the same checks
+    assert d(E23, A16, A16, None, 0, 64, 0, A16, 64, None) == 0
     assert d(E4, A16, A16, None, 0, 64, 0, A16, 64, None) == 0
     g = lib.mx_gemm_mbs_elem
     assert g(E4, A16, A16, None, E4, A16, A16, None, 8, 8, 48, 0, A16, 8, None) == -1
@@ -168,9 +169,9 @@ def test_elem_argument_errors(lib):
 
 
 def test_fp8_dequantizer_shortcut_is_exact():
-    """The MXFP8 dequantizer divides in fp32 where every intermediate is a normal number, although its result is
-    defined through fp64 (quotient rounded at 53 bits, then to fp32).  The two agree for every pair of FP8 code
-    value and MBS word; a power-of-two block scale commutes with the rounding, so this covers every scale byte of
+    """The MXFP8 / MXFP6 dequantizer divides in fp32 where every intermediate is a normal number, although its
+    result is defined through fp64 (quotient rounded at 53 bits, then to fp32).  The two agree for every pair of
+    code value (FP8 and FP6 formats) and MBS word; a power-of-two block scale commutes with the rounding, so this covers every scale byte of
     the shortcut's range."""
     import numpy as np
 
@@ -181,7 +182,7 @@ def test_fp8_dequantizer_shortcut_is_exact():
             out.add(m * 2.0 ** (1 - bias - mbits) if e == 0 else (1 + m / (1 << mbits)) * 2.0 ** (e - bias))
         return sorted(out)
 
-    for vals in (values(4, 3, 7, 0x7E), values(5, 2, 15, 0x7B)):
+    for vals in (values(4, 3, 7, 0x7E), values(5, 2, 15, 0x7B), values(2, 3, 1, 0x1F), values(3, 2, 3, 0x1F)):
         v = np.array(vals, np.float64)[:, None]
         F = 1.0 + np.arange(256, dtype=np.float64)[None, :] / 256.0
         via64 = (v / F).astype(np.float32)

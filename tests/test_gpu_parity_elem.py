@@ -176,7 +176,7 @@ def to_bf16_bits_rne(f32: np.ndarray) -> np.ndarray:
     return r
 
 
-@pytest.mark.parametrize("elem", ELEMS)
+@pytest.mark.parametrize("elem", QUANT_ELEMS)
 def test_dequantize_elem_matches_oracle(mx, oracle, elem):
     """Quantized heavy-tailed tensors, and every code under every scale byte and MBS word: the fp32 output equals
     the oracle's fp64 value rounded to fp32, the bf16 output that fp32 value rounded to nearest even; NaN blocks."""
@@ -187,9 +187,12 @@ def test_dequantize_elem_matches_oracle(mx, oracle, elem):
     cases = [oracle.elem_quantize(elem, x, "oas", mbs=True), oracle.elem_quantize(elem, x, "ocp", mbs=False)]
     rng = np.random.default_rng(5)
     rows, K = 256, 1024
-    c = rng.integers(0, 256, (rows, K), dtype=np.uint8)
-    mag = c & 0x7F
-    c = np.where(mag > MAX_CODE[elem], (c & 0x80) | (mag & 0x3F), c).astype(np.uint8)
+    if elem in ELEMS:
+        c = rng.integers(0, 256, (rows, K), dtype=np.uint8)
+        mag = c & 0x7F
+        c = np.where(mag > MAX_CODE[elem], (c & 0x80) | (mag & 0x3F), c).astype(np.uint8)
+    else:
+        c = rng.integers(0, 64, (rows, K), dtype=np.uint8)                    # every 6-bit code is a number
     s = np.repeat(np.arange(256, dtype=np.uint8)[:, None], K // 32, 1)       # row r: scale byte r (255: NaN)
     w = rng.integers(0, 256, (rows, K // 128), dtype=np.uint8)
     w[:, 0] = 0
@@ -197,7 +200,7 @@ def test_dequantize_elem_matches_oracle(mx, oracle, elem):
     for codes, scales, words in cases:
         with np.errstate(over="ignore"):  # the largest scale bytes overflow fp32 on both sides
             want = oracle.elem_dequantize(elem, codes, scales, words).astype(np.float32)
-        dc, ds, dw = dev_u8(codes), dev_u8(scales), dev_u8(words)
+        dc, ds, dw = dev_u8(canonical_codes(elem, codes)), dev_u8(scales), dev_u8(words)
         got32 = host(mx.mx_dequantize_elem(elem, dc, ds, dw, "f32"))
         got16 = host(mx.mx_dequantize_elem(elem, dc, ds, dw, "bf16").view(torch.int16)).view(np.uint16)
         nan = np.isnan(want)
@@ -208,8 +211,9 @@ def test_dequantize_elem_matches_oracle(mx, oracle, elem):
     # strided output and an odd column offset (element stores)
     codes, scales, words = cases[0]
     big = torch.zeros((37, 2880 + 9), dtype=torch.float32, device="cuda")
-    mx.mx_dequantize_elem(elem, dev_u8(codes), dev_u8(scales), dev_u8(words), "f32", out=big[:, 1:2881])
-    ref = mx.mx_dequantize_elem(elem, dev_u8(codes), dev_u8(scales), dev_u8(words), "f32")
+    packed = dev_u8(canonical_codes(elem, codes))
+    mx.mx_dequantize_elem(elem, packed, dev_u8(scales), dev_u8(words), "f32", out=big[:, 1:2881])
+    ref = mx.mx_dequantize_elem(elem, packed, dev_u8(scales), dev_u8(words), "f32")
     ok = ~torch.isnan(ref)
     assert torch.equal(big[:, 1:2881][ok], ref[ok]) and float(big[:, 0].abs().max()) == 0.0 and float(big[:, 2881:].abs().max()) == 0.0
 
