@@ -12,8 +12,8 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 RULES = ("ocp", "floor", "oas")
-ELEMS = ("e4m3", "e5m2")          # GEMM and dequantizer
-QUANT_ELEMS = ELEMS + ("e2m3", "e3m2")  # quantizer
+ELEMS = ("e4m3", "e5m2")          # the 8-bit formats (one code per byte)
+QUANT_ELEMS = ELEMS + ("e2m3", "e3m2")  # all four (6-bit codes packed)
 MAX_CODE = {"e4m3": 0x7E, "e5m2": 0x7B}
 
 
