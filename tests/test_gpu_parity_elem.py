@@ -356,6 +356,28 @@ def test_gemm_elem_general_form_equals_fast_form(mx, oracle):
             assert torch.equal(fast, general), (M, N, K, words)
 
 
+def test_gemm_elem_general_form_at_full_size_repeats_bit_for_bit(mx):
+    """The general form's stage waits count the loads a wavefront has issued; a count that does not match the
+    loads made (without MBS words two fewer) lets a stage read codes that have not landed, now and then.  At the
+    benchmark's shape, every tile in flight, repeated launches of either variant give the fast form's bits."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 4096, 14336, 4096
+    a_bits, w_bits = synth.llama8b_ffn_up(M, N, K)
+    a = mx.mx_quantize_elem(dev_bf16(a_bits), "e4m3", "oas")
+    b = mx.mx_quantize_elem(dev_bf16(w_bits), "e4m3", "oas")
+    lib = mx.load_library()
+    for words in (True, False):
+        args = ("e4m3", a[0], a[1], a[2] if words else None, "e4m3", b[0], b[1], b[2] if words else None, "bf16")
+        fast = mx.mx_gemm_mbs_elem(*args)
+        lib.mx_internal_set_gemm_elem_general(1)
+        try:
+            for rep in range(5):
+                assert torch.equal(mx.mx_gemm_mbs_elem(*args), fast), (words, rep)
+        finally:
+            lib.mx_internal_set_gemm_elem_general(0)
+
+
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
     """Products that need no alignment (codes for 0, +-0.5, +-1, +-2, 4) add up exactly: any misplaced element,
     scale byte or sigma shows as an integer-sized error."""
