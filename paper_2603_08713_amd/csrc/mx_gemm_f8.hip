@@ -248,9 +248,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // Operands of one macro block in registers.  They are refilled in place: a fragment takes the next stage's
     // data right after the last matrix instruction that reads it has been issued.
     v8i fa[FM][2], fb[FN][2];
-    // (slot_: the ring slot; for 6-bit operands the stage's place in its group.  The 8-byte reads use a plain vector
-    // type: with HIP's uint2 the compiler puts a wait for every outstanding direct-to-LDS load before each.)
-    typedef int v2i __attribute__((ext_vector_type(2)));
+    // (slot_: the ring slot; for 6-bit operands the stage's place in its group.  LDS reads go through plain vector
+    // types: before a read through one of HIP's vector structs, uint2 say, the compiler puts a wait for every
+    // outstanding direct-to-LDS load.)
     auto read_frag = [&](auto slot_, auto is_a_, auto idx_, auto kk_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value, idx = decltype(idx_)::value, kk = decltype(kk_)::value;
         constexpr bool is_a = decltype(is_a_)::value;
@@ -258,14 +258,19 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         if constexpr (kSix) {
             const int* at = is_a ? six_a[slot] : six_b[slot];
             constexpr int row0 = idx * 32 * kF8RowStage;
+            // The middle piece is read once, whole, into registers 4 .. 7 of instruction 0's operand (the matrix
+            // instruction takes six registers of a 6-bit operand; the last two ride along) and its second half is
+            // copied into registers 0 and 1 of instruction 1's operand by patch_frags(), once the read has
+            // landed: three 16-byte reads per fragment instead of two and two 8-byte reads, which the LDS serves
+            // no faster than 16-byte ones (two lanes of a 32-lane pass share a bank pair).
             if constexpr (kk == 0) {
                 const v4i p0 = *reinterpret_cast<const v4i*>(smem + at[0] + row0);
-                const v2i p1 = *reinterpret_cast<const v2i*>(smem + at[1] + row0);
-                v = v8i{p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, 0, 0};
+                const v4i p1 = *reinterpret_cast<const v4i*>(smem + at[1] + row0);
+                v = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
             } else {
-                const v2i p0 = *reinterpret_cast<const v2i*>(smem + at[1] + row0 + 8);
-                const v4i p1 = *reinterpret_cast<const v4i*>(smem + at[2] + row0);
-                v = v8i{p0.x, p0.y, p1.x, p1.y, p1.z, p1.w, 0, 0};
+                const v8i old = is_a ? fa[idx][1] : fb[idx][1];
+                const v4i p2 = *reinterpret_cast<const v4i*>(smem + at[2] + row0);
+                v = v8i{old[0], old[1], p2.x, p2.y, p2.z, p2.w, old[6], old[7]};
             }
         } else {
             constexpr int off = (is_a ? slot * S::kStageA : slot * S::kStageB) + idx * 32 * kF8RowStage;
@@ -281,6 +286,15 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     };
     using IsA = std::integral_constant<bool, true>;
     using IsB = std::integral_constant<bool, false>;
+    // 6-bit: second half of every fragment's middle piece into its place (after the wait for the fragment reads)
+    auto patch_frags = [&]() __attribute__((always_inline)) {
+        if constexpr (kSix) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) { fa[i][1][0] = fa[i][0][6]; fa[i][1][1] = fa[i][0][7]; }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) { fb[j][1][0] = fb[j][0][6]; fb[j][1][1] = fb[j][0][7]; }
+        }
+    };
 
     // E8M0 operands of a stage.  8-bit: lane half h supplies the byte of block 2 kk + h, i.e. bytes h and 2 + h of the
     // row's four, so the dword goes in shifted right by 8 h and op_sel picks byte 0 or 2.  6-bit: the lane's own
@@ -322,6 +336,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_imm(kSix ? (p == 1 ? 1 : kCodeDma) : kLoads));
         bare_barrier();
+        patch_frags();
         if constexpr (kFast) {
             // (t: the stage's place in the turn of the loop, 3 groups of 4 stages)
             constexpr int t = decltype(phase_)::value;
@@ -453,6 +468,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         static_for<FN>([&](auto j_) { read_frag(std::integral_constant<int, 0>{}, IsB{}, j_, kk_); });
         static_for<FM>([&](auto i_) { read_frag(std::integral_constant<int, 0>{}, IsA{}, i_, kk_); });
     });
+    patch_frags();
     if constexpr (kFast) read_scales_fast(0);
     // The loop body is a whole number of turns of the ring and, in the fast form, of groups, so that ring slot and
     // place in the group are compile-time constants; what is left of K follows after the loop, as the first
