@@ -1,5 +1,6 @@
-// Block-scaled GEMM  C = A * B^T  with the Macro Block Scaling correction for operands in the 8-bit MX element
-// formats (E4M3, E5M2; Sec. 1, footnote: the methods carry over to MXFP8), on v_mfma_scale_f32_32x32x64_f8f6f4.
+// Block-scaled GEMM  C = A * B^T  with the Macro Block Scaling correction for operands in the 8-bit and 6-bit MX
+// element formats (E4M3, E5M2, E2M3, E3M2; Sec. 1, footnote: the methods carry over to MXFP6 and MXFP8), on
+// v_mfma_scale_f32_32x32x64_f8f6f4.
 //
 // The sum and the correction are those of the MXFP4 kernels (Sec. 4.3.2, App. E): per macro block of 128
 // K-elements two matrix instructions start from a zero accumulator, and the vector ALUs fold their result in as
@@ -33,6 +34,12 @@
 // sigma = 1 / (1 + m8 / 256) during stage s, into one of two LDS tables that the barrier publishes.  The general
 // form (any K % 128 == 0) fetches one dword of E8M0 bytes and one MBS word per lane and stage into registers and
 // keeps a sigma table per wavefront.
+//
+// 6-bit operands (E2M3, E3M2; codes packed 32 to 24 bytes) run the fast form of the same template.  As for FP4, a
+// lane half holds one whole block per instruction (instruction kk: block kk + 2 h) with the lane's own E8M0
+// byte.  A stage is 96 bytes of a row; so that no 128-byte line of memory is fetched twice, the ring slots hold
+// planes instead of stages: slot L = bytes 128 L .. + 127 of the 384 that a group of four stages takes of each
+// row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.
 #include "mx_gemm_shared.h"
 
 namespace mx {
