@@ -1,7 +1,12 @@
 // Dequantizer: x_hat = value(code) * 2^(E-127) / F  (Sec. 4.3.1).  The fp32 result is correctly rounded (value
 // * 2^(E-127) is exact, the division by F is IEEE), the bf16 result is that fp32 value rounded to nearest even.
 //
-// A lane expands two runs of 8 codes, a wavefront 1024 consecutive elements of a row.
+// A lane expands four runs of 8 codes, 512 elements apart; a wavefront 2048 consecutive elements of a row, so that
+// every code load and every store of the wavefront covers one contiguous piece of the row.  The 64 E8M0 bytes
+// and 16 MBS words of those elements are fetched once, one byte per lane, and handed to the lanes that need
+// them through the LDS crossbar (ds_bpermute): a load instruction occupies the texture-address unit for its 64
+// lanes however few bytes each lane asks for, and fetching a byte of each kind per lane and run made that unit,
+// not the memory, the limit.
 // An E2M1 magnitude is 2^k or 1.5 * 2^k, and scaling by a power of two commutes with rounding, so a run needs
 // only two divisions, 1/F and 1.5/F (F is shared by its 8 elements), and every element is one of the two
 // quotients with k + E - 127 added to its exponent field.  That holds while the result stays a normal number:
@@ -15,7 +20,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int kLaneElems = 16, kChunk = kWave * kLaneElems;
+constexpr int kRuns = 4, kLaneElems = 8 * kRuns, kChunk = kWave * kLaneElems;
 
 // fp32 pattern of an E2M1 magnitude index: {0, .5, 1, 1.5, 2, 3, 4, 6}.
 __device__ __forceinline__ float e2m1_value(uint32_t code) {
@@ -48,27 +53,31 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantArgs q) {
     const uint32_t nwaves = gridDim.x * (kThreads / kWave);
     for (uint32_t c = wave; c < q.total_chunks; c += nwaves) {
         const uint32_t row = c / q.chunks_per_row, col0 = (c - row * q.chunks_per_row) * kChunk + lane * 8;
-        // two runs of 8 elements, 512 apart: every load and store instruction of the wavefront covers one
-        // contiguous piece of the row
-        uint32_t cw[2], E[2], m8[2];
+        // lane l fetches E8M0 byte l and (l < 16) MBS word l of the chunk; run u of lane l wants byte 16 u + l / 4
+        // and word 4 u + l / 16
+        const uint32_t chunk0 = col0 - lane * 8;
+        uint32_t my_e = 127, my_m8 = 0;
+        if (chunk0 + lane * 32 < q.K) my_e = q.scales[(int64_t)row * (q.K >> 5) + (chunk0 >> 5) + lane];
+        if (q.mbs && lane < 16 && chunk0 + lane * 128 < q.K) my_m8 = q.mbs[(int64_t)row * q.nmac + (chunk0 >> 7) + lane];
+        uint32_t cw[kRuns], E[kRuns], m8[kRuns];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kRuns; ++u) {
             const uint32_t col = col0 + u * 512;
-            cw[u] = 0; E[u] = 127; m8[u] = 0;
-            if (col < q.K) {
-                cw[u] = *reinterpret_cast<const uint32_t*>(q.codes + (int64_t)row * (q.K >> 1) + (col >> 1));
-                E[u] = q.scales[(int64_t)row * (q.K >> 5) + (col >> 5)];
-                if (q.mbs) m8[u] = q.mbs[(int64_t)row * q.nmac + (col >> 7)];
-            }
+            cw[u] = 0;
+            if (col < q.K) cw[u] = *reinterpret_cast<const uint32_t*>(q.codes + (int64_t)row * (q.K >> 1) + (col >> 1));
+            E[u] = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((16 * u + (lane >> 2)) * 4), (int)my_e);
+            m8[u] = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((4 * u + (lane >> 4)) * 4), (int)my_m8);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kRuns; ++u) {
             const uint32_t col = col0 + u * 512;
             if (col >= q.K) continue;  // no cross-lane operations below
             const float F = __uint_as_float(0x3F800000u | (m8[u] << 15));  // 1 + m8/256
             float v[8];
             if (E[u] >= 8u && E[u] <= 247u) {
-                const uint32_t r1 = __float_as_uint(1.0f / F), r3 = __float_as_uint(1.5f / F);  // m8 = 0: exactly 1 and 1.5
+                uint32_t r1 = __float_as_uint(1.0f / F), r3 = __float_as_uint(1.5f / F);  // m8 = 0: exactly 1 and 1.5
+                // (opaque to the compiler, which would otherwise select the numerator per element and divide 8 times)
+                asm volatile("" : "+v"(r1), "+v"(r3));
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t code = (cw[u] >> (4 * j)) & 15u, m = code & 7u;
@@ -95,8 +104,11 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantArgs q) {
             } else {
                 float* o = static_cast<float*>(q.out) + (int64_t)row * q.ldo + col;
                 if (q.vec_out) {
-                    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(o));
-                    __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<f32x4*>(o) + 1);
+                    // (ordinary stores: a lane's 32 bytes take two instructions, each of which covers only every
+                    // other 16 bytes of the wavefront's piece of the row; streamed past the caches such half-line
+                    // writes ran at less than half the rate)
+                    *reinterpret_cast<f32x4*>(o) = f32x4{v[0], v[1], v[2], v[3]};
+                    *(reinterpret_cast<f32x4*>(o) + 1) = f32x4{v[4], v[5], v[6], v[7]};
                 } else {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) o[j] = v[j];
