@@ -7,10 +7,12 @@
 // them through the LDS crossbar (ds_bpermute): a load instruction occupies the texture-address unit for its 64
 // lanes however few bytes each lane asks for, and fetching a byte of each kind per lane and run made that unit,
 // not the memory, the limit.
-// An E2M1 magnitude is 2^k or 1.5 * 2^k, and scaling by a power of two commutes with rounding, so a run needs
-// only two divisions, 1/F and 1.5/F (F is shared by its 8 elements), and every element is one of the two
-// quotients with k + E - 127 added to its exponent field.  That holds while the result stays a normal number:
-// lanes whose scale byte is outside [8, 247] (and NaN blocks) take the element-by-element route.
+// The hardware convert expands two codes at a time and applies the block scale (exact).  The division by F costs
+// one IEEE division per run of 8 (F is shared by them): with r = RN(1 / F), q = RN(t r) is corrected once by the
+// exact remainder, q' = RN(q + (t - q F) r), which is the correctly rounded quotient for every E2M1 magnitude
+// (mantissa 1 or 1.5) and every MBS word - checked with exact rationals on the host (tests/test_abi_cpu.py); a
+// power-of-two scale commutes with all of it.  That holds while every intermediate is a normal number: lanes whose
+// scale byte is outside [64, 230] (and NaN blocks) take the element-by-element route.
 #include "mx_common.h"
 
 namespace mx {
@@ -74,17 +76,25 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantArgs q) {
             if (col >= q.K) continue;  // no cross-lane operations below
             const float F = __uint_as_float(0x3F800000u | (m8[u] << 15));  // 1 + m8/256
             float v[8];
-            if (E[u] >= 8u && E[u] <= 247u) {
-                uint32_t r1 = __float_as_uint(1.0f / F), r3 = __float_as_uint(1.5f / F);  // m8 = 0: exactly 1 and 1.5
-                // (opaque to the compiler, which would otherwise select the numerator per element and divide 8 times)
-                asm volatile("" : "+v"(r1), "+v"(r3));
+            if (E[u] >= 64u && E[u] <= 230u) {
+#pragma clang fp contract(off)
+                typedef float v2f __attribute__((ext_vector_type(2)));
+                const float r = 1.0f / F;                         // IEEE division, once per run (m8 = 0: exactly 1)
+                const float scale = __uint_as_float(E[u] << 23);  // 2^(E-127)
+                auto quotient = [&](float t) __attribute__((always_inline)) {  // t / F, correctly rounded (see the header)
+                    const float q0 = t * r;
+                    const float rem = __builtin_fmaf(-q0, F, t);  // exact
+                    return __builtin_copysignf(__builtin_fmaf(rem, r, q0), t);  // (the sign of a zero)
+                };
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t code = (cw[u] >> (4 * j)) & 15u, m = code & 7u;
-                    // magnitudes: 1 -> 0.5, 2 -> 1, 3 -> 1.5, 4 -> 2, 5 -> 3, 6 -> 4, 7 -> 6
-                    const uint32_t quo = (m & 1u) && m > 1u ? r3 : r1;
-                    const uint32_t bits = quo + (((m >> 1) + E[u] - 128u) << 23);
-                    v[j] = __uint_as_float((m ? bits : 0u) | ((code & 8u) << 28));
+                for (int i = 0; i < 4; ++i) {
+                    v2f t;  // codes 2 i and 2 i + 1 (byte i of the dword) times the scale: exact
+                    if (i == 0) t = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw[u], scale, 0);
+                    if (i == 1) t = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw[u], scale, 1);
+                    if (i == 2) t = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw[u], scale, 2);
+                    if (i == 3) t = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw[u], scale, 3);
+                    v[2 * i] = quotient(t.x);
+                    v[2 * i + 1] = quotient(t.y);
                 }
             } else {
 #pragma unroll

@@ -2,9 +2,11 @@
 // the element formats of the OCP MX specification; 6-bit codes packed, 8 codes in 6 bytes).  The fp32 result is defined through fp64: value * 2^(E-127) is
 // exact, the quotient is rounded at 53 bits and once more to fp32; the bf16 result is that fp32 value rounded to
 // nearest even.  A block whose scale byte is 255 (non-finite input) gives NaN.  Where every intermediate is a
-// normal fp32 number (scale byte in [24, 230]) one IEEE fp32 division gives the same bits - checked for every
-// pair of code value and MBS word on the host (tests/test_abi_cpu.py), and a power-of-two scale commutes with
-// rounding; other scale bytes take the fp64 route element by element.
+// normal fp32 number (scale byte in [64, 230]) fp32 arithmetic gives the same bits without a division per element:
+// with r = 1 / F (one IEEE division per run of 8), q = t * r is corrected once by the exact remainder,
+// q' = fma(fma(-q, F, t), r, q), which is the correctly rounded quotient for every pair of code value and MBS
+// word - checked with exact rationals on the host (tests/test_abi_cpu.py); a power-of-two scale commutes with
+// rounding.  Other scale bytes take the fp64 route element by element.
 //
 // A lane expands two runs of 8 codes, 512 apart; a wavefront 1024 consecutive elements of a row, so that every
 // load and store instruction of the wavefront covers one contiguous piece of the row.  (8 codes of a 6-bit format
@@ -24,15 +26,27 @@ constexpr int kDq8Chunk = kWave * 16;
 // E3M2: S.EEE.MM, bias 3; subnormals m * 2^(1 - bias - mbits).  The 8-bit codes past the largest finite one are
 // not produced by the quantizer; every 6-bit code is a number.
 template <int kElem>
+struct ElemBits {
+    static constexpr int kBits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E5M2 ? 8 : 6;
+    static constexpr int kMbits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E2M3 ? 3 : 2;
+    static constexpr int kBias = kElem == MX_ELEM_E4M3 ? 7 : kElem == MX_ELEM_E5M2 ? 15 : kElem == MX_ELEM_E2M3 ? 1 : 3;
+};
+template <int kElem>
+__device__ __forceinline__ float fp8_magnitude(uint32_t code) {
+    using T = ElemBits<kElem>;
+    const uint32_t mag = code & ((1u << (T::kBits - 1)) - 1u);
+    const uint32_t e = mag >> T::kMbits, m = mag & ((1u << T::kMbits) - 1u);
+    const uint32_t normal = ((e + 127u - T::kBias) << 23) | (m << (23 - T::kMbits));
+    const float sub = (float)m * __uint_as_float((uint32_t)(127 + 1 - T::kBias - T::kMbits) << 23);
+    return e ? __uint_as_float(normal) : sub;
+}
+template <int kElem>
+__device__ __forceinline__ uint32_t fp8_sign(uint32_t code) {  // the sign as bit 31
+    return ((code >> (ElemBits<kElem>::kBits - 1)) & 1u) << 31;
+}
+template <int kElem>
 __device__ __forceinline__ float fp8_value(uint32_t code) {
-    constexpr int kBits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E5M2 ? 8 : 6;
-    constexpr int kMbits = kElem == MX_ELEM_E4M3 || kElem == MX_ELEM_E2M3 ? 3 : 2;
-    constexpr int kBias = kElem == MX_ELEM_E4M3 ? 7 : kElem == MX_ELEM_E5M2 ? 15 : kElem == MX_ELEM_E2M3 ? 1 : 3;
-    const uint32_t mag = code & ((1u << (kBits - 1)) - 1u);
-    const uint32_t e = mag >> kMbits, m = mag & ((1u << kMbits) - 1u);
-    const uint32_t normal = ((e + 127u - kBias) << 23) | (m << (23 - kMbits));
-    const float sub = (float)m * __uint_as_float((uint32_t)(127 + 1 - kBias - kMbits) << 23);
-    return __uint_as_float(__float_as_uint(e ? __uint_as_float(normal) : sub) | (((code >> (kBits - 1)) & 1u) << 31));
+    return __uint_as_float(__float_as_uint(fp8_magnitude<kElem>(code)) | fp8_sign<kElem>(code));
 }
 
 // code j of a lane's run of 8: a byte of the 64 bits, or 6 bits of the 48
@@ -85,13 +99,18 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
             const uint32_t col = col0 + u * 512;
             if (col >= q.K) continue;
             float v[8];
-            if (E[u] >= 24u && E[u] <= 230u) {
+            if (E[u] >= 64u && E[u] <= 230u) {
+#pragma clang fp contract(off)
                 const float F = __uint_as_float(0x3F800000u | (m8[u] << 15));  // 1 + m8/256
                 const float scale = __uint_as_float(E[u] << 23);               // 2^(E-127)
+                const float r = 1.0f / F;                                      // IEEE division (m8 = 0: exactly 1)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t code = run_code<kElem>(cw[u], j);
-                    v[j] = (fp8_value<kElem>(code) * scale) / F;  // exact product, IEEE division (m8 = 0: exact)
+                    const float t = fp8_magnitude<kElem>(code) * scale;        // exact
+                    const float q0 = t * r;
+                    const float rem = __builtin_fmaf(-q0, F, t);               // exact
+                    v[j] = __uint_as_float(__float_as_uint(__builtin_fmaf(rem, r, q0)) | fp8_sign<kElem>(code));
                 }
             } else {
                 const double F = 1.0 + (double)m8[u] * (1.0 / 256.0);
@@ -118,8 +137,10 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
             } else {
                 float* o = static_cast<float*>(q.out) + (int64_t)row * q.ldo + col;
                 if (q.vec_out) {
-                    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(o));
-                    __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<f32x4*>(o) + 1);
+                    // (ordinary stores: each of the two instructions covers only every other 16 bytes of the
+                    // wavefront's piece of the row, and streamed past the caches such writes ran at half the rate)
+                    *reinterpret_cast<f32x4*>(o) = f32x4{v[0], v[1], v[2], v[3]};
+                    *(reinterpret_cast<f32x4*>(o) + 1) = f32x4{v[4], v[5], v[6], v[7]};
                 } else {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) o[j] = v[j];

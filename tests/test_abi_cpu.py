@@ -169,25 +169,60 @@ def test_elem_argument_errors(lib):
 
 
 def test_fp8_dequantizer_shortcut_is_exact():
-    """The MXFP8 / MXFP6 dequantizer divides in fp32 where every intermediate is a normal number, although its
-    result is defined through fp64 (quotient rounded at 53 bits, then to fp32).  The two agree for every pair of
-    code value (FP8 and FP6 formats) and MBS word; a power-of-two block scale commutes with the rounding, so this covers every scale byte of
-    the shortcut's range."""
+    """The MXFP8 / MXFP6 dequantizer's result is defined through fp64 (quotient rounded at 53 bits, then to fp32).
+    Where every intermediate is a normal fp32 number the kernel divides once per run, r = RN(1 / F), and per element
+    computes q = RN(t r), rem = t - q F (exact, one fma), q' = RN(q + rem r).  With exact rationals: q' is the
+    correctly rounded t / F, and equals the fp64 route, for every pair of code value (FP8 and FP6 formats) and MBS
+    word; a power-of-two block scale commutes with all of it, so one binade per mantissa covers every scale byte
+    of the shortcut's range."""
+    import math
+    from fractions import Fraction
+
     import numpy as np
 
-    def values(ebits, mbits, bias, top):
+    def rn32(x):  # Fraction -> nearest fp32 (ties to even), normal range, as a Fraction
+        if x == 0:
+            return Fraction(0)
+        e = math.floor(math.log2(x))
+        while Fraction(2) ** e > x:
+            e -= 1
+        while Fraction(2) ** (e + 1) <= x:
+            e += 1
+        n = x / Fraction(2) ** (e - 23)
+        fl = n.numerator // n.denominator
+        rem = n - fl
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+            fl += 1
+        return fl * Fraction(2) ** (e - 23)
+
+    def values(mbits, bias, top):
         out = set()
         for c in range(1, top + 1):
             e, m = c >> mbits, c & ((1 << mbits) - 1)
-            out.add(m * 2.0 ** (1 - bias - mbits) if e == 0 else (1 + m / (1 << mbits)) * 2.0 ** (e - bias))
-        return sorted(out)
+            out.add(Fraction(m, 1 << mbits) * Fraction(2) ** (1 - bias) if e == 0 else (1 + Fraction(m, 1 << mbits)) * Fraction(2) ** (e - bias))
+        return out
 
-    for vals in (values(4, 3, 7, 0x7E), values(5, 2, 15, 0x7B), values(2, 3, 1, 0x1F), values(3, 2, 3, 0x1F)):
-        v = np.array(vals, np.float64)[:, None]
-        F = 1.0 + np.arange(256, dtype=np.float64)[None, :] / 256.0
-        via64 = (v / F).astype(np.float32)
-        direct = v.astype(np.float32) / F.astype(np.float32)  # IEEE fp32 division
-        assert direct.dtype == np.float32 and np.array_equal(via64, direct)
+    vals = set()
+    for fmt in ((3, 7, 0x7E), (2, 15, 0x7B), (3, 1, 0x1F), (2, 3, 0x1F)):  # E4M3, E5M2, E2M3, E3M2
+        vals |= values(*fmt)
+    mantissas = sorted({v / Fraction(2) ** math.floor(math.log2(v)) for v in vals})
+    assert mantissas == [Fraction(8 + k, 8) for k in range(8)]
+    for t in mantissas:
+        for m8 in range(256):
+            F = 1 + Fraction(m8, 256)
+            r = rn32(1 / F)
+            q0 = rn32(t * r)
+            rem = t - q0 * F
+            assert rem == 0 or rn32(abs(rem)) == abs(rem)      # the fma returns it exactly
+            q1 = q0 + rem * r
+            q1 = rn32(q1) if q1 > 0 else Fraction(0)
+            assert q1 == rn32(t / F), (t, m8)
+    # and the correctly rounded quotient is what the fp64 route gives
+    v = np.array([float(x) for x in sorted(vals)], np.float64)[:, None]
+    F = 1.0 + np.arange(256, dtype=np.float64)[None, :] / 256.0
+    via64 = (v / F).astype(np.float32)
+    direct = v.astype(np.float32) / F.astype(np.float32)  # IEEE fp32 division: correctly rounded
+    assert direct.dtype == np.float32 and np.array_equal(via64, direct)
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
