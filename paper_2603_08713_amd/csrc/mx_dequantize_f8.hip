@@ -104,13 +104,37 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
                 const float F = __uint_as_float(0x3F800000u | (m8[u] << 15));  // 1 + m8/256
                 const float scale = __uint_as_float(E[u] << 23);               // 2^(E-127)
                 const float r = 1.0f / F;                                      // IEEE division (m8 = 0: exactly 1)
+                if constexpr (kSix) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t code = run_code<kElem>(cw[u], j);
-                    const float t = fp8_magnitude<kElem>(code) * scale;        // exact
-                    const float q0 = t * r;
-                    const float rem = __builtin_fmaf(-q0, F, t);               // exact
-                    v[j] = __uint_as_float(__float_as_uint(__builtin_fmaf(rem, r, q0)) | fp8_sign<kElem>(code));
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t code = run_code<kElem>(cw[u], j);
+                        const float t = fp8_magnitude<kElem>(code) * scale;    // exact
+                        const float q0 = t * r;
+                        const float rem = __builtin_fmaf(-q0, F, t);           // exact
+                        v[j] = __uint_as_float(__float_as_uint(__builtin_fmaf(rem, r, q0)) | fp8_sign<kElem>(code));
+                    }
+                } else {
+                    // 8-bit codes: the hardware convert expands two at a time and applies the scale (exact)
+                    typedef float v2f __attribute__((ext_vector_type(2)));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t word = i < 2 ? cw[u].x : cw[u].y;
+                        v2f t;
+                        if constexpr (kElem == MX_ELEM_E4M3) {
+                            t = (i & 1) ? __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(word, scale, true)
+                                        : __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(word, scale, false);
+                        } else {
+                            t = (i & 1) ? __builtin_amdgcn_cvt_scalef32_pk_f32_bf8(word, scale, true)
+                                        : __builtin_amdgcn_cvt_scalef32_pk_f32_bf8(word, scale, false);
+                        }
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const float th = h ? t.y : t.x;
+                            const float q0 = th * r;
+                            const float rem = __builtin_fmaf(-q0, F, th);      // exact
+                            v[2 * i + h] = __builtin_copysignf(__builtin_fmaf(rem, r, q0), th);  // (the sign of a zero)
+                        }
+                    }
                 }
             } else {
                 const double F = 1.0 + (double)m8[u] * (1.0 / 256.0);
