@@ -258,6 +258,14 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // are folded in, the next fragment's values (of this or of the next stage) arrive in the other set.
     float sig_m[2][FM];
     v4f sig_n[2][4];
+    // (zeros: the first stage folds in the "last product of the stage before", which is zero times these)
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) sig_m[par][i] = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) sig_n[par][gq] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
     // This lane's 16 bytes inside a fragment's 32 rows, per instruction of the pair, with the wavefront's
     // first row of A (index 0) or of B (index 1) folded in.  The LDS read instruction adds a 16-bit constant
     // to its address register; ring slot, fragment and operand are compile-time constants, so with a second
@@ -373,7 +381,15 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // q + 1 are issued before the product of pair q is folded into the accumulators (two product register
     // sets), and the SIMD's other wavefront fills what gaps remain.
     constexpr int kPairs = FM * FN, kMfmas = kPairs * 2;
+    // The product of a stage's last pair is folded in at the start of the next stage, behind that stage's first
+    // matrix instructions: otherwise every stage would begin with the vector ALUs waiting for the first product
+    // and end with the matrix pipeline idle behind the last one, in both wavefronts of a SIMD at once (the
+    // barrier keeps them in step).  Needs the sigma registers of the stage before (they alternate by stage
+    // parity when FN = 1) and a product register set that the next stage's first pair does not take.
+    constexpr bool kDefer = kMbs && FN == 1 && kPairs % 2 == 0;
     v16f prod[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) prod[0][e] = prod[1][e] = 0.f;
     auto product = [&](const Frags& f, auto q_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
         v16f zero;
@@ -446,6 +462,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             issue(std::integral_constant<int, 0>{});
             // (behind the first pair's instructions: the LDS round trip of the MBS words then overlaps their run)
             convert_sigma(s + 2);  // into the table stage s - 2 was read from
+            if constexpr (kDefer) {
+                __builtin_amdgcn_sched_barrier(0);
+                retire(NextPar{}, std::integral_constant<int, kPairs - 1>{});  // (the other parity: the stage before)
+                __builtin_amdgcn_sched_barrier(0);
+            }
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 if constexpr (q + 1 < kPairs) issue(std::integral_constant<int, q + 1>{});
@@ -458,7 +479,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 slip(std::integral_constant<int, 2 * q>{});
                 slip(std::integral_constant<int, 2 * q + 1>{});
                 __builtin_amdgcn_sched_barrier(0);
-                retire(Par{}, q_);
+                if constexpr (!(kDefer && q == kPairs - 1)) retire(Par{}, q_);
                 __builtin_amdgcn_sched_barrier(0);
             });
         } else {
@@ -505,6 +526,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
     if (NW == 8 || w % 4 < 2) run(std::integral_constant<int, 0>{});
     else run(std::integral_constant<int, 1>{});
+    // (the last stage is the fourth of its group: parity 1)
+    if constexpr (kDefer) retire(std::integral_constant<int, 1>{}, std::integral_constant<int, kPairs - 1>{});
 
     // ---- epilogue ------------------------------------------------------------------------------------
     // A lane holds, per fragment, output row lr and the column groups 8 g + 4 h .. + 3.  Each wavefront
