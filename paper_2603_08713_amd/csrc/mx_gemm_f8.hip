@@ -327,6 +327,41 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
     };
 
+    // MBS: the product of a stage's last pair is folded into the accumulators at the start of the next stage, behind
+    // that stage's first matrix instructions (otherwise every stage begins with the vector ALUs waiting for the
+    // first product and ends with the matrix pipeline idle behind the last, in both wavefronts of a SIMD at once);
+    // it waits in prod[1] with its sigma values.  The first stage folds in zeros.  (Fast form only: the general
+    // form has no registers to spare for it.)
+    constexpr bool kDefer = kMbs && kFast;
+    v16f prod[2];
+    float last_sm = 0.f;
+    uint32_t last_sn[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) prod[0][e] = prod[1][e] = 0.f;
+    // acc[i][j] += prod[which] * sm * sn (sn: the lane's four sigma_B registers of the fragment, fetched by DPP)
+    auto fold = [&](auto i_, auto j_, auto which_, float sm, const uint32_t (&sn)[4]) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_)::value, j = decltype(j_)::value, which = decltype(which_)::value;
+        // sigma_A * sigma_B with the DPP fetch folded into the multiply (written out: the compiler keeps the
+        // fetch as a move of its own); four products at a time, so that no multiply-add follows the
+        // multiply it depends on directly (the compiler would put a wait state between the two)
+        static_for<4>([&](auto gq_) {
+            constexpr int gq = decltype(gq_)::value;
+            float w0, w1, w2, w3;
+            asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w0) : "v"(sn[gq]), "v"(sm));
+            asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w1) : "v"(sn[gq]), "v"(sm));
+            asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w2) : "v"(sn[gq]), "v"(sm));
+            asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w3) : "v"(sn[gq]), "v"(sm));
+            acc[i][j][4 * gq + 0] = fmaf(prod[which][4 * gq + 0], w0, acc[i][j][4 * gq + 0]);
+            acc[i][j][4 * gq + 1] = fmaf(prod[which][4 * gq + 1], w1, acc[i][j][4 * gq + 1]);
+            acc[i][j][4 * gq + 2] = fmaf(prod[which][4 * gq + 2], w2, acc[i][j][4 * gq + 2]);
+            acc[i][j][4 * gq + 3] = fmaf(prod[which][4 * gq + 3], w3, acc[i][j][4 * gq + 3]);
+        });
+    };
+    using LastI = std::integral_constant<int, FM - 1>;
+    using LastJ = std::integral_constant<int, FN - 1>;
+    using Prod1 = std::integral_constant<int, 1>;
+    static_assert((FM * FN) % 2 == 0, "the last pair's product waits in prod[1], which the next stage's first pair leaves alone");
+
     // One stage.  On entry the registers hold the fragments (fast form: and the E8M0 operands) of stage s; the
     // loads of stages s + 1 and s + 2 are in flight.
     auto stage = [&](int s, auto slot_, auto phase_) __attribute__((always_inline)) {
@@ -391,7 +426,6 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         }
         if constexpr (kMbs) {
             constexpr int kPairs = FM * FN;
-            v16f prod[2];
             auto product = [&](auto q_) __attribute__((always_inline)) {  // the instructions of pair q, then the refills they make possible
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 v16f zero;
@@ -413,28 +447,24 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 }
             };
             product(std::integral_constant<int, 0>{});
+            if constexpr (kDefer) {
+                __builtin_amdgcn_sched_barrier(0);
+                fold(LastI{}, LastJ{}, Prod1{}, last_sm, last_sn);  // the stage before
+                __builtin_amdgcn_sched_barrier(0);
+            }
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
                 if constexpr (q + 1 < kPairs) product(std::integral_constant<int, q + 1>{});
                 // (every instruction of the stage has its E8M0 operands: the next stage's may replace them)
                 if constexpr (kFast && q + 1 == kPairs - 1) read_scales_fast(s + 1);
                 __builtin_amdgcn_sched_barrier(0);
-                const float sm = sig_m[i];
-                // sigma_A * sigma_B with the DPP fetch folded into the multiply (written out: the compiler keeps the
-                // fetch as a move of its own); four products at a time, so that no multiply-add follows the
-                // multiply it depends on directly (the compiler would put a wait state between the two)
-                static_for<4>([&](auto gq_) {
-                    constexpr int gq = decltype(gq_)::value;
-                    float w0, w1, w2, w3;
-                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w0) : "v"(sig_n[j][gq]), "v"(sm));
-                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w1) : "v"(sig_n[j][gq]), "v"(sm));
-                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w2) : "v"(sig_n[j][gq]), "v"(sm));
-                    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(w3) : "v"(sig_n[j][gq]), "v"(sm));
-                    acc[i][j][4 * gq + 0] = fmaf(prod[q % 2][4 * gq + 0], w0, acc[i][j][4 * gq + 0]);
-                    acc[i][j][4 * gq + 1] = fmaf(prod[q % 2][4 * gq + 1], w1, acc[i][j][4 * gq + 1]);
-                    acc[i][j][4 * gq + 2] = fmaf(prod[q % 2][4 * gq + 2], w2, acc[i][j][4 * gq + 2]);
-                    acc[i][j][4 * gq + 3] = fmaf(prod[q % 2][4 * gq + 3], w3, acc[i][j][4 * gq + 3]);
-                });
+                if constexpr (q + 1 < kPairs || !kDefer) {
+                    fold(std::integral_constant<int, i>{}, std::integral_constant<int, j>{}, std::integral_constant<int, q % 2>{}, sig_m[i], sig_n[j]);
+                } else {
+                    last_sm = sig_m[i];
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) last_sn[gq] = sig_n[j][gq];
+                }
                 __builtin_amdgcn_sched_barrier(0);
             });
         } else {
@@ -497,6 +527,8 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         run(s, Zero{}, Step{});
         if (s + kStep < nstages) run(s, Step{}, Step{});
     }
+
+    if constexpr (kDefer) fold(LastI{}, LastJ{}, Prod1{}, last_sm, last_sn);  // the last stage's last pair
 
     // ---- epilogue ----
     // A lane holds, per fragment, output row lr and the column groups 8 g + 4 h .. + 3.  Each wavefront passes its
