@@ -29,4 +29,4 @@ def gemm_operand_bytes(M: int, N: int, K: int, mbs: bool) -> float:
 
 # HBM traffic of one MBS GEMM launch on the bench shape (bytes), from the FETCH_SIZE and WRITE_SIZE counter
 # runs whose summaries are kept under profiles/ (scaled by the copy-kernel calibration stated there).
-GEMM_MBS_TRAFFIC_BYTES = int((203.8 + 139.1) * 2 ** 20)  # read 203.8 MiB + written 139.1 MiB
+GEMM_MBS_TRAFFIC_BYTES = int((202.7 + 144.4) * 2 ** 20)  # read 202.7 MiB + written 144.4 MiB
