@@ -55,8 +55,10 @@ def lib() -> ctypes.CDLL:
         L.mxo_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mxo_quantize_given_mbs.restype = ci
         L.mxo_quantize_given_mbs.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp]
-        L.mxo_mbs_dynamic_cost.restype = ctypes.c_float
-        L.mxo_mbs_dynamic_cost.argtypes = [vp, ci, ci, ci, ci, ci, ci]
+        L.mxo_mbs_sse.restype = dbl
+        L.mxo_mbs_sse.argtypes = [vp, ci, ci, ci, ci]
+        L.mxo_mbs_sse_rows.restype = ci
+        L.mxo_mbs_sse_rows.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp]
         L.mxo_quantize_mbs_dynamic.restype = ci
         L.mxo_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.mxo_dequantize.restype = ci
@@ -68,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.mxo_qsnr_db.restype = dbl
         L.mxo_qsnr_db.argtypes = [vp, vp, i64]
         L.mxo_num_threads.restype = ci
+        L.mxo_set_num_threads.restype = ci
+        L.mxo_set_num_threads.argtypes = [ci]
         L.mxo_elem_bits.restype = ci
         L.mxo_elem_bits.argtypes = [ci]
         L.mxo_elem_decode.restype = dbl
@@ -127,6 +131,11 @@ def num_threads() -> int:
     return lib().mxo_num_threads()
 
 
+def set_num_threads(n: int) -> int:
+    """Threads of the row loops from now on; returns the previous number."""
+    return lib().mxo_set_num_threads(int(n))
+
+
 # ---- tensor functions --------------------------------------------------------------------------
 def quantize(x_bf16: np.ndarray, rule="oas", mbs: bool = False, block: int = 32, macro: int = 128):
     """x_bf16: uint16 [rows, K] bf16 bit patterns. Returns (codes, scales, mbs_words or None)."""
@@ -165,7 +174,7 @@ DYNAMIC_DEFAULT = dict(cand_first=0, cand_count=16, cand_stride=16)
 
 def quantize_mbs_dynamic(x_bf16: np.ndarray, rule="oas", cand_first: int = 0, cand_count: int = 16,
                          cand_stride: int = 16, block: int = 32, macro: int = 128):
-    """MBS-Dynamic: per macro block the candidate word of least cost. Returns (codes, scales, words)."""
+    """MBS-Dynamic: per macro block the candidate word of least sum of squared errors. Returns (codes, scales, words)."""
     x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
     rows, K = x.shape
     codes = np.zeros((rows, K // 2), np.uint8)
@@ -178,11 +187,24 @@ def quantize_mbs_dynamic(x_bf16: np.ndarray, rule="oas", cand_first: int = 0, ca
     return codes, scales, words
 
 
-def mbs_dynamic_cost(xm_bf16: np.ndarray, m8: int, e128: int, rule="oas", block: int = 32,
-                     macro: int = 128) -> float:
-    """The binary32 cost MBS-Dynamic assigns to word m8 on one macro block (1-D bf16 bit patterns)."""
+def mbs_sse(xm_bf16: np.ndarray, m8: int, rule="oas", block: int = 32) -> float:
+    """Sum of squared errors of one macro block (1-D bf16 bit patterns) quantized with word m8 (Eq. 6 with
+    the true error); -1 if the block holds a non-finite element."""
     xm = np.ascontiguousarray(xm_bf16, dtype=np.uint16)
-    return float(lib().mxo_mbs_dynamic_cost(_ptr(xm), xm.size, int(m8), _rule(rule), block, macro, int(e128)))
+    return float(lib().mxo_mbs_sse(_ptr(xm), xm.size, int(m8), _rule(rule), block))
+
+
+def mbs_sse_rows(x_bf16: np.ndarray, words: np.ndarray, rule="oas", block: int = 32, macro: int = 128) -> np.ndarray:
+    """The same sum for every macro block of x under the given words [rows, ceil(K/macro)]; fp64 [rows, nmac]."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    words = np.ascontiguousarray(words, np.uint8)
+    assert words.shape == (rows, (K + macro - 1) // macro)
+    out = np.empty(words.shape, np.float64)
+    rc = lib().mxo_mbs_sse_rows(_ptr(x), rows, K, K, _rule(rule), block, macro, _ptr(words), _ptr(out))
+    if rc != 0:
+        raise ValueError("mxo_mbs_sse_rows: bad arguments")
+    return out
 
 
 def dequantize(codes, scales, mbs=None, block: int = 32, macro: int = 128) -> np.ndarray:

@@ -13,9 +13,8 @@
  * Arithmetic: every real number is a C double.  bf16 inputs, the MBS factor (9 significant
  * bits), their product (17 bits) and any power-of-two multiple of it are exact in a double, so
  * codes, scales and MBS words are decided on exact values; there is no rounding anywhere before
- * the final "nearest E2M1 value" decision.  GEMM and QSNR sums are fp64.  The one exception is the
- * cost that MBS-Dynamic minimises: a minimum over rounded sums is reproducible only if the sums
- * are, so that cost is defined in IEEE binary32 with a stated order of operations (see there).
+ * the final "nearest E2M1 value" decision.  GEMM and QSNR sums, and the sum of squared errors that
+ * MBS-Dynamic minimises, are fp64.
  *
  * Conventions (paper silent; fixed here and used by the tests):
  *   - E2M1 code = sign<<3 | magnitude index into {0, .5, 1, 1.5, 2, 3, 4, 6}   (Sec. 2.2, 3.2)
@@ -219,85 +218,74 @@ int mxo_quantize_given_mbs(const uint16_t* x, int64_t rows, int64_t K, int64_t l
     return 0;
 }
 
-/* ---- MBS-Dynamic (Sec. 4.3.1 "Dynamic", Sec. 5.3) ------------------------------------------- */
+/* ---- MBS-Dynamic (Sec. 4.3.3 "Dynamic", Eq. 4-6; Sec. 5.3) ---------------------------------- */
 
-/* The paper picks, out of 16 candidate words, the one with the smallest sum of squared errors of
- * the 1x128 block, and evaluates that sum through a table of approximate squared relative errors.
- * Neither the candidate list nor the table is given, so this build searches the candidates
+/* Eq. 6 picks, out of a list of candidate words, the one with the smallest sum of squared errors
+ * of the 1x128 block, sum_i (x_hat_i - x_i)^2 = sum_i x_i^2 ((x_hat_i - x_i)/x_i)^2, with
+ * x_hat_i the value reconstructed from Q(x_i (1 + m_j) SF) (Eq. 4).  This is that definition
+ * written out: the error of every element is taken on exact values (x_hat = q 2^-s / F in fp64,
+ * one rounding of the division) and summed in fp64, element by element in order.  The paper's table
+ * of approximate squared relative errors (Eq. 5) is a way to evaluate the same sum faster; it is
+ * restated separately below (mxo_quantize_mbs_dynamic_lut).
+ *
+ * The candidate list is not given ("a narrow range", 16 candidates), so it is a parameter:
  *     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count-1
  * (the factor 1 + m/256 is defined up to a power of two, which the local scales absorb, so the
- * words form a circle), and evaluates the sum of squared errors itself rather than a table.
- *
- * A minimum over floating-point sums is only reproducible if the sums are: the cost below is
- * therefore DEFINED in IEEE binary32 with a fixed order of operations, the same one the GPU kernel
- * uses, and is not "the exact SSE" (the pin tests bound its distance from the exact SSE).
- *
- * cost(m), for a macro block whose absmax alpha128 has the biased exponent field e128:
- *   F = 1 + m/256.  For each sub-block b: E_b, s_b as in quantize_macro_block; for each element
- *   t = x F 2^s_b (exact), q = the E2M1 value it rounds to, r = t - q (exact);
- *   the 8 elements of each aligned group of 8 accumulate r*r by fused multiply-add, in element
- *   order, starting from 0; the groups of a sub-block are added pairwise ((g0+g1)+(g2+g3));
- *   that sum is multiplied by 4^(E_b - e128) (exact), which expresses it in units of the macro
- *   block's binade instead of the sub-block's; the sub-blocks are added pairwise in the same way
- *   (a missing sub-block of a short last macro block is 0); the total is divided by F*F (exact
- *   product, one correctly rounded division).  Errors were measured on x F, hence the division.
- *   A sub-block whose own absmax lies more than 30 binades below alpha128 (exponent field below
- *   e128 - 30), or is zero, contributes 0.
- * The search runs only where binary32 holds every intermediate exactly: e128 in [64, 249] and no
- * non-finite element in the macro block.  Elsewhere the static word is kept.
- * The static word is the incumbent; candidates are scanned in the order j = 0, 1, ... and one
- * replaces the current choice only with a strictly smaller cost. */
+ * words form a circle).  The static word always competes and is the incumbent; candidates are
+ * scanned in the order j = 0, 1, ... and one replaces the current choice only with a strictly
+ * smaller sum, so ties keep the static word, then the lowest j.  A macro block that holds a
+ * non-finite element has no finite sum and keeps the static word. */
 
-static float pairwise_sum(const float* v, int n) { /* n a power of two */
-    if (n == 1) return v[0];
-    return pairwise_sum(v, n / 2) + pairwise_sum(v + n / 2, n / 2);
-}
-
-static int exponent_field_bf16(double a) { /* floor(log2 a) + 127: the biased exponent field of a normal a */
-    int ex;
-    frexp(a, &ex);
-    return ex - 1 + 127;
-}
-
-/* cost of word m8 for the macro block xm[0..n), n a multiple of block, block a multiple of 8 with
- * block/8 and macro/block powers of two; all elements finite, e128 as described above. */
-float mxo_mbs_dynamic_cost(const uint16_t* xm, int n, int m8, int rule, int block, int macro,
-                           int e128) {
-    const float F = 1.0f + (float)m8 / 256.0f;
-    float sub[64] = {0};
-    for (int b = 0; b * block < n; ++b) {
-        const uint16_t* xb = xm + b * block;
-        double amax0 = 0.0; /* unscaled absmax of the sub-block */
-        for (int k = 0; k < block; ++k) amax0 = fmax(amax0, fabs(mxo_bf16_value(xb[k])));
-        if (amax0 == 0.0 || exponent_field_bf16(amax0) < e128 - 30) continue;
-        const int E = mxo_e8m0_from_exponent(mxo_scale_exponent(amax0 * (double)F, rule));
-        const int s = 127 - E;
-        float grp[16];
-        for (int g = 0; g < block / 8; ++g) {
-            float acc = 0.0f;
-            for (int k = 8 * g; k < 8 * g + 8; ++k) {
-                const float t = ldexpf((float)mxo_bf16_value(xb[k]) * F, s);
-                float q = (float)E2M1_VALUE[mxo_e2m1_nearest(fabs((double)t))];
-                if (xb[k] & 0x8000u) q = -q;
-                const float r = t - q;
-                acc = fmaf(r, r, acc);
-            }
-            grp[g] = acc;
+/* Sum of squared errors of the macro block xm[0..n) (n a multiple of block, all elements finite)
+ * when it is quantized with word m8: sum_i (x_hat_i - x_i)^2, x_hat_i = value(code_i) 2^(E_b-127) / F.
+ * Returns -1 if an element is not finite. */
+double mxo_mbs_sse(const uint16_t* xm, int n, int m8, int rule, int block) {
+    const double F = 1.0 + m8 / 256.0;
+    double sse = 0.0;
+    for (int b0 = 0; b0 < n; b0 += block) {
+        double amax = 0.0;
+        for (int k = b0; k < b0 + block; ++k) {
+            if (!is_finite_bf16(xm[k])) return -1.0;
+            amax = fmax(amax, fabs(mxo_bf16_value(xm[k]) * F));
         }
-        sub[b] = ldexpf(pairwise_sum(grp, block / 8), 2 * (E - e128));
+        int s = 0;
+        if (amax > 0.0) s = 127 - mxo_e8m0_from_exponent(mxo_scale_exponent(amax, rule));
+        for (int k = b0; k < b0 + block; ++k) {
+            const double x = mxo_bf16_value(xm[k]);
+            const double t = ldexp(x * F, s);                                  /* Eq. 4's argument, exact */
+            double q = E2M1_VALUE[mxo_e2m1_nearest(fabs(t))];
+            if (xm[k] & 0x8000u) q = -q;
+            const double x_hat = ldexp(q, -s) / F;
+            sse += (x_hat - x) * (x_hat - x);
+        }
     }
-    return pairwise_sum(sub, macro / block) / (F * F);
+    return sse;
 }
 
-/* Quantize with MBS-Dynamic words.  Arguments as mxo_quantize plus the candidate list; block must
- * be 8, 16, 32 or 64 and macro/block a power of two (at most 64).  Returns 0 or -1. */
+/* The same sum for every macro block of a tensor under caller-given words: sse_out [rows, ceil(K/macro)]
+ * (-1 for a macro block holding a non-finite element).  What a test needs to judge any choice of words. */
+int mxo_mbs_sse_rows(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule, int block,
+                     int macro, const uint8_t* mbs_in, double* sse_out) {
+    if (rows < 0 || K < 0 || ldx < K || block <= 0 || (block & 1) || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const int64_t nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            sse_out[r * nmac + g] = mxo_mbs_sse(x + r * ldx + k0, (int)(k1 - k0), mbs_in[r * nmac + g], rule, block);
+        }
+    return 0;
+}
+
+/* Quantize with MBS-Dynamic words (Eq. 6 with the true error).  Arguments as mxo_quantize plus the
+ * candidate list.  Returns 0 or -1. */
 int mxo_quantize_mbs_dynamic(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
                              int block, int macro, int cand_first, int cand_count, int cand_stride,
                              uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
-    if (rows < 0 || K < 0 || ldx < K || K % block || macro % block) return -1;
-    if (block != 8 && block != 16 && block != 32 && block != 64) return -1;
-    const int nsub = macro / block;
-    if (nsub < 1 || nsub > 64 || (nsub & (nsub - 1))) return -1;
+    if (rows < 0 || K < 0 || ldx < K || block <= 0 || (block & 1) || macro % block || K % block)
+        return -1;
     if (rule < 0 || rule > 2 || cand_count < 0 || cand_count > 256) return -1;
     const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
 #pragma omp parallel for schedule(static)
@@ -305,18 +293,14 @@ int mxo_quantize_mbs_dynamic(const uint16_t* x, int64_t rows, int64_t K, int64_t
         const uint16_t* xr = x + r * ldx;
         for (int64_t g = 0; g < nmac; ++g) {
             const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
-            const double a128 = macro_absmax(xr, k0, k1);
-            const int m_static = mxo_mbs_static_m8(a128);
-            int finite = 1;
-            for (int64_t k = k0; k < k1; ++k) finite &= is_finite_bf16(xr[k]);
+            const int m_static = mxo_mbs_static_m8(macro_absmax(xr, k0, k1));
             int best = m_static;
-            if (finite && a128 >= ldexp(1.0, 64 - 127) && a128 < ldexp(1.0, 250 - 127)) {
-                const int e128 = exponent_field_bf16(a128);
-                float best_cost = mxo_mbs_dynamic_cost(xr + k0, (int)(k1 - k0), m_static, rule, block, macro, e128);
+            double best_sse = mxo_mbs_sse(xr + k0, (int)(k1 - k0), m_static, rule, block);
+            if (best_sse >= 0.0) {
                 for (int j = 0; j < cand_count; ++j) {
                     const int m = (int)(((int64_t)m_static + (int64_t)(cand_first + j) * cand_stride) & 255);
-                    const float c = mxo_mbs_dynamic_cost(xr + k0, (int)(k1 - k0), m, rule, block, macro, e128);
-                    if (c < best_cost) { best_cost = c; best = m; }
+                    const double c = mxo_mbs_sse(xr + k0, (int)(k1 - k0), m, rule, block);
+                    if (c < best_sse) { best_sse = c; best = m; }
                 }
             }
             mbs[r * nmac + g] = (uint8_t)best;
@@ -630,6 +614,9 @@ double mxo_qsnr_db(const double* ref, const double* test, int64_t n) {
 #ifdef _OPENMP
 #include <omp.h>
 int mxo_num_threads(void) { return omp_get_max_threads(); }
+/* Number of threads the row loops use from now on (for timing the oracle on one core); returns the old number. */
+int mxo_set_num_threads(int n) { int old = omp_get_max_threads(); if (n > 0) omp_set_num_threads(n); return old; }
 #else
 int mxo_num_threads(void) { return 1; }
+int mxo_set_num_threads(int n) { (void)n; return 1; }
 #endif

@@ -1,11 +1,17 @@
 // Yardstick for the GEMM numbers: the rate at which the device sustains back-to-back
 // v_mfma_scale_f32_32x32x64_f8f6f4 (FP4) out of registers, with nothing else going on.  Under load the
 // clock follows the power the operands' bit patterns draw, so the rate depends on the data: constant
-// operands run close to the published peak, random ones far below it.  Not part of the public ABI.
-#include "mx_common.h"
+// operands run close to the published peak, random ones far below it.
+//
+// This file is a measurement aid of the benchmark, built into libmx4_bench.so; it is not part of the product
+// library (libmx4.so allocates nothing and holds no measurement code) and shares nothing with it.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace mx {
+namespace mxb {
 namespace {
+
+constexpr int kWave = 64;
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -47,19 +53,19 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const v4i* op
 }
 
 }  // namespace
-}  // namespace mx
+}  // namespace mxb
 
 // Runs `iters` rounds of four matrix instructions per wavefront on every SIMD of the device and returns the
 // sustained rate in TFLOP/s through *tflops.  random_operands != 0 fills the operand registers with random
-// bits (seeded), otherwise every nibble is the same code.  Allocates and frees its own small buffers.
-extern "C" int mx_internal_mfma_rate(int random_operands, int iters, double* tflops) {
-    using namespace mx;
-    if (!tflops || iters <= 0 || iters > (1 << 22)) return MX_EINVAL;
-    if (int st = check_device()) return st;
+// bits (seeded), otherwise every nibble is the same code.  Allocates and frees its own small buffers.  Returns 0,
+// or -1 on bad arguments or any HIP error.  The caller has made sure the device is gfx950.
+extern "C" int mxb_mfma_rate(int random_operands, int iters, double* tflops) {
+    using namespace mxb;
+    if (!tflops || iters <= 0 || iters > (1 << 22)) return -1;
     v4i* operands = nullptr;
     float* sink = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    int status = MX_ELAUNCH;
+    int status = -1;
     uint32_t* host = new uint32_t[kProbeWords];
     uint32_t x = 0x9E3779B9u;
     for (int i = 0; i < kProbeWords; ++i) {
@@ -78,7 +84,7 @@ extern "C" int mx_internal_mfma_rate(int random_operands, int iters, double* tfl
                 hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f) {
                 const double flops = 2.0 * 32 * 32 * 64 * kProbeChain * (double)iters * (kProbeThreads / kWave) * kProbeBlocks;
                 *tflops = flops / (ms * 1e-3) / 1e12;
-                status = MX_OK;
+                status = 0;
             }
         }
     }

@@ -5,8 +5,10 @@ are allocated with torch when the caller does not pass them.  Nothing is compute
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
+import threading
 from typing import Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -69,8 +71,16 @@ def load_library() -> ctypes.CDLL:
     L.mx_status_string.argtypes = [ci]
     L.mx_version.restype = ci
     L.mx_version.argtypes = []
-    L.mx_internal_mfma_rate.restype = ci
-    L.mx_internal_mfma_rate.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_double)]
+    L.mx_internal_quantize.restype = ci
+    L.mx_internal_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp]
+    L.mx_internal_quantize_elem.restype = ci
+    L.mx_internal_quantize_elem.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp]
+    L.mx_internal_gemm.restype = ci
+    L.mx_internal_gemm.argtypes = [vp, vp, vp, vp, vp, vp, ci, i32, vp, i64, i64, i64, ci, vp, i64, ci, ci, vp]
+    L.mx_internal_gemm_plan.restype = ci
+    L.mx_internal_gemm_plan.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.c_char_p, ci]
+    L.mx_internal_gemm_elem.restype = ci
+    L.mx_internal_gemm_elem.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, ci, vp]
     _lib = L
     return L
 
@@ -83,15 +93,61 @@ def mx_version() -> int:
     return load_library().mx_version()
 
 
+# ---- development routing (tests only) ----------------------------------------------------------------
+# The library keeps no switches.  Its development entry points (csrc/mx_internal.h) take the choice of
+# implementation as one more argument of the call; `forced(...)` makes the functions below pass such a
+# choice, for the calling thread, while the block runs.
+_dev = threading.local()
+
+
+@contextlib.contextmanager
+def forced(**choices):
+    """quantize_hw / quantize_elem_hw = 0 or 1 (rounding implementation), gemm_shape = a kernel form and
+    tile shape code of mx_gemm.hip, gemm_elem_general = 1 (general form of the 8-/6-bit GEMM kernel)."""
+    allowed = {"quantize_hw", "quantize_elem_hw", "gemm_shape", "gemm_elem_general"}
+    if set(choices) - allowed:
+        raise TypeError("unknown choice: %s" % sorted(set(choices) - allowed))
+    old = getattr(_dev, "choices", {})
+    _dev.choices = dict(old, **choices)
+    try:
+        yield
+    finally:
+        _dev.choices = old
+
+
+def _forced(name):
+    return getattr(_dev, "choices", {}).get(name)
+
+
+def gemm_plan(M: int, N: int, K: int, a_has_mbs: bool = True, b_has_mbs: bool = True, grouped: bool = False) -> str:
+    """The kernel the dispatcher of mx_gemm / mx_gemm_mbs / mx_gemm_mbs_grouped picks for a problem with aligned
+    arrays (host only; reported by the benchmark beside its timings)."""
+    buf = ctypes.create_string_buffer(512)
+    _check(load_library().mx_internal_gemm_plan(M, N, K, int(a_has_mbs), int(b_has_mbs), int(grouped), buf, 512),
+           "mx_internal_gemm_plan")
+    return buf.value.decode()
+
+
+def _quantize_call(where, x, rows, K, ldx, rule, use_mbs, codes, scales, mbs, public):
+    hw = _forced("quantize_hw")
+    if hw is None:
+        _check(public(), where)
+    else:
+        _check(load_library().mx_internal_quantize(_ptr(x), rows, K, ldx, rule, int(use_mbs), int(hw), _ptr(codes),
+                                                   _ptr(scales), _ptr(mbs), _stream()), where + " (mx_internal_quantize)")
+
+
+def _gemm_call(where, a, b, grouped, num_groups, row_offsets, M, N, K, code, out, ldc, mbs_entry, public):
+    shape = _forced("gemm_shape")
+    if shape is None:
+        _check(public(), where)
+    else:
+        _check(load_library().mx_internal_gemm(_ptr(a[0]), _ptr(a[1]), _ptr(a[2]), _ptr(b[0]), _ptr(b[1]), _ptr(b[2]),
+                                               int(grouped), int(num_groups), _ptr(row_offsets), M, N, K, code, _ptr(out),
+                                               ldc, int(mbs_entry), int(shape), _stream()), where + " (mx_internal_gemm)")
+
+
 # ---- helpers ---------------------------------------------------------------------------------------
-def mfma_rate(random_operands: bool, iters: int = 20000) -> float:
-    """Measurement aid, not part of the path: the FP4 matrix-instruction rate (TFLOP/s) the device
-    sustains out of registers, with constant or with random operand bits."""
-    out = ctypes.c_double(0.0)
-    _check(load_library().mx_internal_mfma_rate(1 if random_operands else 0, iters, ctypes.byref(out)), "mx_internal_mfma_rate")
-    return out.value
-
-
 def _torch():
     import torch
 
@@ -155,16 +211,16 @@ def mx_quantize(x, rule="ocp", codes=None, scales=None):
     """bf16 [rows, K] -> (codes uint8 [rows, K/2], scales uint8 [rows, K/32]) with `rule`, no MBS."""
     rows, K, ldx = _rows_ld(x)
     codes, scales, _ = _alloc_outputs(x, rows, K, codes, scales, None, False)
-    _check(load_library().mx_quantize(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
-                                      _stream()), "mx_quantize")
+    _quantize_call("mx_quantize", x, rows, K, ldx, _rule(rule), False, codes, scales, None,
+                   lambda: load_library().mx_quantize(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales), _stream()))
     return codes, scales
 
 
 def mx_quantize_oas(x, codes=None, scales=None):
     rows, K, ldx = _rows_ld(x)
     codes, scales, _ = _alloc_outputs(x, rows, K, codes, scales, None, False)
-    _check(load_library().mx_quantize_oas(_ptr(x), rows, K, ldx, _ptr(codes), _ptr(scales), _stream()),
-           "mx_quantize_oas")
+    _quantize_call("mx_quantize_oas", x, rows, K, ldx, MX_RULE_OAS, False, codes, scales, None,
+                   lambda: load_library().mx_quantize_oas(_ptr(x), rows, K, ldx, _ptr(codes), _ptr(scales), _stream()))
     return codes, scales
 
 
@@ -172,8 +228,9 @@ def mx_quantize_mbs(x, rule="oas", codes=None, scales=None, mbs=None):
     """MBS-Static quantization -> (codes, scales, mbs uint8 [rows, ceil(K/128)])."""
     rows, K, ldx = _rows_ld(x)
     codes, scales, mbs = _alloc_outputs(x, rows, K, codes, scales, mbs, True)
-    _check(load_library().mx_quantize_mbs(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
-                                          _ptr(mbs), _stream()), "mx_quantize_mbs")
+    _quantize_call("mx_quantize_mbs", x, rows, K, ldx, _rule(rule), True, codes, scales, mbs,
+                   lambda: load_library().mx_quantize_mbs(_ptr(x), rows, K, ldx, _rule(rule), _ptr(codes), _ptr(scales),
+                                                          _ptr(mbs), _stream()))
     return codes, scales, mbs
 
 
@@ -243,8 +300,9 @@ def mx_gemm(a_codes, a_scales, b_codes, b_scales, out_dtype="f32", out=None):
     if b_codes.shape[1] * 2 != K:
         raise ValueError("A and B disagree on K")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
-    _check(load_library().mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), M, N, K, code,
-                                  _ptr(out), ldc, _stream()), "mx_gemm")
+    _gemm_call("mx_gemm", (a_codes, a_scales, None), (b_codes, b_scales, None), False, 0, None, M, N, K, code, out, ldc, False,
+               lambda: load_library().mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), M, N, K, code,
+                                              _ptr(out), ldc, _stream()))
     return out
 
 
@@ -255,8 +313,9 @@ def mx_gemm_mbs(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, out_dtype="f
     if b_codes.shape[1] * 2 != K:
         raise ValueError("A and B disagree on K")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
-    _check(load_library().mx_gemm_mbs(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes), _ptr(b_scales),
-                                      _ptr(b_mbs), M, N, K, code, _ptr(out), ldc, _stream()), "mx_gemm_mbs")
+    _gemm_call("mx_gemm_mbs", (a_codes, a_scales, a_mbs), (b_codes, b_scales, b_mbs), False, 0, None, M, N, K, code, out, ldc,
+               True, lambda: load_library().mx_gemm_mbs(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes),
+                                                        _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc, _stream()))
     return out
 
 
@@ -279,9 +338,15 @@ def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scale
     _u8(scales, (rows, K // 32), "scales")
     if use_mbs:
         _u8(mbs, (rows, (K + 127) // 128), "mbs")
-    _check(load_library().mx_quantize_elem(_elem(elem), _ptr(x), rows, K, ldx, _rule(rule), int(bool(use_mbs)),
-                                           _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None, _stream()),
-           "mx_quantize_elem")
+    hw = _forced("quantize_elem_hw")
+    if hw is None:
+        _check(load_library().mx_quantize_elem(_elem(elem), _ptr(x), rows, K, ldx, _rule(rule), int(bool(use_mbs)),
+                                               _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None, _stream()),
+               "mx_quantize_elem")
+    else:
+        _check(load_library().mx_internal_quantize_elem(_elem(elem), _ptr(x), rows, K, ldx, _rule(rule), int(bool(use_mbs)),
+                                                        int(hw), _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None,
+                                                        _stream()), "mx_quantize_elem (mx_internal_quantize_elem)")
     return codes, scales, (mbs if use_mbs else None)
 
 
@@ -310,9 +375,14 @@ def mx_gemm_mbs_elem(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales
     if b_scales.shape[1] * 32 != K or a_codes.shape[1] != elem_code_bytes(a_elem, K) or b_codes.shape[1] != elem_code_bytes(b_elem, K):
         raise ValueError("A and B disagree on K, or a code array does not have the row length of its format")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
-    _check(load_library().mx_gemm_mbs_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
-                                           _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,
-                                           _stream()), "mx_gemm_mbs_elem")
+    if _forced("gemm_elem_general"):
+        _check(load_library().mx_internal_gemm_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
+                                                    _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out),
+                                                    ldc, 1, _stream()), "mx_gemm_mbs_elem (mx_internal_gemm_elem)")
+    else:
+        _check(load_library().mx_gemm_mbs_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
+                                               _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,
+                                               _stream()), "mx_gemm_mbs_elem")
     return out
 
 
@@ -340,7 +410,9 @@ def mx_gemm_mbs_grouped(a_codes, a_scales, a_mbs, b_codes, b_scales, b_mbs, row_
     if b_codes.shape[0] != G * N or b_codes.shape[1] * 2 != K:
         raise ValueError("B must hold num_groups stacked [N, K] weights")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
-    _check(load_library().mx_gemm_mbs_grouped(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes),
-                                              _ptr(b_scales), _ptr(b_mbs), G, _ptr(row_offsets), M, N, K, code,
-                                              _ptr(out), ldc, _stream()), "mx_gemm_mbs_grouped")
+    _gemm_call("mx_gemm_mbs_grouped", (a_codes, a_scales, a_mbs), (b_codes, b_scales, b_mbs), True, G, row_offsets, M, N, K,
+               code, out, ldc, True,
+               lambda: load_library().mx_gemm_mbs_grouped(_ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _ptr(b_codes),
+                                                          _ptr(b_scales), _ptr(b_mbs), G, _ptr(row_offsets), M, N, K, code,
+                                                          _ptr(out), ldc, _stream()))
     return out

@@ -13,6 +13,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmx4.so")
+# measurement aids of bench.py (yardstick kernels that allocate their own buffers): a library of their own
+BENCH_CSRC = os.path.join(HERE, "bench_csrc")
+BENCH_LIB = os.path.join(HERE, "libmx4_bench.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -66,7 +69,11 @@ def build(verbose: bool = False) -> str:
         missing = [l.split()[-1] for l in undefined.splitlines() if "_ZN2mx" in l]
         if missing:
             raise RuntimeError("libmx4.so has unresolved symbols: " + ", ".join(missing))
-        os.replace(tmp, LIB) if os.path.dirname(tmp) == HERE else shutil.move(tmp, LIB)
+        shutil.move(tmp, LIB)
+        bench_srcs = sorted(glob.glob(os.path.join(BENCH_CSRC, "*.hip")))
+        tmp = os.path.join(work, "libmx4_bench.so")
+        _run([HIPCC] + FLAGS + ["-shared"] + bench_srcs + ["-o", tmp], verbose)
+        shutil.move(tmp, BENCH_LIB)
     finally:
         shutil.rmtree(work, ignore_errors=True)
     return LIB

@@ -41,6 +41,7 @@
 // planes instead of stages: slot L = bytes 128 L .. + 127 of the 384 that a group of four stages takes of each
 // row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.
 #include "mx_gemm_shared.h"
+#include "mx_internal.h"
 
 namespace mx {
 namespace {
@@ -587,25 +588,15 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
 template <int kFmtA, int kFmtB, bool kMbs, bool kFast>
 int launch_f8_kernel(const GemmArgs& g, unsigned blocks, hipStream_t s) {
     using S = F8Shape<kFast>;
-    static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
     auto* fn = gemm_f8_kernel<kFmtA, kFmtB, kMbs, kFast>;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                S::kLdsBytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return MX_ELAUNCH;
-        }
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;  // one per kernel instantiation
+    if (int st = opt_in.ensure(reinterpret_cast<const void*>(fn), S::kLdsBytes)) return st;
     hipLaunchKernelGGL(fn, dim3(blocks), dim3(S::NT), S::kLdsBytes, s, g);
     return launch_status();
 }
 
-// development switch: 1 = always the general form
-int g_f8_general = 0;
-
 template <int kFmtA, int kFmtB>
-int launch_f8(GemmArgs g, bool use_mbs, hipStream_t s) {
+int launch_f8(GemmArgs g, bool use_mbs, bool force_general, hipStream_t s) {
     using S = F8Shape<true>;
     const int64_t tiles_m = (g.M + S::TM - 1) / S::TM, tiles_n = (g.N + S::TN - 1) / S::TN;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
@@ -613,7 +604,7 @@ int launch_f8(GemmArgs g, bool use_mbs, hipStream_t s) {
     g.tiles_n = (int)tiles_n;
     const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
     // fast form: E8M0 bytes and MBS words travel per group of four stages, as 16-byte pieces and dwords
-    const bool fast = !g_f8_general && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
+    const bool fast = !force_general && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
                       (!g.a_mbs || aligned(g.a_mbs, 4)) && (!g.b_mbs || aligned(g.b_mbs, 4));
     if (fast || kFmtA >= 2)  // (6-bit operands have been checked to allow the fast form)
         return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, true>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, true>(g, blocks, s);
@@ -624,7 +615,7 @@ int launch_f8(GemmArgs g, bool use_mbs, hipStream_t s) {
 
 int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, int b_elem,
                      const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs, int64_t M, int64_t N,
-                     int64_t K, int c_dtype, void* C, int64_t ldc, void* stream) {
+                     int64_t K, int c_dtype, void* C, int64_t ldc, void* stream, bool force_general = false) {
     if (a_elem <= MX_ELEM_E2M1 || a_elem > MX_ELEM_E3M2 || b_elem <= MX_ELEM_E2M1 || b_elem > MX_ELEM_E3M2) return MX_EINVAL;
     if (M < 0 || N < 0 || K < 0 || (K % kBlock) != 0 || ldc < N) return MX_EINVAL;
     if (c_dtype != MX_OUT_F32 && c_dtype != MX_OUT_BF16) return MX_EINVAL;
@@ -654,16 +645,16 @@ int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales
     const bool use_mbs = a_mbs || b_mbs;
     if (!a8) {
         const bool a32 = a_elem == MX_ELEM_E3M2, b32 = b_elem == MX_ELEM_E3M2;
-        if (!a32 && !b32) return launch_f8<2, 2>(g, use_mbs, s);
-        if (!a32 && b32) return launch_f8<2, 3>(g, use_mbs, s);
-        if (a32 && !b32) return launch_f8<3, 2>(g, use_mbs, s);
-        return launch_f8<3, 3>(g, use_mbs, s);
+        if (!a32 && !b32) return launch_f8<2, 2>(g, use_mbs, force_general, s);
+        if (!a32 && b32) return launch_f8<2, 3>(g, use_mbs, force_general, s);
+        if (a32 && !b32) return launch_f8<3, 2>(g, use_mbs, force_general, s);
+        return launch_f8<3, 3>(g, use_mbs, force_general, s);
     }
     const bool a5 = a_elem == MX_ELEM_E5M2, b5 = b_elem == MX_ELEM_E5M2;
-    if (!a5 && !b5) return launch_f8<0, 0>(g, use_mbs, s);
-    if (!a5 && b5) return launch_f8<0, 1>(g, use_mbs, s);
-    if (a5 && !b5) return launch_f8<1, 0>(g, use_mbs, s);
-    return launch_f8<1, 1>(g, use_mbs, s);
+    if (!a5 && !b5) return launch_f8<0, 0>(g, use_mbs, force_general, s);
+    if (!a5 && b5) return launch_f8<0, 1>(g, use_mbs, force_general, s);
+    if (a5 && !b5) return launch_f8<1, 0>(g, use_mbs, force_general, s);
+    return launch_f8<1, 1>(g, use_mbs, force_general, s);
 }
 
 }  // namespace
@@ -677,5 +668,10 @@ extern "C" int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const 
                                 b_mbs_or_null, M, N, K, (int)c_dtype, C, ldc, stream);
 }
 
-// Development switch (not part of the public ABI): 1 = the general form also where the fast form applies.
-extern "C" void mx_internal_set_gemm_elem_general(int general) { mx::g_f8_general = general; }
+extern "C" int mx_internal_gemm_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales,
+                                     const uint8_t* a_mbs_or_null, mx_elem_t b_elem, const uint8_t* b_codes,
+                                     const uint8_t* b_scales, const uint8_t* b_mbs_or_null, int64_t M, int64_t N,
+                                     int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, int force_general, void* stream) {
+    return mx::launch_gemm_elem((int)a_elem, a_codes, a_scales, a_mbs_or_null, (int)b_elem, b_codes, b_scales,
+                                b_mbs_or_null, M, N, K, (int)c_dtype, C, ldc, stream, force_general != 0);
+}

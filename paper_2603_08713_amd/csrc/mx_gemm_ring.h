@@ -593,16 +593,9 @@ int launch_ring(GemmArgs g, hipStream_t s) {
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
     const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
-    static bool attr_set = false;  // dynamic LDS above 64 KiB needs an opt-in once per process
     auto* fn = gemm_ring_kernel<S>;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                S::kLdsBytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return MX_ELAUNCH;
-        }
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;  // one per kernel instantiation
+    if (int st = opt_in.ensure(reinterpret_cast<const void*>(fn), S::kLdsBytes)) return st;
     hipLaunchKernelGGL(fn, dim3(blocks), dim3(S::NT), S::kLdsBytes, s, g);
     return launch_status();
 }

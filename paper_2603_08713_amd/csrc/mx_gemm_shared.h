@@ -1,12 +1,31 @@
 // Pieces shared by the MXFP4 GEMM kernels (private; the public ABI is include/mx4.h).
 #pragma once
 
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
 #include "mx_common.h"
 
 namespace mx {
+
+// Dynamic LDS above 64 KiB needs an opt-in per kernel and device.  The opt-in is idempotent, so two threads
+// that both find it missing may both make it; the flag only saves later launches the call.
+struct LdsOptIn {
+    std::atomic<uint64_t> done{0};  // bit d: made on device d
+    int ensure(const void* fn, int bytes) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return MX_ELAUNCH; }
+        const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;  // (devices past the 64th opt in on every launch)
+        if (done.load(std::memory_order_acquire) & bit) return MX_OK;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return MX_ELAUNCH;
+        }
+        done.fetch_or(bit, std::memory_order_release);
+        return MX_OK;
+    }
+};
 
 struct GemmArgs {
     const uint8_t *a_codes, *a_scales, *a_mbs;
@@ -23,6 +42,7 @@ struct GemmArgs {
 // Main kernels (mx_gemm_ring.h), fast form: K % 512 == 0 and aligned scale and MBS arrays, not grouped; without MBS
 // (mx_gemm_wide.hip: 256 x 256, 256 x 128 or 128 x 128 tiles) and with MBS (mx_gemm_mbs.hip: 256 x 128 or 128 x 128).
 int launch_gemm_wide(const GemmArgs& g, int tile, hipStream_t s);
+const char* describe_gemm_wide(int64_t M, int64_t N);  // what launch_gemm_wide(tile = 0) does with an M x N problem
 int launch_gemm_mbs_ring(const GemmArgs& g, int variant, hipStream_t s);
 // The same kernels in their general forms (any K % 32 == 0, any alignment of the scale arrays, grouped or not),
 // defined in mx_gemm_general.hip (with MBS) and mx_gemm_wide.hip (without).  tile: 0 = 256 x 128, 1 = 128 x 128;

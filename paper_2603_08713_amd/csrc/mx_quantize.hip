@@ -18,6 +18,7 @@
 //     exceeds the rule's threshold (Sec. 4.2: FLOOR 1.5, OAS 1.75, OCP never).
 // Blocks whose magnitudes are so small or so large that fp32 products could leave the normal
 // range, and blocks holding Inf/NaN, take a wave-uniform detour through an all-integer path.
+#include "mx_internal.h"
 #include "mx_quantize_math.h"
 
 namespace mx {
@@ -26,6 +27,7 @@ namespace {
 constexpr int kChunk = 512;        // elements per wavefront step
 constexpr int kUnroll = 4;         // chunks in flight per wavefront
 constexpr int kThreads = 256;
+constexpr int64_t kMaxK = (int64_t)1 << 30;  // a lane's column inside its row is a 32-bit number
 
 struct QuantArgs {
     const uint16_t* x;
@@ -364,15 +366,13 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
     }
 }
 
-int g_quant_hwcvt = 1;
-
-int launch_filled(const QuantArgs& q, int use_mbs, void* stream);
+int launch_filled(const QuantArgs& q, int use_mbs, void* stream, bool hwcvt = true);
 
 // argument checks and the fields common to both quantizer kernels; MX_OK with *empty set means nothing to do
 int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
                     uint8_t* codes, uint8_t* scales, uint8_t* mbs, bool device_check = true) {
     *empty = true;
-    if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
+    if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K || K > kMaxK) return MX_EINVAL;
     if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
     if (rows == 0 || K == 0) return MX_OK;
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
@@ -404,12 +404,12 @@ int fill_quant_args(QuantArgs& q, bool* empty, const void* x, int64_t rows, int6
 }
 
 int launch_quantize(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
-                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+                    uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream, bool hwcvt = true) {
     QuantArgs q;
     bool empty;
     if (int st = fill_quant_args(q, &empty, x, rows, K, ldx, rule, use_mbs, codes, scales, mbs)) return st;
     if (empty) return MX_OK;
-    return launch_filled(q, use_mbs, stream);
+    return launch_filled(q, use_mbs, stream, hwcvt);
 }
 
 // Two tensors with the same K (the two operands of a GEMM) in one launch: the smaller one no longer pays
@@ -438,7 +438,7 @@ int launch_quantize_pair(const void* x0, int64_t rows0, int64_t ldx0, uint8_t* c
     return launch_filled(q0, 1, stream);
 }
 
-int launch_filled(const QuantArgs& q, int use_mbs, void* stream) {
+int launch_filled(const QuantArgs& q, int use_mbs, void* stream, bool hwcvt) {
     const int64_t waves_needed = ((int64_t)q.split + q.total_chunks2 + kUnroll - 1) / kUnroll;
     int64_t blocks = (waves_needed + (kThreads / kWave) - 1) / (kThreads / kWave);
     // one batch of kUnroll chunks per wavefront (the hardware balances the workgroups); the loop in
@@ -447,7 +447,7 @@ int launch_filled(const QuantArgs& q, int use_mbs, void* stream) {
     if (blocks > max_blocks) blocks = max_blocks;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)blocks), block(kThreads);
-    if (g_quant_hwcvt) {
+    if (hwcvt) {
         if (use_mbs) hipLaunchKernelGGL((quantize_kernel<true, true>), grid, block, 0, s, q);
         else hipLaunchKernelGGL((quantize_kernel<true, false>), grid, block, 0, s, q);
     } else {
@@ -513,8 +513,9 @@ int mx_quantize_mbs_dynamic(const void* x_bf16, int64_t rows, int64_t K, int64_t
                                        scales, mbs, stream);
 }
 
-// Development switch (not part of the public ABI): 1 = hardware fp32->E2M1 convert instruction,
-// 0 = integer/float ALU rounding.  Both must give identical codes.
-void mx_internal_set_quantize_convert(int hw) { mx::g_quant_hwcvt = hw; }
+int mx_internal_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule, int use_mbs,
+                         int hw_convert, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize(x_bf16, rows, K, ldx, (int)rule, use_mbs ? 1 : 0, codes, scales, mbs, stream, hw_convert != 0);
+}
 
 }  // extern "C"

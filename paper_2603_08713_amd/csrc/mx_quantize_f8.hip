@@ -13,6 +13,7 @@
 // wave-uniform detour through all-integer arithmetic.
 // Output: 8-bit codes one per byte; 6-bit codes packed, element k of a row in bits 6 k .. 6 k + 5 of the row's
 // bytes (a block is 24 bytes, which three of its four lanes store, 8 bytes each, after a DPP exchange).
+#include "mx_internal.h"
 #include "mx_quantize_math.h"
 
 namespace mx {
@@ -302,12 +303,10 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
     }
 }
 
-int g_quant8_hwcvt = 1;
-
 template <int kElem>
-void launch8(const Quant8Args& q, int use_mbs, dim3 grid, hipStream_t s) {
+void launch8(const Quant8Args& q, int use_mbs, bool hwcvt, dim3 grid, hipStream_t s) {
     const dim3 block(kThreads8);
-    if (g_quant8_hwcvt) {
+    if (hwcvt) {
         if (use_mbs) hipLaunchKernelGGL((quantize8_kernel<kElem, true, true>), grid, block, 0, s, q);
         else hipLaunchKernelGGL((quantize8_kernel<kElem, true, false>), grid, block, 0, s, q);
     } else {
@@ -317,9 +316,10 @@ void launch8(const Quant8Args& q, int use_mbs, dim3 grid, hipStream_t s) {
 }
 
 int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
-                         uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+                         uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream, bool hwcvt = true) {
     if (elem < MX_ELEM_E2M1 || elem > MX_ELEM_E3M2 || elem == MX_ELEM_E2M1) return MX_EINVAL;
     if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
+    if (K > (int64_t)1 << 30) return MX_EINVAL;  // a lane's column inside its row is a 32-bit number
     if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
     if (rows == 0 || K == 0) return MX_OK;
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
@@ -345,10 +345,10 @@ int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64
     if (blocks > (1 << 22)) blocks = 1 << 22;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)blocks);
-    if (elem == MX_ELEM_E4M3) launch8<MX_ELEM_E4M3>(q, use_mbs, grid, s);
-    else if (elem == MX_ELEM_E5M2) launch8<MX_ELEM_E5M2>(q, use_mbs, grid, s);
-    else if (elem == MX_ELEM_E2M3) launch8<MX_ELEM_E2M3>(q, use_mbs, grid, s);
-    else launch8<MX_ELEM_E3M2>(q, use_mbs, grid, s);
+    if (elem == MX_ELEM_E4M3) launch8<MX_ELEM_E4M3>(q, use_mbs, hwcvt, grid, s);
+    else if (elem == MX_ELEM_E5M2) launch8<MX_ELEM_E5M2>(q, use_mbs, hwcvt, grid, s);
+    else if (elem == MX_ELEM_E2M3) launch8<MX_ELEM_E2M3>(q, use_mbs, hwcvt, grid, s);
+    else launch8<MX_ELEM_E3M2>(q, use_mbs, hwcvt, grid, s);
     return launch_status();
 }
 
@@ -362,8 +362,10 @@ int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K
     return mx::launch_quantize_elem((int)elem, x_bf16, rows, K, ldx, (int)rule, use_mbs, codes, scales, mbs, stream);
 }
 
-// Development switch (not part of the public ABI): 1 = hardware fp32->FP8 convert instruction, 0 = ordinary
-// arithmetic.  Both must give identical codes.
-void mx_internal_set_quantize_elem_convert(int hw) { mx::g_quant8_hwcvt = hw; }
+int mx_internal_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                              int use_mbs, int hw_convert, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize_elem((int)elem, x_bf16, rows, K, ldx, (int)rule, use_mbs, codes, scales, mbs, stream,
+                                    hw_convert != 0);
+}
 
 }  // extern "C"

@@ -27,6 +27,32 @@ def gemm_operand_bytes(M: int, N: int, K: int, mbs: bool) -> float:
     return (M + N) * K * per_elt
 
 
-# HBM traffic of one MBS GEMM launch on the bench shape (bytes), from the FETCH_SIZE and WRITE_SIZE counter
-# runs whose summaries are kept under profiles/ (scaled by the copy-kernel calibration stated there).
-GEMM_MBS_TRAFFIC_BYTES = int((202.7 + 144.4) * 2 ** 20)  # read 202.7 MiB + written 144.4 MiB
+# ---- secondary bound of the MBS GEMM: vector-ALU instruction issue -----------------------------------
+# A SIMD issues one vector-ALU instruction per 4 clocks for a 64-lane wavefront (16 lanes per clock; packed
+# fp32 is off in this build), and every scaled matrix instruction holds the same issue port for about 12 clocks
+# (measured on this device).  One macro block of a 32 x 32 output fragment is two 32x32x64 matrix instructions
+# = 2 * 32 * 32 * 128 FLOP; the correction adds `valu_per_fragment` vector instructions and
+# `extra_mfma_per_fragment` further matrix instructions to it.
+SIMDS = 256 * 4
+CLOCK_GHZ = 2.4
+VALU_ISSUE_CLOCKS = 4
+MFMA_ISSUE_CLOCKS = 12
+FRAGMENT_FLOP = 2.0 * 32 * 32 * 128
+
+
+def valu_issue_ceiling_tflops(valu_per_fragment: float, mfma_per_fragment: float = 2.0) -> float:
+    """TFLOP/s at which the vector-issue port of every SIMD is busy all the time, at the published clock."""
+    clocks = valu_per_fragment * VALU_ISSUE_CLOCKS + mfma_per_fragment * MFMA_ISSUE_CLOCKS
+    return FRAGMENT_FLOP / clocks * SIMDS * CLOCK_GHZ * 1e9 / 1e12
+
+
+def read_profile_value(path: str, key: str):
+    """A `key = number` line of a committed rocprofv3 summary under profiles/ (None if the file or key is missing)."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.strip().startswith(key) and "=" in line:
+                    return float(line.split("=", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "mx4.h")
+INTERNAL_HEADER = os.path.join(ROOT, "paper_2603_08713_amd", "csrc", "mx_internal.h")
 
 
 @pytest.fixture(scope="module")
@@ -20,9 +21,13 @@ def lib():
     return binding.load_library()
 
 
-def declared_functions():
-    text = open(HEADER).read()
+A16 = 0x10000  # fake, suitably aligned device addresses: rejected calls never dereference them
+
+
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", "", text)
     return sorted(set(re.findall(r"\b(mx_[a-z0-9_]+)\s*\(", text)))
 
 
@@ -34,6 +39,31 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, n), n
 
 
+def test_every_exported_symbol_is_declared(lib):
+    """The library exports the public ABI and the development entry points of csrc/mx_internal.h (each a public
+    call with one more argument; no switches, no state) and nothing else of its own."""
+    import subprocess
+
+    from paper_2603_08713_amd import build as mxbuild
+
+    internal = declared_functions(INTERNAL_HEADER)
+    assert internal and all(n.startswith("mx_internal_") for n in internal)
+    for n in internal:
+        assert hasattr(lib, n), n
+    out = subprocess.run(["nm", "-D", "--defined-only", mxbuild.LIB], stdout=subprocess.PIPE, text=True, check=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if re.search(r" [TW] mx_", l)}
+    assert exported == set(declared_functions()) | set(internal), exported ^ (set(declared_functions()) | set(internal))
+    assert not any("set_" in n for n in exported)
+
+
+def test_quantize_rejects_rows_longer_than_its_32_bit_columns(lib):
+    K = (1 << 30) + 32
+    assert lib.mx_quantize(A16, 1, K, K, 0, A16, A16, None) == -1
+    assert lib.mx_quantize_mbs(A16, 1, K, K, 2, A16, A16, A16, None) == -1
+    assert lib.mx_quantize_elem(1, A16, 1, K, K, 2, 0, A16, A16, None, None) == -1
+    assert lib.mx_internal_quantize(A16, 1, K, K, 0, 0, 0, A16, A16, None, None) == -1
+
+
 def test_version_and_status_strings(lib):
     assert lib.mx_version() >= 100
     seen = set()
@@ -42,9 +72,6 @@ def test_version_and_status_strings(lib):
         assert s and s not in seen
         seen.add(s)
     assert "unknown" in lib.mx_status_string(-99).decode()
-
-
-A16 = 0x10000  # fake, suitably aligned device addresses: rejected calls never dereference them
 
 
 def test_quantize_argument_errors(lib):

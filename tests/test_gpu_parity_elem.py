@@ -50,10 +50,6 @@ def host(t):
     return None if t is None else t.cpu().numpy()
 
 
-def set_convert(mx, hw: int):
-    mx.load_library().mx_internal_set_quantize_elem_convert(int(hw))
-
-
 def assert_quant_equal(mx, oracle, elem, bits, rule, mbs, what="", x=None):
     x = dev_bf16(bits) if x is None else x
     c, s, w = mx.mx_quantize_elem(x, elem, rule, use_mbs=mbs)
@@ -80,15 +76,12 @@ def assert_quant_equal(mx, oracle, elem, bits, rule, mbs, what="", x=None):
 def test_quantize_elem_tiny_config(mx, oracle, elem, hw):
     from paper_2603_08713_amd import synth
 
-    set_convert(mx, hw)
-    try:
+    with mx.forced(quantize_elem_hw=hw):
         a, w = synth.tiny(0)
         for rule in RULES:
             for mbs in (False, True):
                 assert_quant_equal(mx, oracle, elem, a, rule, mbs, "tiny A")
                 assert_quant_equal(mx, oracle, elem, w, rule, mbs, "tiny W")
-    finally:
-        set_convert(mx, 1)
 
 
 @pytest.mark.parametrize("hw", [1, 0])
@@ -97,8 +90,7 @@ def test_quantize_elem_every_bf16_pattern(mx, oracle, elem, hw):
     """All 65536 bf16 patterns (subnormals, Inf, NaN, both zeros): in natural order (blocks of similar
     magnitude) and shuffled so that blocks mix magnitudes and elements land in every binade of the element
     format, its subnormals included; plus exact ties of every spacing."""
-    set_convert(mx, hw)
-    try:
+    with mx.forced(quantize_elem_hw=hw):
         allbits = np.arange(65536, dtype=np.uint16).reshape(128, 512)
         rng = np.random.default_rng(0)
         flat = allbits.reshape(-1)
@@ -127,8 +119,6 @@ def test_quantize_elem_every_bf16_pattern(mx, oracle, elem, hw):
             for rule in RULES:
                 for mbs in (False, True):
                     assert_quant_equal(mx, oracle, elem, bits, rule, mbs, name)
-    finally:
-        set_convert(mx, 1)
 
 
 @pytest.mark.parametrize("rows,K,ld", [(1, 32, 32), (3, 96, 104), (5, 2880, 2880), (2, 4096 + 64, 4232), (7, 512, 512),
@@ -341,18 +331,14 @@ def test_gemm_elem_general_form_equals_fast_form(mx, oracle):
     """Where both forms of the kernel apply they run the same matrix instructions on the same data in the same
     order: bit-identical results."""
     rng = np.random.default_rng(45)
-    lib = mx.load_library()
     for (M, N, K) in ((300, 200, 512), (257, 390, 2048), (64, 128, 6656)):
         a, b = random_operand(rng, "e4m3", M, K, 118, 136), random_operand(rng, "e5m2", N, K, 118, 132)
         for words in (True, False):
             a1 = a if words else (a[0], a[1], None)
             b1 = b if words else (b[0], b[1], None)
             fast = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
-            lib.mx_internal_set_gemm_elem_general(1)
-            try:
+            with mx.forced(gemm_elem_general=1):
                 general = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
-            finally:
-                lib.mx_internal_set_gemm_elem_general(0)
             assert torch.equal(fast, general), (M, N, K, words)
 
 
@@ -366,16 +352,12 @@ def test_gemm_elem_general_form_at_full_size_repeats_bit_for_bit(mx):
     a_bits, w_bits = synth.llama8b_ffn_up(M, N, K)
     a = mx.mx_quantize_elem(dev_bf16(a_bits), "e4m3", "oas")
     b = mx.mx_quantize_elem(dev_bf16(w_bits), "e4m3", "oas")
-    lib = mx.load_library()
     for words in (True, False):
         args = ("e4m3", a[0], a[1], a[2] if words else None, "e4m3", b[0], b[1], b[2] if words else None, "bf16")
         fast = mx.mx_gemm_mbs_elem(*args)
-        lib.mx_internal_set_gemm_elem_general(1)
-        try:
+        with mx.forced(gemm_elem_general=1):
             for rep in range(5):
                 assert torch.equal(mx.mx_gemm_mbs_elem(*args), fast), (words, rep)
-        finally:
-            lib.mx_internal_set_gemm_elem_general(0)
 
 
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
