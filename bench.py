@@ -468,7 +468,7 @@ def moe_extras(mx, torch, synth, np, metrics, args):
     loads = np.diff(np.asarray(offsets)).astype(int).tolist()
     tg, tp = flops / (ms_g * 1e-3) / 1e12, flops / (ms_p * 1e-3) / 1e12
     return {
-        "workload": "32 experts of 2880x2880 N(0,0.02^2), 8192 tokens x 2880 (Student-t(4), 1% channels x20) routed top-4, "
+        "workload": "32 experts of 2880x2880 N(0,0.02^2), 8192 tokens x 2880 (Student-t(4), 1%% channels x20) routed top-4, "
                     "P(e) ~ (e+1)^-1.1; %d rows in expert order" % rows,
         "kernel": mx.gemm_plan(rows, dim, dim, True, True, True),
         "grouped_gemm_mbs_tflops": round(tg, 1), "grouped_gemm_mbs_frac_of_peak": round(tg / metrics.MFMA_FP4_PEAK_TFLOPS, 4),
