@@ -34,6 +34,14 @@
 // one of four LDS tables.  A wavefront folds a product in while the next pair's instructions run, and
 // the SIMD's other wavefront fills what gaps remain.
 //
+// Where both operands carry words, the surface S = sigma_A (x) sigma_B of Sec. 4.3.2 is itself a matrix product
+// with K = 1, and the matrix cores form it: one v_mfma_f32_32x32x1_2b_f32 takes sigma_B[n] on its rows and, in
+// its two blocks, sigma_A[m] of two neighbouring A fragments on its columns, and returns both fragments'
+// 32 x 32 products RN(sigma_A sigma_B) in exactly the register layout of the partial sums.  That halves the
+// vector work per output (one multiply-add, acc += P * S) at the price of half a matrix instruction more per
+// fragment: on this device a SIMD issues 16 fp32 lanes per clock, so two vector operations per output and
+// macro block (App. B, Eq. 7) cost 128 issue clocks per fragment against the 64 its matrix instructions take.
+//
 // LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
 // c ^ ((r >> 2) & 3), which keeps the 16-lane groups of a fragment read on distinct banks and lets four
 // lanes of a load fetch one contiguous 64-byte piece of a row.
@@ -62,6 +70,7 @@ template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, int kForm_ = 0>
 struct RingShape {
     static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
     static constexpr bool kMbs = kSides != 0, kGen = kForm_ != 0, kBytes = kForm_ == 2;
+    static constexpr bool kSurface = kSides == 3 && FN_ == 1 && FM_ % 2 == 0;
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
     static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
@@ -100,6 +109,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, NT = S::NT, kRows = S::kRows;
     constexpr int kCodeDma = S::kCodeDma, kRowDma = S::kRowDma, kScaleDma = S::kScaleDma, kM8Dma = S::kM8Dma;
     constexpr bool kMbs = S::kMbs, kSigmaA = (S::kSides & 1) != 0, kSigmaB = (S::kSides & 2) != 0;
+    // sigma_A (x) sigma_B on the matrix cores: both sides carry words, one B fragment, A fragments in couples
+    constexpr bool kSurface = S::kSurface;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -258,6 +269,17 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // are folded in, the next fragment's values (of this or of the next stage) arrive in the other set.
     float sig_m[2][FM];
     v4f sig_n[2][4];
+    // With the surface on the matrix cores a lane supplies, per stage, sigma_B of B row lr (to both blocks) and,
+    // per couple c of A fragments, sigma_A of row lr of fragment 2 c + lh (block lh); `surface` holds the two
+    // products of the current couple, registers 16 b .. 16 b + 15 for fragment 2 c + b.
+    float sig_n1[2] = {0.f, 0.f};
+    // Two surfaces are alive at a time, those of consecutive couples, but never more than three of their four
+    // halves: a couple's first fragment is folded in (and its half dead) before the next couple's surface is
+    // issued.  Couples alternate between `surf_a`, which keeps its first fragment in its upper half, and
+    // `surf_b`, which keeps it in its lower half, so that the two can share those 16 registers.
+    v32f surf_a, surf_b;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) surf_a[e] = surf_b[e] = 0.f;
     // (zeros: the first stage folds in the "last product of the stage before", which is zero times these)
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
@@ -324,12 +346,24 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     auto read_sigma_m = [&](int s, auto par_) {
         if constexpr (!kSigmaA) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
+        if constexpr (kSurface) {
+            // couple c of a stage is global couple s FM / 2 + c; even ones use surf_a (first fragment in block 1,
+            // so lane half h supplies fragment 2 c + 1 - h), odd ones surf_b (lane half h supplies fragment 2 c + h)
+            constexpr int par = decltype(par_)::value;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
+            for (int c = 0; c < FM / 2; ++c) {
+                const bool swap = ((FM / 2 == 1 ? par : 0) + c) % 2 == 0;
+                sig_m[par][c] = sig[(wm * FM + 2 * c) * 32 + (swap ? l ^ 32 : l)];
+            }
+            sig_n1[par] = sig[TM + wn * 32 + lr];
+        } else {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
+        }
     };
     auto read_sigma_n = [&](int s, auto j_, auto set_) {
         constexpr int j = decltype(j_)::value, set = decltype(set_)::value;
-        if constexpr (!kSigmaB) return;
+        if constexpr (!kSigmaB || kSurface) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq)
@@ -386,7 +420,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // and end with the matrix pipeline idle behind the last one, in both wavefronts of a SIMD at once (the
     // barrier keeps them in step).  Needs the sigma registers of the stage before (they alternate by stage
     // parity when FN = 1) and a product register set that the next stage's first pair does not take.
-    constexpr bool kDefer = kMbs && FN == 1 && kPairs % 2 == 0;
+    constexpr bool kDefer = kMbs && !kSurface && FN == 1 && kPairs % 2 == 0;
     v16f prod[2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) prod[0][e] = prod[1][e] = 0.f;
@@ -397,6 +431,25 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         for (int e = 0; e < 16; ++e) zero[e] = 0.f;
         prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
         prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
+    };
+    // The surface of couple c (A fragments 2 c and 2 c + 1) of the stage with parity par.
+    auto issue_surface = [&](auto par_, auto c_) {
+        constexpr int par = decltype(par_)::value, c = decltype(c_)::value;
+        v32f zero;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) zero[e] = 0.f;
+        const v32f v = __builtin_amdgcn_mfma_f32_32x32x1f32(sig_n1[par], sig_m[par][c], zero, 0, 0, 0);
+        if constexpr (((FM / 2 == 1 ? par : 0) + c) % 2 == 0) surf_a = v;
+        else surf_b = v;
+    };
+    // Half `half` (8 of the 16 multiply-adds) of folding the product of pair i of the stage with parity par in.
+    auto fold = [&](auto par_, auto i_, auto half_) {
+        constexpr int par = decltype(par_)::value, i = decltype(i_)::value, half = decltype(half_)::value;
+        constexpr bool in_a = ((FM / 2 == 1 ? par : 0) + i / 2) % 2 == 0;
+        constexpr int base = in_a ? (i % 2 == 0 ? 16 : 0) : (i % 2 == 0 ? 0 : 16);
+#pragma unroll
+        for (int e = half * 8; e < half * 8 + 8; ++e)
+            acc[i][0][e] = fmaf(prod[i % 2][e], in_a ? surf_a[base + e] : surf_b[base + e], acc[i][0][e]);
     };
     auto retire = [&](auto par_, auto q_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
@@ -445,7 +498,61 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 });
             }
         };
-        if constexpr (kMbs) {
+        if constexpr (kSurface) {
+            // Two wavefronts share a SIMD's matrix pipeline and its vector issue port well only if each of them
+            // mixes its matrix and vector instructions finely (measured: one wavefront issuing matrix
+            // instructions only and one issuing multiply-adds only slow each other down by a factor of 2.5,
+            // while two that each follow every matrix instruction with a few multiply-adds lose nothing).  So
+            // every product instruction is followed by 8 of the 16 multiply-adds that fold the pair BEFORE in
+            // (its product is complete by then), and the long surface instruction by this wavefront's LDS reads,
+            // loads and table work, which need no vector issue slots.  A couple's surface is issued a whole pair
+            // before its first use, right after the first fragment of the couple before has been folded in.
+            using I0 = std::integral_constant<int, 0>;
+            using I1 = std::integral_constant<int, 1>;
+            constexpr int kShadows = FM / 2;
+            read_sigma_m(s + 1, NextPar{});  // published by this stage's barrier; the next stage's first surface needs it
+            static_for<FM>([&](auto q_) {
+                constexpr int q = decltype(q_)::value, before = (q + FM - 1) % FM;
+                using Before = std::integral_constant<int, before>;
+                using BeforePar = std::conditional_t<q == 0, NextPar, Par>;  // pair FM - 1 of the stage before
+                v16f zero;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                prod[q % 2] = mfma_fp4_wide<0, 0>(cur.n[0][0], cur.m[q][0], zero, cur.scl_n[0], cur.scl_m[q]);
+                __builtin_amdgcn_sched_barrier(0);
+                fold(BeforePar{}, Before{}, I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                prod[q % 2] = mfma_fp4_wide<1, 1>(cur.n[0][1], cur.m[q][1], prod[q % 2], cur.scl_n[0], cur.scl_m[q]);
+                __builtin_amdgcn_sched_barrier(0);
+                fold(BeforePar{}, Before{}, I1{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (q % 2 == 1) {
+                    constexpr int shadow = q / 2;
+                    if constexpr (shadow + 1 < kShadows) issue_surface(Par{}, std::integral_constant<int, shadow + 1>{});
+                    else issue_surface(NextPar{}, I0{});
+                    __builtin_amdgcn_sched_barrier(0);
+                    // in its shadow: refill the couple's fragments (and, at the end, B's) with the next stage's data
+                    static_for<6>([&](auto r_) {
+                        read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (q - 1) * 3 + decltype(r_)::value>{});
+                    });
+                    if constexpr (q == FM - 1) static_for<3>([&](auto r_) {
+                        read_item(next, s + 1, NextSlot{}, std::integral_constant<int, FM * 3 + decltype(r_)::value>{});
+                    });
+                    if constexpr (kIssue) {
+                        static_for<kN>([&](auto n_) {
+                            constexpr int n = decltype(n_)::value;
+                            if constexpr ((n * kShadows) / kN == shadow) {
+                                if constexpr (n < kCodeDma) dma_code(s + kRingSlots, n_);
+                                else if constexpr (kPhase == 0) dma_scale(s / kRingGroup + 1, std::integral_constant<int, n - kCodeDma>{});
+                                else dma_m8(s / kRingGroup + 2, std::integral_constant<int, n - kCodeDma>{});
+                            }
+                        });
+                    }
+                    if constexpr (shadow == kShadows - 1) convert_sigma(s + 2);  // into the table stage s - 2 was read from
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
+        } else if constexpr (kMbs) {
             // The MBS path keeps one set of fragment registers (`cur` and `next` are the same object): a
             // fragment is refilled with the next stage's data right after the instructions of the last pair
             // that uses it have been issued.
@@ -469,6 +576,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             }
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
+                // (behind the last use of the couple before: the product folded in just above)
                 if constexpr (q + 1 < kPairs) issue(std::integral_constant<int, q + 1>{});
                 // first pair of a B fragment: request the sigma values of the next one into the other set
                 if constexpr (i == 0) {
@@ -524,10 +632,15 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     __builtin_amdgcn_s_waitcnt(wait_imm((kRingSlots - 2) * kCodeDma));
     // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
     // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
+    if constexpr (kSurface) issue_surface(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     if (NW == 8 || w % 4 < 2) run(std::integral_constant<int, 0>{});
     else run(std::integral_constant<int, 1>{});
     // (the last stage is the fourth of its group: parity 1)
     if constexpr (kDefer) retire(std::integral_constant<int, 1>{}, std::integral_constant<int, kPairs - 1>{});
+    if constexpr (kSurface) {
+        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, FM - 1>{}, std::integral_constant<int, 0>{});
+        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, FM - 1>{}, std::integral_constant<int, 1>{});
+    }
 
     // ---- epilogue ------------------------------------------------------------------------------------
     // A lane holds, per fragment, output row lr and the column groups 8 g + 4 h .. + 3.  Each wavefront
