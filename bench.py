@@ -38,8 +38,8 @@ HEADLINE = "llama3-70b-ffn"
 PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "bench_llama70b_ffn_hbm_traffic.txt")
 # vector instructions per 32x32 output fragment and macro block in the MBS kernel's inner loop (what the
 # correction itself needs; the loop's address and table work comes on top), and matrix instructions per fragment
-MBS_VALU_PER_FRAGMENT = 32   # 16 products sigma_A * sigma_B + 16 multiply-adds
-MBS_MFMA_PER_FRAGMENT = 2
+MBS_VALU_PER_FRAGMENT = 16    # one multiply-add per output: acc += P * S
+MBS_MFMA_PER_FRAGMENT = 2.5   # two products, and half of the instruction that forms S = sigma_A (x) sigma_B for two fragments
 
 
 def parse():
@@ -193,7 +193,7 @@ def main():
             "avg_launch_ms": round(t["ms_gemm"], 4),
             "secondary": {
                 "bound": "valu-issue",
-                "model": "per 32x32 fragment and macro block: %d vector instructions x %d clocks + %d matrix instructions x %d "
+                "model": "per 32x32 fragment and macro block: %d vector instructions x %.1f clocks + %.1f matrix instructions x %d "
                          "clocks of the SIMD's issue port, %d SIMDs at %.1f GHz"
                          % (MBS_VALU_PER_FRAGMENT, metrics.VALU_ISSUE_CLOCKS, MBS_MFMA_PER_FRAGMENT, metrics.MFMA_ISSUE_CLOCKS,
                             metrics.SIMDS, metrics.CLOCK_GHZ),

@@ -5,12 +5,9 @@
 #include <stdint.h>
 
 #include "mx4.h"
+#include "mx_constants.h"
 
 namespace mx {
-
-constexpr int kBlock = 32;   // elements per E8M0 scale (Sec. 2.2)
-constexpr int kMacro = 128;  // elements per MBS word (Sec. 4.3)
-constexpr int kWave = 64;
 
 // Returns MX_OK when the current device is gfx950; MX_EUNSUPPORTED otherwise (cached per process).
 int check_device();

@@ -20,8 +20,10 @@
 //
 // Pipeline: K advances one macro block (128 elements: 64 code bytes, 4 E8M0 bytes, one MBS word per row)
 // per stage through a ring of four LDS code slots.  While stage s is multiplied out of registers, stage
-// s + 1 is read from LDS into the other register set and the loads of stage s + 4 are issued into the
-// slot stage s has just left: three stages are in flight, enough to cover a miss in the L2.  One
+// s + 1 is read from LDS into the other register set; every other stage issues the loads of stages s + 3 and
+// s + 4 together, line by line, into the slots the stages s - 1 and s have left (mx_gemm_schedule.h: a memory
+// line holds two stages of a row, and its two halves are cheaper requested back to back than a stage apart):
+// two to three stages are in flight, enough to cover a miss in the L2.  One
 // workgroup barrier per stage publishes stage s + 1 and, because every wavefront has finished reading
 // stage s by then, frees its slot.  E8M0 bytes and MBS words travel per group of four stages: a row's 16
 // scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each); the general form, for K
@@ -31,78 +33,32 @@
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
 // The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
-// one of four LDS tables.  A wavefront folds a product in while the next pair's instructions run, and
-// the SIMD's other wavefront fills what gaps remain.
+// one of four LDS tables.  With words on one operand only, a wavefront folds a product in while the next
+// pair's instructions run.
 //
 // Where both operands carry words, the surface S = sigma_A (x) sigma_B of Sec. 4.3.2 is itself a matrix product
 // with K = 1, and the matrix cores form it: one v_mfma_f32_32x32x1_2b_f32 takes sigma_B[n] on its rows and, in
 // its two blocks, sigma_A[m] of two neighbouring A fragments on its columns, and returns both fragments'
 // 32 x 32 products RN(sigma_A sigma_B) in exactly the register layout of the partial sums.  That halves the
 // vector work per output (one multiply-add, acc += P * S) at the price of half a matrix instruction more per
-// fragment: on this device a SIMD issues 16 fp32 lanes per clock, so two vector operations per output and
-// macro block (App. B, Eq. 7) cost 128 issue clocks per fragment against the 64 its matrix instructions take.
+// fragment.  Measured on this device: beside matrix instructions a SIMD issues one fp32 vector instruction per
+// 4.6 clocks whichever of its wavefronts it comes from, and a matrix instruction holds the same port for 12,
+// so the two vector operations per output and macro block of App. B, Eq. 7 cost about 150 issue clocks per
+// fragment against the 64 its two matrix instructions take; with the surface on the matrix cores it is
+// 16 x 4.6 + 2.5 x 12 = 104 against 96.  A wavefront that issues matrix instructions only and one that issues
+// multiply-adds only slow each other down badly (2.5 times), so every product instruction is followed by 8 of
+// the multiply-adds that fold the pair BEFORE in.
 //
 // LDS image of a stage: codes [row][64 B] with the 16-byte chunk c of row r at position
 // c ^ ((r >> 2) & 3), which keeps the 16-lane groups of a fragment read on distinct banks and lets four
 // lanes of a load fetch one contiguous 64-byte piece of a row.
 #pragma once
 
+#include "mx_gemm_schedule.h"
 #include "mx_gemm_shared.h"
 
 namespace mx {
 namespace {
-
-constexpr int kRingStageK = kMacro;             // K elements per stage
-constexpr int kRingRowStage = kRingStageK / 2;  // code bytes per row and stage
-constexpr int kRingSlots = 4;
-constexpr int kRingGroup = 4;                   // stages per 16-byte piece of a row's E8M0 bytes
-constexpr int kRingGroupM = 4;                  // tile-rows walked together for L2 reuse
-constexpr int kSigmaSlots = 4;                  // as many as ring slots: a stage's table index is a compile-time constant
-
-// kSides: which operands carry MBS words (0 none, 1 A only, 2 B only, 3 both).
-// kForm: 0 = fast form, which wants K % 512 == 0 and 16-byte (E8M0) / 4-byte (MBS) aligned rows, so that a row's
-// bytes of four stages travel as one piece per lane.  1, 2 = general forms for everything else, grouped problems
-// included: E8M0 bytes travel as 2-byte pieces (1: any K % 64 == 0, rows of E8M0 bytes on even addresses; one
-// piece per lane and pair of blocks) or as single bytes (2: any K % 32 == 0, any address), MBS words as single
-// bytes, each piece in an LDS dword of its own; the last stage may be partly empty and the stage count is
-// padded to whole groups with stages that read zeros.
-template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, int kForm_ = 0>
-struct RingShape {
-    static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
-    static constexpr bool kMbs = kSides != 0, kGen = kForm_ != 0, kBytes = kForm_ == 2;
-    static constexpr bool kSurface = kSides == 3 && FN_ == 1 && FM_ % 2 == 0;
-    static constexpr int NW = NWM * NWN, NT = NW * kWave;
-    static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
-    static constexpr int kRows = TM + TN;             // rows of A followed by rows of B
-    static constexpr int kCodeDma = kRows / 16 / NW;  // per wavefront and stage: 16 rows x 64 B per load
-    // per wavefront and group of four stages: E8M0 bytes (fast: one row per lane; general: 8 rows x 8 pairs or
-    // 4 rows x 16 bytes per load) and MBS words (fast: one row per lane; general: 16 rows x 4 words per load)
-    static constexpr int kRowDma = ceil_div(kRows, kWave * NW);
-    static constexpr int kScaleRowsPerLoad = kBytes ? 4 : 8;  // general forms
-    static constexpr int kScaleDma = kGen ? kRows / kScaleRowsPerLoad / NW : kRowDma;
-    static constexpr int kM8Dma = kGen ? kRows / 16 / NW : kRowDma;
-    static constexpr int kRowsPadded = kRowDma * NW * kWave;
-    static constexpr int kCodesStage = kRows * kRingRowStage;
-    static constexpr int kScaleGroup = kBytes ? kRows * 64 : kGen ? kRows * 32 : kRowsPadded * 16;
-    static constexpr int kM8Group = !kMbs ? 0 : kGen ? kRows * 16 : kRowsPadded * 4;
-    static constexpr int kSigmaStage = kMbs ? kRows * 4 : 0;
-    // The small arrays come first: their addresses then fit the 16-bit constant of an LDS instruction.
-    static constexpr int kM8Base = 0;
-    static constexpr int kSigmaBase = kM8Base + 2 * kM8Group;
-    static constexpr int kScaleBase = (kSigmaBase + kSigmaSlots * kSigmaStage + 16383) / 16384 * 16384;
-    static constexpr int kDummy = kScaleBase + 2 * kScaleGroup;  // target of padding stores
-    static constexpr int kCodesBase = kDummy + 256;
-    static constexpr int kLdsBytes = kCodesBase + kRingSlots * kCodesStage;
-    static_assert(kCodesBase % 64 == 0 && kCodesBase < 65536, "code rows stay 64-byte aligned; small arrays below 64 KiB");
-    static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);  // per wavefront, epilogue staging
-    static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
-    static_assert((TM / 16) % NW == 0 && (TN / 16) % NW == 0, "16-row code loads: operand fixed per load index");
-    static_assert(!kGen || (TM % 128 == 0 && TN % 128 == 0 && kRows % (16 * NW) == 0), "general forms: operand fixed per load index");
-    static_assert(kLdsBytes <= 160 * 1024, "LDS capacity of a gfx950 compute unit");
-    static_assert(NW * kStageRegion <= kLdsBytes, "epilogue staging fits the LDS of the main loop");
-    static_assert(FM * FN * 16 <= 256, "accumulators fill at most the accumulation registers");
-    static_assert(!kMbs || FN == 1 || FN % 2 == 0, "MBS path: sigma sets line up across stages");
-};
 
 template <typename S>
 __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
@@ -111,6 +67,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     constexpr bool kMbs = S::kMbs, kSigmaA = (S::kSides & 1) != 0, kSigmaB = (S::kSides & 2) != 0;
     // sigma_A (x) sigma_B on the matrix cores: both sides carry words, one B fragment, A fragments in couples
     constexpr bool kSurface = S::kSurface;
+    constexpr int kCouples = FM / 2 * FN;  // surfaces per stage
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -272,7 +229,9 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // With the surface on the matrix cores a lane supplies, per stage, sigma_B of B row lr (to both blocks) and,
     // per couple c of A fragments, sigma_A of row lr of fragment 2 c + lh (block lh); `surface` holds the two
     // products of the current couple, registers 16 b .. 16 b + 15 for fragment 2 c + b.
-    float sig_n1[2] = {0.f, 0.f};
+    float sig_n1[2][FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) sig_n1[0][j] = sig_n1[1][j] = 0.f;
     // Two surfaces are alive at a time, those of consecutive couples, but never more than three of their four
     // halves: a couple's first fragment is folded in (and its half dead) before the next couple's surface is
     // issued.  Couples alternate between `surf_a`, which keeps its first fragment in its upper half, and
@@ -347,15 +306,17 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         if constexpr (!kSigmaA) return;
         const float* sig = reinterpret_cast<const float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
         if constexpr (kSurface) {
-            // couple c of a stage is global couple s FM / 2 + c; even ones use surf_a (first fragment in block 1,
-            // so lane half h supplies fragment 2 c + 1 - h), odd ones surf_b (lane half h supplies fragment 2 c + h)
+            // The couples of all stages, counted on, alternate between surf_a (first fragment in block 1, so lane
+            // half h supplies fragment 2 c + 1 - h) and surf_b (lane half h supplies fragment 2 c + h); couple
+            // j FM / 2 + c has the parity of c, plus the stage's when a stage has an odd number of couples.
             constexpr int par = decltype(par_)::value;
 #pragma unroll
             for (int c = 0; c < FM / 2; ++c) {
-                const bool swap = ((FM / 2 == 1 ? par : 0) + c) % 2 == 0;
+                const bool swap = ((kCouples % 2 == 1 ? par : 0) + c) % 2 == 0;
                 sig_m[par][c] = sig[(wm * FM + 2 * c) * 32 + (swap ? l ^ 32 : l)];
             }
-            sig_n1[par] = sig[TM + wn * 32 + lr];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) sig_n1[par][j] = sig[TM + (wn * FN + j) * 32 + lr];
         } else {
 #pragma unroll
             for (int i = 0; i < FM; ++i) sig_m[decltype(par_)::value][i] = sig[(wm * FM + i) * 32 + lr];
@@ -378,24 +339,28 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // ---- loads per stage ---------------------------------------------------------------------------
-    // Every stage requests the codes of stage s + 4; the first stage of a group (phase 0) also the scales of
-    // the next group, into the slot the previous group left two stages ago; the third (phase 2) the MBS
-    // words of the group after next, which have to be on hand two stages before their first use.
-    constexpr int kLoads[4] = {kCodeDma + kScaleDma, kCodeDma, kCodeDma + (kMbs ? kM8Dma : 0), kCodeDma};
-    static_assert(kRingSlots * kCodeDma + kScaleDma + 2 * kM8Dma < 64, "vmcnt is a 6-bit counter");
+    // ---- loads per stage (mx_gemm_schedule.h) ----------------------------------------------------------
+    using Sched = RingSchedule<kCodeDma, kScaleDma, kMbs ? kM8Dma : 0>;
+    static_assert(Sched::kSlots == kRingSlots && Sched::kGroup == kRingGroup, "the schedule is written for this ring");
+    static_assert(Sched::prologue_count() < 64 && Sched::issue_count(1) + Sched::issue_count(3) < 64, "vmcnt is a 6-bit counter");
+    // load n of those a stage of this phase issues (s: the issuing stage)
+    auto issue_load = [&](int s, auto phase_, auto n_) {
+        constexpr LoadItem it = Sched::issue_item(decltype(phase_)::value, decltype(n_)::value);
+        using Index = std::integral_constant<int, it.index>;
+        if constexpr (it.kind == kLoadCode) dma_code(s + it.what, Index{});
+        else if constexpr (it.kind == kLoadScale) dma_scale(s / kRingGroup + it.what, Index{});
+        else dma_m8(s / kRingGroup + it.what, Index{});
+    };
 
     // ---- prologue: fill the ring, fetch the operands of stage 0 --------------------------------------
-    static_for<kScaleDma>([&](auto i_) { dma_scale(0, i_); });
-    if constexpr (kMbs) {
-        static_for<kM8Dma>([&](auto i_) { dma_m8(0, i_); });
-        static_for<kM8Dma>([&](auto i_) { dma_m8(1, i_); });
-    }
-    static_for<kRingSlots * kCodeDma>([&](auto t_) {
-        constexpr int t = decltype(t_)::value;
-        dma_code(t / kCodeDma, std::integral_constant<int, t % kCodeDma>{});
+    static_for<Sched::prologue_count()>([&](auto n_) {
+        constexpr LoadItem it = Sched::prologue_item(decltype(n_)::value);
+        using Index = std::integral_constant<int, it.index>;
+        if constexpr (it.kind == kLoadCode) dma_code(it.what, Index{});
+        else if constexpr (it.kind == kLoadScale) dma_scale(it.what, Index{});
+        else dma_m8(it.what, Index{});
     });
-    __builtin_amdgcn_s_waitcnt(wait_imm((kRingSlots - 1) * kCodeDma));
+    __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_first()));
     bare_barrier();
     Frags f0, f1;
     if constexpr (kMbs) {
@@ -432,24 +397,28 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
         prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
     };
-    // The surface of couple c (A fragments 2 c and 2 c + 1) of the stage with parity par.
-    auto issue_surface = [&](auto par_, auto c_) {
-        constexpr int par = decltype(par_)::value, c = decltype(c_)::value;
+    // The surface of couple g of the stage with parity par: g = j FM / 2 + c is A fragments 2 c and 2 c + 1 against
+    // B fragment j.  Consecutive couples alternate between the two buffers; a stage with an odd number of couples
+    // (one) alternates by stage parity as well.
+    auto issue_surface = [&](auto par_, auto g_) {
+        constexpr int par = decltype(par_)::value, g = decltype(g_)::value, c = g % (FM / 2), j = g / (FM / 2);
         v32f zero;
 #pragma unroll
         for (int e = 0; e < 32; ++e) zero[e] = 0.f;
-        const v32f v = __builtin_amdgcn_mfma_f32_32x32x1f32(sig_n1[par], sig_m[par][c], zero, 0, 0, 0);
-        if constexpr (((FM / 2 == 1 ? par : 0) + c) % 2 == 0) surf_a = v;
+        const v32f v = __builtin_amdgcn_mfma_f32_32x32x1f32(sig_n1[par][j], sig_m[par][c], zero, 0, 0, 0);
+        if constexpr (((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0) surf_a = v;
         else surf_b = v;
     };
-    // Half `half` (8 of the 16 multiply-adds) of folding the product of pair i of the stage with parity par in.
-    auto fold = [&](auto par_, auto i_, auto half_) {
-        constexpr int par = decltype(par_)::value, i = decltype(i_)::value, half = decltype(half_)::value;
-        constexpr bool in_a = ((FM / 2 == 1 ? par : 0) + i / 2) % 2 == 0;
+    // Half `half` (8 of the 16 multiply-adds) of folding the product of pair q = j FM + i of the stage with parity
+    // par in.
+    auto fold = [&](auto par_, auto q_, auto half_) {
+        constexpr int par = decltype(par_)::value, q = decltype(q_)::value, half = decltype(half_)::value;
+        constexpr int i = q % FM, j = q / FM, g = j * (FM / 2) + i / 2;
+        constexpr bool in_a = ((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0;
         constexpr int base = in_a ? (i % 2 == 0 ? 16 : 0) : (i % 2 == 0 ? 0 : 16);
 #pragma unroll
         for (int e = half * 8; e < half * 8 + 8; ++e)
-            acc[i][0][e] = fmaf(prod[i % 2][e], in_a ? surf_a[base + e] : surf_b[base + e], acc[i][0][e]);
+            acc[i][j][e] = fmaf(prod[q % 2][e], in_a ? surf_a[base + e] : surf_b[base + e], acc[i][j][e]);
     };
     auto retire = [&](auto par_, auto q_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
@@ -473,11 +442,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         using NextSlot = std::integral_constant<int, (kPhase + 1) % kRingSlots>;  // stage s sits in slot s % 4 = kPhase
         static_assert(kRingSlots == kRingGroup, "the phase of a stage is also its ring slot");
         constexpr bool kIssue = decltype(issue_)::value;
-        constexpr int kN = kLoads[kPhase];
-        // Own loads of stage s + 1 (and of what the group loads two or more stages old carry) have landed;
-        // the loads issued in the last two stages may still fly.  Own reads of `cur` are done.
-        constexpr int kYounger = kLoads[(kPhase + 2) % 4] + kLoads[(kPhase + 3) % 4];
-        __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? kYounger : 0));
+        constexpr int kN = Sched::issue_count(kPhase);
+        // Own loads of stage s + 1 (and the E8M0 bytes and MBS words this stage reads) have landed; what was
+        // issued after them may still fly.  Own reads of `cur` are done.
+        __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? Sched::wait_count(kPhase) : 0));
         bare_barrier();
         auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
             constexpr int t = decltype(t_)::value;
@@ -491,9 +459,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 static_for<kN>([&](auto n_) {
                     constexpr int n = decltype(n_)::value, slot = (n * kMfmas) / kN + kLate;
                     if constexpr ((slot < kMfmas ? slot : kMfmas - 1) == t) {
-                        if constexpr (n < kCodeDma) dma_code(s + kRingSlots, n_);
-                        else if constexpr (kPhase == 0) dma_scale(s / kRingGroup + 1, std::integral_constant<int, n - kCodeDma>{});
-                        else dma_m8(s / kRingGroup + 2, std::integral_constant<int, n - kCodeDma>{});
+                        issue_load(s, phase_, n_);
                     }
                 });
             }
@@ -509,20 +475,20 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             // before its first use, right after the first fragment of the couple before has been folded in.
             using I0 = std::integral_constant<int, 0>;
             using I1 = std::integral_constant<int, 1>;
-            constexpr int kShadows = FM / 2;
+            constexpr int kShadows = kCouples;
             read_sigma_m(s + 1, NextPar{});  // published by this stage's barrier; the next stage's first surface needs it
-            static_for<FM>([&](auto q_) {
-                constexpr int q = decltype(q_)::value, before = (q + FM - 1) % FM;
-                using Before = std::integral_constant<int, before>;
-                using BeforePar = std::conditional_t<q == 0, NextPar, Par>;  // pair FM - 1 of the stage before
+            static_for<kPairs>([&](auto q_) {
+                constexpr int q = decltype(q_)::value, i = q % FM, j = q / FM;
+                using Before = std::integral_constant<int, (q + kPairs - 1) % kPairs>;
+                using BeforePar = std::conditional_t<q == 0, NextPar, Par>;  // the last pair of the stage before
                 v16f zero;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-                prod[q % 2] = mfma_fp4_wide<0, 0>(cur.n[0][0], cur.m[q][0], zero, cur.scl_n[0], cur.scl_m[q]);
+                prod[q % 2] = mfma_fp4_wide<0, 0>(cur.n[j][0], cur.m[i][0], zero, cur.scl_n[j], cur.scl_m[i]);
                 __builtin_amdgcn_sched_barrier(0);
                 fold(BeforePar{}, Before{}, I0{});
                 __builtin_amdgcn_sched_barrier(0);
-                prod[q % 2] = mfma_fp4_wide<1, 1>(cur.n[0][1], cur.m[q][1], prod[q % 2], cur.scl_n[0], cur.scl_m[q]);
+                prod[q % 2] = mfma_fp4_wide<1, 1>(cur.n[j][1], cur.m[i][1], prod[q % 2], cur.scl_n[j], cur.scl_m[i]);
                 __builtin_amdgcn_sched_barrier(0);
                 fold(BeforePar{}, Before{}, I1{});
                 __builtin_amdgcn_sched_barrier(0);
@@ -531,21 +497,19 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                     if constexpr (shadow + 1 < kShadows) issue_surface(Par{}, std::integral_constant<int, shadow + 1>{});
                     else issue_surface(NextPar{}, I0{});
                     __builtin_amdgcn_sched_barrier(0);
-                    // in its shadow: refill the couple's fragments (and, at the end, B's) with the next stage's data
-                    static_for<6>([&](auto r_) {
-                        read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (q - 1) * 3 + decltype(r_)::value>{});
-                    });
-                    if constexpr (q == FM - 1) static_for<3>([&](auto r_) {
-                        read_item(next, s + 1, NextSlot{}, std::integral_constant<int, FM * 3 + decltype(r_)::value>{});
+                    // in its shadow: refill the fragments whose last pair lies in this couple with the next stage's
+                    // data (A fragment i serves the pairs (0, i) .. (FN - 1, i), B fragment j the pairs (j, 0) ..
+                    // (j, FM - 1)), this stage's loads, and at the end the table work
+                    static_for<FM + FN>([&](auto f_) {
+                        constexpr int f = decltype(f_)::value;
+                        constexpr int last = f < FM ? (FN - 1) * FM + f : (f - FM) * FM + FM - 1;  // last pair that reads it
+                        if constexpr (last == q || last == q - 1) static_for<3>([&](auto part_) {
+                            read_item(next, s + 1, NextSlot{}, std::integral_constant<int, f * 3 + decltype(part_)::value>{});
+                        });
                     });
                     if constexpr (kIssue) {
                         static_for<kN>([&](auto n_) {
-                            constexpr int n = decltype(n_)::value;
-                            if constexpr ((n * kShadows) / kN == shadow) {
-                                if constexpr (n < kCodeDma) dma_code(s + kRingSlots, n_);
-                                else if constexpr (kPhase == 0) dma_scale(s / kRingGroup + 1, std::integral_constant<int, n - kCodeDma>{});
-                                else dma_m8(s / kRingGroup + 2, std::integral_constant<int, n - kCodeDma>{});
-                            }
+                            if constexpr ((decltype(n_)::value * kShadows) / kN == shadow) issue_load(s, phase_, n_);
                         });
                     }
                     if constexpr (shadow == kShadows - 1) convert_sigma(s + 2);  // into the table stage s - 2 was read from
@@ -625,11 +589,9 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             stage(s + 3, fb, fa, P3{}, late_, No{});
         }
     };
-    // The loads in flight when a stage starts are, in the steady state, those the last two stages issued, and
-    // the stage waits for all but that many.  Stage 0 starts with the prologue's loads of stages 2 and 3 in
-    // flight instead: with MBS that is fewer than two steady-state stages issue, so its wait would let a load
-    // of stage 1 slip past the barrier that publishes stage 1.  Wait for stage 1 here.
-    __builtin_amdgcn_s_waitcnt(wait_imm((kRingSlots - 2) * kCodeDma));
+    // (the prologue has issued what the loop would have issued before stage 0, in the loop's order, so this is
+    // the wait of a stage of phase 0: stage 1 has landed)
+    __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_loop()));
     // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
     // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
     if constexpr (kSurface) issue_surface(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
@@ -638,8 +600,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // (the last stage is the fourth of its group: parity 1)
     if constexpr (kDefer) retire(std::integral_constant<int, 1>{}, std::integral_constant<int, kPairs - 1>{});
     if constexpr (kSurface) {
-        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, FM - 1>{}, std::integral_constant<int, 0>{});
-        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, FM - 1>{}, std::integral_constant<int, 1>{});
+        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, kPairs - 1>{}, std::integral_constant<int, 0>{});
+        fold(std::integral_constant<int, 1>{}, std::integral_constant<int, kPairs - 1>{}, std::integral_constant<int, 1>{});
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------

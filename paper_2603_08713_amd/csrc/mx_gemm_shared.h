@@ -6,6 +6,7 @@
 #include <utility>
 
 #include "mx_common.h"
+#include "mx_gemm_schedule.h"
 
 namespace mx {
 
@@ -73,7 +74,6 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // One operand (A or B) of the tile as the loader sees it: buffer resources rebased to the tile's first
 // row and sized to its valid rows, so that rows past the end read as zero without any branch.

@@ -28,14 +28,14 @@ def gemm_operand_bytes(M: int, N: int, K: int, mbs: bool) -> float:
 
 
 # ---- secondary bound of the MBS GEMM: vector-ALU instruction issue -----------------------------------
-# A SIMD issues one vector-ALU instruction per 4 clocks for a 64-lane wavefront (16 lanes per clock; packed
-# fp32 is off in this build), and every scaled matrix instruction holds the same issue port for about 12 clocks
-# (measured on this device).  One macro block of a 32 x 32 output fragment is two 32x32x64 matrix instructions
-# = 2 * 32 * 32 * 128 FLOP; the correction adds `valu_per_fragment` vector instructions and
-# `extra_mfma_per_fragment` further matrix instructions to it.
+# Measured on this device: beside matrix instructions a SIMD issues one fp32 vector instruction per 4.6 clocks,
+# whichever of its wavefronts it comes from (packed fp32 is off in this build), and every matrix instruction holds
+# the same issue port for about 12 clocks.  One macro block of a 32 x 32 output fragment is two 32x32x64 matrix
+# instructions = 2 * 32 * 32 * 128 FLOP; the correction adds `valu_per_fragment` vector instructions to it and
+# brings the matrix instructions per fragment to `mfma_per_fragment`.
 SIMDS = 256 * 4
 CLOCK_GHZ = 2.4
-VALU_ISSUE_CLOCKS = 4
+VALU_ISSUE_CLOCKS = 4.6
 MFMA_ISSUE_CLOCKS = 12
 FRAGMENT_FLOP = 2.0 * 32 * 32 * 128
 

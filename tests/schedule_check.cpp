@@ -1,0 +1,146 @@
+// Host-side replay of the load schedule of the main GEMM kernel template (no GPU): for every instantiated tile
+// shape, with and without MBS words, and several K lengths, the prologue and every stage are replayed in the order
+// the kernel issues its direct-to-LDS loads, waits (s_waitcnt vmcnt) and passes its barriers, and these are checked:
+//   1. whatever a stage reads from LDS - the codes of stage s + 1, the E8M0 bytes of that stage's group, the MBS
+//      words that become the sigma table of stage s + 2 - was retired by a wait before the barrier that opens the
+//      stage (a wavefront's loads complete in the order it issued them, so "all but the n youngest" have landed);
+//   2. no load is issued into a slot whose contents another wavefront may still read, or that holds a stage not
+//      yet consumed;
+//   3. everything that is read was loaded, exactly once, and no load asks for a stage past the end of K;
+//   4. every wait count fits the 6-bit counter.
+// Prints one line per case; exits 1 at the first violation.  Compiled and run by tests/test_gemm_schedule.py.
+#include <cstdio>
+#include <cstdlib>
+#include <map>
+#include <tuple>
+#include <vector>
+
+#include "mx_gemm_schedule.h"
+
+namespace {
+
+struct Issued {
+    mx::LoadItem item;  // absolute: what = stage (codes) or group (others)
+    int at_stage;       // -1 = prologue
+};
+
+[[noreturn]] void fail(const char* shape, int nstages, const char* why, int a = 0, int b = 0, int c = 0) {
+    std::printf("FAIL %s nstages=%d: %s (%d, %d, %d)\n", shape, nstages, why, a, b, c);
+    std::exit(1);
+}
+
+template <typename S>
+void check(const char* name, int nstages) {
+    constexpr int C = S::kCodeDma, Sc = S::kScaleDma, W = S::kMbs ? S::kM8Dma : 0;
+    using Sched = mx::RingSchedule<C, Sc, W>;
+    std::vector<Issued> issued;
+    size_t landed = 0;  // loads [0, landed) have been retired by a wait
+    auto wait = [&](int n) {
+        if (n < 0 || n > 63) fail(name, nstages, "wait count outside the 6-bit counter", n);
+        const size_t keep = (size_t)n < issued.size() ? issued.size() - (size_t)n : 0;
+        if (keep > landed) landed = keep;
+    };
+    // how often each piece was issued, and whether it has landed
+    auto find = [&](int kind, int what, int index) -> int {
+        int pos = -1, count = 0;
+        for (size_t k = 0; k < issued.size(); ++k)
+            if (issued[k].item.kind == kind && issued[k].item.what == what && issued[k].item.index == index) {
+                pos = (int)k;
+                ++count;
+            }
+        if (count > 1) fail(name, nstages, "a piece is loaded twice", kind, what, index);
+        return pos;
+    };
+    auto need = [&](int kind, int what, int count, int reader_stage) {
+        for (int i = 0; i < count; ++i) {
+            const int pos = find(kind, what, i);
+            if (pos < 0) fail(name, nstages, "a piece that is read was never loaded", kind, what, reader_stage);
+            if ((size_t)pos >= landed) fail(name, nstages, "a piece is read before a wait has retired its load", kind, what, reader_stage);
+        }
+    };
+    auto issue = [&](mx::LoadItem abs, int t) {
+        if (abs.kind == mx::kLoadCode) {
+            if (abs.what >= nstages) fail(name, nstages, "codes requested past the end of K", abs.what, t);
+            // slot what % 4 held stage what - 4, which is read during stage what - 5; during stage t the other
+            // wavefronts read stage t + 1, and stages t + 2, t + 3 wait in their slots
+            if (t >= 0 && !(abs.what - 4 <= t && abs.what > t + 1 && (abs.what % 4) != ((t + 1) % 4)))
+                fail(name, nstages, "codes loaded into a slot that is still in use", abs.what, t);
+        } else if (abs.kind == mx::kLoadScale) {
+            // group G goes where group G - 2 was, whose bytes are last read during stage 4 (G - 2) + 2
+            if (t >= 0 && !(4 * (abs.what - 2) + 2 < t)) fail(name, nstages, "E8M0 bytes loaded into a slot still in use", abs.what, t);
+        } else {
+            // group G goes where group G - 2 was, whose words are last read (by the sigma conversion) during stage 4 (G - 2) + 1
+            if (t >= 0 && !(4 * (abs.what - 2) + 1 < t)) fail(name, nstages, "MBS words loaded into a slot still in use", abs.what, t);
+        }
+        issued.push_back({abs, t});
+    };
+    const int ngroups = nstages / 4;
+    // ---- prologue
+    for (int n = 0; n < Sched::prologue_count(); ++n) issue(Sched::prologue_item(n), -1);
+    wait(Sched::prologue_wait_first());
+    // (barrier) first LDS reads: E8M0 bytes and MBS words of group 0 (sigma tables of stages 0 and 1), codes of stage 0
+    need(mx::kLoadScale, 0, Sc, -1);
+    need(mx::kLoadWords, 0, W, -1);
+    need(mx::kLoadCode, 0, C, -1);
+    wait(Sched::prologue_wait_loop());
+    // ---- the loop
+    const int n_issue = nstages - 4 > 0 ? (nstages - 4 + 3) / 4 * 4 : 0;
+    for (int s = 0; s < nstages; ++s) {
+        const int phase = s % 4;
+        const bool does_issue = s < n_issue;
+        wait(does_issue ? Sched::wait_count(phase) : 0);
+        // (barrier) reads of this stage
+        if (s + 1 < nstages) {
+            need(mx::kLoadCode, s + 1, C, s);
+            need(mx::kLoadScale, (s + 1) / 4, Sc, s);
+        }
+        if (s + 2 < nstages) need(mx::kLoadWords, (s + 2) / 4, W, s);
+        if (does_issue)
+            for (int n = 0; n < Sched::issue_count(phase); ++n) {
+                mx::LoadItem it = Sched::issue_item(phase, n);
+                it.what += it.kind == mx::kLoadCode ? s : s / 4;
+                // (past the last group the kernel fetches the last group again: the slot rule still applies, but the
+                // load brings nothing new)
+                const bool repeat = it.kind != mx::kLoadCode && it.what >= ngroups;
+                issue(it, s);
+                if (repeat) issued.back().item.index += 1000;
+            }
+    }
+    // everything of every stage and group was loaded
+    for (int y = 0; y < nstages; ++y)
+        for (int i = 0; i < C; ++i)
+            if (find(mx::kLoadCode, y, i) < 0) fail(name, nstages, "codes of a stage never loaded", y, i);
+    std::printf("ok %s nstages=%d loads/wavefront: codes %d per stage, E8M0 %d and words %d per group; waits %d %d %d %d\n", name, nstages, C, Sc, W,
+                Sched::wait_count(0), Sched::wait_count(1), Sched::wait_count(2), Sched::wait_count(3));
+}
+
+template <typename S>
+void check_all(const char* name) {
+    static_assert(S::kLdsBytes <= 160 * 1024, "LDS");
+    for (int nstages : {4, 8, 12, 16, 64, 256}) check<S>(name, nstages);
+}
+
+}  // namespace
+
+#define SHAPE(...) check_all<mx::RingShape<__VA_ARGS__>>("RingShape<" #__VA_ARGS__ ">")
+
+int main() {
+    // every shape the library instantiates (tests/test_gemm_schedule.py compares this list with the sources)
+    SHAPE(2, 2, 4, 4, 0);
+    SHAPE(2, 2, 4, 2, 0);
+    SHAPE(2, 2, 2, 2, 0);
+    SHAPE(2, 2, 4, 2, 0, 1);
+    SHAPE(2, 2, 2, 2, 0, 1);
+    SHAPE(2, 2, 2, 2, 0, 2);
+    SHAPE(2, 4, 4, 1, 3);
+    SHAPE(2, 4, 4, 1, 1);
+    SHAPE(2, 4, 4, 1, 2);
+    SHAPE(2, 4, 2, 1, 3);
+    SHAPE(2, 4, 2, 1, 1);
+    SHAPE(2, 4, 2, 1, 2);
+    SHAPE(2, 4, 4, 1, 3, 1);
+    SHAPE(2, 4, 2, 1, 3, 1);
+    SHAPE(2, 4, 2, 1, 3, 2);
+    std::printf("all schedules hold\n");
+    return 0;
+}

@@ -614,8 +614,17 @@ def test_gemm_empty_and_zero_k(mx):
         assert float(out.abs().max()) == 0.0
 
 
+def fragment_rows(M, seed):
+    """One output row out of every 32-row fragment (every wavefront's every fragment of every tile-row is hit), at a
+    seeded offset; first and last row of the matrix included."""
+    rows = np.arange(0, M, 32) + np.random.default_rng(seed).integers(0, 32, size=(M + 31) // 32)
+    rows = np.minimum(rows, M - 1)
+    rows[0], rows[-1] = 0, M - 1
+    return rows.astype(np.int64)
+
+
 def test_gemm_full_size_sampled_rows(mx, oracle):
-    """Llama-3-8B FFN up-projection shape, as bench.py launches it; 24 sampled output rows are
+    """Llama-3-8B FFN up-projection shape; one output row of every 32-row fragment (128 rows, all columns) is
     checked against the fp64 oracle, all rows against cheap invariants."""
     from paper_2603_08713_amd import synth
 
@@ -629,8 +638,7 @@ def test_gemm_full_size_sampled_rows(mx, oracle):
     torch.cuda.synchronize()
     assert torch.equal(c16, c.to(torch.bfloat16))
     assert bool(torch.isfinite(c).all())
-    rows = np.sort(np.random.default_rng(9).choice(M, 24, replace=False))
-    rows[0], rows[-1] = 0, M - 1
+    rows = fragment_rows(M, 9)
     ah, bh = [host(t) for t in a], [host(t) for t in b]
     want = oracle.gemm(ah, bh, rows=rows)
     got = host(c[torch.from_numpy(rows).cuda()])
@@ -655,12 +663,12 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
     serve."""
     rng = np.random.default_rng(50 + shape)
     with mx.forced(gemm_shape=shape):
-        sizes = ((700, 530, 1536), (257, 300, 512)) + (((300, 260, 2880), (130, 129, 64)) if shape >= 8 else ())
+        sizes = ((700, 530, 1536), (257, 300, 512)) + (((300, 260, 2880), (130, 129, 64)) if shape in (8, 9, 10) else ())
         sizes += ((200, 140, 2016), (33, 50, 32)) if shape == 10 else ()
         for (M, N, K) in sizes:
             a, b = random_operand(rng, M, K), random_operand(rng, N, K)
             da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
-            for plain in ((True, False) if shape >= 8 else (shape in (2, 6, 7),)):
+            for plain in ((True, False) if shape in (8, 9, 10) else (shape in (2, 6, 7),)):
                 want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None)) if plain else oracle.gemm(a, b)
                 what = "%s shape %d %dx%dx%d" % ("plain" if plain else "mbs", shape, M, N, K)
                 c32 = gpu_gemm(mx, a, b, "f32", plain=plain)
@@ -688,8 +696,8 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
 
 
 def test_gemm_plain_full_size_sampled_rows(mx, oracle):
-    """The plain GEMM at the bench shape (it takes the 256 x 256 kernel there): sampled rows against the
-    oracle, bf16 output equal to the rounded fp32 output."""
+    """The plain GEMM at the Llama-3-8B FFN shape (it takes the 256 x 256 kernel there): one row of every 32-row
+    fragment against the oracle, bf16 output equal to the rounded fp32 output."""
     rng = np.random.default_rng(51)
     M, N, K = 4096, 14336, 4096
     a, b = random_operand(rng, M, K, 120, 134), random_operand(rng, N, K, 120, 134)
@@ -697,8 +705,7 @@ def test_gemm_plain_full_size_sampled_rows(mx, oracle):
     c = mx.mx_gemm(da[0], da[1], db[0], db[1], "f32")
     c16 = mx.mx_gemm(da[0], da[1], db[0], db[1], "bf16")
     assert torch.equal(c16, c.to(torch.bfloat16))
-    rows = np.sort(rng.choice(M, 16, replace=False))
-    rows[0], rows[-1] = 0, M - 1
+    rows = fragment_rows(M, 52)
     want = oracle.gemm((a[0], a[1], None), (b[0], b[1], None), rows=rows)
     assert_gemm_close(host(c[torch.from_numpy(rows).cuda()]), want, "plain llama8b sampled rows")
 
@@ -770,31 +777,55 @@ def test_config_decode_skinny(mx, oracle):
         assert torch.equal(mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "bf16"), c.to(torch.bfloat16))
 
 
-def test_config_llama70b_ffn_sampled(mx, oracle):
-    """M = 8192, N = 28672, K = 8192: quantized operands bit-exact on sampled rows, sampled output rows of
-    the MBS GEMM and of the plain GEMM against the oracle."""
-    from paper_2603_08713_amd import synth
+_LLAMA70B = {}
 
-    M, N, K = 8192, 28672, 8192
-    a_bits, w_bits = synth.llama70b_ffn(M, N, K)
-    a = mx.mx_quantize_mbs(dev_bf16(a_bits), "oas")
-    b = mx.mx_quantize_mbs(dev_bf16(w_bits), "oas")
-    rng = np.random.default_rng(70)
-    rows = np.sort(rng.choice(M, 8, replace=False))
-    rows[0], rows[-1] = 0, M - 1
-    wrows = np.sort(rng.choice(N, 64, replace=False))
+
+def llama70b_operands(mx):
+    """The Llama-3-70B FFN tensors, quantized on the GPU (shared by the two tests below: drawing them takes seconds)."""
+    if not _LLAMA70B:
+        from paper_2603_08713_amd import synth
+
+        a_bits, w_bits = synth.llama70b_ffn(8192, 28672, 8192)
+        _LLAMA70B.update(a_bits=a_bits, w_bits=w_bits, a=mx.mx_quantize_mbs(dev_bf16(a_bits), "oas"),
+                         b=mx.mx_quantize_mbs(dev_bf16(w_bits), "oas"))
+    return _LLAMA70B
+
+
+def test_config_llama70b_ffn_sampled(mx, oracle):
+    """M = 8192, N = 28672, K = 8192, the benchmark's shape and launch: quantized operands bit-exact on sampled
+    rows; the MBS GEMM against the oracle on one output row of every 32-row fragment (256 rows, all columns)."""
+    M, N = 8192, 28672
+    d = llama70b_operands(mx)
+    a, b = d["a"], d["b"]
+    rows = fragment_rows(M, 70)
+    wrows = np.sort(np.random.default_rng(70).choice(N, 64, replace=False))
     ah = [host(t[torch.from_numpy(rows).cuda()]) for t in a]
-    assert all(np.array_equal(x, y) for x, y in zip(ah, oracle.quantize(a_bits[rows], "oas", mbs=True)))
+    assert all(np.array_equal(x, y) for x, y in zip(ah, oracle.quantize(d["a_bits"][rows], "oas", mbs=True)))
     bw = [host(t[torch.from_numpy(wrows).cuda()]) for t in b]
-    assert all(np.array_equal(x, y) for x, y in zip(bw, oracle.quantize(w_bits[wrows], "oas", mbs=True)))
+    assert all(np.array_equal(x, y) for x, y in zip(bw, oracle.quantize(d["w_bits"][wrows], "oas", mbs=True)))
     bh = [host(t) for t in b]
     c = mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "bf16")
     c32 = mx.mx_gemm_mbs(a[0], a[1], a[2], b[0], b[1], b[2], "f32")
     assert torch.equal(c, c32.to(torch.bfloat16))
-    assert_gemm_close(host(c32[torch.from_numpy(rows).cuda()]), oracle.gemm(ah, bh), "llama70b mbs sampled rows")
+    assert bool(torch.isfinite(c32).all())
+    assert_gemm_close(host(c32[torch.from_numpy(rows).cuda()]), oracle.gemm(ah, bh), "llama70b mbs, a row of every fragment")
+
+
+def test_config_llama70b_ffn_plain_sampled(mx, oracle):
+    """The same shape without MBS words (256 x 256 tiles): two rows of every 256-row tile-row, in different
+    fragments, against the oracle (64 rows, all columns)."""
+    M = 8192
+    d = llama70b_operands(mx)
+    a, b = d["a"], d["b"]
+    rows = fragment_rows(M, 71)
+    rows = np.sort(np.concatenate([rows[(np.arange(32) * 8 + np.arange(32) % 8)], rows[(np.arange(32) * 8 + (np.arange(32) + 4) % 8)]]))
+    ah = [host(t[torch.from_numpy(rows).cuda()]) for t in a]
+    bh = [host(t) for t in b]
     p32 = mx.mx_gemm(a[0], a[1], b[0], b[1], "f32")
+    assert torch.equal(mx.mx_gemm(a[0], a[1], b[0], b[1], "bf16"), p32.to(torch.bfloat16))
     want = oracle.gemm((ah[0], ah[1], None), (bh[0], bh[1], None))
     assert_gemm_close(host(p32[torch.from_numpy(rows).cuda()]), want, "llama70b plain sampled rows")
+    _LLAMA70B.clear()
 
 
 def test_config_moe_grouped_sampled(mx, oracle):
