@@ -61,6 +61,12 @@ def lib() -> ctypes.CDLL:
         L.mxo_mbs_sse_rows.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp]
         L.mxo_quantize_mbs_dynamic.restype = ci
         L.mxo_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+        L.mxo_mbs_lut_entry.restype = dbl
+        L.mxo_mbs_lut_entry.argtypes = [ci, ci, ci]
+        L.mxo_mbs_lut_cost.restype = dbl
+        L.mxo_mbs_lut_cost.argtypes = [vp, ci, ci, ci, ci, vp]
+        L.mxo_quantize_mbs_dynamic_lut.restype = ci
+        L.mxo_quantize_mbs_dynamic_lut.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, ci, vp, vp, vp]
         L.mxo_dequantize.restype = ci
         L.mxo_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp]
         L.mxo_gemm_rows.restype = ci
@@ -205,6 +211,44 @@ def mbs_sse_rows(x_bf16: np.ndarray, words: np.ndarray, rule="oas", block: int =
     if rc != 0:
         raise ValueError("mxo_mbs_sse_rows: bad arguments")
     return out
+
+
+def mbs_lut_entry(table: int, p: int, j: int) -> float:
+    """Definition of an entry of the table of Eq. 5 in fp64 (table 0 = sub-normal, 1 = normal; point p; slot j)."""
+    return lib().mxo_mbs_lut_entry(int(table), int(p), int(j))
+
+
+def mbs_lut() -> np.ndarray:
+    """The 2 x 64 x 16 table of Eq. 5 as fp16 bit patterns (uint16), every entry the fp64 definition rounded to
+    fp16 (nearest even, by numpy)."""
+    t = np.array([[[mbs_lut_entry(tb, p, j) for j in range(16)] for p in range(64)] for tb in range(2)], np.float64)
+    return t.astype(np.float16).view(np.uint16)
+
+
+def mbs_lut_cost(xm_bf16: np.ndarray, j: int, lut: np.ndarray, rule="oas", block: int = 32) -> float:
+    """Eq. 6's sum for candidate j (word 16 j) on one macro block (1-D bf16 bit patterns)."""
+    xm = np.ascontiguousarray(xm_bf16, dtype=np.uint16)
+    lut = np.ascontiguousarray(lut, np.uint16)
+    assert lut.size == 2048
+    return float(lib().mxo_mbs_lut_cost(_ptr(xm), xm.size, int(j), _rule(rule), block, _ptr(lut)))
+
+
+def quantize_mbs_dynamic_lut(x_bf16: np.ndarray, lut: np.ndarray, rule="oas", keep_static: bool = True, block: int = 32,
+                             macro: int = 128):
+    """MBS-Dynamic with the table of Eq. 5: per macro block the word 16 j* of least tabulated cost (or the static
+    word if its true error is not larger and keep_static). Returns (codes, scales, words)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    lut = np.ascontiguousarray(lut, np.uint16)
+    assert lut.size == 2048
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    words = np.zeros((rows, (K + macro - 1) // macro), np.uint8)
+    rc = lib().mxo_quantize_mbs_dynamic_lut(_ptr(x), rows, K, K, _rule(rule), block, macro, _ptr(lut), int(bool(keep_static)),
+                                            _ptr(codes), _ptr(scales), _ptr(words))
+    if rc != 0:
+        raise ValueError("mxo_quantize_mbs_dynamic_lut: bad arguments")
+    return codes, scales, words
 
 
 def dequantize(codes, scales, mbs=None, block: int = 32, macro: int = 128) -> np.ndarray:

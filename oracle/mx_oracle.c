@@ -310,6 +310,116 @@ int mxo_quantize_mbs_dynamic(const uint16_t* x, int64_t rows, int64_t K, int64_t
     return 0;
 }
 
+/* ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3, "Memoization Strategy") --------------------- */
+
+/* Eq. 5-6 replace the error of every element by a tabulated squared RELATIVE error
+ *     T[v, m_j]  ~  ((x_hat - x) / x)^2,    v = |x| SF   (the element in the block's scaled domain, before the
+ *                                                        candidate factor is applied; SF = 2^s is the local scale
+ *                                                        that the rule derives from the block's absmax times F_j)
+ * so that a candidate's sum of squared errors is  sum_i x_i^2 T[v_ij, m_j]  (Eq. 6): one table read and one
+ * multiply-add per element and candidate.  The paper gives the table's size, not its contents: two tables
+ * ("sub-normal" v < 1 and "normal" v >= 1) of 64 points x 16 slots in fp16.  Reading taken here:
+ *   - the 16 slots ARE the 16 candidates, absolute words m_j = 16 j (factors F_j = 1 + j/16): the relative
+ *     error depends on the factor itself, so a table with 16 slots can only serve 16 fixed factors;
+ *   - normal table: point p = the 6 leading mantissa bits of v.  E2M1 has one mantissa bit in every binade and
+ *     nothing saturates below 7 (a block's scaled absmax never exceeds 7 under OAS), so the relative error of
+ *     v F_j repeats from binade to binade and the mantissa is all that matters.  The entry is the squared
+ *     relative error at the middle of the bin, v = 1 + (p + 1/2)/64;
+ *   - sub-normal table: point p = floor(64 v), entry at v = (p + 1/2)/64 (the grid below 1 is {0, 1/2, 1}: the
+ *     error is not periodic there);
+ *   - entries are rounded to fp16 (nearest even); the caller passes the 2 x 64 x 16 table as fp16 bit patterns,
+ *     index (table * 64 + p) * 16 + j, table 0 = sub-normal.
+ * mxo_mbs_lut_entry is the definition of an entry in fp64 (the rounding to fp16 is the caller's).  */
+double mxo_mbs_lut_entry(int table, int p, int j) {
+    const double F = 1.0 + j / 16.0;
+    const double v = table ? 1.0 + (p + 0.5) / 64.0 : (p + 0.5) / 64.0;
+    const double t = v * F;                              /* below 4: no saturation */
+    const double q = E2M1_VALUE[mxo_e2m1_nearest(t)];
+    const double rel = (q / F - v) / v;
+    return rel * rel;
+}
+
+static double half_bits_value(uint16_t h) { /* fp16 bit pattern -> value (finite patterns) */
+    const int e = (h >> 10) & 31, m = h & 1023;
+    const double v = e ? ldexp(1024.0 + m, e - 25) : ldexp((double)m, -24);
+    return (h & 0x8000u) ? -v : v;
+}
+
+/* Point of the table for a scaled magnitude v > 0: *table = 1 (normal) with the 6 leading mantissa bits,
+ * or 0 (sub-normal) with floor(64 v). */
+static int lut_point(double v, int* table) {
+    if (v >= 1.0) {
+        int ex;
+        const double fr = frexp(v, &ex);                 /* v = fr 2^ex, fr in [0.5, 1): mantissa 2 fr in [1, 2) */
+        *table = 1;
+        return (int)floor((2.0 * fr - 1.0) * 64.0);
+    }
+    *table = 0;
+    return (int)floor(v * 64.0);
+}
+
+/* Eq. 6's sum for candidate j (word 16 j) on the macro block xm[0..n), all elements finite:
+ * sum_i x_i^2 T[v_ij, j] in fp64, elements in order.  Returns -1 if an element is not finite. */
+double mxo_mbs_lut_cost(const uint16_t* xm, int n, int j, int rule, int block, const uint16_t* lut) {
+    const double F = 1.0 + j / 16.0;
+    double cost = 0.0;
+    for (int b0 = 0; b0 < n; b0 += block) {
+        double amax = 0.0;
+        for (int k = b0; k < b0 + block; ++k) {
+            if (!is_finite_bf16(xm[k])) return -1.0;
+            amax = fmax(amax, fabs(mxo_bf16_value(xm[k]) * F));
+        }
+        if (amax == 0.0) continue;
+        const int s = 127 - mxo_e8m0_from_exponent(mxo_scale_exponent(amax, rule));
+        for (int k = b0; k < b0 + block; ++k) {
+            const double x = mxo_bf16_value(xm[k]);
+            if (x == 0.0) continue;
+            int table;
+            const int p = lut_point(ldexp(fabs(x), s), &table);
+            cost += x * x * half_bits_value(lut[(table * 64 + p) * 16 + j]);
+        }
+    }
+    return cost;
+}
+
+/* Quantize with the word the table picks: j* = argmin_j of Eq. 6's sum over the 16 candidates (ties: the lowest
+ * j), word 16 j*.  With keep_static != 0 the static word of Eq. 3 is kept instead whenever its TRUE sum of squared
+ * errors (mxo_mbs_sse) is not larger than that of the picked word, so that the result is never worse than MBS-S
+ * (not in the paper: the table cannot price the static word, which is not one of its 16 slots).  A macro block
+ * holding a non-finite element keeps the static word.  Arguments otherwise as mxo_quantize. */
+int mxo_quantize_mbs_dynamic_lut(const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule, int block,
+                                 int macro, const uint16_t* lut, int keep_static, uint8_t* codes,
+                                 uint8_t* scales, uint8_t* mbs) {
+    if (rows < 0 || K < 0 || ldx < K || block <= 0 || (block & 1) || macro % block || K % block || !lut)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * ldx;
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            const int n = (int)(k1 - k0);
+            const int m_static = mxo_mbs_static_m8(macro_absmax(xr, k0, k1));
+            int best = m_static;
+            double best_cost = mxo_mbs_lut_cost(xr + k0, n, 0, rule, block, lut);
+            if (best_cost >= 0.0) {
+                int jbest = 0;
+                for (int j = 1; j < 16; ++j) {
+                    const double c = mxo_mbs_lut_cost(xr + k0, n, j, rule, block, lut);
+                    if (c < best_cost) { best_cost = c; jbest = j; }
+                }
+                best = 16 * jbest;
+                if (keep_static && mxo_mbs_sse(xr + k0, n, m_static, rule, block) <= mxo_mbs_sse(xr + k0, n, best, rule, block))
+                    best = m_static;
+            }
+            mbs[r * nmac + g] = (uint8_t)best;
+            quantize_macro_block(xr, k0, k1, best, rule, block, codes + r * (K / 2), scales + r * nblk);
+        }
+    }
+    return 0;
+}
+
 /* ---- dequantizer (Sec. 4.3.1: value = code * 2^(E-127) / F) --------------------------------- */
 
 static double scale_value(int E) { return (E == 255) ? NAN : ldexp(1.0, E - 127); }
