@@ -290,7 +290,8 @@ def qsnr_weights_gpu(mx, torch, x):
     res = {}
     ref = x.to(torch.float64)
     for name, q in (("+oas", mx.mx_quantize(x, "oas") + (None,)), ("+oas+mbs-s", mx.mx_quantize_mbs(x, "oas")),
-                    ("+oas+mbs-d", mx.mx_quantize_mbs_dynamic(x, "oas"))):
+                    ("+oas+mbs-d", mx.mx_quantize_mbs_dynamic(x, "oas")),
+                    ("+oas+mbs-d(table)", mx.mx_quantize_mbs_dynamic_lut(x, mx.mx_mbs_lut_build(), "oas"))):
         back = mx.mx_dequantize(q[0], q[1], q[2], "f32").to(torch.float64)
         res[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum())), 3)
     res["sample"] = "first %d rows of W" % QSNR_ROWS
@@ -390,6 +391,11 @@ def quantizer_extras(mx, torch, metrics, work, args):
                                  "gbps": round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_MBS / (ms_dyn * 1e-3) / 1e9, 1),
                                  "candidates": "static word + 16 equally spaced",
                                  "paper_context": "paper reports its MBS-D kernel 2.5-3x slower than MBS-S (NVIDIA B200)"}
+    lut = mx.mx_mbs_lut_build()
+    ms_lut = time_loop(torch, lambda i: mx.mx_quantize_mbs_dynamic_lut(xw[i % len(xw)], lut, "oas", True, *qw[i % len(qw)]), n)
+    res["quantize_dynamic_table_W"] = {"ms": round(ms_lut, 4), "slowdown_vs_static": round(ms_lut / ms_s, 2),
+                                       "gbps": round(xw[0].numel() * metrics.QUANT_BYTES_PER_ELT_MBS / (ms_lut * 1e-3) / 1e9, 1),
+                                       "candidates": "words 16 j priced by the 2 x 64 x 16 fp16 table of Eq. 5; static word kept if not worse"}
     # the timing loop above rewrote qw with searched words: put the static ones back for what follows
     for i in range(len(qw)):
         mx.mx_quantize_mbs(xw[i % len(xw)], "oas", *qw[i])
@@ -607,7 +613,8 @@ def cpu_baseline(np, synth, a_bits, w_bits, M, N, K, brief):
     refw = oracle.bf16_to_f64(xw)
     ladder_w = {}
     for name, q in (("+oas", oracle.quantize(xw, "oas")), ("+oas+mbs-s", oracle.quantize(xw, "oas", mbs=True)),
-                    ("+oas+mbs-d", oracle.quantize_mbs_dynamic(xw, "oas"))):
+                    ("+oas+mbs-d", oracle.quantize_mbs_dynamic(xw, "oas")),
+                    ("+oas+mbs-d(table)", oracle.quantize_mbs_dynamic_lut(xw, oracle.mbs_lut(), "oas"))):
         ladder_w[name] = round(oracle.qsnr_db(refw, oracle.dequantize(q[0], q[1], q[2])), 3)
     res["qsnr_db_oracle_weights"] = ladder_w
     a_s, w_s = a_bits[:QSNR_AB_ROWS], w_bits[:QSNR_AB_COLS]

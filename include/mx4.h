@@ -85,7 +85,7 @@ int mx_quantize_mbs_pair(const void* x0_bf16, int64_t rows0, int64_t ldx0,
                          uint8_t* codes1, uint8_t* scales1, uint8_t* mbs1,
                          int64_t K, mx_rule_t rule, void* stream);
 
-/* MBS-Dynamic quantization (Sec. 4.3.1 "Dynamic", Sec. 5.3; meant for weights, which are quantized
+/* MBS-Dynamic quantization (Sec. 4.3.3, Sec. 5.3; meant for weights, which are quantized
  * offline: MBS-Hybrid = this for B, mx_quantize_mbs for A): as mx_quantize_mbs, but the word of each
  * window is searched for the least sum of squared errors of the window among the static word and
  *     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,   j = 0 .. cand_count-1
@@ -98,6 +98,27 @@ int mx_quantize_mbs_pair(const void* x0_bf16, int64_t rows0, int64_t ldx0,
 int mx_quantize_mbs_dynamic(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                             int32_t cand_first, int32_t cand_count, int32_t cand_stride,
                             uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
+/* The table MBS-Dynamic reads in the paper (Sec. 4.3.3, Eq. 5): squared relative errors
+ * T[v, m_j] ~ ((x_hat - x) / x)^2 of an element whose magnitude in its block's scaled domain is v = |x| SF, under
+ * candidate word m_j.  Two tables of 64 points x 16 slots in fp16 (the paper gives this shape, not the contents);
+ * here slot j is the word 16 j (factor 1 + j/16); the "normal" table (v >= 1) is indexed by the 6 leading
+ * mantissa bits of v, the "sub-normal" one (v < 1) by floor(64 v); an entry is the squared relative error at the
+ * middle of its bin, computed in fp64 and rounded once to fp16.  Writes lut_fp16[(table * 64 + p) * 16 + j]
+ * (2048 fp16 bit patterns = 4096 bytes, DEVICE memory, 16-byte aligned; table 0 = sub-normal). */
+int mx_mbs_lut_build(uint16_t* lut_fp16, void* stream);
+
+/* MBS-Dynamic quantization through that table (Sec. 4.3.3, Eq. 4-6): per 1x128 window the candidate j* of least
+ * sum_i x_i^2 T[v_ij, j] (Eq. 6; v_ij taken with the local scale the rule derives from the block's absmax times
+ * 1 + j/16; sums in fp32; ties to the lowest j) gives the word 16 j*.  With keep_static != 0 the static word of
+ * Eq. 3 is kept instead whenever its own sum of squared errors, evaluated directly, is not larger than that of
+ * the picked word, so that no window comes out worse than with mx_quantize_mbs (not in the paper: the table has
+ * no slot for the static word).  lut_fp16: the table in the layout above (mx_mbs_lut_build fills it; a caller
+ * may pass its own), DEVICE memory, 16-byte aligned, read during the call.  Windows holding Inf/NaN, and windows
+ * whose absmax is below 2^-63 or at least 2^123, keep the static word.  Outputs as mx_quantize_mbs. */
+int mx_quantize_mbs_dynamic_lut(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                const uint16_t* lut_fp16, int keep_static,
+                                uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
 /* Reconstruct x_hat = value(code) * 2^(E-127) / F (Sec. 4.3.1) into out [rows, ldo] of
  * `out_dtype` (fp32: correctly rounded; bf16: that fp32 value rounded to nearest even).
@@ -124,8 +145,7 @@ int mx_gemm_mbs(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
                 int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc,
                 void* stream);
 
-/* Few-row (decode) form with the activations quantized on the fly (Sec. 4.3: activations are
- * "quantized on-the-fly"; Sec. 5.3): C = Q(A) * B^T where Q is mx_quantize_mbs(rule) if a_use_mbs != 0,
+/* Few-row (decode) form with the activations quantized inside the GEMM kernel (Sec. 4.3, Sec. 5.3): C = Q(A) * B^T where Q is mx_quantize_mbs(rule) if a_use_mbs != 0,
  * else mx_quantize(rule), applied inside the GEMM kernel to a_bf16 [M, lda] (bf16, row-major, 16-byte
  * aligned, lda % 8 == 0, lda >= K); the quantized activations are never written to memory.  The result
  * is bit-identical to mx_quantize_mbs / mx_quantize followed by mx_gemm_mbs on the same weights.

@@ -53,6 +53,10 @@ def load_library() -> ctypes.CDLL:
     L.mx_quantize_mbs_dynamic.restype = ci
     L.mx_quantize_mbs_dynamic.argtypes = [vp, i64, i64, i64, ci, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                           vp, vp, vp, vp]
+    L.mx_mbs_lut_build.restype = ci
+    L.mx_mbs_lut_build.argtypes = [vp, vp]
+    L.mx_quantize_mbs_dynamic_lut.restype = ci
+    L.mx_quantize_mbs_dynamic_lut.argtypes = [vp, i64, i64, i64, ci, vp, ci, vp, vp, vp, vp]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, vp, i64, vp]
     L.mx_gemm.restype = ci
@@ -256,6 +260,30 @@ def mx_quantize_mbs_dynamic(x, rule="oas", cand_first=0, cand_count=16, cand_str
     _check(load_library().mx_quantize_mbs_dynamic(_ptr(x), rows, K, ldx, _rule(rule), int(cand_first),
                                                   int(cand_count), int(cand_stride), _ptr(codes), _ptr(scales),
                                                   _ptr(mbs), _stream()), "mx_quantize_mbs_dynamic")
+    return codes, scales, mbs
+
+
+def mx_mbs_lut_build(lut=None):
+    """The table of squared relative errors MBS-Dynamic reads (2 x 64 points x 16 slots, fp16 bit patterns as int16)."""
+    torch = _torch()
+    if lut is None:
+        lut = torch.empty((2, 64, 16), dtype=torch.int16, device="cuda")
+    if lut.dtype != torch.int16 or not lut.is_cuda or not lut.is_contiguous() or lut.numel() != 2048:
+        raise TypeError("lut must be a contiguous int16 CUDA tensor of 2048 elements")
+    _check(load_library().mx_mbs_lut_build(_ptr(lut), _stream()), "mx_mbs_lut_build")
+    return lut
+
+
+def mx_quantize_mbs_dynamic_lut(x, lut, rule="oas", keep_static=True, codes=None, scales=None, mbs=None):
+    """MBS-Dynamic quantization through the table (word 16 j* of least tabulated cost per 1x128 window) -> (codes, scales, mbs)."""
+    torch = _torch()
+    rows, K, ldx = _rows_ld(x)
+    if lut.dtype != torch.int16 or not lut.is_cuda or not lut.is_contiguous() or lut.numel() != 2048:
+        raise TypeError("lut must be a contiguous int16 CUDA tensor of 2048 elements")
+    codes, scales, mbs = _alloc_outputs(x, rows, K, codes, scales, mbs, True)
+    _check(load_library().mx_quantize_mbs_dynamic_lut(_ptr(x), rows, K, ldx, _rule(rule), _ptr(lut), int(bool(keep_static)),
+                                                      _ptr(codes), _ptr(scales), _ptr(mbs), _stream()),
+           "mx_quantize_mbs_dynamic_lut")
     return codes, scales, mbs
 
 

@@ -14,7 +14,7 @@
 // blocks: four 16-byte code pieces per fragment, the 16 E8M0 bytes of the row as one 16-byte piece (each
 // instruction takes its byte by shifting), the row's four MBS words as one dword.
 //
-// Fused form (activations quantized on the fly, Sec. 4.3 / 5.3: "quantized on-the-fly"): instead of
+// Fused form (activations quantized inside this kernel, Sec. 4.3 / 5.3): instead of
 // codes the lane fetches the 32 bf16 of its row and k-block (four 16-byte pieces), which is exactly one
 // E8M0 block, so its absmax needs no exchange; the macro-block absmax is the maximum over the four lanes
 // 16 apart.  MBS word, scale byte and codes follow the quantizer's arithmetic to the bit, the 16 bytes of

@@ -366,6 +366,198 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
     }
 }
 
+// ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3, "Memoization Strategy") ----------------------------
+// Eq. 5-6 price a candidate factor by a table of squared relative errors, T[v, m_j] ~ ((x_hat - x) / x)^2 with
+// v = |x| SF the element in its block's scaled domain, so that a candidate's sum of squared errors is
+// sum_i x_i^2 T[v_ij, m_j].  The table is 2 x 64 points x 16 slots of fp16 (4 KiB, held in LDS): slot j is the
+// candidate word 16 j; the "normal" table (v >= 1) is indexed by the 6 leading mantissa bits of v (E2M1's relative
+// error repeats from binade to binade), the "sub-normal" one (v < 1) by floor(64 v); an entry is the squared
+// relative error at the middle of its bin.  A point's 16 slots lie side by side, so one element costs two 16-byte
+// LDS reads and sixteen multiply-adds that take the fp16 entry as it stands (v_fma_mix_f32) for all candidates.
+// The candidates only differ in F_j = 1 + j/16 < 2, so a block's local scale takes at most two values over them,
+// SF and SF/2 from some j on: both points of an element are priced and each candidate takes the sum that
+// belongs to its scale.
+struct LutArgs {
+    QuantArgs q;
+    const uint16_t* lut;
+    int keep_static;
+};
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+
+// fp64 -> fp16 bit pattern, round to nearest even (values in [0, 2): no overflow)
+__device__ __forceinline__ uint32_t f64_to_f16_bits(double v) {
+    const uint64_t u = (uint64_t)__double_as_longlong(v);
+    const int e = (int)((u >> 52) & 0x7FF) - 1023;  // v = 1.m * 2^e
+    if ((u << 1) == 0) return 0;
+    uint64_t m = (u & 0xFFFFFFFFFFFFFull) | (1ull << 52);  // 53 bits, value m * 2^(e - 52)
+    int shift;                                              // result = round(m >> shift) in units of the fp16 ulp
+    uint32_t base;
+    if (e >= -14) { shift = 42; base = (uint32_t)(e + 15 - 1) << 10; }  // normal: 10 mantissa bits, the leading 1 adds to the exponent field
+    else { shift = 42 + (-14 - e); base = 0; }                           // subnormal: ulp 2^-24
+    if (shift > 63) return 0;
+    const uint64_t q = m >> shift, rem = m & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    const uint64_t r = q + ((rem > half || (rem == half && (q & 1))) ? 1 : 0);
+    return base + (uint32_t)r;
+}
+
+// Entry (table, p, j) of the table, as defined above, in fp64 and rounded once to fp16.
+__global__ void mbs_lut_build_kernel(uint16_t* lut) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= 2048) return;
+    const int j = idx & 15, p = (idx >> 4) & 63, table = idx >> 10;
+    const double F = 1.0 + j / 16.0;
+    const double v = table ? 1.0 + (p + 0.5) / 64.0 : (p + 0.5) / 64.0;
+    const double t = v * F;  // below 4: the E2M1 grid {0, .5, 1, 1.5, 2, 3, 4}, ties to the even code
+    double qv;
+    if (t <= 0.25) qv = 0.0;
+    else if (t < 0.75) qv = 0.5;
+    else if (t <= 1.25) qv = 1.0;
+    else if (t < 1.75) qv = 1.5;
+    else if (t <= 2.5) qv = 2.0;
+    else if (t < 3.5) qv = 3.0;
+    else qv = 4.0;
+    const double rel = (qv / F - v) / v;
+    lut[idx] = (uint16_t)f64_to_f16_bits(rel * rel);
+}
+
+__device__ __forceinline__ float dpp_row_ror4_f(float v) { return __uint_as_float(dpp_row_ror4(__float_as_uint(v))); }
+__device__ __forceinline__ float dpp_row_ror8_f(float v) { return __uint_as_float(dpp_row_ror8(__float_as_uint(v))); }
+
+__global__ __launch_bounds__(kThreads) void quantize_dynamic_lut_kernel(LutArgs d) {
+    __shared__ __attribute__((aligned(16))) uint16_t table[2048];
+    reinterpret_cast<u32x4*>(table)[threadIdx.x] = reinterpret_cast<const u32x4*>(d.lut)[threadIdx.x];  // 256 threads x 16 B
+    __syncthreads();
+    const QuantArgs& q = d.q;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kThreads / kWave);
+    for (uint32_t c = wave; c < q.total_chunks; c += nwaves) {
+        const uint32_t row = c / q.chunks_per_row, col = (c - row * q.chunks_per_row) * kChunk + lane * 8;
+        const bool valid = col < q.K;
+        u32x4 v = {0, 0, 0, 0};
+        if (valid) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q.x + (int64_t)row * q.ldx + col));
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+
+        // absmax over the finite elements of the lane, block and macro block; Inf/NaN flag of the macro block
+        uint32_t amax = 0, nf = 0;
+        float xf[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+            if (lo >= 0x7F80u) nf = 1; else amax = max(amax, lo);
+            if (hi >= 0x7F80u) nf = 1; else amax = max(amax, hi);
+            xf[2 * i] = __uint_as_float(w[i] << 16);
+            xf[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+        nf |= dpp_quad_xor1(nf);
+        nf |= dpp_quad_xor2(nf);
+        const uint32_t nf_block = nf;
+        nf |= dpp_row_ror4(nf);
+        nf |= dpp_row_ror8(nf);
+        amax = max(amax, dpp_quad_xor1(amax));
+        amax = max(amax, dpp_quad_xor2(amax));
+        uint32_t mmax = max(amax, dpp_row_ror4(amax));
+        mmax = max(mmax, dpp_row_ror8(mmax));
+
+        const uint32_t m_static = mbs_word_of_absmax(mmax);
+        const uint32_t e128 = mmax >> 7;
+        const bool searchable = !nf && e128 >= 64u && e128 <= 249u;
+        // (a block more than 30 binades below its window prices at nothing: its x^2 is below 2^-60 of the window's)
+        const bool counts = amax != 0 && (amax >> 7) + 30u >= e128;
+
+        // the block's scale byte without a factor, and from which candidate on it is one higher (scale halved)
+        const float amax_f = __uint_as_float(amax << 16);
+        const uint32_t E0 = ((__float_as_uint(amax_f) + q.carry) >> 23) - 2u;
+        uint32_t halved = 0;  // bit j: candidate j quantizes this block with SF / 2
+#pragma unroll
+        for (int j = 1; j < 16; ++j) {
+            const float scaled = amax_f * __uint_as_float(0x3F800000u | ((uint32_t)j << 19));  // absmax * (1 + j/16), exact
+            const uint32_t Ej = ((__float_as_uint(scaled) + q.carry) >> 23) - 2u;
+            halved |= (Ej != E0 ? 1u : 0u) << j;
+        }
+        // elements in the block's scaled domain, v = |x| 2^(127 - E0), and, for the sums, in the window's: xn = x 2^(127 - e128)
+        const float to_block = __uint_as_float(counts ? (254u - E0) << 23 : 0u);
+        const float to_window = __uint_as_float(searchable ? (254u - e128) << 23 : 0u);
+        float cost_hi[16], cost_lo[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost_hi[j] = cost_lo[j] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float vh = __builtin_fabsf(xf[i]) * to_block;  // exact; at most 8
+            const float xn = xf[i] * to_window, x2 = xn * xn;
+            const uint32_t vb = __float_as_uint(vh);
+            // points of v and of v / 2: normal table rows 64 .. 127 by the mantissa, sub-normal rows 0 .. 63 by floor(64 v)
+            const uint32_t mant = (vb >> 17) & 63u;
+            const uint32_t sub = (uint32_t)(vh * 64.0f);  // (only used below 1)
+            const uint32_t row_hi = vh >= 1.0f ? 64u + mant : sub;
+            const uint32_t row_lo = vh >= 2.0f ? 64u + mant : vh >= 1.0f ? 32u + (mant >> 1) : sub >> 1;
+            const h8* ph = reinterpret_cast<const h8*>(table + row_hi * 16);
+            const h8* pl = reinterpret_cast<const h8*>(table + row_lo * 16);
+            const h8 h0 = ph[0], h1 = ph[1], l0 = pl[0], l1 = pl[1];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                cost_hi[j] = __builtin_fmaf(x2, (float)h0[j], cost_hi[j]);
+                cost_hi[8 + j] = __builtin_fmaf(x2, (float)h1[j], cost_hi[8 + j]);
+                cost_lo[j] = __builtin_fmaf(x2, (float)l0[j], cost_lo[j]);
+                cost_lo[8 + j] = __builtin_fmaf(x2, (float)l1[j], cost_lo[8 + j]);
+            }
+        }
+        // every candidate takes the sum of its scale, then the sums of the window's 16 lanes are added up
+        float cost[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost[j] = (halved >> j) & 1u ? cost_lo[j] : cost_hi[j];
+        // (step by step over all candidates: sixteen independent chains leave no wait state between an add and the next)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost[j] += dpp_quad_xor1_f(cost[j]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost[j] += dpp_quad_xor2_f(cost[j]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost[j] += dpp_row_ror4_f(cost[j]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cost[j] += dpp_row_ror8_f(cost[j]);
+        uint32_t j_best = 0;
+        float best = cost[0];
+#pragma unroll
+        for (int j = 1; j < 16; ++j) {
+            if (cost[j] < best) {
+                best = cost[j];
+                j_best = (uint32_t)j;
+            }
+        }
+        uint32_t m_pick = searchable ? 16u * j_best : m_static;
+        // codes and scale byte of the picked word; with keep_static the static word stays unless the picked one's
+        // true sum of squared errors (the fp32 sum of the exact search) is smaller
+        Candidate cand = eval_candidate(xf, amax, counts, e128, m_pick, q.carry);
+        if (d.keep_static && m_pick != m_static) {
+            const Candidate stat = eval_candidate(xf, amax, counts, e128, m_static, q.carry);
+            if (stat.cost <= cand.cost) {
+                cand = stat;
+                m_pick = m_static;
+            }
+        }
+        const bool odd = nf_block || (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
+        ChunkResult res = {cand.codes, cand.E, m_pick};
+        if (__builtin_amdgcn_ballot_w64(odd) != 0) res = quantize_chunk_exact(v, q.rule, 1, (int)m_pick);
+
+        uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
+        if ((lane & 3) != 0) ew = 0;
+        ew |= dpp_row_ror4(ew);
+        ew |= dpp_row_ror8(ew);
+        if (!valid) continue;
+        const uint32_t kblk = col >> 5;
+        uint8_t* srow = q.scales + (int64_t)row * (q.K >> 5);
+        uint8_t* crow = q.codes + (int64_t)row * (q.K >> 1);
+        *reinterpret_cast<uint32_t*>(crow + (col >> 1)) = res.codes;
+        if (q.scales_dword) {
+            if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
+        } else if ((lane & 3) == 0) {
+            srow[kblk] = (uint8_t)res.E;
+        }
+        if ((lane & 15) == 0) q.mbs[(int64_t)row * q.nmac + (col >> 7)] = (uint8_t)res.m8;
+    }
+}
+
 int launch_filled(const QuantArgs& q, int use_mbs, void* stream, bool hwcvt = true);
 
 // argument checks and the fields common to both quantizer kernels; MX_OK with *empty set means nothing to do
@@ -479,10 +671,42 @@ int launch_quantize_dynamic(const void* x, int64_t rows, int64_t K, int64_t ldx,
     return launch_status();
 }
 
+int launch_quantize_dynamic_lut(const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, const uint16_t* lut,
+                                int keep_static, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {
+    LutArgs d;
+    bool empty;
+    if (int st = fill_quant_args(d.q, &empty, x, rows, K, ldx, rule, 1, codes, scales, mbs, false)) return st;
+    if (empty) return MX_OK;
+    if (!lut) return MX_ENULL;
+    if (!aligned(lut, 16)) return MX_EALIGN;
+    if (int st = check_device()) return st;
+    d.lut = lut;
+    d.keep_static = keep_static != 0;
+    int64_t blocks = ((int64_t)d.q.total_chunks + (kThreads / kWave) - 1) / (kThreads / kWave);
+    const int64_t max_blocks = 1 << 20;
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL(quantize_dynamic_lut_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), d);
+    return launch_status();
+}
+
 }  // namespace
 }  // namespace mx
 
 extern "C" {
+
+int mx_mbs_lut_build(uint16_t* lut_fp16, void* stream) {
+    if (!lut_fp16) return MX_ENULL;
+    if (!mx::aligned(lut_fp16, 16)) return MX_EALIGN;
+    if (int st = mx::check_device()) return st;
+    hipLaunchKernelGGL(mx::mbs_lut_build_kernel, dim3(8), dim3(256), 0, static_cast<hipStream_t>(stream), lut_fp16);
+    return mx::launch_status();
+}
+
+int mx_quantize_mbs_dynamic_lut(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                const uint16_t* lut_fp16, int keep_static, uint8_t* codes, uint8_t* scales,
+                                uint8_t* mbs, void* stream) {
+    return mx::launch_quantize_dynamic_lut(x_bf16, rows, K, ldx, (int)rule, lut_fp16, keep_static, codes, scales, mbs, stream);
+}
 
 int mx_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                 uint8_t* codes, uint8_t* scales, void* stream) {

@@ -64,6 +64,17 @@ def test_quantize_rejects_rows_longer_than_its_32_bit_columns(lib):
     assert lib.mx_internal_quantize(A16, 1, K, K, 0, 0, 0, A16, A16, None, None) == -1
 
 
+def test_lut_entry_points_reject_bad_arguments(lib):
+    assert lib.mx_mbs_lut_build(None, None) == -2
+    assert lib.mx_mbs_lut_build(A16 + 2, None) == -3
+    q = lib.mx_quantize_mbs_dynamic_lut
+    assert q(A16, 4, 48, 48, 2, A16, 1, A16, A16, A16, None) == -1       # K % 32
+    assert q(A16, 4, 64, 64, 2, None, 1, A16, A16, A16, None) == -2      # no table
+    assert q(A16, 4, 64, 64, 2, A16 + 4, 1, A16, A16, A16, None) == -3   # table misaligned
+    assert q(A16, 4, 64, 64, 2, A16, 1, A16, A16, None, None) == -2      # mbs required
+    assert q(A16, 0, 64, 64, 2, A16, 1, A16, A16, A16, None) == 0
+
+
 def test_version_and_status_strings(lib):
     assert lib.mx_version() >= 100
     seen = set()

@@ -446,6 +446,158 @@ def test_quantize_dynamic_full_size_weights_sampled_rows(mx, oracle):
 
 
 # ------------------------------------------------------------------------------------------------
+# MBS-Dynamic through the table of Eq. 5
+# ------------------------------------------------------------------------------------------------
+def golden_lut():
+    import os
+
+    lut = np.zeros((2, 64, 16), np.uint16)
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "mbs_lut_fp16.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        lut[int(f[0]), int(f[1])] = [int(h, 16) for h in f[2:]]
+    return lut
+
+
+def test_mbs_lut_build_is_the_oracle_table(mx, oracle):
+    """The library builds the table of Eq. 5 itself (fp64, one rounding to fp16): every one of the 2048 entries
+    equals the stored table that the oracle wrote."""
+    lut = mx.mx_mbs_lut_build()
+    torch.cuda.synchronize()
+    got = host(lut).view(np.uint16)
+    want = golden_lut()
+    assert np.array_equal(want, oracle.mbs_lut())
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, "%d entries differ, first at %s gpu=%#x oracle=%#x" % (len(bad), bad[:3], got[tuple(bad[0])], want[tuple(bad[0])])
+
+
+def assert_lut_valid(mx, oracle, bits, rule="oas", keep_static=True, what="", oracle_rows=None):
+    """The kernel sums Eq. 6 in fp32 (and, for keep_static, the two true errors in fp32), the oracle in fp64: near-ties
+    may fall either way, so what is unique is compared and the rest checked for validity.
+      * a searched window's word is 16 j or (keep_static) the static word; others keep the static word;
+      * the tabulated cost of a picked 16 j is within 1e-4 of the least one; where the least one is separated by more
+        than 1e-3 (and, with keep_static, the true errors of the two contenders by more than 1e-4) the word is the oracle's;
+      * keep_static: the kept word's true error is not larger than the other contender's by more than 1e-5;
+      * codes and scales are, bit for bit, those of the chosen word."""
+    lut = golden_lut()
+    dlut = torch.from_numpy(lut.view(np.int16)).cuda()
+    c, s, w = mx.mx_quantize_mbs_dynamic_lut(dev_bf16(bits), dlut, rule, keep_static)
+    torch.cuda.synchronize()
+    sel = slice(None) if oracle_rows is None else oracle_rows
+    x = np.ascontiguousarray(bits[sel])
+    gw, gs, gc = host(w)[sel], host(s)[sel], host(c)[sel]
+    tag = "%s rule=%s keep_static=%s" % (what, rule, keep_static)
+    rows, K = x.shape
+    static = oracle.quantize(x, rule, mbs=True)[2]
+    nmac = static.shape[1]
+    pad = np.zeros((rows, nmac * 128), np.float64)
+    val = oracle.bf16_to_f64(x)
+    finite = np.ones((rows, nmac * 128), bool)
+    finite[:, :K] = np.isfinite(val)
+    pad[:, :K] = np.where(np.isfinite(val), np.abs(val), 0.0)
+    absmax = pad.reshape(rows, nmac, 128).max(2)
+    searched = finite.reshape(rows, nmac, 128).all(2) & (absmax >= 2.0 ** -63) & (absmax < 2.0 ** 123)
+    bad = np.argwhere(~searched & (gw != static))
+    assert bad.size == 0, "%s: %d windows outside the searched domain left the static word, first %s" % (tag, len(bad), bad[:3])
+    # tabulated costs of all 16 candidates, per window
+    cost = np.full((16, rows, nmac), np.inf)
+    for r in range(rows):
+        for g in range(nmac):
+            if searched[r, g]:
+                seg = x[r, 128 * g:min(128 * g + 128, K)]
+                cost[:, r, g] = [oracle.mbs_lut_cost(seg, j, lut, rule) for j in range(16)]
+    jbest = cost.argmin(0)
+    least = cost.min(0)
+    picked = (gw % 16 == 0) & (cost[(gw // 16).clip(0, 15), np.arange(rows)[:, None], np.arange(nmac)[None, :]] <= least * (1 + 1e-4))
+    ok = picked | (gw == static) if keep_static else picked
+    bad = np.argwhere(searched & ~ok)
+    assert bad.size == 0, "%s: %d windows hold a word that is neither a least-cost candidate nor allowed, first %s word %s" % (
+        tag, len(bad), bad[:3], gw[tuple(bad[0])] if len(bad) else None)
+    _, _, ow = oracle.quantize_mbs_dynamic_lut(x, lut, rule, keep_static)
+    runner = np.sort(cost, axis=0)[1]
+    clear = searched & (runner > least * (1 + 1e-3))
+    if keep_static:
+        w16 = (16 * jbest).astype(np.uint8)
+        sse_pick, sse_stat = oracle.mbs_sse_rows(x, np.where(searched, w16, static), rule), oracle.mbs_sse_rows(x, static, rule)
+        got_sse = oracle.mbs_sse_rows(x, gw, rule)
+        bad = np.argwhere(clear & (got_sse > np.minimum(sse_pick, sse_stat) * (1 + 1e-5)))
+        assert bad.size == 0, "%s: %d windows kept the worse of static and picked word, first %s" % (tag, len(bad), bad[:3])
+        clear &= np.abs(sse_pick - sse_stat) > 1e-4 * np.maximum(sse_pick, sse_stat)
+    bad = np.argwhere(clear & (gw != ow))
+    assert bad.size == 0, "%s: %d clearly decided windows differ from the oracle's word, first %s gpu %s oracle %s" % (
+        tag, len(bad), bad[:3], gw[tuple(bad[0])] if len(bad) else None, ow[tuple(bad[0])] if len(bad) else None)
+    oc, os_, _ = oracle.quantize_given_mbs(x, gw, rule)
+    for name, g, want in (("scales", gs, os_), ("code bytes", gc, oc)):
+        bad = np.argwhere(g != want)
+        assert bad.size == 0, "%s: %d %s differ from those of the chosen word, first at %s" % (tag, len(bad), name, bad[:3])
+    return gw, float(clear.mean())
+
+
+@pytest.mark.parametrize("keep_static", [True, False])
+def test_quantize_dynamic_lut_small(mx, oracle, keep_static):
+    from paper_2603_08713_amd import synth
+
+    a, w = synth.tiny(0)
+    for rule in RULES:
+        for name, bits in (("tiny A", a), ("tiny W", w), ("t(3) outliers", synth.activations_student_t(21, 1024 + 64, 3.0, 0.01, 50.0, 9))):
+            words, clear = assert_lut_valid(mx, oracle, bits, rule, keep_static, name)
+            assert clear > 0.5, (name, clear)                    # most windows are clearly decided: the word check bites
+            if rule == "oas":   # (the table knows no saturation: under the other rules the static word mostly stays)
+                assert (words != oracle.quantize(bits, rule, mbs=True)[2]).mean() > 0.3   # the search moves words
+
+
+def test_quantize_dynamic_lut_edge_cases(mx, oracle):
+    """Every bf16 pattern (Inf/NaN, subnormals, huge values: windows outside the search's domain keep the static
+    word), zero rows, blocks far below their window's absmax, ragged K and strided input."""
+    rng = np.random.default_rng(41)
+    allbits = np.arange(65536, dtype=np.uint16).reshape(128, 512)
+    finite = allbits.reshape(-1)[(allbits.reshape(-1) & 0x7F80) != 0x7F80]
+    spread = np.random.default_rng(42).standard_normal((24, 512)).astype(np.float32)
+    for r in range(24):
+        spread[r, 32:64] *= np.float32(2.0) ** -(2 * r + 2)
+        spread[r, 200:210] *= np.float32(2.0) ** -(4 * r)
+    cases = {
+        "natural": allbits[::4],
+        "shuffled-all": rng.permutation(allbits.reshape(-1)).reshape(128, 512)[:32],
+        "shuffled-finite": rng.choice(finite, size=(24, 640)),
+        "zeros": np.zeros((3, 256), np.uint16),
+        "spread": (spread.view(np.uint32) >> 16).astype(np.uint16),
+    }
+    for name, bits in cases.items():
+        assert_lut_valid(mx, oracle, bits, "oas", True, name)
+    from paper_2603_08713_amd import synth
+
+    full = synth.gaussian(5, 2880 + 40, 0.02, 77)
+    x = dev_bf16(full)[:, :2880]
+    lut = torch.from_numpy(golden_lut().view(np.int16)).cuda()
+    c, s, w = mx.mx_quantize_mbs_dynamic_lut(x, lut, "oas")
+    gw, _ = assert_lut_valid(mx, oracle, np.ascontiguousarray(full[:, :2880]), "oas", True, "ragged 5x2880")
+    assert np.array_equal(host(w), gw)
+
+
+def test_quantize_dynamic_lut_full_size_weights(mx, oracle):
+    """The Llama-3-8B FFN up-projection weight, every row on the GPU with the table the library builds, 64 seeded rows
+    on the oracle; QSNR against the static words and the exact search."""
+    from paper_2603_08713_amd import synth
+
+    _, w_bits = synth.llama8b_ffn_up()
+    rows = np.sort(np.random.default_rng(43).choice(w_bits.shape[0], 64, replace=False))
+    rows[0], rows[-1] = 0, w_bits.shape[0] - 1
+    assert_lut_valid(mx, oracle, w_bits, "oas", True, "L3-8B W", oracle_rows=rows)
+    xw = dev_bf16(w_bits[:512])
+    ref = xw.to(torch.float64)
+
+    def qsnr(q):
+        back = mx.mx_dequantize(q[0], q[1], q[2], "f32").to(torch.float64)
+        return float(10.0 * torch.log10((ref * ref).sum() / ((ref - back) ** 2).sum()))
+
+    lut = mx.mx_mbs_lut_build()
+    st, lu, ex = qsnr(mx.mx_quantize_mbs(xw, "oas")), qsnr(mx.mx_quantize_mbs_dynamic_lut(xw, lut, "oas")), qsnr(mx.mx_quantize_mbs_dynamic(xw, "oas"))
+    assert lu - st > 0.3 and abs(ex - lu) < 0.05, (st, lu, ex)
+
+
+# ------------------------------------------------------------------------------------------------
 # dequantizer and QSNR from both paths
 # ------------------------------------------------------------------------------------------------
 def test_dequantize_matches_oracle(mx, oracle):
