@@ -145,7 +145,8 @@ int mx_internal_gemm_plan(int64_t M, int64_t N, int64_t K, int a_has_mbs, int b_
     const char* what;
     switch (shape) {
         case 2: what = mx::describe_gemm_wide(M, N); break;
-        case 3: what = "gemm_ring_kernel, fast form, 256x128 tile, 8 wavefronts of 128x32"; break;
+        case 3: what = a_has_mbs && b_has_mbs ? "gemm_ring_kernel, fast form, 256x128 tile, 8 wavefronts of 64x64"
+                                              : "gemm_ring_kernel, fast form, 256x128 tile, 8 wavefronts of 128x32"; break;
         case 4: what = "gemm_ring_kernel, fast form, 128x128 tile, 8 wavefronts of 64x32"; break;
         case 5: what = "gemm_skinny_kernel (few rows)"; break;
         case 8: what = use_mbs ? "gemm_ring_kernel, general form (2-byte scale pieces), 256x128 tile, 8 wavefronts" : "gemm_ring_kernel, general form (2-byte scale pieces), 256x128 tile, 4 wavefronts"; break;

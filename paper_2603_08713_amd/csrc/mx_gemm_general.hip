@@ -13,7 +13,7 @@ namespace mx {
 // tiles only: one LDS dword per byte does not fit beside the larger tile).
 int launch_gemm_mbs_general(const GemmArgs& g, int tile, bool bytes, hipStream_t s) {
     if (bytes) return launch_ring<RingShape<2, 4, 2, 1, 3, 2>>(g, s);
-    if (tile == 0) return launch_ring<RingShape<2, 4, 4, 1, 3, 1>>(g, s);
+    if (tile == 0) return launch_ring<RingShape<4, 2, 2, 2, 3, 1>>(g, s);
     return launch_ring<RingShape<2, 4, 2, 1, 3, 1>>(g, s);
 }
 

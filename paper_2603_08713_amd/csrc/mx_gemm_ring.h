@@ -224,7 +224,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // sigma values in registers: this lane's output row of each A fragment, per stage parity, and its 16
     // output columns of a B fragment.  Pairs run B fragment by B fragment; while one fragment's FM pairs
     // are folded in, the next fragment's values (of this or of the next stage) arrive in the other set.
-    float sig_m[2][FM];
+    float sig_m[2][FM > kCouples ? FM : kCouples];
     v4f sig_n[2][4];
     // With the surface on the matrix cores a lane supplies, per stage, sigma_B of B row lr (to both blocks) and,
     // per couple c of A fragments, sigma_A of row lr of fragment 2 c + lh (block lh); `surface` holds the two
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) sig_m[par][i] = 0.f;
+        for (int i = 0; i < (FM > kCouples ? FM : kCouples); ++i) sig_m[par][i] = 0.f;
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) sig_n[par][gq] = v4f{0.f, 0.f, 0.f, 0.f};
     }
@@ -311,9 +311,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             // j FM / 2 + c has the parity of c, plus the stage's when a stage has an odd number of couples.
             constexpr int par = decltype(par_)::value;
 #pragma unroll
-            for (int c = 0; c < FM / 2; ++c) {
-                const bool swap = ((kCouples % 2 == 1 ? par : 0) + c) % 2 == 0;
-                sig_m[par][c] = sig[(wm * FM + 2 * c) * 32 + (swap ? l ^ 32 : l)];
+            for (int g = 0; g < kCouples; ++g) {
+                const int c = g % (FM / 2);
+                const bool swap = ((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0;
+                sig_m[par][g] = sig[(wm * FM + 2 * c) * 32 + (swap ? l ^ 32 : l)];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) sig_n1[par][j] = sig[TM + (wn * FN + j) * 32 + lr];
@@ -401,11 +402,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // B fragment j.  Consecutive couples alternate between the two buffers; a stage with an odd number of couples
     // (one) alternates by stage parity as well.
     auto issue_surface = [&](auto par_, auto g_) {
-        constexpr int par = decltype(par_)::value, g = decltype(g_)::value, c = g % (FM / 2), j = g / (FM / 2);
+        constexpr int par = decltype(par_)::value, g = decltype(g_)::value, j = g / (FM / 2);
         v32f zero;
 #pragma unroll
         for (int e = 0; e < 32; ++e) zero[e] = 0.f;
-        const v32f v = __builtin_amdgcn_mfma_f32_32x32x1f32(sig_n1[par][j], sig_m[par][c], zero, 0, 0, 0);
+        const v32f v = __builtin_amdgcn_mfma_f32_32x32x1f32(sig_n1[par][j], sig_m[par][g], zero, 0, 0, 0);
         if constexpr (((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0) surf_a = v;
         else surf_b = v;
     };

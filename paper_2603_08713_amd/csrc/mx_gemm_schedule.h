@@ -43,9 +43,8 @@ template <int NWM_, int NWN_, int FM_, int FN_, int kSides_, int kForm_ = 0>
 struct RingShape {
     static constexpr int NWM = NWM_, NWN = NWN_, FM = FM_, FN = FN_, kSides = kSides_;
     static constexpr bool kMbs = kSides != 0, kGen = kForm_ != 0, kBytes = kForm_ == 2;
-    // (couples of A fragments against one B fragment.  The code below is written for any number of B fragments
-    // whose couples come in pairs per stage, but only FN = 1 is instantiated and tested.)
-    static constexpr bool kSurface = kSides == 3 && FM_ % 2 == 0 && FN_ == 1;
+    // (couples of A fragments against one B fragment at a time; instantiated with one and with two B fragments)
+    static constexpr bool kSurface = kSides == 3 && FM_ % 2 == 0 && (FN_ == 1 || FN_ == 2);
     static constexpr int NW = NWM * NWN, NT = NW * kWave;
     static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32;
     static constexpr int kRows = TM + TN;             // rows of A followed by rows of B

@@ -132,13 +132,13 @@ int main() {
     SHAPE(2, 2, 4, 2, 0, 1);
     SHAPE(2, 2, 2, 2, 0, 1);
     SHAPE(2, 2, 2, 2, 0, 2);
-    SHAPE(2, 4, 4, 1, 3);
+    SHAPE(4, 2, 2, 2, 3);
     SHAPE(2, 4, 4, 1, 1);
     SHAPE(2, 4, 4, 1, 2);
     SHAPE(2, 4, 2, 1, 3);
     SHAPE(2, 4, 2, 1, 1);
     SHAPE(2, 4, 2, 1, 2);
-    SHAPE(2, 4, 4, 1, 3, 1);
+    SHAPE(4, 2, 2, 2, 3, 1);
     SHAPE(2, 4, 2, 1, 3, 1);
     SHAPE(2, 4, 2, 1, 3, 2);
     std::printf("all schedules hold\n");
