@@ -230,13 +230,13 @@ def assert_gemm_close(got, want, what=""):
     assert err <= GEMM_TOL * rms, "%s: max err %.3e vs %.3e (rms %.3e)" % (what, err, GEMM_TOL * rms, rms)
 
 
-# The matrix instruction adds FP8 products with less than fp32 precision: inside a group of products it aligns
-# them to the group's largest exponent and cuts each off about 13 bits below it (measured: 448 * 448 + p, both
-# in one group, returns p truncated to a multiple of 8; the same p in another group comes back exact).  An
-# error of at most 2^-13 of the group's largest product per product is at most 15 * 2^-13 * sum_k |a_ik b_jk| per
-# output, and far less unless every group has one dominant product.  On quantized tensors this stays inside
-# the 1e-3 * RMS bar (tests below); uniformly random codes under scales spread over 30 binades are checked
-# against the per-output bound 2^-11 * sum_k |a_ik| |b_jk| (the largest measured ratio is below 2^-13).
+# The accumulation contract of mx_gemm_mbs_elem (include/mx4.h) has two bounds.  (1) Quantized tensors, and any
+# operands whose products stay within 2^13 of each other inside a group of 16 K-elements: the 1e-3 * RMS bar of
+# the MXFP4 GEMM (GEMM_TOL; the tests on quantized tensors and on E2M3 codes below).  (2) Any codes and scale
+# bytes: |C - exact| <= 2^-11 * sum_k |a_ik| |b_jk| per output, the secondary bound, because the matrix
+# instruction aligns the products of such a group to the group's largest exponent and cuts them off about 13
+# bits below it.  ABS_TOL is bound (2); it is used only on uniformly random codes under scale bytes spread over
+# 30 binades, which bound (1) does not cover (the largest ratio seen there is below 2^-13).
 ABS_TOL = 2.0 ** -11
 
 

@@ -881,6 +881,35 @@ def test_macro_block_size_ablation_direction(oracle):
         assert all(curve[16, m] > curve[32, m] for m in (32, 64, 128, 256, 512))
 
 
+def test_output_qsnr_sweep_over_macro_and_block_size(oracle):
+    """App. A and Sec. 3.2 carried to the product (Eq. 2, QSNR(AB)): with OAS + MBS-S on both operands the output
+    QSNR falls as the macro block grows from 32 to 512 elements and 16-element blocks beat 32-element blocks at
+    every macro size; MBS-S at the paper's size (1 x 128) keeps most of what the finest macro block gains over
+    OAS alone.  Synthetic tensors: the direction is pinned, absolute values are parity unpinned."""
+    from paper_2603_08713_amd import synth
+
+    a = synth.activations_student_t(24, 2048, 4.0, 0.01, 20.0, 11)
+    w = synth.gaussian(48, 2048, 0.02, 12)
+    ref = oracle.matmul_bf16(a, w)
+    curve = {}
+    for block in (16, 32):
+        qa, qw = oracle.quantize(a, "oas", block=block), oracle.quantize(w, "oas", block=block)
+        curve[block, None] = oracle.qsnr_db(ref, oracle.gemm(qa, qw, block=block))
+        for macro in (32, 64, 128, 256, 512):
+            qa = oracle.quantize(a, "oas", mbs=True, block=block, macro=macro)
+            qw = oracle.quantize(w, "oas", mbs=True, block=block, macro=macro)
+            curve[block, macro] = oracle.qsnr_db(ref, oracle.gemm(qa, qw, block=block, macro=macro))
+        vals = [curve[block, m] for m in (32, 64, 128, 256, 512)]
+        assert all(x > y for x, y in zip(vals, vals[1:])), vals
+        assert vals[-1] > curve[block, None], (vals, curve[block, None])       # even 1 x 512 beats no MBS
+        # 1 x 128 keeps more than half of the gain of 1 x 32 over OAS alone
+        assert curve[block, 128] - curve[block, None] > 0.5 * (curve[block, 32] - curve[block, None])
+    assert all(curve[16, m] > curve[32, m] for m in (None, 32, 64, 128, 256, 512))
+    # the operands' own QSNR and the product's move together: the product loses about as much as the weaker operand
+    drop_ab = curve[32, 32] - curve[32, 512]
+    assert 0.2 < drop_ab < 3.0, drop_ab
+
+
 def test_flush_to_zero_rate_falls_with_block_size(oracle):
     """Sec. 3.2: E2M1 spans a 12x range, so the small values of a high-variance block are quantized to zero; on
     activation tensors halving the block from 32 to 16 elements cuts that share from about 20 % to 13 % (a
