@@ -910,6 +910,41 @@ def test_output_qsnr_sweep_over_macro_and_block_size(oracle):
     assert 0.2 < drop_ab < 3.0, drop_ab
 
 
+def nvfp4_round_trip(x: np.ndarray) -> np.ndarray:
+    """NVFP4 as Sec. 2.2 describes it, for context only (a comparison format, not part of the method): E2M1
+    elements, one E4M3 scale per 16 elements, one fp32 scale per tensor chosen so that the largest block scale is
+    E4M3's 448.  Written here with numpy and torch's float8 cast; not in the oracle."""
+    torch = pytest.importorskip("torch")
+    grid = np.array([float(g) for g in GRID])
+    st = np.abs(x).max() / (448.0 * 6.0)
+    xb = x.reshape(x.shape[0], -1, 16)
+    sb = np.abs(xb).max(-1, keepdims=True) / (6.0 * st)
+    sb = torch.from_numpy(sb).to(torch.float32).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    sb = np.where(sb == 0, 1.0, sb)
+    t = np.clip(xb / (st * sb), -6.0, 6.0)
+    d = np.abs(np.abs(t)[..., None] - grid)
+    best = d.min(-1, keepdims=True)
+    lo, hi = (d == best).argmax(-1), 7 - (d == best)[..., ::-1].argmax(-1)
+    idx = np.where(lo % 2 == 0, lo, hi)                      # ties to the even code
+    return (np.sign(t) * grid[idx] * (st * sb)).reshape(x.shape)
+
+
+def test_nvfp4_context_gap_narrows(oracle):
+    """Sec. 2.2 / 4.4, context: NVFP4 (block 16, E4M3 scales) is more accurate than MXFP4-OCP; OAS + MBS (static
+    for activations, searched for weights: MBS-Hybrid) close more than half of that gap while keeping E8M0
+    scales on 32-element blocks.  Synthetic tensors; the ordering is pinned, absolute values are parity unpinned."""
+    from paper_2603_08713_amd import synth
+
+    for bits, searched in ((synth.activations_student_t(32, 2048, 4.0, 0.01, 20.0, 1), False), (synth.gaussian(32, 2048, 0.02, 2), True)):
+        x = oracle.bf16_to_f64(bits)
+        nv = oracle.qsnr_db(x, nvfp4_round_trip(x))
+        plain = oracle.qsnr_db(x, oracle.dequantize(*oracle.quantize(bits, "ocp")))
+        q = oracle.quantize_mbs_dynamic(bits, "oas") if searched else oracle.quantize(bits, "oas", mbs=True)
+        ours = oracle.qsnr_db(x, oracle.dequantize(*q))
+        assert plain < ours < nv, (plain, ours, nv)
+        assert nv - ours < 0.5 * (nv - plain), (plain, ours, nv)
+
+
 def test_flush_to_zero_rate_falls_with_block_size(oracle):
     """Sec. 3.2: E2M1 spans a 12x range, so the small values of a high-variance block are quantized to zero; on
     activation tensors halving the block from 32 to 16 elements cuts that share from about 20 % to 13 % (a
