@@ -40,40 +40,12 @@
 // byte.  A stage is 96 bytes of a row; so that no 128-byte line of memory is fetched twice, the ring slots hold
 // planes instead of stages: slot L = bytes 128 L .. + 127 of the 384 that a group of four stages takes of each
 // row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.
+#include "mx_gemm_f8_schedule.h"
 #include "mx_gemm_shared.h"
 #include "mx_internal.h"
 
 namespace mx {
 namespace {
-
-constexpr int kF8Slots = 3;
-constexpr int kF8RowStage = kMacro;  // code bytes per row and stage
-constexpr int kF8GroupM = 4;         // tile-rows walked together for L2 reuse
-
-template <bool kFast_>
-struct F8Shape {
-    static constexpr bool kFast = kFast_;
-    static constexpr int NWM = 4, NWN = 2, FM = 2, FN = 2, NW = NWM * NWN, NT = NW * kWave;
-    static constexpr int TM = NWM * FM * 32, TN = NWN * FN * 32, kRows = TM + TN;
-    static constexpr int kCodeDma = kRows / 8 / NW;                     // per wavefront and stage: 8 rows x 128 B per load
-    static constexpr int kRegLoads = kFast ? 0 : FM + FN + 2;           // general form: E8M0 dwords and MBS words per lane and stage
-    static constexpr int kLoads = kCodeDma + kRegLoads;                 // (the general form without MBS loads no words: two fewer)
-    static constexpr int kGroup = 4;                                    // fast form: stages per 16-byte piece of E8M0 bytes
-    static constexpr int kStageA = TM * kF8RowStage, kStageB = TN * kF8RowStage, kStage = kStageA + kStageB;
-    static constexpr int kBaseB = 0, kBaseA = kF8Slots * kStageB;       // the ring slots of B, then those of A
-    static constexpr int kSmallBase = kF8Slots * kStage;
-    // fast form: two buffers of [row][16 E8M0 bytes], two tables of [row] sigma; general form: a table per wavefront
-    static constexpr int kScaleGroup = kRows * 16, kSigmaTable = kRows * 4;
-    static constexpr int kSigmaBase = kSmallBase + (kFast ? 2 * kScaleGroup : 0);
-    static constexpr int kSigmaWave = (FM + FN) * 32 * 4;
-    static constexpr int kSpare = kSigmaBase + 2 * kSigmaTable;         // fast form: 1 KiB nobody reads
-    static constexpr int kLdsBytes = kFast ? kSpare + 1024 : kSigmaBase + NW * kSigmaWave;
-    static constexpr int kStageRegion = 32 * (FN * 32 * 4 + 16);        // per wavefront, epilogue staging
-    static_assert((TM / 8) % NW == 0 && (TN / 8) % NW == 0, "operand fixed per load index");
-    static_assert(kRows % kWave == 0 && TM % kWave == 0, "fast form: a wavefront's rows belong to one operand");
-    static_assert(kLdsBytes <= 160 * 1024 && NW * kStageRegion <= kLdsBytes, "LDS capacity of a gfx950 compute unit");
-    static_assert(kCodeDma <= 2 * FM * FN - 2 && 3 * kLoads + 4 < 64, "vmcnt is a 6-bit counter");
-};
 
 // kFmtA / kFmtB: the matrix instruction's format selector of tensor A / B (0 = E4M3, 1 = E5M2).
 template <int kFmtA, int kFmtB, bool kMbs, bool kFast>
@@ -86,7 +58,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     constexpr int kRowStage = kSix ? 96 : kF8RowStage;  // code bytes per row and stage
     // loads a wavefront makes per stage: what the stage's wait counts (a count that assumed more would let the
     // youngest loads of the stage it is about to read stay in flight)
-    constexpr int kLoads = S::kLoads - (kFast || kMbs ? 0 : 2);
+    using Sched = F8Schedule<kSix ? kF8Six : kFast ? kF8Fast : kF8General, kMbs>;
+    constexpr int kLoads = Sched::kLoads;
+    static_assert(kLoads == S::kLoads - (kFast || kMbs ? 0 : 2) && Sched::kCodeDma == kCodeDma, "the schedule describes this kernel");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles,
@@ -377,7 +351,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         // earlier; since then came one stage's plane (six loads) or, before the group's second stage, the group
         // loads (of which the second may still fly).
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(wait_imm(kSix ? (p == 1 ? 1 : kCodeDma) : kLoads));
+        __builtin_amdgcn_s_waitcnt(wait_imm(Sched::stage_wait(p)));
         bare_barrier();
         patch_frags();
         if constexpr (kFast) {
@@ -490,13 +464,12 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             static_for<kCodeDma>([&](auto i_) { issue_code(decltype(L_)::value * 128, L_, i_); });
         });
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(wait_imm(0));
     } else {
         issue(0, std::integral_constant<int, 0>{});
         issue(1, std::integral_constant<int, 1>{});
         issue(2, std::integral_constant<int, 2>{});
-        __builtin_amdgcn_s_waitcnt(wait_imm(2 * kLoads));
     }
+    __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait()));
     if constexpr (kFast && kMbs) {
         convert_sigma_fast(0, std::integral_constant<int, 0>{});
         __builtin_amdgcn_s_waitcnt(kWaitLds);

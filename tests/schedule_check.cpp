@@ -15,6 +15,7 @@
 #include <tuple>
 #include <vector>
 
+#include "mx_gemm_f8_schedule.h"
 #include "mx_gemm_schedule.h"
 
 namespace {
@@ -120,6 +121,111 @@ void check_all(const char* name) {
     for (int nstages : {4, 8, 12, 16, 64, 256}) check<S>(name, nstages);
 }
 
+// ---- the kernel for 8-bit and 6-bit operands (mx_gemm_f8.hip), same rules ------------------------------------
+struct F8Issued {
+    mx::F8LoadItem item;  // absolute
+    int at_stage;
+    bool repeat;          // past the end of K the kernel fetches the last stage, group or plane again
+};
+
+template <int kForm, bool kMbs>
+void check_f8(const char* name, int nstages) {
+    using Sched = mx::F8Schedule<kForm, kMbs>;
+    constexpr int C = Sched::kCodeDma;
+    constexpr bool kGroups = kForm != mx::kF8General, kSix = kForm == mx::kF8Six;
+    std::vector<F8Issued> issued;
+    size_t landed = 0;
+    auto wait = [&](int n) {
+        if (n < 0 || n > 63) fail(name, nstages, "wait count outside the 6-bit counter", n);
+        const size_t keep = (size_t)n < issued.size() ? issued.size() - (size_t)n : 0;
+        if (keep > landed) landed = keep;
+    };
+    auto find = [&](int kind, int what, int index) -> int {
+        int pos = -1, count = 0;
+        for (size_t k = 0; k < issued.size(); ++k)
+            if (!issued[k].repeat && issued[k].item.kind == kind && issued[k].item.what == what && issued[k].item.index == index) {
+                pos = (int)k;
+                ++count;
+            }
+        if (count > 1) fail(name, nstages, "a piece is loaded twice", kind, what, index);
+        return pos;
+    };
+    auto need = [&](int kind, int what, int count, int reader_stage) {
+        for (int i = 0; i < count; ++i) {
+            const int pos = find(kind, what, i);
+            if (pos < 0) fail(name, nstages, "a piece that is read was never loaded", kind, what, reader_stage);
+            if ((size_t)pos >= landed) fail(name, nstages, "a piece is read before a wait has retired its load", kind, what, reader_stage);
+        }
+    };
+    const int ngroups = nstages / 4, nplanes = 3 * ngroups;
+    auto issue = [&](mx::F8LoadItem abs, int t) {
+        bool repeat = false;
+        if (abs.kind == mx::kF8Code && !kSix) {
+            // stage y goes into slot y % 3 where stage y - 3 was, whose fragments are read during stage y - 4: free
+            // from the barrier of stage y - 3 on
+            if (abs.what >= nstages) { repeat = true; abs.what = nstages - 1; }
+            else if (t >= 0 && !(abs.what - 3 <= t)) fail(name, nstages, "codes loaded into a slot that is still in use", abs.what, t);
+            if (t >= 0 && abs.what <= t + 1 && !repeat) fail(name, nstages, "codes requested too late", abs.what, t);
+        } else if (abs.kind == mx::kF8Code) {
+            // plane 3 g + L goes where plane 3 (g - 1) + L was, last read for the fragments of stage L + 1 of group
+            // g - 1, during stage L of that group: free from the barrier of stage 4 (g - 1) + L + 1 on
+            if (abs.what >= nplanes) { repeat = true; abs.what -= 3; }
+            const int g = abs.what / 3, L = abs.what % 3;
+            if (t >= 0 && !(4 * (g - 1) + L + 1 <= t)) fail(name, nstages, "plane loaded into a slot that is still in use", abs.what, t);
+        } else if (abs.kind == mx::kF8GroupScale) {
+            // group G goes where group G - 2 was, last read (for stage 4 (G - 2) + 3) during stage 4 (G - 2) + 2
+            if (abs.what >= ngroups) { repeat = true; abs.what = ngroups - 1; }
+            if (t >= 0 && !(4 * (abs.what - 2) + 3 <= t)) fail(name, nstages, "E8M0 bytes loaded into a buffer still in use", abs.what, t);
+        }
+        issued.push_back({abs, t, repeat});
+    };
+    // what the fragments of stage y are read from
+    auto need_stage = [&](int y, int reader) {
+        if (!kSix) { need(mx::kF8Code, y, C, reader); return; }
+        const int g = y / 4, q = y % 4;
+        for (int plane = (6 * q) / 8; plane <= (6 * q + 5) / 8; ++plane) need(mx::kF8Code, 3 * g + plane, C, reader);
+    };
+    for (int n = 0; n < Sched::prologue_count(); ++n) issue(Sched::prologue_item(n), -1);
+    wait(Sched::prologue_wait());
+    need_stage(0, -1);
+    if (kGroups) need(mx::kF8GroupScale, 0, 1, -1);
+    for (int s = 0; s < nstages; ++s) {
+        const int p = s % 4;
+        wait(Sched::stage_wait(p));
+        if (s + 1 < nstages) {
+            need_stage(s + 1, s);
+            if (kGroups) need(mx::kF8GroupScale, (s + 1) / 4, 1, s);
+        }
+        for (int n = 0; n < Sched::issue_count(p); ++n) {
+            mx::F8LoadItem it = Sched::issue_item(p, n);
+            if (it.kind == mx::kF8Code) it.what += kSix ? 3 * (s / 4) : s;
+            else if (it.kind == mx::kF8GroupScale || it.kind == mx::kF8GroupWords) it.what += s / 4;
+            else it.what += s;
+            issue(it, s);
+        }
+    }
+    if (kSix) {
+        for (int y = 0; y < nplanes; ++y)
+            for (int i = 0; i < C; ++i)
+                if (find(mx::kF8Code, y, i) < 0) fail(name, nstages, "a plane was never loaded", y, i);
+    } else {
+        for (int y = 0; y < nstages; ++y)
+            for (int i = 0; i < C; ++i)
+                if (find(mx::kF8Code, y, i) < 0) fail(name, nstages, "codes of a stage never loaded", y, i);
+    }
+    std::printf("ok %s nstages=%d loads/wavefront and stage: %d codes; waits %d %d %d %d\n", name, nstages, C, Sched::stage_wait(0),
+                Sched::stage_wait(1), Sched::stage_wait(2), Sched::stage_wait(3));
+}
+
+template <int kForm, bool kMbs>
+void check_f8_all(const char* name) {
+    // the general form takes any number of stages, the fast forms whole groups of four
+    if (kForm == mx::kF8General)
+        for (int nstages : {1, 2, 3, 4, 5, 7, 12, 61, 256}) check_f8<kForm, kMbs>(name, nstages);
+    else
+        for (int nstages : {4, 8, 12, 16, 20, 64, 256}) check_f8<kForm, kMbs>(name, nstages);
+}
+
 }  // namespace
 
 #define SHAPE(...) check_all<mx::RingShape<__VA_ARGS__>>("RingShape<" #__VA_ARGS__ ">")
@@ -141,6 +247,13 @@ int main() {
     SHAPE(4, 2, 2, 2, 3, 1);
     SHAPE(2, 4, 2, 1, 3, 1);
     SHAPE(2, 4, 2, 1, 3, 2);
+    // the forms of the kernel for 8-bit and 6-bit operands, with and without MBS words
+    check_f8_all<mx::kF8General, false>("F8Schedule<general, no MBS>");
+    check_f8_all<mx::kF8General, true>("F8Schedule<general, MBS>");
+    check_f8_all<mx::kF8Fast, false>("F8Schedule<fast, no MBS>");
+    check_f8_all<mx::kF8Fast, true>("F8Schedule<fast, MBS>");
+    check_f8_all<mx::kF8Six, false>("F8Schedule<six, no MBS>");
+    check_f8_all<mx::kF8Six, true>("F8Schedule<six, MBS>");
     std::printf("all schedules hold\n");
     return 0;
 }
