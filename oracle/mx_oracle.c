@@ -218,7 +218,7 @@ int mxo_quantize_given_mbs(const uint16_t* x, int64_t rows, int64_t K, int64_t l
     return 0;
 }
 
-/* ---- MBS-Dynamic (Sec. 4.3.3 "Dynamic", Eq. 4-6; Sec. 5.3) ---------------------------------- */
+/* ---- MBS-Dynamic (Sec. 4.3.3, Eq. 4-6; Sec. 5.3) ---------------------------------- */
 
 /* Eq. 6 picks, out of a list of candidate words, the one with the smallest sum of squared errors
  * of the 1x128 block, sum_i (x_hat_i - x_i)^2 = sum_i x_i^2 ((x_hat_i - x_i)/x_i)^2, with
@@ -228,7 +228,7 @@ int mxo_quantize_given_mbs(const uint16_t* x, int64_t rows, int64_t K, int64_t l
  * of approximate squared relative errors (Eq. 5) is a way to evaluate the same sum faster; it is
  * restated separately below (mxo_quantize_mbs_dynamic_lut).
  *
- * The candidate list is not given ("a narrow range", 16 candidates), so it is a parameter:
+ * The candidate list is not given (the paper says only that there are 16 over a narrow range), so it is a parameter:
  *     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count-1
  * (the factor 1 + m/256 is defined up to a power of two, which the local scales absorb, so the
  * words form a circle).  The static word always competes and is the incumbent; candidates are
@@ -310,7 +310,7 @@ int mxo_quantize_mbs_dynamic(const uint16_t* x, int64_t rows, int64_t K, int64_t
     return 0;
 }
 
-/* ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3, "Memoization Strategy") --------------------- */
+/* ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3) --------------------- */
 
 /* Eq. 5-6 replace the error of every element by a tabulated squared RELATIVE error
  *     T[v, m_j]  ~  ((x_hat - x) / x)^2,    v = |x| SF   (the element in the block's scaled domain, before the

@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
     }
 }
 
-// ---- MBS-Dynamic (Sec. 4.3.1 "Dynamic", Sec. 5.3) ----------------------------------------------------
+// ---- MBS-Dynamic (Sec. 4.3.1, Sec. 5.3) ----------------------------------------------------
 // Per macro block the word is searched among the candidates
 //     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count - 1,
 // for the least sum of squared errors of the 1x128 block.  The paper reads squared relative errors from a
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {
     }
 }
 
-// ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3, "Memoization Strategy") ----------------------------
+// ---- MBS-Dynamic through the table of Eq. 5 (Sec. 4.3.3) ----------------------------
 // Eq. 5-6 price a candidate factor by a table of squared relative errors, T[v, m_j] ~ ((x_hat - x) / x)^2 with
 // v = |x| SF the element in its block's scaled domain, so that a candidate's sum of squared errors is
 // sum_i x_i^2 T[v_ij, m_j].  The table is 2 x 64 points x 16 slots of fp16 (4 KiB, held in LDS): slot j is the
