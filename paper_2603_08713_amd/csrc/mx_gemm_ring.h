@@ -22,18 +22,19 @@
 // per stage through a ring of four LDS code slots.  While stage s is multiplied out of registers, stage
 // s + 1 is read from LDS into the other register set; every other stage issues the loads of stages s + 3 and
 // s + 4 together, line by line, into the slots the stages s - 1 and s have left (mx_gemm_schedule.h: a memory
-// line holds two stages of a row, and its two halves are cheaper requested back to back than a stage apart):
-// two to three stages are in flight, enough to cover a miss in the L2.  One
-// workgroup barrier per stage publishes stage s + 1 and, because every wavefront has finished reading
-// stage s by then, frees its slot.  E8M0 bytes and MBS words travel per group of four stages: a row's 16
+// line holds two stages of a row, and its two halves are cheaper requested back to back than a stage apart).
+// Only those stages open with a wait for the wavefront's loads and the workgroup's barrier, which publishes
+// stages s + 1 and s + 2 and, because every wavefront has finished reading stage s by then, frees the two slots;
+// the stages between read what is published already, so the wavefronts may drift up to two stages apart.
+// E8M0 bytes and MBS words travel per group of four stages: a row's 16
 // scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each); the general form, for K
 // and row addresses that do not allow such pieces, is described at RingShape.
 //
 // MBS (Sec. 4.3.2, App. E): the two instructions of a fragment pair start from a zero accumulator and
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
-// The sigma values of stage s + 2 are computed by the workgroup during stage s (one reciprocal per row) into
-// one of four LDS tables.  With words on one operand only, a wavefront folds a product in while the next
+// The sigma values of stages s + 2 and s + 3 are computed by the workgroup during a stage s without a barrier (one
+// reciprocal per row and stage) into two of four LDS tables, which the next stage's barrier publishes.  With words on one operand only, a wavefront folds a product in while the next
 // pair's instructions run.
 //
 // Where both operands carry words, the surface S = sigma_A (x) sigma_B of Sec. 4.3.2 is itself a matrix product
@@ -433,9 +434,9 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         }
     };
 
-    // One stage: publish stage s + 1; multiply stage s out of `cur`; slipped in between the matrix
-    // instructions, the LDS reads of stage s + 1 into `next` and, with kIssue, this stage's loads.  The
-    // wavefronts issue their loads at different instruction slots (kLate 0 or 1).
+    // One stage: multiply stage s out of `cur`; slipped in between the matrix instructions, the LDS reads of
+    // stage s + 1 into `next` and, with kIssue, this stage's loads.  The wavefronts issue their loads at
+    // different instruction slots (kLate 0 or 1).
     auto stage = [&](int s, const Frags& cur, Frags& next, auto phase_, auto late_, auto issue_) {
         constexpr int kPhase = decltype(phase_)::value, kLate = decltype(late_)::value;
         using Par = std::integral_constant<int, kPhase % 2>;       // stage parity: kRingGroup is even
@@ -444,10 +445,13 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         static_assert(kRingSlots == kRingGroup, "the phase of a stage is also its ring slot");
         constexpr bool kIssue = decltype(issue_)::value;
         constexpr int kN = Sched::issue_count(kPhase);
-        // Own loads of stage s + 1 (and the E8M0 bytes and MBS words this stage reads) have landed; what was
-        // issued after them may still fly.  Own reads of `cur` are done.
-        __builtin_amdgcn_s_waitcnt(wait_imm(kIssue ? Sched::wait_count(kPhase) : 0));
-        bare_barrier();
+        // A stage that issues loads: everything this wavefront has requested has landed (the stages s + 1 and
+        // s + 2, the E8M0 bytes and MBS words of the groups they belong to), own LDS traffic is done, and behind the
+        // barrier every wavefront has finished stage s - 1.  (Stages past the last request keep the barrier.)
+        if constexpr (Sched::has_barrier(kPhase)) {
+            __builtin_amdgcn_s_waitcnt(wait_imm(Sched::wait_count(kPhase)));
+            bare_barrier();
+        }
         auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
             constexpr int t = decltype(t_)::value;
             if constexpr (!kMbs) {
@@ -477,7 +481,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             using I0 = std::integral_constant<int, 0>;
             using I1 = std::integral_constant<int, 1>;
             constexpr int kShadows = kCouples;
-            read_sigma_m(s + 1, NextPar{});  // published by this stage's barrier; the next stage's first surface needs it
+            read_sigma_m(s + 1, NextPar{});  // published by this stage's barrier or the one before; the next stage's first surface needs it
             static_for<kPairs>([&](auto q_) {
                 constexpr int q = decltype(q_)::value, i = q % FM, j = q / FM;
                 using Before = std::integral_constant<int, (q + kPairs - 1) % kPairs>;
@@ -513,7 +517,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                             if constexpr ((decltype(n_)::value * kShadows) / kN == shadow) issue_load(s, phase_, n_);
                         });
                     }
-                    if constexpr (shadow == kShadows - 1) convert_sigma(s + 2);  // into the table stage s - 2 was read from
+                    // (the stages without a barrier convert for two stages: what they write is published by the next
+                    // stage's barrier, into the tables that the stages s - 2 and s - 1 were read from)
+                    if constexpr (shadow == kShadows - 1 && !Sched::has_barrier(kPhase)) {
+                        convert_sigma(s + 2);
+                        convert_sigma(s + 3);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             });
@@ -533,7 +542,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             };
             issue(std::integral_constant<int, 0>{});
             // (behind the first pair's instructions: the LDS round trip of the MBS words then overlaps their run)
-            convert_sigma(s + 2);  // into the table stage s - 2 was read from
+            if constexpr (!Sched::has_barrier(kPhase)) {  // for two stages; published by the next stage's barrier
+                convert_sigma(s + 2);
+                convert_sigma(s + 3);
+            }
             if constexpr (kDefer) {
                 __builtin_amdgcn_sched_barrier(0);
                 retire(NextPar{}, std::integral_constant<int, kPairs - 1>{});  // (the other parity: the stage before)
@@ -590,9 +602,6 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             stage(s + 3, fb, fa, P3{}, late_, No{});
         }
     };
-    // (the prologue has issued what the loop would have issued before stage 0, in the loop's order, so this is
-    // the wait of a stage of phase 0: stage 1 has landed)
-    __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_loop()));
     // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
     // theirs one slot later; with two per SIMD the second copy of the loop is not worth its registers)
     if constexpr (kSurface) issue_surface(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});

@@ -42,23 +42,25 @@ def test_every_instantiated_shape_holds(tmp_path):
 
 
 MUTATIONS = [
-    # a stage of phase 0 lets one load too many fly: the last code load of stage s + 1 may not have landed
-    ("return phase == 0 ? issue_count(3) : phase == 2 ? issue_count(1) : 1;",
-     "return phase == 0 ? issue_count(3) + 1 : phase == 2 ? issue_count(1) : 1;", "read before a wait"),
-    # phases 1 and 3 allow a whole stage's loads instead of its last one
-    ("return phase == 0 ? issue_count(3) : phase == 2 ? issue_count(1) : 1;",
-     "return phase == 0 ? issue_count(3) : phase == 2 ? issue_count(1) : kCodeDma;", "read before a wait"),
+    # the barrier opens the stages that issue nothing instead of those that issue the loads
+    ("static constexpr bool has_barrier(int phase) { return phase % 2 == 1; }",
+     "static constexpr bool has_barrier(int phase) { return phase % 2 == 0; }", "FAIL"),
+    # a barrier in the first stage of a group only
+    ("static constexpr bool has_barrier(int phase) { return phase % 2 == 1; }",
+     "static constexpr bool has_barrier(int phase) { return phase == 1; }", "FAIL"),
+    # a stage with a barrier lets its youngest load fly: the stage after reads it without a wait of its own
+    ("static constexpr int wait_count(int phase) { return has_barrier(phase) ? 0 : 63; }",
+     "static constexpr int wait_count(int phase) { return has_barrier(phase) ? 1 : 63; }", "read before a wait"),
     # the pair of stages is requested one stage too far ahead: into slots that are still being read
     ("return LoadItem{kLoadCode, 3 + (k & 1), k >> 1};", "return LoadItem{kLoadCode, 4 + (k & 1), k >> 1};", "FAIL"),
-    # the E8M0 bytes of the next group behind the codes instead of in front of them
-    ("if (n < small) return phase == 1 ? LoadItem{kLoadScale, 1, n} : LoadItem{kLoadWords, 2, n};",
-     "if (n >= 2 * kCodeDma) return phase == 1 ? LoadItem{kLoadScale, 1, n - 2 * kCodeDma} : LoadItem{kLoadWords, 2, n - 2 * kCodeDma};",
-     "FAIL"),
-    # the prologue's first wait forgets the second batch of MBS words
-    ("static constexpr int prologue_wait_first() { return 1 + kWordDma + 2 * kCodeDma; }",
-     "static constexpr int prologue_wait_first() { return 2 + 2 * kWordDma + 2 * kCodeDma; }", "read before a wait"),
+    # the prologue's wait lets one load of stage 1 fly, which stage 0 reads without a wait of its own
+    ("static constexpr int prologue_wait_first() { return kWordDma + 2 * kCodeDma; }",
+     "static constexpr int prologue_wait_first() { return 1 + kWordDma + 2 * kCodeDma; }", "read before a wait"),
     # the MBS words of the group after next requested a group too late
     ("LoadItem{kLoadWords, 2, n}", "LoadItem{kLoadWords, 3, n}", "FAIL"),
+    # the E8M0 bytes of the next group requested in phase 3 instead of phase 1: not published when first read
+    ("if (n < small) return phase == 1 ? LoadItem{kLoadScale, 1, n} : LoadItem{kLoadWords, 2, n};",
+     "if (n < small) return phase == 3 ? LoadItem{kLoadScale, 1, n} : LoadItem{kLoadWords, 2, n};", "FAIL"),
 ]
 
 
