@@ -2,7 +2,8 @@
 // consume every matrix-instruction result (acc += P * sigma_A * sigma_B), so this translation unit is
 // compiled with the VGPR form of the matrix instructions.  With words on both operands a wavefront owns
 // 64 x 64 outputs (two A fragments against two B fragments: four fragments to read from LDS per four products)
-// and the products sigma_A * sigma_B come from the matrix cores as well (mx_gemm_ring.h); with words on one
+// and the products sigma_A * sigma_B come from the matrix cores as well (mx_gemm_ring.h; its four pairs run in an
+// order that lets every fragment be read again from LDS two pairs before its next use); with words on one
 // operand only it owns 128 x 32 (four A fragments against one B fragment), and the 16 per-lane sigma_B values
 // of the B fragment, or the lane's sigma_A, are read from LDS once per stage and serve four products.
 // Problems with too few 256 x 128 tiles for the device take 128 x 128 tiles (64 x 32 per wavefront).

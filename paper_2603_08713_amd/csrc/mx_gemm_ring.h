@@ -69,6 +69,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // sigma_A (x) sigma_B on the matrix cores: both sides carry words, one B fragment, A fragments in couples
     constexpr bool kSurface = S::kSurface;
     constexpr int kCouples = FM / 2 * FN;  // surfaces per stage
+    // Two A fragments against two B fragments: the pairs of a stage run (A0, B0), (A1, B0), (A1, B1), (A0, B1), so
+    // that a fragment is read again from LDS right after its last pair and every fragment of the next stage has been
+    // requested at least two pairs before its first use.  A0 alone is used by the last pair and by the next stage's
+    // first: it has two register sets, taken in turn by stage parity.
+    constexpr bool kSnake = kSurface && FM == 2 && FN == 2;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -314,7 +319,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 #pragma unroll
             for (int g = 0; g < kCouples; ++g) {
                 const int c = g % (FM / 2);
-                const bool swap = ((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0;
+                // (kSnake: the second couple runs A1 first, so its halves are the other way round)
+                const bool swap = (((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0) != (kSnake && g == 1);
                 sig_m[par][g] = sig[(wm * FM + 2 * c) * 32 + (swap ? l ^ 32 : l)];
             }
 #pragma unroll
@@ -365,6 +371,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_first()));
     bare_barrier();
     Frags f0, f1;
+    Frags alt;  // kSnake: the second register set of A fragment 0 (only m[0] and scl_m[0] are used)
     if constexpr (kMbs) {
         convert_sigma(0);
         convert_sigma(1);
@@ -415,9 +422,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // par in.
     auto fold = [&](auto par_, auto q_, auto half_) {
         constexpr int par = decltype(par_)::value, q = decltype(q_)::value, half = decltype(half_)::value;
-        constexpr int i = q % FM, j = q / FM, g = j * (FM / 2) + i / 2;
+        constexpr int i = kSnake ? (q == 1 || q == 2 ? 1 : 0) : q % FM, j = q / FM, g = j * (FM / 2) + i / 2;
         constexpr bool in_a = ((kCouples % 2 == 1 ? par : 0) + g) % 2 == 0;
-        constexpr int base = in_a ? (i % 2 == 0 ? 16 : 0) : (i % 2 == 0 ? 0 : 16);
+        constexpr bool first = kSnake ? q % 2 == 0 : i % 2 == 0;  // the couple's fragment that is folded in first
+        constexpr int base = in_a ? (first ? 16 : 0) : (first ? 0 : 16);
 #pragma unroll
         for (int e = half * 8; e < half * 8 + 8; ++e)
             acc[i][j][e] = fmaf(prod[q % 2][e], in_a ? surf_a[base + e] : surf_b[base + e], acc[i][j][e]);
@@ -469,7 +477,67 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 });
             }
         };
-        if constexpr (kSurface) {
+        if constexpr (kSnake) {
+            // As the branch below (every product instruction followed by half of the multiply-adds of the pair
+            // before, the surface instruction by loads and table work), in the pair order given at kSnake, with
+            // the LDS reads of a fragment's next contents right behind its last pair.
+            using I0 = std::integral_constant<int, 0>;
+            using I1 = std::integral_constant<int, 1>;
+            constexpr int par = kPhase % 2;
+            read_sigma_m(s + 1, NextPar{});
+            auto refill = [&](Frags& dst, auto f_) {  // fragment f of stage s + 1: two code pieces and the E8M0 pair
+                static_for<3>([&](auto part_) {
+                    read_item(dst, s + 1, NextSlot{}, std::integral_constant<int, decltype(f_)::value * 3 + decltype(part_)::value>{});
+                });
+            };
+            static_for<4>([&](auto q_) {
+                constexpr int q = decltype(q_)::value, i = (q == 1 || q == 2) ? 1 : 0, j = q / 2;
+                using Before = std::integral_constant<int, (q + 3) % 4>;
+                using BeforePar = std::conditional_t<q == 0, NextPar, Par>;  // the last pair of the stage before
+                // A0 of this stage sits in `cur` (even stages) or in `alt` (odd stages)
+                const v4i m0 = i == 0 && par == 1 ? alt.m[0][0] : cur.m[i][0], m1 = i == 0 && par == 1 ? alt.m[0][1] : cur.m[i][1];
+                const uint32_t sm = i == 0 && par == 1 ? alt.scl_m[0] : cur.scl_m[i];
+                v16f zero;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                prod[q % 2] = mfma_fp4_wide<0, 0>(cur.n[j][0], m0, zero, cur.scl_n[j], sm);
+                __builtin_amdgcn_sched_barrier(0);
+                fold(BeforePar{}, Before{}, I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                prod[q % 2] = mfma_fp4_wide<1, 1>(cur.n[j][1], m1, prod[q % 2], cur.scl_n[j], sm);
+                __builtin_amdgcn_sched_barrier(0);
+                fold(BeforePar{}, Before{}, I1{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (q % 2 == 1) {
+                    constexpr int shadow = q / 2;
+                    if constexpr (shadow == 0) issue_surface(Par{}, I1{});
+                    else issue_surface(NextPar{}, I0{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // last pairs: B0 after pair 1, A1 after pair 2, B1 and this stage's A0 after pair 3; the next stage's
+                // A0 goes to the other register set and is requested with B0
+                if constexpr (q == 1) {
+                    refill(next, std::integral_constant<int, FM + 0>{});
+                    if constexpr (par == 0) refill(alt, I0{});
+                    else refill(next, I0{});
+                }
+                if constexpr (q == 2) refill(next, I1{});
+                if constexpr (q == 3) refill(next, std::integral_constant<int, FM + 1>{});
+                if constexpr (q % 2 == 1) {
+                    constexpr int shadow = q / 2;
+                    if constexpr (kIssue) {
+                        static_for<kN>([&](auto n_) {
+                            if constexpr ((decltype(n_)::value * 2) / kN == shadow) issue_load(s, phase_, n_);
+                        });
+                    }
+                    if constexpr (shadow == 1 && !Sched::has_barrier(kPhase)) {
+                        convert_sigma(s + 2);
+                        convert_sigma(s + 3);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else if constexpr (kSurface) {
             // Two wavefronts share a SIMD's matrix pipeline and its vector issue port well only if each of them
             // mixes its matrix and vector instructions finely (measured: one wavefront issuing matrix
             // instructions only and one issuing multiply-adds only slow each other down by a factor of 2.5,
