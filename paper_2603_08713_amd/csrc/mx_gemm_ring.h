@@ -204,22 +204,42 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)dst, 4, voff, min(grp, ngroups - 1) * 4, 0, 0);
         }
     };
-    // MBS words of stage s (landed and published) -> fp32 sigma = 1/F, F = 1 + m8/256 exact, reciprocal
-    // within an ulp.  Thread p serves row p; threads past the last row redo row 0 and store to the padding
-    // area, which keeps the stage body free of branches.
-    auto convert_sigma = [&](int s) {
+    // MBS words of stage s -> fp32 sigma = 1/F, F = 1 + m8/256 exact, reciprocal within an ulp.  Thread p serves
+    // row p (whose words its own wavefront has loaded, so its own wait covers them); threads past the last row
+    // redo row 0 and store to the padding area, which keeps the stage body free of branches.  The words are read
+    // from LDS at the start of a stage (load_words: those of stages s and s + 1, s even, which share a group) and
+    // converted at its end (store_sigma), so that the conversion does not wait for the LDS.
+    constexpr int kConv = ceil_div(kRows, NT);
+    struct RawWords {
+        uint32_t first[kConv], second[kConv];
+    };
+    auto load_words = [&](int s, RawWords& r) {
         const uint32_t* raw = reinterpret_cast<const uint32_t*>(smem + S::kM8Base + ((s / kRingGroup) & 1) * S::kM8Group);
+#pragma unroll
+        for (int i = 0; i < kConv; ++i) {
+            const int q = i * NT + tid;  // (a side without words reads zero and stores sigma = 1, which nobody reads)
+            const int p = (kRows % NT == 0 || q < kRows) ? q : 0;
+            // fast form: a row's four words in one dword; general form: one word per dword, [row][4]
+            r.first[i] = S::kGen ? raw[p * kRingGroup + s % kRingGroup] : raw[p];
+            r.second[i] = S::kGen ? raw[p * kRingGroup + s % kRingGroup + 1] : r.first[i];
+        }
+    };
+    auto store_sigma = [&](int s, const uint32_t (&words)[kConv]) {
         float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
 #pragma unroll
-        for (int i = 0; i < ceil_div(kRows, NT); ++i) {
-            const int q = i * NT + tid;  // (a side without words reads zero and stores sigma = 1, which nobody reads)
+        for (int i = 0; i < kConv; ++i) {
+            const int q = i * NT + tid;
             const bool live = kRows % NT == 0 || q < kRows;
-            const int p = live ? q : 0;
-            // fast form: a row's four words in one dword; general form: one word per dword, [row][4]
-            const uint32_t m8 = S::kGen ? raw[p * kRingGroup + s % kRingGroup] & 0xFFu : (raw[p] >> (8 * (s % kRingGroup))) & 0xFFu;
-            float* dst = live ? sig + p : reinterpret_cast<float*>(smem + S::kDummy);
+            const uint32_t m8 = S::kGen ? words[i] & 0xFFu : (words[i] >> (8 * (s % kRingGroup))) & 0xFFu;
+            float* dst = live ? sig + (live ? q : 0) : reinterpret_cast<float*>(smem + S::kDummy);
             *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
         }
+    };
+    auto convert_sigma_pair = [&](int s) {  // stages s and s + 1 at once (prologue)
+        RawWords r;
+        load_words(s, r);
+        store_sigma(s, r.first);
+        store_sigma(s + 1, r.second);
     };
 
     // ---- operands of one macro block in registers ----------------------------------------------------
@@ -373,8 +393,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     Frags f0, f1;
     Frags alt;  // kSnake: the second register set of A fragment 0 (only m[0] and scl_m[0] are used)
     if constexpr (kMbs) {
-        convert_sigma(0);
-        convert_sigma(1);
+        convert_sigma_pair(0);
         __builtin_amdgcn_s_waitcnt(kWaitLds);
         bare_barrier();
         read_sigma_m(0, std::integral_constant<int, 0>{});
@@ -460,6 +479,17 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             __builtin_amdgcn_s_waitcnt(wait_imm(Sched::wait_count(kPhase)));
             bare_barrier();
         }
+        // a stage without a barrier converts the words of the stages s + 2 and s + 3 at its end (published by the
+        // next stage's barrier, into the tables that the stages s - 2 and s - 1 were read from)
+        constexpr bool kConvert = kMbs && !Sched::has_barrier(kPhase);
+        RawWords words;
+        if constexpr (kConvert) load_words(s + 2, words);
+        auto convert = [&]() {
+            if constexpr (kConvert) {
+                store_sigma(s + 2, words.first);
+                store_sigma(s + 3, words.second);
+            }
+        };
         auto slip = [&](auto t_) {  // after matrix instruction t: LDS reads and loads whose turn it is
             constexpr int t = decltype(t_)::value;
             if constexpr (!kMbs) {
@@ -530,10 +560,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                             if constexpr ((decltype(n_)::value * 2) / kN == shadow) issue_load(s, phase_, n_);
                         });
                     }
-                    if constexpr (shadow == 1 && !Sched::has_barrier(kPhase)) {
-                        convert_sigma(s + 2);
-                        convert_sigma(s + 3);
-                    }
+                    if constexpr (shadow == 1) convert();
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -585,12 +612,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                             if constexpr ((decltype(n_)::value * kShadows) / kN == shadow) issue_load(s, phase_, n_);
                         });
                     }
-                    // (the stages without a barrier convert for two stages: what they write is published by the next
-                    // stage's barrier, into the tables that the stages s - 2 and s - 1 were read from)
-                    if constexpr (shadow == kShadows - 1 && !Sched::has_barrier(kPhase)) {
-                        convert_sigma(s + 2);
-                        convert_sigma(s + 3);
-                    }
+                    if constexpr (shadow == kShadows - 1) convert();
                     __builtin_amdgcn_sched_barrier(0);
                 }
             });
@@ -610,10 +632,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             };
             issue(std::integral_constant<int, 0>{});
             // (behind the first pair's instructions: the LDS round trip of the MBS words then overlaps their run)
-            if constexpr (!Sched::has_barrier(kPhase)) {  // for two stages; published by the next stage's barrier
-                convert_sigma(s + 2);
-                convert_sigma(s + 3);
-            }
+            convert();
             if constexpr (kDefer) {
                 __builtin_amdgcn_sched_barrier(0);
                 retire(NextPar{}, std::integral_constant<int, kPairs - 1>{});  // (the other parity: the stage before)
