@@ -26,16 +26,19 @@
 // Only those stages open with a wait for the wavefront's loads and the workgroup's barrier, which publishes
 // stages s + 1 and s + 2 and, because every wavefront has finished reading stage s by then, frees the two slots;
 // the stages between read what is published already, so the wavefronts may drift up to two stages apart.
-// E8M0 bytes and MBS words travel per group of four stages: a row's 16
-// scale bytes as one 16-byte piece, its 4 words as one dword (two LDS slots each); the general form, for K
-// and row addresses that do not allow such pieces, is described at RingShape.
+// E8M0 bytes and MBS words travel per group of four stages: a row's 16 scale bytes as one 16-byte piece, its
+// 4 words as one dword (two LDS slots each); the general form, for K and row addresses that do not allow such
+// pieces, is described at RingShape.  With MBS a wavefront keeps one set of fragment registers and reads a
+// fragment's next contents from LDS right behind the last pair that uses it; a stage must not begin with a
+// fragment requested at the end of the stage before (the wait for the LDS would stand in front of its first
+// matrix instruction), which the pair order of the 64 x 64 arrangement avoids (kSnake below).
 //
 // MBS (Sec. 4.3.2, App. E): the two instructions of a fragment pair start from a zero accumulator and
 // yield the partial sums of one macro block, which the vector ALUs fold into the running result as
 //     acc[m, n] += P[m, n] * sigma_A[m, g] * sigma_B[n, g],      sigma = 1 / (1 + m8 / 256).
-// The sigma values of stages s + 2 and s + 3 are computed by the workgroup during a stage s without a barrier (one
-// reciprocal per row and stage) into two of four LDS tables, which the next stage's barrier publishes.  With words on one operand only, a wavefront folds a product in while the next
-// pair's instructions run.
+// The sigma values of stages s + 2 and s + 3 are computed by the workgroup during a stage s without a barrier
+// (one reciprocal per row and stage) into two of four LDS tables, which the next stage's barrier publishes.
+// With words on one operand only, a wavefront folds a product in while the next pair's instructions run.
 //
 // Where both operands carry words, the surface S = sigma_A (x) sigma_B of Sec. 4.3.2 is itself a matrix product
 // with K = 1, and the matrix cores form it: one v_mfma_f32_32x32x1_2b_f32 takes sigma_B[n] on its rows and, in
