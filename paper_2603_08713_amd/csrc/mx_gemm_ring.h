@@ -77,6 +77,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // requested at least two pairs before its first use.  A0 alone is used by the last pair and by the next stage's
     // first: it has two register sets, taken in turn by stage parity.
     constexpr bool kSnake = kSurface && FM == 2 && FN == 2;
+    // The other arrangements with MBS have one B fragment, which every pair of a stage uses: read again behind the
+    // last pair, it would be waited for at the start of the next stage.  With the surface (two A fragments, two
+    // pairs) all fragments have two register sets, taken in turn, and the next stage's are requested behind the
+    // first pair; with words on one operand the B fragment alone has two.
+    constexpr bool kDoubleAll = kSurface && !kSnake, kDoubleB = kMbs && !kSurface && FN == 1;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -394,7 +399,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_first()));
     bare_barrier();
     Frags f0, f1;
-    Frags alt;  // kSnake: the second register set of A fragment 0 (only m[0] and scl_m[0] are used)
+    Frags alt;  // the second register set of A fragment 0 (kSnake: m[0], scl_m[0]) or of the B fragment (kDoubleB: n[0], scl_n[0])
     if constexpr (kMbs) {
         convert_sigma_pair(0);
         __builtin_amdgcn_s_waitcnt(kWaitLds);
@@ -420,13 +425,16 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     v16f prod[2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) prod[0][e] = prod[1][e] = 0.f;
-    auto product = [&](const Frags& f, auto q_) {
+    auto product = [&](const Frags& f, auto q_, auto par_) {
         constexpr int q = decltype(q_)::value, j = q / FM, i = q % FM;
+        constexpr bool other = kDoubleB && decltype(par_)::value == 1;  // odd stages: the B fragment sits in `alt`
+        const v4i n0 = other ? alt.n[0][0] : f.n[j][0], n1 = other ? alt.n[0][1] : f.n[j][1];
+        const uint32_t sn = other ? alt.scl_n[0] : f.scl_n[j];
         v16f zero;
 #pragma unroll
         for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-        prod[q % 2] = mfma_fp4_wide<0, 0>(f.n[j][0], f.m[i][0], zero, f.scl_n[j], f.scl_m[i]);
-        prod[q % 2] = mfma_fp4_wide<1, 1>(f.n[j][1], f.m[i][1], prod[q % 2], f.scl_n[j], f.scl_m[i]);
+        prod[q % 2] = mfma_fp4_wide<0, 0>(n0, f.m[i][0], zero, sn, f.scl_m[i]);
+        prod[q % 2] = mfma_fp4_wide<1, 1>(n1, f.m[i][1], prod[q % 2], sn, f.scl_m[i]);
     };
     // The surface of couple g of the stage with parity par: g = j FM / 2 + c is A fragments 2 c and 2 c + 1 against
     // B fragment j.  Consecutive couples alternate between the two buffers; a stage with an odd number of couples
@@ -595,6 +603,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 __builtin_amdgcn_sched_barrier(0);
                 fold(BeforePar{}, Before{}, I1{});
                 __builtin_amdgcn_sched_barrier(0);
+                // (two register sets: the next stage's fragments are requested behind the first pair)
+                if constexpr (kDoubleAll && q == 0) static_for<kReads>([&](auto idx_) { read_item(next, s + 1, NextSlot{}, idx_); });
                 if constexpr (q % 2 == 1) {
                     constexpr int shadow = q / 2;
                     if constexpr (shadow + 1 < kShadows) issue_surface(Par{}, std::integral_constant<int, shadow + 1>{});
@@ -603,7 +613,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                     // in its shadow: refill the fragments whose last pair lies in this couple with the next stage's
                     // data (A fragment i serves the pairs (0, i) .. (FN - 1, i), B fragment j the pairs (j, 0) ..
                     // (j, FM - 1)), this stage's loads, and at the end the table work
-                    static_for<FM + FN>([&](auto f_) {
+                    if constexpr (!kDoubleAll) static_for<FM + FN>([&](auto f_) {
                         constexpr int f = decltype(f_)::value;
                         constexpr int last = f < FM ? (FN - 1) * FM + f : (f - FM) * FM + FM - 1;  // last pair that reads it
                         if constexpr (last == q || last == q - 1) static_for<3>([&](auto part_) {
@@ -625,8 +635,15 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             // that uses it have been issued.
             auto issue = [&](auto p_) {  // the instructions of pair p, then the refills it makes possible
                 constexpr int pj = decltype(p_)::value / FM, pi = decltype(p_)::value % FM;
-                product(cur, p_);
-                if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
+                product(cur, p_, Par{});
+                if constexpr (kDoubleB) {
+                    // the next stage's B fragment into the register set this stage does not use, behind the first pair
+                    if constexpr (decltype(p_)::value == 0) static_for<3>([&](auto part_) {
+                        using Idx = std::integral_constant<int, FM * 3 + decltype(part_)::value>;
+                        if constexpr (kPhase % 2 == 0) read_item(alt, s + 1, NextSlot{}, Idx{});
+                        else read_item(next, s + 1, NextSlot{}, Idx{});
+                    });
+                } else if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
                     read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
                 });
                 if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
@@ -677,7 +694,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         using P2 = std::integral_constant<int, 2>;
         using P3 = std::integral_constant<int, 3>;
         Frags& fa = f0;
-        Frags& fb = kMbs ? f0 : f1;  // the MBS path refills one set in place
+        Frags& fb = kMbs && !kDoubleAll ? f0 : f1;  // the MBS path refills one set in place (kDoubleAll aside)
         int s = 0;
         for (; s < n_issue; s += 4) {
             stage(s, fa, fb, P0{}, late_, Yes{});
