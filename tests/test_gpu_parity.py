@@ -980,6 +980,33 @@ def test_config_llama70b_ffn_plain_sampled(mx, oracle):
     _LLAMA70B.clear()
 
 
+def test_config_llama70b_ffn_launches_agree_under_disturbance(mx):
+    """The benchmark's shape again: the wavefronts of a workgroup synchronise every other stage only and may drift two
+    stages apart, so the timing of a launch varies with what else the memory system is doing.  Launches alternate with
+    a large fill that evicts the caches, in all three MBS forms and the plain one; every output must equal the first
+    launch's bit for bit (a difference would be a synchronisation hole)."""
+    t = llama70b_operands(mx)
+    a, b = t["a"], t["b"]
+    forms = {
+        "both": lambda out: mx.mx_gemm_mbs(*a, *b, "bf16", out=out),
+        "a only": lambda out: mx.mx_gemm_mbs(*a, b[0], b[1], None, "bf16", out=out),
+        "b only": lambda out: mx.mx_gemm_mbs(a[0], a[1], None, *b, "bf16", out=out),
+        "plain": lambda out: mx.mx_gemm(a[0], a[1], b[0], b[1], "bf16", out=out),
+    }
+    junk = torch.empty(384 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+    first = torch.empty((8192, 28672), dtype=torch.bfloat16, device="cuda")
+    again = torch.empty_like(first)
+    for name, run in forms.items():
+        run(first)
+        for rep in range(6):
+            if rep % 2 == 0:
+                junk.fill_(rep)
+            again.fill_(0)
+            run(again)
+            assert torch.equal(first, again), (name, rep)
+    del junk, first, again
+
+
 def test_config_moe_grouped_sampled(mx, oracle):
     """32 experts of 2880 x 2880, 8192 tokens routed top-4 with Zipf load (32768 rows in expert order): rows
     sampled from every non-empty expert against the oracle; K = 2880 ends in a half macro block."""
