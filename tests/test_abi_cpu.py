@@ -75,6 +75,28 @@ def test_lut_entry_points_reject_bad_arguments(lib):
     assert q(A16, 0, 64, 64, 2, A16, 1, A16, A16, A16, None) == 0
 
 
+def test_gemm_plan_names_the_kernel_a_problem_takes(lib):
+    """The planner is host code: which form and tile shape the dispatcher picks, per configuration of the workload
+    list, without launching anything."""
+    import ctypes
+
+    def plan(M, N, K, a=1, b=1, grouped=0):
+        buf = ctypes.create_string_buffer(512)
+        assert lib.mx_internal_gemm_plan(M, N, K, a, b, grouped, buf, 512) == 0
+        return buf.value.decode()
+
+    big = plan(8192, 28672, 8192)
+    assert "fast form" in big and "256x128 tile" in big and "64x64" in big and "A and B" in big
+    assert "128x32" in plan(8192, 28672, 8192, 1, 0) and "MBS words on A" in plan(8192, 28672, 8192, 1, 0)
+    assert "256x256" in plan(8192, 28672, 8192, 0, 0) and "no MBS" in plan(8192, 28672, 8192, 0, 0)
+    assert "128x128" in plan(2048, 2048, 2048)                      # too few large tiles for 256 compute units
+    assert "few rows" in plan(16, 4096, 4096)                       # decode
+    assert "general form" in plan(32768, 2880, 2880, 1, 1, 1)       # grouped, K % 512 != 0
+    assert "single scale bytes" in plan(512, 512, 2016)             # K % 64 == 32
+    assert lib.mx_internal_gemm_plan(8, 8, 48, 1, 1, 0, ctypes.create_string_buffer(8), 8) == -1   # K % 32
+    assert lib.mx_internal_gemm_plan(8, 8, 64, 1, 1, 0, None, 0) == -1
+
+
 def test_version_and_status_strings(lib):
     assert lib.mx_version() >= 100
     seen = set()
