@@ -204,9 +204,10 @@ int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scal
 
 /* mx_gemm_mbs for operands in 8-bit or in 6-bit element formats (A's and B's may differ, but both are 8-bit or
  * both 6-bit): the same sum, the same MBS correction per 128 K-elements (Sec. 4.3.2, which does not depend on
- * the element format), on the same scaled matrix instruction.  Covers, for 8-bit operands, K > 0, K % 128 == 0,
- * codes 16-byte and scale arrays 4-byte aligned; for 6-bit operands K > 0, K % 512 == 0, codes and scale arrays
- * 16-byte and MBS arrays 4-byte aligned; anything else returns MX_EUNSUPPORTED and nothing is launched.
+ * the element format), on the same scaled matrix instruction.  Covers K > 0, K % 128 == 0, codes 16-byte and
+ * scale arrays 4-byte aligned; anything else returns MX_EUNSUPPORTED and nothing is launched.  (K % 512 == 0,
+ * 16-byte aligned scale arrays and 4-byte aligned MBS arrays take a faster form of the kernel; with M <= 64 and
+ * K <= 8192 besides, a kernel that streams the weights once.)
  *
  * Accumulation contract.  The exact result is  C[m, n] = sum over macro blocks g of sigma_A[m, g] sigma_B[n, g]
  * P_g[m, n],  P_g = the sum over the 128 K-elements of g of the products of the dequantized elements.  What is
@@ -227,6 +228,17 @@ int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scal
 int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
                      mx_elem_t b_elem, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
                      int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream);
+
+/* mx_gemm_mbs_grouped for operands in 8-bit or in 6-bit element formats (Sec. 5.3, the MoE case; formats,
+ * conditions on K and alignment, and the accumulation contract as for mx_gemm_mbs_elem): group e owns rows
+ * row_offsets[e] .. row_offsets[e+1]-1 of A and C (row_offsets: DEVICE int64 [num_groups+1], non-decreasing,
+ * row_offsets[0] = 0, row_offsets[num_groups] <= M_total; empty groups are allowed) and is multiplied with the
+ * e-th of the num_groups [N, K] weights stacked along rows in b_*.  Rows of C at or beyond
+ * row_offsets[num_groups] are not written. */
+int mx_gemm_mbs_elem_grouped(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
+                             mx_elem_t b_elem, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
+                             int32_t num_groups, const int64_t* row_offsets, int64_t M_total, int64_t N, int64_t K,
+                             mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream);
 
 /* Human-readable text for a status code (static storage, host pointer). */
 const char* mx_status_string(int status);

@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_internal_gemm.argtypes = [vp, vp, vp, vp, vp, vp, ci, i32, vp, i64, i64, i64, ci, vp, i64, ci, ci, vp]
     L.mx_internal_gemm_plan.restype = ci
     L.mx_internal_gemm_plan.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.c_char_p, ci]
+    L.mx_gemm_mbs_elem_grouped.restype = ci
+    L.mx_gemm_mbs_elem_grouped.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, ctypes.c_int32, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_internal_gemm_elem.restype = ci
     L.mx_internal_gemm_elem.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, i64, i64, i64, ci, vp, i64, ci, vp]
     _lib = L
@@ -107,8 +109,9 @@ _dev = threading.local()
 @contextlib.contextmanager
 def forced(**choices):
     """quantize_hw / quantize_elem_hw = 0 or 1 (rounding implementation), gemm_shape = a kernel form and
-    tile shape code of mx_gemm.hip, gemm_elem_general = 1 (general form of the 8-/6-bit GEMM kernel)."""
-    allowed = {"quantize_hw", "quantize_elem_hw", "gemm_shape", "gemm_elem_general"}
+    tile shape code of mx_gemm.hip, gemm_elem = which kernel takes an 8-/6-bit GEMM (1 = the main kernel's general
+    form, 2 = the main kernel in the form the problem allows, 3 = the few-row kernel)."""
+    allowed = {"quantize_hw", "quantize_elem_hw", "gemm_shape", "gemm_elem"}
     if set(choices) - allowed:
         raise TypeError("unknown choice: %s" % sorted(set(choices) - allowed))
     old = getattr(_dev, "choices", {})
@@ -403,14 +406,34 @@ def mx_gemm_mbs_elem(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales
     if b_scales.shape[1] * 32 != K or a_codes.shape[1] != elem_code_bytes(a_elem, K) or b_codes.shape[1] != elem_code_bytes(b_elem, K):
         raise ValueError("A and B disagree on K, or a code array does not have the row length of its format")
     code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
-    if _forced("gemm_elem_general"):
+    if _forced("gemm_elem"):
         _check(load_library().mx_internal_gemm_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
                                                     _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out),
-                                                    ldc, 1, _stream()), "mx_gemm_mbs_elem (mx_internal_gemm_elem)")
+                                                    ldc, int(_forced("gemm_elem")), _stream()),
+               "mx_gemm_mbs_elem (mx_internal_gemm_elem)")
     else:
         _check(load_library().mx_gemm_mbs_elem(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
                                                _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), M, N, K, code, _ptr(out), ldc,
                                                _stream()), "mx_gemm_mbs_elem")
+    return out
+
+
+def mx_gemm_mbs_elem_grouped(a_elem, a_codes, a_scales, a_mbs, b_elem, b_codes, b_scales, b_mbs, row_offsets, N,
+                             out_dtype="f32", out=None):
+    """Grouped GEMM for operands in 8-bit or 6-bit element formats: rows row_offsets[e]..row_offsets[e+1]-1 of A
+    times B_e^T, B stacked [G*N, ...]."""
+    torch = _torch()
+    M, K = a_codes.shape[0], a_scales.shape[1] * 32
+    if row_offsets.dtype != torch.int64 or not row_offsets.is_cuda or not row_offsets.is_contiguous():
+        raise TypeError("row_offsets must be a contiguous int64 CUDA tensor")
+    G = row_offsets.numel() - 1
+    if (b_codes.shape[0] != G * N or b_scales.shape[1] * 32 != K or a_codes.shape[1] != elem_code_bytes(a_elem, K)
+            or b_codes.shape[1] != elem_code_bytes(b_elem, K)):
+        raise ValueError("B must hold num_groups stacked [N, K] weights in its format's row length")
+    code, out, ldc = _c_tensor(M, N, out_dtype, out, a_codes.device)
+    _check(load_library().mx_gemm_mbs_elem_grouped(_elem(a_elem), _ptr(a_codes), _ptr(a_scales), _ptr(a_mbs), _elem(b_elem),
+                                                   _ptr(b_codes), _ptr(b_scales), _ptr(b_mbs), G, _ptr(row_offsets), M, N, K,
+                                                   code, _ptr(out), ldc, _stream()), "mx_gemm_mbs_elem_grouped")
     return out
 
 

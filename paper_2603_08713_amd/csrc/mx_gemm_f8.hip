@@ -39,7 +39,13 @@
 // lane half holds one whole block per instruction (instruction kk: block kk + 2 h) with the lane's own E8M0
 // byte.  A stage is 96 bytes of a row; so that no 128-byte line of memory is fetched twice, the ring slots hold
 // planes instead of stages: slot L = bytes 128 L .. + 127 of the 384 that a group of four stages takes of each
-// row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.
+// row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.  Their general form (any
+// K % 128 == 0) keeps a stage per ring slot like the 8-bit one: the 96 bytes of a row sit in places 0 .. 5 of the
+// row's eight 16-byte places, a quarter of the lanes of a code load fetch nothing, and a stage's bytes straddle the
+// 128-byte lines of memory, so half of the lines are fetched twice (from the L2).
+//
+// Grouped problems (mx_gemm_mbs_elem_grouped) run the general form: a tile-row belongs to one group, whose rows of
+// A and C and whose weight the workgroup looks up in row_offsets.
 #include "mx_gemm_f8_schedule.h"
 #include "mx_gemm_shared.h"
 #include "mx_internal.h"
@@ -54,11 +60,13 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     constexpr int FM = S::FM, FN = S::FN, TM = S::TM, TN = S::TN, NW = S::NW, kCodeDma = S::kCodeDma;
     // 6-bit codes (format selectors 2, 3) come packed, 24 bytes per block; both operands have the same width
     constexpr bool kSix = kFmtA >= 2;
-    static_assert(kSix == (kFmtB >= 2) && (!kSix || kFast), "6-bit operands: both, and the fast form only");
+    static_assert(kSix == (kFmtB >= 2), "6-bit operands: both or neither");
+    // fast form: ring slots hold planes; general form: a slot holds a stage, six of a row's eight 16-byte places used
+    constexpr bool kSixPlanes = kSix && kFast, kSixGen = kSix && !kFast;
     constexpr int kRowStage = kSix ? 96 : kF8RowStage;  // code bytes per row and stage
     // loads a wavefront makes per stage: what the stage's wait counts (a count that assumed more would let the
     // youngest loads of the stage it is about to read stay in flight)
-    using Sched = F8Schedule<kSix ? kF8Six : kFast ? kF8Fast : kF8General, kMbs>;
+    using Sched = F8Schedule<kSixPlanes ? kF8Six : kFast ? kF8Fast : kF8General, kMbs>;
     constexpr int kLoads = Sched::kLoads;
     static_assert(kLoads == S::kLoads - (kFast || kMbs ? 0 : 2) && Sched::kCodeDma == kCodeDma, "the schedule describes this kernel");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -74,13 +82,34 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     const int band_rows = min(g.tiles_m - first_m, kF8GroupM);
     const int tm = first_m + (linear % band) % band_rows;
     const int tn = (linear % band) / band_rows;
-    const int64_t a_row0 = (int64_t)tm * TM, b_row0 = (int64_t)tn * TN;
+    // Rows of A and C this tile covers and the rows of B it multiplies with.  Grouped (general form only): tile-rows
+    // are counted group by group; group e owns rows row_offsets[e] .. row_offsets[e + 1] - 1 and the e-th of the
+    // stacked [N, K] weights.
+    int64_t a_row0 = (int64_t)tm * TM, a_end = g.M, b_row0 = (int64_t)tn * TN, b_end = g.N;
+    if constexpr (!kFast) {
+        if (g.num_groups > 0) {
+            int e = 0, first = 0;  // first tile-row of group e
+            int64_t lo = g.row_offsets[0], hi = lo;
+            for (;; ++e) {
+                if (e == g.num_groups) return;  // tile-rows beyond the last group (the grid is an upper bound)
+                hi = g.row_offsets[e + 1];
+                const int rows_e = (int)((hi - lo + TM - 1) / TM);
+                if (tm < first + rows_e) break;
+                first += rows_e;
+                lo = hi;
+            }
+            a_row0 = lo + (int64_t)(tm - first) * TM;
+            a_end = hi;
+            b_row0 = (int64_t)e * g.N + (int64_t)tn * TN;
+            b_end = (int64_t)(e + 1) * g.N;
+        }
+    }
 
     const int K = (int)g.K, scale_bytes = K >> 5, nmac = K / kMacro, nstages = nmac;
     const int row_bytes = kSix ? K / 4 * 3 : K;
     // buffer resources rebased to the tile's first row and sized to its valid rows: rows past the end read zero
     const int kRsrcFlags = 0x00020000;
-    const int64_t a_rows = min((int64_t)TM, g.M - a_row0), b_rows = min((int64_t)TN, g.N - b_row0);
+    const int64_t a_rows = min((int64_t)TM, a_end - a_row0), b_rows = min((int64_t)TN, b_end - b_row0);
     const __amdgpu_buffer_rsrc_t a_codes = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(g.a_codes) + a_row0 * row_bytes, 0, (int)(a_rows * row_bytes), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t b_codes = __builtin_amdgcn_make_buffer_rsrc(
@@ -109,8 +138,12 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // unit of loading is therefore a plane, 128 bytes of every row, a third of the group of four stages (384 bytes
     // a row).  Ring slot L holds plane L of the current group, in the 8-bit layout, and is loaded again, with the
     // next group's plane, during stage L + 1 of the group, after the last fragment that reads it has been fetched.
+    // (6-bit general form: a slot holds a stage like an 8-bit one; a row's places 6 and 7 are never read, and the
+    // lanes that would fill them fetch nothing)
     const int code_row0 = w * 8 + (l >> 3);
-    const int code_off0 = code_row0 * row_bytes + (((l & 7) ^ ((code_row0 >> 1) & 7)) * 16);
+    const int code_piece = (l & 7) ^ ((code_row0 >> 1) & 7);
+    const bool code_idle = kSixGen && code_piece >= 6;
+    const int code_off0 = code_row0 * row_bytes + code_piece * 16;
     // general form: a lane's E8M0 dword per fragment and stage, and the MBS word of the row it converts
     const int scale_off_a0 = (wm * FM * 32 + lr) * scale_bytes, scale_off_b0 = (wn * FN * 32 + lr) * scale_bytes;
     const int m8_off_a = (wm * FM * 32 + l) * nmac, m8_off_b = (wn * FN * 32 + l) * nmac;
@@ -131,11 +164,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         constexpr int slot = decltype(slot_)::value, i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
         if constexpr (i < kLoadsA) {
             uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
-            const int voff = code_off0 + i * NW * 8 * row_bytes;
+            const int voff = code_idle ? kOob : code_off0 + i * NW * 8 * row_bytes;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         } else if constexpr (i < kCodeDma) {
             uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
-            const int voff = code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
+            const int voff = code_idle ? kOob : code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         }
     };
@@ -212,8 +245,8 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // 384, that is the 16-byte pieces 6 q + 3 lh .. + 2 of the group's 24 (eight to a plane, swizzled like the
     // 8-bit pieces): instruction 0 reads the first piece and half of the second, instruction 1 the other half and
     // the third.
-    int six_a[kSix ? 4 : 1][3], six_b[kSix ? 4 : 1][3];
-    if constexpr (kSix) {
+    int six_a[kSixPlanes ? 4 : 1][3], six_b[kSixPlanes ? 4 : 1][3];
+    if constexpr (kSixPlanes) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -227,6 +260,23 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             }
     }
 
+    // 6-bit, general form: the stage's six pieces sit at places 0 .. 5 of the row's eight, swizzled like the 8-bit
+    // pieces; the lane's blocks are pieces 3 lh .. 3 lh + 2.  Slot and fragment go into the instruction's constant,
+    // with a second copy of the registers for A's third slot as above.
+    int gsix_b[3], gsix_a[3], gsix_a_hi[3];
+    if constexpr (kSixGen) {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const int at = lr * kF8RowStage + (((3 * lh + c) ^ ((lr >> 1) & 7)) * 16);
+            gsix_b[c] = S::kBaseB + wn * FN * 32 * kF8RowStage + at;
+            gsix_a[c] = S::kBaseA + wm * FM * 32 * kF8RowStage + at;
+            gsix_a_hi[c] = gsix_a[c] + 65536;
+            asm volatile("" : "+v"(gsix_b[c]));
+            asm volatile("" : "+v"(gsix_a[c]));
+            asm volatile("" : "+v"(gsix_a_hi[c]));
+        }
+    }
+
     // Operands of one macro block in registers.  They are refilled in place: a fragment takes the next stage's
     // data right after the last matrix instruction that reads it has been issued.
     v8i fa[FM][2], fb[FN][2];
@@ -238,8 +288,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         constexpr bool is_a = decltype(is_a_)::value;
         v8i v;
         if constexpr (kSix) {
-            const int* at = is_a ? six_a[slot] : six_b[slot];
-            constexpr int row0 = idx * 32 * kF8RowStage;
+            // (fast form: slot_ is the stage's place in its group; general form: the ring slot, in the constant)
+            constexpr int off = kSixGen ? (is_a ? slot * S::kStageA : slot * S::kStageB) : 0;
+            constexpr bool far = kSixGen && is_a && off + idx * 32 * kF8RowStage >= 65536;
+            const int* at = kSixGen ? (is_a ? (far ? gsix_a_hi : gsix_a) : gsix_b) : (is_a ? six_a[slot] : six_b[slot]);
+            constexpr int row0 = idx * 32 * kF8RowStage + (far ? off - 65536 : off);
             // The middle piece is read once, whole, into registers 4 .. 7 of instruction 0's operand (the matrix
             // instruction takes six registers of a 6-bit operand; the last two ride along) and its second half is
             // copied into registers 0 and 1 of instruction 1's operand by patch_frags(), once the read has
@@ -342,7 +395,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     auto stage = [&](int s, auto slot_, auto phase_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
         constexpr int p = decltype(phase_)::value % S::kGroup;  // fast form: the stage's place in its group
-        using Next = std::integral_constant<int, kSix ? (p + 1) % S::kGroup : (slot + 1) % kF8Slots>;
+        using Next = std::integral_constant<int, kSixPlanes ? (p + 1) % S::kGroup : (slot + 1) % kF8Slots>;
         // own loads of stage s + 1 have landed (those of stage s + 2 may still fly; the fast form's group loads
         // are requested ahead of a stage's codes, so they have landed a stage after their request); own LDS
         // traffic is done.  (The count is only right if every load of the earlier issue() calls has been issued
@@ -377,10 +430,10 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         issue_regs(st3, slot_);
         // (6-bit: plane p - 1 of the next group, which the last group fetches from itself again; nothing in the
         // group's first stage)
-        using CodeSlot = std::integral_constant<int, kSix ? (p > 0 ? p - 1 : 0) : slot>;
-        const int code_soff = kSix ? min(s / S::kGroup + 1, ngroups - 1) * (S::kGroup * kRowStage) + (p - 1) * 128 : st3 * kRowStage;
+        using CodeSlot = std::integral_constant<int, kSixPlanes ? (p > 0 ? p - 1 : 0) : slot>;
+        const int code_soff = kSixPlanes ? min(s / S::kGroup + 1, ngroups - 1) * (S::kGroup * kRowStage) + (p - 1) * 128 : st3 * kRowStage;
         auto issue_next = [&](auto i_) __attribute__((always_inline)) {
-            if constexpr (!kSix || p > 0) issue_code(code_soff, CodeSlot{}, i_);
+            if constexpr (!kSixPlanes || p > 0) issue_code(code_soff, CodeSlot{}, i_);
         };
 
         // sigma of this lane's output row per A fragment; of its 16 output columns per B fragment, kept as four
@@ -459,7 +512,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
 
     // ---- prologue: three stages of loads in flight, the fragments of stage 0 into registers ----
     if constexpr (kFast) issue_group(0, std::integral_constant<int, 0>{});
-    if constexpr (kSix) {  // the three planes of group 0
+    if constexpr (kSixPlanes) {  // the three planes of group 0
         static_for<kF8Slots>([&](auto L_) {
             static_for<kCodeDma>([&](auto i_) { issue_code(decltype(L_)::value * 128, L_, i_); });
         });
@@ -512,7 +565,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     bare_barrier();  // every wavefront's loads have landed and all LDS reads are done: the LDS is free
     constexpr int kCols = FN * 32;
     uint8_t* stg = smem + w * S::kStageRegion;
-    const int64_t m0 = a_row0 + wm * FM * 32, n0 = b_row0 + wn * kCols;
+    const int64_t m0 = a_row0 + wm * FM * 32, n0 = (int64_t)tn * TN + wn * kCols;
     auto flush = [&](auto bf16_) __attribute__((always_inline)) {
         constexpr bool kBf16 = decltype(bf16_)::value;
         constexpr int esz = kBf16 ? 2 : 4, per = 16 / esz;
@@ -537,7 +590,7 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                 const int row = decltype(p_)::value * rows_per_pass + rd_row;
                 const v4i v = *reinterpret_cast<const v4i*>(stg + row * pitch + rd_chunk * 16);
                 const int64_t m = m0 + i * 32 + row;
-                if (m < g.M && n < g.N) {
+                if (m < a_end && n < g.N) {
                     uint8_t* o = static_cast<uint8_t*>(g.C) + (m * g.ldc + n) * esz;
                     if (whole) {
                         __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(o));
@@ -571,51 +624,61 @@ int launch_f8_kernel(const GemmArgs& g, unsigned blocks, hipStream_t s) {
 template <int kFmtA, int kFmtB>
 int launch_f8(GemmArgs g, bool use_mbs, bool force_general, hipStream_t s) {
     using S = F8Shape<true>;
-    const int64_t tiles_m = (g.M + S::TM - 1) / S::TM, tiles_n = (g.N + S::TN - 1) / S::TN;
+    // grouped: every group may end with a partial tile-row, so this is an upper bound (the surplus exits)
+    const int64_t tiles_m = g.num_groups > 0 ? g.M / S::TM + g.num_groups : (g.M + S::TM - 1) / S::TM;
+    const int64_t tiles_n = (g.N + S::TN - 1) / S::TN;
     if (tiles_m * tiles_n > (int64_t)1 << 30) return MX_EINVAL;
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
     const unsigned blocks = (unsigned)(((tiles_m * tiles_n + 7) / 8) * 8);
     // fast form: E8M0 bytes and MBS words travel per group of four stages, as 16-byte pieces and dwords
-    const bool fast = !force_general && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
+    // (grouped problems take the general form: a group's rows of E8M0 bytes and MBS words start anywhere)
+    const bool fast = !force_general && g.num_groups == 0 && (g.K % 512) == 0 && aligned(g.a_scales, 16) && aligned(g.b_scales, 16) &&
                       (!g.a_mbs || aligned(g.a_mbs, 4)) && (!g.b_mbs || aligned(g.b_mbs, 4));
-    if (fast || kFmtA >= 2)  // (6-bit operands have been checked to allow the fast form)
+    if (fast)
         return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, true>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, true>(g, blocks, s);
-    if constexpr (kFmtA < 2)
-        return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, false>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, false>(g, blocks, s);
-    return MX_EUNSUPPORTED;
+    return use_mbs ? launch_f8_kernel<kFmtA, kFmtB, true, false>(g, blocks, s) : launch_f8_kernel<kFmtA, kFmtB, false, false>(g, blocks, s);
 }
 
+// force: 0 = automatic, 1 = the main kernel's general form, 2 = the main kernel in the form the problem allows, 3 = the
+// few-row kernel
 int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs, int b_elem,
-                     const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs, int64_t M, int64_t N,
-                     int64_t K, int c_dtype, void* C, int64_t ldc, void* stream, bool force_general = false) {
+                     const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs, int num_groups,
+                     const int64_t* row_offsets, bool grouped, int64_t M, int64_t N, int64_t K, int c_dtype, void* C,
+                     int64_t ldc, void* stream, int force = 0) {
     if (a_elem <= MX_ELEM_E2M1 || a_elem > MX_ELEM_E3M2 || b_elem <= MX_ELEM_E2M1 || b_elem > MX_ELEM_E3M2) return MX_EINVAL;
     if (M < 0 || N < 0 || K < 0 || (K % kBlock) != 0 || ldc < N) return MX_EINVAL;
     if (c_dtype != MX_OUT_F32 && c_dtype != MX_OUT_BF16) return MX_EINVAL;
+    if (grouped && num_groups < 0) return MX_EINVAL;
     // (a tile's rows times the bytes of a row must fit the 32-bit offsets of the buffer loads)
-    if (K > (int64_t)1 << 22 || M > (int64_t)1 << 30 || N > (int64_t)1 << 30) return MX_EINVAL;
-    if (M == 0 || N == 0) return MX_OK;
-    if (!C || (K > 0 && (!a_codes || !a_scales || !b_codes || !b_scales))) return MX_ENULL;
+    if (K > (int64_t)1 << 22 || M > (int64_t)1 << 30 || N > (int64_t)1 << 30 ||
+        (grouped && (int64_t)num_groups * N > (int64_t)1 << 40))
+        return MX_EINVAL;
+    if (M == 0 || N == 0 || (grouped && num_groups == 0)) return MX_OK;
+    if (!C || (grouped && !row_offsets) || (K > 0 && (!a_codes || !a_scales || !b_codes || !b_scales))) return MX_ENULL;
     const size_t esz = c_dtype == MX_OUT_F32 ? 4 : 2;
     if (!aligned(C, esz)) return MX_EALIGN;
     const bool a8 = a_elem == MX_ELEM_E4M3 || a_elem == MX_ELEM_E5M2, b8 = b_elem == MX_ELEM_E4M3 || b_elem == MX_ELEM_E5M2;
     if (a8 != b8 || K == 0 || (K % kMacro) != 0 || !aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(a_scales, 4) ||
         !aligned(b_scales, 4))
         return MX_EUNSUPPORTED;
-    // 6-bit operands: the kernel's fast form only
-    const bool fast_ok = (K % 512) == 0 && aligned(a_scales, 16) && aligned(b_scales, 16) && (!a_mbs || aligned(a_mbs, 4)) &&
-                         (!b_mbs || aligned(b_mbs, 4));
-    if (!a8 && !fast_ok) return MX_EUNSUPPORTED;
     if (int st = check_device()) return st;
     GemmArgs g = {};
     g.a_codes = a_codes; g.a_scales = a_scales; g.a_mbs = a_mbs;
     g.b_codes = b_codes; g.b_scales = b_scales; g.b_mbs = b_mbs;
-    g.C = C;
+    g.C = C; g.row_offsets = row_offsets;
     g.M = M; g.N = N; g.K = K; g.ldc = ldc;
+    g.num_groups = grouped ? num_groups : 0;
     g.c_bf16 = c_dtype == MX_OUT_BF16;
     g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = a_mbs || b_mbs;
+    const bool force_general = force == 1;
+    // few activation rows: the weights are streamed once, nothing is staged (mx_gemm_skinny_f8.hip)
+    const bool skinny_ok = !grouped && M <= 64 && (K % 512) == 0 && K <= 8192 && aligned(a_scales, 16) && aligned(b_scales, 16) &&
+                           (!a_mbs || aligned(a_mbs, 4)) && (!b_mbs || aligned(b_mbs, 4));
+    if (force == 3 && !skinny_ok) return MX_EINVAL;
+    if (skinny_ok && (force == 0 || force == 3)) return launch_gemm_skinny_elem(g, a_elem, b_elem, s);
     if (!a8) {
         const bool a32 = a_elem == MX_ELEM_E3M2, b32 = b_elem == MX_ELEM_E3M2;
         if (!a32 && !b32) return launch_f8<2, 2>(g, use_mbs, force_general, s);
@@ -638,13 +701,22 @@ extern "C" int mx_gemm_mbs_elem(mx_elem_t a_elem, const uint8_t* a_codes, const 
                                 const uint8_t* b_scales, const uint8_t* b_mbs_or_null, int64_t M, int64_t N, int64_t K,
                                 mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream) {
     return mx::launch_gemm_elem((int)a_elem, a_codes, a_scales, a_mbs_or_null, (int)b_elem, b_codes, b_scales,
-                                b_mbs_or_null, M, N, K, (int)c_dtype, C, ldc, stream);
+                                b_mbs_or_null, 0, nullptr, false, M, N, K, (int)c_dtype, C, ldc, stream);
+}
+
+extern "C" int mx_gemm_mbs_elem_grouped(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales,
+                                        const uint8_t* a_mbs_or_null, mx_elem_t b_elem, const uint8_t* b_codes,
+                                        const uint8_t* b_scales, const uint8_t* b_mbs_or_null, int32_t num_groups,
+                                        const int64_t* row_offsets, int64_t M_total, int64_t N, int64_t K,
+                                        mx_dtype_t c_dtype, void* C, int64_t ldc, void* stream) {
+    return mx::launch_gemm_elem((int)a_elem, a_codes, a_scales, a_mbs_or_null, (int)b_elem, b_codes, b_scales,
+                                b_mbs_or_null, num_groups, row_offsets, true, M_total, N, K, (int)c_dtype, C, ldc, stream);
 }
 
 extern "C" int mx_internal_gemm_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales,
                                      const uint8_t* a_mbs_or_null, mx_elem_t b_elem, const uint8_t* b_codes,
                                      const uint8_t* b_scales, const uint8_t* b_mbs_or_null, int64_t M, int64_t N,
-                                     int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, int force_general, void* stream) {
+                                     int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, int force, void* stream) {
     return mx::launch_gemm_elem((int)a_elem, a_codes, a_scales, a_mbs_or_null, (int)b_elem, b_codes, b_scales,
-                                b_mbs_or_null, M, N, K, (int)c_dtype, C, ldc, stream, force_general != 0);
+                                b_mbs_or_null, 0, nullptr, false, M, N, K, (int)c_dtype, C, ldc, stream, force);
 }

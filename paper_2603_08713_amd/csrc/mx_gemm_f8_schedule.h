@@ -9,7 +9,7 @@
 // stage's group of four must have landed.
 //
 // Three forms:
-//   general (8-bit, any K % 128 == 0): a stage issues, for stage s + 3, one dword of E8M0 bytes per fragment and
+//   general (8-bit and 6-bit, any K % 128 == 0): a stage issues, for stage s + 3, one dword of E8M0 bytes per fragment and
 //       (with MBS words) one word per operand into registers, then the code loads into slot s % 3, which the stage
 //       itself has left.  What was issued during the stage before may fly.
 //   fast (8-bit, K % 512 == 0, aligned rows): E8M0 bytes and MBS words travel per group of four stages: the first

@@ -54,6 +54,9 @@ int launch_gemm_wide_general(const GemmArgs& g, int tile, bool bytes, hipStream_
 // Few activation rows (M <= 64, K <= 8192, otherwise the same conditions), defined in mx_gemm_skinny.hip.
 int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s);
 int launch_gemm_skinny_fused(const GemmArgs& g, const void* x_bf16, int64_t ldx, int rule, bool a_mbs, hipStream_t s);
+// The few-row kernel for operands in the 8-bit or 6-bit element formats (a_elem, b_elem: mx_elem_t), under the same
+// conditions, defined in mx_gemm_skinny_f8.hip; an operand without MBS words has a null a_mbs / b_mbs.
+int launch_gemm_skinny_elem(const GemmArgs& g, int a_elem, int b_elem, hipStream_t s);
 
 namespace {
 

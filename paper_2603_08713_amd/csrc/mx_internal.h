@@ -34,10 +34,12 @@ int mx_internal_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint
 // fast form's alignment (host only, nothing is launched): a NUL-terminated description into out[cap].
 int mx_internal_gemm_plan(int64_t M, int64_t N, int64_t K, int a_has_mbs, int b_has_mbs, int grouped, char* out, int cap);
 
-// mx_gemm_mbs_elem with the general form of the kernel forced also where the fast form applies.
+// mx_gemm_mbs_elem with the kernel chosen by the caller.  force: 0 = as mx_gemm_mbs_elem, 1 = the main kernel's
+// general form also where the fast form applies, 2 = the main kernel also where the few-row kernel applies, 3 = the
+// few-row kernel (MX_EINVAL where it does not apply).
 int mx_internal_gemm_elem(mx_elem_t a_elem, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* a_mbs_or_null,
                           mx_elem_t b_elem, const uint8_t* b_codes, const uint8_t* b_scales, const uint8_t* b_mbs_or_null,
-                          int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, int force_general,
+                          int64_t M, int64_t N, int64_t K, mx_dtype_t c_dtype, void* C, int64_t ldc, int force,
                           void* stream);
 
 #ifdef __cplusplus

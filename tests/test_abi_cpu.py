@@ -226,6 +226,14 @@ def test_elem_argument_errors(lib):
     assert g(E4, A16, A16, None, E5, A16, A16 + 2, None, 8, 8, 128, 0, A16, 8, None) == -4  # scale rows not dword-aligned
     assert g(E4, A16, A16, None, E23, A16, A16, None, 8, 8, 128, 0, A16, 8, None) == -4  # 6-bit formats
     assert g(E4, A16, A16, None, E5, A16, A16, None, 0, 8, 128, 0, A16, 8, None) == 0
+    gg = lib.mx_gemm_mbs_elem_grouped
+    assert gg(E4, A16, A16, None, E5, A16, A16, None, -1, A16, 8, 8, 128, 0, A16, 8, None) == -1   # negative group count
+    assert gg(E4, A16, A16, None, E5, A16, A16, None, 2, None, 8, 8, 128, 0, A16, 8, None) == -2   # no offsets
+    assert gg(E4, A16, A16, None, E5, A16, A16, None, 2, A16, 8, 8, 48, 0, A16, 8, None) == -1     # K % 32
+    assert gg(E4, A16, A16, None, E5, A16, A16, None, 2, A16, 8, 8, 64, 0, A16, 8, None) == -4     # K % 128
+    assert gg(E4, A16, A16, None, E23, A16, A16, None, 2, A16, 8, 8, 128, 0, A16, 8, None) == -4   # 8-bit with 6-bit
+    assert gg(E23, A16, A16, None, E23, A16, A16, None, 0, None, 8, 8, 128, 0, A16, 8, None) == 0  # no groups: nothing to do
+    assert gg(E4, A16, A16, None, E5, A16, A16, None, 2, A16, 0, 8, 128, 0, A16, 8, None) == 0
 
 
 def test_fp8_dequantizer_shortcut_is_exact():

@@ -219,9 +219,14 @@ def random_operand(rng, elem, rows, K, lo=110, hi=140):
     return (c, rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8), rng.integers(0, 256, (rows, K // 128), dtype=np.uint8))
 
 
-def gpu_gemm(mx, ea, a, eb, b, out_dtype="f32", out=None):
+def gpu_gemm(mx, ea, a, eb, b, out_dtype="f32", out=None, kernel=2):
+    """kernel: 2 = the main kernel in the form the problem allows (what most tests here are about), 1 = its general
+    form, 3 = the few-row kernel, None = whatever the library picks."""
     da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
-    return mx.mx_gemm_mbs_elem(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], out_dtype, out=out)
+    if kernel is None:
+        return mx.mx_gemm_mbs_elem(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], out_dtype, out=out)
+    with mx.forced(gemm_elem=kernel):
+        return mx.mx_gemm_mbs_elem(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], out_dtype, out=out)
 
 
 def assert_gemm_close(got, want, what=""):
@@ -269,11 +274,11 @@ def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
 def test_gemm_elem_six_bit_random_codes_and_scales(mx, oracle, ea, eb):
     """MXFP6 operands (packed 6-bit codes; every code is a finite value): every code, scale byte and lane position;
     tiles with ragged tails; K of 1 to 4 groups of four stages, one turn of the loop, and a turn plus one and two
-    groups.  E2M3 products span 12 binades and add up without loss, like FP4's; with E3M2 (18 binades) the bound
+    groups; K % 512 != 0 takes the general form (1, 3, 5, 7 and 13 stages).  E2M3 products span 12 binades and add up without loss, like FP4's; with E3M2 (18 binades) the bound
     of the 8-bit formats applies."""
     rng = np.random.default_rng(46)
     for (M, N, K) in ((16, 16, 512), (257, 130, 1536), (100, 129, 2048), (300, 260, 1024), (70, 140, 6144), (33, 260, 6656),
-                      (260, 33, 7168)):
+                      (260, 33, 7168), (16, 16, 128), (130, 200, 384), (300, 260, 640), (520, 390, 896), (257, 129, 1664)):
         a = (rng.integers(0, 64, (M, K), dtype=np.uint8), rng.integers(110, 140, (M, K // 32), dtype=np.uint8),
              rng.integers(0, 256, (M, K // 128), dtype=np.uint8))
         b = (rng.integers(0, 64, (N, K), dtype=np.uint8), rng.integers(110, 140, (N, K // 32), dtype=np.uint8),
@@ -288,12 +293,8 @@ def test_gemm_elem_six_bit_random_codes_and_scales(mx, oracle, ea, eb):
                 absc = oracle.elem_gemm(ea, (a1[0] & 0x1F, a1[1], a1[2]), eb, (b1[0] & 0x1F, b1[1], b1[2]))
                 ratio = float(np.nanmax(np.abs(got.astype(np.float64) - want) / absc))
                 assert ratio <= ABS_TOL, "%s %s x %s %dx%dx%d: %.3e" % (name, ea, eb, M, N, K, ratio)
-    with pytest.raises(mx.MxError) as e:  # 6-bit with 8-bit operands, and K outside the fast form
+    with pytest.raises(mx.MxError) as e:  # 6-bit with 8-bit operands
         gpu_gemm(mx, "e2m3", (canonical_codes("e2m3", a[0]), a[1], a[2]), "e4m3", b)
-    assert e.value.status == -4
-    with pytest.raises(mx.MxError) as e:
-        gpu_gemm(mx, "e2m3", (canonical_codes("e2m3", a[0][:, :640]), a[1][:, :20], a[2][:, :5]), "e2m3",
-                 (canonical_codes("e2m3", b[0][:, :640]), b[1][:, :20], b[2][:, :5]))
     assert e.value.status == -4
 
 
@@ -333,13 +334,15 @@ def test_gemm_elem_general_form_equals_fast_form(mx, oracle):
     rng = np.random.default_rng(45)
     for (M, N, K) in ((300, 200, 512), (257, 390, 2048), (64, 128, 6656)):
         a, b = random_operand(rng, "e4m3", M, K, 118, 136), random_operand(rng, "e5m2", N, K, 118, 132)
+        a6 = (canonical_codes("e3m2", a[0] & 0x3F), a[1], a[2])
+        b6 = (canonical_codes("e2m3", b[0] & 0x3F), b[1], b[2])
         for words in (True, False):
-            a1 = a if words else (a[0], a[1], None)
-            b1 = b if words else (b[0], b[1], None)
-            fast = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
-            with mx.forced(gemm_elem_general=1):
-                general = gpu_gemm(mx, "e4m3", a1, "e5m2", b1)
-            assert torch.equal(fast, general), (M, N, K, words)
+            for ea, a1, eb, b1 in (("e4m3", a, "e5m2", b), ("e3m2", a6, "e2m3", b6)):
+                a1 = a1 if words else (a1[0], a1[1], None)
+                b1 = b1 if words else (b1[0], b1[1], None)
+                fast = gpu_gemm(mx, ea, a1, eb, b1)
+                general = gpu_gemm(mx, ea, a1, eb, b1, kernel=1)
+                assert torch.equal(fast, general), (ea, M, N, K, words)
 
 
 def test_gemm_elem_general_form_at_full_size_repeats_bit_for_bit(mx):
@@ -355,9 +358,123 @@ def test_gemm_elem_general_form_at_full_size_repeats_bit_for_bit(mx):
     for words in (True, False):
         args = ("e4m3", a[0], a[1], a[2] if words else None, "e4m3", b[0], b[1], b[2] if words else None, "bf16")
         fast = mx.mx_gemm_mbs_elem(*args)
-        with mx.forced(gemm_elem_general=1):
+        with mx.forced(gemm_elem=1):
             for rep in range(5):
                 assert torch.equal(mx.mx_gemm_mbs_elem(*args), fast), (words, rep)
+
+
+ALL_PAIRS = [("e4m3", "e4m3"), ("e4m3", "e5m2"), ("e5m2", "e4m3"), ("e5m2", "e5m2"),
+             ("e2m3", "e2m3"), ("e2m3", "e3m2"), ("e3m2", "e2m3"), ("e3m2", "e3m2")]
+
+
+def random_operand_any(rng, elem, rows, K, lo=110, hi=140):
+    """random_operand for any of the four formats: (codes one per byte for the oracle, codes as the library takes them)."""
+    if elem in ELEMS:
+        op = random_operand(rng, elem, rows, K, lo, hi)
+        return op, op
+    op = (rng.integers(0, 64, (rows, K), dtype=np.uint8), rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8),
+          rng.integers(0, 256, (rows, K // 128), dtype=np.uint8))
+    return op, (canonical_codes(elem, op[0]), op[1], op[2])
+
+
+def assert_gemm_elem_ok(oracle, got, ea, a, eb, b, what, rows=None):
+    """Bound (1) of the accumulation contract where it applies to random codes (E2M3 x E2M3), else bound (2)."""
+    want = oracle.elem_gemm(ea, a, eb, b, rows=rows)
+    if ea == "e2m3" and eb == "e2m3":
+        return assert_gemm_close(got, want, what)
+    keep = 0x7F if ea in ELEMS else 0x1F
+    absc = oracle.elem_gemm(ea, (a[0] & keep, a[1], a[2]), eb, (b[0] & keep, b[1], b[2]), rows=rows)
+    ratio = float(np.nanmax(np.abs(got.astype(np.float64) - want) / absc))
+    assert ratio <= ABS_TOL, "%s: max |err| / sum|a||b| = %.3e" % (what, ratio)
+
+
+@pytest.mark.parametrize("ea,eb", ALL_PAIRS)
+def test_gemm_elem_few_rows(mx, oracle, ea, eb):
+    """The few-row kernel (weights streamed once, K split over the wavefronts of a workgroup): every row count's
+    fragment arrangement, ragged N, K of one group of four macro blocks up to the largest, every code, scale byte
+    and lane position of the 16x16x128 instruction's operand layout; with and without MBS words on either side."""
+    rng = np.random.default_rng(50)
+    hi = 132 if "e5m2" in (ea, eb) else 140
+    for (M, N, K) in ((1, 16, 512), (16, 100, 1024), (7, 8200, 512), (17, 130, 4096), (32, 48, 1536), (33, 70, 2560), (64, 40, 8192)):
+        (a, pa), (b, pb) = random_operand_any(rng, ea, M, K, 110, hi), random_operand_any(rng, eb, N, K, 110, hi)
+        for wa, wb in ((True, True), (False, True), (True, False), (False, False)):
+            a1, b1 = (a[0], a[1], a[2] if wa else None), (b[0], b[1], b[2] if wb else None)
+            pa1, pb1 = (pa[0], pa[1], pa[2] if wa else None), (pb[0], pb[1], pb[2] if wb else None)
+            got = gpu_gemm(mx, ea, pa1, eb, pb1, kernel=3)
+            assert_gemm_elem_ok(oracle, host(got), ea, a1, eb, b1, "few rows %s x %s %dx%dx%d words %d%d" % (ea, eb, M, N, K, wa, wb))
+            if (wa, wb) == (True, True):
+                # what the library picks for this shape is this kernel, and bf16 is the rounding of its fp32
+                assert torch.equal(gpu_gemm(mx, ea, pa1, eb, pb1, kernel=None), got)
+                assert torch.equal(gpu_gemm(mx, ea, pa1, eb, pb1, "bf16", kernel=None), got.to(torch.bfloat16))
+    # a strided C with an odd column offset
+    big = torch.zeros((M, N + 5), dtype=torch.float32, device="cuda")
+    gpu_gemm(mx, ea, pa1, eb, pb1, out=big[:, 3:N + 3], kernel=3)
+    assert torch.equal(big[:, 3:N + 3], got) and float(big[:, :3].abs().max()) == 0.0 and float(big[:, N + 3:].abs().max()) == 0.0
+    # outside the kernel's range the request for it is refused, and the library takes the main kernel
+    (a, pa), (b, pb) = random_operand_any(rng, ea, 65, 512, 120, 130), random_operand_any(rng, eb, 32, 512, 120, 130)
+    with pytest.raises(mx.MxError) as e:
+        gpu_gemm(mx, ea, pa, eb, pb, kernel=3)
+    assert e.value.status == -1
+    assert torch.equal(gpu_gemm(mx, ea, pa, eb, pb, kernel=None), gpu_gemm(mx, ea, pa, eb, pb, kernel=2))
+
+
+def test_gemm_elem_few_rows_quantized_decode_shape(mx, oracle):
+    """Decode shape (16 activation rows against a 4096 x 4096 weight), operands quantized on the GPU with OAS and
+    MBS-Static in E4M3 and in E2M3: the whole output against the oracle at the 1e-3 RMS bar, and against the main
+    kernel's."""
+    from paper_2603_08713_amd import synth
+
+    M, N, K = 16, 4096, 4096
+    a_bits = synth.activations_student_t(M, K, 4.0, 0.01, 20.0, 3)
+    w_bits = synth.gaussian(N, K, 0.02, 2)
+    xa, xw = dev_bf16(a_bits), dev_bf16(w_bits)
+    for elem in ("e4m3", "e2m3"):
+        a, b = mx.mx_quantize_elem(xa, elem, "oas"), mx.mx_quantize_elem(xw, elem, "oas")
+        c = mx.mx_gemm_mbs_elem(elem, *a, elem, *b, "f32")
+        with mx.forced(gemm_elem=2):
+            c_main = mx.mx_gemm_mbs_elem(elem, *a, elem, *b, "f32")
+        oa, ob = oracle.elem_quantize(elem, a_bits, "oas", mbs=True), oracle.elem_quantize(elem, w_bits, "oas", mbs=True)
+        want = oracle.elem_gemm(elem, oa, elem, ob)
+        assert_gemm_close(host(c), want, "decode %s" % elem)
+        assert_gemm_close(host(c_main), want, "decode %s, main kernel" % elem)
+
+
+@pytest.mark.parametrize("ea,eb", [("e4m3", "e5m2"), ("e5m2", "e4m3"), ("e2m3", "e3m2"), ("e3m2", "e2m3")])
+def test_gemm_elem_grouped(mx, oracle, ea, eb):
+    """Grouped form: groups of 0, 1, a few, exactly one tile-row and several tile-rows of rows, each against its own
+    weight; rows past the last group stay untouched; the same through mx_gemm_mbs_elem group by group."""
+    rng = np.random.default_rng(51)
+    hi = 132 if "e5m2" in (ea, eb) else 140
+    N, K = 200, 640
+    sizes = [0, 1, 37, 256, 0, 300, 5, 513]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total, G = int(offs[-1]) + 9, len(sizes)
+    (a, pa), (b, pb) = random_operand_any(rng, ea, total, K, 112, hi), random_operand_any(rng, eb, G * N, K, 112, hi)
+    for wa, wb in ((True, True), (False, False), (True, False)):
+        pa1, pb1 = (pa[0], pa[1], pa[2] if wa else None), (pb[0], pb[1], pb[2] if wb else None)
+        da, db = [dev_u8(t) for t in pa1], [dev_u8(t) for t in pb1]
+        out = torch.full((total, N), -7.0, dtype=torch.float32, device="cuda")
+        mx.mx_gemm_mbs_elem_grouped(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], torch.from_numpy(offs).cuda(), N, "f32", out=out)
+        got = host(out)
+        assert np.all(got[offs[-1]:] == -7.0)
+        for e in range(G):
+            lo, hi_ = int(offs[e]), int(offs[e + 1])
+            if lo == hi_:
+                continue
+            a_e = tuple(None if t is None else t[lo:hi_] for t in (a[0], a[1], a[2] if wa else None))
+            b_e = tuple(None if t is None else t[e * N:(e + 1) * N] for t in (b[0], b[1], b[2] if wb else None))
+            assert_gemm_elem_ok(oracle, got[lo:hi_], ea, a_e, eb, b_e, "group %d (%d rows) words %d%d" % (e, hi_ - lo, wa, wb))
+            # the ungrouped entry point's general form runs the same instructions in the same order
+            pa_e = tuple(None if t is None else t[lo:hi_] for t in pa1)
+            pb_e = tuple(None if t is None else t[e * N:(e + 1) * N] for t in pb1)
+            assert np.array_equal(host(gpu_gemm(mx, ea, pa_e, eb, pb_e, kernel=1)), got[lo:hi_]), e
+    out16 = torch.zeros((total, N), dtype=torch.bfloat16, device="cuda")
+    mx.mx_gemm_mbs_elem_grouped(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], torch.from_numpy(offs).cuda(), N, "bf16", out=out16)
+    assert torch.equal(out16[:offs[-1]], out[:offs[-1]].to(torch.bfloat16))
+    # no groups: nothing is written
+    out.fill_(-7.0)
+    mx.mx_gemm_mbs_elem_grouped(ea, da[0], da[1], da[2], eb, db[0][:0], db[1][:0], None, torch.zeros(1, dtype=torch.int64, device="cuda"), N, "f32", out=out)
+    assert float((out + 7.0).abs().max()) == 0.0
 
 
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
