@@ -92,6 +92,12 @@ def lib() -> ctypes.CDLL:
         L.mxo_elem_mbs_static_m8.argtypes = [ci, dbl]
         L.mxo_elem_quantize.restype = ci
         L.mxo_elem_quantize.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
+        L.mxo_elem_quantize_given_mbs.restype = ci
+        L.mxo_elem_quantize_given_mbs.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        L.mxo_elem_mbs_sse_rows.restype = ci
+        L.mxo_elem_mbs_sse_rows.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, vp, vp]
+        L.mxo_elem_quantize_mbs_dynamic.restype = ci
+        L.mxo_elem_quantize_mbs_dynamic.argtypes = [ci, vp, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.mxo_elem_dequantize.restype = ci
         L.mxo_elem_dequantize.argtypes = [ci, vp, vp, vp, i64, i64, ci, ci, vp]
         L.mxo_elem_gemm_rows.restype = ci
@@ -350,6 +356,50 @@ def elem_quantize(fmt, x_bf16: np.ndarray, rule="oas", mbs: bool = False, block:
                                  _ptr(codes), _ptr(scales), _ptr(words))
     if rc != 0:
         raise ValueError("mxo_elem_quantize: bad arguments")
+    return codes, scales, words
+
+
+def elem_quantize_given_mbs(fmt, x_bf16: np.ndarray, words: np.ndarray, rule="oas", block: int = 32, macro: int = 128):
+    """Quantize into element format fmt with caller-chosen MBS words. Returns (codes one per byte, scales, words)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    words = np.ascontiguousarray(words, np.uint8)
+    assert words.shape == (rows, (K + macro - 1) // macro)
+    codes = np.zeros((rows, K), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    rc = lib().mxo_elem_quantize_given_mbs(_elem(fmt), _ptr(x), rows, K, K, _rule(rule), block, macro, _ptr(words),
+                                           _ptr(codes), _ptr(scales))
+    if rc != 0:
+        raise ValueError("mxo_elem_quantize_given_mbs: bad arguments")
+    return codes, scales, words
+
+
+def elem_mbs_sse_rows(fmt, x_bf16: np.ndarray, words: np.ndarray, rule="oas", block: int = 32, macro: int = 128) -> np.ndarray:
+    """Exact sum of squared errors (fp64) of every macro block of x in element format fmt under the given words
+    [rows, ceil(K/macro)]; -1 where a macro block holds a non-finite element (Eq. 6 with the true error)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    words = np.ascontiguousarray(words, np.uint8)
+    assert words.shape == (rows, (K + macro - 1) // macro)
+    out = np.empty(words.shape, np.float64)
+    rc = lib().mxo_elem_mbs_sse_rows(_elem(fmt), _ptr(x), rows, K, K, _rule(rule), block, macro, _ptr(words), _ptr(out))
+    if rc != 0:
+        raise ValueError("mxo_elem_mbs_sse_rows: bad arguments")
+    return out
+
+
+def elem_quantize_mbs_dynamic(fmt, x_bf16: np.ndarray, rule="oas", cand_first: int = 0, cand_count: int = 16,
+                              cand_stride: int = 16, block: int = 32, macro: int = 128):
+    """MBS-Dynamic into element format fmt (Sec. 4.3.3 with the true error). Returns (codes, scales, words)."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    rows, K = x.shape
+    codes = np.zeros((rows, K), np.uint8)
+    scales = np.zeros((rows, K // block), np.uint8)
+    words = np.zeros((rows, (K + macro - 1) // macro), np.uint8)
+    rc = lib().mxo_elem_quantize_mbs_dynamic(_elem(fmt), _ptr(x), rows, K, K, _rule(rule), block, macro, cand_first,
+                                             cand_count, cand_stride, _ptr(codes), _ptr(scales), _ptr(words))
+    if rc != 0:
+        raise ValueError("mxo_elem_quantize_mbs_dynamic: bad arguments")
     return codes, scales, words
 
 

@@ -613,14 +613,42 @@ int mxo_elem_mbs_static_m8(int fmt, double alpha) {
     return (int)(uint64_t)(num / n) - 256;
 }
 
+/* One macro block xr[k0..k1) of a row under word m8 into element format fmt: scale bytes into
+ * scales_row[k / block], codes (one per byte) into codes_row[k]. */
+static void elem_quantize_macro_block(int fmt, const uint16_t* xr, int64_t k0, int64_t k1, int m8, int rule,
+                                      int block, uint8_t* codes_row, uint8_t* scales_row) {
+    const elem_format* f = &ELEM[fmt];
+    const int sign_bit = 1 << (f->ebits + f->mbits);
+    const double F = 1.0 + m8 / 256.0;
+    for (int64_t b0 = k0; b0 < k1; b0 += block) {
+        int finite = 1;
+        double amax = 0.0;
+        for (int64_t k = b0; k < b0 + block; ++k) {
+            if (!is_finite_bf16(xr[k])) finite = 0;
+            else amax = fmax(amax, fabs(mxo_bf16_value(xr[k]) * F));
+        }
+        int E, s;
+        if (!finite) { E = 255; s = 0; }
+        else if (amax == 0.0) { E = 127; s = 0; }
+        else { E = mxo_e8m0_from_exponent(mxo_elem_scale_exponent(fmt, amax, rule)); s = 127 - E; }
+        scales_row[b0 / block] = (uint8_t)E;
+        for (int64_t k = b0; k < b0 + block; ++k) {
+            int code = 0;
+            if (finite) {
+                const double t = ldexp(mxo_bf16_value(xr[k]) * F, s); /* exact */
+                code = mxo_elem_nearest(fmt, fabs(t)) | ((xr[k] & 0x8000u) ? sign_bit : 0);
+            }
+            codes_row[k] = (uint8_t)code;
+        }
+    }
+}
+
 /* Quantize rows of bf16 into element format fmt: as mxo_quantize, with codes [rows, K] one per byte. */
 int mxo_elem_quantize(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
                       int use_mbs, int block, int macro, uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
     if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || ldx < K || block <= 0 || macro % block || K % block)
         return -1;
     if (rule < 0 || rule > 2) return -1;
-    const elem_format* f = &ELEM[fmt];
-    const int sign_bit = 1 << (f->ebits + f->mbits);
     const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
@@ -632,28 +660,97 @@ int mxo_elem_quantize(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64
                 m8 = mxo_elem_mbs_static_m8(fmt, macro_absmax(xr, k0, k1));
                 mbs[r * nmac + g] = (uint8_t)m8;
             }
-            const double F = 1.0 + m8 / 256.0;
-            for (int64_t b0 = k0; b0 < k1; b0 += block) {
-                int finite = 1;
-                double amax = 0.0;
-                for (int64_t k = b0; k < b0 + block; ++k) {
-                    if (!is_finite_bf16(xr[k])) finite = 0;
-                    else amax = fmax(amax, fabs(mxo_bf16_value(xr[k]) * F));
-                }
-                int E, s;
-                if (!finite) { E = 255; s = 0; }
-                else if (amax == 0.0) { E = 127; s = 0; }
-                else { E = mxo_e8m0_from_exponent(mxo_elem_scale_exponent(fmt, amax, rule)); s = 127 - E; }
-                scales[r * nblk + b0 / block] = (uint8_t)E;
-                for (int64_t k = b0; k < b0 + block; ++k) {
-                    int code = 0;
-                    if (finite) {
-                        const double t = ldexp(mxo_bf16_value(xr[k]) * F, s); /* exact */
-                        code = mxo_elem_nearest(fmt, fabs(t)) | ((xr[k] & 0x8000u) ? sign_bit : 0);
-                    }
-                    codes[r * K + k] = (uint8_t)code;
+            elem_quantize_macro_block(fmt, xr, k0, k1, m8, rule, block, codes + r * K, scales + r * nblk);
+        }
+    }
+    return 0;
+}
+
+/* The same with caller-chosen words mbs_in [rows, ceil(K/macro)] (what a test needs to judge any choice of
+ * words, and what MBS-Dynamic ends with). */
+int mxo_elem_quantize_given_mbs(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
+                                int block, int macro, const uint8_t* mbs_in, uint8_t* codes, uint8_t* scales) {
+    if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || ldx < K || block <= 0 || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            elem_quantize_macro_block(fmt, x + r * ldx, k0, k1, mbs_in[r * nmac + g], rule, block, codes + r * K,
+                                      scales + r * nblk);
+        }
+    return 0;
+}
+
+/* MBS-Dynamic for the element formats (Sec. 4.3.3, Eq. 6 with the true error; Sec. 1, footnote).  The
+ * definition does not depend on the element format: among the static word and the candidates
+ * m_j = (m_static + (cand_first + j) * cand_stride) mod 256 the word with the least sum of squared
+ * errors of the 1x128 block wins, ties to the static word, then to the lowest j (see mxo_mbs_sse and
+ * mxo_quantize_mbs_dynamic above, which these two restate with the format's rules and grid). */
+double mxo_elem_mbs_sse(int fmt, const uint16_t* xm, int n, int m8, int rule, int block) {
+    const double F = 1.0 + m8 / 256.0;
+    double sse = 0.0;
+    for (int b0 = 0; b0 < n; b0 += block) {
+        double amax = 0.0;
+        for (int k = b0; k < b0 + block; ++k) {
+            if (!is_finite_bf16(xm[k])) return -1.0;
+            amax = fmax(amax, fabs(mxo_bf16_value(xm[k]) * F));
+        }
+        int s = 0;
+        if (amax > 0.0) s = 127 - mxo_e8m0_from_exponent(mxo_elem_scale_exponent(fmt, amax, rule));
+        for (int k = b0; k < b0 + block; ++k) {
+            const double x = mxo_bf16_value(xm[k]);
+            const double t = ldexp(x * F, s); /* exact */
+            double q = elem_magnitude(&ELEM[fmt], mxo_elem_nearest(fmt, fabs(t)));
+            if (xm[k] & 0x8000u) q = -q;
+            const double x_hat = ldexp(q, -s) / F;
+            sse += (x_hat - x) * (x_hat - x);
+        }
+    }
+    return sse;
+}
+
+int mxo_elem_mbs_sse_rows(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule, int block,
+                          int macro, const uint8_t* mbs_in, double* sse_out) {
+    if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || ldx < K || block <= 0 || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2) return -1;
+    const int64_t nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            sse_out[r * nmac + g] = mxo_elem_mbs_sse(fmt, x + r * ldx + k0, (int)(k1 - k0), mbs_in[r * nmac + g], rule, block);
+        }
+    return 0;
+}
+
+int mxo_elem_quantize_mbs_dynamic(int fmt, const uint16_t* x, int64_t rows, int64_t K, int64_t ldx, int rule,
+                                  int block, int macro, int cand_first, int cand_count, int cand_stride,
+                                  uint8_t* codes, uint8_t* scales, uint8_t* mbs) {
+    if (fmt < 0 || fmt > 4 || rows < 0 || K < 0 || ldx < K || block <= 0 || macro % block || K % block)
+        return -1;
+    if (rule < 0 || rule > 2 || cand_count < 0 || cand_count > 256) return -1;
+    const int64_t nblk = K / block, nmac = (K + macro - 1) / macro;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * ldx;
+        for (int64_t g = 0; g < nmac; ++g) {
+            const int64_t k0 = g * macro, k1 = (k0 + macro < K) ? k0 + macro : K;
+            const int m_static = mxo_elem_mbs_static_m8(fmt, macro_absmax(xr, k0, k1));
+            int best = m_static;
+            double best_sse = mxo_elem_mbs_sse(fmt, xr + k0, (int)(k1 - k0), m_static, rule, block);
+            if (best_sse >= 0.0) {
+                for (int j = 0; j < cand_count; ++j) {
+                    const int m = (int)(((int64_t)m_static + (int64_t)(cand_first + j) * cand_stride) & 255);
+                    const double c = mxo_elem_mbs_sse(fmt, xr + k0, (int)(k1 - k0), m, rule, block);
+                    if (c < best_sse) { best_sse = c; best = m; }
                 }
             }
+            mbs[r * nmac + g] = (uint8_t)best;
+            elem_quantize_macro_block(fmt, xr, k0, k1, best, rule, block, codes + r * K, scales + r * nblk);
         }
     }
     return 0;

@@ -300,3 +300,99 @@ def test_elem_qsnr_directions(oracle):
     assert base["e5m2"] < base["e4m3"] and base["e2m1"] < base["e5m2"]
     for f in base:
         assert best[f] > base[f], (f, base[f], best[f])
+
+
+# ------------------------------------------------------------------------------------------------
+# MBS-Dynamic on the element formats (Sec. 4.3.3 with the true error; the candidate list is a parameter)
+# ------------------------------------------------------------------------------------------------
+def exact_sse(fmt, xs, m8, rule):
+    """Sum of squared errors of one macro block (a list of bf16 patterns) under word m8, in exact rationals, with the
+    block scale and the rounding worked out here from the specification's grid."""
+    _, mb, _, V, _ = SPEC[fmt]
+    vals = grid(fmt)
+    h = half_step_top(fmt)
+    top = max(Fraction(2) ** e for e in range(-20, 20) if Fraction(2) ** e <= V)
+    F = 1 + Fraction(m8, 256)
+    total = Fraction(0)
+    for b in range(0, len(xs), 32):
+        blk = [bf16_frac(int(v)) for v in xs[b:b + 32]]
+        amax = max(abs(v) for v in blk) * F
+        s = 0
+        if amax > 0:
+            # the power of two that takes amax into the rule's interval
+            lo, hi, closed_low = {"floor": (V / 2, V, False), "oas": ((V + h) / 2, V + h, False), "ocp": (top, 2 * top, True)}[rule]
+            while amax * Fraction(2) ** s > hi or (closed_low and amax * Fraction(2) ** s >= hi):
+                s -= 1
+            while amax * Fraction(2) ** s < lo or (not closed_low and amax * Fraction(2) ** s <= lo):
+                s += 1
+        for v in blk:
+            q = vals[nearest_code(vals, abs(v) * F * Fraction(2) ** s)]
+            x_hat = (q if v >= 0 else -q) / (F * Fraction(2) ** s)
+            total += (x_hat - v) ** 2
+    return total
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_elem_mbs_sse_against_exact_rationals(oracle, fmt):
+    rng = np.random.default_rng(60 + FORMATS.index(fmt))
+    x = synth.to_bf16_bits(rng.standard_t(3, (3, 192)) * np.exp2(rng.integers(-10, 10, (3, 1))))  # a half macro block too
+    for rule in ("ocp", "floor", "oas"):
+        words = rng.integers(0, 256, (3, 2), dtype=np.uint8)
+        got = oracle.elem_mbs_sse_rows(fmt, x, words, rule)
+        for r in range(3):
+            for g in range(2):
+                want = exact_sse(fmt, x[r, 128 * g:128 * g + 128], int(words[r, g]), rule)
+                assert abs(Fraction(got[r, g]) - want) <= want * Fraction(1, 10 ** 12), (fmt, rule, r, g)
+    # and it is the error of what the quantizer and the dequantizer give for those words
+    words = rng.integers(0, 256, (3, 2), dtype=np.uint8)
+    c, s, _ = oracle.elem_quantize_given_mbs(fmt, x, words, "oas")
+    err = oracle.elem_dequantize(fmt, c, s, words) - oracle.bf16_to_f64(x)
+    sse = np.stack([(err[:, :128] ** 2).sum(1), (err[:, 128:] ** 2).sum(1)], 1)
+    assert np.allclose(oracle.elem_mbs_sse_rows(fmt, x, words, "oas"), sse, rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_elem_mbs_dynamic_is_the_brute_force_argmin(oracle, fmt):
+    rng = np.random.default_rng(70 + FORMATS.index(fmt))
+    x = synth.to_bf16_bits(rng.standard_t(3, (8, 384)) * 0.05)
+    for rule, cands in (("oas", (0, 16, 16)), ("floor", (-3, 7, 5)), ("ocp", (0, 256, 1))):
+        c, s, w = oracle.elem_quantize_mbs_dynamic(fmt, x, rule, *cands)
+        static = oracle.elem_quantize(fmt, x, rule, mbs=True)[2]
+        steps = [0] + [(cands[0] + j) * cands[2] for j in range(cands[1])]
+        cand = np.stack([((static.astype(np.int64) + st) % 256).astype(np.uint8) for st in steps])
+        sse = np.stack([oracle.elem_mbs_sse_rows(fmt, x, cw, rule) for cw in cand])
+        first_min = sse.argmin(0)  # the first of equal minima: the static word, then the lowest j
+        assert np.array_equal(w, np.take_along_axis(cand, first_min[None], 0)[0])
+        oc, os_, _ = oracle.elem_quantize_given_mbs(fmt, x, w, rule)
+        assert np.array_equal(c, oc) and np.array_equal(s, os_)
+        assert (oracle.elem_mbs_sse_rows(fmt, x, w, rule) <= oracle.elem_mbs_sse_rows(fmt, x, static, rule)).all()
+    # no candidates: MBS-Static
+    c0, s0, w0 = oracle.elem_quantize_mbs_dynamic(fmt, x, "oas", 0, 0, 16)
+    cs, ss, ws = oracle.elem_quantize(fmt, x, "oas", mbs=True)
+    assert np.array_equal(c0, cs) and np.array_equal(s0, ss) and np.array_equal(w0, ws)
+    # a window with a non-finite element keeps the static word; E2M1 through this route is the MXFP4 function
+    y = x.copy()
+    y[0, 7] = 0x7F80
+    assert oracle.elem_quantize_mbs_dynamic(fmt, y, "oas")[2][0, 0] == oracle.elem_quantize(fmt, y, "oas", mbs=True)[2][0, 0]
+
+
+def test_elem_mbs_dynamic_e2m1_reproduces_the_mxfp4_search(oracle):
+    x = synth.gaussian(16, 512, 0.02, 9)
+    c4, s4, w4 = oracle.quantize_mbs_dynamic(x, "oas")
+    c, s, w = oracle.elem_quantize_mbs_dynamic("e2m1", x, "oas")
+    assert np.array_equal(w, w4) and np.array_equal(s, s4)
+    assert np.array_equal(c[:, 0::2] | (c[:, 1::2] << 4), c4)
+    assert np.array_equal(oracle.elem_mbs_sse_rows("e2m1", x, w, "oas"), oracle.mbs_sse_rows(x, w, "oas"))
+
+
+def test_elem_mbs_dynamic_qsnr_direction(oracle):
+    """The searched word lowers the error of Gaussian weights in every format (Sec. 4.3.3: direction only; the size of
+    the gain on these formats is this build's observation)."""
+    x = synth.gaussian(64, 1024, 0.02, 11)
+    ref = oracle.bf16_to_f64(x)
+    for fmt in FORMATS:
+        cs, ss, ws = oracle.elem_quantize(fmt, x, "oas", mbs=True)
+        cd, sd, wd = oracle.elem_quantize_mbs_dynamic(fmt, x, "oas")
+        qs = oracle.qsnr_db(ref, oracle.elem_dequantize(fmt, cs, ss, ws))
+        qd = oracle.qsnr_db(ref, oracle.elem_dequantize(fmt, cd, sd, wd))
+        assert qd > qs, (fmt, qs, qd)
