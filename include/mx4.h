@@ -195,6 +195,16 @@ typedef enum {
 int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                      int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
+/* mx_quantize_mbs_dynamic into an 8-bit or 6-bit element format (Sec. 4.3.3, Sec. 5.3; Sec. 1, footnote): as
+ * mx_quantize_elem with use_mbs != 0, but the word of each 1x128 window is searched for the least sum of squared
+ * errors of the window among the static word and  m_j = (m_static + (cand_first + j) * cand_stride) mod 256,
+ * j = 0 .. cand_count-1.  Candidate limits, evaluation order (fp32, fixed), tie rule (the static word, then the
+ * lowest j) and the windows that keep the static word (Inf/NaN inside, absmax below 2^-63 or at least 2^123) as for
+ * mx_quantize_mbs_dynamic; alignment as for mx_quantize_elem.  mx_gemm_mbs_elem consumes the outputs unchanged. */
+int mx_quantize_elem_mbs_dynamic(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                 int32_t cand_first, int32_t cand_count, int32_t cand_stride,
+                                 uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
 /* mx_dequantize for an 8-bit or 6-bit element format: out[r, k] = value(code) * 2^(E-127) / F, F = 1 without MBS
  * words (Sec. 4.3.1).  The fp32 result is the quotient evaluated in fp64 and rounded once more; the bf16 result is
  * that fp32 value rounded to nearest even; a block with E = 255 gives NaN.  Codes in the layout mx_quantize_elem

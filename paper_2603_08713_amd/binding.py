@@ -83,6 +83,9 @@ def load_library() -> ctypes.CDLL:
     L.mx_internal_gemm.argtypes = [vp, vp, vp, vp, vp, vp, ci, i32, vp, i64, i64, i64, ci, vp, i64, ci, ci, vp]
     L.mx_internal_gemm_plan.restype = ci
     L.mx_internal_gemm_plan.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.c_char_p, ci]
+    L.mx_quantize_elem_mbs_dynamic.restype = ci
+    L.mx_quantize_elem_mbs_dynamic.argtypes = [ci, vp, i64, i64, i64, ci, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                               vp, vp, vp, vp]
     L.mx_gemm_mbs_elem_grouped.restype = ci
     L.mx_gemm_mbs_elem_grouped.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, ctypes.c_int32, vp, i64, i64, i64, ci, vp, i64, vp]
     L.mx_internal_gemm_elem.restype = ci
@@ -379,6 +382,25 @@ def mx_quantize_elem(x, elem="e4m3", rule="oas", use_mbs=True, codes=None, scale
                                                         int(hw), _ptr(codes), _ptr(scales), _ptr(mbs) if use_mbs else None,
                                                         _stream()), "mx_quantize_elem (mx_internal_quantize_elem)")
     return codes, scales, (mbs if use_mbs else None)
+
+
+def mx_quantize_elem_mbs_dynamic(x, elem, rule="oas", cand_first=0, cand_count=16, cand_stride=16, codes=None, scales=None,
+                                 mbs=None):
+    """MBS-Dynamic into an 8-bit or 6-bit element format: the word of every 1x128 window searched among the static
+    word and cand_count candidates for the least squared error.  Returns (codes, scales, mbs)."""
+    torch = _torch()
+    rows, K, ldx = _rows_ld(x)
+    dev = x.device
+    codes = torch.empty((rows, elem_code_bytes(elem, K)), dtype=torch.uint8, device=dev) if codes is None else codes
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=dev) if scales is None else scales
+    mbs = torch.empty((rows, (K + 127) // 128), dtype=torch.uint8, device=dev) if mbs is None else mbs
+    _u8(codes, (rows, elem_code_bytes(elem, K)), "codes")
+    _u8(scales, (rows, K // 32), "scales")
+    _u8(mbs, (rows, (K + 127) // 128), "mbs")
+    _check(load_library().mx_quantize_elem_mbs_dynamic(_elem(elem), _ptr(x), rows, K, ldx, _rule(rule), int(cand_first),
+                                                       int(cand_count), int(cand_stride), _ptr(codes), _ptr(scales),
+                                                       _ptr(mbs), _stream()), "mx_quantize_elem_mbs_dynamic")
+    return codes, scales, mbs
 
 
 def mx_dequantize_elem(elem, codes, scales, mbs=None, out_dtype="f32", out=None):

@@ -143,8 +143,9 @@ __device__ __forceinline__ void put_code(uint32_t& lo, uint32_t& hi, int i, uint
     if (bit + T::kBits > 32) hi |= bit >= 32 ? code << (bit - 32) : code >> (32 - bit);
 }
 
+// (m8_given >= 0 replaces the static word: the searched word of MBS-Dynamic)
 template <typename T>
-__device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_mbs) {
+__device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_mbs, int m8_given = -1) {
     uint32_t h[8] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16,
                      v.z & 0xFFFFu, v.z >> 16, v.w & 0xFFFFu, v.w >> 16};
     uint32_t amax = 0, nf = 0;
@@ -160,7 +161,8 @@ __device__ __noinline__ Chunk8 quantize_chunk8_exact(u32x4 v, int rule, int use_
     uint32_t mmax = amax;
     mmax = max(mmax, dpp_row_ror4(mmax));
     mmax = max(mmax, dpp_row_ror8(mmax));
-    const uint32_t m8 = use_mbs ? mbs8_word_of_absmax<T>(mmax) : 0u;
+    uint32_t m8 = use_mbs ? mbs8_word_of_absmax<T>(mmax) : 0u;
+    if (m8_given >= 0) m8 = (uint32_t)m8_given;
     const uint32_t u = 256u + m8;
     const int E = nf ? 255 : amax == 0 ? 127 : exact_scale_byte8<T>(amax, u, rule);
     uint32_t lo = 0, hi = 0;
@@ -231,6 +233,58 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
     return {out[0], out[1], E, m8};
 }
 
+// A chunk's results to memory: the lane's codes, its block's scale byte, its macro block's word.  Every lane of the
+// wavefront takes part in the exchanges; only valid lanes (inside the row) store.
+template <int kElem, bool kMbs>
+__device__ __forceinline__ void store_chunk8(const Quant8Args& q, const Chunk8& res, uint32_t lane, uint32_t row, uint32_t col,
+                                             bool valid) {
+    // scales of the macro block gathered into one dword across the row of 16 lanes
+    uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
+    if ((lane & 3) != 0) ew = 0;
+    ew |= dpp_row_ror4(ew);
+    ew |= dpp_row_ror8(ew);
+    // 6-bit formats: the block's 4 x 48 bits gathered into six dwords (every lane fetches its three
+    // neighbours' bits; the block's first lanes store)
+    uint32_t six[6] = {0, 0, 0, 0, 0, 0};
+    if constexpr (Fp8<kElem>::kBits == 6) {
+        uint32_t lo[4], hi[4];
+        lo[0] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x00, 0xF, 0xF, true);  // quad_perm: [0,0,0,0]
+        hi[0] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x00, 0xF, 0xF, true);
+        lo[1] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x55, 0xF, 0xF, true);  // [1,1,1,1]
+        hi[1] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x55, 0xF, 0xF, true);
+        lo[2] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xAA, 0xF, 0xF, true);  // [2,2,2,2]
+        hi[2] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xAA, 0xF, 0xF, true);
+        lo[3] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xFF, 0xF, 0xF, true);  // [3,3,3,3]
+        hi[3] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xFF, 0xF, 0xF, true);
+        six[0] = lo[0];
+        six[1] = hi[0] | (lo[1] << 16);
+        six[2] = (lo[1] >> 16) | (hi[1] << 16);
+        six[3] = lo[2];
+        six[4] = hi[2] | (lo[3] << 16);
+        six[5] = (lo[3] >> 16) | (hi[3] << 16);
+    }
+    if (!valid) return;
+    const uint32_t kblk = col >> 5;
+    uint8_t* srow = q.scales + (int64_t)row * (q.K >> 5);
+    if constexpr (Fp8<kElem>::kBits == 6) {
+        // lanes 0, 1, 2 of the block store 8 bytes each: one instruction covers the block's 24 bytes
+        const uint32_t part = lane & 3;
+        if (part < 3) {
+            uint2* dst = reinterpret_cast<uint2*>(q.codes + (int64_t)row * (q.K / 4 * 3) + (int64_t)kblk * 24);
+            dst[part] = make_uint2(part == 0 ? six[0] : part == 1 ? six[2] : six[4],
+                                   part == 0 ? six[1] : part == 1 ? six[3] : six[5]);
+        }
+    } else {
+        *reinterpret_cast<uint2*>(q.codes + (int64_t)row * q.K + col) = make_uint2(res.lo, res.hi);
+    }
+    if (q.scales_dword) {
+        if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
+    } else if ((lane & 3) == 0) {
+        srow[kblk] = (uint8_t)res.E;
+    }
+    if (kMbs && (lane & 15) == 0) q.mbs[(int64_t)row * q.nmac + (col >> 7)] = (uint8_t)res.m8;
+}
+
 template <int kElem, bool kHwCvt, bool kMbs>
 __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
     const uint32_t lane = threadIdx.x & 63;
@@ -255,51 +309,139 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
         for (int u = 0; u < kUnroll8; ++u) {
             if (c0 + u >= q.total_chunks) break;  // wave-uniform
             const Chunk8 res = quantize_chunk8<kElem, kHwCvt, kMbs>(v[u], q);
-            uint32_t ew = res.E << (8 * ((lane >> 2) & 3));
-            if ((lane & 3) != 0) ew = 0;
-            ew |= dpp_row_ror4(ew);
-            ew |= dpp_row_ror8(ew);
-            // 6-bit formats: the block's 4 x 48 bits gathered into six dwords (every lane fetches its three
-            // neighbours' bits; the block's first lane stores)
-            uint32_t six[6] = {0, 0, 0, 0, 0, 0};
-            if constexpr (Fp8<kElem>::kBits == 6) {
-                uint32_t lo[4], hi[4];
-                lo[0] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x00, 0xF, 0xF, true);  // quad_perm: [0,0,0,0]
-                hi[0] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x00, 0xF, 0xF, true);
-                lo[1] = __builtin_amdgcn_update_dpp(0u, res.lo, 0x55, 0xF, 0xF, true);  // [1,1,1,1]
-                hi[1] = __builtin_amdgcn_update_dpp(0u, res.hi, 0x55, 0xF, 0xF, true);
-                lo[2] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xAA, 0xF, 0xF, true);  // [2,2,2,2]
-                hi[2] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xAA, 0xF, 0xF, true);
-                lo[3] = __builtin_amdgcn_update_dpp(0u, res.lo, 0xFF, 0xF, 0xF, true);  // [3,3,3,3]
-                hi[3] = __builtin_amdgcn_update_dpp(0u, res.hi, 0xFF, 0xF, 0xF, true);
-                six[0] = lo[0];
-                six[1] = hi[0] | (lo[1] << 16);
-                six[2] = (lo[1] >> 16) | (hi[1] << 16);
-                six[3] = lo[2];
-                six[4] = hi[2] | (lo[3] << 16);
-                six[5] = (lo[3] >> 16) | (hi[3] << 16);
-            }
-            if (!valid[u]) continue;
-            const uint32_t kblk = col[u] >> 5;
-            uint8_t* srow = q.scales + (int64_t)row[u] * (q.K >> 5);
-            if constexpr (Fp8<kElem>::kBits == 6) {
-                // lanes 0, 1, 2 of the block store 8 bytes each: one instruction covers the block's 24 bytes
-                const uint32_t part = lane & 3;
-                if (part < 3) {
-                    uint2* dst = reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * (q.K / 4 * 3) + (int64_t)kblk * 24);
-                    dst[part] = make_uint2(part == 0 ? six[0] : part == 1 ? six[2] : six[4],
-                                           part == 0 ? six[1] : part == 1 ? six[3] : six[5]);
-                }
-            } else {
-                *reinterpret_cast<uint2*>(q.codes + (int64_t)row[u] * q.K + col[u]) = make_uint2(res.lo, res.hi);
-            }
-            if (q.scales_dword) {
-                if ((lane & 15) == 0) *reinterpret_cast<uint32_t*>(srow + kblk) = ew;
-            } else if ((lane & 3) == 0) {
-                srow[kblk] = (uint8_t)res.E;
-            }
-            if (kMbs && (lane & 15) == 0) q.mbs[(int64_t)row[u] * q.nmac + (col[u] >> 7)] = (uint8_t)res.m8;
+            store_chunk8<kElem, kMbs>(q, res, lane, row[u], col[u], valid[u]);
         }
+    }
+}
+
+// ---- MBS-Dynamic (Sec. 4.3.3, Sec. 5.3) on these formats ----
+// As for MXFP4: per macro block the word is searched among
+//     m_j = (m_static + (cand_first + j) * cand_stride) mod 256,  j = 0 .. cand_count - 1,
+// for the least sum of squared errors of the 1x128 block, measured directly.  The scaled element t = x F 2^s is
+// exact in fp32, its grid value comes out of the rounding addition of code8_alu (the sum minus the added constant),
+// and their difference is exact.  The cost has a fixed order of operations so that the minimum is reproducible:
+// fused multiply-adds over the lane's 8 elements in order, pairwise sums over the 4 lanes of a block, an exact
+// rescale from the block's binade to the macro block's, pairwise sums over the 4 blocks, one correctly rounded
+// division by F^2.  The static word is the incumbent; a candidate replaces the current choice only with a strictly
+// smaller cost.  The search runs where fp32 holds every intermediate exactly (exponent field of the macro-block
+// absmax in [64, 249], no Inf/NaN in it); a block whose own absmax is zero or more than 30 binades below
+// contributes nothing.
+struct Dyn8Args {
+    Quant8Args q;
+    int cand_first, cand_count, cand_stride;
+};
+
+struct Cand8 {
+    uint32_t lo, hi, E;
+    float cost;
+};
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), kCtrl, 0xF, 0xF, true));
+}
+
+// Codes, scale byte and macro-block cost of word m.  xf: the lane's 8 elements; amax: bf16 magnitude bits of the
+// block's absmax; counts: the block contributes to the cost; e128: exponent field of the macro block's absmax.  The
+// cost is uniform over the 16 lanes of the macro block.
+template <typename T>
+__device__ __forceinline__ Cand8 eval_candidate8(const float (&xf)[8], uint32_t amax, bool counts, uint32_t e128, uint32_t m,
+                                                 uint32_t carry) {
+#pragma clang fp contract(off)
+    const float F = __uint_as_float(0x3F800000u | (m << 15));
+    const float scaled_max = __uint_as_float(amax << 16) * F;  // exact
+    uint32_t E = ((__float_as_uint(scaled_max) + carry) >> 23) - (uint32_t)T::kEmax;
+    E = amax ? E : 127u;
+    const float mult = __uint_as_float(((254u - E) << 23) | (m << 15));  // F * 2^(127 - E)
+    const float vmax = __uint_as_float(T::kMaxBits);
+    uint32_t lo = 0, hi = 0;
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float t = xf[i] * mult;  // exact
+        const uint32_t tb = __float_as_uint(t);
+        const float a = __uint_as_float(tb & 0x7FFFFFFFu);
+        const float y = fminf(a, vmax);
+        const uint32_t ey = max(__float_as_uint(y) >> 23, (uint32_t)(127 + 1 - T::kBias));
+        const float magic = __uint_as_float(((ey + 23u - T::kMbits) << 23) | 0x400000u);
+        const float w = y + magic;     // y to the spacing of its binade, nearest even
+        const uint32_t qbits = __float_as_uint(w) & ((1u << (T::kMbits + 2)) - 1u);
+        const uint32_t code = (((ey - 127u + T::kBias) << T::kMbits) + qbits - (1u << T::kMbits)) | ((tb >> 31) << (T::kBits - 1));
+        put_code<T>(lo, hi, i, code);
+        const float r = a - (w - magic);  // exact: the grid value is within a factor 2 of |t|, or |t| is tiny
+        acc = __builtin_fmaf(r, r, acc);
+    }
+    // block sum, then from units of the block's binade to units of the macro block's: 4^(E + emax - e128)
+    acc = counts ? acc : 0.0f;
+    acc = acc + dpp_f<0xB1>(acc);   // quad_perm [1,0,3,2]
+    acc = acc + dpp_f<0x4E>(acc);   // quad_perm [2,3,0,1]
+    const float rescale = __uint_as_float(counts ? (127u + 2u * (E + (uint32_t)T::kEmax - e128)) << 23 : 0x3F800000u);
+    acc = acc * rescale;
+    acc = acc + dpp_f<0x141>(acc);  // lane i <-> 7 - i inside each half row: the neighbouring block
+    acc = acc + dpp_f<0x140>(acc);  // lane i <-> 15 - i inside each row: the neighbouring pair of blocks
+    return {lo, hi, E, acc / (F * F)};
+}
+
+template <int kElem>
+__global__ __launch_bounds__(kThreads8) void quantize8_dynamic_kernel(Dyn8Args d) {
+    using T = Fp8<kElem>;
+    const Quant8Args& q = d.q;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * (kThreads8 / kWave) + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * (kThreads8 / kWave);
+    for (uint32_t c = wave; c < q.total_chunks; c += nwaves) {
+        const uint32_t row = c / q.chunks_per_row, col = (c - row * q.chunks_per_row) * kChunk8 + lane * 8;
+        const bool valid = col < q.K;
+        u32x4 v = {0, 0, 0, 0};
+        if (valid) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q.x + (int64_t)row * q.ldx + col));
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+
+        // absmax over the finite elements of the lane, block and macro block; Inf/NaN flag of the macro block
+        uint32_t amax = 0, nf = 0;
+        float xf[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+            if (lo >= 0x7F80u) nf = 1; else amax = max(amax, lo);
+            if (hi >= 0x7F80u) nf = 1; else amax = max(amax, hi);
+            xf[2 * i] = __uint_as_float(w[i] << 16);
+            xf[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+        nf |= dpp_quad_xor1(nf);
+        nf |= dpp_quad_xor2(nf);
+        const uint32_t nf_block = nf;
+        nf |= dpp_row_ror4(nf);
+        nf |= dpp_row_ror8(nf);
+        amax = max(amax, dpp_quad_xor1(amax));
+        amax = max(amax, dpp_quad_xor2(amax));
+        uint32_t mmax = max(amax, dpp_row_ror4(amax));
+        mmax = max(mmax, dpp_row_ror8(mmax));
+
+        const uint32_t m_static = mbs8_word_of_absmax<T>(mmax);
+        const uint32_t e128 = mmax >> 7;
+        const bool searchable = !nf && e128 >= 64u && e128 <= 249u;
+        const bool counts = amax != 0 && (amax >> 7) + 30u >= e128;
+
+        Cand8 best = eval_candidate8<T>(xf, amax, counts, e128, m_static, q.carry);
+        uint32_t m_best = m_static;
+        for (int j = 0; j < d.cand_count; ++j) {
+            const uint32_t step = (uint32_t)((d.cand_first + j) * d.cand_stride) & 255u;
+            if (step == 0) continue;  // the static word again: it cannot beat itself (uniform over the launch)
+            uint32_t m = (m_static + step) & 255u;
+            m = searchable ? m : m_static;
+            const Cand8 cand = eval_candidate8<T>(xf, amax, counts, e128, m, q.carry);
+            if (cand.cost < best.cost) {
+                best = cand;
+                m_best = m;
+            }
+        }
+
+        // the fp32 route gave valid codes unless some block of this wavefront lies outside its range (Inf/NaN, or an
+        // absmax exponent field outside [24, 249]); then the all-integer path redoes the chunk with the chosen word
+        const bool odd = nf_block || (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
+        Chunk8 res = {best.lo, best.hi, best.E, m_best};
+        if (__builtin_amdgcn_ballot_w64(odd) != 0) res = quantize_chunk8_exact<T>(v, q.rule, 1, (int)m_best);
+        store_chunk8<kElem, true>(q, res, lane, row, col, valid);
     }
 }
 
@@ -315,19 +457,21 @@ void launch8(const Quant8Args& q, int use_mbs, bool hwcvt, dim3 grid, hipStream_
     }
 }
 
-int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
-                         uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream, bool hwcvt = true) {
+// Argument checks and launch parameters shared by the entry points: MX_OK with *nothing = true when there is
+// nothing to do.
+int prepare_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                          uint8_t* codes, uint8_t* scales, uint8_t* mbs, Quant8Args& q, bool* nothing) {
+    *nothing = false;
     if (elem < MX_ELEM_E2M1 || elem > MX_ELEM_E3M2 || elem == MX_ELEM_E2M1) return MX_EINVAL;
     if (rows < 0 || K < 0 || (K % kBlock) != 0 || ldx < K) return MX_EINVAL;
     if (K > (int64_t)1 << 30) return MX_EINVAL;  // a lane's column inside its row is a 32-bit number
     if (rule != MX_RULE_OCP && rule != MX_RULE_FLOOR && rule != MX_RULE_OAS) return MX_EINVAL;
-    if (rows == 0 || K == 0) return MX_OK;
+    if (rows == 0 || K == 0) { *nothing = true; return MX_OK; }
     if (!x || !codes || !scales || (use_mbs && !mbs)) return MX_ENULL;
     if (!aligned(x, 16) || (ldx % 8) != 0 || !aligned(codes, 8)) return MX_EALIGN;
     const int64_t chunks_per_row = (K + kChunk8 - 1) / kChunk8, total = rows * chunks_per_row;
     if (total >= ((int64_t)1 << 32) - kUnroll8 || rows >= ((int64_t)1 << 31)) return MX_EINVAL;  // 32-bit chunk ids
     if (int st = check_device()) return st;
-    Quant8Args q;
     q.x = static_cast<const uint16_t*>(x);
     q.codes = codes; q.scales = scales; q.mbs = mbs;
     q.K = K; q.ldx = ldx; q.nmac = (K + kMacro - 1) / kMacro;
@@ -340,6 +484,16 @@ int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64
     const uint32_t carry_oas[5] = {0, Fp8<MX_ELEM_E4M3>::kCarryOas, Fp8<MX_ELEM_E5M2>::kCarryOas,
                                    Fp8<MX_ELEM_E2M3>::kCarryOas, Fp8<MX_ELEM_E3M2>::kCarryOas};
     q.carry = rule == MX_RULE_FLOOR ? carry_floor[elem] : rule == MX_RULE_OAS ? carry_oas[elem] : 0u;
+    return MX_OK;
+}
+
+int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int use_mbs,
+                         uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream, bool hwcvt = true) {
+    Quant8Args q;
+    bool nothing;
+    if (int st = prepare_quantize_elem(elem, x, rows, K, ldx, rule, use_mbs, codes, scales, mbs, q, &nothing)) return st;
+    if (nothing) return MX_OK;
+    const int64_t total = q.total_chunks;
     const int64_t waves = (total + kUnroll8 - 1) / kUnroll8;
     int64_t blocks = (waves + (kThreads8 / kWave) - 1) / (kThreads8 / kWave);
     if (blocks > (1 << 22)) blocks = 1 << 22;
@@ -352,10 +506,39 @@ int launch_quantize_elem(int elem, const void* x, int64_t rows, int64_t K, int64
     return launch_status();
 }
 
+int launch_quantize_elem_dynamic(int elem, const void* x, int64_t rows, int64_t K, int64_t ldx, int rule, int cand_first,
+                                 int cand_count, int cand_stride, uint8_t* codes, uint8_t* scales, uint8_t* mbs,
+                                 void* stream) {
+    if (cand_count < 0 || cand_count > 256 || cand_first < -65536 || cand_first > 65536 || cand_stride < -65536 ||
+        cand_stride > 65536)
+        return MX_EINVAL;
+    Dyn8Args d;
+    bool nothing;
+    if (int st = prepare_quantize_elem(elem, x, rows, K, ldx, rule, 1, codes, scales, mbs, d.q, &nothing)) return st;
+    if (nothing) return MX_OK;
+    d.cand_first = cand_first; d.cand_count = cand_count; d.cand_stride = cand_stride;
+    int64_t blocks = ((int64_t)d.q.total_chunks + (kThreads8 / kWave) - 1) / (kThreads8 / kWave);
+    if (blocks > (1 << 22)) blocks = 1 << 22;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)blocks), block(kThreads8);
+    if (elem == MX_ELEM_E4M3) hipLaunchKernelGGL(quantize8_dynamic_kernel<MX_ELEM_E4M3>, grid, block, 0, s, d);
+    else if (elem == MX_ELEM_E5M2) hipLaunchKernelGGL(quantize8_dynamic_kernel<MX_ELEM_E5M2>, grid, block, 0, s, d);
+    else if (elem == MX_ELEM_E2M3) hipLaunchKernelGGL(quantize8_dynamic_kernel<MX_ELEM_E2M3>, grid, block, 0, s, d);
+    else hipLaunchKernelGGL(quantize8_dynamic_kernel<MX_ELEM_E3M2>, grid, block, 0, s, d);
+    return launch_status();
+}
+
 }  // namespace
 }  // namespace mx
 
 extern "C" {
+
+int mx_quantize_elem_mbs_dynamic(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                 int32_t cand_first, int32_t cand_count, int32_t cand_stride, uint8_t* codes,
+                                 uint8_t* scales, uint8_t* mbs, void* stream) {
+    return mx::launch_quantize_elem_dynamic((int)elem, x_bf16, rows, K, ldx, (int)rule, cand_first, cand_count, cand_stride,
+                                            codes, scales, mbs, stream);
+}
 
 int mx_quantize_elem(mx_elem_t elem, const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                      int use_mbs, uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream) {

@@ -206,6 +206,14 @@ def test_elem_argument_errors(lib):
     assert q(E5, A16, 4, 64, 64, 2, 0, A16 + 4, A16, None, None) == -3  # codes 8-byte aligned
     assert q(E23, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0     # the 6-bit formats quantize too
     assert q(E4, A16, 0, 64, 64, 2, 0, A16, A16, None, None) == 0
+    qd = lib.mx_quantize_elem_mbs_dynamic
+    assert qd(E4, A16, 4, 48, 48, 2, 0, 16, 16, A16, A16, A16, None) == -1     # K % 32
+    assert qd(E2M1, A16, 4, 64, 64, 2, 0, 16, 16, A16, A16, A16, None) == -1   # the 4-bit format has its own entry point
+    assert qd(E4, A16, 4, 64, 64, 2, 0, 257, 16, A16, A16, A16, None) == -1    # too many candidates
+    assert qd(E4, A16, 4, 64, 64, 2, 0, 16, 70000, A16, A16, A16, None) == -1  # stride out of range
+    assert qd(E4, A16, 4, 64, 64, 2, 0, 16, 16, A16, A16, None, None) == -2    # the words have nowhere to go
+    assert qd(E5, A16, 4, 64, 64, 2, 0, 16, 16, A16 + 4, A16, A16, None) == -3
+    assert qd(E23, A16, 0, 64, 64, 2, 0, 16, 16, A16, A16, A16, None) == 0
     d = lib.mx_dequantize_elem
     assert d(E4, A16, A16, None, 4, 48, 0, A16, 48, None) == -1     # K % 32
     assert d(E2M1, A16, A16, None, 4, 64, 0, A16, 64, None) == -1   # the 4-bit format has its own entry point

@@ -209,6 +209,118 @@ def test_dequantize_elem_matches_oracle(mx, oracle, elem):
 
 
 # ------------------------------------------------------------------------------------------------
+# MBS-Dynamic
+# ------------------------------------------------------------------------------------------------
+def assert_elem_dynamic_valid(mx, oracle, elem, bits, rule="oas", what="", cands=(0, 16, 16)):
+    """The kernel sums squared errors in fp32, the oracle (Sec. 4.3.3, Eq. 6 with the true error) in fp64, so near-ties
+    may fall either way: what is unique is compared, the rest is checked for validity.
+      * the chosen word is the static word or one of the candidates;
+      * its exact sum of squared errors is within 1e-5 of the least one on offer, and where the least one is
+        separated from the runner-up by more than 1e-4 the word itself is the oracle's;
+      * windows the entry point documents as not searched (Inf/NaN inside, absmax outside [2^-63, 2^123)) keep the
+        static word;
+      * codes and scales are, bit for bit, those of the chosen word."""
+    c, s, w = mx.mx_quantize_elem_mbs_dynamic(dev_bf16(bits), elem, rule, *cands)
+    torch.cuda.synchronize()
+    gw, gs, gc = host(w), host(s), host(c)
+    tag = "%s %s rule=%s cands=%s" % (what, elem, rule, cands)
+    static = oracle.elem_quantize(elem, bits, rule, mbs=True)[2]
+    steps = [0] + [(cands[0] + j) * cands[2] for j in range(cands[1])]
+    cand = np.stack([((static.astype(np.int64) + st) % 256).astype(np.uint8) for st in steps])
+    sse = np.stack([oracle.elem_mbs_sse_rows(elem, bits, cw, rule) for cw in cand])
+    rows, K = bits.shape
+    nmac = static.shape[1]
+    pad = np.zeros((rows, nmac * 128), np.float64)
+    val = oracle.bf16_to_f64(bits)
+    pad[:, :K] = np.where(np.isfinite(val), np.abs(val), 0.0)
+    absmax = pad.reshape(rows, nmac, 128).max(2)
+    searched = (sse[0] >= 0) & (absmax >= 2.0 ** -63) & (absmax < 2.0 ** 123)
+    assert (cand == gw[None]).any(0).all(), "%s: a chosen word is not a candidate" % tag
+    bad = np.argwhere(~searched & (gw != static))
+    assert bad.size == 0, "%s: %d windows outside the searched domain left the static word, first %s" % (tag, len(bad), bad[:3])
+    got = oracle.elem_mbs_sse_rows(elem, bits, gw, rule)
+    best = sse.min(0)
+    bad = np.argwhere(searched & (got > best * (1 + 1e-5)))
+    assert bad.size == 0, "%s: %d windows miss the least SSE, first %s got %s best %s" % (
+        tag, len(bad), bad[:3], got[tuple(bad[0])], best[tuple(bad[0])])
+    ow = oracle.elem_quantize_mbs_dynamic(elem, bits, rule, *cands)[2]
+    others = np.where(cand == ow[None], np.inf, sse)
+    clear = searched & (others.min(0) > best * (1 + 1e-4))
+    bad = np.argwhere(clear & (gw != ow))
+    assert bad.size == 0, "%s: %d clearly separated windows differ from the oracle's word, first %s" % (tag, len(bad), bad[:3])
+    oc, os_, _ = oracle.elem_quantize_given_mbs(elem, bits, gw, rule)
+    for name, g, want in (("scales", gs, os_), ("code bytes", gc, canonical_codes(elem, oc))):
+        bad = np.argwhere(g != want)
+        assert bad.size == 0, "%s: %d %s differ from those of the chosen word, first at %s gpu=%s oracle=%s" % (
+            tag, len(bad), name, bad[:3], g[tuple(bad[0])], want[tuple(bad[0])])
+    return gw, float(clear.mean())
+
+
+@pytest.mark.parametrize("elem", QUANT_ELEMS)
+def test_quantize_elem_dynamic(mx, oracle, elem):
+    """MBS-Dynamic on every element format and rule: Gaussian weights and heavy-tailed rows (several chunks of 512
+    per row and a ragged tail with a half macro block), a list of candidates that passes the static word again,
+    none at all, and all 255 other words."""
+    from paper_2603_08713_amd import synth
+
+    w_bits = synth.gaussian(24, 1216, 0.02, 21)
+    t_bits = synth.activations_student_t(9, 2880, 3.0, 0.01, 20.0, 22)
+    moved = 0.0
+    for rule in RULES:
+        gw, clear = assert_elem_dynamic_valid(mx, oracle, elem, w_bits, rule, "weights")
+        static = oracle.elem_quantize(elem, w_bits, rule, mbs=True)[2]
+        moved = max(moved, float((gw != static).mean()))
+        assert clear > 0.5  # most windows have a clear winner: the comparison of words is not vacuous
+        assert_elem_dynamic_valid(mx, oracle, elem, t_bits, rule, "student-t", (-3, 9, 7))
+    assert moved > 0.3      # and the search does move words
+    assert_elem_dynamic_valid(mx, oracle, elem, w_bits[:4], "oas", "all words", (1, 255, 1))
+    # no candidates: MBS-Static, bit for bit
+    c, s, w = mx.mx_quantize_elem_mbs_dynamic(dev_bf16(w_bits), elem, "oas", 0, 0, 16)
+    c0, s0, w0 = mx.mx_quantize_elem(dev_bf16(w_bits), elem, "oas")
+    assert torch.equal(c, c0) and torch.equal(s, s0) and torch.equal(w, w0)
+    # the searched words lower the weights' error, and the GEMM consumes them unchanged
+    wk = np.ascontiguousarray(w_bits[:, :1152])
+    qs, qd = mx.mx_quantize_elem(dev_bf16(wk), elem, "oas"), mx.mx_quantize_elem_mbs_dynamic(dev_bf16(wk), elem, "oas")
+    ref = oracle.bf16_to_f64(wk)
+    q_static = oracle.qsnr_db(ref, host(mx.mx_dequantize_elem(elem, *qs, "f32")).astype(np.float64))
+    q_dynamic = oracle.qsnr_db(ref, host(mx.mx_dequantize_elem(elem, *qd, "f32")).astype(np.float64))
+    assert q_dynamic > q_static, (elem, q_static, q_dynamic)
+    a_bits = synth.activations_student_t(64, 1152, 3.0, 0.01, 20.0, 23)
+    qa = mx.mx_quantize_elem(dev_bf16(a_bits), elem, "oas")
+    oa = oracle.elem_quantize(elem, a_bits, "oas", mbs=True)
+    ob = oracle.elem_quantize_given_mbs(elem, wk, host(qd[2]), "oas")
+    assert_gemm_close(host(mx.mx_gemm_mbs_elem(elem, *qa, elem, *qd, "f32")), oracle.elem_gemm(elem, oa, elem, ob), "dynamic words %s" % elem)
+
+
+@pytest.mark.parametrize("elem", QUANT_ELEMS)
+def test_quantize_elem_dynamic_edge_cases(mx, oracle, elem):
+    """Zero windows, Inf and NaN, subnormal and huge magnitudes, a zero block beside a large one, blocks more than
+    30 binades apart, a strided input."""
+    rng = np.random.default_rng(24)
+    x = np.zeros((12, 512), np.uint16)
+    x[0] = 0                                            # all zero
+    x[1, ::7] = 0x0001                                  # smallest subnormals
+    x[2] = rng.integers(0x0001, 0x0080, 512)            # subnormal magnitudes
+    x[3] = rng.integers(0x7E00, 0x7F80, 512)            # the largest binades
+    x[4] = rng.integers(0x3C00, 0x4000, 512); x[4, 5] = 0x7F80; x[4, 300] = 0xFFC0   # Inf, NaN
+    x[5] = rng.integers(0x3C00, 0x4000, 512); x[5, 128:160] = 0                       # a zero block
+    x[6] = rng.integers(0x3C00, 0x4000, 512); x[6, 32:64] = rng.integers(0x1000, 0x1080, 32)  # ~88 binades below
+    x[7] = rng.integers(0x0000, 0x7F80, 512) | (rng.integers(0, 2, 512) << 15)        # anything finite, both signs
+    x[8] = rng.integers(0x1F80, 0x2100, 512)            # around 2^-63, the lower end of the searched domain
+    x[9] = rng.integers(0x7C80, 0x7E00, 512)            # around 2^123, the upper end
+    x[10] = rng.integers(0x3F80, 0x4000, 512) | 0x8000  # all negative
+    x[11] = 0x3F80                                      # all equal
+    for rule in RULES:
+        assert_elem_dynamic_valid(mx, oracle, elem, x, rule, "edge cases")
+    # strided input and preallocated outputs
+    big = torch.zeros((12, 640), dtype=torch.bfloat16, device="cuda")
+    big[:, :512] = dev_bf16(x)
+    c, s, w = mx.mx_quantize_elem_mbs_dynamic(big[:, :512], elem, "oas")
+    c1, s1, w1 = mx.mx_quantize_elem_mbs_dynamic(dev_bf16(x), elem, "oas")
+    assert torch.equal(c, c1) and torch.equal(s, s1) and torch.equal(w, w1)
+
+
+# ------------------------------------------------------------------------------------------------
 # GEMM
 # ------------------------------------------------------------------------------------------------
 def random_operand(rng, elem, rows, K, lo=110, hi=140):
