@@ -226,6 +226,8 @@ def main():
             ex["quantizers_on_8b_W"] = quantizer_extras(mx, torch, metrics, small, args)
             ex["mxfp8_e4m3"] = mxfp8_extras(mx, torch, small, args)
             ex["mxfp6_e2m3"] = mxfp8_extras(mx, torch, small, args, elem="e2m3")
+            ex["mxfp8_e4m3"]["decode"] = elem_decode_extras(mx, torch, synth, np, "e4m3")
+            ex["mxfp6_e2m3"]["decode"] = elem_decode_extras(mx, torch, synth, np, "e2m3")
         del w2, small
         torch.cuda.empty_cache()
         ex["moe_grouped"] = moe_extras(mx, torch, synth, np, metrics, args)
@@ -443,6 +445,38 @@ def mxfp8_extras(mx, torch, work, args, elem="e4m3"):
         c = mx.mx_gemm_mbs_elem(elem, *ta, elem, *tw, "f32")
         q[name] = round(float(10.0 * torch.log10((ref * ref).sum() / ((ref - c.to(torch.float64)) ** 2).sum())), 3)
     res["qsnr_ab_db_gpu"] = q
+    # MBS-Dynamic on these formats (exact search over 16 candidates), the weights of this shape
+    ms_dyn = time_loop(torch, lambda i: mx.mx_quantize_elem_mbs_dynamic(xw[i % len(xw)], elem, "oas", 0, 16, 16, *qw[i % len(qw)]), max(3, n // 4))
+    res["quantize_dynamic_W_ms"] = round(ms_dyn, 4)
+    res["quantize_static_W_ms"] = round(ms_qw, 4)
+    for i in range(len(qw)):  # (the timed search left its words in qw: back to the static ones)
+        mx.mx_quantize_elem(xw[i], elem, "oas", True, *qw[i])
+    return res
+
+
+def elem_decode_extras(mx, torch, synth, np, elem):
+    """Decode in MXFP8 / MXFP6: 16 activation rows against a 4096 x 4096 and a 14336 x 4096 weight through the few-row
+    kernel (quantized activations given), replayed from a HIP graph over enough copies of the weights to exceed the
+    Infinity Cache.  Bound: the weight bytes streamed once."""
+    res = {}
+    bpe = (0.75 if elem in ("e2m3", "e3m2") else 1.0) + 1 / 32 + 1 / 128
+    for n, copies in ((4096, 20), (14336, 6)):
+        a_bits, w_bits = synth.decode_skinny(n, 4096)
+        xa = torch.from_numpy(a_bits.view(np.int16)).view(torch.bfloat16).cuda()
+        w0 = mx.mx_quantize_elem(torch.from_numpy(w_bits.view(np.int16)).view(torch.bfloat16).cuda(), elem, "oas")
+        ws = [tuple(t.clone() for t in w0) for _ in range(copies)]
+        aq = mx.mx_quantize_elem(xa, elem, "oas")
+        c = torch.empty((16, n), dtype=torch.bfloat16, device="cuda")
+        mx.mx_gemm_mbs_elem(elem, *aq, elem, *ws[0], "bf16", out=c)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(copies):
+                mx.mx_gemm_mbs_elem(elem, *aq, elem, *ws[i], "bf16", out=c)
+        us = time_loop(torch, lambda i: graph.replay(), 20, warm=5) * 1e3 / copies
+        res["N=%d" % n] = {"gemm_us": round(us, 2), "weight_gbps": round(n * 4096 * bpe / us / 1e3, 1)}
+        del ws
+    res["bound"] = "hbm (weights streamed once: %.3f B per weight element)" % bpe
     return res
 
 
@@ -473,7 +507,18 @@ def moe_extras(mx, torch, synth, np, metrics, args):
     ms_qw = time_loop(torch, lambda i: mx.mx_quantize_mbs(xw, "oas", *b), n)
     loads = np.diff(np.asarray(offsets)).astype(int).tolist()
     tg, tp = flops / (ms_g * 1e-3) / 1e12, flops / (ms_p * 1e-3) / 1e12
+    # the same routing in MXFP8 / MXFP6 through the grouped entry point of those formats, which takes whole macro
+    # blocks only: K cut to 2816 = 22 x 128 (not the configuration's K; reported as what this kernel does)
+    kc = 2816
+    xa_c, xw_c = xa[:, :kc].contiguous(), xw[:, :kc].contiguous()
+    elem_grouped = {"K": kc}
+    for elem in ("e4m3", "e2m3"):
+        ea, eb = mx.mx_quantize_elem(xa_c, elem, "oas"), mx.mx_quantize_elem(xw_c, elem, "oas")
+        ms_e = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem_grouped(elem, *ea, elem, *eb, off, dim, "bf16", out=c), n)
+        elem_grouped[elem + "_grouped_gemm_mbs_tflops"] = round(2.0 * rows * dim * kc / (ms_e * 1e-3) / 1e12, 1)
+    del xa_c, xw_c
     return {
+        "mxfp8_mxfp6_grouped": elem_grouped,
         "workload": "32 experts of 2880x2880 N(0,0.02^2), 8192 tokens x 2880 (Student-t(4), 1%% channels x20) routed top-4, "
                     "P(e) ~ (e+1)^-1.1; %d rows in expert order" % rows,
         "kernel": mx.gemm_plan(rows, dim, dim, True, True, True),
