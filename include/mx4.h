@@ -120,6 +120,20 @@ int mx_quantize_mbs_dynamic_lut(const void* x_bf16, int64_t rows, int64_t K, int
                                 const uint16_t* lut_fp16, int keep_static,
                                 uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
 
+/* mx_quantize_mbs_dynamic_lut for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it) and so have no buffer to hand in for the table: the table lives in
+ * a 4 KiB array inside the library's code object, one copy per GPU, held until the process ends.  The array's
+ * size does not depend on the input, so the limits on rows and K are those of mx_quantize_mbs_dynamic_lut and
+ * are reported the same way (MX_EINVAL and the other codes, before anything is launched).  The call allocates
+ * nothing: it writes the whole table on `stream` (the kernel of mx_mbs_lut_build, so its contents are those
+ * bits) and then runs the kernel of mx_quantize_mbs_dynamic_lut on it; outputs are bit-identical to that entry
+ * point given a table from mx_mbs_lut_build.  All calls on one GPU share that GPU's array: calls that overlap on
+ * one GPU (different streams, or threads) race on it, though every writer stores the same values.
+ * x, codes, scales, mbs: DEVICE memory of the caller, as for mx_quantize_mbs. */
+int mx_quantize_mbs_dynamic_lut_static(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                       int keep_static,
+                                       uint8_t* codes, uint8_t* scales, uint8_t* mbs, void* stream);
+
 /* Reconstruct x_hat = value(code) * 2^(E-127) / F (Sec. 4.3.1) into out [rows, ldo] of
  * `out_dtype` (fp32: correctly rounded; bf16: that fp32 value rounded to nearest even).
  * mbs_or_null == NULL means F = 1.  E = 255 gives NaN. */

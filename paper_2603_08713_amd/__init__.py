@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     MX_OUT_BF16, MX_OUT_F32, MX_RULE_FLOOR, MX_RULE_OAS, MX_RULE_OCP, MxError, elem_code_bytes, load_library, forced, gemm_plan,
     mx_dequantize, mx_dequantize_elem, mx_gemm, mx_gemm_mbs, mx_gemm_mbs_elem, mx_gemm_mbs_elem_grouped, mx_gemm_mbs_grouped, mx_gemm_mbs_quantize_a, mx_quantize,
     mx_quantize_elem, mx_quantize_elem_mbs_dynamic, mx_quantize_mbs,
-    mx_mbs_lut_build, mx_quantize_mbs_dynamic, mx_quantize_mbs_dynamic_lut, mx_quantize_mbs_pair, mx_quantize_oas, mx_status_string, mx_version,
+    mx_mbs_lut_build, mx_quantize_mbs_dynamic, mx_quantize_mbs_dynamic_lut, mx_quantize_mbs_dynamic_lut_static, mx_quantize_mbs_pair, mx_quantize_oas, mx_status_string, mx_version,
 )

@@ -57,6 +57,8 @@ def load_library() -> ctypes.CDLL:
     L.mx_mbs_lut_build.argtypes = [vp, vp]
     L.mx_quantize_mbs_dynamic_lut.restype = ci
     L.mx_quantize_mbs_dynamic_lut.argtypes = [vp, i64, i64, i64, ci, vp, ci, vp, vp, vp, vp]
+    L.mx_quantize_mbs_dynamic_lut_static.restype = ci
+    L.mx_quantize_mbs_dynamic_lut_static.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, vp, i64, i64, ci, vp, i64, vp]
     L.mx_gemm.restype = ci
@@ -290,6 +292,17 @@ def mx_quantize_mbs_dynamic_lut(x, lut, rule="oas", keep_static=True, codes=None
     _check(load_library().mx_quantize_mbs_dynamic_lut(_ptr(x), rows, K, ldx, _rule(rule), _ptr(lut), int(bool(keep_static)),
                                                       _ptr(codes), _ptr(scales), _ptr(mbs), _stream()),
            "mx_quantize_mbs_dynamic_lut")
+    return codes, scales, mbs
+
+
+def mx_quantize_mbs_dynamic_lut_static(x, codes, scales, mbs, rule="oas", keep_static=True):
+    """mx_quantize_mbs_dynamic_lut on the table the library keeps per GPU; the call allocates nothing, so the
+    caller passes the three output tensors ([rows, K/2], [rows, K/32], [rows, ceil(K/128)], uint8)."""
+    rows, K, ldx = _rows_ld(x)
+    _alloc_outputs(x, rows, K, codes, scales, mbs, True)  # given all three, this only checks them
+    _check(load_library().mx_quantize_mbs_dynamic_lut_static(_ptr(x), rows, K, ldx, _rule(rule), int(bool(keep_static)),
+                                                             _ptr(codes), _ptr(scales), _ptr(mbs), _stream()),
+           "mx_quantize_mbs_dynamic_lut_static")
     return codes, scales, mbs
 
 

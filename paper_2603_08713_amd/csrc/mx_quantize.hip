@@ -21,6 +21,14 @@
 #include "mx_internal.h"
 #include "mx_quantize_math.h"
 
+#include <mutex>
+
+// The table of Eq. 5 for callers that cannot allocate: one copy per GPU inside the library's code object, held
+// until the process ends.  In host code `scratch` is only a stand-in for the symbol; the per-device address
+// comes from hipGetSymbolAddress, is looked up once per device with that device current, and is what every
+// launch and kernel argument below uses.
+static __device__ __align__(256) uint16_t scratch[2048];
+
 namespace mx {
 namespace {
 
@@ -689,10 +697,51 @@ int launch_quantize_dynamic_lut(const void* x, int64_t rows, int64_t K, int64_t 
     return launch_status();
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint16_t* g_scratch_ptr[kMaxDevices];  // guarded by g_scratch_mutex; null until looked up
+
+int scratch_for_current_device(uint16_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return MX_ELAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return MX_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return MX_ELAUNCH;
+        }
+        g_scratch_ptr[dev] = static_cast<uint16_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return MX_OK;
+}
+
 }  // namespace
 }  // namespace mx
 
 extern "C" {
+
+int mx_quantize_mbs_dynamic_lut_static(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
+                                       int keep_static, uint8_t* codes, uint8_t* scales, uint8_t* mbs,
+                                       void* stream) {
+    // argument errors first, as in the entry point this one is a variant of (nothing is launched on an error)
+    {
+        mx::QuantArgs probe;
+        bool empty;
+        if (int st = mx::fill_quant_args(probe, &empty, x_bf16, rows, K, ldx, (int)rule, 1, codes, scales, mbs, false)) return st;
+        if (empty) return MX_OK;
+    }
+    if (int st = mx::check_device()) return st;
+    uint16_t* table = nullptr;
+    if (int st = mx::scratch_for_current_device(&table)) return st;
+    // The array keeps whatever the last call on this GPU left, and a first call finds it zero: every call
+    // writes the whole table on its own stream in front of the kernel that reads it.
+    hipLaunchKernelGGL(mx::mbs_lut_build_kernel, dim3(8), dim3(256), 0, static_cast<hipStream_t>(stream), table);
+    if (int st = mx::launch_status()) return st;
+    return mx::launch_quantize_dynamic_lut(x_bf16, rows, K, ldx, (int)rule, table, keep_static, codes, scales, mbs, stream);
+}
 
 int mx_mbs_lut_build(uint16_t* lut_fp16, void* stream) {
     if (!lut_fp16) return MX_ENULL;

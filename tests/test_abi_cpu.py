@@ -73,6 +73,10 @@ def test_lut_entry_points_reject_bad_arguments(lib):
     assert q(A16, 4, 64, 64, 2, A16 + 4, 1, A16, A16, A16, None) == -3   # table misaligned
     assert q(A16, 4, 64, 64, 2, A16, 1, A16, A16, None, None) == -2      # mbs required
     assert q(A16, 0, 64, 64, 2, A16, 1, A16, A16, A16, None) == 0
+    s = lib.mx_quantize_mbs_dynamic_lut_static                            # the same checks, before any GPU call
+    assert s(A16, 4, 48, 48, 2, 1, A16, A16, A16, None) == -1
+    assert s(A16, 4, 64, 64, 2, 1, A16, A16, None, None) == -2
+    assert s(A16, 0, 64, 64, 2, 1, A16, A16, A16, None) == 0
 
 
 def test_gemm_plan_names_the_kernel_a_problem_takes(lib):
