@@ -82,6 +82,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // pairs) all fragments have two register sets, taken in turn, and the next stage's are requested behind the
     // first pair; with words on one operand the B fragment alone has two.
     constexpr bool kDoubleAll = kSurface && !kSnake, kDoubleB = kMbs && !kSurface && FN == 1;
+    // The loop over the stages that issue loads takes two groups of four stages per turn (see run below).
+    constexpr bool kTwoGroups = kSnake && !S::kGen;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -221,8 +223,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     struct RawWords {
         uint32_t first[kConv], second[kConv];
     };
-    auto load_words = [&](int s, RawWords& r) {
-        const uint32_t* raw = reinterpret_cast<const uint32_t*>(smem + S::kM8Base + ((s / kRingGroup) & 1) * S::kM8Group);
+    // (gp_: the parity of stage s's group where the caller knows it at compile time, -1 where it does not: a known
+    // parity turns the slot's address into a constant of the LDS instruction)
+    auto load_words = [&](int s, RawWords& r, auto gp_) {
+        constexpr int gp = decltype(gp_)::value;
+        const uint32_t* raw = reinterpret_cast<const uint32_t*>(smem + S::kM8Base + (gp < 0 ? (s / kRingGroup) & 1 : gp) * S::kM8Group);
 #pragma unroll
         for (int i = 0; i < kConv; ++i) {
             const int q = i * NT + tid;  // (a side without words reads zero and stores sigma = 1, which nobody reads)
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     };
     auto convert_sigma_pair = [&](int s) {  // stages s and s + 1 at once (prologue)
         RawWords r;
-        load_words(s, r);
+        load_words(s, r, std::integral_constant<int, -1>{});
         store_sigma(s, r.first);
         store_sigma(s + 1, r.second);
     };
@@ -305,8 +310,9 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // LDS read `idx` of the kReads that fetch the fragments of a stage in ring slot `slot`: per fragment (A's
     // FM, then B's FN) the two 16-byte code pieces and the 16-bit scale pair.
     constexpr int kReads = (FM + FN) * 3;
-    auto read_item = [&](Frags& f, int s, auto slot_, auto idx_) {
+    auto read_item = [&](Frags& f, int s, auto slot_, auto idx_, auto gp_) {
         constexpr int idx = decltype(idx_)::value, fr = idx / 3, part = idx % 3, slot = decltype(slot_)::value;
+        constexpr int gp = decltype(gp_)::value;  // parity of stage s's group, -1: not known at compile time
         constexpr bool is_m = fr < FM;
         constexpr int q = is_m ? fr : fr - FM;
         if constexpr (part < 2) {
@@ -319,7 +325,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             // fast form: [row][16 bytes of the group]; general forms: [row][8 pairs], one pair per dword, or
             // [row][16 bytes], one byte per dword (the lane's two bytes come as two dwords and are packed)
             uint32_t v;
-            const uint8_t* grp_base = smem + S::kScaleBase + ((s / kRingGroup) & 1) * S::kScaleGroup;
+            const uint8_t* grp_base = smem + S::kScaleBase + (gp < 0 ? (s / kRingGroup) & 1 : gp) * S::kScaleGroup;
             if constexpr (S::kBytes) {
                 // (a plain vector type: before a read through HIP's uint2 the compiler waits for every
                 // outstanding direct-to-LDS load)
@@ -407,7 +413,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         read_sigma_m(0, std::integral_constant<int, 0>{});
         read_sigma_n(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     }
-    static_for<kReads>([&](auto idx_) { read_item(f0, 0, std::integral_constant<int, 0>{}, idx_); });
+    static_for<kReads>([&](auto idx_) { read_item(f0, 0, std::integral_constant<int, 0>{}, idx_, std::integral_constant<int, 0>{}); });
 
     // ---- the matrix instructions of one stage ---------------------------------------------------------
     // Plain: instruction t is half kk = t / (FM FN) of fragment pair (i, j); the two halves of a pair are
@@ -475,8 +481,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     // One stage: multiply stage s out of `cur`; slipped in between the matrix instructions, the LDS reads of
     // stage s + 1 into `next` and, with kIssue, this stage's loads.  The wavefronts issue their loads at
     // different instruction slots (kLate 0 or 1).
-    auto stage = [&](int s, const Frags& cur, Frags& next, auto phase_, auto late_, auto issue_) {
-        constexpr int kPhase = decltype(phase_)::value, kLate = decltype(late_)::value;
+    // gp_: the parity of the stage's group of four (which of the two slots its E8M0 bytes and MBS words sit in) where
+    // the caller knows it at compile time, -1 where it does not.
+    auto stage = [&](int s, const Frags& cur, Frags& next, auto phase_, auto late_, auto issue_, auto gp_) {
+        constexpr int kPhase = decltype(phase_)::value, kLate = decltype(late_)::value, kGp = decltype(gp_)::value;
+        using NextGp = std::integral_constant<int, kGp < 0 ? -1 : kPhase == 3 ? 1 - kGp : kGp>;    // of stage s + 1
+        using WordsGp = std::integral_constant<int, kGp < 0 ? -1 : kPhase >= 2 ? 1 - kGp : kGp>;   // of stage s + 2
         using Par = std::integral_constant<int, kPhase % 2>;       // stage parity: kRingGroup is even
         using NextPar = std::integral_constant<int, 1 - kPhase % 2>;
         using NextSlot = std::integral_constant<int, (kPhase + 1) % kRingSlots>;  // stage s sits in slot s % 4 = kPhase
@@ -494,7 +504,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         // next stage's barrier, into the tables that the stages s - 2 and s - 1 were read from)
         constexpr bool kConvert = kMbs && !Sched::has_barrier(kPhase);
         RawWords words;
-        if constexpr (kConvert) load_words(s + 2, words);
+        if constexpr (kConvert) load_words(s + 2, words, WordsGp{});
         auto convert = [&]() {
             if constexpr (kConvert) {
                 store_sigma(s + 2, words.first);
@@ -505,7 +515,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             constexpr int t = decltype(t_)::value;
             if constexpr (!kMbs) {
                 static_for<kReads>([&](auto r_) {
-                    if constexpr ((decltype(r_)::value * kMfmas) / kReads == t) read_item(next, s + 1, NextSlot{}, r_);
+                    if constexpr ((decltype(r_)::value * kMfmas) / kReads == t) read_item(next, s + 1, NextSlot{}, r_, NextGp{});
                 });
             }
             if constexpr (kMbs && t == kMfmas / 2) read_sigma_m(s + 1, NextPar{});
@@ -528,7 +538,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             read_sigma_m(s + 1, NextPar{});
             auto refill = [&](Frags& dst, auto f_) {  // fragment f of stage s + 1: two code pieces and the E8M0 pair
                 static_for<3>([&](auto part_) {
-                    read_item(dst, s + 1, NextSlot{}, std::integral_constant<int, decltype(f_)::value * 3 + decltype(part_)::value>{});
+                    read_item(dst, s + 1, NextSlot{}, std::integral_constant<int, decltype(f_)::value * 3 + decltype(part_)::value>{}, NextGp{});
                 });
             };
             static_for<4>([&](auto q_) {
@@ -604,7 +614,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                 fold(BeforePar{}, Before{}, I1{});
                 __builtin_amdgcn_sched_barrier(0);
                 // (two register sets: the next stage's fragments are requested behind the first pair)
-                if constexpr (kDoubleAll && q == 0) static_for<kReads>([&](auto idx_) { read_item(next, s + 1, NextSlot{}, idx_); });
+                if constexpr (kDoubleAll && q == 0) static_for<kReads>([&](auto idx_) { read_item(next, s + 1, NextSlot{}, idx_, NextGp{}); });
                 if constexpr (q % 2 == 1) {
                     constexpr int shadow = q / 2;
                     if constexpr (shadow + 1 < kShadows) issue_surface(Par{}, std::integral_constant<int, shadow + 1>{});
@@ -617,7 +627,7 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                         constexpr int f = decltype(f_)::value;
                         constexpr int last = f < FM ? (FN - 1) * FM + f : (f - FM) * FM + FM - 1;  // last pair that reads it
                         if constexpr (last == q || last == q - 1) static_for<3>([&](auto part_) {
-                            read_item(next, s + 1, NextSlot{}, std::integral_constant<int, f * 3 + decltype(part_)::value>{});
+                            read_item(next, s + 1, NextSlot{}, std::integral_constant<int, f * 3 + decltype(part_)::value>{}, NextGp{});
                         });
                     });
                     if constexpr (kIssue) {
@@ -640,14 +650,14 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                     // the next stage's B fragment into the register set this stage does not use, behind the first pair
                     if constexpr (decltype(p_)::value == 0) static_for<3>([&](auto part_) {
                         using Idx = std::integral_constant<int, FM * 3 + decltype(part_)::value>;
-                        if constexpr (kPhase % 2 == 0) read_item(alt, s + 1, NextSlot{}, Idx{});
-                        else read_item(next, s + 1, NextSlot{}, Idx{});
+                        if constexpr (kPhase % 2 == 0) read_item(alt, s + 1, NextSlot{}, Idx{}, NextGp{});
+                        else read_item(next, s + 1, NextSlot{}, Idx{}, NextGp{});
                     });
                 } else if constexpr (pi == FM - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{});
+                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, (FM + pj) * 3 + decltype(part_)::value>{}, NextGp{});
                 });
                 if constexpr (pj == FN - 1) static_for<3>([&](auto part_) {
-                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, pi * 3 + decltype(part_)::value>{});
+                    read_item(next, s + 1, NextSlot{}, std::integral_constant<int, pi * 3 + decltype(part_)::value>{}, NextGp{});
                 });
             };
             issue(std::integral_constant<int, 0>{});
@@ -695,18 +705,35 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         using P3 = std::integral_constant<int, 3>;
         Frags& fa = f0;
         Frags& fb = kMbs && !kDoubleAll ? f0 : f1;  // the MBS path refills one set in place (kDoubleAll aside)
+        using G0 = std::integral_constant<int, 0>;
+        using G1 = std::integral_constant<int, 1>;
+        using Gx = std::integral_constant<int, -1>;
         int s = 0;
+        if constexpr (kTwoGroups) {
+            // two groups per turn: which of the two slots a group's E8M0 bytes and MBS words sit in is then a
+            // constant of the LDS instructions that read them, which saves the vector ALUs the address additions
+            for (; s + 8 <= n_issue; s += 8) {
+                stage(s, fa, fb, P0{}, late_, Yes{}, G0{});
+                stage(s + 1, fb, fa, P1{}, late_, Yes{}, G0{});
+                stage(s + 2, fa, fb, P2{}, late_, Yes{}, G0{});
+                stage(s + 3, fb, fa, P3{}, late_, Yes{}, G0{});
+                stage(s + 4, fa, fb, P0{}, late_, Yes{}, G1{});
+                stage(s + 5, fb, fa, P1{}, late_, Yes{}, G1{});
+                stage(s + 6, fa, fb, P2{}, late_, Yes{}, G1{});
+                stage(s + 7, fb, fa, P3{}, late_, Yes{}, G1{});
+            }
+        }
         for (; s < n_issue; s += 4) {
-            stage(s, fa, fb, P0{}, late_, Yes{});
-            stage(s + 1, fb, fa, P1{}, late_, Yes{});
-            stage(s + 2, fa, fb, P2{}, late_, Yes{});
-            stage(s + 3, fb, fa, P3{}, late_, Yes{});
+            stage(s, fa, fb, P0{}, late_, Yes{}, Gx{});
+            stage(s + 1, fb, fa, P1{}, late_, Yes{}, Gx{});
+            stage(s + 2, fa, fb, P2{}, late_, Yes{}, Gx{});
+            stage(s + 3, fb, fa, P3{}, late_, Yes{}, Gx{});
         }
         for (; s < nstages; s += 4) {  // nstages is a multiple of the group
-            stage(s, fa, fb, P0{}, late_, No{});
-            stage(s + 1, fb, fa, P1{}, late_, No{});
-            stage(s + 2, fa, fb, P2{}, late_, No{});
-            stage(s + 3, fb, fa, P3{}, late_, No{});
+            stage(s, fa, fb, P0{}, late_, No{}, Gx{});
+            stage(s + 1, fb, fa, P1{}, late_, No{}, Gx{});
+            stage(s + 2, fa, fb, P2{}, late_, No{}, Gx{});
+            stage(s + 3, fb, fa, P3{}, late_, No{}, Gx{});
         }
     };
     // (with one wavefront per SIMD every stalled load stalls the matrix pipeline: half of the wavefronts issue
