@@ -84,6 +84,8 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     constexpr bool kDoubleAll = kSurface && !kSnake, kDoubleB = kMbs && !kSurface && FN == 1;
     // The loop over the stages that issue loads takes two groups of four stages per turn (see run below).
     constexpr bool kTwoGroups = kSnake && !S::kGen;
+    // sigma = 1 / (1 + m8 / 256) read from a table of its 256 values instead of computed per row and stage
+    constexpr bool kSigmaLut = kSnake && !S::kGen;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
@@ -248,6 +250,28 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
             *dst = __builtin_amdgcn_rcpf(1.0f + (float)m8 * (1.0f / 256.0f));
         }
     };
+    // The same through a table of the 256 possible values (kSigmaLut): the reciprocal runs at a quarter of the
+    // vector rate and the conversion has two more vector instructions in front of it, all on the issue port that
+    // bounds the MBS path; a table read costs the port one LDS instruction.  lookup_sigma requests the values of
+    // stage s, store_looked_up writes them to the stage's table later in the stage.
+    auto lookup_sigma = [&](int s, const uint32_t (&words)[kConv], float (&val)[kConv]) {
+        const uint8_t* tab = smem + S::kRcpBase;
+#pragma unroll
+        for (int i = 0; i < kConv; ++i) {
+            const uint32_t at = S::kGen ? (words[i] & 0xFFu) << 2 : ((words[i] >> (8 * (s % kRingGroup))) & 0xFFu) << 2;
+            val[i] = *reinterpret_cast<const float*>(tab + at);
+        }
+    };
+    auto store_looked_up = [&](int s, const float (&val)[kConv]) {
+        float* sig = reinterpret_cast<float*>(smem + S::kSigmaBase + (s % kSigmaSlots) * S::kSigmaStage);
+#pragma unroll
+        for (int i = 0; i < kConv; ++i) {
+            const int q = i * NT + tid;
+            const bool live = kRows % NT == 0 || q < kRows;
+            float* dst = live ? sig + (live ? q : 0) : reinterpret_cast<float*>(smem + S::kDummy);
+            *dst = val[i];
+        }
+    };
     auto convert_sigma_pair = [&](int s) {  // stages s and s + 1 at once (prologue)
         RawWords r;
         load_words(s, r, std::integral_constant<int, -1>{});
@@ -402,6 +426,11 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         else if constexpr (it.kind == kLoadScale) dma_scale(it.what, Index{});
         else dma_m8(it.what, Index{});
     });
+    if constexpr (kSigmaLut) {
+        static_assert(NT >= 256, "one thread per table entry");
+        if (tid < 256) reinterpret_cast<float*>(smem + S::kRcpBase)[tid] = __builtin_amdgcn_rcpf(1.0f + (float)tid * (1.0f / 256.0f));
+        __builtin_amdgcn_s_waitcnt(kWaitLds);  // the barrier below publishes the table
+    }
     __builtin_amdgcn_s_waitcnt(wait_imm(Sched::prologue_wait_first()));
     bare_barrier();
     Frags f0, f1;
@@ -505,8 +534,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
         constexpr bool kConvert = kMbs && !Sched::has_barrier(kPhase);
         RawWords words;
         if constexpr (kConvert) load_words(s + 2, words, WordsGp{});
+        float looked_up[2][kConv];
         auto convert = [&]() {
-            if constexpr (kConvert) {
+            if constexpr (kConvert && kSigmaLut) {
+                store_looked_up(s + 2, looked_up[0]);
+                store_looked_up(s + 3, looked_up[1]);
+            } else if constexpr (kConvert) {
                 store_sigma(s + 2, words.first);
                 store_sigma(s + 3, words.second);
             }
@@ -580,6 +613,10 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
                         static_for<kN>([&](auto n_) {
                             if constexpr ((decltype(n_)::value * 2) / kN == shadow) issue_load(s, phase_, n_);
                         });
+                    }
+                    if constexpr (shadow == 0 && kConvert && kSigmaLut) {
+                        lookup_sigma(s + 2, words.first, looked_up[0]);
+                        lookup_sigma(s + 3, words.second, looked_up[1]);
                     }
                     if constexpr (shadow == 1) convert();
                 }

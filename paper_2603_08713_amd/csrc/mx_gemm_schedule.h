@@ -66,7 +66,10 @@ struct RingShape {
     // The small arrays come first: their addresses then fit the 16-bit constant of an LDS instruction.
     static constexpr int kM8Base = 0;
     static constexpr int kSigmaBase = kM8Base + 2 * kM8Group;
-    static constexpr int kScaleBase = (kSigmaBase + kSigmaSlots * kSigmaStage + 16383) / 16384 * 16384;
+    // the 256 values sigma can take, 1 / (1 + m8 / 256) in fp32 (kernels that look sigma up instead of computing it)
+    static constexpr int kRcpBase = kSigmaBase + kSigmaSlots * kSigmaStage;
+    static constexpr int kRcpBytes = kMbs ? 1024 : 0;
+    static constexpr int kScaleBase = (kRcpBase + kRcpBytes + 16383) / 16384 * 16384;
     static constexpr int kDummy = kScaleBase + 2 * kScaleGroup;  // target of padding stores
     static constexpr int kCodesBase = kDummy + 256;
     static constexpr int kLdsBytes = kCodesBase + kRingSlots * kCodesStage;
