@@ -128,7 +128,9 @@ int mx_quantize_mbs_dynamic_lut(const void* x_bf16, int64_t rows, int64_t K, int
  * nothing: it writes the whole table on `stream` (the kernel of mx_mbs_lut_build, so its contents are those
  * bits) and then runs the kernel of mx_quantize_mbs_dynamic_lut on it; outputs are bit-identical to that entry
  * point given a table from mx_mbs_lut_build.  All calls on one GPU share that GPU's array: calls that overlap on
- * one GPU (different streams, or threads) race on it, though every writer stores the same values.
+ * one GPU (different streams, or threads) race on it, though every writer stores the same values.  The array's
+ * address on a device is looked up by the first call on that device that has work to do (rows > 0 and K > 0); a
+ * caller that captures graphs makes that first call before the capture begins.
  * x, codes, scales, mbs: DEVICE memory of the caller, as for mx_quantize_mbs. */
 int mx_quantize_mbs_dynamic_lut_static(const void* x_bf16, int64_t rows, int64_t K, int64_t ldx, mx_rule_t rule,
                                        int keep_static,

@@ -324,7 +324,7 @@ int launch_gemm_skinny(const GemmArgs& g, bool use_mbs, hipStream_t s) {
     return launch_skinny_rows<false>(a, s);
 }
 
-// The same with A given as bf16 [M, ldx] and quantized on the fly (rule, MBS-Static words if a_mbs); the
+// The same with A given as bf16 [M, ldx] and quantized inside the kernel (rule, MBS-Static words if a_mbs); the
 // a_* members of g are not used.  Also requires x 16-byte aligned, ldx % 8 == 0 and the rows of x to span
 // less than 2 GiB; the caller has checked these.
 int launch_gemm_skinny_fused(const GemmArgs& g, const void* x, int64_t ldx, int rule, bool a_mbs, hipStream_t s) {
