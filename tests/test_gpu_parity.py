@@ -817,6 +817,9 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
     with mx.forced(gemm_shape=shape):
         sizes = ((700, 530, 1536), (257, 300, 512)) + (((300, 260, 2880), (130, 129, 64)) if shape in (8, 9, 10) else ())
         sizes += ((200, 140, 2016), (33, 50, 32)) if shape == 10 else ()
+        # (the 256 x 128 MBS kernel takes two groups of four stages per loop turn: a K with no such turn and one
+        # with a turn followed by a single group, beside the 1536 above, which has exactly one turn)
+        sizes += ((300, 200, 1024), (260, 130, 2048)) if shape == 3 else ()
         for (M, N, K) in sizes:
             a, b = random_operand(rng, M, K), random_operand(rng, N, K)
             da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
