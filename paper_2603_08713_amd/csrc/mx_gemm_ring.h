@@ -90,13 +90,18 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
 
     // ---- which tile: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of
     // tiles, walked in bands of kRingGroupM tile-rows so that concurrent workgroups share panels in its L2
-    const int total = g.tiles_m * g.tiles_n;
+    // (grouped: the launch took an upper bound of the tile-rows; the tiles are dealt out over the real number)
+    int tiles_m = g.tiles_m;
+    if constexpr (S::kGen) {
+        if (g.num_groups > 0) tiles_m = grouped_tile_rows(g.row_offsets, g.num_groups, TM, (int)(threadIdx.x & 63));
+    }
+    const int total = tiles_m * g.tiles_n;
     const int per_xcd = (total + 7) / 8;
     const int linear = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || linear >= total) return;
     const int band = kRingGroupM * g.tiles_n;
     const int first_m = (linear / band) * kRingGroupM;
-    const int band_rows = min(g.tiles_m - first_m, kRingGroupM);
+    const int band_rows = min(tiles_m - first_m, kRingGroupM);
     const int tm = first_m + (linear % band) % band_rows;
     const int tn = (linear % band) / band_rows;
     // Rows of A and C this tile covers and the rows of B it multiplies with.  Grouped (general form only):
@@ -105,20 +110,12 @@ __global__ __launch_bounds__(S::NT) void gemm_ring_kernel(GemmArgs g) {
     int64_t a_row0 = (int64_t)tm * TM, a_end = g.M, b_row0 = (int64_t)tn * TN, b_end = g.N;
     if constexpr (S::kGen) {
         if (g.num_groups > 0) {
-            int e = 0, first = 0;  // first tile-row of group e
-            int64_t lo = g.row_offsets[0], hi = lo;
-            for (;; ++e) {
-                if (e == g.num_groups) return;  // tile-rows beyond the last group (the grid is an upper bound)
-                hi = g.row_offsets[e + 1];
-                const int rows_e = (int)((hi - lo + TM - 1) / TM);
-                if (tm < first + rows_e) break;
-                first += rows_e;
-                lo = hi;
-            }
-            a_row0 = lo + (int64_t)(tm - first) * TM;
-            a_end = hi;
-            b_row0 = (int64_t)e * g.N + (int64_t)tn * TN;
-            b_end = (int64_t)(e + 1) * g.N;
+            GroupOfTileRow gr;
+            if (!grouped_find(g.row_offsets, g.num_groups, TM, (int)(threadIdx.x & 63), tm, gr)) return;
+            a_row0 = gr.lo + (int64_t)(tm - gr.first) * TM;
+            a_end = gr.hi;
+            b_row0 = (int64_t)gr.group * g.N + (int64_t)tn * TN;
+            b_end = (int64_t)(gr.group + 1) * g.N;
         }
     }
 

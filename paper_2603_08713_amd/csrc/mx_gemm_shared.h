@@ -101,6 +101,67 @@ __device__ __forceinline__ Operand make_operand(const uint8_t* codes, const uint
 
 constexpr int kOob = 0x7FFFFFF0;  // byte offset beyond any buffer: the load returns zero
 
+// ---- grouped problems: which rows a tile-row covers ------------------------------------------------------------
+// Group e owns rows off[e] .. off[e + 1] - 1 of A and C, the e-th of the stacked weights, and
+// ceil(rows / tile_rows) tile-rows; tile-rows are counted group by group.  Every wavefront works this out for
+// itself with one group per lane (64 groups per pass): a walk from group to group would be one memory round trip
+// per group in front of every tile, and only the kernel can know how many tile-rows there really are - the launch
+// takes an upper bound, and tiles dealt out over that bound would leave the last XCDs without work.
+__device__ __forceinline__ int wave_scan_add(int x, int lane) {  // inclusive prefix sum over the 64 lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __builtin_amdgcn_ds_bpermute(((lane - d) & 63) << 2, x);
+        if (lane >= d) x += t;
+    }
+    return x;
+}
+__device__ __forceinline__ int64_t readlane64(int64_t v, int idx) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, idx);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), idx);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+// tile-rows of all groups together (the same value in every lane)
+__device__ __forceinline__ int grouped_tile_rows(const int64_t* off, int num_groups, int tile_rows, int lane) {
+    int total = 0;
+    for (int base = 0; base < num_groups; base += 64) {
+        const int e = base + lane;
+        int rows = 0;
+        if (e < num_groups) rows = (int)((off[e + 1] - off[e] + tile_rows - 1) / tile_rows);
+        total += __builtin_amdgcn_readlane(wave_scan_add(rows, lane), 63);
+    }
+    return total;
+}
+struct GroupOfTileRow {
+    int group, first;  // the group and its first tile-row
+    int64_t lo, hi;    // its rows
+};
+// the group tile-row tm belongs to (uniform over the wavefront); false if tm lies past the last group
+__device__ __forceinline__ bool grouped_find(const int64_t* off, int num_groups, int tile_rows, int lane, int tm,
+                                             GroupOfTileRow& out) {
+    int before = 0;
+    for (int base = 0; base < num_groups; base += 64) {
+        const int e = base + lane;
+        int64_t lo = 0, hi = 0;
+        if (e < num_groups) {
+            lo = off[e];
+            hi = off[e + 1];
+        }
+        const int rows = (int)((hi - lo + tile_rows - 1) / tile_rows);
+        const int incl = wave_scan_add(rows, lane);
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(before + incl > tm);
+        if (hit != 0) {
+            const int idx = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hit));
+            out.group = base + idx;
+            out.first = before + __builtin_amdgcn_readlane(incl - rows, idx);
+            out.lo = readlane64(lo, idx);
+            out.hi = readlane64(hi, idx);
+            return true;
+        }
+        before += __builtin_amdgcn_readlane(incl, 63);
+    }
+    return false;
+}
+
 __device__ __forceinline__ v4f mfma_fp4(v4i n_frag, v4i m_frag, v4f c, uint32_t scale_n, uint32_t scale_m) {
     const v8i a = __builtin_shufflevector(n_frag, n_frag, 0, 1, 2, 3, -1, -1, -1, -1);
     const v8i b = __builtin_shufflevector(m_frag, m_frag, 0, 1, 2, 3, -1, -1, -1, -1);
