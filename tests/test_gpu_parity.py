@@ -889,6 +889,34 @@ def test_grouped_gemm(mx, oracle):
         assert_gemm_close(got[lo:hi], want, "group %d" % e)
 
 
+def test_grouped_gemm_many_groups(mx, oracle):
+    """More groups than a wavefront has lanes (the kernel looks its group up 64 groups at a time), with empty groups
+    at the start, across the boundary between the two passes and at the end, and groups of more than one tile-row."""
+    rng = np.random.default_rng(78)
+    G, N, K = 70, 96, 256
+    counts = rng.integers(1, 40, G)
+    counts[[0, 1, 62, 63, 64, 65, 69]] = 0
+    counts[5], counts[66] = 300, 130
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    M = int(offsets[-1])
+    a, b = random_operand(rng, M, K, 118, 136), random_operand(rng, G * N, K, 118, 136)
+    da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+    doff = torch.from_numpy(offsets).cuda()
+    out = torch.full((M + 3, N), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_mbs_grouped(da[0], da[1], da[2], db[0], db[1], db[2], doff, N, "f32", out=out[:M])
+    plain = mx.mx_gemm_mbs_grouped(da[0], da[1], None, db[0], db[1], None, doff, N, "f32")
+    got, got_plain = host(out), host(plain)
+    assert np.all(got[M:] == -7.0)
+    for e in range(G):
+        lo, hi = offsets[e], offsets[e + 1]
+        if lo == hi:
+            continue
+        rows_a, rows_b = tuple(t[lo:hi] for t in a), tuple(t[e * N:(e + 1) * N] for t in b)
+        assert_gemm_close(got[lo:hi], oracle.gemm(rows_a, rows_b), "group %d of %d" % (e, G))
+        assert_gemm_close(got_plain[lo:hi], oracle.gemm((rows_a[0], rows_a[1], None), (rows_b[0], rows_b[1], None)),
+                          "group %d of %d, no words" % (e, G))
+
+
 @pytest.mark.parametrize("M", [1, 7, 16, 17, 33, 64])
 def test_gemm_few_rows(mx, oracle, M):
     """The few-row (decode) kernel: every fragment count, ragged N, K of one to several load groups per

@@ -589,6 +589,33 @@ def test_gemm_elem_grouped(mx, oracle, ea, eb):
     assert float((out + 7.0).abs().max()) == 0.0
 
 
+def test_gemm_elem_grouped_many_groups(mx, oracle):
+    """More groups than a wavefront has lanes, empty ones at the start, across the 64th and at the end: every group
+    equals the ungrouped entry point's general form on its rows and weight, bit for bit, and the oracle on a few."""
+    rng = np.random.default_rng(52)
+    ea = eb = "e4m3"
+    G, N, K = 70, 72, 256
+    sizes = rng.integers(1, 30, G)
+    sizes[[0, 1, 62, 63, 64, 65, 69]] = 0
+    sizes[7], sizes[67] = 270, 129
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total = int(offs[-1])
+    (a, pa), (b, pb) = random_operand_any(rng, ea, total, K, 112, 140), random_operand_any(rng, eb, G * N, K, 112, 140)
+    da, db = [dev_u8(t) for t in pa], [dev_u8(t) for t in pb]
+    out = torch.full((total + 2, N), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_mbs_elem_grouped(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], torch.from_numpy(offs).cuda(), N, "f32", out=out[:total])
+    got = host(out)
+    assert np.all(got[total:] == -7.0)
+    for e in range(G):
+        lo, hi_ = int(offs[e]), int(offs[e + 1])
+        if lo == hi_:
+            continue
+        pa_e, pb_e = tuple(t[lo:hi_] for t in pa), tuple(t[e * N:(e + 1) * N] for t in pb)
+        assert np.array_equal(host(gpu_gemm(mx, ea, pa_e, eb, pb_e, kernel=1)), got[lo:hi_]), e
+        if e in (2, 7, 61, 66, 67, 68):
+            assert_gemm_elem_ok(oracle, got[lo:hi_], ea, tuple(t[lo:hi_] for t in a), eb, tuple(t[e * N:(e + 1) * N] for t in b), "group %d" % e)
+
+
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
     """Products that need no alignment (codes for 0, +-0.5, +-1, +-2, 4) add up exactly: any misplaced element,
     scale byte or sigma shows as an integer-sized error."""
