@@ -186,17 +186,25 @@ __device__ __forceinline__ uint32_t code8_alu(float t) {
     return (((ey - 127u + T::kBias) << T::kMbits) + q - (1u << T::kMbits)) | ((tb >> 31) << (T::kBits - 1));
 }
 
-template <int kElem, bool kHwCvt, bool kMbs>
-__device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) {
+// The scale byte, the MBS word and the multiplier F * 2^(127 - E) of the lane's block, in fp32 arithmetic; `odd`
+// (uniform over the wavefront) says that some block of the chunk lies outside the range where that arithmetic is
+// exact (exponent field of its absmax outside [24, 249], or Inf/NaN) and the chunk must take the all-integer route.
+struct Scale8 {
+    uint32_t E, m8;
+    float mult;
+    bool odd;
+};
+
+template <int kElem, bool kMbs>
+__device__ __forceinline__ Scale8 chunk_scale8(u32x4 v, const Quant8Args& q) {
     using T = Fp8<kElem>;
     uint32_t m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
                             pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
     uint32_t amax = max(m & 0xFFFFu, m >> 16);
     amax = max(amax, dpp_quad_xor1(amax));
     amax = max(amax, dpp_quad_xor2(amax));
-    // exponent field outside [24, 249] (or Inf/NaN): leave fp32 arithmetic, wave-uniformly
     const bool odd = (amax >= (250u << 7)) || (amax != 0 && amax < (24u << 7));
-    if (__builtin_amdgcn_ballot_w64(odd) != 0) return quantize_chunk8_exact<T>(v, q.rule, kMbs);
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) return {0u, 0u, 0.0f, true};
 
     uint32_t m8 = 0;
     if constexpr (kMbs) {
@@ -207,7 +215,16 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
     const float scaled_max = __uint_as_float(amax << 16) * __uint_as_float(0x3F800000u | (m8 << 15));  // exact
     uint32_t E = ((__float_as_uint(scaled_max) + q.carry) >> 23) - (uint32_t)T::kEmax;
     E = amax ? E : 127u;
-    const float mult = __uint_as_float(((254u - E) << 23) | (m8 << 15));  // F * 2^(127 - E)
+    return {E, m8, __uint_as_float(((254u - E) << 23) | (m8 << 15)), false};
+}
+
+template <int kElem, bool kHwCvt, bool kMbs>
+__device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) {
+    using T = Fp8<kElem>;
+    const Scale8 sc = chunk_scale8<kElem, kMbs>(v, q);
+    if (sc.odd) return quantize_chunk8_exact<T>(v, q.rule, kMbs);
+    const uint32_t E = sc.E, m8 = sc.m8;
+    const float mult = sc.mult;
     const float vmax = __uint_as_float(T::kMaxBits);
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     uint32_t out[2] = {0, 0};
@@ -231,6 +248,49 @@ __device__ __forceinline__ Chunk8 quantize_chunk8(u32x4 v, const Quant8Args& q) 
         }
     }
     return {out[0], out[1], E, m8};
+}
+
+// Four chunks at once through the 32-element hardware convert (v_cvt_scalef32_2xpk16_fp6_f32 / _bf6_f32; measured
+// on the device: result element 2 i is the i-th value of the first operand, element 2 i + 1 the i-th of the second,
+// element e in bits 6 e .. 6 e + 5; nearest even, subnormals kept, saturating at the largest finite magnitude; the
+// scale operand divides).  A dword of the input holds two consecutive elements, so the low halves of all dwords go
+// to the first operand and the high halves to the second.  Returns false, with nothing done, if a chunk has to
+// leave fp32 arithmetic (uniform over the wavefront).
+template <int kElem, bool kMbs>
+__device__ __forceinline__ bool quantize_chunks6_hw(const u32x4 (&v)[kUnroll8], const Quant8Args& q, Chunk8 (&res)[kUnroll8]) {
+    typedef float v16f __attribute__((ext_vector_type(16)));
+    typedef uint32_t v6u __attribute__((ext_vector_type(6)));
+    Scale8 sc[kUnroll8];
+    bool odd = false;
+#pragma unroll
+    for (int u = 0; u < kUnroll8; ++u) {
+        sc[u] = chunk_scale8<kElem, kMbs>(v[u], q);
+        odd |= sc[u].odd;
+    }
+    if (odd) return false;
+    v16f even, uneven;
+#pragma unroll
+    for (int u = 0; u < kUnroll8; ++u) {
+        const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            even[4 * u + i] = __uint_as_float(w[i] << 16) * sc[u].mult;            // exact
+            uneven[4 * u + i] = __uint_as_float(w[i] & 0xFFFF0000u) * sc[u].mult;
+        }
+    }
+    // The instruction writes its six result registers while it still reads its 32 source registers, so the result
+    // must not share registers with the sources.  The compiler's builtin does not know that (its register
+    // allocation put the result inside the second operand, and the elements read after the overwrite came out
+    // as zero), hence the instruction itself with an early-clobber result.
+    v6u r;
+    if constexpr (kElem == MX_ELEM_E2M3) asm("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, 1.0" : "=&v"(r) : "v"(even), "v"(uneven));
+    else asm("v_cvt_scalef32_2xpk16_bf6_f32 %0, %1, %2, 1.0" : "=&v"(r) : "v"(even), "v"(uneven));
+    // chunk u: bits 48 u .. 48 u + 47 of the 192
+    res[0] = {r[0], r[1] & 0xFFFFu, sc[0].E, sc[0].m8};
+    res[1] = {(r[1] >> 16) | (r[2] << 16), r[2] >> 16, sc[1].E, sc[1].m8};
+    res[2] = {r[3], r[4] & 0xFFFFu, sc[2].E, sc[2].m8};
+    res[3] = {(r[4] >> 16) | (r[5] << 16), r[5] >> 16, sc[3].E, sc[3].m8};
+    return true;
 }
 
 // A chunk's results to memory: the lane's codes, its block's scale byte, its macro block's word.  Every lane of the
@@ -305,11 +365,27 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
                 v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q.x + (int64_t)r * q.ldx + col[u]));
             if (++cc == q.chunks_per_row) { cc = 0; ++r; }
         }
+        if constexpr (kHwCvt && Fp8<kElem>::kBits == 6) {
+            // 6-bit formats: the hardware converts 32 fp32 values at a time, which is what a lane holds over the
+            // kUnroll8 chunks in flight (8 each, every chunk with its own multiplier).
+            static_assert(kUnroll8 == 4, "four chunks of eight elements fill one convert");
+            Chunk8 res[kUnroll8];
+            if (!quantize_chunks6_hw<kElem, kMbs>(v, q, res)) {
 #pragma unroll
-        for (int u = 0; u < kUnroll8; ++u) {
-            if (c0 + u >= q.total_chunks) break;  // wave-uniform
-            const Chunk8 res = quantize_chunk8<kElem, kHwCvt, kMbs>(v[u], q);
-            store_chunk8<kElem, kMbs>(q, res, lane, row[u], col[u], valid[u]);
+                for (int u = 0; u < kUnroll8; ++u) res[u] = quantize_chunk8<kElem, false, kMbs>(v[u], q);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll8; ++u) {
+                if (c0 + u >= q.total_chunks) break;  // wave-uniform
+                store_chunk8<kElem, kMbs>(q, res[u], lane, row[u], col[u], valid[u]);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll8; ++u) {
+                if (c0 + u >= q.total_chunks) break;  // wave-uniform
+                const Chunk8 res = quantize_chunk8<kElem, kHwCvt, kMbs>(v[u], q);
+                store_chunk8<kElem, kMbs>(q, res, lane, row[u], col[u], valid[u]);
+            }
         }
     }
 }
