@@ -94,6 +94,21 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
                 if (q.mbs) m8[u] = q.mbs[(int64_t)row * q.nmac + (col >> 7)];
             }
         }
+        // 6-bit codes: the hardware expands 32 at a time (v_cvt_scalef32_pk32_f32_fp6 / _bf6; measured: result
+        // register e is the code in bits 6 e .. 6 e + 5, every code exact, the sign of a zero kept, the scale operand
+        // multiplies); the lane's two runs are 16 of them.  The instruction is issued with an early-clobber result:
+        // it writes its 32 result registers while its six source registers are still being read.
+        float six[16];
+        if constexpr (kSix) {
+            typedef float v32f __attribute__((ext_vector_type(32)));
+            typedef uint32_t v6u __attribute__((ext_vector_type(6)));
+            const v6u packed = {cw[0].x, cw[0].y | (cw[1].x << 16), (cw[1].x >> 16) | (cw[1].y << 16), 0u, 0u, 0u};
+            v32f all;
+            if constexpr (kElem == MX_ELEM_E2M3) asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, 1.0" : "=&v"(all) : "v"(packed));
+            else asm("v_cvt_scalef32_pk32_f32_bf6 %0, %1, 1.0" : "=&v"(all) : "v"(packed));
+#pragma unroll
+            for (int j = 0; j < 16; ++j) six[j] = all[j];
+        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const uint32_t col = col0 + u * 512;
@@ -107,11 +122,10 @@ __global__ __launch_bounds__(kDq8Threads) void dequantize8_kernel(Dequant8Args q
                 if constexpr (kSix) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const uint32_t code = run_code<kElem>(cw[u], j);
-                        const float t = fp8_magnitude<kElem>(code) * scale;    // exact
+                        const float t = six[8 * u + j] * scale;                // exact
                         const float q0 = t * r;
                         const float rem = __builtin_fmaf(-q0, F, t);           // exact
-                        v[j] = __uint_as_float(__float_as_uint(__builtin_fmaf(rem, r, q0)) | fp8_sign<kElem>(code));
+                        v[j] = __builtin_copysignf(__builtin_fmaf(rem, r, q0), t);  // (the sign of a zero)
                     }
                 } else {
                     // 8-bit codes: the hardware convert expands two at a time and applies the scale (exact)
