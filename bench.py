@@ -507,16 +507,13 @@ def moe_extras(mx, torch, synth, np, metrics, args):
     ms_qw = time_loop(torch, lambda i: mx.mx_quantize_mbs(xw, "oas", *b), n)
     loads = np.diff(np.asarray(offsets)).astype(int).tolist()
     tg, tp = flops / (ms_g * 1e-3) / 1e12, flops / (ms_p * 1e-3) / 1e12
-    # the same routing in MXFP8 / MXFP6 through the grouped entry point of those formats, which takes whole macro
-    # blocks only: K cut to 2816 = 22 x 128 (not the configuration's K; reported as what this kernel does)
-    kc = 2816
-    xa_c, xw_c = xa[:, :kc].contiguous(), xw[:, :kc].contiguous()
-    elem_grouped = {"K": kc}
+    # the same routing and the same K in MXFP8 / MXFP6 through the grouped entry point of those formats
+    elem_grouped = {"K": dim}
     for elem in ("e4m3", "e2m3"):
-        ea, eb = mx.mx_quantize_elem(xa_c, elem, "oas"), mx.mx_quantize_elem(xw_c, elem, "oas")
+        ea, eb = mx.mx_quantize_elem(xa, elem, "oas"), mx.mx_quantize_elem(xw, elem, "oas")
         ms_e = time_loop(torch, lambda i: mx.mx_gemm_mbs_elem_grouped(elem, *ea, elem, *eb, off, dim, "bf16", out=c), n)
-        elem_grouped[elem + "_grouped_gemm_mbs_tflops"] = round(2.0 * rows * dim * kc / (ms_e * 1e-3) / 1e12, 1)
-    del xa_c, xw_c
+        elem_grouped[elem + "_grouped_gemm_mbs_tflops"] = round(flops / (ms_e * 1e-3) / 1e12, 1)
+        del ea, eb
     return {
         "mxfp8_mxfp6_grouped": elem_grouped,
         "workload": "32 experts of 2880x2880 N(0,0.02^2), 8192 tokens x 2880 (Student-t(4), 1%% channels x20) routed top-4, "

@@ -230,8 +230,10 @@ int mx_dequantize_elem(mx_elem_t elem, const uint8_t* codes, const uint8_t* scal
 
 /* mx_gemm_mbs for operands in 8-bit or in 6-bit element formats (A's and B's may differ, but both are 8-bit or
  * both 6-bit): the same sum, the same MBS correction per 128 K-elements (Sec. 4.3.2, which does not depend on
- * the element format), on the same scaled matrix instruction.  Covers K > 0, K % 128 == 0, codes 16-byte and
- * scale arrays 4-byte aligned; anything else returns MX_EUNSUPPORTED and nothing is launched.  (K % 512 == 0,
+ * the element format), on the same scaled matrix instruction.  Covers K >= 128 in whole macro blocks or ending
+ * with half of one (K % 64 == 0; the short last macro block of Sec. 4.3.1's windows, as for the MXFP4 entry
+ * points), codes 16-byte aligned, scale arrays 4-byte aligned (2-byte where K % 128 == 64); anything else
+ * returns MX_EUNSUPPORTED and nothing is launched.  (K % 512 == 0,
  * 16-byte aligned scale arrays and 4-byte aligned MBS arrays take a faster form of the kernel; with M <= 64 and
  * K <= 8192 besides, a kernel that streams the weights once.)
  *

@@ -32,7 +32,7 @@
 // stages: a row's 16 E8M0 bytes as one 16-byte piece into one of two LDS buffers, its four MBS words as one dword
 // into a register of the thread that owns the row.  That thread turns the word of stage s + 1 into
 // sigma = 1 / (1 + m8 / 256) during stage s, into one of two LDS tables that the barrier publishes.  The general
-// form (any K % 128 == 0) fetches one dword of E8M0 bytes and one MBS word per lane and stage into registers and
+// form (any K % 64 == 0 from 128 on) fetches one dword of E8M0 bytes and one MBS word per lane and stage into registers and
 // keeps a sigma table per wavefront.
 //
 // 6-bit operands (E2M3, E3M2; codes packed 32 to 24 bytes) run the fast form of the same template.  As for FP4, a
@@ -40,7 +40,7 @@
 // byte.  A stage is 96 bytes of a row; so that no 128-byte line of memory is fetched twice, the ring slots hold
 // planes instead of stages: slot L = bytes 128 L .. + 127 of the 384 that a group of four stages takes of each
 // row, loaded during stage L + 1 of the group before.  Details at the places marked kSix.  Their general form (any
-// K % 128 == 0) keeps a stage per ring slot like the 8-bit one: the 96 bytes of a row sit in places 0 .. 5 of the
+// K % 64 == 0 from 128 on) keeps a stage per ring slot like the 8-bit one: the 96 bytes of a row sit in places 0 .. 5 of the
 // row's eight 16-byte places, a quarter of the lanes of a code load fetch nothing, and a stage's bytes straddle the
 // 128-byte lines of memory, so half of the lines are fetched twice (from the L2).
 //
@@ -102,7 +102,11 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
         }
     }
 
-    const int K = (int)g.K, scale_bytes = K >> 5, nmac = K / kMacro, nstages = nmac;
+    // general form: K may end with half a macro block (K % 128 == 64): the last stage then holds two blocks of
+    // every row; the pieces of its codes past the end of the row are fetched out of range (zeros), and its E8M0 dword
+    // is fetched two bytes early, so that it ends with the row, and shifted down when it is used
+    const int K = (int)g.K, scale_bytes = K >> 5, nmac = (K + kMacro - 1) / kMacro, nstages = nmac;
+    const bool half_tail = !kFast && (K % kMacro) != 0;
     const int row_bytes = kSix ? K / 4 * 3 : K;
     // buffer resources rebased to the tile's first row and sized to its valid rows: rows past the end read zero
     const int kRsrcFlags = 0x00020000;
@@ -141,6 +145,9 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     const int code_piece = (l & 7) ^ ((code_row0 >> 1) & 7);
     const bool code_idle = kSixGen && code_piece >= 6;
     const int code_off0 = code_row0 * row_bytes + code_piece * 16;
+    // (last stage: the lane's piece lies past the end of the row)
+    const int tail_soff = (nstages - 1) * kRowStage;
+    const bool code_past_tail = !kFast && tail_soff + code_piece * 16 >= row_bytes;
     // general form: a lane's E8M0 dword per fragment and stage, and the MBS word of the row it converts
     const int scale_off_a0 = (wm * FM * 32 + lr) * scale_bytes, scale_off_b0 = (wn * FN * 32 + lr) * scale_bytes;
     const int m8_off_a = (wm * FM * 32 + l) * nmac, m8_off_b = (wn * FN * 32 + l) * nmac;
@@ -159,13 +166,14 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     // load i of the codes that start soff bytes into their rows into ring slot `slot`
     auto issue_code = [&](int soff, auto slot_, auto i_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value, i = decltype(i_)::value, kLoadsA = TM / 8 / NW;
+        const bool idle = code_idle || (!kFast && code_past_tail && soff == tail_soff);
         if constexpr (i < kLoadsA) {
             uint8_t* dst = smem + S::kBaseA + slot * S::kStageA + (i * NW + w) * 1024;
-            const int voff = code_idle ? kOob : code_off0 + i * NW * 8 * row_bytes;
+            const int voff = idle ? kOob : code_off0 + i * NW * 8 * row_bytes;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(a_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         } else if constexpr (i < kCodeDma) {
             uint8_t* dst = smem + S::kBaseB + slot * S::kStageB + ((i - kLoadsA) * NW + w) * 1024;
-            const int voff = code_idle ? kOob : code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
+            const int voff = idle ? kOob : code_off0 + (i - kLoadsA) * NW * 8 * row_bytes;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(b_codes, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
         }
     };
@@ -185,13 +193,14 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
     auto issue_regs = [&](int st, auto slot_) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_)::value;
         if constexpr (!kFast) {
+            const int scale_soff = st * 4 - (half_tail && st == nstages - 1 ? 2 : 0);
             static_for<FM>([&](auto i_) {
                 const int voff = scale_off_a0 + decltype(i_)::value * 32 * scale_bytes;
-                pref[slot].sa[decltype(i_)::value] = __builtin_amdgcn_raw_buffer_load_b32(a_scales, voff, st * 4, 0);
+                pref[slot].sa[decltype(i_)::value] = __builtin_amdgcn_raw_buffer_load_b32(a_scales, voff, scale_soff, 0);
             });
             static_for<FN>([&](auto j_) {
                 const int voff = scale_off_b0 + decltype(j_)::value * 32 * scale_bytes;
-                pref[slot].sb[decltype(j_)::value] = __builtin_amdgcn_raw_buffer_load_b32(b_scales, voff, st * 4, 0);
+                pref[slot].sb[decltype(j_)::value] = __builtin_amdgcn_raw_buffer_load_b32(b_scales, voff, scale_soff, 0);
             });
             if constexpr (kMbs) {
                 pref[slot].ma = __builtin_amdgcn_raw_buffer_load_b8(a_mbs, m8_off_a, st, 0);
@@ -411,10 +420,13 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
             if constexpr (t % S::kGroup == 0) issue_group(s / S::kGroup + 1, std::integral_constant<int, (t / S::kGroup + 1) % 3>{});
         } else {
             // what this stage needs of its prefetched registers, before the loads of stage s + 3 take them over
+            // (half a macro block at the end of K: the dword was fetched two bytes early; shifted down, the bytes of
+            // the two blocks that do not exist read 0, a finite scale for their zero codes)
+            const uint32_t early = half_tail && s == nstages - 1 ? 16u : 0u;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) scl_a[i] = pref[slot].sa[i] >> (kSclShift * lh);
+            for (int i = 0; i < FM; ++i) scl_a[i] = (pref[slot].sa[i] >> early) >> (kSclShift * lh);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) scl_b[j] = pref[slot].sb[j] >> (kSclShift * lh);
+            for (int j = 0; j < FN; ++j) scl_b[j] = (pref[slot].sb[j] >> early) >> (kSclShift * lh);
             if constexpr (kMbs) {
                 sig[l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].ma * (1.0f / 256.0f));
                 sig[64 + l] = __builtin_amdgcn_rcpf(1.0f + (float)pref[slot].mb * (1.0f / 256.0f));
@@ -656,8 +668,11 @@ int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales
     const size_t esz = c_dtype == MX_OUT_F32 ? 4 : 2;
     if (!aligned(C, esz)) return MX_EALIGN;
     const bool a8 = a_elem == MX_ELEM_E4M3 || a_elem == MX_ELEM_E5M2, b8 = b_elem == MX_ELEM_E4M3 || b_elem == MX_ELEM_E5M2;
-    if (a8 != b8 || K == 0 || (K % kMacro) != 0 || !aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(a_scales, 4) ||
-        !aligned(b_scales, 4))
+    // K in whole macro blocks, or ending with half of one (the general form; rows of E8M0 bytes then start on even
+    // addresses only)
+    const bool half_tail = (K % kMacro) != 0;
+    if (a8 != b8 || K == 0 || (K % (kMacro / 2)) != 0 || K < kMacro || !aligned(a_codes, 16) || !aligned(b_codes, 16) ||
+        !aligned(a_scales, half_tail ? 2 : 4) || !aligned(b_scales, half_tail ? 2 : 4))
         return MX_EUNSUPPORTED;
     if (int st = check_device()) return st;
     GemmArgs g = {};

@@ -328,7 +328,7 @@ def random_operand(rng, elem, rows, K, lo=110, hi=140):
     c = rng.integers(0, 256, (rows, K), dtype=np.uint8)
     mag = c & 0x7F
     c = np.where(mag > MAX_CODE[elem], (c & 0x80) | (mag & 0x3F), c).astype(np.uint8)
-    return (c, rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8), rng.integers(0, 256, (rows, K // 128), dtype=np.uint8))
+    return (c, rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8), rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
 
 
 def gpu_gemm(mx, ea, a, eb, b, out_dtype="f32", out=None, kernel=2):
@@ -373,7 +373,9 @@ def test_gemm_elem_random_codes_and_scales(mx, oracle, ea, eb):
     # (K % 512 == 0 takes the kernel's fast form: 1, 2, 3 and 4 groups of four stages, then one turn of the loop,
     # and one turn plus one and plus two groups)
     for (M, N, K) in ((16, 16, 128), (64, 48, 256), (130, 200, 384), (257, 129, 1024), (300, 260, 640), (520, 390, 896),
-                      (40, 200, 512), (257, 130, 1536), (100, 129, 2048), (70, 140, 6144), (33, 260, 6656), (260, 33, 7168)):
+                      (40, 200, 512), (257, 130, 1536), (100, 129, 2048), (70, 140, 6144), (33, 260, 6656), (260, 33, 7168),
+                      # K ending with half a macro block (general form; rows of E8M0 bytes on even addresses only)
+                      (130, 200, 192), (257, 129, 1216), (300, 140, 2880)):
         a, b = random_operand(rng, ea, M, K, 110, hi), random_operand(rng, eb, N, K, 110, hi)
         assert_gemm_within_abs_bound(oracle, host(gpu_gemm(mx, ea, a, eb, b)), ea, a, eb, b, "mbs %dx%dx%d" % (M, N, K))
         for a1, b1, name in (((a[0], a[1], None), b, "B words only"), (a, (b[0], b[1], None), "A words only"),
@@ -390,11 +392,13 @@ def test_gemm_elem_six_bit_random_codes_and_scales(mx, oracle, ea, eb):
     of the 8-bit formats applies."""
     rng = np.random.default_rng(46)
     for (M, N, K) in ((16, 16, 512), (257, 130, 1536), (100, 129, 2048), (300, 260, 1024), (70, 140, 6144), (33, 260, 6656),
-                      (260, 33, 7168), (16, 16, 128), (130, 200, 384), (300, 260, 640), (520, 390, 896), (257, 129, 1664)):
+                      (260, 33, 7168), (16, 16, 128), (130, 200, 384), (300, 260, 640), (520, 390, 896), (257, 129, 1664),
+                      # K ending with half a macro block: the last stage holds 48 of its 96 bytes per row
+                      (130, 200, 192), (257, 129, 1216), (300, 140, 2880)):
         a = (rng.integers(0, 64, (M, K), dtype=np.uint8), rng.integers(110, 140, (M, K // 32), dtype=np.uint8),
-             rng.integers(0, 256, (M, K // 128), dtype=np.uint8))
+             rng.integers(0, 256, (M, (K + 127) // 128), dtype=np.uint8))
         b = (rng.integers(0, 64, (N, K), dtype=np.uint8), rng.integers(110, 140, (N, K // 32), dtype=np.uint8),
-             rng.integers(0, 256, (N, K // 128), dtype=np.uint8))
+             rng.integers(0, 256, (N, (K + 127) // 128), dtype=np.uint8))
         for a1, b1, name in ((a, b, "mbs"), ((a[0], a[1], None), b, "B words only"), ((a[0], a[1], None), (b[0], b[1], None), "no words")):
             pa, pb = (canonical_codes(ea, a1[0]), a1[1], a1[2]), (canonical_codes(eb, b1[0]), b1[1], b1[2])
             got = host(gpu_gemm(mx, ea, pa, eb, pb))
@@ -485,7 +489,7 @@ def random_operand_any(rng, elem, rows, K, lo=110, hi=140):
         op = random_operand(rng, elem, rows, K, lo, hi)
         return op, op
     op = (rng.integers(0, 64, (rows, K), dtype=np.uint8), rng.integers(lo, hi, (rows, K // 32), dtype=np.uint8),
-          rng.integers(0, 256, (rows, K // 128), dtype=np.uint8))
+          rng.integers(0, 256, (rows, (K + 127) // 128), dtype=np.uint8))
     return op, (canonical_codes(elem, op[0]), op[1], op[2])
 
 
@@ -616,6 +620,42 @@ def test_gemm_elem_grouped_many_groups(mx, oracle):
             assert_gemm_elem_ok(oracle, got[lo:hi_], ea, tuple(t[lo:hi_] for t in a), eb, tuple(t[e * N:(e + 1) * N] for t in b), "group %d" % e)
 
 
+@pytest.mark.parametrize("ea,eb", [("e4m3", "e4m3"), ("e2m3", "e3m2")])
+def test_gemm_elem_grouped_k_ending_in_half_a_macro_block(mx, oracle, ea, eb):
+    """The MoE configuration's K = 2880 = 22.5 macro blocks, grouped: rows of E8M0 bytes are 90 bytes long, so every
+    other row's dwords start on an address that is even but not a multiple of four; a NaN scale byte (255) at the
+    start of a row must not leak into the row before through the blocks that do not exist."""
+    rng = np.random.default_rng(53)
+    N, K = 136, 2880
+    sizes = [3, 0, 260, 41]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total, G = int(offs[-1]), len(sizes)
+    (a, pa), (b, pb) = random_operand_any(rng, ea, total, K, 116, 136), random_operand_any(rng, eb, G * N, K, 116, 136)
+    # rows 1 and 5 of A and row 1 of every weight start with a NaN block: their own outputs are NaN, no others
+    for t in (a, pa):
+        t[1][[1, 5], 0] = 255
+    for t in (b, pb):
+        t[1][1::N, 0] = 255
+    da, db = [dev_u8(t) for t in pa], [dev_u8(t) for t in pb]
+    out = torch.full((total, N), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_mbs_elem_grouped(ea, da[0], da[1], da[2], eb, db[0], db[1], db[2], torch.from_numpy(offs).cuda(), N, "f32", out=out)
+    got = host(out)
+    nan_rows, nan_cols = np.zeros(total, bool), np.zeros(N, bool)
+    nan_rows[[1, 5]] = True
+    nan_cols[1] = True
+    assert np.all(np.isnan(got[nan_rows])) and np.all(np.isnan(got[:, nan_cols]))
+    keep = np.ix_(~nan_rows, ~nan_cols)
+    assert not np.any(np.isnan(got[keep]))
+    for e in range(G):
+        lo, hi_ = int(offs[e]), int(offs[e + 1])
+        if lo == hi_:
+            continue
+        rows = np.array([r for r in range(lo, hi_) if not nan_rows[r]])
+        a_e = tuple(t[rows] for t in a)
+        b_e = tuple(t[e * N:(e + 1) * N][~nan_cols] for t in b)
+        assert_gemm_elem_ok(oracle, got[rows][:, ~nan_cols], ea, a_e, eb, b_e, "group %d" % e)
+
+
 def test_gemm_elem_exact_on_small_integers(mx, oracle):
     """Products that need no alignment (codes for 0, +-0.5, +-1, +-2, 4) add up exactly: any misplaced element,
     scale byte or sigma shows as an integer-sized error."""
@@ -658,7 +698,12 @@ def test_gemm_elem_empty_and_unsupported(mx):
     b64 = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
     s64 = torch.full((8, 2), 127, dtype=torch.uint8, device="cuda")
     with pytest.raises(mx.MxError) as e:
-        mx.mx_gemm_mbs_elem("e4m3", b64, s64, None, "e4m3", b64, s64, None)  # K % 128 != 0
+        mx.mx_gemm_mbs_elem("e4m3", b64, s64, None, "e4m3", b64, s64, None)  # K below one macro block
+    assert e.value.status == -4
+    b96 = torch.zeros((8, 224), dtype=torch.uint8, device="cuda")
+    s96 = torch.full((8, 7), 127, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mx.MxError) as e:
+        mx.mx_gemm_mbs_elem("e4m3", b96, s96, None, "e4m3", b96, s96, None)  # K % 64 != 0
     assert e.value.status == -4
 
 
