@@ -63,6 +63,35 @@ def test_static_table_entry_point_matches_the_one_with_a_caller_table(mx, keep_s
             assert bool((got[rows] == 0xA5).all()), "%s: guard row written at %dx%d" % (name, rows, K)
 
 
+def test_static_table_entry_point_in_a_captured_graph(mx):
+    """Its callers include code under graph capture: the first call on the device is made before the capture (it looks
+    the table's address up); the captured call is replayed over changing inputs, with eager work between the replays,
+    and every replay equals the entry point with a caller's table."""
+    from paper_2603_08713_amd import synth
+
+    lib = mx.load_library()
+    lut = mx.mx_mbs_lut_build()
+    rows, K = 40, 1536
+    x = _dev_bf16(synth.gaussian(rows, K, 0.02, 21))
+    codes = torch.zeros((rows, K // 2), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((rows, K // 32), dtype=torch.uint8, device="cuda")
+    mbs = torch.zeros((rows, K // 128), dtype=torch.uint8, device="cuda")
+    _call_static(lib, x, 2, 1, codes, scales, mbs)  # outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        _call_static(lib, x, 2, 1, codes, scales, mbs)
+    for replay in range(4):
+        x.copy_(_dev_bf16(synth.gaussian(rows, K, 0.02 * (replay + 1), 30 + replay)))
+        for t in (codes, scales, mbs):
+            t.fill_(0xA5)                                # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = mx.mx_quantize_mbs_dynamic_lut(x, lut, "oas", True)
+        assert torch.equal(codes, want[0]) and torch.equal(scales, want[1]) and torch.equal(mbs, want[2]), replay
+
+
 def test_static_table_entry_point_rejects_what_the_other_rejects(mx):
     lib = mx.load_library()
     x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
