@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantArgs q) {
 // difference is exact in fp32, and its squares are accumulated.  So that the minimum is reproducible the
 // cost has a fixed order of operations: fused multiply-adds over the lane's 8 elements in order, pairwise
 // sums over the 4 lanes of a block, an exact rescale from the block's binade to the macro block's,
-// pairwise sums over the 4 blocks, one correctly rounded division by F^2.  The static word is the
+// pairwise sums over the 4 blocks, one multiplication by the reciprocal of F^2 (within an ulp).  The static word is the
 // incumbent; a candidate replaces the current choice only with a strictly smaller cost.  The search runs
 // where fp32 holds every intermediate exactly (exponent field of the macro-block absmax in [64, 249], no
 // Inf/NaN in it); a block whose own absmax is zero or more than 30 binades below contributes nothing.
@@ -293,7 +293,7 @@ __device__ __forceinline__ Candidate eval_candidate(const float (&xf)[8], uint32
     acc = acc * rescale;
     acc = acc + dpp_half_mirror_f(acc);
     acc = acc + dpp_mirror_f(acc);
-    return {codes, E, acc / (F * F)};
+    return {codes, E, acc * __builtin_amdgcn_rcpf(F * F)};
 }
 
 __global__ __launch_bounds__(kThreads) void quantize_dynamic_kernel(DynArgs d) {

@@ -397,8 +397,8 @@ __global__ __launch_bounds__(kThreads8) void quantize8_kernel(Quant8Args q) {
 // exact in fp32, its grid value comes out of the rounding addition of code8_alu (the sum minus the added constant),
 // and their difference is exact.  The cost has a fixed order of operations so that the minimum is reproducible:
 // fused multiply-adds over the lane's 8 elements in order, pairwise sums over the 4 lanes of a block, an exact
-// rescale from the block's binade to the macro block's, pairwise sums over the 4 blocks, one correctly rounded
-// division by F^2.  The static word is the incumbent; a candidate replaces the current choice only with a strictly
+// rescale from the block's binade to the macro block's, pairwise sums over the 4 blocks, one multiplication by
+// the reciprocal of F^2 (within an ulp).  The static word is the incumbent; a candidate replaces the current choice only with a strictly
 // smaller cost.  The search runs where fp32 holds every intermediate exactly (exponent field of the macro-block
 // absmax in [64, 249], no Inf/NaN in it); a block whose own absmax is zero or more than 30 binades below
 // contributes nothing.
@@ -455,7 +455,7 @@ __device__ __forceinline__ Cand8 eval_candidate8(const float (&xf)[8], uint32_t 
     acc = acc * rescale;
     acc = acc + dpp_f<0x141>(acc);  // lane i <-> 7 - i inside each half row: the neighbouring block
     acc = acc + dpp_f<0x140>(acc);  // lane i <-> 15 - i inside each row: the neighbouring pair of blocks
-    return {lo, hi, E, acc / (F * F)};
+    return {lo, hi, E, acc * __builtin_amdgcn_rcpf(F * F)};
 }
 
 template <int kElem>
