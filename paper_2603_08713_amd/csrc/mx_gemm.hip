@@ -54,6 +54,8 @@ int launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* 
     g.tiles_m = g.tiles_n = 0;
     g.c_bf16 = c_dtype == MX_OUT_BF16;
     g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
+    g.vec_store8 = aligned(C, 8) && (ldc * esz) % 8 == 0;
+    g.vec_store4 = aligned(C, 4) && (ldc * esz) % 4 == 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = mbs_entry && (a_mbs || b_mbs);

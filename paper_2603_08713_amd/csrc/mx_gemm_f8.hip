@@ -604,11 +604,31 @@ __global__ __launch_bounds__(F8Shape<kFast>::NT) void gemm_f8_kernel(GemmArgs g)
                     if (whole) {
                         __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(o));
                     } else {
+                        // rows of C that start on 8-byte but not on 16-byte boundaries: the halves of the piece that
+                        // lie inside the row go out as 8-byte stores, the rest element by element
 #pragma unroll
-                        for (int e = 0; e < per; ++e) {
-                            if (n + e >= g.N) break;
-                            if constexpr (kBf16) reinterpret_cast<uint16_t*>(o)[e] = (uint16_t)((uint32_t)v[e >> 1] >> ((e & 1) * 16));
-                            else reinterpret_cast<int*>(o)[e] = v[e];
+                        for (int half = 0; half < 2; ++half) {
+                            if (g.vec_store8 && n + (half + 1) * (per / 2) <= g.N) {
+                                typedef int v2i_t __attribute__((ext_vector_type(2)));
+                                reinterpret_cast<v2i_t*>(o)[half] = v2i_t{v[2 * half], v[2 * half + 1]};
+                                continue;
+                            }
+                            if constexpr (kBf16) {
+                                // (rows on 4-byte boundaries: two elements at a time where both lie inside the row)
+#pragma unroll
+                                for (int d = 2 * half; d < 2 * half + 2; ++d) {
+                                    if (g.vec_store4 && n + 2 * d + 1 < g.N) {
+                                        reinterpret_cast<int*>(o)[d] = v[d];
+                                    } else {
+                                        if (n + 2 * d < g.N) reinterpret_cast<uint16_t*>(o)[2 * d] = (uint16_t)(uint32_t)v[d];
+                                        if (n + 2 * d + 1 < g.N) reinterpret_cast<uint16_t*>(o)[2 * d + 1] = (uint16_t)((uint32_t)v[d] >> 16);
+                                    }
+                                }
+                            } else {
+#pragma unroll
+                                for (int e = 2 * half; e < 2 * half + 2; ++e)
+                                    if (n + e < g.N) reinterpret_cast<int*>(o)[e] = v[e];
+                            }
                         }
                     }
                 }
@@ -683,6 +703,8 @@ int launch_gemm_elem(int a_elem, const uint8_t* a_codes, const uint8_t* a_scales
     g.num_groups = grouped ? num_groups : 0;
     g.c_bf16 = c_dtype == MX_OUT_BF16;
     g.vec_store16 = aligned(C, 16) && (ldc * esz) % 16 == 0;
+    g.vec_store8 = aligned(C, 8) && (ldc * esz) % 8 == 0;
+    g.vec_store4 = aligned(C, 4) && (ldc * esz) % 4 == 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool use_mbs = a_mbs || b_mbs;
     const bool force_general = force == 1;

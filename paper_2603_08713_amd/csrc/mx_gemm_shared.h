@@ -38,6 +38,8 @@ struct GemmArgs {
     int tiles_m, tiles_n;        // tile grid (tiles_m is an upper bound in grouped mode)
     int c_bf16;
     int vec_store16;             // C rows allow 16-byte vector stores
+    int vec_store8;              // C rows allow 8-byte vector stores
+    int vec_store4;              // C rows allow 4-byte stores (bf16 output: two elements at a time)
 };
 
 // Main kernels (mx_gemm_ring.h), fast form: K % 512 == 0 and aligned scale and MBS arrays, not grouped; without MBS

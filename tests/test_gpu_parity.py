@@ -850,6 +850,35 @@ def test_gemm_every_tile_shape(mx, oracle, shape):
                 assert_gemm_close(host(got), want, "B-only mbs shape %d" % shape)
 
 
+@pytest.mark.parametrize("shape", [2, 3, 8])
+def test_gemm_rows_of_c_on_8_byte_boundaries(mx, oracle, shape):
+    """Rows of C that start on 8-byte but not on 16-byte boundaries (the epilogue's 8-byte stores), with N a multiple
+    of the store width and not: equal to the contiguous result, the frame around C untouched."""
+    rng = np.random.default_rng(60 + shape)
+    plain = shape == 2
+    with mx.forced(gemm_shape=shape):
+        for (M, N, K) in ((300, 264, 512), (130, 263, 1024)):
+            a, b = random_operand(rng, M, K), random_operand(rng, N, K)
+            da, db = [dev_u8(t) for t in a], [dev_u8(t) for t in b]
+            c32 = gpu_gemm(mx, a, b, "f32", plain=plain)
+            assert_gemm_close(host(c32), oracle.gemm((a[0], a[1], None), (b[0], b[1], None)) if plain else oracle.gemm(a, b),
+                              "shape %d %dx%dx%d" % (shape, M, N, K))
+            # (row pitch and first element at 8 mod 16 bytes; for bf16 also at 4 mod 8: two elements per store)
+            for dt, name, off, mod in ((torch.bfloat16, "bf16", 4, 16), (torch.bfloat16, "bf16", 2, 8), (torch.float32, "f32", 2, 16)):
+                width = (N + 7) // 8 * 8 + 3 * off
+                big = torch.full((M + 1, width), -3.0, dtype=dt, device="cuda")
+                out = big[:M, off:off + N]
+                assert out.data_ptr() % mod == mod // 2 and (width * out.element_size()) % mod == mod // 2
+                if plain:
+                    mx.mx_gemm(da[0], da[1], db[0], db[1], name, out=out)
+                else:
+                    mx.mx_gemm_mbs(da[0], da[1], da[2], db[0], db[1], db[2], name, out=out)
+                assert torch.equal(out, c32.to(dt)), (shape, M, N, K, name)
+                frame = big.clone()
+                frame[:M, off:off + N] = -3.0
+                assert bool((frame == -3.0).all()), (shape, M, N, K, name)
+
+
 def test_gemm_plain_full_size_sampled_rows(mx, oracle):
     """The plain GEMM at the Llama-3-8B FFN shape (it takes the 256 x 256 kernel there): one row of every 32-row
     fragment against the oracle, bf16 output equal to the rounded fp32 output."""

@@ -683,6 +683,14 @@ def test_gemm_elem_bf16_output_and_strided_c(mx, oracle):
     big = torch.zeros((M, N + 24), dtype=torch.float32, device="cuda")
     gpu_gemm(mx, "e4m3", a, "e4m3", b, "f32", out=big[:, :N])
     assert torch.equal(big[:, :N], c32) and float(big[:, N:].abs().max()) == 0.0
+    # rows of C on 8-byte (fp32, bf16) and 4-byte (bf16) boundaries: the epilogue's narrower stores
+    for dt, ref, off, pad in ((torch.float32, c32, 2, 26), (torch.bfloat16, c16, 4, 28), (torch.bfloat16, c16, 2, 30)):
+        wide = torch.full((M, N + pad), -3.0, dtype=dt, device="cuda")
+        gpu_gemm(mx, "e4m3", a, "e4m3", b, "f32" if dt == torch.float32 else "bf16", out=wide[:, off:off + N])
+        assert torch.equal(wide[:, off:off + N], ref), (dt, off)
+        frame = wide.clone()
+        frame[:, off:off + N] = -3.0
+        assert bool((frame == -3.0).all()), (dt, off)
     # an odd number of columns and a C that only allows element stores
     odd = torch.zeros((M, N + 3), dtype=torch.bfloat16, device="cuda")
     gpu_gemm(mx, "e4m3", a, "e4m3", (b[0][:N - 1], b[1][:N - 1], b[2][:N - 1]), "bf16", out=odd[:, 1:N])
